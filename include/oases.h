@@ -1,0 +1,210 @@
+/*
+ * oases.h -- C ABI of the MI355X (gfx950) hot path of Oases: one tensor-model-parallel (TMP)
+ * rank's share of a pre-LN GPT transformer layer, forward and backward, run under the
+ * sub-batch schedule of the paper's Algorithm 1.
+ *
+ * Conventions (all entry points)
+ *   - Every data pointer is a DEVICE pointer owned by the caller; the library never
+ *     allocates, frees or keeps device memory.  `oases_layer_cfg`, `oases_weights`,
+ *     `oases_grads`, `oases_peer_sums` and out-parameters are HOST memory.
+ *   - Streams are `hipStream_t` passed as `void*` (NULL = the default stream).  Calls only
+ *     enqueue work; they never synchronise the host with the device.
+ *   - Return value: 0 on success, a negative `OASES_E*` code otherwise; the text of the last
+ *     failure of the calling thread is returned by `oases_last_error()`.  Nothing throws or
+ *     aborts across this boundary.  Calls on one handle are not thread-safe.
+ *   - Notation (paper Sec. II / V; sizes are UNSHARDED unless marked "local"):
+ *       b batch, s sequence, h hidden, nh heads, d = h/nh, t TMP degree, r rank in [0,t),
+ *       hp = h/t (local attention width = nh/t heads), fp = 4h/t (local FFN columns),
+ *       M = b*s tokens, n = number of sub-batches, Ms = M/n rows per sub-batch.
+ *     Token rows are batch-major: row = batch_index*s + position.  Sub-batch j owns rows
+ *     [j*Ms, (j+1)*Ms).  If n > b a sub-batch is a chunk of one sequence (causal only).
+ *   - Tensor layouts, all row-major and 16-byte aligned:
+ *       x, y, dy, dx           [M, h]   fp32   residual stream
+ *       wqkv                   [h, 3hp] bf16   columns = [Q heads | K heads | V heads] of rank r
+ *       bqkv                   [3hp]    fp32
+ *       wo                     [hp, h]  bf16   rows of the unsharded projection owned by rank r
+ *       w1 / b1                [h, fp] bf16 / [fp] fp32   columns owned by rank r
+ *       w2                     [fp, h]  bf16   rows owned by rank r
+ *       bo, b2, ln*_g, ln*_b   [h]      fp32   replicated on every rank
+ *       gradients              fp32, same shapes as the parameter, ACCUMULATED INTO (+=)
+ *       peer sums              [M, h]   fp32   sum over the OTHER t-1 ranks of their partial result
+ *                                              at one reduction point
+ */
+#ifndef OASES_H
+#define OASES_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+  OASES_OK = 0,
+  OASES_EINVAL = -1,     /* bad configuration or argument value */
+  OASES_ENULL = -2,      /* required pointer is NULL */
+  OASES_EALIGN = -3,     /* device pointer not 16-byte aligned */
+  OASES_EWORKSPACE = -4, /* reserved */
+  OASES_EHIP = -5        /* a HIP runtime call failed; text in oases_last_error() */
+};
+
+/* Layer and schedule configuration.  The layer is a pre-LN GPT block: attention block then FFN
+ * (paper Sec. II "Large-scale model architecture", Fig. 1), partitioned Megatron-style (Sec. II
+ * "Tensor model parallelism": QKV and FC1 by column, projection and FC2 by row). */
+typedef struct oases_layer_cfg {
+  int32_t hidden, n_heads, seq, batch; /* h, nh, s, b (unsharded) */
+  int32_t tp_degree, tp_rank;          /* t, r */
+  int32_t n_sub;                       /* sub-batches of the schedule (Alg. 1 uses 2), >= 1 */
+  int32_t n_layers;                    /* stacked layers, >= 1 */
+  int32_t causal;                      /* 1: key j visible to query i iff j <= i */
+  float dropout_p;                     /* hidden-dropout probability, [0,1) */
+  uint64_t seed;                       /* Philox key of the dropout masks */
+  float ln_eps;                        /* LayerNorm epsilon; 0 selects 1e-5 */
+  int32_t flags;                       /* OASES_FLAG_* */
+} oases_layer_cfg;
+
+enum {
+  OASES_FLAG_SERIALISE = 1 /* enqueue everything on stream_compute only (same results) */
+};
+
+typedef struct oases_handle oases_handle; /* opaque; holds host metadata and HIP events only */
+
+typedef struct oases_weights { /* one per layer */
+  const void *ln1_g, *ln1_b, *wqkv, *bqkv, *wo, *bo, *ln2_g, *ln2_b, *w1, *b1, *w2, *b2;
+} oases_weights;
+
+typedef struct oases_grads { /* one per layer; fp32; accumulated into */
+  void *ln1_g, *ln1_b, *wqkv, *bqkv, *wo, *bo, *ln2_g, *ln2_b, *w1, *b1, *w2, *b2;
+} oases_grads;
+
+/* What the TMP AllReduce would add to this rank's partial at each of the four reduction points of
+ * a layer (Sec. IV-B: y = sum_i x_i).  A NULL member means "no peers at this point". */
+typedef struct oases_peer_sums { /* one per layer */
+  const void *fwd_attn; /* added to A*Wo_r        -> Z1  */
+  const void *fwd_ffn;  /* added to f*W2_r        -> Z2  */
+  const void *bwd_ffn;  /* added to dG*W1_r^T     -> dV2 */
+  const void *bwd_attn; /* added to dQKV*Wqkv_r^T -> dU  */
+} oases_peer_sums;
+
+/* Validate the configuration and plan workspace and schedule.  Pure host code: works without a
+ * GPU.  EINVAL if h % nh, nh % t, 4h % t, M % n, d not in {64,128}, r >= t, p outside [0,1),
+ * a sub-batch that is neither whole sequences nor an equal chunk of one sequence, or sequence
+ * chunks with causal = 0. */
+int oases_create(const oases_layer_cfg *cfg, oases_handle **out);
+void oases_destroy(oases_handle *h);
+
+/* Bytes of caller-allocated device workspace (activation stash of all layers + backward scratch).
+ * The same workspace must be passed to oases_forward and to the oases_backward that follows it. */
+size_t oases_workspace_bytes(const oases_handle *h);
+
+/* Forward of all layers under Alg. 1 "At Forward": for each computation sequence, sub-batch after
+ * sub-batch; after each row-parallel GEMM the reduction point of that sub-batch is started on
+ * stream_comm (adds the peer sum, then the fused bias+dropout+residual(+LayerNorm) that consumes it)
+ * while stream_compute goes on with the next sub-batch.  w: [n_layers]; peers: [n_layers] or NULL.
+ * x [M,h] fp32 in, y [M,h] fp32 out (y may not alias x). */
+int oases_forward(oases_handle *h, const oases_weights *w, const void *x, void *y,
+                  const oases_peer_sums *peers, void *workspace, void *stream_compute,
+                  void *stream_comm);
+
+/* Backward of all layers under Alg. 1 "At Backward" with stored activations: sub-batches in
+ * reverse order; each column-parallel input-gradient partial starts its reduction point on
+ * stream_comm, under which the next sub-batch's GEMMs and the weight-gradient GEMMs run.
+ * dy [M,h] fp32 in, dx [M,h] fp32 out; g: [n_layers], accumulated into. */
+int oases_backward(oases_handle *h, const oases_weights *w, const void *dy, void *dx,
+                   const oases_grads *g, const oases_peer_sums *peers, void *workspace,
+                   void *stream_compute, void *stream_comm);
+
+/* The operator order of the schedule as text, one operator per line
+ * ("<stream> <op> L<layer> sb<sub-batch>"), NUL-terminated into buf (at most n bytes).
+ * Returns the number of bytes the full text needs (like snprintf).  Host only. */
+int oases_schedule_dump(const oases_handle *h, int backward, char *buf, size_t n);
+
+/* Byte offset and size inside the workspace of a named stashed tensor of one layer, for tests and
+ * debugging.  Names: "u","qkv","attn","lse","z1","x1","v2","pre","f","z2","mu1","rstd1","mu2",
+ * "rstd2","dz2","dg","dv2","dx1","dz1","da","dqkv","du".  EINVAL for an unknown name. */
+int oases_workspace_tensor(const oases_handle *h, const char *name, int layer, size_t *offset,
+                           size_t *bytes);
+
+const char *oases_last_error(void); /* thread-local, never NULL */
+
+/* ---------------------------------------------------------------------------------------------
+ * Single-operator entry points: the kernels of the path, one at a time (used by the per-operator
+ * parity tests and the per-kernel roofline measurements).  Same conventions as above.
+ * ------------------------------------------------------------------------------------------- */
+
+/* Keep mask of hidden dropout as bytes (1 keep, 0 drop) for global rows row0..row0+rows-1 of the
+ * unsharded [M,h] activation: element e = row*h+col takes word (e mod 4) of Philox4x32-10 with key
+ * (seed lo, seed hi) and counter (e/4 lo, e/4 hi, site, layer); keep iff (word >> 8) >= round(p*2^24). */
+int oases_op_dropout_mask(uint8_t *mask, uint64_t seed, int layer, int site, int64_t row0,
+                          int rows, int h, float p, void *stream);
+
+/* LayerNorm forward over rows of x [rows,h] fp32: out bf16 [rows,h], mu/rstd fp32 [rows]. */
+int oases_op_layernorm_fwd(const void *x, const void *gamma, const void *beta, void *out, void *mu,
+                           void *rstd, int rows, int h, float eps, void *stream);
+
+/* Reduction point + bias + dropout + residual (+ LayerNorm):
+ *   xo = xin + keep * (part + peer + bias) / (1-p);  if ln_out: ln_out = LN(xo) (bf16), mu, rstd.
+ * part, xin, xo fp32 [rows,h]; peer may be NULL; ln_out/gamma/beta/mu/rstd may all be NULL. */
+int oases_op_bias_dropout_residual_ln(const void *part, const void *peer, const void *bias,
+                                      const void *xin, void *xo, const void *gamma,
+                                      const void *beta, void *ln_out, void *mu, void *rstd,
+                                      int rows, int h, float eps, uint64_t seed, int layer,
+                                      int site, int64_t row0, float p, void *stream);
+
+/* Backward of dropout+bias at a forward reduction point:
+ *   dz = keep * dyin / (1-p) -> bf16 [rows,h];  dbias[h] += column sums of dz (fp32 values). */
+int oases_op_dropout_bwd(const void *dyin, void *dz, void *dbias, int rows, int h, uint64_t seed,
+                         int layer, int site, int64_t row0, float p, void *scratch,
+                         void *stream);
+
+/* LayerNorm backward + residual (+ reduction point, + dropout backward of the layer input side):
+ *   g = part + peer;  dxo = dres + LN'(g; x, mu, rstd, gamma);  dgamma += , dbeta += ;
+ *   if dz: dz = keep * dxo / (1-p) (bf16), dbias += column sums of dz.
+ * part/peer/dres/x/dxo fp32 [rows,h]; peer, dz, dbias may be NULL.  scratch: fp32 [4*256*h]. */
+int oases_op_layernorm_bwd(const void *part, const void *peer, const void *dres, const void *x,
+                           const void *mu, const void *rstd, const void *gamma, void *dxo,
+                           void *dgamma, void *dbeta, void *dz, void *dbias, int rows, int h,
+                           uint64_t seed, int layer, int site, int64_t row0, float p,
+                           void *scratch, void *stream);
+
+/* GEMM family on bf16 operands with fp32 accumulation.  `op`:
+ *   OASES_GEMM_NN  C[M,N]  = A[M,K] * B[K,N]            (forward of a linear map)
+ *   OASES_GEMM_NT  C[M,N]  = A[M,K] * B[N,K]^T          (input gradient)
+ *   OASES_GEMM_TN  C[M,N] += A[K,M]^T * B[K,N]          (weight gradient, C fp32)
+ * `epi` (NN/NT): OASES_EPI_F32 C fp32; OASES_EPI_BF16 C bf16; OASES_EPI_BIAS_BF16 C = acc+bias (bf16);
+ *   OASES_EPI_BIAS_GELU aux = acc+bias (bf16, "pre"), C = GeLU_tanh(acc+bias) (bf16);
+ *   OASES_EPI_DGELU C = acc * GeLU_tanh'(aux) (bf16), aux = stored "pre" [M,N] bf16.
+ * lda/ldb/ldc are row strides in elements.  M,N,K must be multiples of 8; EINVAL otherwise. */
+enum { OASES_GEMM_NN = 0, OASES_GEMM_NT = 1, OASES_GEMM_TN = 2 };
+enum { OASES_EPI_F32 = 0, OASES_EPI_BF16 = 1, OASES_EPI_BIAS_BF16 = 2, OASES_EPI_BIAS_GELU = 3,
+       OASES_EPI_DGELU = 4 };
+int oases_op_gemm(int op, int epi, int M, int N, int K, const void *A, int lda, const void *B,
+                  int ldb, void *C, int ldc, const void *bias, void *aux, int ldaux,
+                  void *stream);
+
+/* Column sums of a bf16 matrix [rows, cols] (row stride ld) accumulated into fp32 out[cols].
+ * scratch: fp32 [256*cols]. */
+int oases_op_colsum_bf16(const void *a, int ld, int rows, int cols, void *out, void *scratch,
+                         void *stream);
+
+/* Flash-style attention over the local heads.  qkv [batch*seq, 3*hp] bf16 with hp = heads*d and
+ * columns [Q | K | V]; queries are the rows row0..row0+rows-1 (a whole number of sequences, or a chunk
+ * of one sequence when causal).  Keys/values of the same sequence are read from qkv at any row.
+ * out [batch*seq, hp] bf16 (only the query rows are written); lse [batch, heads, seq] fp32 holds
+ * log-sum-exp of the scaled scores (natural log). */
+int oases_op_attention_fwd(const void *qkv, void *out, void *lse, int batch, int seq, int heads,
+                           int head_dim, int causal, int row0, int rows, void *stream);
+
+/* Attention backward for the rows row0..row0+rows-1: writes dq, dk, dv (bf16) for those rows into
+ * dqkv [batch*seq, 3*hp].  dk/dv of a row sum over every query of its sequence that sees it, so dout
+ * (and out, lse) must already hold the rows of all such queries.  delta: fp32 scratch
+ * [batch, heads, seq]; this call fills it for the query rows it needs. */
+int oases_op_attention_bwd(const void *qkv, const void *out, const void *dout, const void *lse,
+                           void *delta, void *dqkv, int batch, int seq, int heads, int head_dim,
+                           int causal, int row0, int rows, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* OASES_H */
