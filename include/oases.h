@@ -110,9 +110,10 @@ int oases_forward(oases_handle *h, const oases_weights *w, const void *x, void *
 /* Backward of all layers under Alg. 1 "At Backward" with stored activations: sub-batches in
  * reverse order; each column-parallel input-gradient partial starts its reduction point on
  * stream_comm, under which the next sub-batch's GEMMs and the weight-gradient GEMMs run.
+ * x: the input given to oases_forward (read again by the first LayerNorm's backward);
  * dy [M,h] fp32 in, dx [M,h] fp32 out; g: [n_layers], accumulated into. */
-int oases_backward(oases_handle *h, const oases_weights *w, const void *dy, void *dx,
-                   const oases_grads *g, const oases_peer_sums *peers, void *workspace,
+int oases_backward(oases_handle *h, const oases_weights *w, const void *x, const void *dy,
+                   void *dx, const oases_grads *g, const oases_peer_sums *peers, void *workspace,
                    void *stream_compute, void *stream_comm);
 
 /* The operator order of the schedule as text, one operator per line

@@ -156,6 +156,33 @@ def _unheads(t, b, s, nh, d):
     return t.permute(0, 2, 1, 3).reshape(b * s, nh * d)
 
 
+def attention_fwd(q, k, v, batch, seq, nh, d, causal, rb=None):
+    """Softmax attention per (batch item, head) on [batch*seq, nh*d] matrices.  Returns (A, P)."""
+    rb = rb or _Rounder(())
+    qh, kh, vh = (_heads(t, batch, seq, nh, d) for t in (q, k, v))
+    S = (qh @ kh.transpose(2, 3)) / math.sqrt(d)                      # [b, nh, s, s]
+    if causal:
+        i = torch.arange(seq)
+        S = S.masked_fill(i[None, :] > i[:, None], float("-inf"))     # key j visible iff j <= i
+    S = S - S.max(dim=3, keepdim=True).values
+    P = torch.exp(S)
+    P = P / P.sum(dim=3, keepdim=True)
+    A = rb("A", _unheads(rb("P", P) @ vh, batch, seq, nh, d))         # [M, nh*d]
+    return A, P
+
+
+def attention_bwd(dA, q, k, v, P, batch, seq, nh, d, rb=None):
+    """Gradients of attention_fwd's inputs for the output gradient dA (softmax' written out)."""
+    rb = rb or _Rounder(())
+    qh, kh, vh, dAh = (_heads(t, batch, seq, nh, d) for t in (q, k, v, dA))
+    dP = dAh @ vh.transpose(2, 3)
+    dvh = rb("P", P).transpose(2, 3) @ dAh
+    dS = rb("dS", P * (dP - (dP * P).sum(dim=3, keepdim=True)))
+    dqh = (dS @ kh) / math.sqrt(d)
+    dkh = (dS.transpose(2, 3) @ qh) / math.sqrt(d)
+    return tuple(rb("dqkv", _unheads(t, batch, seq, nh, d)) for t in (dqh, dkh, dvh))
+
+
 def rank_layer_forward(p: dict, x, *, batch: int, seq: int, head_dim: int, causal: bool,
                        dropout_p: float = 0.0, seed: int = 0, layer: int = 0, eps: float = 1e-5,
                        gelu_tanh: bool = True, peers: dict | None = None, bf16_sites=()):
@@ -179,15 +206,7 @@ def rank_layer_forward(p: dict, x, *, batch: int, seq: int, head_dim: int, causa
     q = rb("qkv", u @ p["wq"] + p["bq"])
     k = rb("qkv", u @ p["wk"] + p["bk"])
     v = rb("qkv", u @ p["wv"] + p["bv"])
-    qh, kh, vh = (_heads(t, batch, seq, nh, head_dim) for t in (q, k, v))
-    S = (qh @ kh.transpose(2, 3)) / math.sqrt(head_dim)               # [b, nh, s, s]
-    if causal:
-        i = torch.arange(seq)
-        S = S.masked_fill(i[None, :] > i[:, None], float("-inf"))     # key j visible iff j <= i
-    S = S - S.max(dim=3, keepdim=True).values
-    P = torch.exp(S)
-    P = P / P.sum(dim=3, keepdim=True)
-    A = rb("A", _unheads(rb("P", P) @ vh, batch, seq, nh, head_dim))  # [M, hp]
+    A, P = attention_fwd(q, k, v, batch, seq, nh, head_dim, causal, rb)
     Z1r = A @ p["wo"]                                                  # this rank's partial sum
     Z1 = Z1r + peers["fwd_attn"] if peers.get("fwd_attn") is not None else Z1r
     x1 = x + D1 * (Z1 + p["bo"]) * c
@@ -234,14 +253,7 @@ def rank_layer_backward(p: dict, saved: dict, dy, *, peers: dict | None = None, 
     g["bo"] = dZ1.sum(dim=0)
     dA = rb("dA", dZ1 @ p["wo"].t())
     g["wo"] = s["A"].t() @ dZ1
-    qh, kh, vh, dAh = (_heads(t, b, seq, nh, d) for t in (s["q"], s["k"], s["v"], dA))
-    P = s["P"]
-    dP = dAh @ vh.transpose(2, 3)
-    dvh = rb("P", P).transpose(2, 3) @ dAh
-    dS = rb("dS", P * (dP - (dP * P).sum(dim=3, keepdim=True)))
-    dqh = (dS @ kh) / math.sqrt(d)
-    dkh = (dS.transpose(2, 3) @ qh) / math.sqrt(d)
-    dq, dk, dv = (rb("dqkv", _unheads(t, b, seq, nh, d)) for t in (dqh, dkh, dvh))
+    dq, dk, dv = attention_bwd(dA, s["q"], s["k"], s["v"], s["P"], b, seq, nh, d, rb)
     for n, dd in (("q", dq), ("k", dk), ("v", dv)):
         g["w" + n] = s["u"].t() @ dd
         g["b" + n] = dd.sum(dim=0)

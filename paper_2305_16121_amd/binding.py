@@ -1,0 +1,176 @@
+"""ctypes binding of liboases.so: argument marshalling only (see include/oases.h for semantics)."""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "liboases.so")
+
+if not os.path.exists(LIB_PATH):
+    raise ImportError(f"{LIB_PATH} not built: run `python {os.path.join(_HERE, 'csrc', 'build.py')}` "
+                      "(there is no CPU fallback for the HIP path)")
+lib = C.CDLL(LIB_PATH)
+
+OK, EINVAL, ENULL, EALIGN, EWORKSPACE, EHIP = 0, -1, -2, -3, -4, -5
+GEMM_NN, GEMM_NT, GEMM_TN = 0, 1, 2
+EPI_F32, EPI_BF16, EPI_BIAS_BF16, EPI_BIAS_GELU, EPI_DGELU = 0, 1, 2, 3, 4
+FLAG_SERIALISE = 1
+
+_P = C.c_void_p
+_PARAMS = ("ln1_g", "ln1_b", "wqkv", "bqkv", "wo", "bo", "ln2_g", "ln2_b", "w1", "b1", "w2", "b2")
+_PEERS = ("fwd_attn", "fwd_ffn", "bwd_ffn", "bwd_attn")
+
+
+class LayerCfg(C.Structure):
+    _fields_ = [("hidden", C.c_int32), ("n_heads", C.c_int32), ("seq", C.c_int32), ("batch", C.c_int32),
+                ("tp_degree", C.c_int32), ("tp_rank", C.c_int32), ("n_sub", C.c_int32), ("n_layers", C.c_int32),
+                ("causal", C.c_int32), ("dropout_p", C.c_float), ("seed", C.c_uint64), ("ln_eps", C.c_float),
+                ("flags", C.c_int32)]
+
+
+class Weights(C.Structure):
+    _fields_ = [(n, _P) for n in _PARAMS]
+
+
+class Grads(C.Structure):
+    _fields_ = [(n, _P) for n in _PARAMS]
+
+
+class PeerSums(C.Structure):
+    _fields_ = [(n, _P) for n in _PEERS]
+
+
+def _sig(name, res, *args):
+    f = getattr(lib, name)
+    f.restype, f.argtypes = res, list(args)
+    return f
+
+
+_i, _f, _u64, _i64, _sz = C.c_int, C.c_float, C.c_uint64, C.c_int64, C.c_size_t
+_sig("oases_last_error", C.c_char_p)
+_sig("oases_create", _i, C.POINTER(LayerCfg), C.POINTER(_P))
+_sig("oases_destroy", None, _P)
+_sig("oases_workspace_bytes", _sz, _P)
+_sig("oases_forward", _i, _P, C.POINTER(Weights), _P, _P, C.POINTER(PeerSums), _P, _P, _P)
+_sig("oases_backward", _i, _P, C.POINTER(Weights), _P, _P, _P, C.POINTER(Grads), C.POINTER(PeerSums), _P, _P, _P)
+_sig("oases_schedule_dump", _i, _P, _i, C.c_char_p, _sz)
+_sig("oases_workspace_tensor", _i, _P, C.c_char_p, _i, C.POINTER(_sz), C.POINTER(_sz))
+_sig("oases_op_dropout_mask", _i, _P, _u64, _i, _i, _i64, _i, _i, _f, _P)
+_sig("oases_op_layernorm_fwd", _i, _P, _P, _P, _P, _P, _P, _i, _i, _f, _P)
+_sig("oases_op_bias_dropout_residual_ln", _i, _P, _P, _P, _P, _P, _P, _P, _P, _P, _P, _i, _i, _f, _u64, _i, _i, _i64, _f, _P)
+_sig("oases_op_dropout_bwd", _i, _P, _P, _P, _i, _i, _u64, _i, _i, _i64, _f, _P, _P)
+_sig("oases_op_layernorm_bwd", _i, _P, _P, _P, _P, _P, _P, _P, _P, _P, _P, _P, _P, _i, _i, _u64, _i, _i, _i64, _f, _P, _P)
+_sig("oases_op_gemm", _i, _i, _i, _i, _i, _i, _P, _i, _P, _i, _P, _i, _P, _P, _i, _P)
+_sig("oases_op_colsum_bf16", _i, _P, _i, _i, _i, _P, _P, _P)
+_sig("oases_op_attention_fwd", _i, _P, _P, _P, _i, _i, _i, _i, _i, _i, _i, _P)
+_sig("oases_op_attention_bwd", _i, _P, _P, _P, _P, _P, _P, _i, _i, _i, _i, _i, _i, _i, _P)
+
+
+class OasesError(RuntimeError):
+    def __init__(self, code):
+        self.code = code
+        super().__init__(f"oases error {code}: {lib.oases_last_error().decode()}")
+
+
+def check(rc):
+    if rc != 0:
+        raise OasesError(rc)
+
+
+def ptr(t):
+    """Device (or NULL) pointer of a torch tensor / raw int."""
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return t
+    return t.data_ptr()
+
+
+def stream_ptr(s):
+    if s is None:
+        return None
+    return s if isinstance(s, int) else s.cuda_stream
+
+
+def make_cfg(cfg: dict, rank: int = 0, seed: int = 0, flags: int = 0, n_sub: int | None = None) -> LayerCfg:
+    return LayerCfg(cfg["hidden"], cfg["n_heads"], cfg["seq"], cfg["batch"], cfg["tp"], rank,
+                    cfg["n_sub"] if n_sub is None else n_sub, cfg["n_layers"], cfg["causal"], cfg["dropout_p"], seed,
+                    0.0, flags)
+
+
+class Handle:
+    """Owns an oases_handle."""
+
+    def __init__(self, c: LayerCfg):
+        self.cfg = c
+        h = _P()
+        check(lib.oases_create(C.byref(c), C.byref(h)))
+        self._h = h
+
+    def close(self):
+        if self._h:
+            lib.oases_destroy(self._h)
+            self._h = None
+
+    __del__ = close
+
+    @property
+    def workspace_bytes(self) -> int:
+        return lib.oases_workspace_bytes(self._h)
+
+    def schedule(self, backward: bool) -> str:
+        n = lib.oases_schedule_dump(self._h, int(backward), None, 0)
+        buf = C.create_string_buffer(n + 1)
+        lib.oases_schedule_dump(self._h, int(backward), buf, n + 1)
+        return buf.value.decode()
+
+    def tensor_span(self, name: str, layer: int = 0):
+        off, nb = _sz(), _sz()
+        check(lib.oases_workspace_tensor(self._h, name.encode(), layer, C.byref(off), C.byref(nb)))
+        return off.value, nb.value
+
+    @staticmethod
+    def _structs(cls, names, dicts):
+        arr = (cls * len(dicts))()
+        for i, d in enumerate(dicts):
+            for n in names:
+                setattr(arr[i], n, ptr(d.get(n)) if d is not None else None)
+        return arr
+
+    def forward(self, weights, x, y, workspace, peers=None, s_compute=None, s_comm=None):
+        w = self._structs(Weights, _PARAMS, weights)
+        p = self._structs(PeerSums, _PEERS, peers) if peers is not None else None
+        check(lib.oases_forward(self._h, w, ptr(x), ptr(y), p, ptr(workspace), stream_ptr(s_compute), stream_ptr(s_comm)))
+
+    def backward(self, weights, x, dy, dx, grads, workspace, peers=None, s_compute=None, s_comm=None):
+        w = self._structs(Weights, _PARAMS, weights)
+        g = self._structs(Grads, _PARAMS, grads)
+        p = self._structs(PeerSums, _PEERS, peers) if peers is not None else None
+        check(lib.oases_backward(self._h, w, ptr(x), ptr(dy), ptr(dx), g, p, ptr(workspace), stream_ptr(s_compute),
+                                 stream_ptr(s_comm)))
+
+
+# ------------------------------------------------------------------------------------------------
+# device-side layout of one rank's parameters (marshalling only)
+# ------------------------------------------------------------------------------------------------
+def pack_rank_params(shard: dict, device="cuda"):
+    """numpy dict from synth_inputs.shard_layer_params -> dict of device tensors in the library's layout:
+    wqkv [h,3hp] = [wq | wk | wv] bf16, bqkv [3hp] fp32, the other matrices bf16, vectors fp32."""
+    import numpy as np
+    import torch
+    t = lambda a, dt: torch.from_numpy(np.ascontiguousarray(a)).to(device=device, dtype=dt)
+    out = {
+        "wqkv": t(np.concatenate([shard["wq"], shard["wk"], shard["wv"]], axis=1), torch.bfloat16),
+        "bqkv": t(np.concatenate([shard["bq"], shard["bk"], shard["bv"]]), torch.float32),
+    }
+    for k in ("wo", "w1", "w2"):
+        out[k] = t(shard[k], torch.bfloat16)
+    for k in ("ln1_g", "ln1_b", "bo", "ln2_g", "ln2_b", "b1", "b2"):
+        out[k] = t(shard[k], torch.float32)
+    return out
+
+
+def zero_grads_like(params: dict):
+    import torch
+    return {k: torch.zeros(v.shape, dtype=torch.float32, device=v.device) for k, v in params.items()}

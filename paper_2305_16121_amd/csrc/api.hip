@@ -1,0 +1,509 @@
+// C ABI of the library: configuration, workspace plan, the sub-batch schedule of the paper's
+// Algorithm 1 on two HIP streams, and thin single-operator wrappers.
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <string>
+#include <vector>
+
+#include "common.h"
+
+namespace oases {
+
+static thread_local char g_err[512] = "";
+
+void set_error(const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof g_err, fmt, ap);
+  va_end(ap);
+}
+int hip_fail(hipError_t e, const char* what) {
+  set_error("HIP error %d (%s) in %s", (int)e, hipGetErrorString(e), what);
+  return OASES_EHIP;
+}
+
+// ---------------------------------------------------------------------------------------------
+// schedule: operators in host issue order
+// ---------------------------------------------------------------------------------------------
+enum OpKind {
+  // forward
+  F_LN1, F_QKV, F_ATTN, F_PROJ, F_R1, F_FC1, F_FC2, F_R2,
+  // backward
+  B_BDR2, B_FC2_DGRAD, B_FC1_DGRAD, B_R3, B_FC2_WGRAD, B_FC1_WGRAD, B_B1_SUM, B_PROJ_DGRAD, B_PROJ_WGRAD, B_ATTN,
+  B_QKV_DGRAD, B_R4, B_QKV_WGRAD, B_BQKV_SUM,
+  // stream join at the end of a pass
+  JOIN
+};
+static const char* kOpName[] = {
+    "LN1", "QKV", "ATTN", "PROJ", "R1+BDR1+LN2", "FC1+GELU", "FC2", "R2+BDR2",
+    "BDR2.b", "FC2.dgrad+dGELU", "FC1.dgrad", "R3+LN2.b+BDR1.b", "FC2.wgrad", "FC1.wgrad", "b1.sum", "PROJ.dgrad",
+    "PROJ.wgrad", "ATTN.b", "QKV.dgrad", "R4+LN1.b", "QKV.wgrad", "bqkv.sum", "join"};
+
+struct Op {
+  int kind, layer, sub;
+  int stream;  // 0 compute, 1 comm
+  int wait;    // event to wait for before the op (-1 none)
+  int record;  // event recorded after the op (-1 none)
+};
+
+struct Tensor {
+  const char* name;
+  size_t offset, bytes;
+};
+
+}  // namespace oases
+
+using namespace oases;
+
+struct oases_handle {
+  oases_layer_cfg cfg;
+  int h, nh, d, s, b, t, r, n, L, M, Ms, hp, fp, heads_l;
+  float eps;
+  std::vector<Op> fwd, bwd;
+  int n_events;
+  std::vector<hipEvent_t> events;  // created on first use
+  std::vector<Tensor> tensors;     // per-layer tensors, offsets relative to the layer base
+  size_t layer_bytes, scratch_comm_off, scratch_compute_off, total_bytes;
+};
+
+namespace oases {
+
+static size_t align_up(size_t x) { return (x + 255) & ~(size_t)255; }
+
+static void plan_workspace(oases_handle* H) {
+  const size_t M = H->M, h = H->h, hp = H->hp, fp = H->fp, st = (size_t)H->b * H->heads_l * H->s;
+  struct { const char* n; size_t bytes; } list[] = {
+      {"u", M * h * 2},      {"mu1", M * 4},        {"rstd1", M * 4},      {"qkv", M * 3 * hp * 2}, {"attn", M * hp * 2},
+      {"lse", st * 4},       {"z1", M * h * 4},     {"x1", M * h * 4},     {"mu2", M * 4},          {"rstd2", M * 4},
+      {"v2", M * h * 2},     {"pre", M * fp * 2},   {"f", M * fp * 2},     {"z2", M * h * 4},       {"y", M * h * 4},
+      {"dz2", M * h * 2},    {"dg", M * fp * 2},    {"dv2", M * h * 4},    {"dx1", M * h * 4},      {"dz1", M * h * 2},
+      {"da", M * hp * 2},    {"delta", st * 4},     {"dqkv", M * 3 * hp * 2}, {"du", M * h * 4},    {"dy", M * h * 4}};
+  size_t off = 0;
+  for (auto& e : list) {
+    H->tensors.push_back(Tensor{e.n, off, e.bytes});
+    off += align_up(e.bytes);
+  }
+  H->layer_bytes = off;
+  size_t tot = off * H->L;
+  H->scratch_comm_off = tot;
+  tot += align_up((size_t)3 * kColPartials * h * 4);
+  H->scratch_compute_off = tot;
+  size_t wide = 3 * hp > fp ? 3 * hp : fp;
+  tot += align_up((size_t)kColPartials * wide * 4);
+  H->total_bytes = tot;
+}
+
+static size_t tensor_off(const oases_handle* H, const char* name, int layer) {
+  for (auto& t : H->tensors)
+    if (!strcmp(t.name, name)) return (size_t)layer * H->layer_bytes + t.offset;
+  return (size_t)-1;
+}
+
+// Events: ev(layer, point, sub, kind): point 0..3 = R1..R4, kind 0 = "partial ready" (compute -> comm),
+// kind 1 = "reduced and consumed" (comm -> compute).
+static int ev_id(const oases_handle* H, int layer, int point, int sub, int kind) {
+  return ((layer * 4 + point) * H->n + sub) * 2 + kind;
+}
+
+// Alg. 1 "At Forward": walk the operator sequence; at every communication operator start it for the
+// current sub-batch and switch to the next sub-batch, rewinding to the start of the computation
+// sequence; advance past the communication operator once every sub-batch has been through.
+static void build_forward(oases_handle* H) {
+  auto& ops = H->fwd;
+  const int n = H->n;
+  for (int l = 0; l < H->L; l++) {
+    for (int j = 0; j < n; j++) {
+      int w = l > 0 ? ev_id(H, l - 1, 1, j, 1) : -1;  // input of this layer comes out of R2 of the layer below
+      if (l == 0) { ops.push_back(Op{F_LN1, l, j, 0, -1, -1}); }
+      ops.push_back(Op{F_QKV, l, j, 0, w, -1});
+      ops.push_back(Op{F_ATTN, l, j, 0, -1, -1});
+      ops.push_back(Op{F_PROJ, l, j, 0, -1, ev_id(H, l, 0, j, 0)});
+      ops.push_back(Op{F_R1, l, j, 1, ev_id(H, l, 0, j, 0), ev_id(H, l, 0, j, 1)});
+    }
+    for (int j = 0; j < n; j++) {
+      ops.push_back(Op{F_FC1, l, j, 0, ev_id(H, l, 0, j, 1), -1});
+      ops.push_back(Op{F_FC2, l, j, 0, -1, ev_id(H, l, 1, j, 0)});
+      ops.push_back(Op{F_R2, l, j, 1, ev_id(H, l, 1, j, 0), ev_id(H, l, 1, j, 1)});
+    }
+  }
+  for (int j = 0; j < n; j++) ops.push_back(Op{JOIN, H->L - 1, j, 0, ev_id(H, H->L - 1, 1, j, 1), -1});
+}
+
+// Alg. 1 "At Backward" with stored activations: saved sequences are popped last-first (so the last
+// sub-batch goes first); the backward operators of a sequence run until its communication operator,
+// which is started asynchronously; the operators behind it (here: fused into the reduction-point kernel
+// on the communication stream) and the weight-gradient GEMMs, on which no reduction depends, fill in.
+static void build_backward(oases_handle* H) {
+  auto& ops = H->bwd;
+  const int n = H->n, L = H->L;
+  for (int j = n - 1; j >= 0; j--) ops.push_back(Op{B_BDR2, L - 1, j, 1, -1, ev_id(H, L - 1, 1, j, 1)});
+  for (int l = L - 1; l >= 0; l--) {
+    for (int j = n - 1; j >= 0; j--) {
+      // dZ2 of this layer comes from the trailing BDR2.b (top layer) or from R4 of the layer above
+      int w = l == L - 1 ? ev_id(H, l, 1, j, 1) : ev_id(H, l + 1, 3, j, 1);
+      ops.push_back(Op{B_FC2_DGRAD, l, j, 0, w, -1});
+      ops.push_back(Op{B_FC1_DGRAD, l, j, 0, -1, ev_id(H, l, 2, j, 0)});
+      ops.push_back(Op{B_R3, l, j, 1, ev_id(H, l, 2, j, 0), ev_id(H, l, 2, j, 1)});
+      ops.push_back(Op{B_FC2_WGRAD, l, j, 0, -1, -1});
+      ops.push_back(Op{B_FC1_WGRAD, l, j, 0, -1, -1});
+      ops.push_back(Op{B_B1_SUM, l, j, 0, -1, -1});
+    }
+    for (int j = n - 1; j >= 0; j--) {
+      ops.push_back(Op{B_PROJ_DGRAD, l, j, 0, ev_id(H, l, 2, j, 1), -1});
+      ops.push_back(Op{B_ATTN, l, j, 0, -1, -1});
+      ops.push_back(Op{B_QKV_DGRAD, l, j, 0, -1, ev_id(H, l, 3, j, 0)});
+      ops.push_back(Op{B_R4, l, j, 1, ev_id(H, l, 3, j, 0), ev_id(H, l, 3, j, 1)});
+      ops.push_back(Op{B_PROJ_WGRAD, l, j, 0, -1, -1});
+      ops.push_back(Op{B_QKV_WGRAD, l, j, 0, -1, -1});
+      ops.push_back(Op{B_BQKV_SUM, l, j, 0, -1, -1});
+    }
+  }
+  for (int j = n - 1; j >= 0; j--) ops.push_back(Op{JOIN, 0, j, 0, ev_id(H, 0, 3, j, 1), -1});
+}
+
+static int check_ptrs(const void* const* p, int n, const char* who) {
+  for (int i = 0; i < n; i++) {
+    if (!p[i]) { set_error("%s: NULL device pointer (argument %d)", who, i); return OASES_ENULL; }
+    if (!aligned16(p[i])) { set_error("%s: device pointer %d not 16-byte aligned", who, i); return OASES_EALIGN; }
+  }
+  return 0;
+}
+
+static int ensure_events(oases_handle* H) {
+  if (!H->events.empty()) return 0;
+  H->events.resize(H->n_events);
+  for (auto& e : H->events) {
+    hipError_t err = hipEventCreateWithFlags(&e, hipEventDisableTiming);
+    if (err != hipSuccess) {
+      H->events.clear();
+      return hip_fail(err, "hipEventCreateWithFlags");
+    }
+  }
+  return 0;
+}
+
+struct Run {
+  oases_handle* H;
+  const oases_weights* w;
+  const oases_grads* g;
+  const oases_peer_sums* peers;
+  char* ws;
+  const float* x;   // forward input
+  float* y;         // forward output
+  const float* dy;  // backward input
+  float* dx;        // backward output
+  hipStream_t st[2];
+};
+
+template <typename T>
+static T* wsp(const Run& R, const char* name, int layer) {
+  return reinterpret_cast<T*>(R.ws + tensor_off(R.H, name, layer));
+}
+
+static int run_op(const Run& R, const Op& op) {
+  const oases_handle* H = R.H;
+  const int l = op.layer, j = op.sub, Ms = H->Ms, h = H->h, hp = H->hp, fp = H->fp, L = H->L;
+  const size_t r0 = (size_t)j * Ms;  // first token row of the sub-batch
+  hipStream_t s = R.st[op.stream];
+  const oases_weights& W = R.w[l];
+  const oases_peer_sums* P = R.peers ? &R.peers[l] : nullptr;
+  auto peer = [&](const void* base) -> const float* { return base ? (const float*)base + r0 * h : nullptr; };
+  const float p = H->cfg.dropout_p;
+  const uint64_t seed = H->cfg.seed;
+  const float* xin = l == 0 ? R.x : wsp<float>(R, "y", l - 1);                 // layer input
+  float* yout = l == L - 1 ? R.y : wsp<float>(R, "y", l);                      // layer output
+  const float* dyin = R.dy && l == L - 1 ? R.dy : wsp<float>(R, "dy", l);      // gradient of the layer output
+  float* dxout = l == 0 ? R.dx : wsp<float>(R, "dy", l - 1);                   // gradient of the layer input
+  float* scr_comm = reinterpret_cast<float*>(R.ws + H->scratch_comm_off);
+  float* scr_comp = reinterpret_cast<float*>(R.ws + H->scratch_compute_off);
+  uint16_t* u = wsp<uint16_t>(R, "u", l);
+  uint16_t* qkv = wsp<uint16_t>(R, "qkv", l);
+  uint16_t* attn = wsp<uint16_t>(R, "attn", l);
+  uint16_t* v2 = wsp<uint16_t>(R, "v2", l);
+  uint16_t* pre = wsp<uint16_t>(R, "pre", l);
+  uint16_t* f = wsp<uint16_t>(R, "f", l);
+  switch (op.kind) {
+    case F_LN1:
+      return launch_layernorm_fwd(xin + r0 * h, (const float*)W.ln1_g, (const float*)W.ln1_b, u + r0 * h,
+                                  wsp<float>(R, "mu1", l) + r0, wsp<float>(R, "rstd1", l) + r0, Ms, h, H->eps, s);
+    case F_QKV:
+      return launch_gemm(OASES_GEMM_NN, OASES_EPI_BIAS_BF16, Ms, 3 * hp, h, u + r0 * h, h, W.wqkv, 3 * hp, qkv + r0 * 3 * hp,
+                         3 * hp, (const float*)W.bqkv, nullptr, 0, s);
+    case F_ATTN:
+      return launch_attention_fwd(qkv, attn, wsp<float>(R, "lse", l), H->b, H->s, H->heads_l, H->d, H->cfg.causal, (int)r0, Ms, s);
+    case F_PROJ:
+      return launch_gemm(OASES_GEMM_NN, OASES_EPI_F32, Ms, h, hp, attn + r0 * hp, hp, W.wo, h, wsp<float>(R, "z1", l) + r0 * h, h,
+                         nullptr, nullptr, 0, s);
+    case F_R1:
+      return launch_bdr_ln(wsp<float>(R, "z1", l) + r0 * h, peer(P ? P->fwd_attn : nullptr), (const float*)W.bo, xin + r0 * h,
+                           wsp<float>(R, "x1", l) + r0 * h, (const float*)W.ln2_g, (const float*)W.ln2_b, v2 + r0 * h,
+                           wsp<float>(R, "mu2", l) + r0, wsp<float>(R, "rstd2", l) + r0, Ms, h, H->eps,
+                           make_drop_cfg(seed, l, 0, p), (int64_t)r0, s);
+    case F_FC1:
+      return launch_gemm(OASES_GEMM_NN, OASES_EPI_BIAS_GELU, Ms, fp, h, v2 + r0 * h, h, W.w1, fp, f + r0 * fp, fp,
+                         (const float*)W.b1, pre + r0 * fp, fp, s);
+    case F_FC2:
+      return launch_gemm(OASES_GEMM_NN, OASES_EPI_F32, Ms, h, fp, f + r0 * fp, fp, W.w2, h, wsp<float>(R, "z2", l) + r0 * h, h,
+                         nullptr, nullptr, 0, s);
+    case F_R2: {
+      const bool more = l + 1 < L;  // fuse the next layer's LN1 behind this layer's output
+      return launch_bdr_ln(wsp<float>(R, "z2", l) + r0 * h, peer(P ? P->fwd_ffn : nullptr), (const float*)W.b2,
+                           wsp<float>(R, "x1", l) + r0 * h, yout + r0 * h, more ? (const float*)R.w[l + 1].ln1_g : nullptr,
+                           more ? (const float*)R.w[l + 1].ln1_b : nullptr, more ? wsp<uint16_t>(R, "u", l + 1) + r0 * h : nullptr,
+                           more ? wsp<float>(R, "mu1", l + 1) + r0 : nullptr, more ? wsp<float>(R, "rstd1", l + 1) + r0 : nullptr,
+                           Ms, h, H->eps, make_drop_cfg(seed, l, 1, p), (int64_t)r0, s);
+    }
+    // ---------------------------------------------------------------- backward
+    case B_BDR2:
+      return launch_dropout_bwd(dyin + r0 * h, wsp<uint16_t>(R, "dz2", l) + r0 * h, (float*)R.g[l].b2, Ms, h,
+                                make_drop_cfg(seed, l, 1, p), (int64_t)r0, scr_comm, s);
+    case B_FC2_DGRAD:
+      return launch_gemm(OASES_GEMM_NT, OASES_EPI_DGELU, Ms, fp, h, wsp<uint16_t>(R, "dz2", l) + r0 * h, h, W.w2, h,
+                         wsp<uint16_t>(R, "dg", l) + r0 * fp, fp, nullptr, pre + r0 * fp, fp, s);
+    case B_FC1_DGRAD:
+      return launch_gemm(OASES_GEMM_NT, OASES_EPI_F32, Ms, h, fp, wsp<uint16_t>(R, "dg", l) + r0 * fp, fp, W.w1, fp,
+                         wsp<float>(R, "dv2", l) + r0 * h, h, nullptr, nullptr, 0, s);
+    case B_R3:
+      return launch_layernorm_bwd(wsp<float>(R, "dv2", l) + r0 * h, peer(P ? P->bwd_ffn : nullptr), dyin + r0 * h,
+                                  wsp<float>(R, "x1", l) + r0 * h, wsp<float>(R, "mu2", l) + r0, wsp<float>(R, "rstd2", l) + r0,
+                                  (const float*)W.ln2_g, wsp<float>(R, "dx1", l) + r0 * h, (float*)R.g[l].ln2_g,
+                                  (float*)R.g[l].ln2_b, wsp<uint16_t>(R, "dz1", l) + r0 * h, (float*)R.g[l].bo, Ms, h,
+                                  make_drop_cfg(seed, l, 0, p), (int64_t)r0, scr_comm, s);
+    case B_FC2_WGRAD:
+      return launch_gemm(OASES_GEMM_TN, 0, fp, h, Ms, f + r0 * fp, fp, wsp<uint16_t>(R, "dz2", l) + r0 * h, h, R.g[l].w2, h,
+                         nullptr, nullptr, 0, s);
+    case B_FC1_WGRAD:
+      return launch_gemm(OASES_GEMM_TN, 0, h, fp, Ms, v2 + r0 * h, h, wsp<uint16_t>(R, "dg", l) + r0 * fp, fp, R.g[l].w1, fp,
+                         nullptr, nullptr, 0, s);
+    case B_B1_SUM:
+      return launch_colsum_bf16(wsp<uint16_t>(R, "dg", l) + r0 * fp, fp, Ms, fp, (float*)R.g[l].b1, scr_comp, s);
+    case B_PROJ_DGRAD:
+      return launch_gemm(OASES_GEMM_NT, OASES_EPI_BF16, Ms, hp, h, wsp<uint16_t>(R, "dz1", l) + r0 * h, h, W.wo, h,
+                         wsp<uint16_t>(R, "da", l) + r0 * hp, hp, nullptr, nullptr, 0, s);
+    case B_PROJ_WGRAD:
+      return launch_gemm(OASES_GEMM_TN, 0, hp, h, Ms, attn + r0 * hp, hp, wsp<uint16_t>(R, "dz1", l) + r0 * h, h, R.g[l].wo, h,
+                         nullptr, nullptr, 0, s);
+    case B_ATTN:
+      return launch_attention_bwd(qkv, attn, wsp<uint16_t>(R, "da", l), wsp<float>(R, "lse", l), wsp<float>(R, "delta", l),
+                                  wsp<uint16_t>(R, "dqkv", l), H->b, H->s, H->heads_l, H->d, H->cfg.causal, (int)r0, Ms, s);
+    case B_QKV_DGRAD:
+      return launch_gemm(OASES_GEMM_NT, OASES_EPI_F32, Ms, h, 3 * hp, wsp<uint16_t>(R, "dqkv", l) + r0 * 3 * hp, 3 * hp, W.wqkv,
+                         3 * hp, wsp<float>(R, "du", l) + r0 * h, h, nullptr, nullptr, 0, s);
+    case B_R4: {
+      const bool more = l > 0;  // fuse the dropout backward of the layer below (its BDR2) behind dx
+      return launch_layernorm_bwd(wsp<float>(R, "du", l) + r0 * h, peer(P ? P->bwd_attn : nullptr),
+                                  wsp<float>(R, "dx1", l) + r0 * h, xin + r0 * h, wsp<float>(R, "mu1", l) + r0,
+                                  wsp<float>(R, "rstd1", l) + r0, (const float*)W.ln1_g, dxout + r0 * h, (float*)R.g[l].ln1_g,
+                                  (float*)R.g[l].ln1_b, more ? wsp<uint16_t>(R, "dz2", l - 1) + r0 * h : nullptr,
+                                  more ? (float*)R.g[l - 1].b2 : nullptr, Ms, h, make_drop_cfg(seed, l - 1, 1, p), (int64_t)r0,
+                                  scr_comm, s);
+    }
+    case B_QKV_WGRAD:
+      return launch_gemm(OASES_GEMM_TN, 0, h, 3 * hp, Ms, u + r0 * h, h, wsp<uint16_t>(R, "dqkv", l) + r0 * 3 * hp, 3 * hp,
+                         R.g[l].wqkv, 3 * hp, nullptr, nullptr, 0, s);
+    case B_BQKV_SUM:
+      return launch_colsum_bf16(wsp<uint16_t>(R, "dqkv", l) + r0 * 3 * hp, 3 * hp, Ms, 3 * hp, (float*)R.g[l].bqkv, scr_comp, s);
+    case JOIN:
+      return 0;
+  }
+  set_error("unknown operator %d", op.kind);
+  return OASES_EINVAL;
+}
+
+static int run_ops(const Run& R, const std::vector<Op>& ops) {
+  oases_handle* H = R.H;
+  const bool serial = (H->cfg.flags & OASES_FLAG_SERIALISE) || R.st[0] == R.st[1];
+  if (!serial) {
+    int rc = ensure_events(H);
+    if (rc) return rc;
+  }
+  if (!serial) {  // everything already enqueued on stream_compute (inputs) precedes the work on stream_comm
+    OASES_HIP(hipEventRecord(H->events[H->n_events - 1], R.st[0]));
+    OASES_HIP(hipStreamWaitEvent(R.st[1], H->events[H->n_events - 1], 0));
+  }
+  for (const Op& op0 : ops) {
+    Op op = op0;
+    if (serial) op.stream = 0;
+    if (!serial && op.wait >= 0) OASES_HIP(hipStreamWaitEvent(R.st[op.stream], H->events[op.wait], 0));
+    int rc = run_op(R, op);
+    if (rc) return rc;
+    if (!serial && op.record >= 0) OASES_HIP(hipEventRecord(H->events[op.record], R.st[op.stream]));
+  }
+  return 0;
+}
+
+}  // namespace oases
+
+// =================================================================================================
+extern "C" {
+
+const char* oases_last_error(void) { return g_err; }
+
+int oases_create(const oases_layer_cfg* c, oases_handle** out) {
+  if (!c || !out) { set_error("oases_create: NULL argument"); return OASES_ENULL; }
+  *out = nullptr;
+#define BAD(...) do { set_error(__VA_ARGS__); return OASES_EINVAL; } while (0)
+  if (c->hidden <= 0 || c->n_heads <= 0 || c->seq <= 0 || c->batch <= 0) BAD("hidden, n_heads, seq, batch must be positive");
+  if (c->tp_degree <= 0 || c->tp_rank < 0 || c->tp_rank >= c->tp_degree) BAD("tp_rank %d outside [0, %d)", c->tp_rank, c->tp_degree);
+  if (c->n_sub <= 0 || c->n_layers <= 0) BAD("n_sub and n_layers must be >= 1");
+  if (c->hidden % c->n_heads) BAD("hidden %d not divisible by n_heads %d", c->hidden, c->n_heads);
+  const int d = c->hidden / c->n_heads;
+  if (d != 64 && d != 128) BAD("head dimension %d unsupported (64 or 128)", d);
+  if (c->n_heads % c->tp_degree) BAD("n_heads %d not divisible by tp_degree %d", c->n_heads, c->tp_degree);
+  if ((4 * c->hidden) % c->tp_degree) BAD("FFN width %d not divisible by tp_degree %d", 4 * c->hidden, c->tp_degree);
+  if (c->hidden > 16384) BAD("hidden %d too large (max 16384)", c->hidden);
+  if (!(c->dropout_p >= 0.f && c->dropout_p < 1.f)) BAD("dropout_p %g outside [0,1)", (double)c->dropout_p);
+  if (c->ln_eps < 0.f) BAD("ln_eps negative");
+  const long M = (long)c->batch * c->seq;
+  if (M > (1l << 30)) BAD("too many tokens");
+  if (M % c->n_sub) BAD("tokens %ld not divisible by n_sub %d", M, c->n_sub);
+  const long Ms = M / c->n_sub;
+  if (Ms % 8) BAD("rows per sub-batch %ld must be a multiple of 8", Ms);
+  if (c->n_sub <= c->batch) {
+    if (c->batch % c->n_sub) BAD("batch %d not divisible by n_sub %d", c->batch, c->n_sub);
+  } else {
+    if (c->n_sub % c->batch || c->seq % (c->n_sub / c->batch)) BAD("n_sub %d does not split %d sequences of %d evenly", c->n_sub, c->batch, c->seq);
+    if (!c->causal) BAD("sub-batches that are chunks of a sequence need causal attention");
+  }
+#undef BAD
+  oases_handle* H = new (std::nothrow) oases_handle();
+  if (!H) { set_error("out of host memory"); return OASES_EINVAL; }
+  H->cfg = *c;
+  H->h = c->hidden; H->nh = c->n_heads; H->d = d; H->s = c->seq; H->b = c->batch; H->t = c->tp_degree; H->r = c->tp_rank;
+  H->n = c->n_sub; H->L = c->n_layers; H->M = (int)M; H->Ms = (int)Ms;
+  H->hp = c->hidden / c->tp_degree; H->fp = 4 * c->hidden / c->tp_degree; H->heads_l = c->n_heads / c->tp_degree;
+  H->eps = c->ln_eps > 0.f ? c->ln_eps : 1e-5f;
+  H->n_events = H->L * 4 * H->n * 2 + 1;  // + the fork event that orders stream_comm behind stream_compute
+  plan_workspace(H);
+  build_forward(H);
+  build_backward(H);
+  *out = H;
+  return 0;
+}
+
+void oases_destroy(oases_handle* H) {
+  if (!H) return;
+  for (auto& e : H->events) (void)hipEventDestroy(e);
+  delete H;
+}
+
+size_t oases_workspace_bytes(const oases_handle* H) { return H ? H->total_bytes : 0; }
+
+int oases_workspace_tensor(const oases_handle* H, const char* name, int layer, size_t* offset, size_t* bytes) {
+  if (!H || !name || !offset || !bytes) { set_error("oases_workspace_tensor: NULL argument"); return OASES_ENULL; }
+  if (layer < 0 || layer >= H->L) { set_error("layer %d out of range", layer); return OASES_EINVAL; }
+  for (auto& t : H->tensors)
+    if (!strcmp(t.name, name)) {
+      *offset = (size_t)layer * H->layer_bytes + t.offset;
+      *bytes = t.bytes;
+      return 0;
+    }
+  set_error("unknown workspace tensor '%s'", name);
+  return OASES_EINVAL;
+}
+
+int oases_schedule_dump(const oases_handle* H, int backward, char* buf, size_t n) {
+  if (!H) { set_error("oases_schedule_dump: NULL handle"); return OASES_ENULL; }
+  std::string s;
+  char line[96];
+  for (const Op& op : backward ? H->bwd : H->fwd) {
+    snprintf(line, sizeof line, "%s %s L%d sb%d\n", op.stream ? "comm" : "compute", kOpName[op.kind], op.layer, op.sub);
+    s += line;
+  }
+  if (buf && n) {
+    size_t k = s.size() < n - 1 ? s.size() : n - 1;
+    memcpy(buf, s.data(), k);
+    buf[k] = 0;
+  }
+  return (int)s.size();
+}
+
+static int check_weights(const oases_handle* H, const oases_weights* w) {
+  for (int l = 0; l < H->L; l++) {
+    const void* p[] = {w[l].ln1_g, w[l].ln1_b, w[l].wqkv, w[l].bqkv, w[l].wo, w[l].bo, w[l].ln2_g, w[l].ln2_b, w[l].w1, w[l].b1, w[l].w2, w[l].b2};
+    int rc = check_ptrs(p, 12, "weights");
+    if (rc) return rc;
+  }
+  return 0;
+}
+
+int oases_forward(oases_handle* H, const oases_weights* w, const void* x, void* y, const oases_peer_sums* peers,
+                  void* workspace, void* stream_compute, void* stream_comm) {
+  if (!H || !w) { set_error("oases_forward: NULL handle or weights"); return OASES_ENULL; }
+  const void* p[] = {x, y, workspace};
+  int rc = check_ptrs(p, 3, "oases_forward");
+  if (rc) return rc;
+  if (x == y) { set_error("oases_forward: y may not alias x"); return OASES_EINVAL; }
+  if ((rc = check_weights(H, w))) return rc;
+  Run R{H, w, nullptr, peers, (char*)workspace, (const float*)x, (float*)y, nullptr, nullptr,
+        {(hipStream_t)stream_compute, (hipStream_t)stream_comm}};
+  return run_ops(R, H->fwd);
+}
+
+int oases_backward(oases_handle* H, const oases_weights* w, const void* x, const void* dy, void* dx, const oases_grads* g,
+                   const oases_peer_sums* peers, void* workspace, void* stream_compute, void* stream_comm) {
+  if (!H || !w || !g) { set_error("oases_backward: NULL handle, weights or grads"); return OASES_ENULL; }
+  const void* p[] = {x, dy, dx, workspace};
+  int rc = check_ptrs(p, 4, "oases_backward");
+  if (rc) return rc;
+  if ((rc = check_weights(H, w))) return rc;
+  for (int l = 0; l < H->L; l++) {
+    const void* q[] = {g[l].ln1_g, g[l].ln1_b, g[l].wqkv, g[l].bqkv, g[l].wo, g[l].bo, g[l].ln2_g, g[l].ln2_b, g[l].w1, g[l].b1, g[l].w2, g[l].b2};
+    if ((rc = check_ptrs(q, 12, "grads"))) return rc;
+  }
+  Run R{H, w, g, peers, (char*)workspace, (const float*)x, nullptr, (const float*)dy, (float*)dx,
+        {(hipStream_t)stream_compute, (hipStream_t)stream_comm}};
+  return run_ops(R, H->bwd);
+}
+
+// ---------------------------------------------------------------------------------------------
+// single operators
+// ---------------------------------------------------------------------------------------------
+int oases_op_dropout_mask(uint8_t* mask, uint64_t seed, int layer, int site, int64_t row0, int rows, int h, float p, void* stream) {
+  return launch_dropout_mask(mask, make_drop_cfg(seed, layer, site, p), row0, rows, h, (hipStream_t)stream);
+}
+int oases_op_layernorm_fwd(const void* x, const void* gamma, const void* beta, void* out, void* mu, void* rstd, int rows, int h,
+                           float eps, void* stream) {
+  return launch_layernorm_fwd((const float*)x, (const float*)gamma, (const float*)beta, out, (float*)mu, (float*)rstd, rows, h, eps,
+                              (hipStream_t)stream);
+}
+int oases_op_bias_dropout_residual_ln(const void* part, const void* peer, const void* bias, const void* xin, void* xo,
+                                      const void* gamma, const void* beta, void* ln_out, void* mu, void* rstd, int rows, int h,
+                                      float eps, uint64_t seed, int layer, int site, int64_t row0, float p, void* stream) {
+  if (!part) { set_error("bias_dropout_residual_ln: NULL partial"); return OASES_ENULL; }
+  return launch_bdr_ln((const float*)part, (const float*)peer, (const float*)bias, (const float*)xin, (float*)xo, (const float*)gamma,
+                       (const float*)beta, ln_out, (float*)mu, (float*)rstd, rows, h, eps, make_drop_cfg(seed, layer, site, p), row0,
+                       (hipStream_t)stream);
+}
+int oases_op_dropout_bwd(const void* dyin, void* dz, void* dbias, int rows, int h, uint64_t seed, int layer, int site, int64_t row0,
+                         float p, void* scratch, void* stream) {
+  return launch_dropout_bwd((const float*)dyin, dz, (float*)dbias, rows, h, make_drop_cfg(seed, layer, site, p), row0, (float*)scratch,
+                            (hipStream_t)stream);
+}
+int oases_op_layernorm_bwd(const void* part, const void* peer, const void* dres, const void* x, const void* mu, const void* rstd,
+                           const void* gamma, void* dxo, void* dgamma, void* dbeta, void* dz, void* dbias, int rows, int h,
+                           uint64_t seed, int layer, int site, int64_t row0, float p, void* scratch, void* stream) {
+  return launch_layernorm_bwd((const float*)part, (const float*)peer, (const float*)dres, (const float*)x, (const float*)mu,
+                              (const float*)rstd, (const float*)gamma, (float*)dxo, (float*)dgamma, (float*)dbeta, dz, (float*)dbias,
+                              rows, h, make_drop_cfg(seed, layer, site, p), row0, (float*)scratch, (hipStream_t)stream);
+}
+int oases_op_gemm(int op, int epi, int M, int N, int K, const void* A, int lda, const void* B, int ldb, void* C, int ldc,
+                  const void* bias, void* aux, int ldaux, void* stream) {
+  return launch_gemm(op, epi, M, N, K, A, lda, B, ldb, C, ldc, (const float*)bias, aux, ldaux, (hipStream_t)stream);
+}
+int oases_op_colsum_bf16(const void* a, int ld, int rows, int cols, void* out, void* scratch, void* stream) {
+  return launch_colsum_bf16(a, ld, rows, cols, (float*)out, (float*)scratch, (hipStream_t)stream);
+}
+int oases_op_attention_fwd(const void* qkv, void* out, void* lse, int batch, int seq, int heads, int head_dim, int causal, int row0,
+                           int rows, void* stream) {
+  return launch_attention_fwd(qkv, out, (float*)lse, batch, seq, heads, head_dim, causal, row0, rows, (hipStream_t)stream);
+}
+int oases_op_attention_bwd(const void* qkv, const void* out, const void* dout, const void* lse, void* delta, void* dqkv, int batch,
+                           int seq, int heads, int head_dim, int causal, int row0, int rows, void* stream) {
+  return launch_attention_bwd(qkv, out, dout, (const float*)lse, (float*)delta, dqkv, batch, seq, heads, head_dim, causal, row0, rows,
+                              (hipStream_t)stream);
+}
+
+}  // extern "C"

@@ -1,0 +1,375 @@
+// HBM-bound kernels of the layer: LayerNorm forward/backward, the fused
+// reduction-point + bias + dropout + residual (+ LayerNorm) step, dropout backward, and the
+// two-stage (deterministic) column reductions that give bias / LayerNorm-parameter gradients.
+// One 256-thread workgroup walks whole rows with 16-byte accesses; a row stays in registers
+// between its reduction and its write, so every tensor is read once and written once.
+#include "common.h"
+
+namespace oases {
+
+namespace {
+
+constexpr int NT = 256;
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+
+// sum over the 256 threads of the workgroup, result in every thread; red: 2 x 4 floats of LDS
+__device__ __forceinline__ void block_sum2(float& a, float& b, float* red) {
+  a = wave_sum(a);
+  b = wave_sum(b);
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  __syncthreads();  // red may still be read by the previous use
+  if (lane == 0) { red[w] = a; red[4 + w] = b; }
+  __syncthreads();
+  a = red[0] + red[1] + red[2] + red[3];
+  b = red[4] + red[5] + red[6] + red[7];
+}
+
+__device__ __forceinline__ void store_bf16x4(uint16_t* p, float a, float b, float c, float d) {
+  u32x2 v = {pack_bf16x2(a, b), pack_bf16x2(c, d)};
+  *reinterpret_cast<u32x2*>(p) = v;
+}
+
+// ------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(NT) void dropout_mask_kernel(uint8_t* mask, DropCfg d, uint64_t q0, int64_t nq) {
+  int64_t i = (int64_t)blockIdx.x * NT + threadIdx.x;
+  if (i >= nq) return;
+  bool k[4];
+  dropout_keep4(d, q0 + (uint64_t)i, k);
+  uint32_t v = (uint32_t)k[0] | ((uint32_t)k[1] << 8) | ((uint32_t)k[2] << 16) | ((uint32_t)k[3] << 24);
+  reinterpret_cast<uint32_t*>(mask)[i] = v;
+}
+
+// ------------------------------------------------------------------------------------------------
+// xo = xin + keep * (part + peer + bias) * scale   (if part != nullptr; else the row is xin itself)
+// ln_out = gamma * (xo - mu) * rstd + beta          (if ln_out != nullptr)
+template <int NC>
+__global__ __launch_bounds__(NT) void bdr_ln_kernel(const float* __restrict__ part, const float* __restrict__ peer,
+                                                    const float* __restrict__ bias, const float* __restrict__ xin,
+                                                    float* __restrict__ xo, const float* __restrict__ gamma,
+                                                    const float* __restrict__ beta, uint16_t* __restrict__ ln_out,
+                                                    float* __restrict__ mu_out, float* __restrict__ rstd_out, int h,
+                                                    float eps, DropCfg d, int64_t row0) {
+  __shared__ float red[8];
+  const int row = blockIdx.x, tid = threadIdx.x;
+  const int nc = h >> 2;
+  const size_t base = (size_t)row * h;
+  f32x4 v[NC];
+  float s = 0.f, dummy = 0.f;
+#pragma unroll
+  for (int i = 0; i < NC; i++) {
+    const int c = tid + i * NT;
+    v[i] = f32x4{0.f, 0.f, 0.f, 0.f};
+    if (c < nc) {
+      f32x4 x = *reinterpret_cast<const f32x4*>(xin + base + 4 * c);
+      if (part) {
+        f32x4 z = *reinterpret_cast<const f32x4*>(part + base + 4 * c);
+        if (peer) z += *reinterpret_cast<const f32x4*>(peer + base + 4 * c);
+        z += *reinterpret_cast<const f32x4*>(bias + 4 * c);
+        bool k[4];
+        dropout_keep4(d, ((uint64_t)(row0 + row) * h >> 2) + c, k);
+#pragma unroll
+        for (int j = 0; j < 4; j++) x[j] = k[j] ? x[j] + z[j] * d.scale : x[j];
+        *reinterpret_cast<f32x4*>(xo + base + 4 * c) = x;
+      }
+      v[i] = x;
+      s += x[0] + x[1] + x[2] + x[3];
+    }
+  }
+  if (!ln_out) return;
+  block_sum2(s, dummy, red);
+  const float mu = s / h;
+  float q = 0.f;
+#pragma unroll
+  for (int i = 0; i < NC; i++) {
+    const int c = tid + i * NT;
+    if (c < nc) {
+#pragma unroll
+      for (int j = 0; j < 4; j++) { float t = v[i][j] - mu; q += t * t; }
+    }
+  }
+  block_sum2(q, dummy, red);
+  const float rstd = rsqrtf(q / h + eps);
+  if (tid == 0) { mu_out[row] = mu; rstd_out[row] = rstd; }
+#pragma unroll
+  for (int i = 0; i < NC; i++) {
+    const int c = tid + i * NT;
+    if (c < nc) {
+      f32x4 gm = *reinterpret_cast<const f32x4*>(gamma + 4 * c);
+      f32x4 bt = *reinterpret_cast<const f32x4*>(beta + 4 * c);
+      f32x4 o;
+#pragma unroll
+      for (int j = 0; j < 4; j++) o[j] = gm[j] * ((v[i][j] - mu) * rstd) + bt[j];
+      store_bf16x4(ln_out + base + 4 * c, o[0], o[1], o[2], o[3]);
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
+// dz = keep * dyin * scale (bf16); partial column sums of the unrounded dz into scratch[group][h]
+template <int NC>
+__global__ __launch_bounds__(NT) void dropout_bwd_kernel(const float* __restrict__ dyin, uint16_t* __restrict__ dz,
+                                                         float* __restrict__ scratch, int rows, int h, DropCfg d,
+                                                         int64_t row0) {
+  const int tid = threadIdx.x, nc = h >> 2;
+  f32x4 acc[NC];
+#pragma unroll
+  for (int i = 0; i < NC; i++) acc[i] = f32x4{0.f, 0.f, 0.f, 0.f};
+  for (int row = blockIdx.x; row < rows; row += gridDim.x) {
+    const size_t base = (size_t)row * h;
+#pragma unroll
+    for (int i = 0; i < NC; i++) {
+      const int c = tid + i * NT;
+      if (c < nc) {
+        f32x4 g = *reinterpret_cast<const f32x4*>(dyin + base + 4 * c);
+        bool k[4];
+        dropout_keep4(d, ((uint64_t)(row0 + row) * h >> 2) + c, k);
+#pragma unroll
+        for (int j = 0; j < 4; j++) g[j] = k[j] ? g[j] * d.scale : 0.f;
+        store_bf16x4(dz + base + 4 * c, g[0], g[1], g[2], g[3]);
+        acc[i] += g;
+      }
+    }
+  }
+  if (scratch) {
+#pragma unroll
+    for (int i = 0; i < NC; i++) {
+      const int c = tid + i * NT;
+      if (c < nc) *reinterpret_cast<f32x4*>(scratch + (size_t)blockIdx.x * h + 4 * c) = acc[i];
+    }
+  }
+}
+
+// out[c] += sum_g scratch[k][g][c], for k < nk outputs
+struct FinalizeArgs {
+  float* out[3];
+  int nk;
+};
+__global__ __launch_bounds__(NT) void colsum_finalize_kernel(const float* __restrict__ scratch, FinalizeArgs a, int groups,
+                                                             int cols) {
+  const int c = blockIdx.x * NT + threadIdx.x;
+  if (c >= cols) return;
+  for (int k = 0; k < a.nk; k++) {
+    if (!a.out[k]) continue;
+    const float* p = scratch + (size_t)k * groups * cols + c;
+    float s = 0.f;
+    for (int g = 0; g < groups; g++) s += p[(size_t)g * cols];
+    a.out[k][c] += s;
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
+// g = part + peer;  dxo = dres + rstd * (g*gamma - mean(g*gamma) - xhat * mean(g*gamma*xhat))
+// partials: scratch[0] dgamma = sum g*xhat, scratch[1] dbeta = sum g, scratch[2] dbias = sum dz
+template <int NC>
+__global__ __launch_bounds__(NT) void layernorm_bwd_kernel(const float* __restrict__ part, const float* __restrict__ peer,
+                                                           const float* __restrict__ dres, const float* __restrict__ x,
+                                                           const float* __restrict__ mu, const float* __restrict__ rstd,
+                                                           const float* __restrict__ gamma, float* __restrict__ dxo,
+                                                           uint16_t* __restrict__ dz, float* __restrict__ scratch, int rows,
+                                                           int h, DropCfg d, int64_t row0) {
+  __shared__ float red[8];
+  const int tid = threadIdx.x, nc = h >> 2;
+  const size_t gstride = (size_t)gridDim.x * h;
+  f32x4 ag[NC], ab[NC], az[NC], gm[NC];
+#pragma unroll
+  for (int i = 0; i < NC; i++) {
+    ag[i] = ab[i] = az[i] = gm[i] = f32x4{0.f, 0.f, 0.f, 0.f};
+    const int c = tid + i * NT;
+    if (c < nc) gm[i] = *reinterpret_cast<const f32x4*>(gamma + 4 * c);
+  }
+  for (int row = blockIdx.x; row < rows; row += gridDim.x) {
+    const size_t base = (size_t)row * h;
+    const float m = mu[row], rs = rstd[row];
+    f32x4 gg[NC], xh[NC];
+    float s1 = 0.f, s2 = 0.f;
+#pragma unroll
+    for (int i = 0; i < NC; i++) {
+      const int c = tid + i * NT;
+      gg[i] = xh[i] = f32x4{0.f, 0.f, 0.f, 0.f};
+      if (c < nc) {
+        f32x4 g = *reinterpret_cast<const f32x4*>(part + base + 4 * c);
+        if (peer) g += *reinterpret_cast<const f32x4*>(peer + base + 4 * c);
+        f32x4 xv = *reinterpret_cast<const f32x4*>(x + base + 4 * c);
+#pragma unroll
+        for (int j = 0; j < 4; j++) {
+          xh[i][j] = (xv[j] - m) * rs;
+          ag[i][j] += g[j] * xh[i][j];
+          ab[i][j] += g[j];
+          gg[i][j] = g[j] * gm[i][j];
+          s1 += gg[i][j];
+          s2 += gg[i][j] * xh[i][j];
+        }
+      }
+    }
+    block_sum2(s1, s2, red);
+    const float m1 = s1 / h, m2 = s2 / h;
+#pragma unroll
+    for (int i = 0; i < NC; i++) {
+      const int c = tid + i * NT;
+      if (c < nc) {
+        f32x4 o = *reinterpret_cast<const f32x4*>(dres + base + 4 * c);
+#pragma unroll
+        for (int j = 0; j < 4; j++) o[j] += rs * (gg[i][j] - m1 - xh[i][j] * m2);
+        *reinterpret_cast<f32x4*>(dxo + base + 4 * c) = o;
+        if (dz) {
+          bool k[4];
+          dropout_keep4(d, ((uint64_t)(row0 + row) * h >> 2) + c, k);
+#pragma unroll
+          for (int j = 0; j < 4; j++) o[j] = k[j] ? o[j] * d.scale : 0.f;
+          store_bf16x4(dz + base + 4 * c, o[0], o[1], o[2], o[3]);
+          az[i] += o;
+        }
+      }
+    }
+  }
+#pragma unroll
+  for (int i = 0; i < NC; i++) {
+    const int c = tid + i * NT;
+    if (c < nc) {
+      float* p = scratch + (size_t)blockIdx.x * h + 4 * c;
+      *reinterpret_cast<f32x4*>(p) = ag[i];
+      *reinterpret_cast<f32x4*>(p + gstride) = ab[i];
+      if (dz) *reinterpret_cast<f32x4*>(p + 2 * gstride) = az[i];
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
+// partial column sums of a bf16 matrix; each thread owns 8 columns
+__global__ __launch_bounds__(NT) void colsum_bf16_kernel(const uint16_t* __restrict__ a, int ld, int rows, int cols,
+                                                         float* __restrict__ scratch) {
+  const int c = blockIdx.y * NT + threadIdx.x;  // 8-column chunk
+  if (c * 8 >= cols) return;
+  float acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+  for (int row = blockIdx.x; row < rows; row += gridDim.x) {
+    u32x4 v = *reinterpret_cast<const u32x4*>(a + (size_t)row * ld + 8 * c);
+#pragma unroll
+    for (int j = 0; j < 4; j++) {
+      acc[2 * j] += bf16_bits_to_f32(v[j] & 0xffffu);
+      acc[2 * j + 1] += bf16_bits_to_f32(v[j] >> 16);
+    }
+  }
+  float* p = scratch + (size_t)blockIdx.x * cols + 8 * c;
+  *reinterpret_cast<f32x4*>(p) = f32x4{acc[0], acc[1], acc[2], acc[3]};
+  *reinterpret_cast<f32x4*>(p + 4) = f32x4{acc[4], acc[5], acc[6], acc[7]};
+}
+
+int pick_nc(int h) {
+  const int nc = (h / 4 + NT - 1) / NT;
+  for (int c = 1; c <= 16; c *= 2)
+    if (nc <= c) return c;
+  return 0;
+}
+
+bool check_h(int rows, int h, const char* who) {
+  if (rows <= 0 || h <= 0 || (h % 8) != 0 || pick_nc(h) == 0) {
+    set_error("%s: rows=%d h=%d unsupported (h must be a multiple of 8, at most 16384)", who, rows, h);
+    return false;
+  }
+  return true;
+}
+
+#define OASES_NC_DISPATCH(NCV, ...)          \
+  switch (NCV) {                             \
+    case 1: { constexpr int NC = 1; __VA_ARGS__; break; }   \
+    case 2: { constexpr int NC = 2; __VA_ARGS__; break; }   \
+    case 4: { constexpr int NC = 4; __VA_ARGS__; break; }   \
+    case 8: { constexpr int NC = 8; __VA_ARGS__; break; }   \
+    default: { constexpr int NC = 16; __VA_ARGS__; break; } \
+  }
+
+}  // namespace
+
+DropCfg make_drop_cfg(uint64_t seed, int layer, int site, float p) {
+  DropCfg d;
+  d.k0 = (uint32_t)seed;
+  d.k1 = (uint32_t)(seed >> 32);
+  d.site = (uint32_t)site;
+  d.layer = (uint32_t)layer;
+  double t = (double)p * 16777216.0;
+  d.thresh = p > 0.f ? (uint32_t)__builtin_rint(t) : 0u;
+  d.scale = (float)(1.0 / (1.0 - (double)p));
+  return d;
+}
+
+int launch_dropout_mask(uint8_t* mask, const DropCfg& d, int64_t row0, int rows, int h, hipStream_t s) {
+  if (!mask) { set_error("dropout_mask: NULL"); return OASES_ENULL; }
+  if (rows <= 0 || h <= 0 || h % 4) { set_error("dropout_mask: bad shape"); return OASES_EINVAL; }
+  int64_t nq = (int64_t)rows * h / 4;
+  hipLaunchKernelGGL(dropout_mask_kernel, dim3((unsigned)((nq + NT - 1) / NT)), dim3(NT), 0, s, mask, d,
+                     (uint64_t)row0 * h / 4, nq);
+  OASES_LAUNCH_CHECK("dropout_mask_kernel");
+  return 0;
+}
+
+int launch_bdr_ln(const float* part, const float* peer, const float* bias, const float* xin, float* xo,
+                  const float* gamma, const float* beta, void* ln_out, float* mu, float* rstd, int rows, int h,
+                  float eps, const DropCfg& d, int64_t row0, hipStream_t s) {
+  if (!check_h(rows, h, "bias_dropout_residual_ln")) return OASES_EINVAL;
+  if (!xin || (part && (!bias || !xo)) || (ln_out && (!gamma || !beta || !mu || !rstd))) {
+    set_error("bias_dropout_residual_ln: NULL argument");
+    return OASES_ENULL;
+  }
+  OASES_NC_DISPATCH(pick_nc(h), hipLaunchKernelGGL(bdr_ln_kernel<NC>, dim3(rows), dim3(NT), 0, s, part, peer, bias, xin, xo,
+                                                   gamma, beta, (uint16_t*)ln_out, mu, rstd, h, eps, d, row0));
+  OASES_LAUNCH_CHECK("bdr_ln_kernel");
+  return 0;
+}
+
+int launch_layernorm_fwd(const float* x, const float* gamma, const float* beta, void* out, float* mu, float* rstd,
+                         int rows, int h, float eps, hipStream_t s) {
+  DropCfg d = make_drop_cfg(0, 0, 0, 0.f);
+  if (!out) { set_error("layernorm_fwd: NULL output"); return OASES_ENULL; }
+  return launch_bdr_ln(nullptr, nullptr, nullptr, x, nullptr, gamma, beta, out, mu, rstd, rows, h, eps, d, 0, s);
+}
+
+static int finalize(float* scratch, float* o0, float* o1, float* o2, int nk, int groups, int cols, hipStream_t s) {
+  FinalizeArgs a{{o0, o1, o2}, nk};
+  hipLaunchKernelGGL(colsum_finalize_kernel, dim3((cols + NT - 1) / NT), dim3(NT), 0, s, scratch, a, groups, cols);
+  OASES_LAUNCH_CHECK("colsum_finalize_kernel");
+  return 0;
+}
+
+int launch_dropout_bwd(const float* dyin, void* dz, float* dbias, int rows, int h, const DropCfg& d, int64_t row0,
+                       float* scratch, hipStream_t s) {
+  if (!check_h(rows, h, "dropout_bwd")) return OASES_EINVAL;
+  if (!dyin || !dz || (dbias && !scratch)) { set_error("dropout_bwd: NULL argument"); return OASES_ENULL; }
+  const int groups = rows < kColPartials ? rows : kColPartials;
+  OASES_NC_DISPATCH(pick_nc(h), hipLaunchKernelGGL(dropout_bwd_kernel<NC>, dim3(groups), dim3(NT), 0, s, dyin, (uint16_t*)dz,
+                                                   dbias ? scratch : nullptr, rows, h, d, row0));
+  OASES_LAUNCH_CHECK("dropout_bwd_kernel");
+  if (dbias) return finalize(scratch, dbias, nullptr, nullptr, 1, groups, h, s);
+  return 0;
+}
+
+int launch_layernorm_bwd(const float* part, const float* peer, const float* dres, const float* x, const float* mu,
+                         const float* rstd, const float* gamma, float* dxo, float* dgamma, float* dbeta, void* dz,
+                         float* dbias, int rows, int h, const DropCfg& d, int64_t row0, float* scratch, hipStream_t s) {
+  if (!check_h(rows, h, "layernorm_bwd")) return OASES_EINVAL;
+  if (!part || !dres || !x || !mu || !rstd || !gamma || !dxo || !dgamma || !dbeta || !scratch || (dz && !dbias)) {
+    set_error("layernorm_bwd: NULL argument");
+    return OASES_ENULL;
+  }
+  const int groups = rows < kColPartials ? rows : kColPartials;
+  OASES_NC_DISPATCH(pick_nc(h), hipLaunchKernelGGL(layernorm_bwd_kernel<NC>, dim3(groups), dim3(NT), 0, s, part, peer, dres, x, mu,
+                                                   rstd, gamma, dxo, (uint16_t*)dz, scratch, rows, h, d, row0));
+  OASES_LAUNCH_CHECK("layernorm_bwd_kernel");
+  return finalize(scratch, dgamma, dbeta, dz ? dbias : nullptr, dz ? 3 : 2, groups, h, s);
+}
+
+int launch_colsum_bf16(const void* a, int ld, int rows, int cols, float* out, float* scratch, hipStream_t s) {
+  if (!a || !out || !scratch) { set_error("colsum_bf16: NULL argument"); return OASES_ENULL; }
+  if (rows <= 0 || cols <= 0 || cols % 8 || ld % 8 || ld < cols) { set_error("colsum_bf16: bad shape"); return OASES_EINVAL; }
+  const int groups = rows < kColPartials ? rows : kColPartials;
+  hipLaunchKernelGGL(colsum_bf16_kernel, dim3(groups, (cols / 8 + NT - 1) / NT), dim3(NT), 0, s, (const uint16_t*)a, ld, rows,
+                     cols, scratch);
+  OASES_LAUNCH_CHECK("colsum_bf16_kernel");
+  return finalize(scratch, out, nullptr, nullptr, 1, groups, cols, s);
+}
+
+}  // namespace oases

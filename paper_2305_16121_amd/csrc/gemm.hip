@@ -1,0 +1,266 @@
+// bf16 MFMA GEMM family for gfx950: C = A*B with fp32 accumulation, LDS-staged tiles.
+//
+// One kernel template covers the three contractions of a linear map under Megatron's partition
+// (paper Sec. II): forward (A k-contiguous, B n-contiguous), input gradient (both k-contiguous) and
+// weight gradient (both stored with the contraction index as the row).  A k-contiguous operand tile
+// is kept in LDS as [rows][64 k] with a 16-byte-chunk XOR swizzle and read with ds_read_b128; an
+// operand stored with the contraction index as row is kept as [64 k][rows] (padded rows) and read
+// with the LDS transpose read ds_read_b64_tr_b16, which hands each lane 4 consecutive k of one row.
+// v_mfma_f32_32x32x16_bf16: A lane l holds row l%32, k = 8*(l/32)..+7; B the same with columns;
+// accumulator element i of lane l is C[8*(i/4) + 4*(l/32) + i%4][l%32].
+#include "common.h"
+
+namespace oases {
+
+namespace {
+
+constexpr int BK = 64;          // k extent of one LDS stage
+constexpr int kMcPadBytes = 64; // row padding of a "contraction-major" tile (keeps transpose reads off the same banks)
+
+struct GemmArgs {
+  const uint16_t* A;
+  const uint16_t* B;
+  void* C;
+  const float* bias;
+  uint16_t* aux;
+  int M, N, K;
+  int lda, ldb, ldc, ldaux;
+  int tiles_m, tiles_n;
+};
+
+template <int R, bool KC>
+struct TileLayout {
+  static constexpr int row_bytes = KC ? BK * 2 : R * 2 + kMcPadBytes;
+  static constexpr int rows = KC ? R : BK;
+  static constexpr int bytes = rows * row_bytes;
+  static constexpr int chunks_per_row = KC ? BK / 8 : R / 8;
+  static constexpr int chunks = rows * chunks_per_row;
+};
+
+// global -> registers for one operand tile
+template <int R, bool KC, int NT>
+__device__ __forceinline__ void load_tile_global(u32x4* regs, const uint16_t* __restrict__ base,
+                                                 int ld, int r0, int k0, int rmax, int kmax, int tid) {
+  using L = TileLayout<R, KC>;
+#pragma unroll
+  for (int i = 0; i < L::chunks / NT; i++) {
+    int c = tid + i * NT;
+    int row = c / L::chunks_per_row, cc = c % L::chunks_per_row;
+    int gr, gk;
+    if (KC) { gr = r0 + row; gk = k0 + cc * 8; } else { gk = k0 + row; gr = r0 + cc * 8; }
+    bool ok = (gr < rmax) && (gk < kmax);
+    const uint16_t* p = KC ? base + (size_t)gr * ld + gk : base + (size_t)gk * ld + gr;
+    u32x4 v = {0u, 0u, 0u, 0u};
+    if (ok) v = *reinterpret_cast<const u32x4*>(p);
+    regs[i] = v;
+  }
+}
+
+template <int R, bool KC, int NT>
+__device__ __forceinline__ void store_tile_lds(const u32x4* regs, char* lds, int tid) {
+  using L = TileLayout<R, KC>;
+#pragma unroll
+  for (int i = 0; i < L::chunks / NT; i++) {
+    int c = tid + i * NT;
+    int row = c / L::chunks_per_row, cc = c % L::chunks_per_row;
+    int off = KC ? row * L::row_bytes + ((cc ^ (row & 7)) << 4) : row * L::row_bytes + (cc << 4);
+    *reinterpret_cast<u32x4*>(lds + off) = regs[i];
+  }
+}
+
+// One 32(row) x 16(k) MFMA operand fragment out of an LDS tile.  r0: first row of the fragment in the
+// tile (multiple of 32); kk: which 16-wide k step of the stage.
+template <int R, bool KC>
+__device__ __forceinline__ bf16x8 read_frag(const char* lds, int r0, int kk, int lane) {
+  using L = TileLayout<R, KC>;
+  if (KC) {
+    int row = r0 + (lane & 31);
+    int chunk = kk * 2 + (lane >> 5);
+    const char* p = lds + row * L::row_bytes + ((chunk ^ (lane & 7)) << 4);
+    return *reinterpret_cast<const bf16x8*>(p);
+  } else {
+    int krow = kk * 16 + 8 * (lane >> 5) + ((lane & 15) >> 2);
+    int col = r0 + 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
+    const char* p = lds + krow * L::row_bytes + col * 2;
+    short4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((OASES_LDS short4v*)(p));
+    short4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((OASES_LDS short4v*)(p + 4 * L::row_bytes));
+    typedef short short8v __attribute__((ext_vector_type(8)));
+    short8v v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+    return __builtin_bit_cast(bf16x8, v);
+  }
+}
+
+enum { EPI_F32 = 0, EPI_BF16 = 1, EPI_BIAS_BF16 = 2, EPI_BIAS_GELU = 3, EPI_DGELU = 4, EPI_ACC_F32 = 5 };
+
+template <int BM, int BN, int WGM, int WGN, bool A_KC, bool B_KC, int EPI>
+__global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmArgs g) {
+  constexpr int NT = 64 * WGM * WGN;
+  constexpr int WTM = BM / WGM, WTN = BN / WGN;
+  constexpr int TM = WTM / 32, TN = WTN / 32;
+  using LA = TileLayout<BM, A_KC>;
+  using LB = TileLayout<BN, B_KC>;
+  __shared__ __attribute__((aligned(16))) char lds[2 * (LA::bytes + LB::bytes)];
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave / WGN, wn = wave % WGN;
+
+  // workgroup -> tile: undo the round-robin of workgroup ids over the 8 XCDs so that each XCD's L2 sees a
+  // contiguous range of tiles, then walk that range in groups of 8 tile rows.
+  int tile_m, tile_n;
+  {
+    const int T = g.tiles_m * g.tiles_n;
+    int pid = blockIdx.x;
+    const int per = (T + 7) / 8, tall = (T % 8 == 0) ? 8 : T % 8;
+    int xcd = pid & 7, local = pid >> 3;
+    int logical = xcd < tall ? xcd * per + local : tall * per + (xcd - tall) * (per - 1) + local;
+    constexpr int GM = 8;
+    int width = GM * g.tiles_n;
+    int group = logical / width, first_m = group * GM;
+    int gsz = min(g.tiles_m - first_m, GM);
+    tile_m = first_m + (logical % width) % gsz;
+    tile_n = (logical % width) / gsz;
+  }
+  const int m0 = tile_m * BM, n0 = tile_n * BN;
+
+  f32x16 acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; i++)
+#pragma unroll
+    for (int j = 0; j < TN; j++)
+#pragma unroll
+      for (int e = 0; e < 16; e++) acc[i][j][e] = 0.f;
+
+  u32x4 ra[LA::chunks / NT], rb[LB::chunks / NT];
+  const int nk = (g.K + BK - 1) / BK;
+  constexpr int kStage = LA::bytes + LB::bytes;  // stage s: A at lds + s*kStage, B behind it
+
+  load_tile_global<BM, A_KC, NT>(ra, g.A, g.lda, m0, 0, g.M, g.K, tid);
+  load_tile_global<BN, B_KC, NT>(rb, g.B, g.ldb, n0, 0, g.N, g.K, tid);
+  store_tile_lds<BM, A_KC, NT>(ra, lds, tid);
+  store_tile_lds<BN, B_KC, NT>(rb, lds + LA::bytes, tid);
+  if (nk > 1) {
+    load_tile_global<BM, A_KC, NT>(ra, g.A, g.lda, m0, BK, g.M, g.K, tid);
+    load_tile_global<BN, B_KC, NT>(rb, g.B, g.ldb, n0, BK, g.N, g.K, tid);
+  }
+  __syncthreads();
+
+  for (int kt = 0; kt < nk; kt++) {
+    const int cur = kt & 1;
+    if (kt + 1 < nk) {  // tile kt+1 sits in registers: park it in the other stage, then fetch tile kt+2
+      store_tile_lds<BM, A_KC, NT>(ra, lds + (cur ^ 1) * kStage, tid);
+      store_tile_lds<BN, B_KC, NT>(rb, lds + (cur ^ 1) * kStage + LA::bytes, tid);
+      if (kt + 2 < nk) {
+        load_tile_global<BM, A_KC, NT>(ra, g.A, g.lda, m0, (kt + 2) * BK, g.M, g.K, tid);
+        load_tile_global<BN, B_KC, NT>(rb, g.B, g.ldb, n0, (kt + 2) * BK, g.N, g.K, tid);
+      }
+    }
+    const char* la = lds + cur * kStage;
+    const char* lb = la + LA::bytes;
+#pragma unroll
+    for (int kk = 0; kk < BK / 16; kk++) {
+      bf16x8 fa[TM], fb[TN];
+#pragma unroll
+      for (int i = 0; i < TM; i++) fa[i] = read_frag<BM, A_KC>(la, wm * WTM + i * 32, kk, lane);
+#pragma unroll
+      for (int j = 0; j < TN; j++) fb[j] = read_frag<BN, B_KC>(lb, wn * WTN + j * 32, kk, lane);
+#pragma unroll
+      for (int i = 0; i < TM; i++)
+#pragma unroll
+        for (int j = 0; j < TN; j++)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+    }
+    __syncthreads();
+  }
+
+  // epilogue: lane l owns column l%32 of each 32x32 tile and rows 8*(i/4) + 4*(l/32) + i%4
+#pragma unroll
+  for (int j = 0; j < TN; j++) {
+    const int col = n0 + wn * WTN + j * 32 + (lane & 31);
+    const bool cok = col < g.N;
+    float bias = 0.f;
+    if ((EPI == EPI_BIAS_BF16 || EPI == EPI_BIAS_GELU) && cok) bias = g.bias[col];
+#pragma unroll
+    for (int i = 0; i < TM; i++) {
+#pragma unroll
+      for (int e = 0; e < 16; e++) {
+        const int row = m0 + wm * WTM + i * 32 + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
+        if (!cok || row >= g.M) continue;
+        float v = acc[i][j][e];
+        const size_t o = (size_t)row * g.ldc + col;
+        if (EPI == EPI_F32) {
+          reinterpret_cast<float*>(g.C)[o] = v;
+        } else if (EPI == EPI_ACC_F32) {
+          reinterpret_cast<float*>(g.C)[o] += v;
+        } else if (EPI == EPI_BF16) {
+          reinterpret_cast<uint16_t*>(g.C)[o] = (uint16_t)f32_to_bf16_bits(v);
+        } else if (EPI == EPI_BIAS_BF16) {
+          reinterpret_cast<uint16_t*>(g.C)[o] = (uint16_t)f32_to_bf16_bits(v + bias);
+        } else if (EPI == EPI_BIAS_GELU) {
+          float pre = v + bias;
+          g.aux[(size_t)row * g.ldaux + col] = (uint16_t)f32_to_bf16_bits(pre);
+          reinterpret_cast<uint16_t*>(g.C)[o] = (uint16_t)f32_to_bf16_bits(gelu_tanh(pre));
+        } else if (EPI == EPI_DGELU) {
+          float pre = bf16_bits_to_f32(g.aux[(size_t)row * g.ldaux + col]);
+          reinterpret_cast<uint16_t*>(g.C)[o] = (uint16_t)f32_to_bf16_bits(v * gelu_tanh_grad(pre));
+        }
+      }
+    }
+  }
+}
+
+template <int BM, int BN, int WGM, int WGN, bool A_KC, bool B_KC, int EPI>
+int launch_one(const GemmArgs& g0, hipStream_t s) {
+  GemmArgs g = g0;
+  g.tiles_m = (g.M + BM - 1) / BM;
+  g.tiles_n = (g.N + BN - 1) / BN;
+  dim3 grid(g.tiles_m * g.tiles_n), block(64 * WGM * WGN);
+  hipLaunchKernelGGL((gemm_kernel<BM, BN, WGM, WGN, A_KC, B_KC, EPI>), grid, block, 0, s, g);
+  OASES_LAUNCH_CHECK("gemm_kernel");
+  return 0;
+}
+
+// tile choice: 256x256 when it fills the chip at least once over, else 128x128
+template <bool A_KC, bool B_KC, int EPI>
+int launch_shape(const GemmArgs& g, hipStream_t s) {
+  long t256 = (long)((g.M + 255) / 256) * ((g.N + 255) / 256);
+  if (t256 >= 256 && g.M % 256 == 0 && g.N % 256 == 0) return launch_one<256, 256, 2, 2, A_KC, B_KC, EPI>(g, s);
+  return launch_one<128, 128, 2, 2, A_KC, B_KC, EPI>(g, s);
+}
+
+}  // namespace
+
+int launch_gemm(int op, int epi, int M, int N, int K, const void* A, int lda, const void* B, int ldb, void* C,
+                int ldc, const float* bias, void* aux, int ldaux, hipStream_t s) {
+  if (M <= 0 || N <= 0 || K <= 0 || (M % 8) || (N % 8) || (K % 8) || (lda % 8) || (ldb % 8)) {
+    set_error("gemm: M,N,K,lda,ldb must be positive multiples of 8 (got M=%d N=%d K=%d lda=%d ldb=%d)", M, N, K, lda, ldb);
+    return OASES_EINVAL;
+  }
+  if (!A || !B || !C) { set_error("gemm: NULL operand"); return OASES_ENULL; }
+  if (!aligned16(A) || !aligned16(B) || !aligned16(C)) { set_error("gemm: operand not 16-byte aligned"); return OASES_EALIGN; }
+  GemmArgs g{(const uint16_t*)A, (const uint16_t*)B, C, bias, (uint16_t*)aux, M, N, K, lda, ldb, ldc, ldaux, 0, 0};
+  if (op == OASES_GEMM_TN) {
+    if (lda < M || ldb < N || ldc < N) { set_error("gemm TN: leading dimension too small"); return OASES_EINVAL; }
+    return launch_shape<false, false, EPI_ACC_F32>(g, s);
+  }
+  const bool nn = op == OASES_GEMM_NN;
+  if (!nn && op != OASES_GEMM_NT) { set_error("gemm: unknown op %d", op); return OASES_EINVAL; }
+  if (lda < K || (nn ? ldb < N : ldb < K) || ldc < N) { set_error("gemm: leading dimension too small"); return OASES_EINVAL; }
+  if ((epi == OASES_EPI_BIAS_BF16 || epi == OASES_EPI_BIAS_GELU) && !bias) { set_error("gemm: bias epilogue without bias"); return OASES_ENULL; }
+  if ((epi == OASES_EPI_BIAS_GELU || epi == OASES_EPI_DGELU) && (!aux || ldaux < N)) { set_error("gemm: GeLU epilogue without aux"); return OASES_ENULL; }
+#define OASES_GEMM_CASE(E)                                                   \
+  case E:                                                                    \
+    return nn ? launch_shape<true, false, E>(g, s) : launch_shape<true, true, E>(g, s);
+  switch (epi) {
+    OASES_GEMM_CASE(EPI_F32)
+    OASES_GEMM_CASE(EPI_BF16)
+    OASES_GEMM_CASE(EPI_BIAS_BF16)
+    OASES_GEMM_CASE(EPI_BIAS_GELU)
+    OASES_GEMM_CASE(EPI_DGELU)
+    default:
+      set_error("gemm: unknown epilogue %d", epi);
+      return OASES_EINVAL;
+  }
+#undef OASES_GEMM_CASE
+}
+
+}  // namespace oases

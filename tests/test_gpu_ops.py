@@ -1,0 +1,318 @@
+"""Per-operator parity of the HIP kernels (through the C ABI) against the oracle's operator
+definitions, on seeded inputs that span several tiles and a ragged tail."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from tests.util import rel_err, rms_err, bf16_round, bf16_close, assert_bf16_close, dev, randn
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def B():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2305_16121_amd import binding
+    return binding
+
+
+@pytest.fixture(scope="module")
+def lo():
+    from oracle import layer_oracle
+    return layer_oracle
+
+
+def gen(seed):
+    g = torch.Generator()
+    g.manual_seed(seed)
+    return g
+
+
+# ------------------------------------------------------------------ dropout mask: bit exact
+@pytest.mark.parametrize("p,row0,rows,h", [(0.1, 0, 64, 512), (0.5, 1000, 37, 264), (0.1, (1 << 31) // 512, 16, 512), (0.0, 0, 8, 64)])
+def test_dropout_mask_bits(B, lo, p, row0, rows, h):
+    seed = 0x0123456789ABCDEF
+    m = torch.empty(rows * h, dtype=torch.uint8, device="cuda")
+    B.check(B.lib.oases_op_dropout_mask(m.data_ptr(), seed, 3, 1, row0, rows, h, p, None))
+    torch.cuda.synchronize()
+    ref = lo.dropout_keep_mask(seed, 3, 1, rows, h, p, row0=row0)
+    assert np.array_equal(m.cpu().numpy().reshape(rows, h).astype(bool), ref)
+
+
+# ------------------------------------------------------------------ LayerNorm forward
+@pytest.mark.parametrize("rows,h", [(300, 512), (70, 1000), (33, 4096), (9, 8192), (5, 16384), (4, 8)])
+def test_layernorm_fwd(B, lo, rows, h):
+    g = gen(1)
+    x = randn(g, rows, h) * 3 + 0.5
+    gam, bet = 1 + 0.1 * randn(g, h), 0.1 * randn(g, h)
+    xd, gd, bd = dev(x, torch.float32), dev(gam, torch.float32), dev(bet, torch.float32)
+    out = torch.empty(rows, h, dtype=torch.bfloat16, device="cuda")
+    mu = torch.empty(rows, dtype=torch.float32, device="cuda")
+    rstd = torch.empty_like(mu)
+    B.check(B.lib.oases_op_layernorm_fwd(xd.data_ptr(), gd.data_ptr(), bd.data_ptr(), out.data_ptr(), mu.data_ptr(),
+                                         rstd.data_ptr(), rows, h, 1e-5, None))
+    ref, rmu, rrstd = lo.layer_norm_fwd(xd.cpu().double(), gd.cpu().double(), bd.cpu().double(), 1e-5)
+    assert_bf16_close(out.float(), ref, 1e-5, 2e-6 * float(ref.abs().max()))
+    assert rel_err(mu, rmu.flatten()) < 1e-5 and rel_err(rstd, rrstd.flatten()) < 1e-5
+
+
+# ------------------------------------------------------------------ reduction point + bias + dropout + residual (+LN)
+@pytest.mark.parametrize("rows,h,p,with_peer,with_ln", [(130, 512, 0.1, True, True), (40, 2048, 0.0, False, True),
+                                                        (17, 8192, 0.3, True, False), (64, 1032, 0.1, False, True)])
+def test_bias_dropout_residual_ln(B, lo, rows, h, p, with_peer, with_ln):
+    g = gen(2)
+    part, peer, xin = randn(g, rows, h), randn(g, rows, h), randn(g, rows, h)
+    bias, gam, bet = 0.1 * randn(g, h), 1 + 0.1 * randn(g, h), 0.1 * randn(g, h)
+    d = {k: dev(v, torch.float32) for k, v in dict(part=part, peer=peer, xin=xin, bias=bias, gam=gam, bet=bet).items()}
+    xo = torch.empty(rows, h, dtype=torch.float32, device="cuda")
+    ln = torch.empty(rows, h, dtype=torch.bfloat16, device="cuda")
+    mu = torch.empty(rows, dtype=torch.float32, device="cuda")
+    rstd = torch.empty_like(mu)
+    seed, layer, site, row0 = 77, 2, 0, 4096
+    B.check(B.lib.oases_op_bias_dropout_residual_ln(
+        d["part"].data_ptr(), d["peer"].data_ptr() if with_peer else None, d["bias"].data_ptr(), d["xin"].data_ptr(),
+        xo.data_ptr(), d["gam"].data_ptr() if with_ln else None, d["bet"].data_ptr() if with_ln else None,
+        ln.data_ptr() if with_ln else None, mu.data_ptr() if with_ln else None, rstd.data_ptr() if with_ln else None,
+        rows, h, 1e-5, seed, layer, site, row0, p, None))
+    keep = torch.from_numpy(lo.dropout_keep_mask(seed, layer, site, rows, h, p, row0=row0)).double()
+    c = {k: v.cpu().double() for k, v in d.items()}
+    z = c["part"] + (c["peer"] if with_peer else 0) + c["bias"]
+    ref = c["xin"] + keep * z / (1 - p)
+    assert rel_err(xo, ref) < 1e-6
+    if with_ln:
+        rln, rmu, rrstd = lo.layer_norm_fwd(ref, c["gam"], c["bet"], 1e-5)
+        assert_bf16_close(ln.float(), rln, 1e-5, 2e-6 * float(rln.abs().max()))
+        assert rel_err(mu, rmu.flatten()) < 1e-5 and rel_err(rstd, rrstd.flatten()) < 1e-5
+
+
+# ------------------------------------------------------------------ dropout backward + bias gradient
+@pytest.mark.parametrize("rows,h,p", [(300, 512, 0.1), (1000, 1032, 0.5), (7, 8192, 0.0)])
+def test_dropout_bwd(B, lo, rows, h, p):
+    g = gen(3)
+    dy = dev(randn(g, rows, h), torch.float32)
+    dz = torch.empty(rows, h, dtype=torch.bfloat16, device="cuda")
+    db = torch.full((h,), 1.0, dtype=torch.float32, device="cuda")      # accumulated into
+    scratch = torch.empty(256 * h, dtype=torch.float32, device="cuda")
+    B.check(B.lib.oases_op_dropout_bwd(dy.data_ptr(), dz.data_ptr(), db.data_ptr(), rows, h, 5, 1, 1, 64, p, scratch.data_ptr(), None))
+    keep = torch.from_numpy(lo.dropout_keep_mask(5, 1, 1, rows, h, p, row0=64)).double()
+    ref = keep * dy.cpu().double() / (1 - p)
+    assert_bf16_close(dz.float(), ref, 1e-6)
+    assert rel_err(db, 1.0 + ref.sum(0)) < 1e-5
+
+
+# ------------------------------------------------------------------ LayerNorm backward fusion
+@pytest.mark.parametrize("rows,h,p,with_peer,with_dz", [(300, 512, 0.1, True, True), (1000, 1032, 0.0, False, False),
+                                                        (50, 8192, 0.2, True, True), (520, 4096, 0.1, False, True)])
+def test_layernorm_bwd(B, lo, rows, h, p, with_peer, with_dz):
+    g = gen(4)
+    part, peer, dres, x = randn(g, rows, h), randn(g, rows, h), randn(g, rows, h), randn(g, rows, h) * 2 + 1
+    gam = 1 + 0.1 * randn(g, h)
+    d = {k: dev(v, torch.float32) for k, v in dict(part=part, peer=peer, dres=dres, x=x, gam=gam).items()}
+    c = {k: v.cpu().double() for k, v in d.items()}
+    _, rmu, rrstd = lo.layer_norm_fwd(c["x"], c["gam"], torch.zeros(h, dtype=torch.float64), 1e-5)
+    mu, rstd = dev(rmu.flatten(), torch.float32), dev(rrstd.flatten(), torch.float32)
+    dxo = torch.empty(rows, h, dtype=torch.float32, device="cuda")
+    dz = torch.empty(rows, h, dtype=torch.bfloat16, device="cuda")
+    dgam = torch.zeros(h, dtype=torch.float32, device="cuda")
+    dbet = torch.zeros_like(dgam)
+    dbias = torch.zeros_like(dgam)
+    scratch = torch.empty(4 * 256 * h, dtype=torch.float32, device="cuda")
+    B.check(B.lib.oases_op_layernorm_bwd(
+        d["part"].data_ptr(), d["peer"].data_ptr() if with_peer else None, d["dres"].data_ptr(), d["x"].data_ptr(),
+        mu.data_ptr(), rstd.data_ptr(), d["gam"].data_ptr(), dxo.data_ptr(), dgam.data_ptr(), dbet.data_ptr(),
+        dz.data_ptr() if with_dz else None, dbias.data_ptr() if with_dz else None, rows, h, 9, 0, 1, 128, p,
+        scratch.data_ptr(), None))
+    gin = c["part"] + (c["peer"] if with_peer else 0)
+    rdx, rdg, rdb = lo.layer_norm_bwd(gin, c["x"], mu.cpu().double()[:, None], rstd.cpu().double()[:, None], c["gam"])
+    ref = c["dres"] + rdx
+    assert rel_err(dxo, ref) < 2e-5
+    assert rel_err(dgam, rdg) < 2e-5 and rel_err(dbet, rdb) < 2e-5
+    if with_dz:
+        keep = torch.from_numpy(lo.dropout_keep_mask(9, 0, 1, rows, h, p, row0=128)).double()
+        rz = keep * ref / (1 - p)
+        assert_bf16_close(dz.float(), rz, 1e-5, 2e-6 * float(rz.abs().max()))
+        assert rel_err(dbias, rz.sum(0)) < 2e-5
+
+
+# ------------------------------------------------------------------ column sums
+@pytest.mark.parametrize("rows,cols,ld", [(1000, 768, 768), (37, 4096, 4104), (300, 8, 16)])
+def test_colsum(B, rows, cols, ld):
+    a = dev(bf16_round(randn(gen(5), rows, ld)), torch.bfloat16)
+    out = torch.full((cols,), 2.0, dtype=torch.float32, device="cuda")
+    scratch = torch.empty(256 * cols, dtype=torch.float32, device="cuda")
+    B.check(B.lib.oases_op_colsum_bf16(a.data_ptr(), ld, rows, cols, out.data_ptr(), scratch.data_ptr(), None))
+    assert rel_err(out, 2.0 + a.cpu().double()[:, :cols].sum(0)) < 1e-5
+
+
+# ------------------------------------------------------------------ GEMM family
+GEMM_SHAPES = [(256, 256, 256), (384, 768, 512), (136, 264, 72), (2048, 1024, 1024), (8, 8, 8), (520, 128, 4096), (4096, 4096, 512)]
+
+
+@pytest.mark.parametrize("M,N,K", GEMM_SHAPES)
+@pytest.mark.parametrize("op", ["NN", "NT", "TN"])
+def test_gemm_plain(B, M, N, K, op):
+    g = gen(6)
+    a = bf16_round(randn(g, M, K))
+    b = bf16_round(randn(g, K, N))
+    ref = a @ b
+    if op == "NN":
+        ad, bd = dev(a, torch.bfloat16), dev(b, torch.bfloat16)
+        c = torch.empty(M, N, dtype=torch.float32, device="cuda")
+        B.check(B.lib.oases_op_gemm(B.GEMM_NN, B.EPI_F32, M, N, K, ad.data_ptr(), K, bd.data_ptr(), N, c.data_ptr(), N, None, None, 0, None))
+    elif op == "NT":
+        ad, bd = dev(a, torch.bfloat16), dev(b.t().contiguous(), torch.bfloat16)
+        c = torch.empty(M, N, dtype=torch.float32, device="cuda")
+        B.check(B.lib.oases_op_gemm(B.GEMM_NT, B.EPI_F32, M, N, K, ad.data_ptr(), K, bd.data_ptr(), K, c.data_ptr(), N, None, None, 0, None))
+    else:
+        ad, bd = dev(a.t().contiguous(), torch.bfloat16), dev(b, torch.bfloat16)
+        c = torch.full((M, N), 0.5, dtype=torch.float32, device="cuda")         # accumulated into
+        B.check(B.lib.oases_op_gemm(B.GEMM_TN, 0, M, N, K, ad.data_ptr(), M, bd.data_ptr(), N, c.data_ptr(), N, None, None, 0, None))
+        ref = ref + 0.5
+    assert rel_err(c, ref) < 1e-5, (op, M, N, K)     # exact products of bf16 values, fp32 accumulation
+
+
+@pytest.mark.parametrize("M,N,K", [(384, 768, 512), (136, 264, 72), (2048, 2048, 256)])
+def test_gemm_epilogues(B, lo, M, N, K):
+    g = gen(7)
+    a, b = bf16_round(randn(g, M, K)), bf16_round(randn(g, K, N, scale=0.05))
+    bias = 0.1 * randn(g, N)
+    ad, bd, biasd = dev(a, torch.bfloat16), dev(b, torch.bfloat16), dev(bias, torch.float32)
+    bias = biasd.cpu().double()
+    acc = a @ b
+    c = torch.empty(M, N, dtype=torch.bfloat16, device="cuda")
+    aux = torch.empty(M, N, dtype=torch.bfloat16, device="cuda")
+    run = lambda epi, auxp: B.check(B.lib.oases_op_gemm(B.GEMM_NN, epi, M, N, K, ad.data_ptr(), K, bd.data_ptr(), N, c.data_ptr(), N,
+                                                        biasd.data_ptr(), auxp, N, None))
+    run(B.EPI_BF16, None)
+    assert_bf16_close(c.float(), acc, 1e-5, 2e-6 * float(acc.abs().max()))
+    run(B.EPI_BIAS_BF16, None)
+    assert_bf16_close(c.float(), acc + bias, 1e-5, 2e-6 * float(acc.abs().max()))
+    run(B.EPI_BIAS_GELU, aux.data_ptr())
+    assert_bf16_close(aux.float(), acc + bias, 1e-5, 2e-6 * float(acc.abs().max()))
+    assert_bf16_close(c.float(), lo.gelu_fwd(acc + bias), 1e-4, 1e-5, 'gelu')
+    # dGeLU epilogue on the input-gradient form: C = (A B^T) * gelu'(aux)
+    bt = dev(b.t().contiguous(), torch.bfloat16)
+    B.check(B.lib.oases_op_gemm(B.GEMM_NT, B.EPI_DGELU, M, N, K, ad.data_ptr(), K, bt.data_ptr(), K, c.data_ptr(), N, None, aux.data_ptr(), N, None))
+    assert_bf16_close(c.float(), acc * lo.gelu_grad(aux.cpu().double()), 1e-4, 1e-5, 'dgelu')
+
+
+def test_gemm_strided_views(B):
+    # operands that are column blocks of wider matrices (the way the layer calls it on sub-batch rows)
+    g = gen(8)
+    M, N, K, lda, ldb, ldc = 264, 136, 200, 328, 256, 144
+    a, b = bf16_round(randn(g, M, lda)), bf16_round(randn(g, K, ldb))
+    ad, bd = dev(a, torch.bfloat16), dev(b, torch.bfloat16)
+    c = torch.zeros(M, ldc, dtype=torch.float32, device="cuda")
+    B.check(B.lib.oases_op_gemm(B.GEMM_NN, B.EPI_F32, M, N, K, ad.data_ptr(), lda, bd.data_ptr(), ldb, c.data_ptr(), ldc, None, None, 0, None))
+    assert rel_err(c[:, :N], a[:, :K] @ b[:, :N]) < 1e-5
+    assert float(c[:, N:].abs().max()) == 0.0
+
+
+def test_gemm_argument_errors(B):
+    t = torch.zeros(64, 64, dtype=torch.bfloat16, device="cuda")
+    c = torch.zeros(64, 64, dtype=torch.float32, device="cuda")
+    assert B.lib.oases_op_gemm(B.GEMM_NN, B.EPI_F32, 60, 64, 64, t.data_ptr(), 64, t.data_ptr(), 64, c.data_ptr(), 64, None, None, 0, None) == B.EINVAL
+    assert B.lib.oases_op_gemm(B.GEMM_NN, B.EPI_F32, 64, 64, 64, None, 64, t.data_ptr(), 64, c.data_ptr(), 64, None, None, 0, None) == B.ENULL
+    assert B.lib.oases_op_gemm(B.GEMM_NN, B.EPI_F32, 64, 64, 64, t.data_ptr() + 2, 64, t.data_ptr(), 64, c.data_ptr(), 64, None, None, 0, None) == B.EALIGN
+    assert B.lib.oases_op_gemm(B.GEMM_NN, B.EPI_BIAS_BF16, 64, 64, 64, t.data_ptr(), 64, t.data_ptr(), 64, c.data_ptr(), 64, None, None, 0, None) == B.ENULL
+    assert b"bias" in B.lib.oases_last_error()
+
+
+# ------------------------------------------------------------------ attention
+def _attn_ref(lo, qkv, batch, seq, heads, d, causal):
+    hp = heads * d
+    q, k, v = qkv[:, :hp], qkv[:, hp:2 * hp], qkv[:, 2 * hp:]
+    A, P = lo.attention_fwd(q, k, v, batch, seq, heads, d, causal)
+    return q, k, v, A, P
+
+
+ATTN_CASES = [(2, 256, 2, 64, 1), (2, 256, 2, 128, 1), (3, 200, 1, 64, 0), (1, 328, 2, 128, 0), (2, 72, 3, 64, 1), (1, 1, 1, 64, 1),
+              (1, 1024, 1, 128, 1)]
+
+
+@pytest.mark.parametrize("batch,seq,heads,d,causal", ATTN_CASES)
+def test_attention_fwd_bwd(B, lo, batch, seq, heads, d, causal):
+    g = gen(9)
+    M, hp = batch * seq, heads * d
+    qkv = bf16_round(randn(g, M, 3 * hp))
+    dout = bf16_round(randn(g, M, hp))
+    q, k, v, A, P = _attn_ref(lo, qkv, batch, seq, heads, d, causal)
+    qd, dod = dev(qkv, torch.bfloat16), dev(dout, torch.bfloat16)
+    out = torch.zeros(M, hp, dtype=torch.bfloat16, device="cuda")
+    lse = torch.zeros(batch * heads * seq, dtype=torch.float32, device="cuda")
+    B.check(B.lib.oases_op_attention_fwd(qd.data_ptr(), out.data_ptr(), lse.data_ptr(), batch, seq, heads, d, causal, 0, M, None))
+    # P is rounded to bf16 before P*V (relative 2^-9 per weight), then the output is rounded once
+    assert_bf16_close(out.float(), A, 0.0, 2.0 ** -9 * float(v.abs().max()), 'attention forward')
+    # log-sum-exp of the scaled scores
+    S = (lo._heads(q, batch, seq, heads, d) @ lo._heads(k, batch, seq, heads, d).transpose(2, 3)) / math.sqrt(d)
+    if causal:
+        i = torch.arange(seq)
+        S = S.masked_fill(i[None, :] > i[:, None], float("-inf"))
+    assert float((lse.cpu().double().reshape(batch, heads, seq) - torch.logsumexp(S, dim=3)).abs().max()) < 2e-3
+    # backward consumes the kernel's own rounded output, as the layer does
+    dq, dk, dv = lo.attention_bwd(dout, q, k, v, P, batch, seq, heads, d)
+    dqkv = torch.zeros(M, 3 * hp, dtype=torch.bfloat16, device="cuda")
+    delta = torch.zeros_like(lse)
+    B.check(B.lib.oases_op_attention_bwd(qd.data_ptr(), out.data_ptr(), dod.data_ptr(), lse.data_ptr(), delta.data_ptr(),
+                                         dqkv.data_ptr(), batch, seq, heads, d, causal, 0, M, None))
+    got = dqkv.float().cpu().double()
+    got = dict(dq=got[:, :hp], dk=got[:, hp:2 * hp], dv=got[:, 2 * hp:])
+    # (a) against the exact definition: small in the rms sense (the max norm is dominated by bf16 storage of O, P, dS)
+    for name, ref in (("dq", dq), ("dk", dk), ("dv", dv)):
+        assert rms_err(got[name], ref) < 6e-3, name
+    # (b) against the same mathematics with the kernel's storage roundings written out: delta from the bf16 output,
+    #     P and dS rounded to bf16 where they enter a matrix product; then only the final bf16 rounding remains
+    H = lambda t: lo._heads(t, batch, seq, heads, d)
+    Og = out.float().cpu().double()
+    dl = (H(dout) * H(Og)).sum(dim=3, keepdim=True)
+    dP = H(dout) @ H(v).transpose(2, 3)
+    dS = P * (dP - dl)
+    U = lambda t: lo._unheads(t, batch, seq, heads, d)
+    ref_b = dict(dv=U(bf16_round(P).transpose(2, 3) @ H(dout)), dq=U(bf16_round(dS) @ H(k)) / math.sqrt(d),
+                 dk=U(bf16_round(dS).transpose(2, 3) @ H(q)) / math.sqrt(d))
+    for name in ("dq", "dk", "dv"):
+        r = ref_b[name]
+        assert_bf16_close(got[name], r, 2e-3, 2e-3 * float(torch.sqrt((r ** 2).mean())), name)
+
+
+@pytest.mark.parametrize("d", [64, 128])
+def test_attention_sequence_chunks(B, lo, d):
+    """Sub-batches that are chunks of one sequence: forward chunk by chunk in order, backward in reverse order,
+    must give what one call over whole sequences gives (bit for bit: same tiles, same order of accumulation)."""
+    g = gen(10)
+    batch, seq, heads, nchunk = 2, 512, 2, 4
+    M, hp = batch * seq, heads * d
+    qd = dev(bf16_round(randn(g, M, 3 * hp)), torch.bfloat16)
+    dod = dev(bf16_round(randn(g, M, hp)), torch.bfloat16)
+    res = []
+    for split in (False, True):
+        out = torch.zeros(M, hp, dtype=torch.bfloat16, device="cuda")
+        lse = torch.zeros(batch * heads * seq, dtype=torch.float32, device="cuda")
+        dqkv = torch.zeros(M, 3 * hp, dtype=torch.bfloat16, device="cuda")
+        delta = torch.zeros_like(lse)
+        rows = seq // nchunk if split else M
+        starts = list(range(0, M, rows))
+        for r0 in starts:
+            B.check(B.lib.oases_op_attention_fwd(qd.data_ptr(), out.data_ptr(), lse.data_ptr(), batch, seq, heads, d, 1, r0, rows, None))
+        for r0 in reversed(starts):
+            B.check(B.lib.oases_op_attention_bwd(qd.data_ptr(), out.data_ptr(), dod.data_ptr(), lse.data_ptr(), delta.data_ptr(),
+                                                 dqkv.data_ptr(), batch, seq, heads, d, 1, r0, rows, None))
+        torch.cuda.synchronize()
+        res.append((out.clone(), lse.clone(), dqkv.clone()))
+    for a, b in zip(*res):
+        assert torch.equal(a, b)
+
+
+def test_attention_argument_errors(B):
+    t = torch.zeros(256, 3 * 64, dtype=torch.bfloat16, device="cuda")
+    o = torch.zeros(256, 64, dtype=torch.bfloat16, device="cuda")
+    l = torch.zeros(256, dtype=torch.float32, device="cuda")
+    f = B.lib.oases_op_attention_fwd
+    assert f(t.data_ptr(), o.data_ptr(), l.data_ptr(), 2, 128, 1, 96, 1, 0, 256, None) == B.EINVAL       # head_dim
+    assert f(t.data_ptr(), o.data_ptr(), l.data_ptr(), 2, 128, 1, 64, 1, 64, 128, None) == B.EINVAL      # straddles sequences
+    assert f(t.data_ptr(), o.data_ptr(), l.data_ptr(), 2, 128, 1, 64, 0, 0, 64, None) == B.EINVAL        # chunk, non-causal
+    assert f(t.data_ptr(), o.data_ptr(), l.data_ptr(), 2, 128, 1, 64, 1, 0, 512, None) == B.EINVAL       # beyond the batch
+    assert f(None, o.data_ptr(), l.data_ptr(), 2, 128, 1, 64, 1, 0, 256, None) == B.ENULL
