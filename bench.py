@@ -1,0 +1,192 @@
+#!/usr/bin/env python3
+"""Benchmark of the hot path: one TMP rank's transformer-layer shard, forward + backward, under the
+sub-batch schedule, on ONE MI355X.  Prints one JSON line.
+
+A step = one oases_forward + one oases_backward over one synthetic batch (inputs resident in HBM).
+Metric: model TFLOP/s of the shard (GEMMs 2mnk, attention 2*M*s*hp causal / 4*M*s*hp full in forward,
+backward = 2x forward; the score recomputation of the attention backward is not counted).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2516.6     # MI355X dense bf16 MFMA (256 CU x 2.4 GHz x 4096 flop/clk/CU)
+PEAK_HBM_GBS = 8000.0
+
+
+def model_flops(cfg):
+    M, h, s, t, L = cfg["batch"] * cfg["seq"], cfg["hidden"], cfg["seq"], cfg["tp"], cfg["n_layers"]
+    hp = h // t
+    gemm = 24.0 * M * h * hp
+    attn = (2.0 if cfg["causal"] else 4.0) * M * s * hp
+    return 3.0 * (gemm + attn) * L
+
+
+def op_flops(line, cfg):
+    """Algorithmic flops of one scheduled GEMM / attention operator (one sub-batch); 0 for the HBM-bound ones."""
+    M, h, s, t = cfg["batch"] * cfg["seq"], cfg["hidden"], cfg["seq"], cfg["tp"]
+    Ms, hp, fp = M // cfg["n_sub"], h // t, 4 * h // t
+    op = line.split()[1]
+    base = op.split(".")[0].split("+")[0]
+    table = {"QKV": 2.0 * Ms * h * 3 * hp, "PROJ": 2.0 * Ms * hp * h, "FC1": 2.0 * Ms * h * fp, "FC2": 2.0 * Ms * fp * h}
+    if base in table:
+        return table[base]
+    if base == "ATTN":
+        f = (2.0 if cfg["causal"] else 4.0) * Ms * s * hp
+        return 2.0 * f if op.endswith(".b") else f
+    return 0.0
+
+
+def op_bytes(line, cfg):
+    """Algorithmic HBM bytes of one HBM-bound operator (one sub-batch): each tensor read once, written once."""
+    M, h = cfg["batch"] * cfg["seq"], cfg["hidden"]
+    e = (M // cfg["n_sub"]) * h
+    op = line.split()[1]
+    per_elem = {"LN1": 4 + 2, "R1+BDR1+LN2": 4 + 4 + 4 + 2, "R2+BDR2": 4 + 4 + 4, "BDR2.b": 4 + 2,
+                "R3+LN2.b+BDR1.b": 4 + 4 + 4 + 4 + 2, "R4+LN1.b": 4 + 4 + 4 + 4}
+    return float(per_elem.get(op, 0)) * e
+
+
+def gemm_kernel_label(line, cfg, B):
+    """Kernel instantiation a GEMM operator runs on: (contraction form, epilogue, block tile)."""
+    M, h, t = cfg["batch"] * cfg["seq"], cfg["hidden"], cfg["tp"]
+    Ms, hp, fp = M // cfg["n_sub"], h // t, 4 * h // t
+    op = line.split()[1]
+    shapes = {"QKV": ("NN", "bias_bf16", Ms, 3 * hp, h), "PROJ": ("NN", "f32", Ms, h, hp), "FC1+GELU": ("NN", "bias_gelu", Ms, fp, h),
+              "FC2": ("NN", "f32", Ms, h, fp), "FC2.dgrad+dGELU": ("NT", "dgelu", Ms, fp, h), "FC1.dgrad": ("NT", "f32", Ms, h, fp),
+              "PROJ.dgrad": ("NT", "bf16", Ms, hp, h), "QKV.dgrad": ("NT", "f32", Ms, h, 3 * hp), "FC2.wgrad": ("TN", "acc_f32", fp, h, Ms),
+              "FC1.wgrad": ("TN", "acc_f32", h, fp, Ms), "PROJ.wgrad": ("TN", "acc_f32", hp, h, Ms), "QKV.wgrad": ("TN", "acc_f32", h, 3 * hp, Ms)}
+    if op not in shapes:
+        return None
+    form, epi, m, n, k = shapes[op]
+    tile = B.lib.oases_op_gemm_variant({"NN": 0, "NT": 1, "TN": 2}[form], 0, m, n, k)
+    return f"gemm_{form}_{epi}_{tile}x{tile}"
+
+
+def cpu_baseline(cfg, name):
+    """The oracle as it stands, timed on the host cores: the rank-0 shard's layer (the same work the GPU does)."""
+    import torch
+    import synth_inputs as si
+    from oracle import layer_oracle as lo
+    layers = [si.shard_layer_params(si.make_layer_params(cfg, l, 0), cfg, 0) for l in range(cfg["n_layers"])]
+    x, dy = si.make_activations(cfg, 0)
+    t0 = time.perf_counter()
+    lo.model_forward_backward(layers, x, dy, cfg, seed=0, dtype=torch.float32)
+    dt = time.perf_counter() - t0
+    return {"value": round(model_flops(cfg) / dt / 1e12, 4), "unit": "TFLOP/s", "cores": torch.get_num_threads(), "kind": "oracle",
+            "seconds": round(dt, 2),
+            "sample": f"the whole step: rank-0 shard of {name}, forward+backward, fp32 torch-CPU oracle, one repetition"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", default="C4", help="workload: C1..C5 (default C4, h=4096)")
+    ap.add_argument("--n-sub", type=int, default=None, help="override the sub-batch count of the workload")
+    ap.add_argument("--serialise", action="store_true", help="single stream")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-profile", action="store_true")
+    a = ap.parse_args()
+    if a.gpus != 1:
+        sys.exit("bench.py: this build runs on one GPU only (no collectives, no sharding across GPUs); use --gpus 1")
+
+    import torch
+    import synth_inputs as si
+    from paper_2305_16121_amd import binding as B
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible")
+
+    cfg = dict(si.CONFIGS[a.config])
+    if a.n_sub:
+        cfg["n_sub"] = a.n_sub
+    M, h = cfg["batch"] * cfg["seq"], cfg["hidden"]
+    layers = [si.make_layer_params(cfg, l, 0) for l in range(cfg["n_layers"])]
+    x, dy = si.make_activations(cfg, 0)
+    W = [B.pack_rank_params(si.shard_layer_params(p, cfg, 0)) for p in layers]
+    G = [B.zero_grads_like(w) for w in W]
+    xd, dyd = torch.from_numpy(x).cuda(), torch.from_numpy(dy).cuda()
+    yd, dxd = torch.empty_like(xd), torch.empty_like(xd)
+    flags = B.FLAG_SERIALISE if a.serialise else 0
+    H = B.Handle(B.make_cfg(cfg, rank=0, seed=0, flags=flags))
+    ws = torch.empty(H.workspace_bytes, dtype=torch.uint8, device="cuda")
+    s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+
+    def step(handle):
+        handle.forward(W, xd, yd, ws, s_compute=s1, s_comm=s2)
+        handle.backward(W, xd, dyd, dxd, G, ws, s_compute=s1, s_comm=s2)
+
+    for _ in range(a.warmup):
+        step(H)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(a.steps):
+        step(H)
+    torch.cuda.synchronize()
+    dt = (time.perf_counter() - t0) / a.steps
+    flops = model_flops(cfg)
+    tflops = flops / dt / 1e12
+
+    out = {"metric": "model TFLOP/s of one TMP-rank layer shard, forward+backward, sub-batched (ms per step in ms_per_step)",
+           "value": round(tflops, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
+           "ms_per_step": round(dt * 1e3, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
+           "data": "synthetic",
+           "config": {"workload": f"{a.config}: GPT layer h={h} heads={cfg['n_heads']} seq={cfg['seq']} batch={cfg['batch']} "
+                                  f"t={cfg['tp']} rank 0 layers={cfg['n_layers']} causal={cfg['causal']} p={cfg['dropout_p']}",
+                      "n_sub": cfg["n_sub"], "streams": 1 if a.serialise else 2, "model_gflop_per_step": round(flops / 1e9, 1),
+                      "frac_of_bf16_peak": round(tflops / PEAK_BF16_TFLOPS, 4)}}
+
+    # per-operator HIP-event timers over the same schedule (serialised so that every bracket holds one operator)
+    if not a.no_profile:
+        HP = B.Handle(B.make_cfg(cfg, rank=0, seed=0, flags=B.FLAG_SERIALISE | B.FLAG_PROFILE))
+        acc = {}
+        reps = max(3, min(a.steps, 10))
+        step(HP)
+        for _ in range(reps):
+            step(HP)
+            torch.cuda.synchronize()
+            for bwd in (False, True):
+                for line, ms in HP.profile(bwd):
+                    if " join " in line:
+                        continue
+                    lab = gemm_kernel_label(line, cfg, B) or line.split()[1]
+                    d = acc.setdefault(lab, dict(ms=0.0, launches=0, flops=0.0, bytes=0.0))
+                    d["ms"] += ms
+                    d["launches"] += 1
+                    d["flops"] += op_flops(line, cfg)
+                    d["bytes"] += op_bytes(line, cfg)
+        table = []
+        for lab, d in acc.items():
+            avg_ms = d["ms"] / d["launches"]
+            row = {"kernel": lab, "launches_per_step": d["launches"] // reps, "avg_ms": round(avg_ms, 4),
+                   "ms_per_step": round(d["ms"] / reps, 4)}
+            if d["flops"]:
+                row["tflops"] = round(d["flops"] / d["launches"] / (avg_ms * 1e-3) / 1e12, 1)
+            if d["bytes"]:
+                row["gbs"] = round(d["bytes"] / d["launches"] / (avg_ms * 1e-3) / 1e9, 1)
+            table.append(row)
+        table.sort(key=lambda r: -r["ms_per_step"])
+        out["kernels"] = table
+        out["config"]["serialised_sum_ms"] = round(sum(r["ms_per_step"] for r in table), 4)
+        dom = next(r for r in table if r["kernel"].startswith("gemm_"))
+        d = acc[dom["kernel"]]
+        out["roofline"] = {"kernel": dom["kernel"], "bound": "mfma", "achieved": dom["tflops"], "peak": PEAK_BF16_TFLOPS,
+                           "unit": "TFLOP/s", "frac": round(dom["tflops"] / PEAK_BF16_TFLOPS, 4), "traffic": None,
+                           "avg_launch_ms": dom["avg_ms"], "flops_per_launch": d["flops"] / d["launches"]}
+        HP.close()
+
+    if not a.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(cfg, a.config)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

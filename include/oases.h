@@ -65,7 +65,8 @@ typedef struct oases_layer_cfg {
 } oases_layer_cfg;
 
 enum {
-  OASES_FLAG_SERIALISE = 1 /* enqueue everything on stream_compute only (same results) */
+  OASES_FLAG_SERIALISE = 1, /* enqueue everything on stream_compute only (same results) */
+  OASES_FLAG_PROFILE = 2    /* bracket every operator with timing events, see oases_profile_read */
 };
 
 typedef struct oases_handle oases_handle; /* opaque; holds host metadata and HIP events only */
@@ -127,6 +128,14 @@ int oases_schedule_dump(const oases_handle *h, int backward, char *buf, size_t n
 int oases_workspace_tensor(const oases_handle *h, const char *name, int layer, size_t *offset,
                            size_t *bytes);
 
+/* Per-operator timers (the paper's offline profiling records each operation's time with dedicated
+ * timers, Sec. V "Implementation"): with OASES_FLAG_PROFILE set at creation, every operator of the last
+ * oases_forward (backward = 0) or oases_backward (backward = 1) call is bracketed by HIP events on its
+ * stream.  This call waits for those events and writes the elapsed milliseconds of the first n operators,
+ * in the order of oases_schedule_dump, to HOST array ms.  Returns the number of operators of the pass,
+ * or a negative error (EINVAL if the flag was not set or the pass has not run). */
+int oases_profile_read(oases_handle *h, int backward, float *ms, int n);
+
 const char *oases_last_error(void); /* thread-local, never NULL */
 
 /* ---------------------------------------------------------------------------------------------
@@ -183,6 +192,10 @@ enum { OASES_EPI_F32 = 0, OASES_EPI_BF16 = 1, OASES_EPI_BIAS_BF16 = 2, OASES_EPI
 int oases_op_gemm(int op, int epi, int M, int N, int K, const void *A, int lda, const void *B,
                   int ldb, void *C, int ldc, const void *bias, void *aux, int ldaux,
                   void *stream);
+
+/* Which kernel instantiation oases_op_gemm launches for a problem: returns the block-tile edge (256 or
+ * 128), or EINVAL.  Host only; used to group per-operator timings by kernel. */
+int oases_op_gemm_variant(int op, int epi, int M, int N, int K);
 
 /* Column sums of a bf16 matrix [rows, cols] (row stride ld) accumulated into fp32 out[cols].
  * scratch: fp32 [256*cols]. */

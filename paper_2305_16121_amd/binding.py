@@ -15,7 +15,7 @@ lib = C.CDLL(LIB_PATH)
 OK, EINVAL, ENULL, EALIGN, EWORKSPACE, EHIP = 0, -1, -2, -3, -4, -5
 GEMM_NN, GEMM_NT, GEMM_TN = 0, 1, 2
 EPI_F32, EPI_BF16, EPI_BIAS_BF16, EPI_BIAS_GELU, EPI_DGELU = 0, 1, 2, 3, 4
-FLAG_SERIALISE = 1
+FLAG_SERIALISE, FLAG_PROFILE = 1, 2
 
 _P = C.c_void_p
 _PARAMS = ("ln1_g", "ln1_b", "wqkv", "bqkv", "wo", "bo", "ln2_g", "ln2_b", "w1", "b1", "w2", "b2")
@@ -55,6 +55,7 @@ _sig("oases_workspace_bytes", _sz, _P)
 _sig("oases_forward", _i, _P, C.POINTER(Weights), _P, _P, C.POINTER(PeerSums), _P, _P, _P)
 _sig("oases_backward", _i, _P, C.POINTER(Weights), _P, _P, _P, C.POINTER(Grads), C.POINTER(PeerSums), _P, _P, _P)
 _sig("oases_schedule_dump", _i, _P, _i, C.c_char_p, _sz)
+_sig("oases_profile_read", _i, _P, _i, C.POINTER(C.c_float), _i)
 _sig("oases_workspace_tensor", _i, _P, C.c_char_p, _i, C.POINTER(_sz), C.POINTER(_sz))
 _sig("oases_op_dropout_mask", _i, _P, _u64, _i, _i, _i64, _i, _i, _f, _P)
 _sig("oases_op_layernorm_fwd", _i, _P, _P, _P, _P, _P, _P, _i, _i, _f, _P)
@@ -62,6 +63,7 @@ _sig("oases_op_bias_dropout_residual_ln", _i, _P, _P, _P, _P, _P, _P, _P, _P, _P
 _sig("oases_op_dropout_bwd", _i, _P, _P, _P, _i, _i, _u64, _i, _i, _i64, _f, _P, _P)
 _sig("oases_op_layernorm_bwd", _i, _P, _P, _P, _P, _P, _P, _P, _P, _P, _P, _P, _P, _i, _i, _u64, _i, _i, _i64, _f, _P, _P)
 _sig("oases_op_gemm", _i, _i, _i, _i, _i, _i, _P, _i, _P, _i, _P, _i, _P, _P, _i, _P)
+_sig("oases_op_gemm_variant", _i, _i, _i, _i, _i, _i)
 _sig("oases_op_colsum_bf16", _i, _P, _i, _i, _i, _P, _P, _P)
 _sig("oases_op_attention_fwd", _i, _P, _P, _P, _i, _i, _i, _i, _i, _i, _i, _P)
 _sig("oases_op_attention_bwd", _i, _P, _P, _P, _P, _P, _P, _i, _i, _i, _i, _i, _i, _i, _P)
@@ -124,6 +126,15 @@ class Handle:
         buf = C.create_string_buffer(n + 1)
         lib.oases_schedule_dump(self._h, int(backward), buf, n + 1)
         return buf.value.decode()
+
+    def profile(self, backward: bool):
+        """[(operator line of the schedule, milliseconds)] of the last pass (needs FLAG_PROFILE)."""
+        names = self.schedule(backward).strip().splitlines()
+        ms = (C.c_float * len(names))()
+        n = lib.oases_profile_read(self._h, int(backward), ms, len(names))
+        if n < 0:
+            raise OasesError(n)
+        return list(zip(names, [float(v) for v in ms]))
 
     def tensor_span(self, name: str, layer: int = 0):
         off, nb = _sz(), _sz()

@@ -64,6 +64,8 @@ struct oases_handle {
   std::vector<Op> fwd, bwd;
   int n_events;
   std::vector<hipEvent_t> events;  // created on first use
+  std::vector<hipEvent_t> prof[2];  // OASES_FLAG_PROFILE: start/stop event per operator of each pass
+  bool prof_ran[2] = {false, false};
   std::vector<Tensor> tensors;     // per-layer tensors, offsets relative to the layer base
   size_t layer_bytes, scratch_comm_off, scratch_compute_off, total_bytes;
 };
@@ -323,14 +325,31 @@ static int run_ops(const Run& R, const std::vector<Op>& ops) {
     OASES_HIP(hipEventRecord(H->events[H->n_events - 1], R.st[0]));
     OASES_HIP(hipStreamWaitEvent(R.st[1], H->events[H->n_events - 1], 0));
   }
+  const bool profile = H->cfg.flags & OASES_FLAG_PROFILE;
+  const int pass = &ops == &H->bwd;
+  if (profile && H->prof[pass].empty()) {
+    H->prof[pass].resize(2 * ops.size());
+    for (auto& e : H->prof[pass]) {
+      hipError_t err = hipEventCreate(&e);
+      if (err != hipSuccess) {
+        H->prof[pass].clear();
+        return hip_fail(err, "hipEventCreate");
+      }
+    }
+  }
+  size_t i = 0;
   for (const Op& op0 : ops) {
     Op op = op0;
     if (serial) op.stream = 0;
     if (!serial && op.wait >= 0) OASES_HIP(hipStreamWaitEvent(R.st[op.stream], H->events[op.wait], 0));
+    if (profile) OASES_HIP(hipEventRecord(H->prof[pass][2 * i], R.st[op.stream]));
     int rc = run_op(R, op);
     if (rc) return rc;
+    if (profile) OASES_HIP(hipEventRecord(H->prof[pass][2 * i + 1], R.st[op.stream]));
     if (!serial && op.record >= 0) OASES_HIP(hipEventRecord(H->events[op.record], R.st[op.stream]));
+    i++;
   }
+  if (profile) H->prof_ran[pass] = true;
   return 0;
 }
 
@@ -386,6 +405,8 @@ int oases_create(const oases_layer_cfg* c, oases_handle** out) {
 void oases_destroy(oases_handle* H) {
   if (!H) return;
   for (auto& e : H->events) (void)hipEventDestroy(e);
+  for (auto& v : H->prof)
+    for (auto& e : v) (void)hipEventDestroy(e);
   delete H;
 }
 
@@ -402,6 +423,21 @@ int oases_workspace_tensor(const oases_handle* H, const char* name, int layer, s
     }
   set_error("unknown workspace tensor '%s'", name);
   return OASES_EINVAL;
+}
+
+int oases_profile_read(oases_handle* H, int backward, float* ms, int n) {
+  if (!H || (n > 0 && !ms)) { set_error("oases_profile_read: NULL argument"); return OASES_ENULL; }
+  const int pass = backward ? 1 : 0;
+  const std::vector<Op>& ops = pass ? H->bwd : H->fwd;
+  if (!(H->cfg.flags & OASES_FLAG_PROFILE) || !H->prof_ran[pass]) {
+    set_error("oases_profile_read: handle not created with OASES_FLAG_PROFILE, or the pass has not run");
+    return OASES_EINVAL;
+  }
+  for (size_t i = 0; i < ops.size() && (int)i < n; i++) {
+    OASES_HIP(hipEventSynchronize(H->prof[pass][2 * i + 1]));
+    OASES_HIP(hipEventElapsedTime(&ms[i], H->prof[pass][2 * i], H->prof[pass][2 * i + 1]));
+  }
+  return (int)ops.size();
 }
 
 int oases_schedule_dump(const oases_handle* H, int backward, char* buf, size_t n) {
@@ -492,6 +528,11 @@ int oases_op_layernorm_bwd(const void* part, const void* peer, const void* dres,
 int oases_op_gemm(int op, int epi, int M, int N, int K, const void* A, int lda, const void* B, int ldb, void* C, int ldc,
                   const void* bias, void* aux, int ldaux, void* stream) {
   return launch_gemm(op, epi, M, N, K, A, lda, B, ldb, C, ldc, (const float*)bias, aux, ldaux, (hipStream_t)stream);
+}
+int oases_op_gemm_variant(int op, int epi, int M, int N, int K) {
+  (void)epi;
+  if (op < 0 || op > 2 || M <= 0 || N <= 0 || K <= 0) { set_error("oases_op_gemm_variant: bad argument"); return OASES_EINVAL; }
+  return gemm_variant(op, M, N, K);
 }
 int oases_op_colsum_bf16(const void* a, int ld, int rows, int cols, void* out, void* scratch, void* stream) {
   return launch_colsum_bf16(a, ld, rows, cols, (float*)out, (float*)scratch, (hipStream_t)stream);

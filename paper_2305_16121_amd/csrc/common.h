@@ -117,6 +117,7 @@ int launch_layernorm_bwd(const float* part, const float* peer, const float* dres
 int launch_colsum_bf16(const void* a, int ld, int rows, int cols, float* out, float* scratch, hipStream_t s);
 int launch_gemm(int op, int epi, int M, int N, int K, const void* A, int lda, const void* B, int ldb, void* C,
                 int ldc, const float* bias, void* aux, int ldaux, hipStream_t s);
+int gemm_variant(int op, int M, int N, int K);
 int launch_attention_fwd(const void* qkv, void* out, float* lse, int batch, int seq, int heads, int head_dim,
                          int causal, int row0, int rows, hipStream_t s);
 int launch_attention_bwd(const void* qkv, const void* out, const void* dout, const float* lse, float* delta,

@@ -220,14 +220,24 @@ int launch_one(const GemmArgs& g0, hipStream_t s) {
 }
 
 // tile choice: 256x256 when it fills the chip at least once over, else 128x128
+int pick_tile(int M, int N, int K) {
+  (void)K;
+  long t256 = (long)((M + 255) / 256) * ((N + 255) / 256);
+  return (t256 >= 256 && M % 256 == 0 && N % 256 == 0) ? 256 : 128;
+}
+
 template <bool A_KC, bool B_KC, int EPI>
 int launch_shape(const GemmArgs& g, hipStream_t s) {
-  long t256 = (long)((g.M + 255) / 256) * ((g.N + 255) / 256);
-  if (t256 >= 256 && g.M % 256 == 0 && g.N % 256 == 0) return launch_one<256, 256, 2, 2, A_KC, B_KC, EPI>(g, s);
+  if (pick_tile(g.M, g.N, g.K) == 256) return launch_one<256, 256, 2, 2, A_KC, B_KC, EPI>(g, s);
   return launch_one<128, 128, 2, 2, A_KC, B_KC, EPI>(g, s);
 }
 
 }  // namespace
+
+int gemm_variant(int op, int M, int N, int K) {
+  (void)op;
+  return pick_tile(M, N, K);
+}
 
 int launch_gemm(int op, int epi, int M, int N, int K, const void* A, int lda, const void* B, int ldb, void* C,
                 int ldc, const float* bias, void* aux, int ldaux, hipStream_t s) {
