@@ -151,14 +151,32 @@ struct FinalizeArgs {
 };
 __global__ __launch_bounds__(NT) void colsum_finalize_kernel(const float* __restrict__ scratch, FinalizeArgs a, int groups,
                                                              int cols) {
-  const int c = blockIdx.x * NT + threadIdx.x;
-  if (c >= cols) return;
+  // 32 columns x 8 group slices per workgroup; fixed summation tree, so the result does not depend on timing
+  __shared__ float red[8][33];
+  const int cx = threadIdx.x & 31, gy = threadIdx.x >> 5;
+  const int c = blockIdx.x * 32 + cx;
   for (int k = 0; k < a.nk; k++) {
     if (!a.out[k]) continue;
-    const float* p = scratch + (size_t)k * groups * cols + c;
     float s = 0.f;
-    for (int g = 0; g < groups; g++) s += p[(size_t)g * cols];
-    a.out[k][c] += s;
+    if (c < cols) {
+      const float* p = scratch + (size_t)k * groups * cols + c;
+      int g = gy;
+      for (; g + 24 < groups; g += 32) {
+        float v0 = p[(size_t)g * cols], v1 = p[(size_t)(g + 8) * cols], v2 = p[(size_t)(g + 16) * cols],
+              v3 = p[(size_t)(g + 24) * cols];
+        s += (v0 + v1) + (v2 + v3);
+      }
+      for (; g < groups; g += 8) s += p[(size_t)g * cols];
+    }
+    __syncthreads();
+    red[gy][cx] = s;
+    __syncthreads();
+    if (gy == 0 && c < cols) {
+      float t = 0.f;
+#pragma unroll
+      for (int i = 0; i < 8; i++) t += red[i][cx];
+      a.out[k][c] += t;
+    }
   }
 }
 
@@ -330,7 +348,7 @@ int launch_layernorm_fwd(const float* x, const float* gamma, const float* beta, 
 
 static int finalize(float* scratch, float* o0, float* o1, float* o2, int nk, int groups, int cols, hipStream_t s) {
   FinalizeArgs a{{o0, o1, o2}, nk};
-  hipLaunchKernelGGL(colsum_finalize_kernel, dim3((cols + NT - 1) / NT), dim3(NT), 0, s, scratch, a, groups, cols);
+  hipLaunchKernelGGL(colsum_finalize_kernel, dim3((cols + 31) / 32), dim3(NT), 0, s, scratch, a, groups, cols);
   OASES_LAUNCH_CHECK("colsum_finalize_kernel");
   return 0;
 }
