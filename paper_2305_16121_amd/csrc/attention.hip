@@ -46,6 +46,13 @@ struct Tile {
   static constexpr int mc_bytes = ROWS * mc_row;
 };
 
+// XOR swizzle of the 16-byte chunk index of a row-major [rows][D] tile: 16 consecutive rows read at the same
+// logical chunk must land on 16 different bank groups (64 banks x 4 bytes, 16 lanes per LDS cycle)
+template <int D>
+__device__ __forceinline__ int kc_swizzle(int row) {
+  return D == 128 ? (row & 15) : ((row >> 1) & 7);
+}
+
 // rows [r0, r0+ROWS) of a [*, D] slice with row stride ld; rows >= rmax read as zero
 template <int ROWS, int D>
 __device__ __forceinline__ void load_rows(u32x4* regs, const uint16_t* __restrict__ base, int ld,
@@ -67,7 +74,7 @@ __device__ __forceinline__ void store_kc(const u32x4* regs, char* lds, int tid) 
   for (int i = 0; i < T::per_thread; i++) {
     int c = tid + i * NT;
     int row = c / T::cpr, cc = c % T::cpr;
-    *reinterpret_cast<u32x4*>(lds + row * T::kc_row + ((cc ^ (row & 7)) << 4)) = regs[i];
+    *reinterpret_cast<u32x4*>(lds + row * T::kc_row + ((cc ^ kc_swizzle<D>(row)) << 4)) = regs[i];
   }
 }
 template <int ROWS, int D>
@@ -85,7 +92,7 @@ template <int D>
 __device__ __forceinline__ bf16x8 kc_frag(const char* lds, int r0, int ks, int lane) {
   int row = r0 + (lane & 31);
   int chunk = ks * 2 + (lane >> 5);
-  return *reinterpret_cast<const bf16x8*>(lds + row * (D * 2) + ((chunk ^ (lane & 7)) << 4));
+  return *reinterpret_cast<const bf16x8*>(lds + row * (D * 2) + ((chunk ^ kc_swizzle<D>(lane & 31)) << 4));
 }
 // operand fragment whose contraction index is the tile ROW (16-row step j) and whose free index is the
 // column c0 + l%32; element e of lane half g is row 16j + 8*(e/4) + 4g + e%4 (matches an accumulator column)

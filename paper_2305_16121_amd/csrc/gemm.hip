@@ -3,11 +3,14 @@
 // One kernel template covers the three contractions of a linear map under Megatron's partition
 // (paper Sec. II): forward (A k-contiguous, B n-contiguous), input gradient (both k-contiguous) and
 // weight gradient (both stored with the contraction index as the row).  A k-contiguous operand tile
-// is kept in LDS as [rows][64 k] with a 16-byte-chunk XOR swizzle and read with ds_read_b128; an
+// is kept in LDS as [rows][64 k] with a 16-byte-chunk XOR swizzle (chunk ^ (row/2)%8: 16 consecutive rows of
+// 128 bytes then cover all 64 banks once) and read with ds_read_b128; an
 // operand stored with the contraction index as row is kept as [64 k][rows] (padded rows) and read
 // with the LDS transpose read ds_read_b64_tr_b16, which hands each lane 4 consecutive k of one row.
 // v_mfma_f32_32x32x16_bf16: A lane l holds row l%32, k = 8*(l/32)..+7; B the same with columns;
 // accumulator element i of lane l is C[8*(i/4) + 4*(l/32) + i%4][l%32].
+#include <type_traits>
+
 #include "common.h"
 
 namespace oases {
@@ -37,10 +40,12 @@ struct TileLayout {
   static constexpr int chunks = rows * chunks_per_row;
 };
 
-// global -> registers for one operand tile
-template <int R, bool KC, int NT>
-__device__ __forceinline__ void load_tile_global(u32x4* regs, const uint16_t* __restrict__ base,
-                                                 int ld, int r0, int k0, int rmax, int kmax, int tid) {
+// global -> registers for one operand tile.  FULL: the tile lies inside the matrix and the k range inside K,
+// so no predicate is needed; otherwise addresses are clamped into the matrix and out-of-range chunks zeroed
+// (no divergent branches either way).
+template <int R, bool KC, int NT, bool FULL>
+__device__ __forceinline__ void load_tile_global(u32x4* regs, const uint16_t* __restrict__ base, int ld, int r0, int k0,
+                                                 int rmax, int kmax, int tid) {
   using L = TileLayout<R, KC>;
 #pragma unroll
   for (int i = 0; i < L::chunks / NT; i++) {
@@ -48,11 +53,21 @@ __device__ __forceinline__ void load_tile_global(u32x4* regs, const uint16_t* __
     int row = c / L::chunks_per_row, cc = c % L::chunks_per_row;
     int gr, gk;
     if (KC) { gr = r0 + row; gk = k0 + cc * 8; } else { gk = k0 + row; gr = r0 + cc * 8; }
-    bool ok = (gr < rmax) && (gk < kmax);
-    const uint16_t* p = KC ? base + (size_t)gr * ld + gk : base + (size_t)gk * ld + gr;
-    u32x4 v = {0u, 0u, 0u, 0u};
-    if (ok) v = *reinterpret_cast<const u32x4*>(p);
-    regs[i] = v;
+    if (FULL) {
+      // uniform base (scalar registers, advanced per k iteration) + one loop-invariant 32-bit lane offset
+      static_assert(NT % L::chunks_per_row == 0, "row of a chunk must not depend on the pass");
+      constexpr int rows_per_pass = NT / L::chunks_per_row;
+      const char* sb = reinterpret_cast<const char*>(base) +
+                       ((size_t)(KC ? r0 : k0) * ld + (KC ? k0 : r0) + (size_t)i * rows_per_pass * ld) * 2;
+      const uint32_t voff = (uint32_t)(((tid / L::chunks_per_row) * ld + (tid % L::chunks_per_row) * 8) * 2);
+      regs[i] = *reinterpret_cast<const u32x4*>(sb + voff);
+    } else {
+      const bool ok = (gr < rmax) && (gk < kmax);
+      const int cr = min(gr, KC ? rmax - 1 : rmax - 8), ck = min(gk, KC ? kmax - 8 : kmax - 1);
+      const uint16_t* p = KC ? base + (size_t)cr * ld + ck : base + (size_t)ck * ld + cr;
+      u32x4 v = *reinterpret_cast<const u32x4*>(p);
+      regs[i] = ok ? v : u32x4{0u, 0u, 0u, 0u};
+    }
   }
 }
 
@@ -63,7 +78,7 @@ __device__ __forceinline__ void store_tile_lds(const u32x4* regs, char* lds, int
   for (int i = 0; i < L::chunks / NT; i++) {
     int c = tid + i * NT;
     int row = c / L::chunks_per_row, cc = c % L::chunks_per_row;
-    int off = KC ? row * L::row_bytes + ((cc ^ (row & 7)) << 4) : row * L::row_bytes + (cc << 4);
+    int off = KC ? row * L::row_bytes + ((cc ^ ((row >> 1) & 7)) << 4) : row * L::row_bytes + (cc << 4);
     *reinterpret_cast<u32x4*>(lds + off) = regs[i];
   }
 }
@@ -76,7 +91,7 @@ __device__ __forceinline__ bf16x8 read_frag(const char* lds, int r0, int kk, int
   if (KC) {
     int row = r0 + (lane & 31);
     int chunk = kk * 2 + (lane >> 5);
-    const char* p = lds + row * L::row_bytes + ((chunk ^ (lane & 7)) << 4);
+    const char* p = lds + row * L::row_bytes + ((chunk ^ ((lane >> 1) & 7)) << 4);
     return *reinterpret_cast<const bf16x8*>(p);
   } else {
     int krow = kk * 16 + 8 * (lane >> 5) + ((lane & 15) >> 2);
@@ -92,17 +107,159 @@ __device__ __forceinline__ bf16x8 read_frag(const char* lds, int r0, int kk, int
 
 enum { EPI_F32 = 0, EPI_BF16 = 1, EPI_BIAS_BF16 = 2, EPI_BIAS_GELU = 3, EPI_DGELU = 4, EPI_ACC_F32 = 5 };
 
-template <int BM, int BN, int WGM, int WGN, bool A_KC, bool B_KC, int EPI>
-__global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmArgs g) {
+// instruction-group hints for the machine scheduler (kinds: 0x8 MFMA, 0x20 VMEM read, 0x100 LDS read, 0x200 LDS write)
+#define SGB(mask, n) __builtin_amdgcn_sched_group_barrier(mask, n, 0)
+
+template <int BM, int BN, int WGM, int WGN, bool A_KC, bool B_KC, int EPI, bool FULL>
+__device__ __forceinline__ void gemm_tile(const GemmArgs& g, char* lds, int m0, int n0) {
   constexpr int NT = 64 * WGM * WGN;
   constexpr int WTM = BM / WGM, WTN = BN / WGN;
   constexpr int TM = WTM / 32, TN = WTN / 32;
   using LA = TileLayout<BM, A_KC>;
   using LB = TileLayout<BN, B_KC>;
-  __shared__ __attribute__((aligned(16))) char lds[2 * (LA::bytes + LB::bytes)];
+  constexpr int NA = LA::chunks / NT, NB = LB::chunks / NT;
+  constexpr int kStage = LA::bytes + LB::bytes;  // stage s: A at lds + s*kStage, B behind it
+  constexpr int NREAD = TM * (A_KC ? 1 : 2) + TN * (B_KC ? 1 : 2);  // LDS reads of one 16-wide k step
+  constexpr int NMFMA = TM * TN;
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave / WGN, wn = wave % WGN;
+
+  f32x16 acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; i++)
+#pragma unroll
+    for (int j = 0; j < TN; j++)
+#pragma unroll
+      for (int e = 0; e < 16; e++) acc[i][j][e] = 0.f;
+
+  u32x4 ra[NA], rb[NB];
+  bf16x8 fa[2][TM], fb[2][TN];
+  const int nk = (g.K + BK - 1) / BK;
+
+  auto fetch = [&](int kt) {
+    load_tile_global<BM, A_KC, NT, FULL>(ra, g.A, g.lda, m0, kt * BK, g.M, g.K, tid);
+    load_tile_global<BN, B_KC, NT, FULL>(rb, g.B, g.ldb, n0, kt * BK, g.N, g.K, tid);
+  };
+  auto park = [&](int stage) {
+    store_tile_lds<BM, A_KC, NT>(ra, lds + stage * kStage, tid);
+    store_tile_lds<BN, B_KC, NT>(rb, lds + stage * kStage + LA::bytes, tid);
+  };
+  auto frags = [&](int stage, int kk, int buf) {
+    const char* la = lds + stage * kStage;
+    const char* lb = la + LA::bytes;
+#pragma unroll
+    for (int i = 0; i < TM; i++) fa[buf][i] = read_frag<BM, A_KC>(la, wm * WTM + i * 32, kk, lane);
+#pragma unroll
+    for (int j = 0; j < TN; j++) fb[buf][j] = read_frag<BN, B_KC>(lb, wn * WTN + j * 32, kk, lane);
+  };
+  // the B fragment is the first MFMA operand: the accumulator then holds C^T, i.e. a lane owns 4 consecutive
+  // columns of one row of C per group of four accumulator elements (16-byte stores in the epilogue)
+  auto mma = [&](int buf) {
+#pragma unroll
+    for (int i = 0; i < TM; i++)
+#pragma unroll
+      for (int j = 0; j < TN; j++)
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[buf][j], fa[buf][i], acc[i][j], 0, 0, 0);
+  };
+  // one 16-wide k step: LDS reads of the next step interleaved one-for-one with this step's MFMAs
+  auto hint_step = [&]() {
+    constexpr int PER = (NREAD + NMFMA - 1) / NMFMA;
+#pragma unroll
+    for (int i = 0; i < NMFMA; i++) {
+      SGB(0x008, 1);
+      SGB(0x100, PER);
+    }
+  };
+
+  fetch(0);
+  park(0);
+  if (nk > 1) fetch(1);
+  __syncthreads();
+  frags(0, 0, 0);
+
+  // one 64-wide k iteration; MORE: tile kt+1 exists (it sits in registers), MORE2: tile kt+2 exists.
+  // The steady state (both true) is branch-free so that the scheduler sees one block per iteration.
+  auto iteration = [&](auto more_c, auto more2_c, int kt) {
+    constexpr bool MORE = decltype(more_c)::value, MORE2 = decltype(more2_c)::value;
+    const int cur = kt & 1;
+    if (MORE) park(cur ^ 1);        // tile kt+1: registers -> the other stage
+    if (MORE2) fetch(kt + 2);       // tile kt+2: global -> the same registers
+    frags(cur, 1, 1);
+    mma(0);
+    // LDS stores first (they free the staging registers), then the global loads as early as possible so that
+    // they have a whole iteration to land, interleaved with this step's MFMAs and fragment reads
+    if (MORE) SGB(0x200, NA + NB);
+#pragma unroll
+    for (int i = 0; i < NMFMA; i++) {
+      SGB(0x008, 1);
+      if (MORE2) SGB(0x020, (NA + NB + NMFMA - 1) / NMFMA);
+      SGB(0x100, (NREAD + NMFMA - 1) / NMFMA);
+    }
+    frags(cur, 2, 0);
+    mma(1);
+    hint_step();
+    frags(cur, 3, 1);
+    mma(0);
+    hint_step();
+    // every wave has its last fragments of stage `cur` in registers and stage cur^1 is complete
+    __syncthreads();
+    if (MORE) frags(cur ^ 1, 0, 0);
+    mma(1);
+    hint_step();
+  };
+  using T_ = std::true_type;
+  using F_ = std::false_type;
+  int kt = 0;
+  for (; kt + 2 < nk; kt++) iteration(T_{}, T_{}, kt);
+  if (kt + 1 < nk) { iteration(T_{}, F_{}, kt); kt++; }
+  iteration(F_{}, F_{}, kt);
+
+  // epilogue: accumulator element e of tile (i,j) is C[row][col + (e&3)] with
+  //   row = m0 + wm*WTM + 32 i + (lane & 31),  col = n0 + wn*WTN + 32 j + 8 (e>>2) + 4 (lane>>5)
+#pragma unroll
+  for (int i = 0; i < TM; i++) {
+    const int row = m0 + wm * WTM + i * 32 + (lane & 31);
+    if (!FULL && row >= g.M) continue;
+#pragma unroll
+    for (int j = 0; j < TN; j++) {
+#pragma unroll
+      for (int q = 0; q < 4; q++) {
+        const int col = n0 + wn * WTN + j * 32 + 8 * q + 4 * (lane >> 5);
+        if (!FULL && col >= g.N) continue;
+        f32x4 v = {acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]};
+        const size_t o = (size_t)row * g.ldc + col;
+        if (EPI == EPI_F32) {
+          *reinterpret_cast<f32x4*>(reinterpret_cast<float*>(g.C) + o) = v;
+        } else if (EPI == EPI_ACC_F32) {
+          f32x4* p = reinterpret_cast<f32x4*>(reinterpret_cast<float*>(g.C) + o);
+          *p = *p + v;
+        } else {
+          uint16_t* cp = reinterpret_cast<uint16_t*>(g.C) + o;
+          if (EPI == EPI_BIAS_BF16 || EPI == EPI_BIAS_GELU) v += *reinterpret_cast<const f32x4*>(g.bias + col);
+          if (EPI == EPI_BIAS_GELU) {
+            *reinterpret_cast<u32x2*>(g.aux + (size_t)row * g.ldaux + col) = u32x2{pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3])};
+#pragma unroll
+            for (int e = 0; e < 4; e++) v[e] = gelu_tanh(v[e]);
+          } else if (EPI == EPI_DGELU) {
+            u32x2 a = *reinterpret_cast<const u32x2*>(g.aux + (size_t)row * g.ldaux + col);
+            v[0] *= gelu_tanh_grad(bf16_bits_to_f32(a[0] & 0xffffu));
+            v[1] *= gelu_tanh_grad(bf16_bits_to_f32(a[0] >> 16));
+            v[2] *= gelu_tanh_grad(bf16_bits_to_f32(a[1] & 0xffffu));
+            v[3] *= gelu_tanh_grad(bf16_bits_to_f32(a[1] >> 16));
+          }
+          *reinterpret_cast<u32x2*>(cp) = u32x2{pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3])};
+        }
+      }
+    }
+  }
+}
+
+template <int BM, int BN, int WGM, int WGN, bool A_KC, bool B_KC, int EPI>
+__global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmArgs g) {
+  using LA = TileLayout<BM, A_KC>;
+  using LB = TileLayout<BN, B_KC>;
+  __shared__ __attribute__((aligned(16))) char lds[2 * (LA::bytes + LB::bytes)];
 
   // workgroup -> tile: undo the round-robin of workgroup ids over the 8 XCDs so that each XCD's L2 sees a
   // contiguous range of tiles, then walk that range in groups of 8 tile rows.
@@ -121,91 +278,9 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmArgs g) {
     tile_n = (logical % width) / gsz;
   }
   const int m0 = tile_m * BM, n0 = tile_n * BN;
-
-  f32x16 acc[TM][TN];
-#pragma unroll
-  for (int i = 0; i < TM; i++)
-#pragma unroll
-    for (int j = 0; j < TN; j++)
-#pragma unroll
-      for (int e = 0; e < 16; e++) acc[i][j][e] = 0.f;
-
-  u32x4 ra[LA::chunks / NT], rb[LB::chunks / NT];
-  const int nk = (g.K + BK - 1) / BK;
-  constexpr int kStage = LA::bytes + LB::bytes;  // stage s: A at lds + s*kStage, B behind it
-
-  load_tile_global<BM, A_KC, NT>(ra, g.A, g.lda, m0, 0, g.M, g.K, tid);
-  load_tile_global<BN, B_KC, NT>(rb, g.B, g.ldb, n0, 0, g.N, g.K, tid);
-  store_tile_lds<BM, A_KC, NT>(ra, lds, tid);
-  store_tile_lds<BN, B_KC, NT>(rb, lds + LA::bytes, tid);
-  if (nk > 1) {
-    load_tile_global<BM, A_KC, NT>(ra, g.A, g.lda, m0, BK, g.M, g.K, tid);
-    load_tile_global<BN, B_KC, NT>(rb, g.B, g.ldb, n0, BK, g.N, g.K, tid);
-  }
-  __syncthreads();
-
-  for (int kt = 0; kt < nk; kt++) {
-    const int cur = kt & 1;
-    if (kt + 1 < nk) {  // tile kt+1 sits in registers: park it in the other stage, then fetch tile kt+2
-      store_tile_lds<BM, A_KC, NT>(ra, lds + (cur ^ 1) * kStage, tid);
-      store_tile_lds<BN, B_KC, NT>(rb, lds + (cur ^ 1) * kStage + LA::bytes, tid);
-      if (kt + 2 < nk) {
-        load_tile_global<BM, A_KC, NT>(ra, g.A, g.lda, m0, (kt + 2) * BK, g.M, g.K, tid);
-        load_tile_global<BN, B_KC, NT>(rb, g.B, g.ldb, n0, (kt + 2) * BK, g.N, g.K, tid);
-      }
-    }
-    const char* la = lds + cur * kStage;
-    const char* lb = la + LA::bytes;
-#pragma unroll
-    for (int kk = 0; kk < BK / 16; kk++) {
-      bf16x8 fa[TM], fb[TN];
-#pragma unroll
-      for (int i = 0; i < TM; i++) fa[i] = read_frag<BM, A_KC>(la, wm * WTM + i * 32, kk, lane);
-#pragma unroll
-      for (int j = 0; j < TN; j++) fb[j] = read_frag<BN, B_KC>(lb, wn * WTN + j * 32, kk, lane);
-#pragma unroll
-      for (int i = 0; i < TM; i++)
-#pragma unroll
-        for (int j = 0; j < TN; j++)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
-    }
-    __syncthreads();
-  }
-
-  // epilogue: lane l owns column l%32 of each 32x32 tile and rows 8*(i/4) + 4*(l/32) + i%4
-#pragma unroll
-  for (int j = 0; j < TN; j++) {
-    const int col = n0 + wn * WTN + j * 32 + (lane & 31);
-    const bool cok = col < g.N;
-    float bias = 0.f;
-    if ((EPI == EPI_BIAS_BF16 || EPI == EPI_BIAS_GELU) && cok) bias = g.bias[col];
-#pragma unroll
-    for (int i = 0; i < TM; i++) {
-#pragma unroll
-      for (int e = 0; e < 16; e++) {
-        const int row = m0 + wm * WTM + i * 32 + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
-        if (!cok || row >= g.M) continue;
-        float v = acc[i][j][e];
-        const size_t o = (size_t)row * g.ldc + col;
-        if (EPI == EPI_F32) {
-          reinterpret_cast<float*>(g.C)[o] = v;
-        } else if (EPI == EPI_ACC_F32) {
-          reinterpret_cast<float*>(g.C)[o] += v;
-        } else if (EPI == EPI_BF16) {
-          reinterpret_cast<uint16_t*>(g.C)[o] = (uint16_t)f32_to_bf16_bits(v);
-        } else if (EPI == EPI_BIAS_BF16) {
-          reinterpret_cast<uint16_t*>(g.C)[o] = (uint16_t)f32_to_bf16_bits(v + bias);
-        } else if (EPI == EPI_BIAS_GELU) {
-          float pre = v + bias;
-          g.aux[(size_t)row * g.ldaux + col] = (uint16_t)f32_to_bf16_bits(pre);
-          reinterpret_cast<uint16_t*>(g.C)[o] = (uint16_t)f32_to_bf16_bits(gelu_tanh(pre));
-        } else if (EPI == EPI_DGELU) {
-          float pre = bf16_bits_to_f32(g.aux[(size_t)row * g.ldaux + col]);
-          reinterpret_cast<uint16_t*>(g.C)[o] = (uint16_t)f32_to_bf16_bits(v * gelu_tanh_grad(pre));
-        }
-      }
-    }
-  }
+  const bool full = (m0 + BM <= g.M) && (n0 + BN <= g.N) && (g.K % BK == 0);
+  if (full) gemm_tile<BM, BN, WGM, WGN, A_KC, B_KC, EPI, true>(g, lds, m0, n0);
+  else gemm_tile<BM, BN, WGM, WGN, A_KC, B_KC, EPI, false>(g, lds, m0, n0);
 }
 
 template <int BM, int BN, int WGM, int WGN, bool A_KC, bool B_KC, int EPI>
@@ -241,12 +316,12 @@ int gemm_variant(int op, int M, int N, int K) {
 
 int launch_gemm(int op, int epi, int M, int N, int K, const void* A, int lda, const void* B, int ldb, void* C,
                 int ldc, const float* bias, void* aux, int ldaux, hipStream_t s) {
-  if (M <= 0 || N <= 0 || K <= 0 || (M % 8) || (N % 8) || (K % 8) || (lda % 8) || (ldb % 8)) {
-    set_error("gemm: M,N,K,lda,ldb must be positive multiples of 8 (got M=%d N=%d K=%d lda=%d ldb=%d)", M, N, K, lda, ldb);
+  if (M <= 0 || N <= 0 || K <= 0 || (M % 8) || (N % 8) || (K % 8) || (lda % 8) || (ldb % 8) || (ldc % 4) || (aux && ldaux % 4)) {
+    set_error("gemm: M,N,K,lda,ldb must be positive multiples of 8, ldc/ldaux of 4 (got M=%d N=%d K=%d lda=%d ldb=%d ldc=%d)", M, N, K, lda, ldb, ldc);
     return OASES_EINVAL;
   }
   if (!A || !B || !C) { set_error("gemm: NULL operand"); return OASES_ENULL; }
-  if (!aligned16(A) || !aligned16(B) || !aligned16(C)) { set_error("gemm: operand not 16-byte aligned"); return OASES_EALIGN; }
+  if (!aligned16(A) || !aligned16(B) || !aligned16(C) || !aligned16(bias) || !aligned16(aux)) { set_error("gemm: operand not 16-byte aligned"); return OASES_EALIGN; }
   GemmArgs g{(const uint16_t*)A, (const uint16_t*)B, C, bias, (uint16_t*)aux, M, N, K, lda, ldb, ldc, ldaux, 0, 0};
   if (op == OASES_GEMM_TN) {
     if (lda < M || ldb < N || ldc < N) { set_error("gemm TN: leading dimension too small"); return OASES_EINVAL; }
