@@ -171,7 +171,7 @@ int oases_op_dropout_bwd(const void *dyin, void *dz, void *dbias, int rows, int 
 /* LayerNorm backward + residual (+ reduction point, + dropout backward of the layer input side):
  *   g = part + peer;  dxo = dres + LN'(g; x, mu, rstd, gamma);  dgamma += , dbeta += ;
  *   if dz: dz = keep * dxo / (1-p) (bf16), dbias += column sums of dz.
- * part/peer/dres/x/dxo fp32 [rows,h]; peer, dz, dbias may be NULL.  scratch: fp32 [4*256*h]. */
+ * part/peer/dres/x/dxo fp32 [rows,h]; peer, dz, dbias may be NULL.  scratch: fp32 [3*1024*h]. */
 int oases_op_layernorm_bwd(const void *part, const void *peer, const void *dres, const void *x,
                            const void *mu, const void *rstd, const void *gamma, void *dxo,
                            void *dgamma, void *dbeta, void *dz, void *dbias, int rows, int h,
@@ -198,7 +198,7 @@ int oases_op_gemm(int op, int epi, int M, int N, int K, const void *A, int lda, 
 int oases_op_gemm_variant(int op, int epi, int M, int N, int K);
 
 /* Column sums of a bf16 matrix [rows, cols] (row stride ld) accumulated into fp32 out[cols].
- * scratch: fp32 [256*cols]. */
+ * scratch: fp32 [1024*cols]. */
 int oases_op_colsum_bf16(const void *a, int ld, int rows, int cols, void *out, void *scratch,
                          void *stream);
 

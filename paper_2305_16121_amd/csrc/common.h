@@ -124,6 +124,6 @@ int launch_attention_bwd(const void* qkv, const void* out, const void* dout, con
                          void* dqkv, int batch, int seq, int heads, int head_dim, int causal, int row0,
                          int rows, hipStream_t s);
 
-constexpr int kColPartials = 256;  // row-groups of the two-stage column reductions
+constexpr int kColPartials = 1024;  // row-groups of the two-stage column reductions
 
 }  // namespace oases

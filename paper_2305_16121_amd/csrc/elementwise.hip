@@ -151,22 +151,22 @@ struct FinalizeArgs {
 };
 __global__ __launch_bounds__(NT) void colsum_finalize_kernel(const float* __restrict__ scratch, FinalizeArgs a, int groups,
                                                              int cols) {
-  // 32 columns x 8 group slices per workgroup; fixed summation tree, so the result does not depend on timing
-  __shared__ float red[8][33];
-  const int cx = threadIdx.x & 31, gy = threadIdx.x >> 5;
-  const int c = blockIdx.x * 32 + cx;
+  // 16 columns x 16 group slices per workgroup; fixed summation tree, so the result does not depend on timing
+  __shared__ float red[16][17];
+  const int cx = threadIdx.x & 15, gy = threadIdx.x >> 4;
+  const int c = blockIdx.x * 16 + cx;
   for (int k = 0; k < a.nk; k++) {
     if (!a.out[k]) continue;
     float s = 0.f;
     if (c < cols) {
       const float* p = scratch + (size_t)k * groups * cols + c;
       int g = gy;
-      for (; g + 24 < groups; g += 32) {
-        float v0 = p[(size_t)g * cols], v1 = p[(size_t)(g + 8) * cols], v2 = p[(size_t)(g + 16) * cols],
-              v3 = p[(size_t)(g + 24) * cols];
+      for (; g + 48 < groups; g += 64) {
+        float v0 = p[(size_t)g * cols], v1 = p[(size_t)(g + 16) * cols], v2 = p[(size_t)(g + 32) * cols],
+              v3 = p[(size_t)(g + 48) * cols];
         s += (v0 + v1) + (v2 + v3);
       }
-      for (; g < groups; g += 8) s += p[(size_t)g * cols];
+      for (; g < groups; g += 16) s += p[(size_t)g * cols];
     }
     __syncthreads();
     red[gy][cx] = s;
@@ -174,7 +174,7 @@ __global__ __launch_bounds__(NT) void colsum_finalize_kernel(const float* __rest
     if (gy == 0 && c < cols) {
       float t = 0.f;
 #pragma unroll
-      for (int i = 0; i < 8; i++) t += red[i][cx];
+      for (int i = 0; i < 16; i++) t += red[i][cx];
       a.out[k][c] += t;
     }
   }
@@ -193,32 +193,30 @@ __global__ __launch_bounds__(NT) void layernorm_bwd_kernel(const float* __restri
   __shared__ float red[8];
   const int tid = threadIdx.x, nc = h >> 2;
   const size_t gstride = (size_t)gridDim.x * h;
-  f32x4 ag[NC], ab[NC], az[NC], gm[NC];
+  f32x4 ag[NC], ab[NC], az[NC];
 #pragma unroll
-  for (int i = 0; i < NC; i++) {
-    ag[i] = ab[i] = az[i] = gm[i] = f32x4{0.f, 0.f, 0.f, 0.f};
-    const int c = tid + i * NT;
-    if (c < nc) gm[i] = *reinterpret_cast<const f32x4*>(gamma + 4 * c);
-  }
+  for (int i = 0; i < NC; i++) ag[i] = ab[i] = az[i] = f32x4{0.f, 0.f, 0.f, 0.f};
   for (int row = blockIdx.x; row < rows; row += gridDim.x) {
     const size_t base = (size_t)row * h;
     const float m = mu[row], rs = rstd[row];
-    f32x4 gg[NC], xh[NC];
+    f32x4 gg[NC], xh[NC], dr[NC];
     float s1 = 0.f, s2 = 0.f;
 #pragma unroll
     for (int i = 0; i < NC; i++) {
       const int c = tid + i * NT;
-      gg[i] = xh[i] = f32x4{0.f, 0.f, 0.f, 0.f};
+      gg[i] = xh[i] = dr[i] = f32x4{0.f, 0.f, 0.f, 0.f};
       if (c < nc) {
         f32x4 g = *reinterpret_cast<const f32x4*>(part + base + 4 * c);
         if (peer) g += *reinterpret_cast<const f32x4*>(peer + base + 4 * c);
         f32x4 xv = *reinterpret_cast<const f32x4*>(x + base + 4 * c);
+        dr[i] = *reinterpret_cast<const f32x4*>(dres + base + 4 * c);   // needed only after the reduction: fetched now
+        f32x4 gm = *reinterpret_cast<const f32x4*>(gamma + 4 * c);
 #pragma unroll
         for (int j = 0; j < 4; j++) {
           xh[i][j] = (xv[j] - m) * rs;
           ag[i][j] += g[j] * xh[i][j];
           ab[i][j] += g[j];
-          gg[i][j] = g[j] * gm[i][j];
+          gg[i][j] = g[j] * gm[j];
           s1 += gg[i][j];
           s2 += gg[i][j] * xh[i][j];
         }
@@ -230,7 +228,7 @@ __global__ __launch_bounds__(NT) void layernorm_bwd_kernel(const float* __restri
     for (int i = 0; i < NC; i++) {
       const int c = tid + i * NT;
       if (c < nc) {
-        f32x4 o = *reinterpret_cast<const f32x4*>(dres + base + 4 * c);
+        f32x4 o = dr[i];
 #pragma unroll
         for (int j = 0; j < 4; j++) o[j] += rs * (gg[i][j] - m1 - xh[i][j] * m2);
         *reinterpret_cast<f32x4*>(dxo + base + 4 * c) = o;
@@ -275,6 +273,12 @@ __global__ __launch_bounds__(NT) void colsum_bf16_kernel(const uint16_t* __restr
   float* p = scratch + (size_t)blockIdx.x * cols + 8 * c;
   *reinterpret_cast<f32x4*>(p) = f32x4{acc[0], acc[1], acc[2], acc[3]};
   *reinterpret_cast<f32x4*>(p + 4) = f32x4{acc[4], acc[5], acc[6], acc[7]};
+}
+
+// row groups of a two-stage column reduction: about four rows per group, at most kColPartials groups
+int col_groups(int rows) {
+  int g = rows / 4;
+  return g < 1 ? 1 : (g > kColPartials ? kColPartials : g);
 }
 
 int pick_nc(int h) {
@@ -348,7 +352,7 @@ int launch_layernorm_fwd(const float* x, const float* gamma, const float* beta, 
 
 static int finalize(float* scratch, float* o0, float* o1, float* o2, int nk, int groups, int cols, hipStream_t s) {
   FinalizeArgs a{{o0, o1, o2}, nk};
-  hipLaunchKernelGGL(colsum_finalize_kernel, dim3((cols + 31) / 32), dim3(NT), 0, s, scratch, a, groups, cols);
+  hipLaunchKernelGGL(colsum_finalize_kernel, dim3((cols + 15) / 16), dim3(NT), 0, s, scratch, a, groups, cols);
   OASES_LAUNCH_CHECK("colsum_finalize_kernel");
   return 0;
 }
@@ -357,7 +361,7 @@ int launch_dropout_bwd(const float* dyin, void* dz, float* dbias, int rows, int 
                        float* scratch, hipStream_t s) {
   if (!check_h(rows, h, "dropout_bwd")) return OASES_EINVAL;
   if (!dyin || !dz || (dbias && !scratch)) { set_error("dropout_bwd: NULL argument"); return OASES_ENULL; }
-  const int groups = rows < kColPartials ? rows : kColPartials;
+  const int groups = col_groups(rows);
   OASES_NC_DISPATCH(pick_nc(h), hipLaunchKernelGGL(dropout_bwd_kernel<NC>, dim3(groups), dim3(NT), 0, s, dyin, (uint16_t*)dz,
                                                    dbias ? scratch : nullptr, rows, h, d, row0));
   OASES_LAUNCH_CHECK("dropout_bwd_kernel");
@@ -373,7 +377,7 @@ int launch_layernorm_bwd(const float* part, const float* peer, const float* dres
     set_error("layernorm_bwd: NULL argument");
     return OASES_ENULL;
   }
-  const int groups = rows < kColPartials ? rows : kColPartials;
+  const int groups = col_groups(rows);
   OASES_NC_DISPATCH(pick_nc(h), hipLaunchKernelGGL(layernorm_bwd_kernel<NC>, dim3(groups), dim3(NT), 0, s, part, peer, dres, x, mu,
                                                    rstd, gamma, dxo, (uint16_t*)dz, scratch, rows, h, d, row0));
   OASES_LAUNCH_CHECK("layernorm_bwd_kernel");
@@ -383,7 +387,7 @@ int launch_layernorm_bwd(const float* part, const float* peer, const float* dres
 int launch_colsum_bf16(const void* a, int ld, int rows, int cols, float* out, float* scratch, hipStream_t s) {
   if (!a || !out || !scratch) { set_error("colsum_bf16: NULL argument"); return OASES_ENULL; }
   if (rows <= 0 || cols <= 0 || cols % 8 || ld % 8 || ld < cols) { set_error("colsum_bf16: bad shape"); return OASES_EINVAL; }
-  const int groups = rows < kColPartials ? rows : kColPartials;
+  const int groups = col_groups(rows);
   hipLaunchKernelGGL(colsum_bf16_kernel, dim3(groups, (cols / 8 + NT - 1) / NT), dim3(NT), 0, s, (const uint16_t*)a, ld, rows,
                      cols, scratch);
   OASES_LAUNCH_CHECK("colsum_bf16_kernel");

@@ -95,7 +95,7 @@ def test_dropout_bwd(B, lo, rows, h, p):
     dy = dev(randn(g, rows, h), torch.float32)
     dz = torch.empty(rows, h, dtype=torch.bfloat16, device="cuda")
     db = torch.full((h,), 1.0, dtype=torch.float32, device="cuda")      # accumulated into
-    scratch = torch.empty(256 * h, dtype=torch.float32, device="cuda")
+    scratch = torch.empty(1024 * h, dtype=torch.float32, device="cuda")
     B.check(B.lib.oases_op_dropout_bwd(dy.data_ptr(), dz.data_ptr(), db.data_ptr(), rows, h, 5, 1, 1, 64, p, scratch.data_ptr(), None))
     keep = torch.from_numpy(lo.dropout_keep_mask(5, 1, 1, rows, h, p, row0=64)).double()
     ref = keep * dy.cpu().double() / (1 - p)
@@ -119,7 +119,7 @@ def test_layernorm_bwd(B, lo, rows, h, p, with_peer, with_dz):
     dgam = torch.zeros(h, dtype=torch.float32, device="cuda")
     dbet = torch.zeros_like(dgam)
     dbias = torch.zeros_like(dgam)
-    scratch = torch.empty(4 * 256 * h, dtype=torch.float32, device="cuda")
+    scratch = torch.empty(3 * 1024 * h, dtype=torch.float32, device="cuda")
     B.check(B.lib.oases_op_layernorm_bwd(
         d["part"].data_ptr(), d["peer"].data_ptr() if with_peer else None, d["dres"].data_ptr(), d["x"].data_ptr(),
         mu.data_ptr(), rstd.data_ptr(), d["gam"].data_ptr(), dxo.data_ptr(), dgam.data_ptr(), dbet.data_ptr(),
@@ -142,7 +142,7 @@ def test_layernorm_bwd(B, lo, rows, h, p, with_peer, with_dz):
 def test_colsum(B, rows, cols, ld):
     a = dev(bf16_round(randn(gen(5), rows, ld)), torch.bfloat16)
     out = torch.full((cols,), 2.0, dtype=torch.float32, device="cuda")
-    scratch = torch.empty(256 * cols, dtype=torch.float32, device="cuda")
+    scratch = torch.empty(1024 * cols, dtype=torch.float32, device="cuda")
     B.check(B.lib.oases_op_colsum_bf16(a.data_ptr(), ld, rows, cols, out.data_ptr(), scratch.data_ptr(), None))
     assert rel_err(out, 2.0 + a.cpu().double()[:, :cols].sum(0)) < 1e-5
 
