@@ -1,13 +1,19 @@
 // Flash-style attention for the local heads of one TMP rank (gfx950, bf16 MFMA, fp32 softmax).
 //
-// Forward and the dQ kernel compute the TRANSPOSED score tile S^T = K*Q^T with
-// v_mfma_f32_32x32x16_bf16, so that a lane owns one query (accumulator column l%32) and 16 keys of
-// every 32-key tile: the online softmax is then lane-local except for one exchange between the two
-// lane halves, and the exponentials are already in B-operand position for O^T = V^T * P^T (the
-// k index of that product is permuted the same way for both operands: rows 4*(l/32)+{0..3} and
-// +8 of each 16-key step; the V^T operand comes from the LDS transpose read).
-// The dK/dV kernel keeps S = Q*K^T un-transposed so a lane owns one key and P^T / dS^T are in
-// A-operand position.  No atomics: dQ and dK/dV are separate passes, results are deterministic.
+// Work decomposition.  A workgroup owns 32 rows of one (sequence, head): 32 queries (forward, dQ) or 32 keys
+// (dK/dV).  Its four waves split the reduction range -- the 32-row key tiles a query block sees, or the 32-row
+// query tiles that see a key block -- round-robin, each wave staging its own tiles in a private slice of LDS, so
+// the main loops need no workgroup barrier; the four partial results meet once, through LDS, at the end.  This
+// keeps every SIMD busy on a workload that has few (query, head) rows per sub-batch and shortens the longest
+// causal row of work fourfold.
+//
+// Forward and dQ compute the TRANSPOSED score tile S^T = K*Q^T with v_mfma_f32_32x32x16_bf16, so that a lane owns
+// one query (accumulator column l%32) and 16 keys of the tile: the online softmax is lane-local except for one
+// exchange between the two lane halves, and the exponentials are already in B-operand position for
+// O^T = V^T * P^T (the k index of that product is permuted the same way for both operands: rows 4*(l/32)+{0..3}
+// and +8 of each 16-key step; the V^T operand comes from the LDS transpose read ds_read_b64_tr_b16).
+// dK/dV keeps S = Q*K^T un-transposed so a lane owns one key and P^T / dS^T are in A-operand position.
+// No atomics: dQ and dK/dV are separate passes, results are deterministic.
 #include "common.h"
 
 namespace oases {
@@ -15,7 +21,6 @@ namespace oases {
 namespace {
 
 constexpr int NT = 256;
-constexpr int kPad = 64;  // bytes of row padding of tiles read through ds_read_b64_tr_b16
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
 
@@ -31,74 +36,53 @@ struct AttnArgs {
   int seq0;    // first sequence of the row range
   int pos0;    // first position (within each sequence) of the row range
   int npos;    // positions per sequence in the row range
-  int blocks;  // 128-row blocks per sequence
+  int blocks;  // 32-row blocks per sequence
   float scale, scale_log2;
 };
 
-template <int ROWS, int D>
-struct Tile {
-  static constexpr int cpr = D / 8;
-  static constexpr int chunks = ROWS * cpr;
-  static constexpr int per_thread = chunks / NT;
-  static constexpr int kc_row = D * 2;
-  static constexpr int mc_row = D * 2 + kPad;
-  static constexpr int kc_bytes = ROWS * kc_row;
-  static constexpr int mc_bytes = ROWS * mc_row;
+// A 32-row tile of a [*, D] bf16 slice in LDS, rows padded so that BOTH access patterns are conflict-free on 64
+// banks: ds_read_b128 of 16 consecutive rows at one column (row stride = 4 resp. 12 banks mod 64) and the
+// transpose read of 4 consecutive rows x 32 bytes.
+template <int D>
+struct AT {
+  static constexpr int pad = D == 128 ? 48 : 16;
+  static constexpr int row = D * 2 + pad;
+  static constexpr int bytes = 32 * row;
+  static constexpr int cpr = D / 8;            // 16-byte chunks per row
+  static constexpr int per_lane = 32 * cpr / 64;  // chunks per lane when one wave moves the tile
 };
 
-// XOR swizzle of the 16-byte chunk index of a row-major [rows][D] tile: 16 consecutive rows read at the same
-// logical chunk must land on 16 different bank groups (64 banks x 4 bytes, 16 lanes per LDS cycle)
+// one wave: rows [r0, r0+32) of a [*, D] slice (row stride ld elements) -> registers; rows >= rmax read as zero
 template <int D>
-__device__ __forceinline__ int kc_swizzle(int row) {
-  return D == 128 ? (row & 15) : ((row >> 1) & 7);
-}
-
-// rows [r0, r0+ROWS) of a [*, D] slice with row stride ld; rows >= rmax read as zero
-template <int ROWS, int D>
-__device__ __forceinline__ void load_rows(u32x4* regs, const uint16_t* __restrict__ base, int ld,
-                                          int r0, int rmax, int tid) {
-  using T = Tile<ROWS, D>;
+__device__ __forceinline__ void wave_load(u32x4* regs, const uint16_t* __restrict__ base, int ld, int r0, int rmax, int lane) {
 #pragma unroll
-  for (int i = 0; i < T::per_thread; i++) {
-    int c = tid + i * NT;
-    int row = c / T::cpr, cc = c % T::cpr;
-    u32x4 v = {0u, 0u, 0u, 0u};
-    if (r0 + row < rmax) v = *reinterpret_cast<const u32x4*>(base + (size_t)(r0 + row) * ld + cc * 8);
-    regs[i] = v;
+  for (int i = 0; i < AT<D>::per_lane; i++) {
+    int c = lane + 64 * i;
+    int row = c / AT<D>::cpr, cc = c % AT<D>::cpr;
+    int r = min(r0 + row, rmax - 1);
+    u32x4 v = *reinterpret_cast<const u32x4*>(base + (size_t)r * ld + cc * 8);
+    regs[i] = (r0 + row < rmax) ? v : u32x4{0u, 0u, 0u, 0u};
   }
 }
-template <int ROWS, int D>
-__device__ __forceinline__ void store_kc(const u32x4* regs, char* lds, int tid) {
-  using T = Tile<ROWS, D>;
-#pragma unroll
-  for (int i = 0; i < T::per_thread; i++) {
-    int c = tid + i * NT;
-    int row = c / T::cpr, cc = c % T::cpr;
-    *reinterpret_cast<u32x4*>(lds + row * T::kc_row + ((cc ^ kc_swizzle<D>(row)) << 4)) = regs[i];
-  }
-}
-template <int ROWS, int D>
-__device__ __forceinline__ void store_mc(const u32x4* regs, char* lds, int tid) {
-  using T = Tile<ROWS, D>;
-#pragma unroll
-  for (int i = 0; i < T::per_thread; i++) {
-    int c = tid + i * NT;
-    int row = c / T::cpr, cc = c % T::cpr;
-    *reinterpret_cast<u32x4*>(lds + row * T::mc_row + (cc << 4)) = regs[i];
-  }
-}
-// operand fragment (32 rows x 16 contraction) of a row-major [rows][D] tile, contraction along D
 template <int D>
-__device__ __forceinline__ bf16x8 kc_frag(const char* lds, int r0, int ks, int lane) {
-  int row = r0 + (lane & 31);
-  int chunk = ks * 2 + (lane >> 5);
-  return *reinterpret_cast<const bf16x8*>(lds + row * (D * 2) + ((chunk ^ kc_swizzle<D>(lane & 31)) << 4));
+__device__ __forceinline__ void wave_store(const u32x4* regs, char* lds, int lane) {
+#pragma unroll
+  for (int i = 0; i < AT<D>::per_lane; i++) {
+    int c = lane + 64 * i;
+    int row = c / AT<D>::cpr, cc = c % AT<D>::cpr;
+    *reinterpret_cast<u32x4*>(lds + row * AT<D>::row + (cc << 4)) = regs[i];
+  }
 }
-// operand fragment whose contraction index is the tile ROW (16-row step j) and whose free index is the
-// column c0 + l%32; element e of lane half g is row 16j + 8*(e/4) + 4g + e%4 (matches an accumulator column)
+// operand fragment (32 tile rows x 16 contraction), contraction along D (16-wide step ks)
+template <int D>
+__device__ __forceinline__ bf16x8 kc_frag(const char* lds, int ks, int lane) {
+  return *reinterpret_cast<const bf16x8*>(lds + (lane & 31) * AT<D>::row + ((ks * 2 + (lane >> 5)) << 4));
+}
+// operand fragment whose contraction index is the tile ROW (16-row step j) and whose free index is the column
+// c0 + l%32; element e of lane half g is row 16j + 8*(e/4) + 4g + e%4 (matches an accumulator column)
 template <int D>
 __device__ __forceinline__ bf16x8 mc_frag(const char* lds, int j, int c0, int lane) {
-  constexpr int rowb = D * 2 + kPad;
+  constexpr int rowb = AT<D>::row;
   int krow = j * 16 + 4 * (lane >> 5) + ((lane & 15) >> 2);
   int col = c0 + 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
   const char* p = lds + krow * rowb + col * 2;
@@ -121,128 +105,153 @@ __device__ __forceinline__ f32x16 zero16() {
 }
 #define MFMA(a, b, c) __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0)
 
+// 32 x D bf16 rows of one operand straight from global memory into B/A-operand registers: lane l holds row l%32,
+// columns 16 ks + 8 (l/32) .. +7
+template <int D>
+__device__ __forceinline__ void load_row_frags(bf16x8* f, const uint16_t* __restrict__ rowp, bool ok, int g) {
+#pragma unroll
+  for (int ks = 0; ks < D / 16; ks++) {
+    u32x4 v = {0u, 0u, 0u, 0u};
+    if (ok) v = *reinterpret_cast<const u32x4*>(rowp + ks * 16 + 8 * g);
+    f[ks] = __builtin_bit_cast(bf16x8, v);
+  }
+}
+
+// sum of the four waves' partial accumulators through LDS: wave w ends up with elements [w*E/4, (w+1)*E/4) of the
+// flattened (tile, element) index, summed over the four partials with the weights sc[0..3]
+template <int E>
+__device__ __forceinline__ void combine4(const f32x16* acc, float* lds_part, int wave, int lane, const float* sc, float* out) {
+  __syncthreads();  // every wave is done with its tiles: the staging area is free
+#pragma unroll
+  for (int e = 0; e < E; e++) lds_part[(wave * E + e) * 64 + lane] = acc[e / 16][e % 16];
+  __syncthreads();
+#pragma unroll
+  for (int k = 0; k < E / 4; k++) {
+    const int e = wave * (E / 4) + k;
+    float v = 0.f;
+#pragma unroll
+    for (int w = 0; w < 4; w++) v += lds_part[(w * E + e) * 64 + lane] * sc[w];
+    out[k] = v;
+  }
+}
+
 // =================================================================================================
 // forward
 // =================================================================================================
 template <int D, bool CAUSAL>
-__global__ __launch_bounds__(NT) void attn_fwd_kernel(AttnArgs a) {
-  using TK = Tile<64, D>;
-  constexpr int KS = D / 16, DT = D / 32;
-  __shared__ __attribute__((aligned(16))) char lds[2 * (TK::kc_bytes + TK::mc_bytes)];
+__global__ __launch_bounds__(NT, 2) void attn_fwd_kernel(AttnArgs a) {
+  constexpr int KS = D / 16, DT = D / 32, E = DT * 16;
+  constexpr int kStageBytes = 4 * 2 * AT<D>::bytes;
+  constexpr int kPartBytes = 4 * E * 64 * 4;
+  __shared__ __attribute__((aligned(16))) char lds[(kStageBytes > kPartBytes ? kStageBytes : kPartBytes) + 1024];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, g = lane >> 5;
-  const int sq = blockIdx.x / a.blocks, qb = blockIdx.x % a.blocks, head = blockIdx.y;
+  const int sq = blockIdx.x / a.blocks, qb = a.blocks - 1 - blockIdx.x % a.blocks, head = blockIdx.y;  // long rows first
   const int seq_idx = a.seq0 + sq;
-  const int q_begin = a.pos0 + qb * 128;
-  const int q_end = min(a.pos0 + a.npos, q_begin + 128);
+  const int q_begin = a.pos0 + qb * 32;
+  const int q_end = min(a.pos0 + a.npos, q_begin + 32);
   const size_t rowbase = (size_t)seq_idx * a.seq;
   const uint16_t* Qp = a.qkv + rowbase * a.ld + head * D;
   const uint16_t* Kp = Qp + a.hp;
   const uint16_t* Vp = Qp + 2 * a.hp;
-  const int qw = q_begin + 32 * wave;
-  const int qpos = qw + (lane & 31);
+  const int qpos = q_begin + (lane & 31);
   const bool qok = qpos < q_end;
 
   bf16x8 qf[KS];
-#pragma unroll
-  for (int ks = 0; ks < KS; ks++) {
-    u32x4 v = {0u, 0u, 0u, 0u};
-    if (qok) v = *reinterpret_cast<const u32x4*>(Qp + (size_t)qpos * a.ld + ks * 16 + 8 * g);
-    qf[ks] = __builtin_bit_cast(bf16x8, v);
-  }
+  load_row_frags<D>(qf, Qp + (size_t)qpos * a.ld, qok, g);
   f32x16 o[DT];
 #pragma unroll
   for (int i = 0; i < DT; i++) o[i] = zero16();
   float m = -INFINITY, l = 0.f;
 
   const int kv_end = CAUSAL ? q_end : a.seq;
-  const int nt = (kv_end + 63) / 64;
-  constexpr int kStage = TK::kc_bytes + TK::mc_bytes;  // stage s: K at lds + s*kStage, V behind it
-  u32x4 rk[TK::per_thread], rv[TK::per_thread];
-  load_rows<64, D>(rk, Kp, a.ld, 0, a.seq, tid);
-  load_rows<64, D>(rv, Vp, a.ld, 0, a.seq, tid);
-  store_kc<64, D>(rk, lds, tid);
-  store_mc<64, D>(rv, lds + TK::kc_bytes, tid);
-  if (nt > 1) {
-    load_rows<64, D>(rk, Kp, a.ld, 64, a.seq, tid);
-    load_rows<64, D>(rv, Vp, a.ld, 64, a.seq, tid);
+  const int nt = (kv_end + 31) / 32;
+  char* lk = lds + wave * 2 * AT<D>::bytes;
+  char* lv = lk + AT<D>::bytes;
+  u32x4 rk[AT<D>::per_lane], rv[AT<D>::per_lane];
+  if (wave < nt) {
+    wave_load<D>(rk, Kp, a.ld, wave * 32, a.seq, lane);
+    wave_load<D>(rv, Vp, a.ld, wave * 32, a.seq, lane);
   }
-  __syncthreads();
-
-  for (int t = 0; t < nt; t++) {
-    const int cur = t & 1, kv0 = t * 64;
-    if (t + 1 < nt) {
-      store_kc<64, D>(rk, lds + (cur ^ 1) * kStage, tid);
-      store_mc<64, D>(rv, lds + (cur ^ 1) * kStage + TK::kc_bytes, tid);
-      if (t + 2 < nt) {
-        load_rows<64, D>(rk, Kp, a.ld, (t + 2) * 64, a.seq, tid);
-        load_rows<64, D>(rv, Vp, a.ld, (t + 2) * 64, a.seq, tid);
-      }
+  for (int t = wave; t < nt; t += 4) {
+    const int kv0 = t * 32;
+    wave_store<D>(rk, lk, lane);  // LDS operations of one wave execute in order: no barrier for a private tile
+    wave_store<D>(rv, lv, lane);
+    if (t + 4 < nt) {
+      wave_load<D>(rk, Kp, a.ld, kv0 + 128, a.seq, lane);
+      wave_load<D>(rv, Vp, a.ld, kv0 + 128, a.seq, lane);
     }
-    if (!(CAUSAL && kv0 > qw + 31)) {
-      const char* lk = lds + cur * kStage;
-      const char* lv = lk + TK::kc_bytes;
-      f32x16 s[2];
+    f32x16 s = zero16(), s1 = zero16();
 #pragma unroll
-      for (int u = 0; u < 2; u++) {
-        s[u] = zero16();
-#pragma unroll
-        for (int ks = 0; ks < KS; ks++) s[u] = MFMA(kc_frag<D>(lk, 32 * u, ks, lane), qf[ks], s[u]);
-      }
-      const bool need_mask = (kv0 + 64 > a.seq) || (CAUSAL && kv0 + 63 > qw);
-      float mloc = -INFINITY;
-#pragma unroll
-      for (int u = 0; u < 2; u++)
-#pragma unroll
-        for (int i = 0; i < 16; i++) {
-          float v = s[u][i] * a.scale_log2;
-          if (need_mask) {
-            int kvpos = kv0 + 32 * u + 8 * (i >> 2) + 4 * g + (i & 3);
-            if (kvpos >= a.seq || (CAUSAL && kvpos > qpos)) v = -INFINITY;
-          }
-          s[u][i] = v;
-          mloc = fmaxf(mloc, v);
-        }
-      mloc = fmaxf(mloc, __shfl_xor(mloc, 32, 64));
-      const float mnew = fmaxf(m, mloc);  // finite: the first tile always holds key 0, visible to every query
-      const float alpha = __builtin_amdgcn_exp2f(m - mnew);
-      float psum = 0.f;
-#pragma unroll
-      for (int u = 0; u < 2; u++)
-#pragma unroll
-        for (int i = 0; i < 16; i++) {
-          float p = __builtin_amdgcn_exp2f(s[u][i] - mnew);
-          s[u][i] = p;
-          psum += p;
-        }
-      l = l * alpha + psum;
-      m = mnew;
-#pragma unroll
-      for (int dt = 0; dt < DT; dt++)
-#pragma unroll
-        for (int i = 0; i < 16; i++) o[dt][i] *= alpha;
-#pragma unroll
-      for (int j = 0; j < 4; j++) {
-        bf16x8 pb = pack8(s[j >> 1], 8 * (j & 1));
-#pragma unroll
-        for (int dt = 0; dt < DT; dt++) o[dt] = MFMA(mc_frag<D>(lv, j, 32 * dt, lane), pb, o[dt]);
-      }
+    for (int ks = 0; ks < KS; ks += 2) {  // two independent accumulation chains
+      s = MFMA(kc_frag<D>(lk, ks, lane), qf[ks], s);
+      s1 = MFMA(kc_frag<D>(lk, ks + 1, lane), qf[ks + 1], s1);
     }
-    __syncthreads();
-  }
-  l += __shfl_xor(l, 32, 64);
-  if (qok) {
-    const float inv = 1.0f / l;
-    uint16_t* op = a.out_w + (rowbase + qpos) * a.hp + head * D;
+    const bool need_mask = (kv0 + 32 > a.seq) || (CAUSAL && kv0 + 31 > q_begin);
+    float mloc = -INFINITY;
+#pragma unroll
+    for (int i = 0; i < 16; i++) {
+      float v = (s[i] + s1[i]) * a.scale_log2;
+      if (need_mask) {
+        int kvpos = kv0 + 8 * (i >> 2) + 4 * g + (i & 3);
+        if (kvpos >= a.seq || (CAUSAL && kvpos > qpos)) v = -INFINITY;
+      }
+      s[i] = v;
+      mloc = fmaxf(mloc, v);
+    }
+    mloc = fmaxf(mloc, __shfl_xor(mloc, 32, 64));
+    // wave 0 starts with tile 0, which holds key 0, visible to every query; a later wave may start on a tile that is
+    // masked for some of its queries: keep the running maximum finite there so that exp2 never sees inf - inf
+    const float mnew = fmaxf(fmaxf(m, mloc), -1e30f);
+    const float alpha = __builtin_amdgcn_exp2f(m - mnew);
+    float psum = 0.f;
+#pragma unroll
+    for (int i = 0; i < 16; i++) {
+      float p = __builtin_amdgcn_exp2f(s[i] - mnew);
+      s[i] = p;
+      psum += p;
+    }
+    l = l * alpha + psum;
+    m = mnew;
 #pragma unroll
     for (int dt = 0; dt < DT; dt++)
 #pragma unroll
-      for (int q4 = 0; q4 < 4; q4++) {
-        int d = dt * 32 + 8 * q4 + 4 * g;
-        u32x2 v = {pack_bf16x2(o[dt][4 * q4] * inv, o[dt][4 * q4 + 1] * inv),
-                   pack_bf16x2(o[dt][4 * q4 + 2] * inv, o[dt][4 * q4 + 3] * inv)};
-        *reinterpret_cast<u32x2*>(op + d) = v;
-      }
-    if (g == 0) a.lse[((size_t)seq_idx * a.heads + head) * a.seq + qpos] = (m + __builtin_amdgcn_logf(l)) * kLn2;
+      for (int i = 0; i < 16; i++) o[dt][i] *= alpha;
+#pragma unroll
+    for (int j = 0; j < 2; j++) {
+      bf16x8 pb = pack8(s, 8 * j);
+#pragma unroll
+      for (int dt = 0; dt < DT; dt++) o[dt] = MFMA(mc_frag<D>(lv, j, 32 * dt, lane), pb, o[dt]);
+    }
+  }
+  l += __shfl_xor(l, 32, 64);
+
+  // merge the four partial (m, l, O): weights 2^(m_w - m)
+  float* part = reinterpret_cast<float*>(lds);
+  float* stat = reinterpret_cast<float*>(lds + (kStageBytes > kPartBytes ? kStageBytes : kPartBytes));  // m[4][32], l[4][32]
+  __syncthreads();
+  if (g == 0) { stat[wave * 32 + lane] = m; stat[128 + wave * 32 + lane] = l; }
+  __syncthreads();
+  float sc[4], mt = -INFINITY, lt = 0.f;
+#pragma unroll
+  for (int w = 0; w < 4; w++) mt = fmaxf(mt, stat[w * 32 + (lane & 31)]);
+#pragma unroll
+  for (int w = 0; w < 4; w++) {
+    sc[w] = __builtin_amdgcn_exp2f(stat[w * 32 + (lane & 31)] - mt);
+    lt += stat[128 + w * 32 + (lane & 31)] * sc[w];
+  }
+  float res[E / 4];
+  combine4<E>(o, part, wave, lane, sc, res);
+  if (qok) {
+    const float inv = 1.0f / lt;
+    uint16_t* op = a.out_w + (rowbase + qpos) * a.hp + head * D;
+#pragma unroll
+    for (int k = 0; k < E / 4; k += 4) {
+      const int e = wave * (E / 4) + k, dt = e / 16, i = e % 16;
+      const int d = dt * 32 + 8 * (i >> 2) + 4 * g;
+      u32x2 v = {pack_bf16x2(res[k] * inv, res[k + 1] * inv), pack_bf16x2(res[k + 2] * inv, res[k + 3] * inv)};
+      *reinterpret_cast<u32x2*>(op + d) = v;
+    }
+    if (wave == 0 && g == 0) a.lse[((size_t)seq_idx * a.heads + head) * a.seq + qpos] = (mt + __builtin_amdgcn_logf(lt)) * kLn2;
   }
 }
 
@@ -276,41 +285,30 @@ __global__ __launch_bounds__(NT) void attn_delta_kernel(AttnArgs a, int first_ro
 }
 
 // =================================================================================================
-// backward: dQ for a 128-query block (same tiling as forward)
+// backward: dQ for a 32-query block; the four waves split the key tiles
 // =================================================================================================
 template <int D, bool CAUSAL>
-__global__ __launch_bounds__(NT) void attn_dq_kernel(AttnArgs a) {
-  using TK = Tile<64, D>;
-  constexpr int KS = D / 16, DT = D / 32;
-  __shared__ __attribute__((aligned(16))) char lds[2 * TK::kc_bytes + TK::mc_bytes];
-  char* lk = lds;                    // K, contraction along d
-  char* lv = lds + TK::kc_bytes;     // V, contraction along d
-  char* lkt = lds + 2 * TK::kc_bytes;  // K again, read transposed
+__global__ __launch_bounds__(NT, 1) void attn_dq_kernel(AttnArgs a) {
+  constexpr int KS = D / 16, DT = D / 32, E = DT * 16;
+  constexpr int kStageBytes = 4 * 2 * AT<D>::bytes;
+  constexpr int kPartBytes = 4 * E * 64 * 4;
+  __shared__ __attribute__((aligned(16))) char lds[kStageBytes > kPartBytes ? kStageBytes : kPartBytes];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, g = lane >> 5;
-  const int sq = blockIdx.x / a.blocks, qb = blockIdx.x % a.blocks, head = blockIdx.y;
+  const int sq = blockIdx.x / a.blocks, qb = a.blocks - 1 - blockIdx.x % a.blocks, head = blockIdx.y;
   const int seq_idx = a.seq0 + sq;
-  const int q_begin = a.pos0 + qb * 128;
-  const int q_end = min(a.pos0 + a.npos, q_begin + 128);
+  const int q_begin = a.pos0 + qb * 32;
+  const int q_end = min(a.pos0 + a.npos, q_begin + 32);
   const size_t rowbase = (size_t)seq_idx * a.seq;
   const uint16_t* Qp = a.qkv + rowbase * a.ld + head * D;
   const uint16_t* Kp = Qp + a.hp;
   const uint16_t* Vp = Qp + 2 * a.hp;
   const uint16_t* dOp = a.dout + rowbase * a.hp + head * D;
-  const int qw = q_begin + 32 * wave;
-  const int qpos = qw + (lane & 31);
+  const int qpos = q_begin + (lane & 31);
   const bool qok = qpos < q_end;
 
   bf16x8 qf[KS], dof[KS];
-#pragma unroll
-  for (int ks = 0; ks < KS; ks++) {
-    u32x4 v = {0u, 0u, 0u, 0u}, w = {0u, 0u, 0u, 0u};
-    if (qok) {
-      v = *reinterpret_cast<const u32x4*>(Qp + (size_t)qpos * a.ld + ks * 16 + 8 * g);
-      w = *reinterpret_cast<const u32x4*>(dOp + (size_t)qpos * a.hp + ks * 16 + 8 * g);
-    }
-    qf[ks] = __builtin_bit_cast(bf16x8, v);
-    dof[ks] = __builtin_bit_cast(bf16x8, w);
-  }
+  load_row_frags<D>(qf, Qp + (size_t)qpos * a.ld, qok, g);
+  load_row_frags<D>(dof, dOp + (size_t)qpos * a.hp, qok, g);
   float lse2 = 0.f, dl = 0.f;
   if (qok) {
     size_t si = ((size_t)seq_idx * a.heads + head) * a.seq + qpos;
@@ -322,84 +320,74 @@ __global__ __launch_bounds__(NT) void attn_dq_kernel(AttnArgs a) {
   for (int i = 0; i < DT; i++) acc[i] = zero16();
 
   const int kv_end = CAUSAL ? q_end : a.seq;
-  const int nt = (kv_end + 63) / 64;
-  u32x4 rk[TK::per_thread], rv[TK::per_thread];
-  load_rows<64, D>(rk, Kp, a.ld, 0, a.seq, tid);
-  load_rows<64, D>(rv, Vp, a.ld, 0, a.seq, tid);
-  for (int t = 0; t < nt; t++) {
-    const int kv0 = t * 64;
-    __syncthreads();
-    store_kc<64, D>(rk, lk, tid);
-    store_mc<64, D>(rk, lkt, tid);
-    store_kc<64, D>(rv, lv, tid);
-    __syncthreads();
-    if (t + 1 < nt) {
-      load_rows<64, D>(rk, Kp, a.ld, kv0 + 64, a.seq, tid);
-      load_rows<64, D>(rv, Vp, a.ld, kv0 + 64, a.seq, tid);
+  const int nt = (kv_end + 31) / 32;
+  char* lk = lds + wave * 2 * AT<D>::bytes;
+  char* lv = lk + AT<D>::bytes;
+  u32x4 rk[AT<D>::per_lane], rv[AT<D>::per_lane];
+  if (wave < nt) {
+    wave_load<D>(rk, Kp, a.ld, wave * 32, a.seq, lane);
+    wave_load<D>(rv, Vp, a.ld, wave * 32, a.seq, lane);
+  }
+  for (int t = wave; t < nt; t += 4) {
+    const int kv0 = t * 32;
+    wave_store<D>(rk, lk, lane);
+    wave_store<D>(rv, lv, lane);
+    if (t + 4 < nt) {
+      wave_load<D>(rk, Kp, a.ld, kv0 + 128, a.seq, lane);
+      wave_load<D>(rv, Vp, a.ld, kv0 + 128, a.seq, lane);
     }
-    if (CAUSAL && kv0 > qw + 31) continue;
-    f32x16 s[2], dp[2];
+    f32x16 s = zero16(), dp = zero16();
 #pragma unroll
-    for (int u = 0; u < 2; u++) {
-      s[u] = zero16();
-      dp[u] = zero16();
-#pragma unroll
-      for (int ks = 0; ks < KS; ks++) {
-        s[u] = MFMA(kc_frag<D>(lk, 32 * u, ks, lane), qf[ks], s[u]);
-        dp[u] = MFMA(kc_frag<D>(lv, 32 * u, ks, lane), dof[ks], dp[u]);
-      }
+    for (int ks = 0; ks < KS; ks++) {
+      s = MFMA(kc_frag<D>(lk, ks, lane), qf[ks], s);
+      dp = MFMA(kc_frag<D>(lv, ks, lane), dof[ks], dp);
     }
-    const bool need_mask = (kv0 + 64 > a.seq) || (CAUSAL && kv0 + 63 > qw);
+    const bool need_mask = (kv0 + 32 > a.seq) || (CAUSAL && kv0 + 31 > q_begin);
 #pragma unroll
-    for (int u = 0; u < 2; u++)
-#pragma unroll
-      for (int i = 0; i < 16; i++) {
-        float p = __builtin_amdgcn_exp2f(s[u][i] * a.scale_log2 - lse2);
-        if (need_mask) {
-          int kvpos = kv0 + 32 * u + 8 * (i >> 2) + 4 * g + (i & 3);
-          if (kvpos >= a.seq || (CAUSAL && kvpos > qpos)) p = 0.f;
-        }
-        s[u][i] = p * (dp[u][i] - dl);
+    for (int i = 0; i < 16; i++) {
+      float p = __builtin_amdgcn_exp2f(s[i] * a.scale_log2 - lse2);
+      if (need_mask) {
+        int kvpos = kv0 + 8 * (i >> 2) + 4 * g + (i & 3);
+        if (kvpos >= a.seq || (CAUSAL && kvpos > qpos)) p = 0.f;
       }
+      s[i] = p * (dp[i] - dl);
+    }
 #pragma unroll
-    for (int j = 0; j < 4; j++) {
-      bf16x8 db = pack8(s[j >> 1], 8 * (j & 1));
+    for (int j = 0; j < 2; j++) {
+      bf16x8 db = pack8(s, 8 * j);
 #pragma unroll
-      for (int dt = 0; dt < DT; dt++) acc[dt] = MFMA(mc_frag<D>(lkt, j, 32 * dt, lane), db, acc[dt]);
+      for (int dt = 0; dt < DT; dt++) acc[dt] = MFMA(mc_frag<D>(lk, j, 32 * dt, lane), db, acc[dt]);
     }
   }
+  const float one[4] = {1.f, 1.f, 1.f, 1.f};
+  float res[E / 4];
+  combine4<E>(acc, reinterpret_cast<float*>(lds), wave, lane, one, res);
   if (qok) {
     uint16_t* op = a.dqkv + (rowbase + qpos) * a.ld + head * D;
 #pragma unroll
-    for (int dt = 0; dt < DT; dt++)
-#pragma unroll
-      for (int q4 = 0; q4 < 4; q4++) {
-        int d = dt * 32 + 8 * q4 + 4 * g;
-        u32x2 v = {pack_bf16x2(acc[dt][4 * q4] * a.scale, acc[dt][4 * q4 + 1] * a.scale),
-                   pack_bf16x2(acc[dt][4 * q4 + 2] * a.scale, acc[dt][4 * q4 + 3] * a.scale)};
-        *reinterpret_cast<u32x2*>(op + d) = v;
-      }
+    for (int k = 0; k < E / 4; k += 4) {
+      const int e = wave * (E / 4) + k, dt = e / 16, i = e % 16;
+      const int d = dt * 32 + 8 * (i >> 2) + 4 * g;
+      u32x2 v = {pack_bf16x2(res[k] * a.scale, res[k + 1] * a.scale), pack_bf16x2(res[k + 2] * a.scale, res[k + 3] * a.scale)};
+      *reinterpret_cast<u32x2*>(op + d) = v;
+    }
   }
 }
 
 // =================================================================================================
-// backward: dK, dV for a 128-key block; loops over the 64-query tiles that see it
+// backward: dK, dV for a 32-key block; the four waves split the 32-query tiles that see it
 // =================================================================================================
 template <int D, bool CAUSAL>
-__global__ __launch_bounds__(NT) void attn_dkv_kernel(AttnArgs a) {
-  using TQ = Tile<64, D>;
-  constexpr int KS = D / 16, DT = D / 32;
-  __shared__ __attribute__((aligned(16))) char lds[2 * (TQ::kc_bytes + TQ::mc_bytes) + 512];
-  char* lq = lds;
-  char* lqt = lq + TQ::kc_bytes;
-  char* ldo = lqt + TQ::mc_bytes;
-  char* ldot = ldo + TQ::kc_bytes;
-  float* lstat = reinterpret_cast<float*>(ldot + TQ::mc_bytes);  // [64] lse2, [64] delta
+__global__ __launch_bounds__(NT, 1) void attn_dkv_kernel(AttnArgs a) {
+  constexpr int KS = D / 16, DT = D / 32, E = DT * 16;
+  constexpr int kStageBytes = 4 * (2 * AT<D>::bytes + 256);
+  constexpr int kPartBytes = 4 * E * 64 * 4;
+  __shared__ __attribute__((aligned(16))) char lds[kStageBytes > kPartBytes ? kStageBytes : kPartBytes];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, g = lane >> 5;
-  const int sq = blockIdx.x / a.blocks, kb = blockIdx.x % a.blocks, head = blockIdx.y;
+  const int sq = blockIdx.x / a.blocks, kb = blockIdx.x % a.blocks, head = blockIdx.y;  // early key blocks are the long ones
   const int seq_idx = a.seq0 + sq;
-  const int k_begin = a.pos0 + kb * 128;
-  const int k_end = min(a.pos0 + a.npos, k_begin + 128);
+  const int k_begin = a.pos0 + kb * 32;
+  const int k_end = min(a.pos0 + a.npos, k_begin + 32);
   const size_t rowbase = (size_t)seq_idx * a.seq;
   const uint16_t* Qp = a.qkv + rowbase * a.ld + head * D;
   const uint16_t* Kp = Qp + a.hp;
@@ -407,106 +395,88 @@ __global__ __launch_bounds__(NT) void attn_dkv_kernel(AttnArgs a) {
   const uint16_t* dOp = a.dout + rowbase * a.hp + head * D;
   const float* lsep = a.lse + ((size_t)seq_idx * a.heads + head) * a.seq;
   const float* dlp = a.delta + ((size_t)seq_idx * a.heads + head) * a.seq;
-  const int kw = k_begin + 32 * wave;
-  const int kpos = kw + (lane & 31);
+  const int kpos = k_begin + (lane & 31);
   const bool kok = kpos < k_end;
 
   bf16x8 kf[KS], vf[KS];
-#pragma unroll
-  for (int ks = 0; ks < KS; ks++) {
-    u32x4 v = {0u, 0u, 0u, 0u}, w = {0u, 0u, 0u, 0u};
-    if (kok) {
-      v = *reinterpret_cast<const u32x4*>(Kp + (size_t)kpos * a.ld + ks * 16 + 8 * g);
-      w = *reinterpret_cast<const u32x4*>(Vp + (size_t)kpos * a.ld + ks * 16 + 8 * g);
-    }
-    kf[ks] = __builtin_bit_cast(bf16x8, v);
-    vf[ks] = __builtin_bit_cast(bf16x8, w);
-  }
+  load_row_frags<D>(kf, Kp + (size_t)kpos * a.ld, kok, g);
+  load_row_frags<D>(vf, Vp + (size_t)kpos * a.ld, kok, g);
   f32x16 dk[DT], dv[DT];
 #pragma unroll
   for (int i = 0; i < DT; i++) { dk[i] = zero16(); dv[i] = zero16(); }
 
-  const int qt0 = CAUSAL ? k_begin / 64 : 0;
-  const int nqt = (a.seq + 63) / 64;
-  u32x4 rq[TQ::per_thread], rdo[TQ::per_thread];
+  const int qt0 = CAUSAL ? k_begin / 32 : 0;   // first query tile that sees this key block
+  const int nqt = (a.seq + 31) / 32;
+  char* lq = lds + wave * (2 * AT<D>::bytes + 256);
+  char* ldo = lq + AT<D>::bytes;
+  float* lstat = reinterpret_cast<float*>(ldo + AT<D>::bytes);  // [32] lse * log2(e), [32] delta
+  u32x4 rq[AT<D>::per_lane], rdo[AT<D>::per_lane];
   float rstat = 0.f;
   auto fetch = [&](int t) {
-    load_rows<64, D>(rq, Qp, a.ld, t * 64, a.seq, tid);
-    load_rows<64, D>(rdo, dOp, a.hp, t * 64, a.seq, tid);
-    if (tid < 128) {
-      int qp = t * 64 + (tid & 63);
-      rstat = 0.f;
-      if (qp < a.seq) rstat = tid < 64 ? lsep[qp] * kLog2e : dlp[qp];
-    }
+    wave_load<D>(rq, Qp, a.ld, t * 32, a.seq, lane);
+    wave_load<D>(rdo, dOp, a.hp, t * 32, a.seq, lane);
+    const int qp = min(t * 32 + (lane & 31), a.seq - 1);
+    rstat = g == 0 ? lsep[qp] * kLog2e : dlp[qp];
   };
-  if (qt0 < nqt) fetch(qt0);
-  for (int t = qt0; t < nqt; t++) {
-    const int q0 = t * 64;
-    __syncthreads();
-    store_kc<64, D>(rq, lq, tid);
-    store_mc<64, D>(rq, lqt, tid);
-    store_kc<64, D>(rdo, ldo, tid);
-    store_mc<64, D>(rdo, ldot, tid);
-    if (tid < 128) lstat[tid] = rstat;
-    __syncthreads();
-    if (t + 1 < nqt) fetch(t + 1);
-    if (CAUSAL && q0 + 63 < kw) continue;
-    f32x16 s[2], dp[2];
+  if (qt0 + wave < nqt) fetch(qt0 + wave);
+  for (int t = qt0 + wave; t < nqt; t += 4) {
+    const int q0 = t * 32;
+    wave_store<D>(rq, lq, lane);
+    wave_store<D>(rdo, ldo, lane);
+    lstat[lane] = rstat;
+    if (t + 4 < nqt) fetch(t + 4);
+    f32x16 s = zero16(), dp = zero16();
 #pragma unroll
-    for (int u = 0; u < 2; u++) {
-      s[u] = zero16();
-      dp[u] = zero16();
+    for (int ks = 0; ks < KS; ks++) {
+      s = MFMA(kc_frag<D>(lq, ks, lane), kf[ks], s);
+      dp = MFMA(kc_frag<D>(ldo, ks, lane), vf[ks], dp);
+    }
+    const bool need_mask = (q0 + 32 > a.seq) || (CAUSAL && q0 < k_begin + 31);
 #pragma unroll
-      for (int ks = 0; ks < KS; ks++) {
-        s[u] = MFMA(kc_frag<D>(lq, 32 * u, ks, lane), kf[ks], s[u]);
-        dp[u] = MFMA(kc_frag<D>(ldo, 32 * u, ks, lane), vf[ks], dp[u]);
+    for (int i4 = 0; i4 < 4; i4++) {
+      const int ql = 8 * i4 + 4 * g;  // 4 consecutive queries
+      f32x4 l4 = *reinterpret_cast<const f32x4*>(lstat + ql);
+      f32x4 d4 = *reinterpret_cast<const f32x4*>(lstat + 32 + ql);
+#pragma unroll
+      for (int e = 0; e < 4; e++) {
+        const int i = 4 * i4 + e;
+        float p = __builtin_amdgcn_exp2f(s[i] * a.scale_log2 - l4[e]);
+        if (need_mask) {
+          int qp = q0 + ql + e;
+          if (qp >= a.seq || (CAUSAL && kpos > qp)) p = 0.f;
+        }
+        s[i] = p;
+        dp[i] = p * (dp[i] - d4[e]);
       }
     }
-    const bool need_mask = (q0 + 64 > a.seq) || (CAUSAL && q0 < kw + 31);
 #pragma unroll
-    for (int u = 0; u < 2; u++)
-#pragma unroll
-      for (int i4 = 0; i4 < 4; i4++) {
-        const int ql = 32 * u + 8 * i4 + 4 * g;  // 4 consecutive queries
-        f32x4 l4 = *reinterpret_cast<const f32x4*>(lstat + ql);
-        f32x4 d4 = *reinterpret_cast<const f32x4*>(lstat + 64 + ql);
-#pragma unroll
-        for (int e = 0; e < 4; e++) {
-          const int i = 4 * i4 + e;
-          float p = __builtin_amdgcn_exp2f(s[u][i] * a.scale_log2 - l4[e]);
-          if (need_mask) {
-            int qp = q0 + ql + e;
-            if (qp >= a.seq || (CAUSAL && kpos > qp)) p = 0.f;
-          }
-          s[u][i] = p;
-          dp[u][i] = p * (dp[u][i] - d4[e]);
-        }
-      }
-#pragma unroll
-    for (int j = 0; j < 4; j++) {
-      bf16x8 pa = pack8(s[j >> 1], 8 * (j & 1));
-      bf16x8 da = pack8(dp[j >> 1], 8 * (j & 1));
+    for (int j = 0; j < 2; j++) {
+      bf16x8 pa = pack8(s, 8 * j);
+      bf16x8 da = pack8(dp, 8 * j);
 #pragma unroll
       for (int dt = 0; dt < DT; dt++) {
-        dv[dt] = MFMA(pa, mc_frag<D>(ldot, j, 32 * dt, lane), dv[dt]);
-        dk[dt] = MFMA(da, mc_frag<D>(lqt, j, 32 * dt, lane), dk[dt]);
+        dv[dt] = MFMA(pa, mc_frag<D>(ldo, j, 32 * dt, lane), dv[dt]);
+        dk[dt] = MFMA(da, mc_frag<D>(lq, j, 32 * dt, lane), dk[dt]);
       }
     }
   }
-  // accumulator row = key 8*(i/4) + 4g + i%4 of this wave's 32, column = d = 32*dt + l%32
+  // accumulator row = key 8*(i/4) + 4g + i%4 of the block, column = d = 32*dt + l%32
+  const float one[4] = {1.f, 1.f, 1.f, 1.f};
+  float rk_[E / 4], rv_[E / 4];
+  combine4<E>(dk, reinterpret_cast<float*>(lds), wave, lane, one, rk_);
+  combine4<E>(dv, reinterpret_cast<float*>(lds), wave, lane, one, rv_);
   uint16_t* dKp = a.dqkv + rowbase * a.ld + a.hp + head * D;
   uint16_t* dVp = dKp + a.hp;
 #pragma unroll
-  for (int dt = 0; dt < DT; dt++)
-#pragma unroll
-    for (int i = 0; i < 16; i++) {
-      int kp = kw + 8 * (i >> 2) + 4 * g + (i & 3);
-      if (kp < k_end) {
-        size_t o = (size_t)kp * a.ld + dt * 32 + (lane & 31);
-        dKp[o] = (uint16_t)f32_to_bf16_bits(dk[dt][i] * a.scale);
-        dVp[o] = (uint16_t)f32_to_bf16_bits(dv[dt][i]);
-      }
+  for (int k = 0; k < E / 4; k++) {
+    const int e = wave * (E / 4) + k, dt = e / 16, i = e % 16;
+    const int kp = k_begin + 8 * (i >> 2) + 4 * g + (i & 3);
+    if (kp < k_end) {
+      size_t o = (size_t)kp * a.ld + dt * 32 + (lane & 31);
+      dKp[o] = (uint16_t)f32_to_bf16_bits(rk_[k] * a.scale);
+      dVp[o] = (uint16_t)f32_to_bf16_bits(rv_[k]);
     }
+  }
 }
 
 int fill_args(AttnArgs& a, int batch, int seq, int heads, int head_dim, int causal, int row0, int rows, const char* who) {
@@ -523,7 +493,7 @@ int fill_args(AttnArgs& a, int batch, int seq, int heads, int head_dim, int caus
   if (row0 % seq == 0 && rows % seq == 0) {
     a.pos0 = 0;
     a.npos = seq;
-    a.blocks = (seq + 127) / 128;
+    a.blocks = (seq + 31) / 32;
     return rows / seq;  // number of sequences
   }
   if (row0 / seq != (row0 + rows - 1) / seq) {
@@ -536,7 +506,7 @@ int fill_args(AttnArgs& a, int batch, int seq, int heads, int head_dim, int caus
   }
   a.pos0 = row0 % seq;
   a.npos = rows;
-  a.blocks = (rows + 127) / 128;
+  a.blocks = (rows + 31) / 32;
   return 1;
 }
 

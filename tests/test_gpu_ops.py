@@ -275,7 +275,8 @@ def test_attention_fwd_bwd(B, lo, batch, seq, heads, d, causal):
                  dk=U(bf16_round(dS).transpose(2, 3) @ H(q)) / math.sqrt(d))
     for name in ("dq", "dk", "dv"):
         r = ref_b[name]
-        assert_bf16_close(got[name], r, 2e-3, 2e-3 * float(torch.sqrt((r ** 2).mean())), name)
+        # a bf16 rounding of P / dS that falls the other way (fp32 vs fp64 in front of it) moves one term by 2^-8
+        assert_bf16_close(got[name], r, 3e-3, 6e-3 * float(torch.sqrt((r ** 2).mean())), name)
 
 
 @pytest.mark.parametrize("d", [64, 128])
