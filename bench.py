@@ -32,7 +32,7 @@ def model_flops(cfg):
 def op_flops(line, cfg):
     """Algorithmic flops of one scheduled GEMM / attention operator (one sub-batch); 0 for the HBM-bound ones."""
     M, h, s, t = cfg["batch"] * cfg["seq"], cfg["hidden"], cfg["seq"], cfg["tp"]
-    Ms, hp, fp = M // cfg["n_sub"], h // t, 4 * h // t
+    Ms, hp, fp = (M if line.endswith("sb*") else M // cfg["n_sub"]), h // t, 4 * h // t
     op = line.split()[1]
     base = op.split(".")[0].split("+")[0]
     table = {"QKV": 2.0 * Ms * h * 3 * hp, "PROJ": 2.0 * Ms * hp * h, "FC1": 2.0 * Ms * h * fp, "FC2": 2.0 * Ms * fp * h}
@@ -57,7 +57,7 @@ def op_bytes(line, cfg):
 def gemm_kernel_label(line, cfg, B):
     """Kernel instantiation a GEMM operator runs on: (contraction form, epilogue, block tile)."""
     M, h, t = cfg["batch"] * cfg["seq"], cfg["hidden"], cfg["tp"]
-    Ms, hp, fp = M // cfg["n_sub"], h // t, 4 * h // t
+    Ms, hp, fp = (M if line.endswith("sb*") else M // cfg["n_sub"]), h // t, 4 * h // t
     op = line.split()[1]
     shapes = {"QKV": ("NN", "bias_bf16", Ms, 3 * hp, h), "PROJ": ("NN", "f32", Ms, h, hp), "FC1+GELU": ("NN", "bias_gelu", Ms, fp, h),
               "FC2": ("NN", "f32", Ms, h, fp), "FC2.dgrad+dGELU": ("NT", "dgelu", Ms, fp, h), "FC1.dgrad": ("NT", "f32", Ms, h, fp),
@@ -67,7 +67,7 @@ def gemm_kernel_label(line, cfg, B):
         return None
     form, epi, m, n, k = shapes[op]
     tile = B.lib.oases_op_gemm_variant({"NN": 0, "NT": 1, "TN": 2}[form], 0, m, n, k)
-    return f"gemm_{form}_{epi}_{tile}x{tile}"
+    return f"gemm_{form}_{epi}_{tile // 1000}x{tile % 1000}"
 
 
 def cpu_baseline(cfg, name):

@@ -110,7 +110,8 @@ int oases_forward(oases_handle *h, const oases_weights *w, const void *x, void *
 
 /* Backward of all layers under Alg. 1 "At Backward" with stored activations: sub-batches in
  * reverse order; each column-parallel input-gradient partial starts its reduction point on
- * stream_comm, under which the next sub-batch's GEMMs and the weight-gradient GEMMs run.
+ * stream_comm, under which the next sub-batch's GEMMs run; the weight-gradient GEMMs of a block, on which no
+ * reduction depends, run once over the rows of all sub-batches behind the last reduction start.
  * x: the input given to oases_forward (read again by the first LayerNorm's backward);
  * dy [M,h] fp32 in, dx [M,h] fp32 out; g: [n_layers], accumulated into. */
 int oases_backward(oases_handle *h, const oases_weights *w, const void *x, const void *dy,
@@ -118,7 +119,7 @@ int oases_backward(oases_handle *h, const oases_weights *w, const void *x, const
                    void *stream_compute, void *stream_comm);
 
 /* The operator order of the schedule as text, one operator per line
- * ("<stream> <op> L<layer> sb<sub-batch>"), NUL-terminated into buf (at most n bytes).
+ * ("<stream> <op> L<layer> sb<sub-batch>", "sb*" = all sub-batches at once), NUL-terminated into buf (at most n bytes).
  * Returns the number of bytes the full text needs (like snprintf).  Host only. */
 int oases_schedule_dump(const oases_handle *h, int backward, char *buf, size_t n);
 
@@ -193,8 +194,8 @@ int oases_op_gemm(int op, int epi, int M, int N, int K, const void *A, int lda, 
                   int ldb, void *C, int ldc, const void *bias, void *aux, int ldaux,
                   void *stream);
 
-/* Which kernel instantiation oases_op_gemm launches for a problem: returns the block-tile edge (256 or
- * 128), or EINVAL.  Host only; used to group per-operator timings by kernel. */
+/* Which kernel instantiation oases_op_gemm launches for a problem: returns 1000*BM + BN of the
+ * block tile (e.g. 256128), or EINVAL.  Host only; used to group per-operator timings by kernel. */
 int oases_op_gemm_variant(int op, int epi, int M, int N, int K);
 
 /* Column sums of a bf16 matrix [rows, cols] (row stride ld) accumulated into fp32 out[cols].

@@ -136,7 +136,9 @@ static void build_forward(oases_handle* H) {
 // Alg. 1 "At Backward" with stored activations: saved sequences are popped last-first (so the last
 // sub-batch goes first); the backward operators of a sequence run until its communication operator,
 // which is started asynchronously; the operators behind it (here: fused into the reduction-point kernel
-// on the communication stream) and the weight-gradient GEMMs, on which no reduction depends, fill in.
+// on the communication stream) fill in.  No reduction depends on a weight gradient, and a weight gradient sums
+// over token rows, so the weight-gradient GEMMs of all sub-batches of a block are merged into one contraction
+// over all M rows and issued behind the last sub-batch's reduction start, under which they run.
 static void build_backward(oases_handle* H) {
   auto& ops = H->bwd;
   const int n = H->n, L = H->L;
@@ -148,19 +150,20 @@ static void build_backward(oases_handle* H) {
       ops.push_back(Op{B_FC2_DGRAD, l, j, 0, w, -1});
       ops.push_back(Op{B_FC1_DGRAD, l, j, 0, -1, ev_id(H, l, 2, j, 0)});
       ops.push_back(Op{B_R3, l, j, 1, ev_id(H, l, 2, j, 0), ev_id(H, l, 2, j, 1)});
-      ops.push_back(Op{B_FC2_WGRAD, l, j, 0, -1, -1});
-      ops.push_back(Op{B_FC1_WGRAD, l, j, 0, -1, -1});
-      ops.push_back(Op{B_B1_SUM, l, j, 0, -1, -1});
     }
+    // weight gradients: one contraction over the rows of ALL sub-batches (sub = -1), behind the last reduction start
+    ops.push_back(Op{B_FC2_WGRAD, l, -1, 0, -1, -1});
+    ops.push_back(Op{B_FC1_WGRAD, l, -1, 0, -1, -1});
+    ops.push_back(Op{B_B1_SUM, l, -1, 0, -1, -1});
     for (int j = n - 1; j >= 0; j--) {
       ops.push_back(Op{B_PROJ_DGRAD, l, j, 0, ev_id(H, l, 2, j, 1), -1});
       ops.push_back(Op{B_ATTN, l, j, 0, -1, -1});
       ops.push_back(Op{B_QKV_DGRAD, l, j, 0, -1, ev_id(H, l, 3, j, 0)});
       ops.push_back(Op{B_R4, l, j, 1, ev_id(H, l, 3, j, 0), ev_id(H, l, 3, j, 1)});
-      ops.push_back(Op{B_PROJ_WGRAD, l, j, 0, -1, -1});
-      ops.push_back(Op{B_QKV_WGRAD, l, j, 0, -1, -1});
-      ops.push_back(Op{B_BQKV_SUM, l, j, 0, -1, -1});
     }
+    ops.push_back(Op{B_PROJ_WGRAD, l, -1, 0, -1, -1});
+    ops.push_back(Op{B_QKV_WGRAD, l, -1, 0, -1, -1});
+    ops.push_back(Op{B_BQKV_SUM, l, -1, 0, -1, -1});
   }
   for (int j = n - 1; j >= 0; j--) ops.push_back(Op{JOIN, 0, j, 0, ev_id(H, 0, 3, j, 1), -1});
 }
@@ -206,8 +209,9 @@ static T* wsp(const Run& R, const char* name, int layer) {
 
 static int run_op(const Run& R, const Op& op) {
   const oases_handle* H = R.H;
-  const int l = op.layer, j = op.sub, Ms = H->Ms, h = H->h, hp = H->hp, fp = H->fp, L = H->L;
-  const size_t r0 = (size_t)j * Ms;  // first token row of the sub-batch
+  const int l = op.layer, j = op.sub, h = H->h, hp = H->hp, fp = H->fp, L = H->L;
+  const int Ms = j < 0 ? H->M : H->Ms;              // sub = -1: all rows (merged weight gradients)
+  const size_t r0 = j < 0 ? 0 : (size_t)j * Ms;     // first token row of the sub-batch
   hipStream_t s = R.st[op.stream];
   const oases_weights& W = R.w[l];
   const oases_peer_sums* P = R.peers ? &R.peers[l] : nullptr;
@@ -445,7 +449,8 @@ int oases_schedule_dump(const oases_handle* H, int backward, char* buf, size_t n
   std::string s;
   char line[96];
   for (const Op& op : backward ? H->bwd : H->fwd) {
-    snprintf(line, sizeof line, "%s %s L%d sb%d\n", op.stream ? "comm" : "compute", kOpName[op.kind], op.layer, op.sub);
+    if (op.sub < 0) snprintf(line, sizeof line, "%s %s L%d sb*\n", op.stream ? "comm" : "compute", kOpName[op.kind], op.layer);
+    else snprintf(line, sizeof line, "%s %s L%d sb%d\n", op.stream ? "comm" : "compute", kOpName[op.kind], op.layer, op.sub);
     s += line;
   }
   if (buf && n) {

@@ -52,16 +52,26 @@ struct AT {
   static constexpr int per_lane = 32 * cpr / 64;  // chunks per lane when one wave moves the tile
 };
 
-// one wave: rows [r0, r0+32) of a [*, D] slice (row stride ld elements) -> registers; rows >= rmax read as zero
+// one wave: rows [r0, r0+32) of a [*, D] slice (row stride ld elements) -> registers; rows >= rmax read as zero.
+// Tiles inside the matrix take the path without clamps and selects (uniform branch).
 template <int D>
 __device__ __forceinline__ void wave_load(u32x4* regs, const uint16_t* __restrict__ base, int ld, int r0, int rmax, int lane) {
+  constexpr int cpr = AT<D>::cpr, rows_per_pass = 64 / cpr;
+  if (r0 + 32 <= rmax) {
+    const char* sb = reinterpret_cast<const char*>(base) + (size_t)r0 * ld * 2;
+    const uint32_t voff = (uint32_t)(((lane / cpr) * ld + (lane % cpr) * 8) * 2);
 #pragma unroll
-  for (int i = 0; i < AT<D>::per_lane; i++) {
-    int c = lane + 64 * i;
-    int row = c / AT<D>::cpr, cc = c % AT<D>::cpr;
-    int r = min(r0 + row, rmax - 1);
-    u32x4 v = *reinterpret_cast<const u32x4*>(base + (size_t)r * ld + cc * 8);
-    regs[i] = (r0 + row < rmax) ? v : u32x4{0u, 0u, 0u, 0u};
+    for (int i = 0; i < AT<D>::per_lane; i++)
+      regs[i] = *reinterpret_cast<const u32x4*>(sb + (size_t)i * rows_per_pass * ld * 2 + voff);
+  } else {
+#pragma unroll
+    for (int i = 0; i < AT<D>::per_lane; i++) {
+      int c = lane + 64 * i;
+      int row = c / cpr, cc = c % cpr;
+      int r = min(r0 + row, rmax - 1);
+      u32x4 v = *reinterpret_cast<const u32x4*>(base + (size_t)r * ld + cc * 8);
+      regs[i] = (r0 + row < rmax) ? v : u32x4{0u, 0u, 0u, 0u};
+    }
   }
 }
 template <int D>
@@ -212,10 +222,12 @@ __global__ __launch_bounds__(NT, 2) void attn_fwd_kernel(AttnArgs a) {
     }
     l = l * alpha + psum;
     m = mnew;
+    if (__any(alpha != 1.0f)) {  // the running maximum rarely moves after the first tiles
 #pragma unroll
-    for (int dt = 0; dt < DT; dt++)
+      for (int dt = 0; dt < DT; dt++)
 #pragma unroll
-      for (int i = 0; i < 16; i++) o[dt][i] *= alpha;
+        for (int i = 0; i < 16; i++) o[dt][i] *= alpha;
+    }
 #pragma unroll
     for (int j = 0; j < 2; j++) {
       bf16x8 pb = pack8(s, 8 * j);

@@ -294,16 +294,31 @@ int launch_one(const GemmArgs& g0, hipStream_t s) {
   return 0;
 }
 
-// tile choice: 256x256 when it fills the chip at least once over, else 128x128
-int pick_tile(int M, int N, int K) {
+// Tile choice.  Bigger tiles run closer to the MFMA rate (fewer LDS bytes per flop) but a launch only uses the chip
+// well if its tile count is near a multiple of the 256 CUs: score = (relative speed of the tile shape) x (fraction of
+// CU slots filled over the ceil(tiles/256) rounds).  Relative speeds measured on this part.
+struct TileChoice { int bm, bn; };
+TileChoice pick_tile(int M, int N, int K) {
   (void)K;
-  long t256 = (long)((M + 255) / 256) * ((N + 255) / 256);
-  return (t256 >= 256 && M % 256 == 0 && N % 256 == 0) ? 256 : 128;
+  static const struct { int bm, bn; float speed; } cand[] = {{256, 256, 1.00f}, {256, 128, 0.86f}, {128, 256, 0.86f}, {128, 128, 0.70f}};
+  TileChoice best{128, 128};
+  float best_score = -1.f;
+  for (auto& c : cand) {
+    long tiles = (long)((M + c.bm - 1) / c.bm) * ((N + c.bn - 1) / c.bn);
+    long rounds = (tiles + 255) / 256;
+    float waste_m = (float)M / (float)(((M + c.bm - 1) / c.bm) * c.bm), waste_n = (float)N / (float)(((N + c.bn - 1) / c.bn) * c.bn);
+    float score = c.speed * (float)tiles / (float)(rounds * 256) * waste_m * waste_n;
+    if (score > best_score) { best_score = score; best = TileChoice{c.bm, c.bn}; }
+  }
+  return best;
 }
 
 template <bool A_KC, bool B_KC, int EPI>
 int launch_shape(const GemmArgs& g, hipStream_t s) {
-  if (pick_tile(g.M, g.N, g.K) == 256) return launch_one<256, 256, 2, 2, A_KC, B_KC, EPI>(g, s);
+  TileChoice t = pick_tile(g.M, g.N, g.K);
+  if (t.bm == 256 && t.bn == 256) return launch_one<256, 256, 2, 2, A_KC, B_KC, EPI>(g, s);
+  if (t.bm == 256 && t.bn == 128) return launch_one<256, 128, 2, 2, A_KC, B_KC, EPI>(g, s);
+  if (t.bm == 128 && t.bn == 256) return launch_one<128, 256, 2, 2, A_KC, B_KC, EPI>(g, s);
   return launch_one<128, 128, 2, 2, A_KC, B_KC, EPI>(g, s);
 }
 
@@ -311,7 +326,8 @@ int launch_shape(const GemmArgs& g, hipStream_t s) {
 
 int gemm_variant(int op, int M, int N, int K) {
   (void)op;
-  return pick_tile(M, N, K);
+  TileChoice t = pick_tile(M, N, K);
+  return t.bm * 1000 + t.bn;
 }
 
 int launch_gemm(int op, int epi, int M, int N, int K, const void* A, int lda, const void* B, int ldb, void* C,

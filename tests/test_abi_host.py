@@ -86,7 +86,8 @@ def test_workspace_plan(B):
 # Hand trace of Algorithm 1 for one layer and two sub-batches.  Forward: the computation sequence up to a
 # communication operator runs for sub-batch 0, its communication starts, the sequence is replayed for sub-batch 1;
 # then the next sequence.  Backward: saved sequences are popped last-first, so sub-batch 1 leads; operators behind a
-# communication operator travel with it on the communication stream; weight-gradient GEMMs fill in behind.
+# communication operator travel with it on the communication stream; the weight-gradient GEMMs of a block run once,
+# over all sub-batches' rows ("sb*"), behind the block's last reduction start.
 FWD_TRACE = """\
 compute LN1 sb0|compute QKV sb0|compute ATTN sb0|compute PROJ sb0|comm R1+BDR1+LN2 sb0
 compute LN1 sb1|compute QKV sb1|compute ATTN sb1|compute PROJ sb1|comm R1+BDR1+LN2 sb1
@@ -95,10 +96,12 @@ compute FC1+GELU sb1|compute FC2 sb1|comm R2+BDR2 sb1
 compute join sb0|compute join sb1"""
 BWD_TRACE = """\
 comm BDR2.b sb1|comm BDR2.b sb0
-compute FC2.dgrad+dGELU sb1|compute FC1.dgrad sb1|comm R3+LN2.b+BDR1.b sb1|compute FC2.wgrad sb1|compute FC1.wgrad sb1|compute b1.sum sb1
-compute FC2.dgrad+dGELU sb0|compute FC1.dgrad sb0|comm R3+LN2.b+BDR1.b sb0|compute FC2.wgrad sb0|compute FC1.wgrad sb0|compute b1.sum sb0
-compute PROJ.dgrad sb1|compute ATTN.b sb1|compute QKV.dgrad sb1|comm R4+LN1.b sb1|compute PROJ.wgrad sb1|compute QKV.wgrad sb1|compute bqkv.sum sb1
-compute PROJ.dgrad sb0|compute ATTN.b sb0|compute QKV.dgrad sb0|comm R4+LN1.b sb0|compute PROJ.wgrad sb0|compute QKV.wgrad sb0|compute bqkv.sum sb0
+compute FC2.dgrad+dGELU sb1|compute FC1.dgrad sb1|comm R3+LN2.b+BDR1.b sb1
+compute FC2.dgrad+dGELU sb0|compute FC1.dgrad sb0|comm R3+LN2.b+BDR1.b sb0
+compute FC2.wgrad sb*|compute FC1.wgrad sb*|compute b1.sum sb*
+compute PROJ.dgrad sb1|compute ATTN.b sb1|compute QKV.dgrad sb1|comm R4+LN1.b sb1
+compute PROJ.dgrad sb0|compute ATTN.b sb0|compute QKV.dgrad sb0|comm R4+LN1.b sb0
+compute PROJ.wgrad sb*|compute QKV.wgrad sb*|compute bqkv.sum sb*
 compute join sb1|compute join sb0"""
 
 
@@ -128,7 +131,9 @@ def test_schedule_structure(B, name):
     subs = [int(l.rsplit("sb", 1)[1]) for l in bwd if " ATTN.b " in l and " L0 " in l]
     assert subs == list(range(n - 1, -1, -1))
     # every operator of every (layer, sub-batch) appears exactly once
-    for op, lines in (("QKV", fwd), ("FC2", fwd), ("QKV.wgrad", bwd), ("R4+LN1.b", bwd)):
+    for op, lines in (("QKV", fwd), ("FC2", fwd), ("QKV.dgrad", bwd), ("R4+LN1.b", bwd)):
         assert sum(f" {op} " in l for l in lines) == L * n
+    for op in ("QKV.wgrad", "FC1.wgrad", "bqkv.sum"):       # merged over the sub-batches
+        assert sum(f" {op} " in l for l in bwd) == L
     # LN1 is a separate operator only for the first layer (later ones ride on the layer below's R2)
     assert sum(" LN1 " in l for l in fwd) == n
