@@ -54,7 +54,7 @@ def op_bytes(line, cfg):
     return float(per_elem.get(op, 0)) * e
 
 
-def gemm_kernel_label(line, cfg, B):
+def gemm_kernel_label(line, cfg, B, ws_bytes):
     """Kernel instantiation a GEMM operator runs on: (contraction form, epilogue, block tile)."""
     M, h, t = cfg["batch"] * cfg["seq"], cfg["hidden"], cfg["tp"]
     Ms, hp, fp = (M if line.endswith("sb*") else M // cfg["n_sub"]), h // t, 4 * h // t
@@ -66,8 +66,9 @@ def gemm_kernel_label(line, cfg, B):
     if op not in shapes:
         return None
     form, epi, m, n, k = shapes[op]
-    tile = B.lib.oases_op_gemm_variant({"NN": 0, "NT": 1, "TN": 2}[form], 0, m, n, k)
-    return f"gemm_{form}_{epi}_{tile // 1000}x{tile % 1000}"
+    tile = B.lib.oases_op_gemm_variant({"NN": 0, "NT": 1, "TN": 2}[form], 0, m, n, k, ws_bytes)
+    split = f"_splitk{tile // 1000000}" if tile >= 2000000 else ""
+    return f"gemm_{form}_{epi}_{tile // 1000 % 1000}x{tile % 1000}{split}"
 
 
 def cpu_baseline(cfg, name):
@@ -157,7 +158,7 @@ def main():
                 for line, ms in HP.profile(bwd):
                     if " join " in line:
                         continue
-                    lab = gemm_kernel_label(line, cfg, B) or line.split()[1]
+                    lab = gemm_kernel_label(line, cfg, B, HP.gemm_workspace_bytes) or line.split()[1]
                     d = acc.setdefault(lab, dict(ms=0.0, launches=0, flops=0.0, bytes=0.0))
                     d["ms"] += ms
                     d["launches"] += 1

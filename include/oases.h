@@ -186,17 +186,23 @@ int oases_op_layernorm_bwd(const void *part, const void *peer, const void *dres,
  * `epi` (NN/NT): OASES_EPI_F32 C fp32; OASES_EPI_BF16 C bf16; OASES_EPI_BIAS_BF16 C = acc+bias (bf16);
  *   OASES_EPI_BIAS_GELU aux = acc+bias (bf16, "pre"), C = GeLU_tanh(acc+bias) (bf16);
  *   OASES_EPI_DGELU C = acc * GeLU_tanh'(aux) (bf16), aux = stored "pre" [M,N] bf16.
- * lda/ldb/ldc are row strides in elements.  M,N,K must be multiples of 8; EINVAL otherwise. */
+ * lda/ldb/ldc are row strides in elements.  M,N,K must be multiples of 8; EINVAL otherwise.
+ * workspace (optional, fp32 scratch of workspace_bytes): lets tile-starved shapes split K -- slices write fp32
+ * partial planes [slices][M][N] that a second kernel adds in slice order before the epilogue (deterministic).
+ * NULL: never split. */
 enum { OASES_GEMM_NN = 0, OASES_GEMM_NT = 1, OASES_GEMM_TN = 2 };
 enum { OASES_EPI_F32 = 0, OASES_EPI_BF16 = 1, OASES_EPI_BIAS_BF16 = 2, OASES_EPI_BIAS_GELU = 3,
        OASES_EPI_DGELU = 4 };
 int oases_op_gemm(int op, int epi, int M, int N, int K, const void *A, int lda, const void *B,
                   int ldb, void *C, int ldc, const void *bias, void *aux, int ldaux,
-                  void *stream);
+                  void *workspace, size_t workspace_bytes, void *stream);
 
-/* Which kernel instantiation oases_op_gemm launches for a problem: returns 1000*BM + BN of the
- * block tile (e.g. 256128), or EINVAL.  Host only; used to group per-operator timings by kernel. */
-int oases_op_gemm_variant(int op, int epi, int M, int N, int K);
+/* Which kernel instantiation oases_op_gemm launches for a problem given workspace_bytes of split-K scratch:
+ * returns 1000000*slices + 1000*BM + BN (e.g. 2256128 = 2 k slices of 256x128 tiles), or EINVAL.
+ * Host only; used to group per-operator timings by kernel. */
+int oases_op_gemm_variant(int op, int epi, int M, int N, int K, size_t workspace_bytes);
+/* Bytes of split-K scratch that oases_forward / oases_backward set aside inside the workspace. */
+size_t oases_gemm_workspace_bytes(const oases_handle *h);
 
 /* Column sums of a bf16 matrix [rows, cols] (row stride ld) accumulated into fp32 out[cols].
  * scratch: fp32 [1024*cols]. */

@@ -62,8 +62,9 @@ _sig("oases_op_layernorm_fwd", _i, _P, _P, _P, _P, _P, _P, _i, _i, _f, _P)
 _sig("oases_op_bias_dropout_residual_ln", _i, _P, _P, _P, _P, _P, _P, _P, _P, _P, _P, _i, _i, _f, _u64, _i, _i, _i64, _f, _P)
 _sig("oases_op_dropout_bwd", _i, _P, _P, _P, _i, _i, _u64, _i, _i, _i64, _f, _P, _P)
 _sig("oases_op_layernorm_bwd", _i, _P, _P, _P, _P, _P, _P, _P, _P, _P, _P, _P, _P, _i, _i, _u64, _i, _i, _i64, _f, _P, _P)
-_sig("oases_op_gemm", _i, _i, _i, _i, _i, _i, _P, _i, _P, _i, _P, _i, _P, _P, _i, _P)
-_sig("oases_op_gemm_variant", _i, _i, _i, _i, _i, _i)
+_sig("oases_op_gemm", _i, _i, _i, _i, _i, _i, _P, _i, _P, _i, _P, _i, _P, _P, _i, _P, _sz, _P)
+_sig("oases_op_gemm_variant", _i, _i, _i, _i, _i, _i, _sz)
+_sig("oases_gemm_workspace_bytes", _sz, _P)
 _sig("oases_op_colsum_bf16", _i, _P, _i, _i, _i, _P, _P, _P)
 _sig("oases_op_attention_fwd", _i, _P, _P, _P, _i, _i, _i, _i, _i, _i, _i, _P)
 _sig("oases_op_attention_bwd", _i, _P, _P, _P, _P, _P, _P, _i, _i, _i, _i, _i, _i, _i, _P)
@@ -120,6 +121,10 @@ class Handle:
     @property
     def workspace_bytes(self) -> int:
         return lib.oases_workspace_bytes(self._h)
+
+    @property
+    def gemm_workspace_bytes(self) -> int:
+        return lib.oases_gemm_workspace_bytes(self._h)
 
     def schedule(self, backward: bool) -> str:
         n = lib.oases_schedule_dump(self._h, int(backward), None, 0)

@@ -29,6 +29,7 @@ struct GemmArgs {
   int M, N, K;
   int lda, ldb, ldc, ldaux;
   int tiles_m, tiles_n;
+  int ksplit, k_per;  // split-K: slice s covers k in [s*k_per, min(K, (s+1)*k_per)) and writes partial s
 };
 
 template <int R, bool KC>
@@ -256,17 +257,18 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, char* lds, int m0, 
 }
 
 template <int BM, int BN, int WGM, int WGN, bool A_KC, bool B_KC, int EPI>
-__global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmArgs g) {
+__global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmArgs g) {  // g: by value, adjusted per k slice
   using LA = TileLayout<BM, A_KC>;
   using LB = TileLayout<BN, B_KC>;
   __shared__ __attribute__((aligned(16))) char lds[2 * (LA::bytes + LB::bytes)];
 
-  // workgroup -> tile: undo the round-robin of workgroup ids over the 8 XCDs so that each XCD's L2 sees a
+  // workgroup -> (k slice, tile): undo the round-robin of workgroup ids over the 8 XCDs so that each XCD's L2 sees a
   // contiguous range of tiles, then walk that range in groups of 8 tile rows.
   int tile_m, tile_n;
+  const int T = g.tiles_m * g.tiles_n;
+  const int slice = blockIdx.x / T;
   {
-    const int T = g.tiles_m * g.tiles_n;
-    int pid = blockIdx.x;
+    int pid = blockIdx.x - slice * T;
     const int per = (T + 7) / 8, tall = (T % 8 == 0) ? 8 : T % 8;
     int xcd = pid & 7, local = pid >> 3;
     int logical = xcd < tall ? xcd * per + local : tall * per + (xcd - tall) * (per - 1) + local;
@@ -277,71 +279,133 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmArgs g) {
     tile_m = first_m + (logical % width) % gsz;
     tile_n = (logical % width) / gsz;
   }
+  if (g.ksplit > 1) {  // this workgroup's k range and partial-result plane
+    const int k0 = slice * g.k_per;
+    g.A += A_KC ? (size_t)k0 : (size_t)k0 * g.lda;
+    g.B += B_KC ? (size_t)k0 : (size_t)k0 * g.ldb;
+    g.K = min(g.K - k0, g.k_per);
+    g.C = reinterpret_cast<float*>(g.C) + (size_t)slice * g.M * g.ldc;
+  }
   const int m0 = tile_m * BM, n0 = tile_n * BN;
   const bool full = (m0 + BM <= g.M) && (n0 + BN <= g.N) && (g.K % BK == 0);
   if (full) gemm_tile<BM, BN, WGM, WGN, A_KC, B_KC, EPI, true>(g, lds, m0, n0);
   else gemm_tile<BM, BN, WGM, WGN, A_KC, B_KC, EPI, false>(g, lds, m0, n0);
 }
 
+// split-K second pass: C = epilogue(sum over slices of the fp32 partial planes), slices added in index order
+template <int EPI>
+__global__ __launch_bounds__(256) void splitk_fixup_kernel(const float* __restrict__ part, int S, GemmArgs g) {
+  const int nc4 = g.N >> 2;
+  const long idx = (long)blockIdx.x * 256 + threadIdx.x;
+  if (idx >= (long)g.M * nc4) return;
+  const int row = (int)(idx / nc4), col = (int)(idx % nc4) * 4;
+  const size_t plane = (size_t)g.M * g.N;
+  f32x4 v = *reinterpret_cast<const f32x4*>(part + (size_t)row * g.N + col);
+  for (int s2 = 1; s2 < S; s2++) v += *reinterpret_cast<const f32x4*>(part + s2 * plane + (size_t)row * g.N + col);
+  const size_t o = (size_t)row * g.ldc + col;
+  if (EPI == EPI_F32) {
+    *reinterpret_cast<f32x4*>(reinterpret_cast<float*>(g.C) + o) = v;
+  } else if (EPI == EPI_ACC_F32) {
+    f32x4* p = reinterpret_cast<f32x4*>(reinterpret_cast<float*>(g.C) + o);
+    *p = *p + v;
+  } else {
+    uint16_t* cp = reinterpret_cast<uint16_t*>(g.C) + o;
+    if (EPI == EPI_BIAS_BF16 || EPI == EPI_BIAS_GELU) v += *reinterpret_cast<const f32x4*>(g.bias + col);
+    if (EPI == EPI_BIAS_GELU) {
+      *reinterpret_cast<u32x2*>(g.aux + (size_t)row * g.ldaux + col) = u32x2{pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3])};
+#pragma unroll
+      for (int e = 0; e < 4; e++) v[e] = gelu_tanh(v[e]);
+    } else if (EPI == EPI_DGELU) {
+      u32x2 a = *reinterpret_cast<const u32x2*>(g.aux + (size_t)row * g.ldaux + col);
+      v[0] *= gelu_tanh_grad(bf16_bits_to_f32(a[0] & 0xffffu));
+      v[1] *= gelu_tanh_grad(bf16_bits_to_f32(a[0] >> 16));
+      v[2] *= gelu_tanh_grad(bf16_bits_to_f32(a[1] & 0xffffu));
+      v[3] *= gelu_tanh_grad(bf16_bits_to_f32(a[1] >> 16));
+    }
+    *reinterpret_cast<u32x2*>(cp) = u32x2{pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3])};
+  }
+}
+
 template <int BM, int BN, int WGM, int WGN, bool A_KC, bool B_KC, int EPI>
-int launch_one(const GemmArgs& g0, hipStream_t s) {
+int launch_one(const GemmArgs& g0, int ksplit, float* ws, hipStream_t s) {
   GemmArgs g = g0;
   g.tiles_m = (g.M + BM - 1) / BM;
   g.tiles_n = (g.N + BN - 1) / BN;
-  dim3 grid(g.tiles_m * g.tiles_n), block(64 * WGM * WGN);
-  hipLaunchKernelGGL((gemm_kernel<BM, BN, WGM, WGN, A_KC, B_KC, EPI>), grid, block, 0, s, g);
-  OASES_LAUNCH_CHECK("gemm_kernel");
+  g.ksplit = 1;
+  g.k_per = g.K;
+  dim3 block(64 * WGM * WGN);
+  if (ksplit <= 1) {
+    hipLaunchKernelGGL((gemm_kernel<BM, BN, WGM, WGN, A_KC, B_KC, EPI>), dim3(g.tiles_m * g.tiles_n), block, 0, s, g);
+    OASES_LAUNCH_CHECK("gemm_kernel");
+    return 0;
+  }
+  // first pass: fp32 partial planes [ksplit][M][N] in the workspace; second pass: sum + the real epilogue
+  GemmArgs p = g;
+  p.ksplit = ksplit;
+  p.k_per = ((g.K + ksplit - 1) / ksplit + BK - 1) / BK * BK;
+  p.C = ws;
+  p.ldc = g.N;
+  hipLaunchKernelGGL((gemm_kernel<BM, BN, WGM, WGN, A_KC, B_KC, EPI_F32>), dim3(g.tiles_m * g.tiles_n * ksplit), block, 0, s, p);
+  OASES_LAUNCH_CHECK("gemm_kernel (split-K)");
+  const long n4 = (long)g.M * (g.N / 4);
+  hipLaunchKernelGGL((splitk_fixup_kernel<EPI>), dim3((unsigned)((n4 + 255) / 256)), dim3(256), 0, s, ws, ksplit, g);
+  OASES_LAUNCH_CHECK("splitk_fixup_kernel");
   return 0;
 }
 
-// Tile choice.  Bigger tiles run closer to the MFMA rate (fewer LDS bytes per flop) but a launch only uses the chip
-// well if its tile count is near a multiple of the 256 CUs: score = (relative speed of the tile shape) x (fraction of
-// CU slots filled over the ceil(tiles/256) rounds).  Relative speeds measured on this part.
-struct TileChoice { int bm, bn; };
-TileChoice pick_tile(int M, int N, int K) {
-  (void)K;
-  static const struct { int bm, bn; float speed; } cand[] = {{256, 256, 1.00f}, {256, 128, 0.86f}, {128, 256, 0.86f}, {128, 128, 0.70f}};
-  TileChoice best{128, 128};
-  float best_score = -1.f;
+// Tile and split-K choice by a small time model.  Bigger tiles run closer to the MFMA rate (fewer LDS bytes per flop)
+// but a launch only uses the chip well if its workgroup count is near a multiple of the 256 CUs; splitting K multiplies
+// the workgroup count at the price of a second pass over fp32 partial planes.  Rates measured on this part.
+struct TileChoice { int bm, bn, ksplit; };
+TileChoice pick_tile(int M, int N, int K, size_t ws_bytes) {
+  static const struct { int bm, bn; float tflops; } cand[] = {{256, 256, 1050.f}, {256, 128, 900.f}, {128, 256, 900.f}, {128, 128, 740.f}};
+  TileChoice best{128, 128, 1};
+  double best_t = 1e30;
   for (auto& c : cand) {
-    long tiles = (long)((M + c.bm - 1) / c.bm) * ((N + c.bn - 1) / c.bn);
-    long rounds = (tiles + 255) / 256;
-    float waste_m = (float)M / (float)(((M + c.bm - 1) / c.bm) * c.bm), waste_n = (float)N / (float)(((N + c.bn - 1) / c.bn) * c.bn);
-    float score = c.speed * (float)tiles / (float)(rounds * 256) * waste_m * waste_n;
-    if (score > best_score) { best_score = score; best = TileChoice{c.bm, c.bn}; }
+    const long tm = (M + c.bm - 1) / c.bm, tn = (N + c.bn - 1) / c.bn;
+    for (int S = 1; S <= 8; S *= 2) {
+      if (S > 1 && ((size_t)S * M * N * 4 > ws_bytes || K / S < 512)) break;
+      const long wgs = tm * tn * S, rounds = (wgs + 255) / 256;
+      // time of one workgroup's tile slice at the tile's rate (one workgroup per CU), times the number of rounds
+      double t = (double)rounds * (2.0 * c.bm * c.bn * ((double)K / S) + 3.0e6) / (c.tflops * 1e12 / 256.0);
+      if (S > 1) t += ((double)(2 * S + 1) * M * N * 4.0) / 3.0e12 + 4e-6;
+      if (t < best_t) { best_t = t; best = TileChoice{c.bm, c.bn, S}; }
+    }
   }
   return best;
 }
 
 template <bool A_KC, bool B_KC, int EPI>
-int launch_shape(const GemmArgs& g, hipStream_t s) {
-  TileChoice t = pick_tile(g.M, g.N, g.K);
-  if (t.bm == 256 && t.bn == 256) return launch_one<256, 256, 2, 2, A_KC, B_KC, EPI>(g, s);
-  if (t.bm == 256 && t.bn == 128) return launch_one<256, 128, 2, 2, A_KC, B_KC, EPI>(g, s);
-  if (t.bm == 128 && t.bn == 256) return launch_one<128, 256, 2, 2, A_KC, B_KC, EPI>(g, s);
-  return launch_one<128, 128, 2, 2, A_KC, B_KC, EPI>(g, s);
+int launch_shape(const GemmArgs& g, float* ws, size_t ws_bytes, hipStream_t s) {
+  TileChoice t = pick_tile(g.M, g.N, g.K, ws ? ws_bytes : 0);
+  if (t.bm == 256 && t.bn == 256) return launch_one<256, 256, 2, 2, A_KC, B_KC, EPI>(g, t.ksplit, ws, s);
+  if (t.bm == 256 && t.bn == 128) return launch_one<256, 128, 2, 2, A_KC, B_KC, EPI>(g, t.ksplit, ws, s);
+  if (t.bm == 128 && t.bn == 256) return launch_one<128, 256, 2, 2, A_KC, B_KC, EPI>(g, t.ksplit, ws, s);
+  return launch_one<128, 128, 2, 2, A_KC, B_KC, EPI>(g, t.ksplit, ws, s);
 }
 
 }  // namespace
 
-int gemm_variant(int op, int M, int N, int K) {
+int gemm_variant(int op, int M, int N, int K, size_t ws_bytes) {
   (void)op;
-  TileChoice t = pick_tile(M, N, K);
-  return t.bm * 1000 + t.bn;
+  TileChoice t = pick_tile(M, N, K, ws_bytes);
+  return t.ksplit * 1000000 + t.bm * 1000 + t.bn;
 }
 
 int launch_gemm(int op, int epi, int M, int N, int K, const void* A, int lda, const void* B, int ldb, void* C,
-                int ldc, const float* bias, void* aux, int ldaux, hipStream_t s) {
+                int ldc, const float* bias, void* aux, int ldaux, void* splitk_ws, size_t splitk_ws_bytes, hipStream_t s) {
+  float* ws = reinterpret_cast<float*>(splitk_ws);
+  const size_t wsb = splitk_ws_bytes;
   if (M <= 0 || N <= 0 || K <= 0 || (M % 8) || (N % 8) || (K % 8) || (lda % 8) || (ldb % 8) || (ldc % 4) || (aux && ldaux % 4)) {
     set_error("gemm: M,N,K,lda,ldb must be positive multiples of 8, ldc/ldaux of 4 (got M=%d N=%d K=%d lda=%d ldb=%d ldc=%d)", M, N, K, lda, ldb, ldc);
     return OASES_EINVAL;
   }
   if (!A || !B || !C) { set_error("gemm: NULL operand"); return OASES_ENULL; }
   if (!aligned16(A) || !aligned16(B) || !aligned16(C) || !aligned16(bias) || !aligned16(aux)) { set_error("gemm: operand not 16-byte aligned"); return OASES_EALIGN; }
-  GemmArgs g{(const uint16_t*)A, (const uint16_t*)B, C, bias, (uint16_t*)aux, M, N, K, lda, ldb, ldc, ldaux, 0, 0};
+  GemmArgs g{(const uint16_t*)A, (const uint16_t*)B, C, bias, (uint16_t*)aux, M, N, K, lda, ldb, ldc, ldaux, 0, 0, 1, K};
   if (op == OASES_GEMM_TN) {
     if (lda < M || ldb < N || ldc < N) { set_error("gemm TN: leading dimension too small"); return OASES_EINVAL; }
-    return launch_shape<false, false, EPI_ACC_F32>(g, s);
+    return launch_shape<false, false, EPI_ACC_F32>(g, ws, wsb, s);
   }
   const bool nn = op == OASES_GEMM_NN;
   if (!nn && op != OASES_GEMM_NT) { set_error("gemm: unknown op %d", op); return OASES_EINVAL; }
@@ -350,7 +414,7 @@ int launch_gemm(int op, int epi, int M, int N, int K, const void* A, int lda, co
   if ((epi == OASES_EPI_BIAS_GELU || epi == OASES_EPI_DGELU) && (!aux || ldaux < N)) { set_error("gemm: GeLU epilogue without aux"); return OASES_ENULL; }
 #define OASES_GEMM_CASE(E)                                                   \
   case E:                                                                    \
-    return nn ? launch_shape<true, false, E>(g, s) : launch_shape<true, true, E>(g, s);
+    return nn ? launch_shape<true, false, E>(g, ws, wsb, s) : launch_shape<true, true, E>(g, ws, wsb, s);
   switch (epi) {
     OASES_GEMM_CASE(EPI_F32)
     OASES_GEMM_CASE(EPI_BF16)

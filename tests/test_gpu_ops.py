@@ -161,15 +161,15 @@ def test_gemm_plain(B, M, N, K, op):
     if op == "NN":
         ad, bd = dev(a, torch.bfloat16), dev(b, torch.bfloat16)
         c = torch.empty(M, N, dtype=torch.float32, device="cuda")
-        B.check(B.lib.oases_op_gemm(B.GEMM_NN, B.EPI_F32, M, N, K, ad.data_ptr(), K, bd.data_ptr(), N, c.data_ptr(), N, None, None, 0, None))
+        B.check(B.lib.oases_op_gemm(B.GEMM_NN, B.EPI_F32, M, N, K, ad.data_ptr(), K, bd.data_ptr(), N, c.data_ptr(), N, None, None, 0, None, 0, None))
     elif op == "NT":
         ad, bd = dev(a, torch.bfloat16), dev(b.t().contiguous(), torch.bfloat16)
         c = torch.empty(M, N, dtype=torch.float32, device="cuda")
-        B.check(B.lib.oases_op_gemm(B.GEMM_NT, B.EPI_F32, M, N, K, ad.data_ptr(), K, bd.data_ptr(), K, c.data_ptr(), N, None, None, 0, None))
+        B.check(B.lib.oases_op_gemm(B.GEMM_NT, B.EPI_F32, M, N, K, ad.data_ptr(), K, bd.data_ptr(), K, c.data_ptr(), N, None, None, 0, None, 0, None))
     else:
         ad, bd = dev(a.t().contiguous(), torch.bfloat16), dev(b, torch.bfloat16)
         c = torch.full((M, N), 0.5, dtype=torch.float32, device="cuda")         # accumulated into
-        B.check(B.lib.oases_op_gemm(B.GEMM_TN, 0, M, N, K, ad.data_ptr(), M, bd.data_ptr(), N, c.data_ptr(), N, None, None, 0, None))
+        B.check(B.lib.oases_op_gemm(B.GEMM_TN, 0, M, N, K, ad.data_ptr(), M, bd.data_ptr(), N, c.data_ptr(), N, None, None, 0, None, 0, None))
         ref = ref + 0.5
     assert rel_err(c, ref) < 1e-5, (op, M, N, K)     # exact products of bf16 values, fp32 accumulation
 
@@ -185,7 +185,7 @@ def test_gemm_epilogues(B, lo, M, N, K):
     c = torch.empty(M, N, dtype=torch.bfloat16, device="cuda")
     aux = torch.empty(M, N, dtype=torch.bfloat16, device="cuda")
     run = lambda epi, auxp: B.check(B.lib.oases_op_gemm(B.GEMM_NN, epi, M, N, K, ad.data_ptr(), K, bd.data_ptr(), N, c.data_ptr(), N,
-                                                        biasd.data_ptr(), auxp, N, None))
+                                                        biasd.data_ptr(), auxp, N, None, 0, None))
     run(B.EPI_BF16, None)
     assert_bf16_close(c.float(), acc, 1e-5, 2e-6 * float(acc.abs().max()))
     run(B.EPI_BIAS_BF16, None)
@@ -195,8 +195,56 @@ def test_gemm_epilogues(B, lo, M, N, K):
     assert_bf16_close(c.float(), lo.gelu_fwd(acc + bias), 1e-4, 1e-5, 'gelu')
     # dGeLU epilogue on the input-gradient form: C = (A B^T) * gelu'(aux)
     bt = dev(b.t().contiguous(), torch.bfloat16)
-    B.check(B.lib.oases_op_gemm(B.GEMM_NT, B.EPI_DGELU, M, N, K, ad.data_ptr(), K, bt.data_ptr(), K, c.data_ptr(), N, None, aux.data_ptr(), N, None))
+    B.check(B.lib.oases_op_gemm(B.GEMM_NT, B.EPI_DGELU, M, N, K, ad.data_ptr(), K, bt.data_ptr(), K, c.data_ptr(), N, None, aux.data_ptr(), N, None, 0, None))
     assert_bf16_close(c.float(), acc * lo.gelu_grad(aux.cpu().double()), 1e-4, 1e-5, 'dgelu')
+
+
+@pytest.mark.parametrize("op,epi,M,N,K", [("NT", "bf16", 1024, 1024, 8192), ("TN", "acc", 512, 4096, 8192), ("NN", "bias_gelu", 512, 1024, 8192),
+                                          ("NT", "dgelu", 520, 264, 4104), ("NN", "f32", 256, 512, 2048)])
+def test_gemm_split_k(B, lo, op, epi, M, N, K):
+    """Tile-starved shapes with a workspace: K is split into slices whose fp32 partial planes are added in slice order."""
+    g = gen(11)
+    a, b = bf16_round(randn(g, M, K)), bf16_round(randn(g, K, N, scale=0.05))
+    bias = dev(0.1 * randn(g, N), torch.float32)
+    pre = dev(bf16_round(randn(g, M, N)), torch.bfloat16)
+    ws = torch.full((64 << 20,), 0xFF, dtype=torch.uint8, device="cuda")
+    opc = {"NN": B.GEMM_NN, "NT": B.GEMM_NT, "TN": B.GEMM_TN}[op]
+    variant = B.lib.oases_op_gemm_variant(opc, 0, M, N, K, ws.numel())
+    assert variant >= 2000000, f"shape was expected to split K, got {variant}"
+    ad = dev(a if op != "TN" else a.t().contiguous(), torch.bfloat16)
+    bd = dev(b if op != "NT" else b.t().contiguous(), torch.bfloat16)
+    lda = K if op != "TN" else M
+    ldb = N if op != "NT" else K
+    acc = a @ b
+    res = []
+    for wsp, wsb in ((ws.data_ptr(), ws.numel()), (None, 0)):
+        if epi == "acc":
+            c = torch.full((M, N), 0.25, dtype=torch.float32, device="cuda")
+            B.check(B.lib.oases_op_gemm(opc, 0, M, N, K, ad.data_ptr(), lda, bd.data_ptr(), ldb, c.data_ptr(), N, None, None, 0, wsp, wsb, None))
+            assert rel_err(c, acc + 0.25) < 1e-5
+        elif epi == "f32":
+            c = torch.empty(M, N, dtype=torch.float32, device="cuda")
+            B.check(B.lib.oases_op_gemm(opc, B.EPI_F32, M, N, K, ad.data_ptr(), lda, bd.data_ptr(), ldb, c.data_ptr(), N, None, None, 0, wsp, wsb, None))
+            assert rel_err(c, acc) < 1e-5
+        elif epi == "bf16":
+            c = torch.empty(M, N, dtype=torch.bfloat16, device="cuda")
+            B.check(B.lib.oases_op_gemm(opc, B.EPI_BF16, M, N, K, ad.data_ptr(), lda, bd.data_ptr(), ldb, c.data_ptr(), N, None, None, 0, wsp, wsb, None))
+            assert_bf16_close(c.float(), acc, 1e-5, 2e-6 * float(acc.abs().max()))
+        elif epi == "bias_gelu":
+            c = torch.empty(M, N, dtype=torch.bfloat16, device="cuda")
+            aux = torch.empty(M, N, dtype=torch.bfloat16, device="cuda")
+            B.check(B.lib.oases_op_gemm(opc, B.EPI_BIAS_GELU, M, N, K, ad.data_ptr(), lda, bd.data_ptr(), ldb, c.data_ptr(), N, bias.data_ptr(),
+                                        aux.data_ptr(), N, wsp, wsb, None))
+            z = acc + bias.cpu().double()
+            assert_bf16_close(aux.float(), z, 1e-5, 2e-6 * float(z.abs().max()))
+            assert_bf16_close(c.float(), lo.gelu_fwd(z), 1e-4, 1e-5)
+        else:
+            c = torch.empty(M, N, dtype=torch.bfloat16, device="cuda")
+            B.check(B.lib.oases_op_gemm(opc, B.EPI_DGELU, M, N, K, ad.data_ptr(), lda, bd.data_ptr(), ldb, c.data_ptr(), N, None, pre.data_ptr(), N,
+                                        wsp, wsb, None))
+            assert_bf16_close(c.float(), acc * lo.gelu_grad(pre.float().cpu().double()), 1e-4, 1e-5)
+        res.append(c.float().cpu())
+    assert rel_err(res[0], res[1]) < 3e-2       # split and unsplit agree up to the accumulation order (and one bf16 ulp)
 
 
 def test_gemm_strided_views(B):
@@ -206,7 +254,7 @@ def test_gemm_strided_views(B):
     a, b = bf16_round(randn(g, M, lda)), bf16_round(randn(g, K, ldb))
     ad, bd = dev(a, torch.bfloat16), dev(b, torch.bfloat16)
     c = torch.zeros(M, ldc, dtype=torch.float32, device="cuda")
-    B.check(B.lib.oases_op_gemm(B.GEMM_NN, B.EPI_F32, M, N, K, ad.data_ptr(), lda, bd.data_ptr(), ldb, c.data_ptr(), ldc, None, None, 0, None))
+    B.check(B.lib.oases_op_gemm(B.GEMM_NN, B.EPI_F32, M, N, K, ad.data_ptr(), lda, bd.data_ptr(), ldb, c.data_ptr(), ldc, None, None, 0, None, 0, None))
     assert rel_err(c[:, :N], a[:, :K] @ b[:, :N]) < 1e-5
     assert float(c[:, N:].abs().max()) == 0.0
 
@@ -214,10 +262,10 @@ def test_gemm_strided_views(B):
 def test_gemm_argument_errors(B):
     t = torch.zeros(64, 64, dtype=torch.bfloat16, device="cuda")
     c = torch.zeros(64, 64, dtype=torch.float32, device="cuda")
-    assert B.lib.oases_op_gemm(B.GEMM_NN, B.EPI_F32, 60, 64, 64, t.data_ptr(), 64, t.data_ptr(), 64, c.data_ptr(), 64, None, None, 0, None) == B.EINVAL
-    assert B.lib.oases_op_gemm(B.GEMM_NN, B.EPI_F32, 64, 64, 64, None, 64, t.data_ptr(), 64, c.data_ptr(), 64, None, None, 0, None) == B.ENULL
-    assert B.lib.oases_op_gemm(B.GEMM_NN, B.EPI_F32, 64, 64, 64, t.data_ptr() + 2, 64, t.data_ptr(), 64, c.data_ptr(), 64, None, None, 0, None) == B.EALIGN
-    assert B.lib.oases_op_gemm(B.GEMM_NN, B.EPI_BIAS_BF16, 64, 64, 64, t.data_ptr(), 64, t.data_ptr(), 64, c.data_ptr(), 64, None, None, 0, None) == B.ENULL
+    assert B.lib.oases_op_gemm(B.GEMM_NN, B.EPI_F32, 60, 64, 64, t.data_ptr(), 64, t.data_ptr(), 64, c.data_ptr(), 64, None, None, 0, None, 0, None) == B.EINVAL
+    assert B.lib.oases_op_gemm(B.GEMM_NN, B.EPI_F32, 64, 64, 64, None, 64, t.data_ptr(), 64, c.data_ptr(), 64, None, None, 0, None, 0, None) == B.ENULL
+    assert B.lib.oases_op_gemm(B.GEMM_NN, B.EPI_F32, 64, 64, 64, t.data_ptr() + 2, 64, t.data_ptr(), 64, c.data_ptr(), 64, None, None, 0, None, 0, None) == B.EALIGN
+    assert B.lib.oases_op_gemm(B.GEMM_NN, B.EPI_BIAS_BF16, 64, 64, 64, t.data_ptr(), 64, t.data_ptr(), 64, c.data_ptr(), 64, None, None, 0, None, 0, None) == B.ENULL
     assert b"bias" in B.lib.oases_last_error()
 
 
