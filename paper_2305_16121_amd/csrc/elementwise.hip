@@ -17,16 +17,19 @@ __device__ __forceinline__ float wave_sum(float v) {
   return v;
 }
 
-// sum over the 256 threads of the workgroup, result in every thread; red: 2 x 4 floats of LDS
+// sum over the NW*64 threads of the workgroup, result in every thread; red: 2 x NW floats of LDS
+template <int NW = 4>
 __device__ __forceinline__ void block_sum2(float& a, float& b, float* red) {
   a = wave_sum(a);
   b = wave_sum(b);
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
   __syncthreads();  // red may still be read by the previous use
-  if (lane == 0) { red[w] = a; red[4 + w] = b; }
+  if (lane == 0) { red[w] = a; red[NW + w] = b; }
   __syncthreads();
-  a = red[0] + red[1] + red[2] + red[3];
-  b = red[4] + red[5] + red[6] + red[7];
+  a = 0.f;
+  b = 0.f;
+#pragma unroll
+  for (int i = 0; i < NW; i++) { a += red[i]; b += red[NW + i]; }
 }
 
 __device__ __forceinline__ void store_bf16x4(uint16_t* p, float a, float b, float c, float d) {
@@ -111,7 +114,7 @@ __global__ __launch_bounds__(NT) void bdr_ln_kernel(const float* __restrict__ pa
 
 // ------------------------------------------------------------------------------------------------
 // dz = keep * dyin * scale (bf16); partial column sums of the unrounded dz into scratch[group][h]
-template <int NC>
+template <int NC, int NT>
 __global__ __launch_bounds__(NT) void dropout_bwd_kernel(const float* __restrict__ dyin, uint16_t* __restrict__ dz,
                                                          float* __restrict__ scratch, int rows, int h, DropCfg d,
                                                          int64_t row0) {
@@ -183,14 +186,14 @@ __global__ __launch_bounds__(NT) void colsum_finalize_kernel(const float* __rest
 // ------------------------------------------------------------------------------------------------
 // g = part + peer;  dxo = dres + rstd * (g*gamma - mean(g*gamma) - xhat * mean(g*gamma*xhat))
 // partials: scratch[0] dgamma = sum g*xhat, scratch[1] dbeta = sum g, scratch[2] dbias = sum dz
-template <int NC>
+template <int NC, int NT>
 __global__ __launch_bounds__(NT) void layernorm_bwd_kernel(const float* __restrict__ part, const float* __restrict__ peer,
                                                            const float* __restrict__ dres, const float* __restrict__ x,
                                                            const float* __restrict__ mu, const float* __restrict__ rstd,
                                                            const float* __restrict__ gamma, float* __restrict__ dxo,
                                                            uint16_t* __restrict__ dz, float* __restrict__ scratch, int rows,
                                                            int h, DropCfg d, int64_t row0) {
-  __shared__ float red[8];
+  __shared__ float red[2 * (NT / 64)];
   const int tid = threadIdx.x, nc = h >> 2;
   const size_t gstride = (size_t)gridDim.x * h;
   f32x4 ag[NC], ab[NC], az[NC];
@@ -222,7 +225,7 @@ __global__ __launch_bounds__(NT) void layernorm_bwd_kernel(const float* __restri
         }
       }
     }
-    block_sum2(s1, s2, red);
+    block_sum2<NT / 64>(s1, s2, red);
     const float m1 = s1 / h, m2 = s2 / h;
 #pragma unroll
     for (int i = 0; i < NC; i++) {
@@ -275,9 +278,11 @@ __global__ __launch_bounds__(NT) void colsum_bf16_kernel(const uint16_t* __restr
   *reinterpret_cast<f32x4*>(p + 4) = f32x4{acc[4], acc[5], acc[6], acc[7]};
 }
 
-// row groups of a two-stage column reduction: about four rows per group, at most kColPartials groups
+// row groups of a two-stage column reduction: about eight rows per group (few partial rows to add up), but at
+// least one group per CU when the rows allow it, at most kColPartials groups
 int col_groups(int rows) {
-  int g = rows / 4;
+  int g = rows / 8;
+  if (g < 256) g = rows / 2 < 256 ? rows / 2 : 256;
   return g < 1 ? 1 : (g > kColPartials ? kColPartials : g);
 }
 
@@ -295,6 +300,24 @@ bool check_h(int rows, int h, const char* who) {
   }
   return true;
 }
+
+// backward kernels: 1024-thread workgroups for wide rows (more bytes in flight per row, fewer registers per thread)
+#define OASES_BWD_DISPATCH(H, ...)                                                   \
+  if ((H) >= 4096) {                                                                 \
+    constexpr int NTHR = 1024;                                                       \
+    switch (((H) / 4 + NTHR - 1) / NTHR) {                                           \
+      case 1: { constexpr int NC = 1; __VA_ARGS__; break; }                          \
+      case 2: { constexpr int NC = 2; __VA_ARGS__; break; }                          \
+      default: { constexpr int NC = 4; __VA_ARGS__; break; }                         \
+    }                                                                                \
+  } else {                                                                           \
+    constexpr int NTHR = 256;                                                        \
+    switch (pick_nc(H)) {                                                            \
+      case 1: { constexpr int NC = 1; __VA_ARGS__; break; }                          \
+      case 2: { constexpr int NC = 2; __VA_ARGS__; break; }                          \
+      default: { constexpr int NC = 4; __VA_ARGS__; break; }                         \
+    }                                                                                \
+  }
 
 #define OASES_NC_DISPATCH(NCV, ...)          \
   switch (NCV) {                             \
@@ -362,8 +385,8 @@ int launch_dropout_bwd(const float* dyin, void* dz, float* dbias, int rows, int 
   if (!check_h(rows, h, "dropout_bwd")) return OASES_EINVAL;
   if (!dyin || !dz || (dbias && !scratch)) { set_error("dropout_bwd: NULL argument"); return OASES_ENULL; }
   const int groups = col_groups(rows);
-  OASES_NC_DISPATCH(pick_nc(h), hipLaunchKernelGGL(dropout_bwd_kernel<NC>, dim3(groups), dim3(NT), 0, s, dyin, (uint16_t*)dz,
-                                                   dbias ? scratch : nullptr, rows, h, d, row0));
+  OASES_BWD_DISPATCH(h, hipLaunchKernelGGL((dropout_bwd_kernel<NC, NTHR>), dim3(groups), dim3(NTHR), 0, s, dyin, (uint16_t*)dz,
+                                           dbias ? scratch : nullptr, rows, h, d, row0));
   OASES_LAUNCH_CHECK("dropout_bwd_kernel");
   if (dbias) return finalize(scratch, dbias, nullptr, nullptr, 1, groups, h, s);
   return 0;
@@ -378,8 +401,8 @@ int launch_layernorm_bwd(const float* part, const float* peer, const float* dres
     return OASES_ENULL;
   }
   const int groups = col_groups(rows);
-  OASES_NC_DISPATCH(pick_nc(h), hipLaunchKernelGGL(layernorm_bwd_kernel<NC>, dim3(groups), dim3(NT), 0, s, part, peer, dres, x, mu,
-                                                   rstd, gamma, dxo, (uint16_t*)dz, scratch, rows, h, d, row0));
+  OASES_BWD_DISPATCH(h, hipLaunchKernelGGL((layernorm_bwd_kernel<NC, NTHR>), dim3(groups), dim3(NTHR), 0, s, part, peer, dres, x, mu,
+                                           rstd, gamma, dxo, (uint16_t*)dz, scratch, rows, h, d, row0));
   OASES_LAUNCH_CHECK("layernorm_bwd_kernel");
   return finalize(scratch, dgamma, dbeta, dz ? dbias : nullptr, dz ? 3 : 2, groups, h, s);
 }
