@@ -96,6 +96,8 @@ def main():
     ap.add_argument("--serialise", action="store_true", help="single stream")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-profile", action="store_true")
+    ap.add_argument("--calib-copy", action="store_true",
+                    help="run one plain elementwise kernel of known size (reads and writes 256 MiB) first: the unit check for rocprofv3 byte counters")
     a = ap.parse_args()
     if a.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (no collectives, no sharding across GPUs); use --gpus 1")
@@ -125,6 +127,11 @@ def main():
         handle.forward(W, xd, yd, ws, s_compute=s1, s_comm=s2)
         handle.backward(W, xd, dyd, dxd, G, ws, s_compute=s1, s_comm=s2)
 
+    if a.calib_copy:
+        src = torch.ones(64 << 20, dtype=torch.float32, device="cuda")
+        dst = src * 2.0          # one elementwise kernel: 256 MiB read, 256 MiB written
+        torch.cuda.synchronize()
+        del src, dst
     for _ in range(a.warmup):
         step(H)
     torch.cuda.synchronize()
@@ -179,8 +186,12 @@ def main():
         out["config"]["serialised_sum_ms"] = round(sum(r["ms_per_step"] for r in table), 4)
         dom = next(r for r in table if r["kernel"].startswith("gemm_"))
         d = acc[dom["kernel"]]
+        traffic = None     # HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs, stored under profiles/
+        tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+        if os.path.exists(tpath):
+            traffic = json.load(open(tpath)).get(a.config, {}).get(dom["kernel"])
         out["roofline"] = {"kernel": dom["kernel"], "bound": "mfma", "achieved": dom["tflops"], "peak": PEAK_BF16_TFLOPS,
-                           "unit": "TFLOP/s", "frac": round(dom["tflops"] / PEAK_BF16_TFLOPS, 4), "traffic": None,
+                           "unit": "TFLOP/s", "frac": round(dom["tflops"] / PEAK_BF16_TFLOPS, 4), "traffic": traffic,
                            "avg_launch_ms": dom["avg_ms"], "flops_per_launch": d["flops"] / d["launches"]}
         HP.close()
 
