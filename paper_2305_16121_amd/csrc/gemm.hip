@@ -138,14 +138,10 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, char* lds, int m0, 
   bf16x8 fa[2][TM], fb[2][TN];
   const int nk = (g.K + BK - 1) / BK;
 
-  auto fetch = [&](int kt) {
-    load_tile_global<BM, A_KC, NT, FULL>(ra, g.A, g.lda, m0, kt * BK, g.M, g.K, tid);
-    load_tile_global<BN, B_KC, NT, FULL>(rb, g.B, g.ldb, n0, kt * BK, g.N, g.K, tid);
-  };
-  auto park = [&](int stage) {
-    store_tile_lds<BM, A_KC, NT>(ra, lds + stage * kStage, tid);
-    store_tile_lds<BN, B_KC, NT>(rb, lds + stage * kStage + LA::bytes, tid);
-  };
+  auto fetch_a = [&](int kt) { load_tile_global<BM, A_KC, NT, FULL>(ra, g.A, g.lda, m0, kt * BK, g.M, g.K, tid); };
+  auto fetch_b = [&](int kt) { load_tile_global<BN, B_KC, NT, FULL>(rb, g.B, g.ldb, n0, kt * BK, g.N, g.K, tid); };
+  auto park_a = [&](int stage) { store_tile_lds<BM, A_KC, NT>(ra, lds + stage * kStage, tid); };
+  auto park_b = [&](int stage) { store_tile_lds<BN, B_KC, NT>(rb, lds + stage * kStage + LA::bytes, tid); };
   auto frags = [&](int stage, int kk, int buf) {
     const char* la = lds + stage * kStage;
     const char* lb = la + LA::bytes;
@@ -173,48 +169,107 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, char* lds, int m0, 
     }
   };
 
-  fetch(0);
-  park(0);
-  if (nk > 1) fetch(1);
-  __syncthreads();
-  frags(0, 0, 0);
-
-  // one 64-wide k iteration; MORE: tile kt+1 exists (it sits in registers), MORE2: tile kt+2 exists.
-  // The steady state (both true) is branch-free so that the scheduler sees one block per iteration.
-  auto iteration = [&](auto more_c, auto more2_c, int kt) {
-    constexpr bool MORE = decltype(more_c)::value, MORE2 = decltype(more2_c)::value;
-    const int cur = kt & 1;
-    if (MORE) park(cur ^ 1);        // tile kt+1: registers -> the other stage
-    if (MORE2) fetch(kt + 2);       // tile kt+2: global -> the same registers
-    frags(cur, 1, 1);
-    mma(0);
-    // LDS stores first (they free the staging registers), then the global loads as early as possible so that
-    // they have a whole iteration to land, interleaved with this step's MFMAs and fragment reads
-    if (MORE) SGB(0x200, NA + NB);
-#pragma unroll
-    for (int i = 0; i < NMFMA; i++) {
-      SGB(0x008, 1);
-      if (MORE2) SGB(0x020, (NA + NB + NMFMA - 1) / NMFMA);
-      SGB(0x100, (NREAD + NMFMA - 1) / NMFMA);
-    }
-    frags(cur, 2, 0);
-    mma(1);
-    hint_step();
-    frags(cur, 3, 1);
-    mma(0);
-    hint_step();
-    // every wave has its last fragments of stage `cur` in registers and stage cur^1 is complete
+  if constexpr (BM * BN >= 256 * 256) {
+    // Pipeline.  While tile kt is multiplied out of stage kt&1, tile kt+1 sits in the other stage.  The A half of
+    // tile kt+2 is written into stage kt&1 right behind the barrier of iteration kt (which releases that stage), the
+    // B half during the first k step of iteration kt+1; each half's registers are refilled from global memory right
+    // behind its LDS store, a whole iteration ahead of the next store.  LDS stores and global loads are thus spread
+    // over two k steps and never wait at the top of the loop.
+    fetch_a(0);
+    fetch_b(0);
+    park_a(0);
+    park_b(0);
+    if (nk > 1) { fetch_a(1); park_a(1); fetch_b(1); }
+    if (nk > 2) fetch_a(2);
     __syncthreads();
-    if (MORE) frags(cur ^ 1, 0, 0);
-    mma(1);
-    hint_step();
-  };
-  using T_ = std::true_type;
-  using F_ = std::false_type;
-  int kt = 0;
-  for (; kt + 2 < nk; kt++) iteration(T_{}, T_{}, kt);
-  if (kt + 1 < nk) { iteration(T_{}, F_{}, kt); kt++; }
-  iteration(F_{}, F_{}, kt);
+    frags(0, 0, 0);
+
+    // one 64-wide k iteration; M1/M2/M3: tile kt+1 / kt+2 / kt+3 exists.  The steady state (all true) is branch-free
+    // so that the scheduler sees one block per iteration.
+    auto iteration = [&](auto m1_c, auto m2_c, auto m3_c, int kt) {
+      constexpr bool M1 = decltype(m1_c)::value, M2 = decltype(m2_c)::value, M3 = decltype(m3_c)::value;
+      const int cur = kt & 1;
+      if (M1) park_b(cur ^ 1);     // B half of tile kt+1 (the stage was released by the previous barrier)
+      if (M2) fetch_b(kt + 2);
+      frags(cur, 1, 1);
+      mma(0);
+  #pragma unroll
+      for (int i = 0; i < NMFMA; i++) {
+        SGB(0x008, 1);
+        SGB(0x100, (NREAD + NMFMA - 1) / NMFMA);
+        if (M1) SGB(0x200, (NB + NMFMA - 1) / NMFMA);
+        if (M2) SGB(0x020, (NB + NMFMA - 1) / NMFMA);
+      }
+      frags(cur, 2, 0);
+      mma(1);
+      hint_step();
+      frags(cur, 3, 1);
+      mma(0);
+      hint_step();
+      // every wave has its last fragments of stage `cur` in registers, and stage cur^1 (tile kt+1) is complete
+      __syncthreads();
+      if (M1) frags(cur ^ 1, 0, 0);
+      if (M2) park_a(cur);         // A half of tile kt+2 -> the stage just released
+      if (M3) fetch_a(kt + 3);
+      mma(1);
+  #pragma unroll
+      for (int i = 0; i < NMFMA; i++) {
+        SGB(0x008, 1);
+        if (M1) SGB(0x100, (NREAD + NMFMA - 1) / NMFMA);
+        if (M2) SGB(0x200, (NA + NMFMA - 1) / NMFMA);
+        if (M3) SGB(0x020, (NA + NMFMA - 1) / NMFMA);
+      }
+    };
+    using T_ = std::true_type;
+    using F_ = std::false_type;
+    int kt = 0;
+    for (; kt + 3 < nk; kt++) iteration(T_{}, T_{}, T_{}, kt);
+    if (kt + 2 < nk) { iteration(T_{}, T_{}, F_{}, kt); kt++; }
+    if (kt + 1 < nk) { iteration(T_{}, F_{}, F_{}, kt); kt++; }
+    iteration(F_{}, F_{}, F_{}, kt);
+  } else {
+    // Pipeline for the smaller tiles (their LDS traffic per MFMA is higher; a single burst of LDS stores at the top of
+    // the iteration disturbs the fragment reads least): tile kt+1 waits in registers, is stored into the other stage
+    // at the top of iteration kt, and the registers are refilled with tile kt+2 right behind.
+    fetch_a(0);
+    fetch_b(0);
+    park_a(0);
+    park_b(0);
+    if (nk > 1) { fetch_a(1); fetch_b(1); }
+    __syncthreads();
+    frags(0, 0, 0);
+    auto iteration = [&](auto m1_c, auto m2_c, int kt) {
+      constexpr bool M1 = decltype(m1_c)::value, M2 = decltype(m2_c)::value;
+      const int cur = kt & 1;
+      if (M1) { park_a(cur ^ 1); park_b(cur ^ 1); }
+      if (M2) { fetch_a(kt + 2); fetch_b(kt + 2); }
+      frags(cur, 1, 1);
+      mma(0);
+      if (M1) SGB(0x200, NA + NB);
+  #pragma unroll
+      for (int i = 0; i < NMFMA; i++) {
+        SGB(0x008, 1);
+        if (M2) SGB(0x020, (NA + NB + NMFMA - 1) / NMFMA);
+        SGB(0x100, (NREAD + NMFMA - 1) / NMFMA);
+      }
+      frags(cur, 2, 0);
+      mma(1);
+      hint_step();
+      frags(cur, 3, 1);
+      mma(0);
+      hint_step();
+      __syncthreads();
+      if (M1) frags(cur ^ 1, 0, 0);
+      mma(1);
+      hint_step();
+    };
+    using T_ = std::true_type;
+    using F_ = std::false_type;
+    int kt = 0;
+    for (; kt + 2 < nk; kt++) iteration(T_{}, T_{}, kt);
+    if (kt + 1 < nk) { iteration(T_{}, F_{}, kt); kt++; }
+    iteration(F_{}, F_{}, kt);
+  }
 
   // epilogue: accumulator element e of tile (i,j) is C[row][col + (e&3)] with
   //   row = m0 + wm*WTM + 32 i + (lane & 31),  col = n0 + wn*WTN + 32 j + 8 (e>>2) + 4 (lane>>5)
@@ -358,7 +413,7 @@ int launch_one(const GemmArgs& g0, int ksplit, float* ws, hipStream_t s) {
 // the workgroup count at the price of a second pass over fp32 partial planes.  Rates measured on this part.
 struct TileChoice { int bm, bn, ksplit; };
 TileChoice pick_tile(int M, int N, int K, size_t ws_bytes) {
-  static const struct { int bm, bn; float tflops; } cand[] = {{256, 256, 1050.f}, {256, 128, 900.f}, {128, 256, 900.f}, {128, 128, 740.f}};
+  static const struct { int bm, bn; float tflops; } cand[] = {{256, 256, 1150.f}, {256, 128, 880.f}, {128, 256, 880.f}, {128, 128, 740.f}};
   TileChoice best{128, 128, 1};
   double best_t = 1e30;
   for (auto& c : cand) {
