@@ -37,6 +37,7 @@ struct AttnArgs {
   int pos0;    // first position (within each sequence) of the row range
   int npos;    // positions per sequence in the row range
   int blocks;  // 32-row blocks per sequence
+  int nseq;    // sequences in the row range
   float scale, scale_log2;
 };
 
@@ -51,6 +52,17 @@ struct AT {
   static constexpr int cpr = D / 8;            // 16-byte chunks per row
   static constexpr int per_lane = 32 * cpr / 64;  // chunks per lane when one wave moves the tile
 };
+
+// Workgroup id -> ((sequence, head) pair, 32-row block).  Workgroup ids go round-robin over the 8 XCDs, so pair p
+// of every group of 8 pairs is given the ids congruent to p mod 8: all blocks of one (sequence, head) then run on
+// one XCD and its K/V (about 1 MB) stays in that XCD's L2 instead of every L2 streaming every head.
+__device__ __forceinline__ void decode_block(int wg, int pairs, int blocks, int& pair, int& blk) {
+  const int per_group = 8 * blocks;
+  const int gi = wg / per_group, w = wg - gi * per_group;
+  const int pg = min(8, pairs - 8 * gi);
+  pair = 8 * gi + w % pg;
+  blk = w / pg;
+}
 
 // one wave: rows [r0, r0+32) of a [*, D] slice (row stride ld elements) -> registers; rows >= rmax read as zero.
 // Tiles inside the matrix take the path without clamps and selects (uniform branch).
@@ -155,7 +167,9 @@ __global__ __launch_bounds__(NT, 2) void attn_fwd_kernel(AttnArgs a) {
   constexpr int kPartBytes = 4 * E * 64 * 4;
   __shared__ __attribute__((aligned(16))) char lds[(kStageBytes > kPartBytes ? kStageBytes : kPartBytes) + 1024];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, g = lane >> 5;
-  const int sq = blockIdx.x / a.blocks, qb = a.blocks - 1 - blockIdx.x % a.blocks, head = blockIdx.y;  // long rows first
+  int pair, blk;
+  decode_block(blockIdx.x, a.nseq * a.heads, a.blocks, pair, blk);
+  const int sq = pair / a.heads, head = pair % a.heads, qb = a.blocks - 1 - blk;  // long rows first
   const int seq_idx = a.seq0 + sq;
   const int q_begin = a.pos0 + qb * 32;
   const int q_end = min(a.pos0 + a.npos, q_begin + 32);
@@ -306,7 +320,9 @@ __global__ __launch_bounds__(NT, 1) void attn_dq_kernel(AttnArgs a) {
   constexpr int kPartBytes = 4 * E * 64 * 4;
   __shared__ __attribute__((aligned(16))) char lds[kStageBytes > kPartBytes ? kStageBytes : kPartBytes];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, g = lane >> 5;
-  const int sq = blockIdx.x / a.blocks, qb = a.blocks - 1 - blockIdx.x % a.blocks, head = blockIdx.y;
+  int pair, blk;
+  decode_block(blockIdx.x, a.nseq * a.heads, a.blocks, pair, blk);
+  const int sq = pair / a.heads, head = pair % a.heads, qb = a.blocks - 1 - blk;
   const int seq_idx = a.seq0 + sq;
   const int q_begin = a.pos0 + qb * 32;
   const int q_end = min(a.pos0 + a.npos, q_begin + 32);
@@ -396,7 +412,9 @@ __global__ __launch_bounds__(NT, 1) void attn_dkv_kernel(AttnArgs a) {
   constexpr int kPartBytes = 4 * E * 64 * 4;
   __shared__ __attribute__((aligned(16))) char lds[kStageBytes > kPartBytes ? kStageBytes : kPartBytes];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, g = lane >> 5;
-  const int sq = blockIdx.x / a.blocks, kb = blockIdx.x % a.blocks, head = blockIdx.y;  // early key blocks are the long ones
+  int pair, kb;
+  decode_block(blockIdx.x, a.nseq * a.heads, a.blocks, pair, kb);  // early key blocks are the long ones
+  const int sq = pair / a.heads, head = pair % a.heads;
   const int seq_idx = a.seq0 + sq;
   const int k_begin = a.pos0 + kb * 32;
   const int k_end = min(a.pos0 + a.npos, k_begin + 32);
@@ -536,7 +554,8 @@ int launch_attention_fwd(const void* qkv, void* out, float* lse, int batch, int 
   a.lse = lse;
   a.scale = 1.0f / sqrtf((float)head_dim);
   a.scale_log2 = a.scale * kLog2e;
-  dim3 grid(nseq * a.blocks, heads), block(NT);
+  a.nseq = nseq;
+  dim3 grid(nseq * a.blocks * heads), block(NT);
   if (head_dim == 64) {
     if (causal) hipLaunchKernelGGL((attn_fwd_kernel<64, true>), grid, block, 0, s, a);
     else hipLaunchKernelGGL((attn_fwd_kernel<64, false>), grid, block, 0, s, a);
@@ -570,7 +589,8 @@ int launch_attention_bwd(const void* qkv, const void* out, const void* dout, con
   const int first_row = row0;
   const int n_rows = (a.seq0 + nseq) * seq - row0;
   const long pairs = (long)n_rows * heads * (head_dim / 8);
-  dim3 dgrid((unsigned)((pairs + NT - 1) / NT)), block(NT), grid(nseq * a.blocks, heads);
+  a.nseq = nseq;
+  dim3 dgrid((unsigned)((pairs + NT - 1) / NT)), block(NT), grid(nseq * a.blocks * heads);
   if (head_dim == 64) hipLaunchKernelGGL((attn_delta_kernel<64>), dgrid, block, 0, s, a, first_row, n_rows);
   else hipLaunchKernelGGL((attn_delta_kernel<128>), dgrid, block, 0, s, a, first_row, n_rows);
   OASES_LAUNCH_CHECK("attn_delta_kernel");
