@@ -62,7 +62,10 @@ __global__ __launch_bounds__(NT) void bdr_ln_kernel(const float* __restrict__ pa
   const int nc = h >> 2;
   const size_t base = (size_t)row * h;
   f32x4 v[NC];
-  float s = 0.f, dummy = 0.f;
+  // mean and variance in ONE reduction: moments of (x - shift) with shift = first element of the input row (a value
+  // within a few standard deviations of the mean, so E[d^2] - E[d]^2 does not cancel)
+  const float shift = xin[base];
+  float s = 0.f, q = 0.f;
 #pragma unroll
   for (int i = 0; i < NC; i++) {
     const int c = tid + i * NT;
@@ -80,23 +83,15 @@ __global__ __launch_bounds__(NT) void bdr_ln_kernel(const float* __restrict__ pa
         *reinterpret_cast<f32x4*>(xo + base + 4 * c) = x;
       }
       v[i] = x;
-      s += x[0] + x[1] + x[2] + x[3];
+#pragma unroll
+      for (int j = 0; j < 4; j++) { float t = x[j] - shift; s += t; q += t * t; }
     }
   }
   if (!ln_out) return;
-  block_sum2(s, dummy, red);
-  const float mu = s / h;
-  float q = 0.f;
-#pragma unroll
-  for (int i = 0; i < NC; i++) {
-    const int c = tid + i * NT;
-    if (c < nc) {
-#pragma unroll
-      for (int j = 0; j < 4; j++) { float t = v[i][j] - mu; q += t * t; }
-    }
-  }
-  block_sum2(q, dummy, red);
-  const float rstd = rsqrtf(q / h + eps);
+  block_sum2(s, q, red);
+  const float ms = s / h;
+  const float mu = shift + ms;
+  const float rstd = rsqrtf(fmaxf(q / h - ms * ms, 0.f) + eps);
   if (tid == 0) { mu_out[row] = mu; rstd_out[row] = rstd; }
 #pragma unroll
   for (int i = 0; i < NC; i++) {

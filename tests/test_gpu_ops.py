@@ -59,6 +59,23 @@ def test_layernorm_fwd(B, lo, rows, h):
     assert rel_err(mu, rmu.flatten()) < 1e-5 and rel_err(rstd, rrstd.flatten()) < 1e-5
 
 
+def test_layernorm_fwd_large_mean(B, lo):
+    """Rows whose mean is far from zero compared with their spread: the one-pass statistics must not cancel."""
+    g = gen(12)
+    rows, h = 64, 4096
+    x = randn(g, rows, h) * 0.5 + 300.0 * randn(g, rows, 1)
+    xd = dev(x, torch.float32)
+    gd, bd = dev(torch.ones(h), torch.float32), dev(torch.zeros(h), torch.float32)
+    out = torch.empty(rows, h, dtype=torch.bfloat16, device="cuda")
+    mu = torch.empty(rows, dtype=torch.float32, device="cuda")
+    rstd = torch.empty_like(mu)
+    B.check(B.lib.oases_op_layernorm_fwd(xd.data_ptr(), gd.data_ptr(), bd.data_ptr(), out.data_ptr(), mu.data_ptr(),
+                                         rstd.data_ptr(), rows, h, 1e-5, None))
+    ref, rmu, rrstd = lo.layer_norm_fwd(xd.cpu().double(), gd.cpu().double(), bd.cpu().double(), 1e-5)
+    assert rel_err(mu, rmu.flatten()) < 1e-6 and rel_err(rstd, rrstd.flatten()) < 1e-3
+    assert rel_err(out.float(), ref) < 2e-2      # x itself carries only 2^-24 * 300 of absolute precision in fp32
+
+
 # ------------------------------------------------------------------ reduction point + bias + dropout + residual (+LN)
 @pytest.mark.parametrize("rows,h,p,with_peer,with_ln", [(130, 512, 0.1, True, True), (40, 2048, 0.0, False, True),
                                                         (17, 8192, 0.3, True, False), (64, 1032, 0.1, False, True)])
