@@ -64,12 +64,14 @@ __device__ __forceinline__ void decode_block(int wg, int pairs, int blocks, int&
   blk = w / pg;
 }
 
-// one wave: rows [r0, r0+32) of a [*, D] slice (row stride ld elements) -> registers; rows >= rmax read as zero.
-// Tiles inside the matrix take the path without clamps and selects (uniform branch).
+// one wave: rows [r0, r0+32) of a [*, D] slice (row stride ld elements) -> registers; rows outside [rmin, rmax) read
+// as ZERO: such rows may hold anything (rows of a sub-batch that has not been computed yet), and a masked
+// probability of 0 would still turn an inf/NaN there into NaN inside the MFMA.  Tiles inside the range take the
+// path without clamps and selects (uniform branch).
 template <int D>
-__device__ __forceinline__ void wave_load(u32x4* regs, const uint16_t* __restrict__ base, int ld, int r0, int rmax, int lane) {
+__device__ __forceinline__ void wave_load(u32x4* regs, const uint16_t* __restrict__ base, int ld, int r0, int rmin, int rmax, int lane) {
   constexpr int cpr = AT<D>::cpr, rows_per_pass = 64 / cpr;
-  if (r0 + 32 <= rmax) {
+  if (r0 >= rmin && r0 + 32 <= rmax) {
     const char* sb = reinterpret_cast<const char*>(base) + (size_t)r0 * ld * 2;
     const uint32_t voff = (uint32_t)(((lane / cpr) * ld + (lane % cpr) * 8) * 2);
 #pragma unroll
@@ -80,9 +82,9 @@ __device__ __forceinline__ void wave_load(u32x4* regs, const uint16_t* __restric
     for (int i = 0; i < AT<D>::per_lane; i++) {
       int c = lane + 64 * i;
       int row = c / cpr, cc = c % cpr;
-      int r = min(r0 + row, rmax - 1);
+      int r = max(min(r0 + row, rmax - 1), rmin);
       u32x4 v = *reinterpret_cast<const u32x4*>(base + (size_t)r * ld + cc * 8);
-      regs[i] = (r0 + row < rmax) ? v : u32x4{0u, 0u, 0u, 0u};
+      regs[i] = (r0 + row >= rmin && r0 + row < rmax) ? v : u32x4{0u, 0u, 0u, 0u};
     }
   }
 }
@@ -193,16 +195,16 @@ __global__ __launch_bounds__(NT, 2) void attn_fwd_kernel(AttnArgs a) {
   char* lv = lk + AT<D>::bytes;
   u32x4 rk[AT<D>::per_lane], rv[AT<D>::per_lane];
   if (wave < nt) {
-    wave_load<D>(rk, Kp, a.ld, wave * 32, a.seq, lane);
-    wave_load<D>(rv, Vp, a.ld, wave * 32, a.seq, lane);
+    wave_load<D>(rk, Kp, a.ld, wave * 32, 0, kv_end, lane);
+    wave_load<D>(rv, Vp, a.ld, wave * 32, 0, kv_end, lane);
   }
   for (int t = wave; t < nt; t += 4) {
     const int kv0 = t * 32;
     wave_store<D>(rk, lk, lane);  // LDS operations of one wave execute in order: no barrier for a private tile
     wave_store<D>(rv, lv, lane);
     if (t + 4 < nt) {
-      wave_load<D>(rk, Kp, a.ld, kv0 + 128, a.seq, lane);
-      wave_load<D>(rv, Vp, a.ld, kv0 + 128, a.seq, lane);
+      wave_load<D>(rk, Kp, a.ld, kv0 + 128, 0, kv_end, lane);
+      wave_load<D>(rv, Vp, a.ld, kv0 + 128, 0, kv_end, lane);
     }
     f32x16 s = zero16(), s1 = zero16();
 #pragma unroll
@@ -353,16 +355,16 @@ __global__ __launch_bounds__(NT, 1) void attn_dq_kernel(AttnArgs a) {
   char* lv = lk + AT<D>::bytes;
   u32x4 rk[AT<D>::per_lane], rv[AT<D>::per_lane];
   if (wave < nt) {
-    wave_load<D>(rk, Kp, a.ld, wave * 32, a.seq, lane);
-    wave_load<D>(rv, Vp, a.ld, wave * 32, a.seq, lane);
+    wave_load<D>(rk, Kp, a.ld, wave * 32, 0, kv_end, lane);
+    wave_load<D>(rv, Vp, a.ld, wave * 32, 0, kv_end, lane);
   }
   for (int t = wave; t < nt; t += 4) {
     const int kv0 = t * 32;
     wave_store<D>(rk, lk, lane);
     wave_store<D>(rv, lv, lane);
     if (t + 4 < nt) {
-      wave_load<D>(rk, Kp, a.ld, kv0 + 128, a.seq, lane);
-      wave_load<D>(rv, Vp, a.ld, kv0 + 128, a.seq, lane);
+      wave_load<D>(rk, Kp, a.ld, kv0 + 128, 0, kv_end, lane);
+      wave_load<D>(rv, Vp, a.ld, kv0 + 128, 0, kv_end, lane);
     }
     f32x16 s = zero16(), dp = zero16();
 #pragma unroll
@@ -373,12 +375,12 @@ __global__ __launch_bounds__(NT, 1) void attn_dq_kernel(AttnArgs a) {
     const bool need_mask = (kv0 + 32 > a.seq) || (CAUSAL && kv0 + 31 > q_begin);
 #pragma unroll
     for (int i = 0; i < 16; i++) {
-      float p = __builtin_amdgcn_exp2f(s[i] * a.scale_log2 - lse2);
+      float ds = __builtin_amdgcn_exp2f(s[i] * a.scale_log2 - lse2) * (dp[i] - dl);
       if (need_mask) {
         int kvpos = kv0 + 8 * (i >> 2) + 4 * g + (i & 3);
-        if (kvpos >= a.seq || (CAUSAL && kvpos > qpos)) p = 0.f;
+        if (kvpos >= a.seq || (CAUSAL && kvpos > qpos)) ds = 0.f;
       }
-      s[i] = p * (dp[i] - dl);
+      s[i] = ds;
     }
 #pragma unroll
     for (int j = 0; j < 2; j++) {
@@ -436,6 +438,7 @@ __global__ __launch_bounds__(NT, 1) void attn_dkv_kernel(AttnArgs a) {
   for (int i = 0; i < DT; i++) { dk[i] = zero16(); dv[i] = zero16(); }
 
   const int qt0 = CAUSAL ? k_begin / 32 : 0;   // first query tile that sees this key block
+  const int qmin = CAUSAL ? a.pos0 : 0;        // earlier queries never see a key of this row range
   const int nqt = (a.seq + 31) / 32;
   char* lq = lds + wave * (2 * AT<D>::bytes + 256);
   char* ldo = lq + AT<D>::bytes;
@@ -443,8 +446,8 @@ __global__ __launch_bounds__(NT, 1) void attn_dkv_kernel(AttnArgs a) {
   u32x4 rq[AT<D>::per_lane], rdo[AT<D>::per_lane];
   float rstat = 0.f;
   auto fetch = [&](int t) {
-    wave_load<D>(rq, Qp, a.ld, t * 32, a.seq, lane);
-    wave_load<D>(rdo, dOp, a.hp, t * 32, a.seq, lane);
+    wave_load<D>(rq, Qp, a.ld, t * 32, qmin, a.seq, lane);
+    wave_load<D>(rdo, dOp, a.hp, t * 32, qmin, a.seq, lane);
     const int qp = min(t * 32 + (lane & 31), a.seq - 1);
     rstat = g == 0 ? lsep[qp] * kLog2e : dlp[qp];
   };
@@ -471,12 +474,13 @@ __global__ __launch_bounds__(NT, 1) void attn_dkv_kernel(AttnArgs a) {
       for (int e = 0; e < 4; e++) {
         const int i = 4 * i4 + e;
         float p = __builtin_amdgcn_exp2f(s[i] * a.scale_log2 - l4[e]);
+        float ds = p * (dp[i] - d4[e]);
         if (need_mask) {
           int qp = q0 + ql + e;
-          if (qp >= a.seq || (CAUSAL && kpos > qp)) p = 0.f;
+          if (qp >= a.seq || (CAUSAL && kpos > qp)) { p = 0.f; ds = 0.f; }   // select, never multiply: the rest may be NaN
         }
         s[i] = p;
-        dp[i] = p * (dp[i] - d4[e]);
+        dp[i] = ds;
       }
     }
 #pragma unroll

@@ -76,6 +76,23 @@ def test_rank_shard_matches_oracle(name, ranks, dtype):
         torch.cuda.empty_cache()
 
 
+# ------------------------------------------------------------------ shapes off the tile grid, other head size, 3 layers, 3 sub-batches
+@pytest.mark.parametrize("cfg", [
+    dict(hidden=1024, n_heads=8, seq=200, batch=3, tp=2, n_sub=3, n_layers=3, causal=1, dropout_p=0.2, w_sigma=0.02),   # d=128, ragged seq
+    dict(hidden=768, n_heads=12, seq=72, batch=4, tp=3, n_sub=2, n_layers=1, causal=0, dropout_p=0.0, w_sigma=0.02),    # d=64, t=3, non-causal
+    dict(hidden=512, n_heads=4, seq=264, batch=1, tp=1, n_sub=3, n_layers=2, causal=1, dropout_p=0.1, w_sigma=0.02),    # t=1, chunks of one sequence
+])
+def test_ragged_configurations(cfg):
+    layers, x, dy = LH.make_inputs(cfg, seed=3)
+    for r in sorted({0, cfg["tp"] - 1}):
+        print(f"\n== ragged config h={cfg['hidden']} seq={cfg['seq']} rank {r}", flush=True)
+        gpu = LH.gpu_rank_run(cfg, r, layers, x, dy, seed=11)
+        ora = LH.oracle_rank_only(cfg, r, layers, x, dy, seed=11)
+        from oracle import layer_oracle as lo
+        fl = LH.oracle_rank_only(cfg, r, layers, x, dy, seed=11, bf16_sites=lo.BF16_OPERAND_SITES)
+        assert compare_run(gpu, ora, fl, cfg["n_layers"])
+
+
 # ------------------------------------------------------------------ with peer sums: every rank reproduces the unsharded layer
 @pytest.mark.timeout(900)
 @pytest.mark.parametrize("name,ranks", [("C1", (0, 1)), ("C2", (0, 1, 2, 3))])

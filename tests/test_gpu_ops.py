@@ -372,6 +372,49 @@ def test_attention_sequence_chunks(B, lo, d):
         assert torch.equal(a, b)
 
 
+@pytest.mark.parametrize("d", [64, 128])
+def test_attention_chunks_never_touch_rows_outside_their_range(B, lo, d):
+    """Chunks whose boundaries are off the 32-row tile grid.  Forward of a chunk must not depend on later rows of qkv
+    (not computed yet when the layer runs it), backward of a chunk not on dout / out / delta rows in front of it:
+    those rows are filled with NaN here; results must equal the whole-sequence run."""
+    g = gen(13)
+    batch, seq, heads, chunk = 1, 264, 2, 88
+    M, hp = seq, heads * d
+    qkv = bf16_round(randn(g, M, 3 * hp))
+    dout = bf16_round(randn(g, M, hp))
+    qd, dod = dev(qkv, torch.bfloat16), dev(dout, torch.bfloat16)
+    nan = float("nan")
+    # reference: one call over the whole sequence
+    out0 = torch.zeros(M, hp, dtype=torch.bfloat16, device="cuda")
+    lse0 = torch.zeros(heads * seq, dtype=torch.float32, device="cuda")
+    dq0 = torch.zeros(M, 3 * hp, dtype=torch.bfloat16, device="cuda")
+    dl0 = torch.zeros_like(lse0)
+    B.check(B.lib.oases_op_attention_fwd(qd.data_ptr(), out0.data_ptr(), lse0.data_ptr(), batch, seq, heads, d, 1, 0, M, None))
+    B.check(B.lib.oases_op_attention_bwd(qd.data_ptr(), out0.data_ptr(), dod.data_ptr(), lse0.data_ptr(), dl0.data_ptr(), dq0.data_ptr(),
+                                         batch, seq, heads, d, 1, 0, M, None))
+    # chunked: forward in order, rows behind the current chunk poisoned
+    out = torch.full((M, hp), nan, dtype=torch.bfloat16, device="cuda")
+    lse = torch.full((heads * seq,), nan, dtype=torch.float32, device="cuda")
+    for r0 in range(0, M, chunk):
+        qpart = qd.clone()
+        qpart[r0 + chunk:] = nan
+        B.check(B.lib.oases_op_attention_fwd(qpart.data_ptr(), out.data_ptr(), lse.data_ptr(), batch, seq, heads, d, 1, r0, chunk, None))
+        torch.cuda.synchronize()
+    assert torch.equal(out, out0) and torch.equal(lse, lse0)
+    # backward in reverse order, dout / delta rows in front of the current chunk poisoned
+    dqkv = torch.full((M, 3 * hp), nan, dtype=torch.bfloat16, device="cuda")
+    delta = torch.full_like(lse0, nan)
+    for r0 in reversed(range(0, M, chunk)):
+        dpart = dod.clone()
+        dpart[:r0] = nan
+        B.check(B.lib.oases_op_attention_bwd(qd.data_ptr(), out.data_ptr(), dpart.data_ptr(), lse.data_ptr(), delta.data_ptr(),
+                                             dqkv.data_ptr(), batch, seq, heads, d, 1, r0, chunk, None))
+        torch.cuda.synchronize()
+    assert not bool(torch.isnan(dqkv.float()).any())
+    # same tiles, but the split of a block's reduction range over the waves depends on where the block starts
+    assert rel_err(dqkv.float(), dq0.float()) < 2e-2
+
+
 def test_attention_argument_errors(B):
     t = torch.zeros(256, 3 * 64, dtype=torch.bfloat16, device="cuda")
     o = torch.zeros(256, 64, dtype=torch.bfloat16, device="cuda")
