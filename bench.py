@@ -94,6 +94,8 @@ def main():
     ap.add_argument("--config", default="C4", help="workload: C1..C5 (default C4, h=4096)")
     ap.add_argument("--n-sub", type=int, default=None, help="override the sub-batch count of the workload")
     ap.add_argument("--serialise", action="store_true", help="single stream")
+    ap.add_argument("--recompute", action="store_true",
+                    help="fine-grained recomputation: activations are rebuilt inside backward (model flops unchanged, more work)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-profile", action="store_true")
     ap.add_argument("--calib-copy", action="store_true",
@@ -118,7 +120,7 @@ def main():
     G = [B.zero_grads_like(w) for w in W]
     xd, dyd = torch.from_numpy(x).cuda(), torch.from_numpy(dy).cuda()
     yd, dxd = torch.empty_like(xd), torch.empty_like(xd)
-    flags = B.FLAG_SERIALISE if a.serialise else 0
+    flags = (B.FLAG_SERIALISE if a.serialise else 0) | (B.FLAG_RECOMPUTE if a.recompute else 0)
     H = B.Handle(B.make_cfg(cfg, rank=0, seed=0, flags=flags))
     ws = torch.empty(H.workspace_bytes, dtype=torch.uint8, device="cuda")
     s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
@@ -149,12 +151,13 @@ def main():
            "data": "synthetic",
            "config": {"workload": f"{a.config}: GPT layer h={h} heads={cfg['n_heads']} seq={cfg['seq']} batch={cfg['batch']} "
                                   f"t={cfg['tp']} rank 0 layers={cfg['n_layers']} causal={cfg['causal']} p={cfg['dropout_p']}",
-                      "n_sub": cfg["n_sub"], "streams": 1 if a.serialise else 2, "model_gflop_per_step": round(flops / 1e9, 1),
+                      "n_sub": cfg["n_sub"], "streams": 1 if a.serialise else 2, "recompute": bool(a.recompute),
+                      "workspace_mib": round(H.workspace_bytes / 2 ** 20, 1), "model_gflop_per_step": round(flops / 1e9, 1),
                       "frac_of_bf16_peak": round(tflops / PEAK_BF16_TFLOPS, 4)}}
 
     # per-operator HIP-event timers over the same schedule (serialised so that every bracket holds one operator)
     if not a.no_profile:
-        HP = B.Handle(B.make_cfg(cfg, rank=0, seed=0, flags=B.FLAG_SERIALISE | B.FLAG_PROFILE))
+        HP = B.Handle(B.make_cfg(cfg, rank=0, seed=0, flags=B.FLAG_SERIALISE | B.FLAG_PROFILE | (B.FLAG_RECOMPUTE if a.recompute else 0)))
         acc = {}
         reps = max(3, min(a.steps, 10))
         step(HP)

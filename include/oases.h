@@ -66,7 +66,12 @@ typedef struct oases_layer_cfg {
 
 enum {
   OASES_FLAG_SERIALISE = 1, /* enqueue everything on stream_compute only (same results) */
-  OASES_FLAG_PROFILE = 2    /* bracket every operator with timing events, see oases_profile_read */
+  OASES_FLAG_PROFILE = 2,   /* bracket every operator with timing events, see oases_profile_read */
+  OASES_FLAG_RECOMPUTE = 4  /* fine-grained recomputation (paper Sec. IV-B): keep only the input of each computation
+                               sequence (x, x1) per layer, rebuild u, qkv, attention output, LSE, v2, pre, f inside
+                               oases_backward with the forward kernels -- never a reduction point -- interleaved with
+                               the backward operators of the same sub-batch (Alg. 1 "At Backward"); the rebuilt
+                               activations share one region of the workspace across layers; same results, bit for bit */
 };
 
 typedef struct oases_handle oases_handle; /* opaque; holds host metadata and HIP events only */

@@ -15,7 +15,7 @@ lib = C.CDLL(LIB_PATH)
 OK, EINVAL, ENULL, EALIGN, EWORKSPACE, EHIP = 0, -1, -2, -3, -4, -5
 GEMM_NN, GEMM_NT, GEMM_TN = 0, 1, 2
 EPI_F32, EPI_BF16, EPI_BIAS_BF16, EPI_BIAS_GELU, EPI_DGELU = 0, 1, 2, 3, 4
-FLAG_SERIALISE, FLAG_PROFILE = 1, 2
+FLAG_SERIALISE, FLAG_PROFILE, FLAG_RECOMPUTE = 1, 2, 4
 
 _P = C.c_void_p
 _PARAMS = ("ln1_g", "ln1_b", "wqkv", "bqkv", "wo", "bo", "ln2_g", "ln2_b", "w1", "b1", "w2", "b2")

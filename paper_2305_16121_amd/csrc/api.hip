@@ -33,13 +33,16 @@ enum OpKind {
   // backward
   B_BDR2, B_FC2_DGRAD, B_FC1_DGRAD, B_R3, B_FC2_WGRAD, B_FC1_WGRAD, B_B1_SUM, B_PROJ_DGRAD, B_PROJ_WGRAD, B_ATTN,
   B_QKV_DGRAD, B_R4, B_QKV_WGRAD, B_BQKV_SUM,
+  // recompute mode: Recompute() of the saved sequences inside the backward pass
+  R_LN2, R_FC1, R_LN1, R_QKV, R_ATTN,
   // stream join at the end of a pass
   JOIN
 };
 static const char* kOpName[] = {
     "LN1", "QKV", "ATTN", "PROJ", "R1+BDR1+LN2", "FC1+GELU", "FC2", "R2+BDR2",
     "BDR2.b", "FC2.dgrad+dGELU", "FC1.dgrad", "R3+LN2.b+BDR1.b", "FC2.wgrad", "FC1.wgrad", "b1.sum", "PROJ.dgrad",
-    "PROJ.wgrad", "ATTN.b", "QKV.dgrad", "R4+LN1.b", "QKV.wgrad", "bqkv.sum", "join"};
+    "PROJ.wgrad", "ATTN.b", "QKV.dgrad", "R4+LN1.b", "QKV.wgrad", "bqkv.sum",
+    "LN2.r", "FC1+GELU.r", "LN1.r", "QKV.r", "ATTN.r", "join"};
 
 struct Op {
   int kind, layer, sub;
@@ -51,6 +54,7 @@ struct Op {
 struct Tensor {
   const char* name;
   size_t offset, bytes;
+  bool shared;  // recompute mode: a forward activation that is rebuilt in backward, one copy for all layers
 };
 
 }  // namespace oases
@@ -67,7 +71,7 @@ struct oases_handle {
   std::vector<hipEvent_t> prof[2];  // OASES_FLAG_PROFILE: start/stop event per operator of each pass
   bool prof_ran[2] = {false, false};
   std::vector<Tensor> tensors;     // per-layer tensors, offsets relative to the layer base
-  size_t layer_bytes, scratch_comm_off, scratch_compute_off, gemm_ws_off, gemm_ws_bytes, total_bytes;
+  size_t layer_bytes, shared_off, scratch_comm_off, scratch_compute_off, gemm_ws_off, gemm_ws_bytes, total_bytes;
 };
 
 namespace oases {
@@ -82,13 +86,27 @@ static void plan_workspace(oases_handle* H) {
       {"v2", M * h * 2},     {"pre", M * fp * 2},   {"f", M * fp * 2},     {"z2", M * h * 4},       {"y", M * h * 4},
       {"dz2", M * h * 2},    {"dg", M * fp * 2},    {"dv2", M * h * 4},    {"dx1", M * h * 4},      {"dz1", M * h * 2},
       {"da", M * hp * 2},    {"delta", st * 4},     {"dqkv", M * 3 * hp * 2}, {"du", M * h * 4},    {"dy", M * h * 4}};
-  size_t off = 0;
+  // Recompute mode (the paper's fine-grained recomputation, Sec. IV-B): only the input of each computation
+  // sequence is kept per layer -- x (= y of the layer below) for [LN1,QKV,ATTN,PROJ] and x1 for [LN2,FC1,FC2] -- the
+  // activations in between are rebuilt inside backward and live in one region shared by all layers.
+  const bool recompute = H->cfg.flags & OASES_FLAG_RECOMPUTE;
+  static const char* kAct[] = {"u", "qkv", "attn", "lse", "v2", "pre", "f", "z1", "z2"};
+  size_t off = 0, soff = 0;
   for (auto& e : list) {
-    H->tensors.push_back(Tensor{e.n, off, e.bytes});
-    off += align_up(e.bytes);
+    bool act = false;
+    for (const char* a : kAct) act = act || !strcmp(a, e.n);
+    if (recompute && act) {
+      H->tensors.push_back(Tensor{e.n, soff, e.bytes, true});
+      soff += align_up(e.bytes);
+    } else {
+      H->tensors.push_back(Tensor{e.n, off, e.bytes, false});
+      off += align_up(e.bytes);
+    }
   }
   H->layer_bytes = off;
   size_t tot = off * H->L;
+  H->shared_off = tot;
+  tot += soff;
   H->scratch_comm_off = tot;
   tot += align_up((size_t)3 * kColPartials * h * 4);
   H->scratch_compute_off = tot;
@@ -106,7 +124,7 @@ static void plan_workspace(oases_handle* H) {
 
 static size_t tensor_off(const oases_handle* H, const char* name, int layer) {
   for (auto& t : H->tensors)
-    if (!strcmp(t.name, name)) return (size_t)layer * H->layer_bytes + t.offset;
+    if (!strcmp(t.name, name)) return t.shared ? H->shared_off + t.offset : (size_t)layer * H->layer_bytes + t.offset;
   return (size_t)-1;
 }
 
@@ -149,11 +167,17 @@ static void build_forward(oases_handle* H) {
 static void build_backward(oases_handle* H) {
   auto& ops = H->bwd;
   const int n = H->n, L = H->L;
+  const bool recompute = H->cfg.flags & OASES_FLAG_RECOMPUTE;
+  const bool chunks = H->n > H->b;  // sub-batches are parts of a sequence: attention of a chunk reads earlier chunks' K/V
   for (int j = n - 1; j >= 0; j--) ops.push_back(Op{B_BDR2, L - 1, j, 1, -1, ev_id(H, L - 1, 1, j, 1)});
   for (int l = L - 1; l >= 0; l--) {
     for (int j = n - 1; j >= 0; j--) {
       // dZ2 of this layer comes from the trailing BDR2.b (top layer) or from R4 of the layer above
       int w = l == L - 1 ? ev_id(H, l, 1, j, 1) : ev_id(H, l + 1, 3, j, 1);
+      if (recompute) {  // Recompute() of the saved sequence [LN2, FC1]: starts at x1, behind the forward reduction
+        ops.push_back(Op{R_LN2, l, j, 0, -1, -1});
+        ops.push_back(Op{R_FC1, l, j, 0, -1, -1});
+      }
       ops.push_back(Op{B_FC2_DGRAD, l, j, 0, w, -1});
       ops.push_back(Op{B_FC1_DGRAD, l, j, 0, -1, ev_id(H, l, 2, j, 0)});
       ops.push_back(Op{B_R3, l, j, 1, ev_id(H, l, 2, j, 0), ev_id(H, l, 2, j, 1)});
@@ -162,7 +186,19 @@ static void build_backward(oases_handle* H) {
     ops.push_back(Op{B_FC2_WGRAD, l, -1, 0, -1, -1});
     ops.push_back(Op{B_FC1_WGRAD, l, -1, 0, -1, -1});
     ops.push_back(Op{B_B1_SUM, l, -1, 0, -1, -1});
+    if (recompute && chunks)  // K/V of every chunk must exist again before any chunk's attention is rebuilt
+      for (int j = n - 1; j >= 0; j--) {
+        ops.push_back(Op{R_LN1, l, j, 0, -1, -1});
+        ops.push_back(Op{R_QKV, l, j, 0, -1, -1});
+      }
+    if (recompute && chunks)  // ... and the attention output / LSE of later chunks before an earlier chunk's dK/dV
+      for (int j = 0; j < n; j++) ops.push_back(Op{R_ATTN, l, j, 0, -1, -1});
     for (int j = n - 1; j >= 0; j--) {
+      if (recompute && !chunks) {  // Recompute() of [LN1, QKV, ATTN]: starts at the layer input
+        ops.push_back(Op{R_LN1, l, j, 0, -1, -1});
+        ops.push_back(Op{R_QKV, l, j, 0, -1, -1});
+        ops.push_back(Op{R_ATTN, l, j, 0, -1, -1});
+      }
       ops.push_back(Op{B_PROJ_DGRAD, l, j, 0, ev_id(H, l, 2, j, 1), -1});
       ops.push_back(Op{B_ATTN, l, j, 0, -1, -1});
       ops.push_back(Op{B_QKV_DGRAD, l, j, 0, -1, ev_id(H, l, 3, j, 0)});
@@ -319,6 +355,28 @@ static int run_op(const Run& R, const Op& op) {
                          R.g[l].wqkv, 3 * hp, nullptr, nullptr, 0, gws, H->gemm_ws_bytes, s);
     case B_BQKV_SUM:
       return launch_colsum_bf16(wsp<uint16_t>(R, "dqkv", l) + r0 * 3 * hp, 3 * hp, Ms, 3 * hp, (float*)R.g[l].bqkv, scr_comp, s);
+    // ---------------------------------------------------------------- recompute: the forward kernels again
+    case R_LN1:
+      return launch_layernorm_fwd(xin + r0 * h, (const float*)W.ln1_g, (const float*)W.ln1_b, u + r0 * h,
+                                  wsp<float>(R, "mu1", l) + r0, wsp<float>(R, "rstd1", l) + r0, Ms, h, H->eps, s);
+    case R_QKV: {
+      Op f = op;
+      f.kind = F_QKV;
+      return run_op(R, f);
+    }
+    case R_ATTN: {
+      Op f = op;
+      f.kind = F_ATTN;
+      return run_op(R, f);
+    }
+    case R_LN2:
+      return launch_layernorm_fwd(wsp<float>(R, "x1", l) + r0 * h, (const float*)W.ln2_g, (const float*)W.ln2_b, v2 + r0 * h,
+                                  wsp<float>(R, "mu2", l) + r0, wsp<float>(R, "rstd2", l) + r0, Ms, h, H->eps, s);
+    case R_FC1: {
+      Op f = op;
+      f.kind = F_FC1;
+      return run_op(R, f);
+    }
     case JOIN:
       return 0;
   }
@@ -429,7 +487,7 @@ int oases_workspace_tensor(const oases_handle* H, const char* name, int layer, s
   if (layer < 0 || layer >= H->L) { set_error("layer %d out of range", layer); return OASES_EINVAL; }
   for (auto& t : H->tensors)
     if (!strcmp(t.name, name)) {
-      *offset = (size_t)layer * H->layer_bytes + t.offset;
+      *offset = tensor_off(H, name, layer);
       *bytes = t.bytes;
       return 0;
     }

@@ -62,9 +62,18 @@ __global__ __launch_bounds__(NT) void bdr_ln_kernel(const float* __restrict__ pa
   const int nc = h >> 2;
   const size_t base = (size_t)row * h;
   f32x4 v[NC];
-  // mean and variance in ONE reduction: moments of (x - shift) with shift = first element of the input row (a value
-  // within a few standard deviations of the mean, so E[d^2] - E[d]^2 does not cancel)
-  const float shift = xin[base];
+  // mean and variance in ONE reduction: moments of (x - shift) with shift = first element of the row that is
+  // normalised (a value within a few standard deviations of the mean, so E[d^2] - E[d]^2 does not cancel).  Every
+  // thread rebuilds that element itself, so the statistics are the same function of the row whether the row was
+  // just produced here (fused reduction point) or is read back later (LayerNorm alone, recomputation).
+  float shift = xin[base];
+  if (part) {
+    float z0 = part[base] + bias[0];
+    if (peer) z0 += peer[base];
+    bool k0[4];
+    dropout_keep4(d, (uint64_t)(row0 + row) * h >> 2, k0);
+    if (k0[0]) shift += z0 * d.scale;
+  }
   float s = 0.f, q = 0.f;
 #pragma unroll
   for (int i = 0; i < NC; i++) {

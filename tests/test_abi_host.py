@@ -105,6 +105,19 @@ compute PROJ.wgrad sb*|compute QKV.wgrad sb*|compute bqkv.sum sb*
 compute join sb1|compute join sb0"""
 
 
+# The same with fine-grained recomputation (Sec. IV-B): each popped sequence is first rebuilt from its stored input by the
+# forward kernels (".r"), starting BEHIND the forward communication operator, so no reduction point is ever re-run.
+BWD_TRACE_RECOMPUTE = """\
+comm BDR2.b sb1|comm BDR2.b sb0
+compute LN2.r sb1|compute FC1+GELU.r sb1|compute FC2.dgrad+dGELU sb1|compute FC1.dgrad sb1|comm R3+LN2.b+BDR1.b sb1
+compute LN2.r sb0|compute FC1+GELU.r sb0|compute FC2.dgrad+dGELU sb0|compute FC1.dgrad sb0|comm R3+LN2.b+BDR1.b sb0
+compute FC2.wgrad sb*|compute FC1.wgrad sb*|compute b1.sum sb*
+compute LN1.r sb1|compute QKV.r sb1|compute ATTN.r sb1|compute PROJ.dgrad sb1|compute ATTN.b sb1|compute QKV.dgrad sb1|comm R4+LN1.b sb1
+compute LN1.r sb0|compute QKV.r sb0|compute ATTN.r sb0|compute PROJ.dgrad sb0|compute ATTN.b sb0|compute QKV.dgrad sb0|comm R4+LN1.b sb0
+compute PROJ.wgrad sb*|compute QKV.wgrad sb*|compute bqkv.sum sb*
+compute join sb1|compute join sb0"""
+
+
 def _norm(trace):
     return [x.strip() for line in trace.splitlines() for x in line.split("|")]
 
@@ -114,6 +127,25 @@ def test_schedule_matches_hand_trace(B):
     strip = lambda s: [re.sub(r" L0", "", l) for l in s.strip().splitlines()]
     assert strip(H.schedule(False)) == _norm(FWD_TRACE)
     assert strip(H.schedule(True)) == _norm(BWD_TRACE)
+    HR = B.Handle(B.make_cfg(si.CONFIGS["C1"], flags=B.FLAG_RECOMPUTE))
+    assert strip(HR.schedule(False)) == _norm(FWD_TRACE)          # forward is the same
+    assert strip(HR.schedule(True)) == _norm(BWD_TRACE_RECOMPUTE)
+
+
+def test_recompute_mode_workspace_and_chunk_order(B):
+    # stacked layers: the rebuilt activations share one region, so the workspace shrinks
+    cfg = si.CONFIGS["C2"]
+    a, b = B.Handle(B.make_cfg(cfg)), B.Handle(B.make_cfg(cfg, flags=B.FLAG_RECOMPUTE))
+    assert b.workspace_bytes < a.workspace_bytes
+    assert a.tensor_span("qkv", 0)[0] != a.tensor_span("qkv", 1)[0]
+    assert b.tensor_span("qkv", 0)[0] == b.tensor_span("qkv", 1)[0]          # shared
+    assert b.tensor_span("x1", 0)[0] != b.tensor_span("x1", 1)[0]            # sequence inputs stay per layer
+    # sub-batches that are chunks of a sequence: K/V of every chunk are rebuilt before any chunk's attention
+    c = B.Handle(B.make_cfg(si.CONFIGS["C5"], flags=B.FLAG_RECOMPUTE)).schedule(True).splitlines()
+    idx = lambda op, sb: next(i for i, l in enumerate(c) if f" {op} " in l and l.endswith(f"sb{sb}"))
+    assert max(idx("QKV.r", j) for j in range(4)) < min(idx("ATTN.r", j) for j in range(4))
+    assert [idx("ATTN.r", j) for j in range(4)] == sorted(idx("ATTN.r", j) for j in range(4))    # earlier chunks first
+    assert max(idx("ATTN.r", j) for j in range(4)) < min(idx("ATTN.b", j) for j in range(4))
 
 
 @pytest.mark.parametrize("name", ["C2", "C5"])

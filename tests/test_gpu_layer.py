@@ -163,6 +163,30 @@ def test_streams_do_not_change_results():
                 assert torch.equal(a["grads"][l][k], other["grads"][l][k]), (l, k)
 
 
+@pytest.mark.parametrize("name,n_sub", [("C1", None), ("C2", None), ("C2", 16)])
+def test_recompute_mode_reproduces_stored_activation_mode(name, n_sub):
+    """Fine-grained recomputation (Sec. IV-B): the activations between the inputs of the computation sequences are rebuilt
+    inside backward by the forward kernels -- same kernels, same inputs, so every result is bit-identical -- and the
+    rebuilt activations share one workspace region across layers."""
+    cfg = si.CONFIGS[name]
+    layers, x, dy = LH.make_inputs(cfg)
+    from paper_2305_16121_amd import binding as B
+    a = LH.gpu_rank_run(cfg, 0, layers, x, dy, n_sub=n_sub, keep=True)
+    b = LH.gpu_rank_run(cfg, 0, layers, x, dy, n_sub=n_sub, flags=B.FLAG_RECOMPUTE, keep=True)
+    assert torch.equal(a["y"], b["y"])
+    assert torch.equal(a["dx"], b["dx"]), f"dx differs: max/rms {rel_err(b['dx'], a['dx']):.3g}"
+    for l in range(cfg["n_layers"]):
+        for k in LH.GPU_PARAMS:
+            assert torch.equal(a["grads"][l][k], b["grads"][l][k]), (l, k)
+    if cfg["n_layers"] > 1:
+        assert b["handle"].workspace_bytes < a["handle"].workspace_bytes
+    sched = b["handle"].schedule(True)
+    L, n = cfg["n_layers"], (n_sub or cfg["n_sub"])
+    for op in ("LN2.r", "FC1+GELU.r", "LN1.r", "QKV.r", "ATTN.r"):
+        assert sum(f" {op} " in line for line in sched.splitlines()) == L * n
+    assert " R1" not in sched and " R2" not in sched          # no forward reduction point is ever re-run (Eq. (1))
+
+
 def test_gradients_accumulate_and_calls_repeat():
     cfg = si.CONFIGS["C1"]
     layers, x, dy = LH.make_inputs(cfg)
