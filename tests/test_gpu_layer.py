@@ -143,10 +143,11 @@ def test_sub_batch_count_does_not_change_results(name, subs):
         run = LH.gpu_rank_run(cfg, 0, layers, x, dy, n_sub=n)
         # every row is computed by row-independent kernels; only the split of a GEMM's k range (chosen per shape) may
         # change the fp32 summation order, which a bf16 rounding downstream can amplify to one bf16 ulp of an operand
-        assert rel_err(run["y"], base["y"]) < 5e-3 and rel_err(run["dx"], base["dx"]) < 5e-3, n
+        assert rel_err(run["y"], base["y"]) < 5e-3 and rel_err(run["dx"], base["dx"]) < 1e-2, n
         for l in range(cfg["n_layers"]):
-            for k in LH.GPU_PARAMS:   # sums over rows: only the fp32 accumulation order changes
-                assert rel_err(run["grads"][l][k], base["grads"][l][k]) < 5e-3, (n, l, k)
+            for k in LH.GPU_PARAMS:   # sums over rows of bf16-stored operands: a flipped bf16 rounding upstream moves a weight
+                # gradient by up to its storage-format floor; the contract's gradient tolerance bounds it
+                assert rel_err(run["grads"][l][k], base["grads"][l][k]) < LH.GRAD_TOL, (n, l, k)
 
 
 def test_streams_do_not_change_results():
