@@ -66,9 +66,12 @@ def gemm_kernel_label(line, cfg, B, ws_bytes):
     if op not in shapes:
         return None
     form, epi, m, n, k = shapes[op]
-    tile = B.lib.oases_op_gemm_variant({"NN": 0, "NT": 1, "TN": 2}[form], 0, m, n, k, ws_bytes)
-    split = f"_splitk{tile // 1000000}" if tile >= 2000000 else ""
-    return f"gemm_{form}_{epi}_{tile // 1000 % 1000}x{tile % 1000}{split}"
+    epi_id = {"f32": 0, "bf16": 1, "bias_bf16": 2, "bias_gelu": 3, "dgelu": 4, "acc_f32": 0}[epi]
+    tile = B.lib.oases_op_gemm_variant({"NN": 0, "NT": 1, "TN": 2}[form], epi_id, m, n, k, ws_bytes)
+    slices = tile // 1000000 % 100
+    split = f"_splitk{slices}" if slices >= 2 else ""
+    wk = "_wavek2" if tile >= 100000000 else ""
+    return f"gemm_{form}_{epi}_{tile // 1000 % 1000}x{tile % 1000}{wk}{split}"
 
 
 def cpu_baseline(cfg, name):

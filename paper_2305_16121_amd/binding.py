@@ -64,6 +64,7 @@ _sig("oases_op_dropout_bwd", _i, _P, _P, _P, _i, _i, _u64, _i, _i, _i64, _f, _P,
 _sig("oases_op_layernorm_bwd", _i, _P, _P, _P, _P, _P, _P, _P, _P, _P, _P, _P, _P, _i, _i, _u64, _i, _i, _i64, _f, _P, _P)
 _sig("oases_op_gemm", _i, _i, _i, _i, _i, _i, _P, _i, _P, _i, _P, _i, _P, _P, _i, _P, _sz, _P)
 _sig("oases_op_gemm_variant", _i, _i, _i, _i, _i, _i, _sz)
+_sig("oases_op_gemm_forced", _i, _i, _i, _i, _i, _i, _i, _P, _i, _P, _i, _P, _i, _P, _P, _i, _P, _sz, _P)
 _sig("oases_gemm_workspace_bytes", _sz, _P)
 _sig("oases_op_colsum_bf16", _i, _P, _i, _i, _i, _P, _P, _P)
 _sig("oases_op_attention_fwd", _i, _P, _P, _P, _i, _i, _i, _i, _i, _i, _i, _P)

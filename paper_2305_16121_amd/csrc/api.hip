@@ -280,12 +280,12 @@ static int run_op(const Run& R, const Op& op) {
                                   wsp<float>(R, "mu1", l) + r0, wsp<float>(R, "rstd1", l) + r0, Ms, h, H->eps, s);
     case F_QKV:
       return launch_gemm(OASES_GEMM_NN, OASES_EPI_BIAS_BF16, Ms, 3 * hp, h, u + r0 * h, h, W.wqkv, 3 * hp, qkv + r0 * 3 * hp,
-                         3 * hp, (const float*)W.bqkv, nullptr, 0, gws, H->gemm_ws_bytes, s);
+                         3 * hp, (const float*)W.bqkv, nullptr, 0, gws, H->gemm_ws_bytes, 0, s);
     case F_ATTN:
       return launch_attention_fwd(qkv, attn, wsp<float>(R, "lse", l), H->b, H->s, H->heads_l, H->d, H->cfg.causal, (int)r0, Ms, s);
     case F_PROJ:
       return launch_gemm(OASES_GEMM_NN, OASES_EPI_F32, Ms, h, hp, attn + r0 * hp, hp, W.wo, h, wsp<float>(R, "z1", l) + r0 * h, h,
-                         nullptr, nullptr, 0, gws, H->gemm_ws_bytes, s);
+                         nullptr, nullptr, 0, gws, H->gemm_ws_bytes, 0, s);
     case F_R1:
       return launch_bdr_ln(wsp<float>(R, "z1", l) + r0 * h, peer(P ? P->fwd_attn : nullptr), (const float*)W.bo, xin + r0 * h,
                            wsp<float>(R, "x1", l) + r0 * h, (const float*)W.ln2_g, (const float*)W.ln2_b, v2 + r0 * h,
@@ -293,10 +293,10 @@ static int run_op(const Run& R, const Op& op) {
                            make_drop_cfg(seed, l, 0, p), (int64_t)r0, s);
     case F_FC1:
       return launch_gemm(OASES_GEMM_NN, OASES_EPI_BIAS_GELU, Ms, fp, h, v2 + r0 * h, h, W.w1, fp, f + r0 * fp, fp,
-                         (const float*)W.b1, pre + r0 * fp, fp, gws, H->gemm_ws_bytes, s);
+                         (const float*)W.b1, pre + r0 * fp, fp, gws, H->gemm_ws_bytes, 0, s);
     case F_FC2:
       return launch_gemm(OASES_GEMM_NN, OASES_EPI_F32, Ms, h, fp, f + r0 * fp, fp, W.w2, h, wsp<float>(R, "z2", l) + r0 * h, h,
-                         nullptr, nullptr, 0, gws, H->gemm_ws_bytes, s);
+                         nullptr, nullptr, 0, gws, H->gemm_ws_bytes, 0, s);
     case F_R2: {
       const bool more = l + 1 < L;  // fuse the next layer's LN1 behind this layer's output
       return launch_bdr_ln(wsp<float>(R, "z2", l) + r0 * h, peer(P ? P->fwd_ffn : nullptr), (const float*)W.b2,
@@ -311,10 +311,10 @@ static int run_op(const Run& R, const Op& op) {
                                 make_drop_cfg(seed, l, 1, p), (int64_t)r0, scr_comm, s);
     case B_FC2_DGRAD:
       return launch_gemm(OASES_GEMM_NT, OASES_EPI_DGELU, Ms, fp, h, wsp<uint16_t>(R, "dz2", l) + r0 * h, h, W.w2, h,
-                         wsp<uint16_t>(R, "dg", l) + r0 * fp, fp, nullptr, pre + r0 * fp, fp, gws, H->gemm_ws_bytes, s);
+                         wsp<uint16_t>(R, "dg", l) + r0 * fp, fp, nullptr, pre + r0 * fp, fp, gws, H->gemm_ws_bytes, 0, s);
     case B_FC1_DGRAD:
       return launch_gemm(OASES_GEMM_NT, OASES_EPI_F32, Ms, h, fp, wsp<uint16_t>(R, "dg", l) + r0 * fp, fp, W.w1, fp,
-                         wsp<float>(R, "dv2", l) + r0 * h, h, nullptr, nullptr, 0, gws, H->gemm_ws_bytes, s);
+                         wsp<float>(R, "dv2", l) + r0 * h, h, nullptr, nullptr, 0, gws, H->gemm_ws_bytes, 0, s);
     case B_R3:
       return launch_layernorm_bwd(wsp<float>(R, "dv2", l) + r0 * h, peer(P ? P->bwd_ffn : nullptr), dyin + r0 * h,
                                   wsp<float>(R, "x1", l) + r0 * h, wsp<float>(R, "mu2", l) + r0, wsp<float>(R, "rstd2", l) + r0,
@@ -323,24 +323,24 @@ static int run_op(const Run& R, const Op& op) {
                                   make_drop_cfg(seed, l, 0, p), (int64_t)r0, scr_comm, s);
     case B_FC2_WGRAD:
       return launch_gemm(OASES_GEMM_TN, 0, fp, h, Ms, f + r0 * fp, fp, wsp<uint16_t>(R, "dz2", l) + r0 * h, h, R.g[l].w2, h,
-                         nullptr, nullptr, 0, gws, H->gemm_ws_bytes, s);
+                         nullptr, nullptr, 0, gws, H->gemm_ws_bytes, 0, s);
     case B_FC1_WGRAD:
       return launch_gemm(OASES_GEMM_TN, 0, h, fp, Ms, v2 + r0 * h, h, wsp<uint16_t>(R, "dg", l) + r0 * fp, fp, R.g[l].w1, fp,
-                         nullptr, nullptr, 0, gws, H->gemm_ws_bytes, s);
+                         nullptr, nullptr, 0, gws, H->gemm_ws_bytes, 0, s);
     case B_B1_SUM:
       return launch_colsum_bf16(wsp<uint16_t>(R, "dg", l) + r0 * fp, fp, Ms, fp, (float*)R.g[l].b1, scr_comp, s);
     case B_PROJ_DGRAD:
       return launch_gemm(OASES_GEMM_NT, OASES_EPI_BF16, Ms, hp, h, wsp<uint16_t>(R, "dz1", l) + r0 * h, h, W.wo, h,
-                         wsp<uint16_t>(R, "da", l) + r0 * hp, hp, nullptr, nullptr, 0, gws, H->gemm_ws_bytes, s);
+                         wsp<uint16_t>(R, "da", l) + r0 * hp, hp, nullptr, nullptr, 0, gws, H->gemm_ws_bytes, 0, s);
     case B_PROJ_WGRAD:
       return launch_gemm(OASES_GEMM_TN, 0, hp, h, Ms, attn + r0 * hp, hp, wsp<uint16_t>(R, "dz1", l) + r0 * h, h, R.g[l].wo, h,
-                         nullptr, nullptr, 0, gws, H->gemm_ws_bytes, s);
+                         nullptr, nullptr, 0, gws, H->gemm_ws_bytes, 0, s);
     case B_ATTN:
       return launch_attention_bwd(qkv, attn, wsp<uint16_t>(R, "da", l), wsp<float>(R, "lse", l), wsp<float>(R, "delta", l),
                                   wsp<uint16_t>(R, "dqkv", l), H->b, H->s, H->heads_l, H->d, H->cfg.causal, (int)r0, Ms, s);
     case B_QKV_DGRAD:
       return launch_gemm(OASES_GEMM_NT, OASES_EPI_F32, Ms, h, 3 * hp, wsp<uint16_t>(R, "dqkv", l) + r0 * 3 * hp, 3 * hp, W.wqkv,
-                         3 * hp, wsp<float>(R, "du", l) + r0 * h, h, nullptr, nullptr, 0, gws, H->gemm_ws_bytes, s);
+                         3 * hp, wsp<float>(R, "du", l) + r0 * h, h, nullptr, nullptr, 0, gws, H->gemm_ws_bytes, 0, s);
     case B_R4: {
       const bool more = l > 0;  // fuse the dropout backward of the layer below (its BDR2) behind dx
       return launch_layernorm_bwd(wsp<float>(R, "du", l) + r0 * h, peer(P ? P->bwd_attn : nullptr),
@@ -352,7 +352,7 @@ static int run_op(const Run& R, const Op& op) {
     }
     case B_QKV_WGRAD:
       return launch_gemm(OASES_GEMM_TN, 0, h, 3 * hp, Ms, u + r0 * h, h, wsp<uint16_t>(R, "dqkv", l) + r0 * 3 * hp, 3 * hp,
-                         R.g[l].wqkv, 3 * hp, nullptr, nullptr, 0, gws, H->gemm_ws_bytes, s);
+                         R.g[l].wqkv, 3 * hp, nullptr, nullptr, 0, gws, H->gemm_ws_bytes, 0, s);
     case B_BQKV_SUM:
       return launch_colsum_bf16(wsp<uint16_t>(R, "dqkv", l) + r0 * 3 * hp, 3 * hp, Ms, 3 * hp, (float*)R.g[l].bqkv, scr_comp, s);
     // ---------------------------------------------------------------- recompute: the forward kernels again
@@ -600,12 +600,19 @@ int oases_op_gemm(int op, int epi, int M, int N, int K, const void* A, int lda, 
                   const void* bias, void* aux, int ldaux, void* workspace, size_t workspace_bytes, void* stream) {
   if (workspace && !aligned16(workspace)) { set_error("gemm: workspace not 16-byte aligned"); return OASES_EALIGN; }
   return launch_gemm(op, epi, M, N, K, A, lda, B, ldb, C, ldc, (const float*)bias, aux, ldaux, workspace, workspace ? workspace_bytes : 0,
-                     (hipStream_t)stream);
+                     0, (hipStream_t)stream);
+}
+int oases_op_gemm_forced(int variant, int op, int epi, int M, int N, int K, const void* A, int lda, const void* B, int ldb, void* C,
+                         int ldc, const void* bias, void* aux, int ldaux, void* workspace, size_t workspace_bytes, void* stream) {
+  if (workspace && !aligned16(workspace)) { set_error("gemm: workspace not 16-byte aligned"); return OASES_EALIGN; }
+  if (variant <= 0) { set_error("gemm: variant must be positive"); return OASES_EINVAL; }
+  return launch_gemm(op, epi, M, N, K, A, lda, B, ldb, C, ldc, (const float*)bias, aux, ldaux, workspace, workspace ? workspace_bytes : 0,
+                     variant, (hipStream_t)stream);
 }
 int oases_op_gemm_variant(int op, int epi, int M, int N, int K, size_t workspace_bytes) {
   (void)epi;
   if (op < 0 || op > 2 || M <= 0 || N <= 0 || K <= 0) { set_error("oases_op_gemm_variant: bad argument"); return OASES_EINVAL; }
-  return gemm_variant(op, M, N, K, workspace_bytes);
+  return gemm_variant(op, epi, M, N, K, workspace_bytes);
 }
 size_t oases_gemm_workspace_bytes(const oases_handle* H) { return H ? H->gemm_ws_bytes : 0; }
 int oases_op_colsum_bf16(const void* a, int ld, int rows, int cols, void* out, void* scratch, void* stream) {

@@ -112,10 +112,12 @@ int launch_layernorm_bwd(const float* part, const float* peer, const float* dres
                          float* dbeta, void* dz, float* dbias, int rows, int h, const DropCfg& d,
                          int64_t row0, float* scratch, hipStream_t s);
 int launch_colsum_bf16(const void* a, int ld, int rows, int cols, float* out, float* scratch, hipStream_t s);
-// splitk_ws: optional fp32 scratch for split-K partial planes (NULL: never split)
+// splitk_ws: optional fp32 scratch for split-K partial planes (NULL: never split); forced_variant: 0 = choose, else
+// the instantiation to launch, encoded as gemm_variant() returns it
 int launch_gemm(int op, int epi, int M, int N, int K, const void* A, int lda, const void* B, int ldb, void* C,
-                int ldc, const float* bias, void* aux, int ldaux, void* splitk_ws, size_t splitk_ws_bytes, hipStream_t s);
-int gemm_variant(int op, int M, int N, int K, size_t ws_bytes);  // ksplit*1e6 + BM*1e3 + BN
+                int ldc, const float* bias, void* aux, int ldaux, void* splitk_ws, size_t splitk_ws_bytes, int forced_variant,
+                hipStream_t s);
+int gemm_variant(int op, int epi, int M, int N, int K, size_t ws_bytes);  // 1e8*[waves split k] + 1e6*slices + 1e3*BM + BN
 constexpr size_t kSplitKWorkspaceBytes = 256u << 20;
 int launch_attention_fwd(const void* qkv, void* out, float* lse, int batch, int seq, int heads, int head_dim,
                          int causal, int row0, int rows, hipStream_t s);

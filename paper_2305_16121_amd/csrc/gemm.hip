@@ -111,11 +111,17 @@ enum { EPI_F32 = 0, EPI_BF16 = 1, EPI_BIAS_BF16 = 2, EPI_BIAS_GELU = 3, EPI_DGEL
 // instruction-group hints for the machine scheduler (kinds: 0x8 MFMA, 0x20 VMEM read, 0x100 LDS read, 0x200 LDS write)
 #define SGB(mask, n) __builtin_amdgcn_sched_group_barrier(mask, n, 0)
 
-template <int BM, int BN, int WGM, int WGN, bool A_KC, bool B_KC, int EPI, bool FULL>
+// Waves of a workgroup form a WGM x WGN x WGK grid: a wave owns a (BM/WGM) x (BN/WGN) part of the block tile and,
+// when WGK > 1, every WGK-th pair of the 16-wide k steps of each stage; the WGK partial accumulators of a part are
+// added through LDS after the k loop, in a fixed order.  Splitting k inside the workgroup instead of the tile keeps
+// the wave tile at 128 x 128 for the rectangular block tiles, which is what bounds the LDS bytes read per MFMA.
+template <int BM, int BN, int WGM, int WGN, int WGK, bool A_KC, bool B_KC, int EPI, bool FULL>
 __device__ __forceinline__ void gemm_tile(const GemmArgs& g, char* lds, int m0, int n0) {
-  constexpr int NT = 64 * WGM * WGN;
+  constexpr int NT = 64 * WGM * WGN * WGK;
   constexpr int WTM = BM / WGM, WTN = BN / WGN;
   constexpr int TM = WTM / 32, TN = WTN / 32;
+  constexpr int KS = (BK / 16) / WGK;  // k steps of one stage that a wave multiplies
+  static_assert(WGK == 1 || (KS == 2 && TM * TN >= 16), "k split inside the workgroup: two steps per wave, deep pipeline");
   using LA = TileLayout<BM, A_KC>;
   using LB = TileLayout<BN, B_KC>;
   constexpr int NA = LA::chunks / NT, NB = LB::chunks / NT;
@@ -124,7 +130,7 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, char* lds, int m0, 
   constexpr int NMFMA = TM * TN;
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int wm = wave / WGN, wn = wave % WGN;
+  const int wk = wave / (WGM * WGN), wm = (wave / WGN) % WGM, wn = wave % WGN;
 
   f32x16 acc[TM][TN];
 #pragma unroll
@@ -146,9 +152,9 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, char* lds, int m0, 
     const char* la = lds + stage * kStage;
     const char* lb = la + LA::bytes;
 #pragma unroll
-    for (int i = 0; i < TM; i++) fa[buf][i] = read_frag<BM, A_KC>(la, wm * WTM + i * 32, kk, lane);
+    for (int i = 0; i < TM; i++) fa[buf][i] = read_frag<BM, A_KC>(la, wm * WTM + i * 32, wk * KS + kk, lane);
 #pragma unroll
-    for (int j = 0; j < TN; j++) fb[buf][j] = read_frag<BN, B_KC>(lb, wn * WTN + j * 32, kk, lane);
+    for (int j = 0; j < TN; j++) fb[buf][j] = read_frag<BN, B_KC>(lb, wn * WTN + j * 32, wk * KS + kk, lane);
   };
   // the B fragment is the first MFMA operand: the accumulator then holds C^T, i.e. a lane owns 4 consecutive
   // columns of one row of C per group of four accumulator elements (16-byte stores in the epilogue)
@@ -169,18 +175,26 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, char* lds, int m0, 
     }
   };
 
-  if constexpr (BM * BN >= 256 * 256) {
-    // Pipeline.  While tile kt is multiplied out of stage kt&1, tile kt+1 sits in the other stage.  The A half of
-    // tile kt+2 is written into stage kt&1 right behind the barrier of iteration kt (which releases that stage), the
-    // B half during the first k step of iteration kt+1; each half's registers are refilled from global memory right
-    // behind its LDS store, a whole iteration ahead of the next store.  LDS stores and global loads are thus spread
-    // over two k steps and never wait at the top of the loop.
+  if constexpr (TM * TN >= 16) {
+    // Pipeline.  While tile kt is multiplied out of stage kt&1, tile kt+1 sits in the other stage.  One operand's half
+    // of tile kt+2 is written into stage kt&1 right behind the barrier of iteration kt (which releases that stage),
+    // the other's during the first k step of iteration kt+1; each half's registers are refilled from global memory
+    // right behind its LDS store, a whole iteration ahead of the next store.  LDS stores and global loads are thus
+    // spread over two k steps and never wait at the top of the loop.
+    // "early" half: stored during the first k step, "late" half: stored behind the barrier, where it competes with the
+    // first fragment reads of the next stage -- the smaller operand tile goes there.
+    constexpr bool LATE_A = BM <= BN;
+    constexpr int N_EARLY = LATE_A ? NB : NA, N_LATE = LATE_A ? NA : NB;
+    auto fetch_early = [&](int kt) { if constexpr (LATE_A) fetch_b(kt); else fetch_a(kt); };
+    auto fetch_late = [&](int kt) { if constexpr (LATE_A) fetch_a(kt); else fetch_b(kt); };
+    auto park_early = [&](int stage) { if constexpr (LATE_A) park_b(stage); else park_a(stage); };
+    auto park_late = [&](int stage) { if constexpr (LATE_A) park_a(stage); else park_b(stage); };
     fetch_a(0);
     fetch_b(0);
     park_a(0);
     park_b(0);
-    if (nk > 1) { fetch_a(1); park_a(1); fetch_b(1); }
-    if (nk > 2) fetch_a(2);
+    if (nk > 1) { fetch_late(1); park_late(1); fetch_early(1); }
+    if (nk > 2) fetch_late(2);
     __syncthreads();
     frags(0, 0, 0);
 
@@ -189,35 +203,37 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, char* lds, int m0, 
     auto iteration = [&](auto m1_c, auto m2_c, auto m3_c, int kt) {
       constexpr bool M1 = decltype(m1_c)::value, M2 = decltype(m2_c)::value, M3 = decltype(m3_c)::value;
       const int cur = kt & 1;
-      if (M1) park_b(cur ^ 1);     // B half of tile kt+1 (the stage was released by the previous barrier)
-      if (M2) fetch_b(kt + 2);
+      if (M1) park_early(cur ^ 1);  // early half of tile kt+1 (the stage was released by the previous barrier)
+      if (M2) fetch_early(kt + 2);
       frags(cur, 1, 1);
       mma(0);
   #pragma unroll
       for (int i = 0; i < NMFMA; i++) {
         SGB(0x008, 1);
         SGB(0x100, (NREAD + NMFMA - 1) / NMFMA);
-        if (M1) SGB(0x200, (NB + NMFMA - 1) / NMFMA);
-        if (M2) SGB(0x020, (NB + NMFMA - 1) / NMFMA);
+        if (M1) SGB(0x200, (N_EARLY + NMFMA - 1) / NMFMA);
+        if (M2) SGB(0x020, (N_EARLY + NMFMA - 1) / NMFMA);
       }
-      frags(cur, 2, 0);
-      mma(1);
-      hint_step();
-      frags(cur, 3, 1);
-      mma(0);
-      hint_step();
+      if (KS == 4) {
+        frags(cur, 2, 0);
+        mma(1);
+        hint_step();
+        frags(cur, 3, 1);
+        mma(0);
+        hint_step();
+      }
       // every wave has its last fragments of stage `cur` in registers, and stage cur^1 (tile kt+1) is complete
       __syncthreads();
       if (M1) frags(cur ^ 1, 0, 0);
-      if (M2) park_a(cur);         // A half of tile kt+2 -> the stage just released
-      if (M3) fetch_a(kt + 3);
+      if (M2) park_late(cur);       // late half of tile kt+2 -> the stage just released
+      if (M3) fetch_late(kt + 3);
       mma(1);
   #pragma unroll
       for (int i = 0; i < NMFMA; i++) {
         SGB(0x008, 1);
         if (M1) SGB(0x100, (NREAD + NMFMA - 1) / NMFMA);
-        if (M2) SGB(0x200, (NA + NMFMA - 1) / NMFMA);
-        if (M3) SGB(0x020, (NA + NMFMA - 1) / NMFMA);
+        if (M2) SGB(0x200, (N_LATE + NMFMA - 1) / NMFMA);
+        if (M3) SGB(0x020, (N_LATE + NMFMA - 1) / NMFMA);
       }
     };
     using T_ = std::true_type;
@@ -271,51 +287,96 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, char* lds, int m0, 
     iteration(F_{}, F_{}, kt);
   }
 
-  // epilogue: accumulator element e of tile (i,j) is C[row][col + (e&3)] with
+  // epilogue of one 32 x 32 accumulator tile (i,j) of this wave: element e is C[row][col + (e&3)] with
   //   row = m0 + wm*WTM + 32 i + (lane & 31),  col = n0 + wn*WTN + 32 j + 8 (e>>2) + 4 (lane>>5)
-#pragma unroll
-  for (int i = 0; i < TM; i++) {
+  auto emit = [&](int i, int j, const f32x16& a) {
     const int row = m0 + wm * WTM + i * 32 + (lane & 31);
-    if (!FULL && row >= g.M) continue;
+    if (!FULL && row >= g.M) return;
 #pragma unroll
-    for (int j = 0; j < TN; j++) {
+    for (int q = 0; q < 4; q++) {
+      const int col = n0 + wn * WTN + j * 32 + 8 * q + 4 * (lane >> 5);
+      if (!FULL && col >= g.N) continue;
+      f32x4 v = {a[4 * q], a[4 * q + 1], a[4 * q + 2], a[4 * q + 3]};
+      const size_t o = (size_t)row * g.ldc + col;
+      if (EPI == EPI_F32) {
+        *reinterpret_cast<f32x4*>(reinterpret_cast<float*>(g.C) + o) = v;
+      } else if (EPI == EPI_ACC_F32) {
+        f32x4* p = reinterpret_cast<f32x4*>(reinterpret_cast<float*>(g.C) + o);
+        *p = *p + v;
+      } else {
+        uint16_t* cp = reinterpret_cast<uint16_t*>(g.C) + o;
+        if (EPI == EPI_BIAS_BF16 || EPI == EPI_BIAS_GELU) v += *reinterpret_cast<const f32x4*>(g.bias + col);
+        if (EPI == EPI_BIAS_GELU) {
+          *reinterpret_cast<u32x2*>(g.aux + (size_t)row * g.ldaux + col) = u32x2{pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3])};
 #pragma unroll
-      for (int q = 0; q < 4; q++) {
-        const int col = n0 + wn * WTN + j * 32 + 8 * q + 4 * (lane >> 5);
-        if (!FULL && col >= g.N) continue;
-        f32x4 v = {acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]};
-        const size_t o = (size_t)row * g.ldc + col;
-        if (EPI == EPI_F32) {
-          *reinterpret_cast<f32x4*>(reinterpret_cast<float*>(g.C) + o) = v;
-        } else if (EPI == EPI_ACC_F32) {
-          f32x4* p = reinterpret_cast<f32x4*>(reinterpret_cast<float*>(g.C) + o);
-          *p = *p + v;
-        } else {
-          uint16_t* cp = reinterpret_cast<uint16_t*>(g.C) + o;
-          if (EPI == EPI_BIAS_BF16 || EPI == EPI_BIAS_GELU) v += *reinterpret_cast<const f32x4*>(g.bias + col);
-          if (EPI == EPI_BIAS_GELU) {
-            *reinterpret_cast<u32x2*>(g.aux + (size_t)row * g.ldaux + col) = u32x2{pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3])};
-#pragma unroll
-            for (int e = 0; e < 4; e++) v[e] = gelu_tanh(v[e]);
-          } else if (EPI == EPI_DGELU) {
-            u32x2 a = *reinterpret_cast<const u32x2*>(g.aux + (size_t)row * g.ldaux + col);
-            v[0] *= gelu_tanh_grad(bf16_bits_to_f32(a[0] & 0xffffu));
-            v[1] *= gelu_tanh_grad(bf16_bits_to_f32(a[0] >> 16));
-            v[2] *= gelu_tanh_grad(bf16_bits_to_f32(a[1] & 0xffffu));
-            v[3] *= gelu_tanh_grad(bf16_bits_to_f32(a[1] >> 16));
-          }
-          *reinterpret_cast<u32x2*>(cp) = u32x2{pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3])};
+          for (int e = 0; e < 4; e++) v[e] = gelu_tanh(v[e]);
+        } else if (EPI == EPI_DGELU) {
+          u32x2 x = *reinterpret_cast<const u32x2*>(g.aux + (size_t)row * g.ldaux + col);
+          v[0] *= gelu_tanh_grad(bf16_bits_to_f32(x[0] & 0xffffu));
+          v[1] *= gelu_tanh_grad(bf16_bits_to_f32(x[0] >> 16));
+          v[2] *= gelu_tanh_grad(bf16_bits_to_f32(x[1] & 0xffffu));
+          v[3] *= gelu_tanh_grad(bf16_bits_to_f32(x[1] >> 16));
         }
+        *reinterpret_cast<u32x2*>(cp) = u32x2{pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3])};
       }
     }
+  };
+
+  if constexpr (WGK == 1) {
+#pragma unroll
+    for (int i = 0; i < TM; i++)
+#pragma unroll
+      for (int j = 0; j < TN; j++) emit(i, j, acc[i][j]);
+  } else {
+    // The two waves that hold the k halves of one part each finish one half of its rows: a wave hands the
+    // accumulator tiles of the other half over through LDS (lane-for-lane, 16 bytes per lane and store) and adds what
+    // it receives to its own; the sum of two terms does not depend on which of them is "own".
+    static_assert(WGK == 2 && TM % 2 == 0, "pairwise exchange");
+    constexpr int HM = TM / 2;
+    f32x4* xch = reinterpret_cast<f32x4*>(lds);
+    const int mine = wave * (HM * TN * 4), theirs = (wave ^ (WGM * WGN)) * (HM * TN * 4);
+    __syncthreads();  // every wave is done with the operand stages
+    auto hand_over = [&](auto half_c) {  // half_c: which half of the tile rows leaves this wave
+      constexpr int H = decltype(half_c)::value;
+#pragma unroll
+      for (int i = 0; i < HM; i++)
+#pragma unroll
+        for (int j = 0; j < TN; j++)
+#pragma unroll
+          for (int q = 0; q < 4; q++) {
+            const f32x16& a = acc[H * HM + i][j];
+            xch[(mine + (i * TN + j) * 4 + q) * 64 + lane] = f32x4{a[4 * q], a[4 * q + 1], a[4 * q + 2], a[4 * q + 3]};
+          }
+    };
+    auto finish = [&](auto half_c) {  // half_c: which half of the tile rows this wave keeps
+      constexpr int H = decltype(half_c)::value;
+#pragma unroll
+      for (int i = 0; i < HM; i++)
+#pragma unroll
+        for (int j = 0; j < TN; j++) {
+          f32x16 a = acc[H * HM + i][j];
+#pragma unroll
+          for (int q = 0; q < 4; q++) {
+            const f32x4 o = xch[(theirs + (i * TN + j) * 4 + q) * 64 + lane];
+#pragma unroll
+            for (int e = 0; e < 4; e++) a[4 * q + e] += o[e];
+          }
+          emit(H * HM + i, j, a);
+        }
+    };
+    if (wk == 0) hand_over(std::integral_constant<int, 1>{}); else hand_over(std::integral_constant<int, 0>{});
+    __syncthreads();
+    if (wk == 0) finish(std::integral_constant<int, 0>{}); else finish(std::integral_constant<int, 1>{});
   }
 }
 
-template <int BM, int BN, int WGM, int WGN, bool A_KC, bool B_KC, int EPI>
-__global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmArgs g) {  // g: by value, adjusted per k slice
+template <int BM, int BN, int WGM, int WGN, int WGK, bool A_KC, bool B_KC, int EPI>
+__global__ __launch_bounds__(64 * WGM * WGN * WGK) void gemm_kernel(GemmArgs g) {  // g: by value, adjusted per k slice
   using LA = TileLayout<BM, A_KC>;
   using LB = TileLayout<BN, B_KC>;
-  __shared__ __attribute__((aligned(16))) char lds[2 * (LA::bytes + LB::bytes)];
+  constexpr int kStages = 2 * (LA::bytes + LB::bytes);
+  constexpr int kExchange = WGK > 1 ? BM * BN * 4 : 0;  // half of every wave's accumulator
+  __shared__ __attribute__((aligned(16))) char lds[kStages > kExchange ? kStages : kExchange];
 
   // workgroup -> (k slice, tile): undo the round-robin of workgroup ids over the 8 XCDs so that each XCD's L2 sees a
   // contiguous range of tiles, then walk that range in groups of 8 tile rows.
@@ -343,8 +404,8 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmArgs g) {  // 
   }
   const int m0 = tile_m * BM, n0 = tile_n * BN;
   const bool full = (m0 + BM <= g.M) && (n0 + BN <= g.N) && (g.K % BK == 0);
-  if (full) gemm_tile<BM, BN, WGM, WGN, A_KC, B_KC, EPI, true>(g, lds, m0, n0);
-  else gemm_tile<BM, BN, WGM, WGN, A_KC, B_KC, EPI, false>(g, lds, m0, n0);
+  if (full) gemm_tile<BM, BN, WGM, WGN, WGK, A_KC, B_KC, EPI, true>(g, lds, m0, n0);
+  else gemm_tile<BM, BN, WGM, WGN, WGK, A_KC, B_KC, EPI, false>(g, lds, m0, n0);
 }
 
 // split-K second pass: C = epilogue(sum over slices of the fp32 partial planes), slices added in index order
@@ -381,26 +442,27 @@ __global__ __launch_bounds__(256) void splitk_fixup_kernel(const float* __restri
   }
 }
 
-template <int BM, int BN, int WGM, int WGN, bool A_KC, bool B_KC, int EPI>
+template <int BM, int BN, int WGM, int WGN, int WGK, bool A_KC, bool B_KC, int EPI>
 int launch_one(const GemmArgs& g0, int ksplit, float* ws, hipStream_t s) {
   GemmArgs g = g0;
   g.tiles_m = (g.M + BM - 1) / BM;
   g.tiles_n = (g.N + BN - 1) / BN;
   g.ksplit = 1;
   g.k_per = g.K;
-  dim3 block(64 * WGM * WGN);
+  dim3 block(64 * WGM * WGN * WGK);
   if (ksplit <= 1) {
-    hipLaunchKernelGGL((gemm_kernel<BM, BN, WGM, WGN, A_KC, B_KC, EPI>), dim3(g.tiles_m * g.tiles_n), block, 0, s, g);
+    hipLaunchKernelGGL((gemm_kernel<BM, BN, WGM, WGN, WGK, A_KC, B_KC, EPI>), dim3(g.tiles_m * g.tiles_n), block, 0, s, g);
     OASES_LAUNCH_CHECK("gemm_kernel");
     return 0;
   }
   // first pass: fp32 partial planes [ksplit][M][N] in the workspace; second pass: sum + the real epilogue
+  if (!ws) { set_error("gemm: split-K chosen without a workspace"); return OASES_ENULL; }
   GemmArgs p = g;
   p.ksplit = ksplit;
   p.k_per = ((g.K + ksplit - 1) / ksplit + BK - 1) / BK * BK;
   p.C = ws;
   p.ldc = g.N;
-  hipLaunchKernelGGL((gemm_kernel<BM, BN, WGM, WGN, A_KC, B_KC, EPI_F32>), dim3(g.tiles_m * g.tiles_n * ksplit), block, 0, s, p);
+  hipLaunchKernelGGL((gemm_kernel<BM, BN, WGM, WGN, WGK, A_KC, B_KC, EPI_F32>), dim3(g.tiles_m * g.tiles_n * ksplit), block, 0, s, p);
   OASES_LAUNCH_CHECK("gemm_kernel (split-K)");
   const long n4 = (long)g.M * (g.N / 4);
   hipLaunchKernelGGL((splitk_fixup_kernel<EPI>), dim3((unsigned)((n4 + 255) / 256)), dim3(256), 0, s, ws, ksplit, g);
@@ -411,10 +473,16 @@ int launch_one(const GemmArgs& g0, int ksplit, float* ws, hipStream_t s) {
 // Tile and split-K choice by a small time model.  Bigger tiles run closer to the MFMA rate (fewer LDS bytes per flop)
 // but a launch only uses the chip well if its workgroup count is near a multiple of the 256 CUs; splitting K multiplies
 // the workgroup count at the price of a second pass over fp32 partial planes.  Rates measured on this part.
-struct TileChoice { int bm, bn, ksplit; };
-TileChoice pick_tile(int M, int N, int K, size_t ws_bytes) {
-  static const struct { int bm, bn; float tflops; } cand[] = {{256, 256, 1150.f}, {256, 128, 880.f}, {128, 256, 880.f}, {128, 128, 740.f}};
-  TileChoice best{128, 128, 1};
+struct TileChoice { int bm, bn, ksplit; bool wave_ksplit; };
+// per kind of contraction (0: NN, 1: NT, 2: TN, 3: NN with the bias+GeLU epilogue): whether the rectangular tiles
+// split k between waves, and the sustained rates of the four block tiles
+struct KindTable { bool wave_ksplit; float r256x256, r128x256, r256x128, r128x128; };
+const KindTable g_kinds[4] = {{true, 1150.f, 1000.f, 960.f, 740.f}, {true, 1150.f, 1000.f, 960.f, 740.f},
+                        {true, 1150.f, 1000.f, 960.f, 740.f}, {false, 1150.f, 880.f, 900.f, 740.f}};
+TileChoice pick_tile(int kind, int M, int N, int K, size_t ws_bytes) {
+  const KindTable& kt = g_kinds[kind];
+  const struct { int bm, bn; float tflops; } cand[] = {{256, 256, kt.r256x256}, {128, 256, kt.r128x256}, {256, 128, kt.r256x128}, {128, 128, kt.r128x128}};
+  TileChoice best{128, 128, 1, kt.wave_ksplit};
   double best_t = 1e30;
   for (auto& c : cand) {
     const long tm = (M + c.bm - 1) / c.bm, tn = (N + c.bn - 1) / c.bn;
@@ -424,31 +492,60 @@ TileChoice pick_tile(int M, int N, int K, size_t ws_bytes) {
       // time of one workgroup's tile slice at the tile's rate (one workgroup per CU), times the number of rounds
       double t = (double)rounds * (2.0 * c.bm * c.bn * ((double)K / S) + 3.0e6) / (c.tflops * 1e12 / 256.0);
       if (S > 1) t += ((double)(2 * S + 1) * M * N * 4.0) / 3.0e12 + 4e-6;
-      if (t < best_t) { best_t = t; best = TileChoice{c.bm, c.bn, S}; }
+      if (t < best_t) { best_t = t; best = TileChoice{c.bm, c.bn, S, kt.wave_ksplit}; }
     }
   }
   return best;
 }
 
+int encode_variant(const TileChoice& t) {
+  const bool rect = t.bm != t.bn;
+  return (rect && t.wave_ksplit ? 100000000 : 0) + t.ksplit * 1000000 + t.bm * 1000 + t.bn;
+}
+// variant -> TileChoice; false if no such instantiation exists or the k slices do not fit the problem / workspace
+bool decode_variant(int variant, int M, int N, int K, size_t ws_bytes, TileChoice* t) {
+  if (variant <= 0) return false;
+  const int wk = variant / 100000000, S = variant / 1000000 % 100, bm = variant / 1000 % 1000, bn = variant % 1000;
+  const bool square = (bm == 256 && bn == 256) || (bm == 128 && bn == 128), rect = (bm == 256 && bn == 128) || (bm == 128 && bn == 256);
+  if (wk > 1 || !(square || rect) || (wk == 1 && !rect) || S < 1 || S > 8) return false;
+  if (S > 1) {
+    const int k_per = ((K + S - 1) / S + BK - 1) / BK * BK;
+    if ((size_t)S * M * N * 4 > ws_bytes || (long)(S - 1) * k_per >= K) return false;
+  }
+  *t = TileChoice{bm, bn, S, wk == 1};
+  return true;
+}
+
 template <bool A_KC, bool B_KC, int EPI>
-int launch_shape(const GemmArgs& g, float* ws, size_t ws_bytes, hipStream_t s) {
-  TileChoice t = pick_tile(g.M, g.N, g.K, ws ? ws_bytes : 0);
-  if (t.bm == 256 && t.bn == 256) return launch_one<256, 256, 2, 2, A_KC, B_KC, EPI>(g, t.ksplit, ws, s);
-  if (t.bm == 256 && t.bn == 128) return launch_one<256, 128, 2, 2, A_KC, B_KC, EPI>(g, t.ksplit, ws, s);
-  if (t.bm == 128 && t.bn == 256) return launch_one<128, 256, 2, 2, A_KC, B_KC, EPI>(g, t.ksplit, ws, s);
-  return launch_one<128, 128, 2, 2, A_KC, B_KC, EPI>(g, t.ksplit, ws, s);
+int launch_shape(const GemmArgs& g, float* ws, size_t ws_bytes, int forced_variant, hipStream_t s) {
+  constexpr int kind = !A_KC ? 2 : B_KC ? 1 : EPI == EPI_BIAS_GELU ? 3 : 0;
+  TileChoice t;
+  if (forced_variant == 0) {
+    t = pick_tile(kind, g.M, g.N, g.K, ws ? ws_bytes : 0);
+  } else if (!decode_variant(forced_variant, g.M, g.N, g.K, ws ? ws_bytes : 0, &t)) {
+    set_error("gemm: variant %d does not exist or does not fit M=%d N=%d K=%d with %zu workspace bytes", forced_variant, g.M, g.N, g.K, ws ? ws_bytes : (size_t)0);
+    return OASES_EINVAL;
+  }
+  if (t.bm == 256 && t.bn == 256) return launch_one<256, 256, 2, 2, 1, A_KC, B_KC, EPI>(g, t.ksplit, ws, s);
+  if (!t.wave_ksplit) {
+    if (t.bm == 256 && t.bn == 128) return launch_one<256, 128, 2, 2, 1, A_KC, B_KC, EPI>(g, t.ksplit, ws, s);
+    if (t.bm == 128 && t.bn == 256) return launch_one<128, 256, 2, 2, 1, A_KC, B_KC, EPI>(g, t.ksplit, ws, s);
+  }
+  if (t.bm == 256 && t.bn == 128) return launch_one<256, 128, 2, 1, 2, A_KC, B_KC, EPI>(g, t.ksplit, ws, s);
+  if (t.bm == 128 && t.bn == 256) return launch_one<128, 256, 1, 2, 2, A_KC, B_KC, EPI>(g, t.ksplit, ws, s);
+  return launch_one<128, 128, 2, 2, 1, A_KC, B_KC, EPI>(g, t.ksplit, ws, s);
 }
 
 }  // namespace
 
-int gemm_variant(int op, int M, int N, int K, size_t ws_bytes) {
-  (void)op;
-  TileChoice t = pick_tile(M, N, K, ws_bytes);
-  return t.ksplit * 1000000 + t.bm * 1000 + t.bn;
+int gemm_variant(int op, int epi, int M, int N, int K, size_t ws_bytes) {
+  const int kind = op == OASES_GEMM_TN ? 2 : op == OASES_GEMM_NT ? 1 : epi == EPI_BIAS_GELU ? 3 : 0;
+  return encode_variant(pick_tile(kind, M, N, K, ws_bytes));
 }
 
 int launch_gemm(int op, int epi, int M, int N, int K, const void* A, int lda, const void* B, int ldb, void* C,
-                int ldc, const float* bias, void* aux, int ldaux, void* splitk_ws, size_t splitk_ws_bytes, hipStream_t s) {
+                int ldc, const float* bias, void* aux, int ldaux, void* splitk_ws, size_t splitk_ws_bytes, int forced_variant,
+                hipStream_t s) {
   float* ws = reinterpret_cast<float*>(splitk_ws);
   const size_t wsb = splitk_ws_bytes;
   if (M <= 0 || N <= 0 || K <= 0 || (M % 8) || (N % 8) || (K % 8) || (lda % 8) || (ldb % 8) || (ldc % 4) || (aux && ldaux % 4)) {
@@ -460,7 +557,7 @@ int launch_gemm(int op, int epi, int M, int N, int K, const void* A, int lda, co
   GemmArgs g{(const uint16_t*)A, (const uint16_t*)B, C, bias, (uint16_t*)aux, M, N, K, lda, ldb, ldc, ldaux, 0, 0, 1, K};
   if (op == OASES_GEMM_TN) {
     if (lda < M || ldb < N || ldc < N) { set_error("gemm TN: leading dimension too small"); return OASES_EINVAL; }
-    return launch_shape<false, false, EPI_ACC_F32>(g, ws, wsb, s);
+    return launch_shape<false, false, EPI_ACC_F32>(g, ws, wsb, forced_variant, s);
   }
   const bool nn = op == OASES_GEMM_NN;
   if (!nn && op != OASES_GEMM_NT) { set_error("gemm: unknown op %d", op); return OASES_EINVAL; }
@@ -469,7 +566,7 @@ int launch_gemm(int op, int epi, int M, int N, int K, const void* A, int lda, co
   if ((epi == OASES_EPI_BIAS_GELU || epi == OASES_EPI_DGELU) && (!aux || ldaux < N)) { set_error("gemm: GeLU epilogue without aux"); return OASES_ENULL; }
 #define OASES_GEMM_CASE(E)                                                   \
   case E:                                                                    \
-    return nn ? launch_shape<true, false, E>(g, ws, wsb, s) : launch_shape<true, true, E>(g, ws, wsb, s);
+    return nn ? launch_shape<true, false, E>(g, ws, wsb, forced_variant, s) : launch_shape<true, true, E>(g, ws, wsb, forced_variant, s);
   switch (epi) {
     OASES_GEMM_CASE(EPI_F32)
     OASES_GEMM_CASE(EPI_BF16)

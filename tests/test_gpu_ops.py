@@ -191,6 +191,61 @@ def test_gemm_plain(B, M, N, K, op):
     assert rel_err(c, ref) < 1e-5, (op, M, N, K)     # exact products of bf16 values, fp32 accumulation
 
 
+GEMM_VARIANTS = [1256256, 1128256, 1256128, 101128256, 101256128, 1128128, 2256256, 102128256, 102256128, 3128128]
+
+
+@pytest.mark.parametrize("variant", GEMM_VARIANTS)
+@pytest.mark.parametrize("op", ["NN", "NT", "TN"])
+def test_gemm_every_variant(B, lo, op, variant):
+    """Every compiled instantiation (block tile, wave grid, k slices), named explicitly, on a shape with several tiles
+    in both directions, ragged edges and a ragged k tail; plus the bias+GeLU / dGeLU epilogues of the same variant."""
+    M, N, K = 776, 1032, 712
+    g = gen(variant % 1000 + variant // 1000000)
+    a, b = bf16_round(randn(g, M, K)), bf16_round(randn(g, K, N, scale=0.05))
+    ref = a @ b
+    ws = torch.full((32 << 20,), 0xFF, dtype=torch.uint8, device="cuda")
+    opc = {"NN": B.GEMM_NN, "NT": B.GEMM_NT, "TN": B.GEMM_TN}[op]
+    ad = dev(a if op != "TN" else a.t().contiguous(), torch.bfloat16)
+    bd = dev(b if op != "NT" else b.t().contiguous(), torch.bfloat16)
+    lda, ldb = (K if op != "TN" else M), (N if op != "NT" else K)
+    c = torch.full((M, N), 0.5, dtype=torch.float32, device="cuda")
+    B.check(B.lib.oases_op_gemm_forced(variant, opc, B.EPI_F32, M, N, K, ad.data_ptr(), lda, bd.data_ptr(), ldb, c.data_ptr(), N, None, None, 0,
+                                       ws.data_ptr(), ws.numel(), None))
+    assert rel_err(c, ref + (0.5 if op == "TN" else 0.0)) < 1e-5, (op, variant)
+    if op == "TN":
+        return
+    bias = dev(0.1 * randn(g, N), torch.float32)
+    pre = dev(bf16_round(randn(g, M, N)), torch.bfloat16)
+    cb = torch.empty(M, N, dtype=torch.bfloat16, device="cuda")
+    if op == "NN":
+        aux = torch.empty(M, N, dtype=torch.bfloat16, device="cuda")
+        B.check(B.lib.oases_op_gemm_forced(variant, opc, B.EPI_BIAS_GELU, M, N, K, ad.data_ptr(), lda, bd.data_ptr(), ldb, cb.data_ptr(), N,
+                                           bias.data_ptr(), aux.data_ptr(), N, ws.data_ptr(), ws.numel(), None))
+        z = ref + bias.cpu().double()
+        assert_bf16_close(aux.float(), z, 1e-5, 2e-6 * float(z.abs().max()))
+        assert_bf16_close(cb.float(), lo.gelu_fwd(z), 1e-4, 1e-5)
+    else:
+        B.check(B.lib.oases_op_gemm_forced(variant, opc, B.EPI_DGELU, M, N, K, ad.data_ptr(), lda, bd.data_ptr(), ldb, cb.data_ptr(), N,
+                                           None, pre.data_ptr(), N, ws.data_ptr(), ws.numel(), None))
+        assert_bf16_close(cb.float(), ref * lo.gelu_grad(pre.float().cpu().double()), 1e-4, 1e-5)
+
+
+def test_gemm_forced_variant_errors(B):
+    """Variants that do not exist, k slices that do not fit K or the workspace: EINVAL before any launch."""
+    M = N = K = 256
+    a = torch.zeros(M, K, dtype=torch.bfloat16, device="cuda")
+    c = torch.zeros(M, N, dtype=torch.float32, device="cuda")
+    ws = torch.zeros(1 << 20, dtype=torch.uint8, device="cuda")
+    call = lambda v, wsb: B.lib.oases_op_gemm_forced(v, B.GEMM_NN, B.EPI_F32, M, N, K, a.data_ptr(), K, a.data_ptr(), N, c.data_ptr(), N, None, None, 0,
+                                                     ws.data_ptr(), wsb, None)
+    assert call(1128128, ws.numel()) == 0
+    for bad in (0, -5, 1192192, 1064064, 101256256, 101128128, 201128256, 9128128, 128128):
+        assert call(bad, ws.numel()) == B.EINVAL, bad
+    assert call(2128128, 1024) == B.EINVAL           # workspace too small for two planes
+    assert call(8128128, ws.numel()) == B.EINVAL     # 8 slices of 64 do not all start inside K = 256
+    torch.cuda.synchronize()
+
+
 @pytest.mark.parametrize("M,N,K", [(384, 768, 512), (136, 264, 72), (2048, 2048, 256)])
 def test_gemm_epilogues(B, lo, M, N, K):
     g = gen(7)
@@ -227,7 +282,7 @@ def test_gemm_split_k(B, lo, op, epi, M, N, K):
     ws = torch.full((64 << 20,), 0xFF, dtype=torch.uint8, device="cuda")
     opc = {"NN": B.GEMM_NN, "NT": B.GEMM_NT, "TN": B.GEMM_TN}[op]
     variant = B.lib.oases_op_gemm_variant(opc, 0, M, N, K, ws.numel())
-    assert variant >= 2000000, f"shape was expected to split K, got {variant}"
+    assert variant // 1000000 % 100 >= 2, f"shape was expected to split K, got {variant}"
     ad = dev(a if op != "TN" else a.t().contiguous(), torch.bfloat16)
     bd = dev(b if op != "NT" else b.t().contiguous(), torch.bfloat16)
     lda = K if op != "TN" else M
