@@ -46,7 +46,8 @@ enum {
   OASES_ENULL = -2,      /* required pointer is NULL */
   OASES_EALIGN = -3,     /* device pointer not 16-byte aligned */
   OASES_EWORKSPACE = -4, /* reserved */
-  OASES_EHIP = -5        /* a HIP runtime call failed; text in oases_last_error() */
+  OASES_EHIP = -5,       /* a HIP runtime call failed; text in oases_last_error() */
+  OASES_EINFEASIBLE = -6 /* planner: no strategy satisfies the constraints */
 };
 
 /* Layer and schedule configuration.  The layer is a pre-LN GPT block: attention block then FFN

@@ -1,4 +1,4 @@
-"""Compile the HIP sources of this directory for gfx950 into liboases.so (in-tree, next to the package)."""
+"""Compile the sources of this directory (HIP kernels for gfx950, host C++) into liboases.so (in-tree, next to the package)."""
 from __future__ import annotations
 
 import os
@@ -9,7 +9,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 PKG = os.path.dirname(HERE)
 LIB = os.path.join(PKG, "liboases.so")
-SOURCES = ("api.hip", "gemm.hip", "attention.hip", "elementwise.hip")
+SOURCES = ("gemm.hip", "api.hip", "attention.hip", "elementwise.hip", "planner.cc")  # planner.cc: host code only
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wno-unused-command-line-argument", "-fno-gpu-rdc"]
 
@@ -27,7 +27,7 @@ def build(verbose: bool = False, extra: list[str] | None = None) -> str:
     hipcc = _hipcc()
 
     def one(src):
-        obj = os.path.join(objdir, src.replace(".hip", ".o"))
+        obj = os.path.join(objdir, os.path.splitext(src)[0] + ".o")
         cmd = [hipcc, *FLAGS, *(extra or []), "-c", os.path.join(HERE, src), "-o", obj]
         r = subprocess.run(cmd, capture_output=True, text=True)
         err = "\n".join(l for l in r.stderr.splitlines() if "packed-fp32-ops" not in l)
@@ -37,7 +37,7 @@ def build(verbose: bool = False, extra: list[str] | None = None) -> str:
             print(err, file=sys.stderr)
         return obj
 
-    with ThreadPoolExecutor(max_workers=4) as ex:
+    with ThreadPoolExecutor(max_workers=5) as ex:
         objs = list(ex.map(one, SOURCES))
     r = subprocess.run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs], capture_output=True, text=True)
     if r.returncode != 0:

@@ -1,0 +1,126 @@
+"""The library's planner (include/oases_planner.h, host code) against the enumeration oracle of Eq. (2)-(6): random
+chains with every strategy enumerated, with and without the memory bound and ties; cost breakdown of given strategies;
+argument errors.  No GPU."""
+import random
+import time
+
+import numpy as np
+import pytest
+
+from oracle import planner_oracle as po
+from paper_2305_16121_amd import binding as B
+from paper_2305_16121_amd import planner as P
+
+
+def random_problem(rng, n, p, bounded, ties=False, ag=True):
+    vec = lambda lo, hi: [[rng.uniform(lo, hi) for _ in range(p)] for _ in range(n)]
+    q = {"n_nodes": n, "n_strategies": p}
+    # higher scheme index = more shards: less computation, more communication
+    for name in ("d0_f", "d1_f", "d0_b", "d1_b"):
+        q[name] = [[rng.uniform(0.5, 2.0) * (2.0 if name.endswith("b") else 1.0) / (j + 1) for j in range(p)] for _ in range(n)]
+    for name in ("c0_f", "c1_f", "c0_b", "c1_b"):
+        q[name] = [[rng.uniform(0.1, 1.5) * j for j in range(p)] for _ in range(n)]
+    if ag:
+        q["t_ag_f"] = [[[rng.uniform(0.0, 0.4) for _ in range(p)] for _ in range(p)] for _ in range(n - 1)]
+        q["t_ag_b"] = [[[rng.uniform(0.0, 0.4) for _ in range(p)] for _ in range(p)] for _ in range(n - 1)]
+    if bounded:
+        q["m_s"] = [[8.0 / (j + 1) * rng.choice((1.0, 1.0, 2.0)) for j in range(p)] for _ in range(n)]
+        q["m_t"] = vec(0.5, 1.0)
+        q["m_r"] = [rng.uniform(0.5, 3.0) for _ in range(p)]
+        lo = min(po.memory(q, [j] * n) for j in range(p))
+        hi = max(po.memory(q, [j] * n) for j in range(p))
+        q["m"] = rng.uniform(lo * 0.95, hi * 1.05)
+    if ties:
+        q["tie"] = [rng.randint(0, 1) for _ in range(n - 1)]
+    return q
+
+
+@pytest.mark.parametrize("seed", range(40))
+def test_solve_matches_enumeration(seed):
+    rng = random.Random(seed)
+    n, p = rng.randint(1, 7), rng.randint(1, 4)
+    q = random_problem(rng, n, p, bounded=seed % 2 == 1, ties=seed % 4 >= 2, ag=seed % 5 != 0)
+    want_s, want_c = po.brute_force(q)
+    s, c, mem = P.plan_solve(q)
+    if want_s is None:
+        assert s is None
+        return
+    assert s is not None
+    assert c == pytest.approx(want_c, rel=1e-12)                       # the optimum is unique as a value
+    assert po.feasible(q, s)                                           # ... the strategy only has to be one that reaches it
+    assert po.strategy_cost(q, s)["total"] == pytest.approx(c, rel=1e-12)
+    if "m_s" in q:
+        assert mem == pytest.approx(po.memory(q, s), rel=1e-12)
+
+
+@pytest.mark.parametrize("seed", range(10))
+def test_cost_breakdown_matches_definition(seed):
+    rng = random.Random(100 + seed)
+    n, p = rng.randint(1, 9), rng.randint(1, 5)
+    q = random_problem(rng, n, p, bounded=True)
+    for _ in range(5):
+        s = [rng.randrange(p) for _ in range(n)]
+        got, want = P.plan_cost(q, s), po.strategy_cost(q, s)
+        for k in ("tv_f", "tv_b", "edges", "total"):
+            assert got[k] == pytest.approx(want[k], rel=1e-13, abs=1e-300), k
+        assert got["memory"] == pytest.approx(po.memory(q, s), rel=1e-13)
+
+
+def test_uniform_model_prefers_lower_degree_when_memory_allows():
+    """Qualitative behaviour the paper reports (Sec. V-C, Table II): the lower degree (scheme 0) communicates less at
+    equal computation but holds more model states; with a memory bound that does not admit it everywhere, as many
+    layers as fit move to it, in few contiguous groups."""
+    n, p = 16, 2
+    q = {"n_nodes": n, "n_strategies": p}
+    for name, v in (("d0_f", [2.0, 2.0]), ("d1_f", [2.0, 2.0]), ("d0_b", [4.0, 4.0]), ("d1_b", [4.0, 4.0]),
+                    ("c0_f", [0.5, 3.0]), ("c1_f", [0.5, 3.0]), ("c0_b", [0.5, 3.0]), ("c1_b", [0.5, 3.0])):
+        q[name] = [v] * n
+    q["t_ag_f"] = q["t_ag_b"] = np.full((n - 1, p, p), 0.3)
+    q["m_s"], q["m_t"], q["m_r"] = [[10.0, 5.0]] * n, [[1.0, 1.0]] * n, [2.0, 2.0]
+    q["m"] = 2.0 + 16 * 6.0 + 5 * 5.0 + 0.1          # room for five nodes on the memory-hungry scheme 0
+    s, c, mem = P.plan_solve(q)
+    assert sum(1 for x in s if x == 0) == 5 and mem < q["m"]
+    changes = sum(1 for a, b in zip(s, s[1:]) if a != b)
+    assert 1 <= changes <= 2                          # few reshards (the exposed ends of the chain favour scheme 0 too)
+    assert c < P.plan_cost(q, [1] * n)["total"]
+    assert c == pytest.approx(po.strategy_cost(q, s)["total"], rel=1e-12)
+    q["m"] = 0.0
+    assert P.plan_solve(q)[0] == [0] * n              # unbounded: the cheaper scheme everywhere
+
+
+def test_long_chain_is_fast_and_consistent():
+    rng = random.Random(7)
+    q = random_problem(rng, 96, 4, bounded=True)
+    q["m"] = 0.5 * (po.memory(q, [0] * 96) + po.memory(q, [3] * 96))
+    t0 = time.perf_counter()
+    s, c, mem = P.plan_solve(q)
+    dt = time.perf_counter() - t0
+    assert s is not None and dt < 5.0
+    assert po.feasible(q, s) and po.strategy_cost(q, s)["total"] == pytest.approx(c, rel=1e-12)
+    # no single-node change that stays feasible improves it
+    for v in range(96):
+        for j in range(4):
+            t = list(s); t[v] = j
+            if po.feasible(q, t):
+                assert po.strategy_cost(q, t)["total"] >= c * (1 - 1e-12)
+
+
+def test_argument_errors():
+    rng = random.Random(3)
+    q = random_problem(rng, 3, 2, bounded=True)
+    bad = dict(q); bad["d0_f"] = [[-1.0, 1.0]] * 3
+    with pytest.raises(B.OasesError):
+        P.plan_solve(bad)
+    bad = dict(q); bad["c1_b"] = [[float("nan"), 1.0]] * 3
+    with pytest.raises(B.OasesError):
+        P.plan_solve(bad)
+    bad = dict(q); del bad["m_r"]
+    with pytest.raises(B.OasesError):
+        P.plan_solve(bad)
+    with pytest.raises(B.OasesError):
+        P.plan_cost(q, [0, 2, 0])
+    with pytest.raises(ValueError):
+        bad = dict(q); bad["m_s"] = [[1.0, 1.0]] * 2
+        P.plan_solve(bad)
+    q["m"] = 1e-9
+    assert P.plan_solve(q) == (None, float("inf"), None)
