@@ -8,7 +8,7 @@ into one tensor-model-parallel rank's share (Megatron partition, Sec. II
 projection / FC2).
 
 Workloads: GPT-style pre-LN layers at the hidden sizes of the paper's model
-table (Table III); sequence length, head count and TP degree per config are
+table (Table III), and LLaMA-style layers (RMSNorm, rotary embedding, SwiGLU); sequence length, head count and TP degree per config are
 the ones this build is measured on.  Every tensor has its own
 ``numpy.random.default_rng([seed, layer, tensor_id])`` stream, so generation
 order does not matter.
@@ -26,10 +26,21 @@ CONFIGS = {
     "C5": dict(hidden=8192, n_heads=64, seq=2048, batch=2, tp=8, n_sub=4, n_layers=1, causal=1, dropout_p=0.1, w_sigma=0.01),
 }
 
+# Second layer family of the paper's model table (the LLaMA rows): pre-RMSNorm, rotary embedding, SwiGLU FFN of inner
+# width `ffn_hidden`, no biases.  L4 is LLaMA-7B's layer at the same sequence length, batch and TP degree as C4.
+LLAMA_CONFIGS = {
+    "L1": dict(arch="llama", hidden=256, n_heads=4, seq=128, batch=4, tp=2, n_sub=2, n_layers=1, causal=1, dropout_p=0.0,
+               ffn_hidden=704, rope_theta=10000.0, w_sigma=0.03),
+    "L2": dict(arch="llama", hidden=1024, n_heads=16, seq=512, batch=4, tp=4, n_sub=2, n_layers=2, causal=1, dropout_p=0.1,
+               ffn_hidden=2816, rope_theta=10000.0, w_sigma=0.02),
+    "L4": dict(arch="llama", hidden=4096, n_heads=32, seq=2048, batch=4, tp=8, n_sub=2, n_layers=1, causal=1, dropout_p=0.0,
+               ffn_hidden=11008, rope_theta=10000.0, w_sigma=0.02),
+}
+
 PARAM_NAMES = ("ln1_g", "ln1_b", "wq", "wk", "wv", "bq", "bk", "bv", "wo", "bo",
                "ln2_g", "ln2_b", "w1", "b1", "w2", "b2")
 _TENSOR_ID = {n: i for i, n in enumerate(PARAM_NAMES)}
-_TENSOR_ID.update(x=100, dy=101)
+_TENSOR_ID.update(x=100, dy=101, wg=50, wu=51)
 
 
 def round_to_bf16(a: np.ndarray) -> np.ndarray:
@@ -60,6 +71,35 @@ def make_layer_params(cfg: dict, layer: int, seed: int = 0) -> dict:
     for name in ("ln1_g", "ln2_g"):
         p[name] = _normal(seed, layer, name, (h,), 0.02, mean=1.0)
     return p
+
+
+def make_llama_layer_params(cfg: dict, layer: int, seed: int = 0) -> dict:
+    """Unsharded parameters of one LLaMA-style layer: wq, wk, wv, wo [h,h], wg, wu [h,F], w2 [F,h] (bf16-representable),
+    RMSNorm weights ln1_g, ln2_g [h] fp32."""
+    h, F = cfg["hidden"], cfg["ffn_hidden"]
+    sw = cfg.get("w_sigma", 0.02)
+    p = {}
+    for name, shape in (("wq", (h, h)), ("wk", (h, h)), ("wv", (h, h)), ("wo", (h, h)), ("wg", (h, F)), ("wu", (h, F)), ("w2", (F, h))):
+        p[name] = round_to_bf16(_normal(seed, layer, name, shape, sw))
+    for name in ("ln1_g", "ln2_g"):
+        p[name] = _normal(seed, layer, name, (h,), 0.02, mean=1.0)
+    return p
+
+
+def shard_llama_layer_params(p: dict, cfg: dict, rank: int) -> dict:
+    """Rank `rank`'s share: contiguous heads -> columns of wq/wk/wv and rows of wo; FFN columns
+    [rank*F/t, (rank+1)*F/t) -> columns of wg, wu and rows of w2.  RMSNorm weights are replicated."""
+    h, t, F = cfg["hidden"], cfg["tp"], cfg["ffn_hidden"]
+    hp, fp = h // t, F // t
+    a, f = slice(rank * hp, (rank + 1) * hp), slice(rank * fp, (rank + 1) * fp)
+    s = {k: p[k] for k in ("ln1_g", "ln2_g")}
+    for k in ("wq", "wk", "wv"):
+        s[k] = np.ascontiguousarray(p[k][:, a])
+    s["wo"] = np.ascontiguousarray(p["wo"][a, :])
+    for k in ("wg", "wu"):
+        s[k] = np.ascontiguousarray(p[k][:, f])
+    s["w2"] = np.ascontiguousarray(p["w2"][f, :])
+    return s
 
 
 def make_activations(cfg: dict, seed: int = 0):
