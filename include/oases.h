@@ -185,6 +185,30 @@ int oases_op_layernorm_bwd(const void *part, const void *peer, const void *dres,
                            uint64_t seed, int layer, int site, int64_t row0, float p,
                            void *scratch, void *stream);
 
+/* RMSNorm counterparts (the LLaMA layers of the paper's Table III): y = gamma * x * rstd, rstd = 1/sqrt(mean(x^2)+eps);
+ * no mean, no beta, no bias at the reduction point.  Shapes and optional arguments as for the LayerNorm entry
+ * points above; scratch of the backward: fp32 [3*1024*h]. */
+int oases_op_rmsnorm_fwd(const void *x, const void *gamma, void *out, void *rstd, int rows, int h,
+                         float eps, void *stream);
+/*   xo = xin + keep * (part + peer) / (1-p);  if ln_out: ln_out = RMSNorm(xo) (bf16), rstd. */
+int oases_op_dropout_residual_rmsnorm(const void *part, const void *peer, const void *xin, void *xo,
+                                      const void *gamma, void *ln_out, void *rstd, int rows, int h,
+                                      float eps, uint64_t seed, int layer, int site, int64_t row0,
+                                      float p, void *stream);
+/*   g = part + peer;  dxo = dres + RMSNorm'(g; x, rstd, gamma);  dgamma += ;  if dz: dz = keep * dxo / (1-p) (bf16). */
+int oases_op_rmsnorm_bwd(const void *part, const void *peer, const void *dres, const void *x,
+                         const void *rstd, const void *gamma, void *dxo, void *dgamma, void *dz,
+                         int rows, int h, uint64_t seed, int layer, int site, int64_t row0, float p,
+                         void *scratch, void *stream);
+
+/* Rotary position embedding.  table: fp32 [seq][head_dim/2][2] = (cos, sin) of pos * theta^(-2i/head_dim), written
+ * by oases_op_rope_table (angles in fp64).  oases_op_rope rotates, in place, the pair (i, i + head_dim/2) of every
+ * head of the Q and K parts of qkv [rows, ld] bf16 = [Q heads | K heads | V heads] by the angle of the token's
+ * position (row0 + row) mod seq; inverse != 0 rotates back (what the gradients of Q and K need).  head_dim % 16 == 0. */
+int oases_op_rope_table(void *table, int seq, int head_dim, float theta, void *stream);
+int oases_op_rope(void *qkv, int ld, int rows, int64_t row0, int seq, int heads, int head_dim,
+                  const void *table, int inverse, void *stream);
+
 /* GEMM family on bf16 operands with fp32 accumulation.  `op`:
  *   OASES_GEMM_NN  C[M,N]  = A[M,K] * B[K,N]            (forward of a linear map)
  *   OASES_GEMM_NT  C[M,N]  = A[M,K] * B[N,K]^T          (input gradient)
@@ -192,13 +216,19 @@ int oases_op_layernorm_bwd(const void *part, const void *peer, const void *dres,
  * `epi` (NN/NT): OASES_EPI_F32 C fp32; OASES_EPI_BF16 C bf16; OASES_EPI_BIAS_BF16 C = acc+bias (bf16);
  *   OASES_EPI_BIAS_GELU aux = acc+bias (bf16, "pre"), C = GeLU_tanh(acc+bias) (bf16);
  *   OASES_EPI_DGELU C = acc * GeLU_tanh'(aux) (bf16), aux = stored "pre" [M,N] bf16.
+ *   OASES_EPI_SWIGLU (NN only, N % 64 == 0): the N columns of B are the gate and up projections of a SwiGLU block
+ *     interleaved in blocks of 32: columns [64k, 64k+32) = gate columns [32k, 32k+32), [64k+32, 64k+64) = the same
+ *     up columns.  aux [M,N] bf16 = acc (gate and up pre-activations, same interleaving, ldaux >= N);
+ *     C [M,N/2] bf16 = silu(gate) * up, ldc >= N/2.  Never runs over k slices.
+ *   OASES_EPI_DSWIGLU (NT only, N % 32 == 0): acc = dF [M,N]; aux [M,2N] = the stored pre-activations (layout
+ *     above); C [M,2N] bf16 = [dF * up * silu'(gate) | dF * silu(gate)] in the same interleaving, ldc >= 2N.
  * lda/ldb/ldc are row strides in elements.  M,N,K must be multiples of 8; EINVAL otherwise.
  * workspace (optional, fp32 scratch of workspace_bytes): lets tile-starved shapes split K -- slices write fp32
  * partial planes [slices][M][N] that a second kernel adds in slice order before the epilogue (deterministic).
  * NULL: never split. */
 enum { OASES_GEMM_NN = 0, OASES_GEMM_NT = 1, OASES_GEMM_TN = 2 };
 enum { OASES_EPI_F32 = 0, OASES_EPI_BF16 = 1, OASES_EPI_BIAS_BF16 = 2, OASES_EPI_BIAS_GELU = 3,
-       OASES_EPI_DGELU = 4 };
+       OASES_EPI_DGELU = 4, OASES_EPI_SWIGLU = 6, OASES_EPI_DSWIGLU = 7 };
 int oases_op_gemm(int op, int epi, int M, int N, int K, const void *A, int lda, const void *B,
                   int ldb, void *C, int ldc, const void *bias, void *aux, int ldaux,
                   void *workspace, size_t workspace_bytes, void *stream);

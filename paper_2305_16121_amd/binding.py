@@ -15,6 +15,7 @@ lib = C.CDLL(LIB_PATH)
 OK, EINVAL, ENULL, EALIGN, EWORKSPACE, EHIP = 0, -1, -2, -3, -4, -5
 GEMM_NN, GEMM_NT, GEMM_TN = 0, 1, 2
 EPI_F32, EPI_BF16, EPI_BIAS_BF16, EPI_BIAS_GELU, EPI_DGELU = 0, 1, 2, 3, 4
+EPI_SWIGLU, EPI_DSWIGLU = 6, 7
 FLAG_SERIALISE, FLAG_PROFILE, FLAG_RECOMPUTE = 1, 2, 4
 
 _P = C.c_void_p
@@ -62,6 +63,11 @@ _sig("oases_op_layernorm_fwd", _i, _P, _P, _P, _P, _P, _P, _i, _i, _f, _P)
 _sig("oases_op_bias_dropout_residual_ln", _i, _P, _P, _P, _P, _P, _P, _P, _P, _P, _P, _i, _i, _f, _u64, _i, _i, _i64, _f, _P)
 _sig("oases_op_dropout_bwd", _i, _P, _P, _P, _i, _i, _u64, _i, _i, _i64, _f, _P, _P)
 _sig("oases_op_layernorm_bwd", _i, _P, _P, _P, _P, _P, _P, _P, _P, _P, _P, _P, _P, _i, _i, _u64, _i, _i, _i64, _f, _P, _P)
+_sig("oases_op_rmsnorm_fwd", _i, _P, _P, _P, _P, _i, _i, _f, _P)
+_sig("oases_op_dropout_residual_rmsnorm", _i, _P, _P, _P, _P, _P, _P, _P, _i, _i, _f, _u64, _i, _i, _i64, _f, _P)
+_sig("oases_op_rmsnorm_bwd", _i, _P, _P, _P, _P, _P, _P, _P, _P, _P, _i, _i, _u64, _i, _i, _i64, _f, _P, _P)
+_sig("oases_op_rope_table", _i, _P, _i, _i, _f, _P)
+_sig("oases_op_rope", _i, _P, _i, _i, _i64, _i, _i, _i, _P, _i, _P)
 _sig("oases_op_gemm", _i, _i, _i, _i, _i, _i, _P, _i, _P, _i, _P, _i, _P, _P, _i, _P, _sz, _P)
 _sig("oases_op_gemm_variant", _i, _i, _i, _i, _i, _i, _sz)
 _sig("oases_op_gemm_forced", _i, _i, _i, _i, _i, _i, _i, _P, _i, _P, _i, _P, _i, _P, _P, _i, _P, _sz, _P)

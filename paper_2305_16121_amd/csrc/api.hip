@@ -596,6 +596,31 @@ int oases_op_layernorm_bwd(const void* part, const void* peer, const void* dres,
                               (const float*)rstd, (const float*)gamma, (float*)dxo, (float*)dgamma, (float*)dbeta, dz, (float*)dbias,
                               rows, h, make_drop_cfg(seed, layer, site, p), row0, (float*)scratch, (hipStream_t)stream);
 }
+int oases_op_rmsnorm_fwd(const void* x, const void* gamma, void* out, void* rstd, int rows, int h, float eps, void* stream) {
+  return launch_layernorm_fwd((const float*)x, (const float*)gamma, nullptr, out, nullptr, (float*)rstd, rows, h, eps, (hipStream_t)stream,
+                              true);
+}
+int oases_op_dropout_residual_rmsnorm(const void* part, const void* peer, const void* xin, void* xo, const void* gamma, void* ln_out,
+                                      void* rstd, int rows, int h, float eps, uint64_t seed, int layer, int site, int64_t row0, float p,
+                                      void* stream) {
+  if (!part) { set_error("dropout_residual_rmsnorm: NULL partial"); return OASES_ENULL; }
+  return launch_bdr_ln((const float*)part, (const float*)peer, nullptr, (const float*)xin, (float*)xo, (const float*)gamma, nullptr, ln_out,
+                       nullptr, (float*)rstd, rows, h, eps, make_drop_cfg(seed, layer, site, p), row0, (hipStream_t)stream, true);
+}
+int oases_op_rmsnorm_bwd(const void* part, const void* peer, const void* dres, const void* x, const void* rstd, const void* gamma,
+                         void* dxo, void* dgamma, void* dz, int rows, int h, uint64_t seed, int layer, int site, int64_t row0, float p,
+                         void* scratch, void* stream) {
+  return launch_layernorm_bwd((const float*)part, (const float*)peer, (const float*)dres, (const float*)x, nullptr, (const float*)rstd,
+                              (const float*)gamma, (float*)dxo, (float*)dgamma, nullptr, dz, nullptr, rows, h,
+                              make_drop_cfg(seed, layer, site, p), row0, (float*)scratch, (hipStream_t)stream, true);
+}
+int oases_op_rope_table(void* table, int seq, int head_dim, float theta, void* stream) {
+  return launch_rope_table((float*)table, seq, head_dim, theta, (hipStream_t)stream);
+}
+int oases_op_rope(void* qkv, int ld, int rows, int64_t row0, int seq, int heads, int head_dim, const void* table, int inverse,
+                  void* stream) {
+  return launch_rope(qkv, ld, rows, row0, seq, heads, head_dim, (const float*)table, inverse, (hipStream_t)stream);
+}
 int oases_op_gemm(int op, int epi, int M, int N, int K, const void* A, int lda, const void* B, int ldb, void* C, int ldc,
                   const void* bias, void* aux, int ldaux, void* workspace, size_t workspace_bytes, void* stream) {
   if (workspace && !aligned16(workspace)) { set_error("gemm: workspace not 16-byte aligned"); return OASES_EALIGN; }

@@ -100,17 +100,22 @@ __device__ __forceinline__ float gelu_tanh_grad(float x) {
 
 // ---- kernel launchers (one per .hip file), all enqueue-only, return 0 or OASES_E* ---------------
 int launch_dropout_mask(uint8_t* mask, const DropCfg& d, int64_t row0, int rows, int h, hipStream_t s);
+// rms = true: RMSNorm (no mean, no beta; mu / beta unused and may be NULL); bias may be NULL with rms
 int launch_layernorm_fwd(const float* x, const float* gamma, const float* beta, void* out, float* mu,
-                         float* rstd, int rows, int h, float eps, hipStream_t s);
+                         float* rstd, int rows, int h, float eps, hipStream_t s, bool rms = false);
 int launch_bdr_ln(const float* part, const float* peer, const float* bias, const float* xin, float* xo,
                   const float* gamma, const float* beta, void* ln_out, float* mu, float* rstd, int rows,
-                  int h, float eps, const DropCfg& d, int64_t row0, hipStream_t s);
+                  int h, float eps, const DropCfg& d, int64_t row0, hipStream_t s, bool rms = false);
+// rotary embedding: table [seq][head_dim/2] of (cos, sin) fp32; rotation in place on the Q and K parts of qkv
+int launch_rope_table(float* tab, int seq, int head_dim, float theta, hipStream_t s);
+int launch_rope(void* qkv, int ld, int rows, int64_t row0, int seq, int heads, int head_dim, const float* tab, int inverse,
+                hipStream_t s);
 int launch_dropout_bwd(const float* dyin, void* dz, float* dbias, int rows, int h, const DropCfg& d,
                        int64_t row0, float* scratch, hipStream_t s);
 int launch_layernorm_bwd(const float* part, const float* peer, const float* dres, const float* x,
                          const float* mu, const float* rstd, const float* gamma, float* dxo, float* dgamma,
                          float* dbeta, void* dz, float* dbias, int rows, int h, const DropCfg& d,
-                         int64_t row0, float* scratch, hipStream_t s);
+                         int64_t row0, float* scratch, hipStream_t s, bool rms = false);
 int launch_colsum_bf16(const void* a, int ld, int rows, int cols, float* out, float* scratch, hipStream_t s);
 // splitk_ws: optional fp32 scratch for split-K partial planes (NULL: never split); forced_variant: 0 = choose, else
 // the instantiation to launch, encoded as gemm_variant() returns it

@@ -48,9 +48,10 @@ __global__ __launch_bounds__(NT) void dropout_mask_kernel(uint8_t* mask, DropCfg
 }
 
 // ------------------------------------------------------------------------------------------------
-// xo = xin + keep * (part + peer + bias) * scale   (if part != nullptr; else the row is xin itself)
+// xo = xin + keep * (part + peer + bias) * scale   (if part != nullptr; else the row is xin itself; bias may be NULL)
 // ln_out = gamma * (xo - mu) * rstd + beta          (if ln_out != nullptr)
-template <int NC>
+// RMS: ln_out = gamma * xo * rstd with rstd = 1/sqrt(mean(xo^2) + eps) (RMSNorm: no mean, no beta, mu_out unused)
+template <int NC, bool RMS>
 __global__ __launch_bounds__(NT) void bdr_ln_kernel(const float* __restrict__ part, const float* __restrict__ peer,
                                                     const float* __restrict__ bias, const float* __restrict__ xin,
                                                     float* __restrict__ xo, const float* __restrict__ gamma,
@@ -66,9 +67,9 @@ __global__ __launch_bounds__(NT) void bdr_ln_kernel(const float* __restrict__ pa
   // normalised (a value within a few standard deviations of the mean, so E[d^2] - E[d]^2 does not cancel).  Every
   // thread rebuilds that element itself, so the statistics are the same function of the row whether the row was
   // just produced here (fused reduction point) or is read back later (LayerNorm alone, recomputation).
-  float shift = xin[base];
-  if (part) {
-    float z0 = part[base] + bias[0];
+  float shift = RMS ? 0.f : xin[base];
+  if (!RMS && part) {
+    float z0 = part[base] + (bias ? bias[0] : 0.f);
     if (peer) z0 += peer[base];
     bool k0[4];
     dropout_keep4(d, (uint64_t)(row0 + row) * h >> 2, k0);
@@ -84,7 +85,7 @@ __global__ __launch_bounds__(NT) void bdr_ln_kernel(const float* __restrict__ pa
       if (part) {
         f32x4 z = *reinterpret_cast<const f32x4*>(part + base + 4 * c);
         if (peer) z += *reinterpret_cast<const f32x4*>(peer + base + 4 * c);
-        z += *reinterpret_cast<const f32x4*>(bias + 4 * c);
+        if (bias) z += *reinterpret_cast<const f32x4*>(bias + 4 * c);
         bool k[4];
         dropout_keep4(d, ((uint64_t)(row0 + row) * h >> 2) + c, k);
 #pragma unroll
@@ -98,16 +99,20 @@ __global__ __launch_bounds__(NT) void bdr_ln_kernel(const float* __restrict__ pa
   }
   if (!ln_out) return;
   block_sum2(s, q, red);
-  const float ms = s / h;
+  const float ms = RMS ? 0.f : s / h;
   const float mu = shift + ms;
   const float rstd = rsqrtf(fmaxf(q / h - ms * ms, 0.f) + eps);
-  if (tid == 0) { mu_out[row] = mu; rstd_out[row] = rstd; }
+  if (tid == 0) {
+    if (!RMS) mu_out[row] = mu;
+    rstd_out[row] = rstd;
+  }
 #pragma unroll
   for (int i = 0; i < NC; i++) {
     const int c = tid + i * NT;
     if (c < nc) {
       f32x4 gm = *reinterpret_cast<const f32x4*>(gamma + 4 * c);
-      f32x4 bt = *reinterpret_cast<const f32x4*>(beta + 4 * c);
+      f32x4 bt = f32x4{0.f, 0.f, 0.f, 0.f};
+      if (!RMS) bt = *reinterpret_cast<const f32x4*>(beta + 4 * c);
       f32x4 o;
 #pragma unroll
       for (int j = 0; j < 4; j++) o[j] = gm[j] * ((v[i][j] - mu) * rstd) + bt[j];
@@ -190,13 +195,14 @@ __global__ __launch_bounds__(NT) void colsum_finalize_kernel(const float* __rest
 // ------------------------------------------------------------------------------------------------
 // g = part + peer;  dxo = dres + rstd * (g*gamma - mean(g*gamma) - xhat * mean(g*gamma*xhat))
 // partials: scratch[0] dgamma = sum g*xhat, scratch[1] dbeta = sum g, scratch[2] dbias = sum dz
-template <int NC, int NT>
+// RMS: xhat = x * rstd, dxo = dres + rstd * (g*gamma - xhat * mean(g*gamma*xhat)), no dbeta
+template <int NC, int NT, bool RMS>
 __global__ __launch_bounds__(NT) void layernorm_bwd_kernel(const float* __restrict__ part, const float* __restrict__ peer,
                                                            const float* __restrict__ dres, const float* __restrict__ x,
                                                            const float* __restrict__ mu, const float* __restrict__ rstd,
                                                            const float* __restrict__ gamma, float* __restrict__ dxo,
                                                            uint16_t* __restrict__ dz, float* __restrict__ scratch, int rows,
-                                                           int h, DropCfg d, int64_t row0) {
+                                                           int h, DropCfg d, int64_t row0, int want_dbias) {
   __shared__ float red[2 * (NT / 64)];
   const int tid = threadIdx.x, nc = h >> 2;
   const size_t gstride = (size_t)gridDim.x * h;
@@ -205,7 +211,7 @@ __global__ __launch_bounds__(NT) void layernorm_bwd_kernel(const float* __restri
   for (int i = 0; i < NC; i++) ag[i] = ab[i] = az[i] = f32x4{0.f, 0.f, 0.f, 0.f};
   for (int row = blockIdx.x; row < rows; row += gridDim.x) {
     const size_t base = (size_t)row * h;
-    const float m = mu[row], rs = rstd[row];
+    const float m = RMS ? 0.f : mu[row], rs = rstd[row];
     f32x4 gg[NC], xh[NC], dr[NC];
     float s1 = 0.f, s2 = 0.f;
 #pragma unroll
@@ -230,7 +236,7 @@ __global__ __launch_bounds__(NT) void layernorm_bwd_kernel(const float* __restri
       }
     }
     block_sum2<NT / 64>(s1, s2, red);
-    const float m1 = s1 / h, m2 = s2 / h;
+    const float m1 = RMS ? 0.f : s1 / h, m2 = s2 / h;
 #pragma unroll
     for (int i = 0; i < NC; i++) {
       const int c = tid + i * NT;
@@ -256,8 +262,8 @@ __global__ __launch_bounds__(NT) void layernorm_bwd_kernel(const float* __restri
     if (c < nc) {
       float* p = scratch + (size_t)blockIdx.x * h + 4 * c;
       *reinterpret_cast<f32x4*>(p) = ag[i];
-      *reinterpret_cast<f32x4*>(p + gstride) = ab[i];
-      if (dz) *reinterpret_cast<f32x4*>(p + 2 * gstride) = az[i];
+      if (!RMS) *reinterpret_cast<f32x4*>(p + gstride) = ab[i];
+      if (dz && want_dbias) *reinterpret_cast<f32x4*>(p + 2 * gstride) = az[i];
     }
   }
 }
@@ -280,6 +286,44 @@ __global__ __launch_bounds__(NT) void colsum_bf16_kernel(const uint16_t* __restr
   float* p = scratch + (size_t)blockIdx.x * cols + 8 * c;
   *reinterpret_cast<f32x4*>(p) = f32x4{acc[0], acc[1], acc[2], acc[3]};
   *reinterpret_cast<f32x4*>(p + 4) = f32x4{acc[4], acc[5], acc[6], acc[7]};
+}
+
+// ------------------------------------------------------------------------------------------------
+// Rotary position embedding.  tab[pos][i] = (cos, sin) of pos * theta^(-2i/d), i < d/2, built in fp64.
+__global__ __launch_bounds__(NT) void rope_table_kernel(float2* __restrict__ tab, int seq, int half, double log2_theta) {
+  const int idx = blockIdx.x * NT + threadIdx.x;
+  if (idx >= seq * half) return;
+  const int pos = idx / half, i = idx % half;
+  const double ang = (double)pos * exp2(-(double)i / (double)half * log2_theta);
+  tab[idx] = make_float2((float)cos(ang), (float)sin(ang));
+}
+
+// In place on the Q and K parts of qkv [rows, ld] = [Q heads | K heads | V heads]: the pair (i, i + d/2) of every head
+// turns by the token's angle (sign = +1), or back (sign = -1: the transpose, which is what a gradient needs).
+// One thread owns 8 consecutive i of one head of one row: two 16-byte loads, two 16-byte stores.
+__global__ __launch_bounds__(NT) void rope_kernel(uint16_t* __restrict__ qkv, int ld, int rows, int64_t row0, int seq, int heads,
+                                                  int d, const float2* __restrict__ tab, float sign) {
+  const int half = d >> 1, cpw = half >> 3;  // 8-element chunks per half head
+  const int64_t idx = (int64_t)blockIdx.x * NT + threadIdx.x;
+  const int64_t per_row = (int64_t)2 * heads * cpw;
+  if (idx >= (int64_t)rows * per_row) return;
+  const int row = (int)(idx / per_row), r = (int)(idx % per_row);
+  const int hd = r / cpw, c = r % cpw;  // hd < 2*heads runs over the Q heads, then the K heads
+  const int pos = (int)((row0 + row) % seq);
+  uint16_t* p = qkv + (size_t)row * ld + (size_t)hd * d + 8 * c;
+  const u32x4 a = *reinterpret_cast<const u32x4*>(p), b = *reinterpret_cast<const u32x4*>(p + half);
+  const float2* t = tab + (size_t)pos * half + 8 * c;
+  float o1[8], o2[8];
+#pragma unroll
+  for (int j = 0; j < 8; j++) {
+    const float x1 = bf16_bits_to_f32((j & 1) ? a[j >> 1] >> 16 : a[j >> 1] & 0xffffu);
+    const float x2 = bf16_bits_to_f32((j & 1) ? b[j >> 1] >> 16 : b[j >> 1] & 0xffffu);
+    const float cs = t[j].x, sn = sign * t[j].y;
+    o1[j] = x1 * cs - x2 * sn;
+    o2[j] = x2 * cs + x1 * sn;
+  }
+  *reinterpret_cast<u32x4*>(p) = u32x4{pack_bf16x2(o1[0], o1[1]), pack_bf16x2(o1[2], o1[3]), pack_bf16x2(o1[4], o1[5]), pack_bf16x2(o1[6], o1[7])};
+  *reinterpret_cast<u32x4*>(p + half) = u32x4{pack_bf16x2(o2[0], o2[1]), pack_bf16x2(o2[2], o2[3]), pack_bf16x2(o2[4], o2[5]), pack_bf16x2(o2[6], o2[7])};
 }
 
 // row groups of a two-stage column reduction: about eight rows per group (few partial rows to add up), but at
@@ -358,23 +402,28 @@ int launch_dropout_mask(uint8_t* mask, const DropCfg& d, int64_t row0, int rows,
 
 int launch_bdr_ln(const float* part, const float* peer, const float* bias, const float* xin, float* xo,
                   const float* gamma, const float* beta, void* ln_out, float* mu, float* rstd, int rows, int h,
-                  float eps, const DropCfg& d, int64_t row0, hipStream_t s) {
+                  float eps, const DropCfg& d, int64_t row0, hipStream_t s, bool rms) {
   if (!check_h(rows, h, "bias_dropout_residual_ln")) return OASES_EINVAL;
-  if (!xin || (part && (!bias || !xo)) || (ln_out && (!gamma || !beta || !mu || !rstd))) {
+  if (!xin || (part && !xo) || (part && !rms && !bias) || (ln_out && (!gamma || !rstd || (!rms && (!beta || !mu))))) {
     set_error("bias_dropout_residual_ln: NULL argument");
     return OASES_ENULL;
   }
-  OASES_NC_DISPATCH(pick_nc(h), hipLaunchKernelGGL(bdr_ln_kernel<NC>, dim3(rows), dim3(NT), 0, s, part, peer, bias, xin, xo,
-                                                   gamma, beta, (uint16_t*)ln_out, mu, rstd, h, eps, d, row0));
+  if (rms) {
+    OASES_NC_DISPATCH(pick_nc(h), hipLaunchKernelGGL((bdr_ln_kernel<NC, true>), dim3(rows), dim3(NT), 0, s, part, peer, bias, xin, xo,
+                                                     gamma, beta, (uint16_t*)ln_out, mu, rstd, h, eps, d, row0));
+  } else {
+    OASES_NC_DISPATCH(pick_nc(h), hipLaunchKernelGGL((bdr_ln_kernel<NC, false>), dim3(rows), dim3(NT), 0, s, part, peer, bias, xin, xo,
+                                                     gamma, beta, (uint16_t*)ln_out, mu, rstd, h, eps, d, row0));
+  }
   OASES_LAUNCH_CHECK("bdr_ln_kernel");
   return 0;
 }
 
 int launch_layernorm_fwd(const float* x, const float* gamma, const float* beta, void* out, float* mu, float* rstd,
-                         int rows, int h, float eps, hipStream_t s) {
+                         int rows, int h, float eps, hipStream_t s, bool rms) {
   DropCfg d = make_drop_cfg(0, 0, 0, 0.f);
   if (!out) { set_error("layernorm_fwd: NULL output"); return OASES_ENULL; }
-  return launch_bdr_ln(nullptr, nullptr, nullptr, x, nullptr, gamma, beta, out, mu, rstd, rows, h, eps, d, 0, s);
+  return launch_bdr_ln(nullptr, nullptr, nullptr, x, nullptr, gamma, beta, out, mu, rstd, rows, h, eps, d, 0, s, rms);
 }
 
 static int finalize(float* scratch, float* o0, float* o1, float* o2, int nk, int groups, int cols, hipStream_t s) {
@@ -398,17 +447,47 @@ int launch_dropout_bwd(const float* dyin, void* dz, float* dbias, int rows, int 
 
 int launch_layernorm_bwd(const float* part, const float* peer, const float* dres, const float* x, const float* mu,
                          const float* rstd, const float* gamma, float* dxo, float* dgamma, float* dbeta, void* dz,
-                         float* dbias, int rows, int h, const DropCfg& d, int64_t row0, float* scratch, hipStream_t s) {
+                         float* dbias, int rows, int h, const DropCfg& d, int64_t row0, float* scratch, hipStream_t s, bool rms) {
   if (!check_h(rows, h, "layernorm_bwd")) return OASES_EINVAL;
-  if (!part || !dres || !x || !mu || !rstd || !gamma || !dxo || !dgamma || !dbeta || !scratch || (dz && !dbias)) {
+  if (!part || !dres || !x || !rstd || !gamma || !dxo || !dgamma || !scratch || (!rms && (!mu || !dbeta || (dz && !dbias)))) {
     set_error("layernorm_bwd: NULL argument");
     return OASES_ENULL;
   }
   const int groups = col_groups(rows);
-  OASES_BWD_DISPATCH(h, hipLaunchKernelGGL((layernorm_bwd_kernel<NC, NTHR>), dim3(groups), dim3(NTHR), 0, s, part, peer, dres, x, mu,
-                                           rstd, gamma, dxo, (uint16_t*)dz, scratch, rows, h, d, row0));
+  const int want_dbias = dz && dbias;
+  if (rms) {
+    OASES_BWD_DISPATCH(h, hipLaunchKernelGGL((layernorm_bwd_kernel<NC, NTHR, true>), dim3(groups), dim3(NTHR), 0, s, part, peer, dres, x,
+                                             mu, rstd, gamma, dxo, (uint16_t*)dz, scratch, rows, h, d, row0, want_dbias));
+  } else {
+    OASES_BWD_DISPATCH(h, hipLaunchKernelGGL((layernorm_bwd_kernel<NC, NTHR, false>), dim3(groups), dim3(NTHR), 0, s, part, peer, dres, x,
+                                             mu, rstd, gamma, dxo, (uint16_t*)dz, scratch, rows, h, d, row0, want_dbias));
+  }
   OASES_LAUNCH_CHECK("layernorm_bwd_kernel");
-  return finalize(scratch, dgamma, dbeta, dz ? dbias : nullptr, dz ? 3 : 2, groups, h, s);
+  return finalize(scratch, dgamma, rms ? nullptr : dbeta, want_dbias ? dbias : nullptr, want_dbias ? 3 : 2, groups, h, s);
+}
+
+int launch_rope_table(float* tab, int seq, int head_dim, float theta, hipStream_t s) {
+  if (!tab) { set_error("rope_table: NULL"); return OASES_ENULL; }
+  if (seq <= 0 || head_dim <= 0 || head_dim % 16 || !(theta > 1.f)) { set_error("rope_table: bad argument (head_dim %% 16, theta > 1)"); return OASES_EINVAL; }
+  const int n = seq * (head_dim / 2);
+  hipLaunchKernelGGL(rope_table_kernel, dim3((n + NT - 1) / NT), dim3(NT), 0, s, reinterpret_cast<float2*>(tab), seq, head_dim / 2,
+                     log2((double)theta));
+  OASES_LAUNCH_CHECK("rope_table_kernel");
+  return 0;
+}
+
+int launch_rope(void* qkv, int ld, int rows, int64_t row0, int seq, int heads, int head_dim, const float* tab, int inverse,
+                hipStream_t s) {
+  if (!qkv || !tab) { set_error("rope: NULL argument"); return OASES_ENULL; }
+  if (rows <= 0 || seq <= 0 || heads <= 0 || head_dim % 16 || ld % 8 || ld < 3 * heads * head_dim || row0 < 0 || !aligned16(qkv)) {
+    set_error("rope: bad shape (head_dim %% 16, ld %% 8, ld >= 3*heads*head_dim)");
+    return OASES_EINVAL;
+  }
+  const int64_t n = (int64_t)rows * 2 * heads * (head_dim / 16);
+  hipLaunchKernelGGL(rope_kernel, dim3((unsigned)((n + NT - 1) / NT)), dim3(NT), 0, s, (uint16_t*)qkv, ld, rows, row0, seq, heads,
+                     head_dim, reinterpret_cast<const float2*>(tab), inverse ? -1.f : 1.f);
+  OASES_LAUNCH_CHECK("rope_kernel");
+  return 0;
 }
 
 int launch_colsum_bf16(const void* a, int ld, int rows, int cols, float* out, float* scratch, hipStream_t s) {

@@ -106,7 +106,12 @@ __device__ __forceinline__ bf16x8 read_frag(const char* lds, int r0, int kk, int
   }
 }
 
-enum { EPI_F32 = 0, EPI_BF16 = 1, EPI_BIAS_BF16 = 2, EPI_BIAS_GELU = 3, EPI_DGELU = 4, EPI_ACC_F32 = 5 };
+enum { EPI_F32 = 0, EPI_BF16 = 1, EPI_BIAS_BF16 = 2, EPI_BIAS_GELU = 3, EPI_DGELU = 4, EPI_ACC_F32 = 5, EPI_SWIGLU = 6, EPI_DSWIGLU = 7 };
+
+// silu(z) = z * sigmoid(z) and its derivative, on the fast exp2 / rcp units
+__device__ __forceinline__ float fast_sigmoid(float z) { return __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-1.4426950408889634f * z)); }
+__device__ __forceinline__ float silu_f(float z) { return z * fast_sigmoid(z); }
+__device__ __forceinline__ float silu_grad_f(float z) { const float sg = fast_sigmoid(z); return sg * (1.0f + z * (1.0f - sg)); }
 
 // instruction-group hints for the machine scheduler (kinds: 0x8 MFMA, 0x20 VMEM read, 0x100 LDS read, 0x200 LDS write)
 #define SGB(mask, n) __builtin_amdgcn_sched_group_barrier(mask, n, 0)
@@ -298,7 +303,24 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, char* lds, int m0, 
       if (!FULL && col >= g.N) continue;
       f32x4 v = {a[4 * q], a[4 * q + 1], a[4 * q + 2], a[4 * q + 3]};
       const size_t o = (size_t)row * g.ldc + col;
-      if (EPI == EPI_F32) {
+      if (EPI == EPI_DSWIGLU) {
+        // the accumulator holds dF for 4 columns of f; gate and up pre-activations of those columns sit in 32-column
+        // blocks side by side in aux ([gate 32 | up 32] per block), and so do their gradients in C
+        const size_t cg = (size_t)col + (col & ~31);
+        const u32x2 gt = *reinterpret_cast<const u32x2*>(g.aux + (size_t)row * g.ldaux + cg);
+        const u32x2 up = *reinterpret_cast<const u32x2*>(g.aux + (size_t)row * g.ldaux + cg + 32);
+        float dg[4], du[4];
+#pragma unroll
+        for (int e = 0; e < 4; e++) {
+          const float ge = bf16_bits_to_f32((e & 1) ? gt[e >> 1] >> 16 : gt[e >> 1] & 0xffffu);
+          const float ue = bf16_bits_to_f32((e & 1) ? up[e >> 1] >> 16 : up[e >> 1] & 0xffffu);
+          dg[e] = v[e] * ue * silu_grad_f(ge);
+          du[e] = v[e] * silu_f(ge);
+        }
+        uint16_t* cp = reinterpret_cast<uint16_t*>(g.C) + (size_t)row * g.ldc + cg;
+        *reinterpret_cast<u32x2*>(cp) = u32x2{pack_bf16x2(dg[0], dg[1]), pack_bf16x2(dg[2], dg[3])};
+        *reinterpret_cast<u32x2*>(cp + 32) = u32x2{pack_bf16x2(du[0], du[1]), pack_bf16x2(du[2], du[3])};
+      } else if (EPI == EPI_F32) {
         *reinterpret_cast<f32x4*>(reinterpret_cast<float*>(g.C) + o) = v;
       } else if (EPI == EPI_ACC_F32) {
         f32x4* p = reinterpret_cast<f32x4*>(reinterpret_cast<float*>(g.C) + o);
@@ -322,11 +344,38 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, char* lds, int m0, 
     }
   };
 
+  // SwiGLU: accumulator tiles 2jj (gate) and 2jj+1 (up) of a wave hold the same 32 columns of f, element for element
+  auto emit_pair = [&](int i, int jj, const f32x16& ag, const f32x16& au) {
+    const int row = m0 + wm * WTM + i * 32 + (lane & 31);
+    if (!FULL && row >= g.M) return;
+#pragma unroll
+    for (int q = 0; q < 4; q++) {
+      const int cg = n0 + wn * WTN + jj * 64 + 8 * q + 4 * (lane >> 5);  // gate column in the interleaved [gate 32 | up 32] layout
+      if (!FULL && cg >= g.N) continue;
+      const int cf = (n0 + wn * WTN) / 2 + jj * 32 + 8 * q + 4 * (lane >> 5);
+      uint16_t* ap = g.aux + (size_t)row * g.ldaux + cg;
+      *reinterpret_cast<u32x2*>(ap) = u32x2{pack_bf16x2(ag[4 * q], ag[4 * q + 1]), pack_bf16x2(ag[4 * q + 2], ag[4 * q + 3])};
+      *reinterpret_cast<u32x2*>(ap + 32) = u32x2{pack_bf16x2(au[4 * q], au[4 * q + 1]), pack_bf16x2(au[4 * q + 2], au[4 * q + 3])};
+      float f[4];
+#pragma unroll
+      for (int e = 0; e < 4; e++) f[e] = silu_f(ag[4 * q + e]) * au[4 * q + e];
+      *reinterpret_cast<u32x2*>(reinterpret_cast<uint16_t*>(g.C) + (size_t)row * g.ldc + cf) = u32x2{pack_bf16x2(f[0], f[1]), pack_bf16x2(f[2], f[3])};
+    }
+  };
+
+  static_assert(TN % 2 == 0, "tiles of a wave are finished in pairs");
   if constexpr (WGK == 1) {
 #pragma unroll
     for (int i = 0; i < TM; i++)
 #pragma unroll
-      for (int j = 0; j < TN; j++) emit(i, j, acc[i][j]);
+      for (int j = 0; j < TN; j += 2) {
+        if constexpr (EPI == EPI_SWIGLU) {
+          emit_pair(i, j / 2, acc[i][j], acc[i][j + 1]);
+        } else {
+          emit(i, j, acc[i][j]);
+          emit(i, j + 1, acc[i][j + 1]);
+        }
+      }
   } else {
     // The two waves that hold the k halves of one part each finish one half of its rows: a wave hands the
     // accumulator tiles of the other half over through LDS (lane-for-lane, 16 bytes per lane and store) and adds what
@@ -353,15 +402,22 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, char* lds, int m0, 
 #pragma unroll
       for (int i = 0; i < HM; i++)
 #pragma unroll
-        for (int j = 0; j < TN; j++) {
-          f32x16 a = acc[H * HM + i][j];
+        for (int j = 0; j < TN; j += 2) {
+          f32x16 a[2] = {acc[H * HM + i][j], acc[H * HM + i][j + 1]};
 #pragma unroll
-          for (int q = 0; q < 4; q++) {
-            const f32x4 o = xch[(theirs + (i * TN + j) * 4 + q) * 64 + lane];
+          for (int t = 0; t < 2; t++)
 #pragma unroll
-            for (int e = 0; e < 4; e++) a[4 * q + e] += o[e];
+            for (int q = 0; q < 4; q++) {
+              const f32x4 o = xch[(theirs + (i * TN + j + t) * 4 + q) * 64 + lane];
+#pragma unroll
+              for (int e = 0; e < 4; e++) a[t][4 * q + e] += o[e];
+            }
+          if constexpr (EPI == EPI_SWIGLU) {
+            emit_pair(H * HM + i, j / 2, a[0], a[1]);
+          } else {
+            emit(H * HM + i, j, a[0]);
+            emit(H * HM + i, j + 1, a[1]);
           }
-          emit(H * HM + i, j, a);
         }
     };
     if (wk == 0) hand_over(std::integral_constant<int, 1>{}); else hand_over(std::integral_constant<int, 0>{});
@@ -457,6 +513,7 @@ int launch_one(const GemmArgs& g0, int ksplit, float* ws, hipStream_t s) {
   }
   // first pass: fp32 partial planes [ksplit][M][N] in the workspace; second pass: sum + the real epilogue
   if (!ws) { set_error("gemm: split-K chosen without a workspace"); return OASES_ENULL; }
+  if (EPI == EPI_SWIGLU || EPI == EPI_DSWIGLU) { set_error("gemm: the SwiGLU epilogues do not run over k slices"); return OASES_EINVAL; }
   GemmArgs p = g;
   p.ksplit = ksplit;
   p.k_per = ((g.K + ksplit - 1) / ksplit + BK - 1) / BK * BK;
@@ -518,7 +575,8 @@ bool decode_variant(int variant, int M, int N, int K, size_t ws_bytes, TileChoic
 
 template <bool A_KC, bool B_KC, int EPI>
 int launch_shape(const GemmArgs& g, float* ws, size_t ws_bytes, int forced_variant, hipStream_t s) {
-  constexpr int kind = !A_KC ? 2 : B_KC ? 1 : EPI == EPI_BIAS_GELU ? 3 : 0;
+  constexpr int kind = !A_KC ? 2 : B_KC ? 1 : (EPI == EPI_BIAS_GELU || EPI == EPI_SWIGLU) ? 3 : 0;
+  if (EPI == EPI_SWIGLU || EPI == EPI_DSWIGLU) ws_bytes = 0;  // their epilogues pair columns: no second pass over partial planes
   TileChoice t;
   if (forced_variant == 0) {
     t = pick_tile(kind, g.M, g.N, g.K, ws ? ws_bytes : 0);
@@ -539,7 +597,8 @@ int launch_shape(const GemmArgs& g, float* ws, size_t ws_bytes, int forced_varia
 }  // namespace
 
 int gemm_variant(int op, int epi, int M, int N, int K, size_t ws_bytes) {
-  const int kind = op == OASES_GEMM_TN ? 2 : op == OASES_GEMM_NT ? 1 : epi == EPI_BIAS_GELU ? 3 : 0;
+  const int kind = op == OASES_GEMM_TN ? 2 : op == OASES_GEMM_NT ? 1 : (epi == EPI_BIAS_GELU || epi == EPI_SWIGLU) ? 3 : 0;
+  if (epi == EPI_SWIGLU || epi == EPI_DSWIGLU) ws_bytes = 0;
   return encode_variant(pick_tile(kind, M, N, K, ws_bytes));
 }
 
@@ -561,7 +620,10 @@ int launch_gemm(int op, int epi, int M, int N, int K, const void* A, int lda, co
   }
   const bool nn = op == OASES_GEMM_NN;
   if (!nn && op != OASES_GEMM_NT) { set_error("gemm: unknown op %d", op); return OASES_EINVAL; }
-  if (lda < K || (nn ? ldb < N : ldb < K) || ldc < N) { set_error("gemm: leading dimension too small"); return OASES_EINVAL; }
+  const int c_cols = epi == EPI_SWIGLU ? N / 2 : epi == EPI_DSWIGLU ? 2 * N : N;  // SwiGLU: C is [M, N/2]; its gradient: [M, 2N]
+  if (lda < K || (nn ? ldb < N : ldb < K) || ldc < c_cols) { set_error("gemm: leading dimension too small"); return OASES_EINVAL; }
+  if (epi == EPI_SWIGLU && (!nn || N % 64 || !aux || ldaux < N)) { set_error("gemm: SwiGLU epilogue needs the NN form, N %% 64 == 0 and aux [M,N]"); return OASES_EINVAL; }
+  if (epi == EPI_DSWIGLU && (nn || N % 32 || !aux || ldaux < 2 * N)) { set_error("gemm: SwiGLU-gradient epilogue needs the NT form, N %% 32 == 0 and aux [M,2N]"); return OASES_EINVAL; }
   if ((epi == OASES_EPI_BIAS_BF16 || epi == OASES_EPI_BIAS_GELU) && !bias) { set_error("gemm: bias epilogue without bias"); return OASES_ENULL; }
   if ((epi == OASES_EPI_BIAS_GELU || epi == OASES_EPI_DGELU) && (!aux || ldaux < N)) { set_error("gemm: GeLU epilogue without aux"); return OASES_ENULL; }
 #define OASES_GEMM_CASE(E)                                                   \
@@ -573,6 +635,10 @@ int launch_gemm(int op, int epi, int M, int N, int K, const void* A, int lda, co
     OASES_GEMM_CASE(EPI_BIAS_BF16)
     OASES_GEMM_CASE(EPI_BIAS_GELU)
     OASES_GEMM_CASE(EPI_DGELU)
+    case EPI_SWIGLU:
+      return launch_shape<true, false, EPI_SWIGLU>(g, ws, wsb, forced_variant, s);
+    case EPI_DSWIGLU:
+      return launch_shape<true, true, EPI_DSWIGLU>(g, ws, wsb, forced_variant, s);
     default:
       set_error("gemm: unknown epilogue %d", epi);
       return OASES_EINVAL;
