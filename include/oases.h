@@ -63,7 +63,21 @@ typedef struct oases_layer_cfg {
   uint64_t seed;                       /* Philox key of the dropout masks */
   float ln_eps;                        /* LayerNorm epsilon; 0 selects 1e-5 */
   int32_t flags;                       /* OASES_FLAG_* */
+  int32_t arch;                        /* OASES_ARCH_GPT (0) or OASES_ARCH_LLAMA */
+  int32_t ffn_hidden;                  /* unsharded inner width F of the FFN; 0 selects 4h (OASES_ARCH_GPT requires 0 or 4h) */
+  float rope_theta;                    /* base of the rotary embedding (OASES_ARCH_LLAMA); 0 selects 10000 */
 } oases_layer_cfg;
+
+/* Layer families (the model rows of the paper's Table III).
+ * OASES_ARCH_GPT: pre-LayerNorm block, GeLU FFN of width 4h, biases on the four linear maps.
+ * OASES_ARCH_LLAMA: pre-RMSNorm block (ln1_g / ln2_g are the RMSNorm weights), rotary embedding on Q and K
+ *   ("rotate-half" pairing: element i of a head with element i + d/2, angle pos * theta^(-2i/d), pos = index of the
+ *   token in its sequence), SwiGLU FFN f = silu(v2 Wg) * (v2 Wu) of inner width F, no biases.  With fp = F/t
+ *   (fp % 32 == 0) the members of oases_weights / oases_grads mean: w1 [h, 2fp] bf16 = this rank's gate and up
+ *   columns interleaved in blocks of 32 (columns [64k, 64k+32) = gate columns [32k, 32k+32), the next 32 = the same up
+ *   columns), w2 [fp, h]; ln1_b, bqkv, bo, ln2_b, b1, b2 are unused and may be NULL.  The same Megatron partition,
+ *   the same four reduction points, schedule, flags and peer sums as OASES_ARCH_GPT. */
+enum { OASES_ARCH_GPT = 0, OASES_ARCH_LLAMA = 1 };
 
 enum {
   OASES_FLAG_SERIALISE = 1, /* enqueue everything on stream_compute only (same results) */

@@ -17,6 +17,7 @@ GEMM_NN, GEMM_NT, GEMM_TN = 0, 1, 2
 EPI_F32, EPI_BF16, EPI_BIAS_BF16, EPI_BIAS_GELU, EPI_DGELU = 0, 1, 2, 3, 4
 EPI_SWIGLU, EPI_DSWIGLU = 6, 7
 FLAG_SERIALISE, FLAG_PROFILE, FLAG_RECOMPUTE = 1, 2, 4
+ARCH_GPT, ARCH_LLAMA = 0, 1
 
 _P = C.c_void_p
 _PARAMS = ("ln1_g", "ln1_b", "wqkv", "bqkv", "wo", "bo", "ln2_g", "ln2_b", "w1", "b1", "w2", "b2")
@@ -27,7 +28,7 @@ class LayerCfg(C.Structure):
     _fields_ = [("hidden", C.c_int32), ("n_heads", C.c_int32), ("seq", C.c_int32), ("batch", C.c_int32),
                 ("tp_degree", C.c_int32), ("tp_rank", C.c_int32), ("n_sub", C.c_int32), ("n_layers", C.c_int32),
                 ("causal", C.c_int32), ("dropout_p", C.c_float), ("seed", C.c_uint64), ("ln_eps", C.c_float),
-                ("flags", C.c_int32)]
+                ("flags", C.c_int32), ("arch", C.c_int32), ("ffn_hidden", C.c_int32), ("rope_theta", C.c_float)]
 
 
 class Weights(C.Structure):
@@ -104,9 +105,11 @@ def stream_ptr(s):
 
 
 def make_cfg(cfg: dict, rank: int = 0, seed: int = 0, flags: int = 0, n_sub: int | None = None) -> LayerCfg:
+    llama = cfg.get("arch") == "llama"
     return LayerCfg(cfg["hidden"], cfg["n_heads"], cfg["seq"], cfg["batch"], cfg["tp"], rank,
                     cfg["n_sub"] if n_sub is None else n_sub, cfg["n_layers"], cfg["causal"], cfg["dropout_p"], seed,
-                    0.0, flags)
+                    0.0, flags, ARCH_LLAMA if llama else ARCH_GPT, cfg.get("ffn_hidden", 0) if llama else 0,
+                    cfg.get("rope_theta", 0.0) if llama else 0.0)
 
 
 class Handle:
@@ -192,6 +195,33 @@ def pack_rank_params(shard: dict, device="cuda"):
     for k in ("ln1_g", "ln1_b", "bo", "ln2_g", "ln2_b", "b1", "b2"):
         out[k] = t(shard[k], torch.float32)
     return out
+
+
+def interleave_gate_up(gate, up):
+    """[.., fp] x 2 -> [.., 2fp]: blocks of 32 gate columns, each followed by the same 32 up columns (the layout of
+    w1 and of the stored pre-activations in the LLaMA-style layer, see OASES_ARCH_LLAMA)."""
+    import numpy as np
+    *lead, fp = gate.shape
+    return np.stack([gate.reshape(*lead, fp // 32, 32), up.reshape(*lead, fp // 32, 32)], axis=-2).reshape(*lead, 2 * fp)
+
+
+def split_gate_up(w13):
+    """Inverse of interleave_gate_up on a numpy array or torch tensor: [.., 2fp] -> (gate [.., fp], up [.., fp])."""
+    *lead, two_fp = w13.shape
+    v = w13.reshape(*lead, two_fp // 64, 2, 32)
+    return v[..., 0, :].reshape(*lead, two_fp // 2), v[..., 1, :].reshape(*lead, two_fp // 2)
+
+
+def pack_llama_rank_params(shard: dict, device="cuda"):
+    """numpy dict from synth_inputs.shard_llama_layer_params -> device tensors in the library's layout: wqkv [h,3hp],
+    w1 [h,2fp] = gate / up columns interleaved in blocks of 32, wo, w2 bf16; RMSNorm weights fp32."""
+    import numpy as np
+    import torch
+    t = lambda a, dt: torch.from_numpy(np.ascontiguousarray(a)).to(device=device, dtype=dt)
+    return {"wqkv": t(np.concatenate([shard["wq"], shard["wk"], shard["wv"]], axis=1), torch.bfloat16),
+            "w1": t(interleave_gate_up(shard["wg"], shard["wu"]), torch.bfloat16),
+            "wo": t(shard["wo"], torch.bfloat16), "w2": t(shard["w2"], torch.bfloat16),
+            "ln1_g": t(shard["ln1_g"], torch.float32), "ln2_g": t(shard["ln2_g"], torch.float32)}
 
 
 def zero_grads_like(params: dict):

@@ -36,13 +36,36 @@ enum OpKind {
   // recompute mode: Recompute() of the saved sequences inside the backward pass
   R_LN2, R_FC1, R_LN1, R_QKV, R_ATTN,
   // stream join at the end of a pass
-  JOIN
+  JOIN,
+  // rotary embedding of the LLaMA-style layer: table once per forward pass, rotation of Q and K behind QKV (forward,
+  // recomputation), rotation back of dQ and dK behind the attention backward
+  F_ROPE_TABLE, F_ROPE, R_ROPE, B_ROPE
 };
 static const char* kOpName[] = {
     "LN1", "QKV", "ATTN", "PROJ", "R1+BDR1+LN2", "FC1+GELU", "FC2", "R2+BDR2",
     "BDR2.b", "FC2.dgrad+dGELU", "FC1.dgrad", "R3+LN2.b+BDR1.b", "FC2.wgrad", "FC1.wgrad", "b1.sum", "PROJ.dgrad",
     "PROJ.wgrad", "ATTN.b", "QKV.dgrad", "R4+LN1.b", "QKV.wgrad", "bqkv.sum",
-    "LN2.r", "FC1+GELU.r", "LN1.r", "QKV.r", "ATTN.r", "join"};
+    "LN2.r", "FC1+GELU.r", "LN1.r", "QKV.r", "ATTN.r", "join", "ROPE.table", "ROPE", "ROPE.r", "ROPE.b"};
+// names of the same operator slots in the LLaMA-style layer (RMSNorm, SwiGLU)
+static const char* op_name(int kind, bool llama) {
+  if (llama) {
+    switch (kind) {
+      case F_FC1: return "FC1+SWIGLU";
+      case R_FC1: return "FC1+SWIGLU.r";
+      case B_FC2_DGRAD: return "FC2.dgrad+dSWIGLU";
+      case F_R1: return "R1+DR1+RMS2";
+      case F_R2: return "R2+DR2";
+      case B_BDR2: return "DR2.b";
+      case B_R3: return "R3+RMS2.b+DR1.b";
+      case B_R4: return "R4+RMS1.b";
+      case F_LN1: return "RMS1";
+      case R_LN1: return "RMS1.r";
+      case R_LN2: return "RMS2.r";
+      default: break;
+    }
+  }
+  return kOpName[kind];
+}
 
 struct Op {
   int kind, layer, sub;
@@ -64,7 +87,9 @@ using namespace oases;
 struct oases_handle {
   oases_layer_cfg cfg;
   int h, nh, d, s, b, t, r, n, L, M, Ms, hp, fp, heads_l;
-  float eps;
+  int fw;        // columns of the FC1 output that is stored for backward: fp (GeLU), 2*fp (SwiGLU: gate and up)
+  bool llama;    // OASES_ARCH_LLAMA: RMSNorm, rotary embedding, SwiGLU, no biases
+  float eps, theta;
   std::vector<Op> fwd, bwd;
   int n_events;
   std::vector<hipEvent_t> events;  // created on first use
@@ -79,13 +104,15 @@ namespace oases {
 static size_t align_up(size_t x) { return (x + 255) & ~(size_t)255; }
 
 static void plan_workspace(oases_handle* H) {
-  const size_t M = H->M, h = H->h, hp = H->hp, fp = H->fp, st = (size_t)H->b * H->heads_l * H->s;
+  const size_t M = H->M, h = H->h, hp = H->hp, fp = H->fp, fw = H->fw, st = (size_t)H->b * H->heads_l * H->s;
+  const size_t rope = H->llama ? (size_t)H->s * (H->d / 2) * 8 : 0;  // (cos, sin) table; layer 0's copy is the one in use
   struct { const char* n; size_t bytes; } list[] = {
       {"u", M * h * 2},      {"mu1", M * 4},        {"rstd1", M * 4},      {"qkv", M * 3 * hp * 2}, {"attn", M * hp * 2},
       {"lse", st * 4},       {"z1", M * h * 4},     {"x1", M * h * 4},     {"mu2", M * 4},          {"rstd2", M * 4},
-      {"v2", M * h * 2},     {"pre", M * fp * 2},   {"f", M * fp * 2},     {"z2", M * h * 4},       {"y", M * h * 4},
-      {"dz2", M * h * 2},    {"dg", M * fp * 2},    {"dv2", M * h * 4},    {"dx1", M * h * 4},      {"dz1", M * h * 2},
-      {"da", M * hp * 2},    {"delta", st * 4},     {"dqkv", M * 3 * hp * 2}, {"du", M * h * 4},    {"dy", M * h * 4}};
+      {"v2", M * h * 2},     {"pre", M * fw * 2},   {"f", M * fp * 2},     {"z2", M * h * 4},       {"y", M * h * 4},
+      {"dz2", M * h * 2},    {"dg", M * fw * 2},    {"dv2", M * h * 4},    {"dx1", M * h * 4},      {"dz1", M * h * 2},
+      {"da", M * hp * 2},    {"delta", st * 4},     {"dqkv", M * 3 * hp * 2}, {"du", M * h * 4},    {"dy", M * h * 4},
+      {"rope", rope}};
   // Recompute mode (the paper's fine-grained recomputation, Sec. IV-B): only the input of each computation
   // sequence is kept per layer -- x (= y of the layer below) for [LN1,QKV,ATTN,PROJ] and x1 for [LN2,FC1,FC2] -- the
   // activations in between are rebuilt inside backward and live in one region shared by all layers.
@@ -110,12 +137,12 @@ static void plan_workspace(oases_handle* H) {
   H->scratch_comm_off = tot;
   tot += align_up((size_t)3 * kColPartials * h * 4);
   H->scratch_compute_off = tot;
-  size_t wide = 3 * hp > fp ? 3 * hp : fp;
+  size_t wide = 3 * hp > fw ? 3 * hp : fw;
   tot += align_up((size_t)kColPartials * wide * 4);
   // split-K partial planes: up to 8 fp32 copies of the widest GEMM output of the layer
   const size_t Ms = H->Ms;
   size_t mn = Ms * h;
-  for (size_t v : {Ms * 3 * hp, Ms * fp, fp * h, h * 3 * hp, hp * h}) mn = v > mn ? v : mn;
+  for (size_t v : {Ms * 3 * hp, Ms * fw, fw * h, h * 3 * hp, hp * h}) mn = v > mn ? v : mn;
   H->gemm_ws_off = tot;
   H->gemm_ws_bytes = 8 * mn * 4 < kSplitKWorkspaceBytes ? 8 * mn * 4 : kSplitKWorkspaceBytes;
   tot += align_up(H->gemm_ws_bytes);
@@ -140,11 +167,13 @@ static int ev_id(const oases_handle* H, int layer, int point, int sub, int kind)
 static void build_forward(oases_handle* H) {
   auto& ops = H->fwd;
   const int n = H->n;
+  if (H->llama) ops.push_back(Op{F_ROPE_TABLE, 0, -1, 0, -1, -1});
   for (int l = 0; l < H->L; l++) {
     for (int j = 0; j < n; j++) {
       int w = l > 0 ? ev_id(H, l - 1, 1, j, 1) : -1;  // input of this layer comes out of R2 of the layer below
       if (l == 0) { ops.push_back(Op{F_LN1, l, j, 0, -1, -1}); }
       ops.push_back(Op{F_QKV, l, j, 0, w, -1});
+      if (H->llama) ops.push_back(Op{F_ROPE, l, j, 0, -1, -1});
       ops.push_back(Op{F_ATTN, l, j, 0, -1, -1});
       ops.push_back(Op{F_PROJ, l, j, 0, -1, ev_id(H, l, 0, j, 0)});
       ops.push_back(Op{F_R1, l, j, 1, ev_id(H, l, 0, j, 0), ev_id(H, l, 0, j, 1)});
@@ -185,11 +214,12 @@ static void build_backward(oases_handle* H) {
     // weight gradients: one contraction over the rows of ALL sub-batches (sub = -1), behind the last reduction start
     ops.push_back(Op{B_FC2_WGRAD, l, -1, 0, -1, -1});
     ops.push_back(Op{B_FC1_WGRAD, l, -1, 0, -1, -1});
-    ops.push_back(Op{B_B1_SUM, l, -1, 0, -1, -1});
+    if (!H->llama) ops.push_back(Op{B_B1_SUM, l, -1, 0, -1, -1});
     if (recompute && chunks)  // K/V of every chunk must exist again before any chunk's attention is rebuilt
       for (int j = n - 1; j >= 0; j--) {
         ops.push_back(Op{R_LN1, l, j, 0, -1, -1});
         ops.push_back(Op{R_QKV, l, j, 0, -1, -1});
+        if (H->llama) ops.push_back(Op{R_ROPE, l, j, 0, -1, -1});
       }
     if (recompute && chunks)  // ... and the attention output / LSE of later chunks before an earlier chunk's dK/dV
       for (int j = 0; j < n; j++) ops.push_back(Op{R_ATTN, l, j, 0, -1, -1});
@@ -197,16 +227,18 @@ static void build_backward(oases_handle* H) {
       if (recompute && !chunks) {  // Recompute() of [LN1, QKV, ATTN]: starts at the layer input
         ops.push_back(Op{R_LN1, l, j, 0, -1, -1});
         ops.push_back(Op{R_QKV, l, j, 0, -1, -1});
+        if (H->llama) ops.push_back(Op{R_ROPE, l, j, 0, -1, -1});
         ops.push_back(Op{R_ATTN, l, j, 0, -1, -1});
       }
       ops.push_back(Op{B_PROJ_DGRAD, l, j, 0, ev_id(H, l, 2, j, 1), -1});
       ops.push_back(Op{B_ATTN, l, j, 0, -1, -1});
+      if (H->llama) ops.push_back(Op{B_ROPE, l, j, 0, -1, -1});
       ops.push_back(Op{B_QKV_DGRAD, l, j, 0, -1, ev_id(H, l, 3, j, 0)});
       ops.push_back(Op{B_R4, l, j, 1, ev_id(H, l, 3, j, 0), ev_id(H, l, 3, j, 1)});
     }
     ops.push_back(Op{B_PROJ_WGRAD, l, -1, 0, -1, -1});
     ops.push_back(Op{B_QKV_WGRAD, l, -1, 0, -1, -1});
-    ops.push_back(Op{B_BQKV_SUM, l, -1, 0, -1, -1});
+    if (!H->llama) ops.push_back(Op{B_BQKV_SUM, l, -1, 0, -1, -1});
   }
   for (int j = n - 1; j >= 0; j--) ops.push_back(Op{JOIN, 0, j, 0, ev_id(H, 0, 3, j, 1), -1});
 }
@@ -274,13 +306,23 @@ static int run_op(const Run& R, const Op& op) {
   uint16_t* v2 = wsp<uint16_t>(R, "v2", l);
   uint16_t* pre = wsp<uint16_t>(R, "pre", l);
   uint16_t* f = wsp<uint16_t>(R, "f", l);
+  const bool rms = H->llama;   // RMSNorm, no biases: the bias / beta / mean arguments below are NULL and unused
+  const int fw = H->fw;
   switch (op.kind) {
     case F_LN1:
       return launch_layernorm_fwd(xin + r0 * h, (const float*)W.ln1_g, (const float*)W.ln1_b, u + r0 * h,
-                                  wsp<float>(R, "mu1", l) + r0, wsp<float>(R, "rstd1", l) + r0, Ms, h, H->eps, s);
+                                  wsp<float>(R, "mu1", l) + r0, wsp<float>(R, "rstd1", l) + r0, Ms, h, H->eps, s, rms);
     case F_QKV:
-      return launch_gemm(OASES_GEMM_NN, OASES_EPI_BIAS_BF16, Ms, 3 * hp, h, u + r0 * h, h, W.wqkv, 3 * hp, qkv + r0 * 3 * hp,
-                         3 * hp, (const float*)W.bqkv, nullptr, 0, gws, H->gemm_ws_bytes, 0, s);
+      return launch_gemm(OASES_GEMM_NN, rms ? OASES_EPI_BF16 : OASES_EPI_BIAS_BF16, Ms, 3 * hp, h, u + r0 * h, h, W.wqkv, 3 * hp,
+                         qkv + r0 * 3 * hp, 3 * hp, (const float*)W.bqkv, nullptr, 0, gws, H->gemm_ws_bytes, 0, s);
+    case F_ROPE_TABLE:
+      return launch_rope_table(wsp<float>(R, "rope", 0), H->s, H->d, H->theta, s);
+    case F_ROPE:
+    case R_ROPE:
+      return launch_rope(qkv + r0 * 3 * hp, 3 * hp, Ms, (int64_t)r0, H->s, H->heads_l, H->d, wsp<float>(R, "rope", 0), 0, s);
+    case B_ROPE:
+      return launch_rope(wsp<uint16_t>(R, "dqkv", l) + r0 * 3 * hp, 3 * hp, Ms, (int64_t)r0, H->s, H->heads_l, H->d,
+                         wsp<float>(R, "rope", 0), 1, s);
     case F_ATTN:
       return launch_attention_fwd(qkv, attn, wsp<float>(R, "lse", l), H->b, H->s, H->heads_l, H->d, H->cfg.causal, (int)r0, Ms, s);
     case F_PROJ:
@@ -290,8 +332,11 @@ static int run_op(const Run& R, const Op& op) {
       return launch_bdr_ln(wsp<float>(R, "z1", l) + r0 * h, peer(P ? P->fwd_attn : nullptr), (const float*)W.bo, xin + r0 * h,
                            wsp<float>(R, "x1", l) + r0 * h, (const float*)W.ln2_g, (const float*)W.ln2_b, v2 + r0 * h,
                            wsp<float>(R, "mu2", l) + r0, wsp<float>(R, "rstd2", l) + r0, Ms, h, H->eps,
-                           make_drop_cfg(seed, l, 0, p), (int64_t)r0, s);
+                           make_drop_cfg(seed, l, 0, p), (int64_t)r0, s, rms);
     case F_FC1:
+      if (H->llama)  // w1 = [gate | up] columns interleaved in blocks of 32; pre = both pre-activations, f = silu(gate)*up
+        return launch_gemm(OASES_GEMM_NN, OASES_EPI_SWIGLU, Ms, fw, h, v2 + r0 * h, h, W.w1, fw, f + r0 * fp, fp, nullptr,
+                           pre + r0 * fw, fw, gws, H->gemm_ws_bytes, 0, s);
       return launch_gemm(OASES_GEMM_NN, OASES_EPI_BIAS_GELU, Ms, fp, h, v2 + r0 * h, h, W.w1, fp, f + r0 * fp, fp,
                          (const float*)W.b1, pre + r0 * fp, fp, gws, H->gemm_ws_bytes, 0, s);
     case F_FC2:
@@ -303,29 +348,32 @@ static int run_op(const Run& R, const Op& op) {
                            wsp<float>(R, "x1", l) + r0 * h, yout + r0 * h, more ? (const float*)R.w[l + 1].ln1_g : nullptr,
                            more ? (const float*)R.w[l + 1].ln1_b : nullptr, more ? wsp<uint16_t>(R, "u", l + 1) + r0 * h : nullptr,
                            more ? wsp<float>(R, "mu1", l + 1) + r0 : nullptr, more ? wsp<float>(R, "rstd1", l + 1) + r0 : nullptr,
-                           Ms, h, H->eps, make_drop_cfg(seed, l, 1, p), (int64_t)r0, s);
+                           Ms, h, H->eps, make_drop_cfg(seed, l, 1, p), (int64_t)r0, s, rms);
     }
     // ---------------------------------------------------------------- backward
     case B_BDR2:
       return launch_dropout_bwd(dyin + r0 * h, wsp<uint16_t>(R, "dz2", l) + r0 * h, (float*)R.g[l].b2, Ms, h,
                                 make_drop_cfg(seed, l, 1, p), (int64_t)r0, scr_comm, s);
     case B_FC2_DGRAD:
+      if (H->llama)
+        return launch_gemm(OASES_GEMM_NT, OASES_EPI_DSWIGLU, Ms, fp, h, wsp<uint16_t>(R, "dz2", l) + r0 * h, h, W.w2, h,
+                           wsp<uint16_t>(R, "dg", l) + r0 * fw, fw, nullptr, pre + r0 * fw, fw, gws, H->gemm_ws_bytes, 0, s);
       return launch_gemm(OASES_GEMM_NT, OASES_EPI_DGELU, Ms, fp, h, wsp<uint16_t>(R, "dz2", l) + r0 * h, h, W.w2, h,
                          wsp<uint16_t>(R, "dg", l) + r0 * fp, fp, nullptr, pre + r0 * fp, fp, gws, H->gemm_ws_bytes, 0, s);
     case B_FC1_DGRAD:
-      return launch_gemm(OASES_GEMM_NT, OASES_EPI_F32, Ms, h, fp, wsp<uint16_t>(R, "dg", l) + r0 * fp, fp, W.w1, fp,
+      return launch_gemm(OASES_GEMM_NT, OASES_EPI_F32, Ms, h, fw, wsp<uint16_t>(R, "dg", l) + r0 * fw, fw, W.w1, fw,
                          wsp<float>(R, "dv2", l) + r0 * h, h, nullptr, nullptr, 0, gws, H->gemm_ws_bytes, 0, s);
     case B_R3:
       return launch_layernorm_bwd(wsp<float>(R, "dv2", l) + r0 * h, peer(P ? P->bwd_ffn : nullptr), dyin + r0 * h,
                                   wsp<float>(R, "x1", l) + r0 * h, wsp<float>(R, "mu2", l) + r0, wsp<float>(R, "rstd2", l) + r0,
                                   (const float*)W.ln2_g, wsp<float>(R, "dx1", l) + r0 * h, (float*)R.g[l].ln2_g,
                                   (float*)R.g[l].ln2_b, wsp<uint16_t>(R, "dz1", l) + r0 * h, (float*)R.g[l].bo, Ms, h,
-                                  make_drop_cfg(seed, l, 0, p), (int64_t)r0, scr_comm, s);
+                                  make_drop_cfg(seed, l, 0, p), (int64_t)r0, scr_comm, s, rms);
     case B_FC2_WGRAD:
       return launch_gemm(OASES_GEMM_TN, 0, fp, h, Ms, f + r0 * fp, fp, wsp<uint16_t>(R, "dz2", l) + r0 * h, h, R.g[l].w2, h,
                          nullptr, nullptr, 0, gws, H->gemm_ws_bytes, 0, s);
     case B_FC1_WGRAD:
-      return launch_gemm(OASES_GEMM_TN, 0, h, fp, Ms, v2 + r0 * h, h, wsp<uint16_t>(R, "dg", l) + r0 * fp, fp, R.g[l].w1, fp,
+      return launch_gemm(OASES_GEMM_TN, 0, h, fw, Ms, v2 + r0 * h, h, wsp<uint16_t>(R, "dg", l) + r0 * fw, fw, R.g[l].w1, fw,
                          nullptr, nullptr, 0, gws, H->gemm_ws_bytes, 0, s);
     case B_B1_SUM:
       return launch_colsum_bf16(wsp<uint16_t>(R, "dg", l) + r0 * fp, fp, Ms, fp, (float*)R.g[l].b1, scr_comp, s);
@@ -348,7 +396,7 @@ static int run_op(const Run& R, const Op& op) {
                                   wsp<float>(R, "rstd1", l) + r0, (const float*)W.ln1_g, dxout + r0 * h, (float*)R.g[l].ln1_g,
                                   (float*)R.g[l].ln1_b, more ? wsp<uint16_t>(R, "dz2", l - 1) + r0 * h : nullptr,
                                   more ? (float*)R.g[l - 1].b2 : nullptr, Ms, h, make_drop_cfg(seed, l - 1, 1, p), (int64_t)r0,
-                                  scr_comm, s);
+                                  scr_comm, s, rms);
     }
     case B_QKV_WGRAD:
       return launch_gemm(OASES_GEMM_TN, 0, h, 3 * hp, Ms, u + r0 * h, h, wsp<uint16_t>(R, "dqkv", l) + r0 * 3 * hp, 3 * hp,
@@ -358,7 +406,7 @@ static int run_op(const Run& R, const Op& op) {
     // ---------------------------------------------------------------- recompute: the forward kernels again
     case R_LN1:
       return launch_layernorm_fwd(xin + r0 * h, (const float*)W.ln1_g, (const float*)W.ln1_b, u + r0 * h,
-                                  wsp<float>(R, "mu1", l) + r0, wsp<float>(R, "rstd1", l) + r0, Ms, h, H->eps, s);
+                                  wsp<float>(R, "mu1", l) + r0, wsp<float>(R, "rstd1", l) + r0, Ms, h, H->eps, s, rms);
     case R_QKV: {
       Op f = op;
       f.kind = F_QKV;
@@ -371,7 +419,7 @@ static int run_op(const Run& R, const Op& op) {
     }
     case R_LN2:
       return launch_layernorm_fwd(wsp<float>(R, "x1", l) + r0 * h, (const float*)W.ln2_g, (const float*)W.ln2_b, v2 + r0 * h,
-                                  wsp<float>(R, "mu2", l) + r0, wsp<float>(R, "rstd2", l) + r0, Ms, h, H->eps, s);
+                                  wsp<float>(R, "mu2", l) + r0, wsp<float>(R, "rstd2", l) + r0, Ms, h, H->eps, s, rms);
     case R_FC1: {
       Op f = op;
       f.kind = F_FC1;
@@ -441,7 +489,14 @@ int oases_create(const oases_layer_cfg* c, oases_handle** out) {
   const int d = c->hidden / c->n_heads;
   if (d != 64 && d != 128) BAD("head dimension %d unsupported (64 or 128)", d);
   if (c->n_heads % c->tp_degree) BAD("n_heads %d not divisible by tp_degree %d", c->n_heads, c->tp_degree);
-  if ((4 * c->hidden) % c->tp_degree) BAD("FFN width %d not divisible by tp_degree %d", 4 * c->hidden, c->tp_degree);
+  if (c->arch != OASES_ARCH_GPT && c->arch != OASES_ARCH_LLAMA) BAD("unknown arch %d", c->arch);
+  const bool llama = c->arch == OASES_ARCH_LLAMA;
+  if (!llama && c->ffn_hidden != 0 && c->ffn_hidden != 4 * c->hidden) BAD("the GPT layer has FFN width 4h (ffn_hidden = 0)");
+  const int F = c->ffn_hidden > 0 ? c->ffn_hidden : 4 * c->hidden;
+  if (F % c->tp_degree) BAD("FFN width %d not divisible by tp_degree %d", F, c->tp_degree);
+  if (llama && (F / c->tp_degree) % 32) BAD("SwiGLU: FFN columns per rank %d must be a multiple of 32", F / c->tp_degree);
+  if (!llama && (F / c->tp_degree) % 8) BAD("FFN columns per rank %d must be a multiple of 8", F / c->tp_degree);
+  if (c->rope_theta != 0.f && !(c->rope_theta > 1.f)) BAD("rope_theta %g must exceed 1", (double)c->rope_theta);
   if (c->hidden > 16384) BAD("hidden %d too large (max 16384)", c->hidden);
   if (!(c->dropout_p >= 0.f && c->dropout_p < 1.f)) BAD("dropout_p %g outside [0,1)", (double)c->dropout_p);
   if (c->ln_eps < 0.f) BAD("ln_eps negative");
@@ -462,8 +517,11 @@ int oases_create(const oases_layer_cfg* c, oases_handle** out) {
   H->cfg = *c;
   H->h = c->hidden; H->nh = c->n_heads; H->d = d; H->s = c->seq; H->b = c->batch; H->t = c->tp_degree; H->r = c->tp_rank;
   H->n = c->n_sub; H->L = c->n_layers; H->M = (int)M; H->Ms = (int)Ms;
-  H->hp = c->hidden / c->tp_degree; H->fp = 4 * c->hidden / c->tp_degree; H->heads_l = c->n_heads / c->tp_degree;
+  H->hp = c->hidden / c->tp_degree; H->fp = F / c->tp_degree; H->heads_l = c->n_heads / c->tp_degree;
+  H->llama = llama;
+  H->fw = llama ? 2 * H->fp : H->fp;
   H->eps = c->ln_eps > 0.f ? c->ln_eps : 1e-5f;
+  H->theta = c->rope_theta > 0.f ? c->rope_theta : 10000.f;
   H->n_events = H->L * 4 * H->n * 2 + 1;  // + the fork event that orders stream_comm behind stream_compute
   plan_workspace(H);
   build_forward(H);
@@ -515,8 +573,9 @@ int oases_schedule_dump(const oases_handle* H, int backward, char* buf, size_t n
   std::string s;
   char line[96];
   for (const Op& op : backward ? H->bwd : H->fwd) {
-    if (op.sub < 0) snprintf(line, sizeof line, "%s %s L%d sb*\n", op.stream ? "comm" : "compute", kOpName[op.kind], op.layer);
-    else snprintf(line, sizeof line, "%s %s L%d sb%d\n", op.stream ? "comm" : "compute", kOpName[op.kind], op.layer, op.sub);
+    const char* name = op_name(op.kind, H->llama);
+    if (op.sub < 0) snprintf(line, sizeof line, "%s %s L%d sb*\n", op.stream ? "comm" : "compute", name, op.layer);
+    else snprintf(line, sizeof line, "%s %s L%d sb%d\n", op.stream ? "comm" : "compute", name, op.layer, op.sub);
     s += line;
   }
   if (buf && n) {
@@ -529,8 +588,8 @@ int oases_schedule_dump(const oases_handle* H, int backward, char* buf, size_t n
 
 static int check_weights(const oases_handle* H, const oases_weights* w) {
   for (int l = 0; l < H->L; l++) {
-    const void* p[] = {w[l].ln1_g, w[l].ln1_b, w[l].wqkv, w[l].bqkv, w[l].wo, w[l].bo, w[l].ln2_g, w[l].ln2_b, w[l].w1, w[l].b1, w[l].w2, w[l].b2};
-    int rc = check_ptrs(p, 12, "weights");
+    const void* p[] = {w[l].ln1_g, w[l].wqkv, w[l].wo, w[l].ln2_g, w[l].w1, w[l].w2, w[l].ln1_b, w[l].bqkv, w[l].bo, w[l].ln2_b, w[l].b1, w[l].b2};
+    int rc = check_ptrs(p, H->llama ? 6 : 12, "weights");  // the LLaMA-style layer has no biases and no LayerNorm shifts
     if (rc) return rc;
   }
   return 0;
@@ -557,8 +616,8 @@ int oases_backward(oases_handle* H, const oases_weights* w, const void* x, const
   if (rc) return rc;
   if ((rc = check_weights(H, w))) return rc;
   for (int l = 0; l < H->L; l++) {
-    const void* q[] = {g[l].ln1_g, g[l].ln1_b, g[l].wqkv, g[l].bqkv, g[l].wo, g[l].bo, g[l].ln2_g, g[l].ln2_b, g[l].w1, g[l].b1, g[l].w2, g[l].b2};
-    if ((rc = check_ptrs(q, 12, "grads"))) return rc;
+    const void* q[] = {g[l].ln1_g, g[l].wqkv, g[l].wo, g[l].ln2_g, g[l].w1, g[l].w2, g[l].ln1_b, g[l].bqkv, g[l].bo, g[l].ln2_b, g[l].b1, g[l].b2};
+    if ((rc = check_ptrs(q, H->llama ? 6 : 12, "grads"))) return rc;
   }
   Run R{H, w, g, peers, (char*)workspace, (const float*)x, nullptr, (const float*)dy, (float*)dx,
         {(hipStream_t)stream_compute, (hipStream_t)stream_comm}};
