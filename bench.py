@@ -21,10 +21,18 @@ PEAK_BF16_TFLOPS = 2516.6     # MI355X dense bf16 MFMA (256 CU x 2.4 GHz x 4096 
 PEAK_HBM_GBS = 8000.0
 
 
+def widths(cfg):
+    """(hp, fp, fw): local attention width, local FFN inner width, columns of the FC1 GEMM (SwiGLU: gate and up)."""
+    h, t = cfg["hidden"], cfg["tp"]
+    llama = cfg.get("arch") == "llama"
+    fp = (cfg["ffn_hidden"] if llama else 4 * h) // t
+    return h // t, fp, (2 * fp if llama else fp)
+
+
 def model_flops(cfg):
     M, h, s, t, L = cfg["batch"] * cfg["seq"], cfg["hidden"], cfg["seq"], cfg["tp"], cfg["n_layers"]
-    hp = h // t
-    gemm = 24.0 * M * h * hp
+    hp, fp, fw = widths(cfg)
+    gemm = 2.0 * M * h * (3 * hp + hp + fw + fp)
     attn = (2.0 if cfg["causal"] else 4.0) * M * s * hp
     return 3.0 * (gemm + attn) * L
 
@@ -32,10 +40,11 @@ def model_flops(cfg):
 def op_flops(line, cfg):
     """Algorithmic flops of one scheduled GEMM / attention operator (one sub-batch); 0 for the HBM-bound ones."""
     M, h, s, t = cfg["batch"] * cfg["seq"], cfg["hidden"], cfg["seq"], cfg["tp"]
-    Ms, hp, fp = (M if line.endswith("sb*") else M // cfg["n_sub"]), h // t, 4 * h // t
+    Ms = M if line.endswith("sb*") else M // cfg["n_sub"]
+    hp, fp, fw = widths(cfg)
     op = line.split()[1]
     base = op.split(".")[0].split("+")[0]
-    table = {"QKV": 2.0 * Ms * h * 3 * hp, "PROJ": 2.0 * Ms * hp * h, "FC1": 2.0 * Ms * h * fp, "FC2": 2.0 * Ms * fp * h}
+    table = {"QKV": 2.0 * Ms * h * 3 * hp, "PROJ": 2.0 * Ms * hp * h, "FC1": 2.0 * Ms * h * fw, "FC2": 2.0 * Ms * fp * h}
     if base in table:
         return table[base]
     if base == "ATTN":
@@ -50,23 +59,33 @@ def op_bytes(line, cfg):
     e = (M // cfg["n_sub"]) * h
     op = line.split()[1]
     per_elem = {"LN1": 4 + 2, "R1+BDR1+LN2": 4 + 4 + 4 + 2, "R2+BDR2": 4 + 4 + 4, "BDR2.b": 4 + 2,
-                "R3+LN2.b+BDR1.b": 4 + 4 + 4 + 4 + 2, "R4+LN1.b": 4 + 4 + 4 + 4}
+                "R3+LN2.b+BDR1.b": 4 + 4 + 4 + 4 + 2, "R4+LN1.b": 4 + 4 + 4 + 4,
+                "RMS1": 4 + 2, "R1+DR1+RMS2": 4 + 4 + 4 + 2, "R2+DR2": 4 + 4 + 4, "DR2.b": 4 + 2,
+                "R3+RMS2.b+DR1.b": 4 + 4 + 4 + 4 + 2, "R4+RMS1.b": 4 + 4 + 4 + 4}
+    if op.startswith("ROPE") and op != "ROPE.table":      # Q and K parts of the bf16 qkv rows, read and written
+        return float((M // cfg["n_sub"]) * 2 * widths(cfg)[0] * 2 * 2)
     return float(per_elem.get(op, 0)) * e
 
 
 def gemm_kernel_label(line, cfg, B, ws_bytes):
     """Kernel instantiation a GEMM operator runs on: (contraction form, epilogue, block tile)."""
     M, h, t = cfg["batch"] * cfg["seq"], cfg["hidden"], cfg["tp"]
-    Ms, hp, fp = (M if line.endswith("sb*") else M // cfg["n_sub"]), h // t, 4 * h // t
+    Ms = M if line.endswith("sb*") else M // cfg["n_sub"]
+    hp, fp, fw = widths(cfg)
+    llama = cfg.get("arch") == "llama"
     op = line.split()[1]
-    shapes = {"QKV": ("NN", "bias_bf16", Ms, 3 * hp, h), "PROJ": ("NN", "f32", Ms, h, hp), "FC1+GELU": ("NN", "bias_gelu", Ms, fp, h),
-              "FC2": ("NN", "f32", Ms, h, fp), "FC2.dgrad+dGELU": ("NT", "dgelu", Ms, fp, h), "FC1.dgrad": ("NT", "f32", Ms, h, fp),
+    if op.endswith(".r"):
+        op = op[:-2]
+    shapes = {"QKV": ("NN", "bf16" if llama else "bias_bf16", Ms, 3 * hp, h), "PROJ": ("NN", "f32", Ms, h, hp),
+              "FC1+GELU": ("NN", "bias_gelu", Ms, fp, h), "FC1+SWIGLU": ("NN", "swiglu", Ms, fw, h),
+              "FC2": ("NN", "f32", Ms, h, fp), "FC2.dgrad+dGELU": ("NT", "dgelu", Ms, fp, h), "FC2.dgrad+dSWIGLU": ("NT", "dswiglu", Ms, fp, h),
+              "FC1.dgrad": ("NT", "f32", Ms, h, fw),
               "PROJ.dgrad": ("NT", "bf16", Ms, hp, h), "QKV.dgrad": ("NT", "f32", Ms, h, 3 * hp), "FC2.wgrad": ("TN", "acc_f32", fp, h, Ms),
-              "FC1.wgrad": ("TN", "acc_f32", h, fp, Ms), "PROJ.wgrad": ("TN", "acc_f32", hp, h, Ms), "QKV.wgrad": ("TN", "acc_f32", h, 3 * hp, Ms)}
+              "FC1.wgrad": ("TN", "acc_f32", h, fw, Ms), "PROJ.wgrad": ("TN", "acc_f32", hp, h, Ms), "QKV.wgrad": ("TN", "acc_f32", h, 3 * hp, Ms)}
     if op not in shapes:
         return None
     form, epi, m, n, k = shapes[op]
-    epi_id = {"f32": 0, "bf16": 1, "bias_bf16": 2, "bias_gelu": 3, "dgelu": 4, "acc_f32": 0}[epi]
+    epi_id = {"f32": 0, "bf16": 1, "bias_bf16": 2, "bias_gelu": 3, "dgelu": 4, "acc_f32": 0, "swiglu": 6, "dswiglu": 7}[epi]
     tile = B.lib.oases_op_gemm_variant({"NN": 0, "NT": 1, "TN": 2}[form], epi_id, m, n, k, ws_bytes)
     slices = tile // 1000000 % 100
     split = f"_splitk{slices}" if slices >= 2 else ""
@@ -78,8 +97,12 @@ def cpu_baseline(cfg, name):
     """The oracle as it stands, timed on the host cores: the rank-0 shard's layer (the same work the GPU does)."""
     import torch
     import synth_inputs as si
-    from oracle import layer_oracle as lo
-    layers = [si.shard_layer_params(si.make_layer_params(cfg, l, 0), cfg, 0) for l in range(cfg["n_layers"])]
+    if cfg.get("arch") == "llama":
+        from oracle import llama_oracle as lo
+        layers = [si.shard_llama_layer_params(si.make_llama_layer_params(cfg, l, 0), cfg, 0) for l in range(cfg["n_layers"])]
+    else:
+        from oracle import layer_oracle as lo
+        layers = [si.shard_layer_params(si.make_layer_params(cfg, l, 0), cfg, 0) for l in range(cfg["n_layers"])]
     x, dy = si.make_activations(cfg, 0)
     t0 = time.perf_counter()
     lo.model_forward_backward(layers, x, dy, cfg, seed=0, dtype=torch.float32)
@@ -94,7 +117,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--config", default="C4", help="workload: C1..C5 (default C4, h=4096)")
+    ap.add_argument("--config", default="C4", help="workload: C1..C5 GPT layers (default C4, h=4096), L1/L2/L4 LLaMA-style layers")
     ap.add_argument("--n-sub", type=int, default=None, help="override the sub-batch count of the workload")
     ap.add_argument("--serialise", action="store_true", help="single stream")
     ap.add_argument("--recompute", action="store_true",
@@ -113,13 +136,15 @@ def main():
     if not torch.cuda.is_available():
         sys.exit("bench.py: no GPU visible")
 
-    cfg = dict(si.CONFIGS[a.config])
+    cfg = dict({**si.CONFIGS, **si.LLAMA_CONFIGS}[a.config])
     if a.n_sub:
         cfg["n_sub"] = a.n_sub
     M, h = cfg["batch"] * cfg["seq"], cfg["hidden"]
-    layers = [si.make_layer_params(cfg, l, 0) for l in range(cfg["n_layers"])]
     x, dy = si.make_activations(cfg, 0)
-    W = [B.pack_rank_params(si.shard_layer_params(p, cfg, 0)) for p in layers]
+    if cfg.get("arch") == "llama":
+        W = [B.pack_llama_rank_params(si.shard_llama_layer_params(si.make_llama_layer_params(cfg, l, 0), cfg, 0)) for l in range(cfg["n_layers"])]
+    else:
+        W = [B.pack_rank_params(si.shard_layer_params(si.make_layer_params(cfg, l, 0), cfg, 0)) for l in range(cfg["n_layers"])]
     G = [B.zero_grads_like(w) for w in W]
     xd, dyd = torch.from_numpy(x).cuda(), torch.from_numpy(dy).cuda()
     yd, dxd = torch.empty_like(xd), torch.empty_like(xd)
@@ -152,8 +177,8 @@ def main():
            "value": round(tflops, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
            "ms_per_step": round(dt * 1e3, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
            "data": "synthetic",
-           "config": {"workload": f"{a.config}: GPT layer h={h} heads={cfg['n_heads']} seq={cfg['seq']} batch={cfg['batch']} "
-                                  f"t={cfg['tp']} rank 0 layers={cfg['n_layers']} causal={cfg['causal']} p={cfg['dropout_p']}",
+           "config": {"workload": f"{a.config}: {'LLaMA-style' if cfg.get('arch') == 'llama' else 'GPT'} layer h={h} heads={cfg['n_heads']} seq={cfg['seq']} batch={cfg['batch']} "
+                                  f"t={cfg['tp']} rank 0 layers={cfg['n_layers']} causal={cfg['causal']} p={cfg['dropout_p']}" + (f" ffn={cfg['ffn_hidden']}" if cfg.get("arch") == "llama" else ""),
                       "n_sub": cfg["n_sub"], "streams": 1 if a.serialise else 2, "recompute": bool(a.recompute),
                       "workspace_mib": round(H.workspace_bytes / 2 ** 20, 1), "model_gflop_per_step": round(flops / 1e9, 1),
                       "frac_of_bf16_peak": round(tflops / PEAK_BF16_TFLOPS, 4)}}

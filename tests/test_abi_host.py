@@ -169,3 +169,59 @@ def test_schedule_structure(B, name):
         assert sum(f" {op} " in l for l in bwd) == L
     # LN1 is a separate operator only for the first layer (later ones ride on the layer below's R2)
     assert sum(" LN1 " in l for l in fwd) == n
+
+
+# ------------------------------------------------------------------ LLaMA-style layer: schedule and configuration checks
+LLAMA_FWD_TRACE = """\
+compute ROPE.table sb*
+compute RMS1 sb0|compute QKV sb0|compute ROPE sb0|compute ATTN sb0|compute PROJ sb0|comm R1+DR1+RMS2 sb0
+compute RMS1 sb1|compute QKV sb1|compute ROPE sb1|compute ATTN sb1|compute PROJ sb1|comm R1+DR1+RMS2 sb1
+compute FC1+SWIGLU sb0|compute FC2 sb0|comm R2+DR2 sb0
+compute FC1+SWIGLU sb1|compute FC2 sb1|comm R2+DR2 sb1
+compute join sb0|compute join sb1"""
+# backward with recomputation: the rotation is redone behind QKV.r, and dQ / dK are rotated back behind the attention
+# backward, before the input-gradient GEMM of QKV; no bias sums
+LLAMA_BWD_TRACE_RECOMPUTE = """\
+comm DR2.b sb1|comm DR2.b sb0
+compute RMS2.r sb1|compute FC1+SWIGLU.r sb1|compute FC2.dgrad+dSWIGLU sb1|compute FC1.dgrad sb1|comm R3+RMS2.b+DR1.b sb1
+compute RMS2.r sb0|compute FC1+SWIGLU.r sb0|compute FC2.dgrad+dSWIGLU sb0|compute FC1.dgrad sb0|comm R3+RMS2.b+DR1.b sb0
+compute FC2.wgrad sb*|compute FC1.wgrad sb*
+compute RMS1.r sb1|compute QKV.r sb1|compute ROPE.r sb1|compute ATTN.r sb1|compute PROJ.dgrad sb1|compute ATTN.b sb1|compute ROPE.b sb1|compute QKV.dgrad sb1|comm R4+RMS1.b sb1
+compute RMS1.r sb0|compute QKV.r sb0|compute ROPE.r sb0|compute ATTN.r sb0|compute PROJ.dgrad sb0|compute ATTN.b sb0|compute ROPE.b sb0|compute QKV.dgrad sb0|comm R4+RMS1.b sb0
+compute PROJ.wgrad sb*|compute QKV.wgrad sb*
+compute join sb1|compute join sb0"""
+
+
+def test_llama_schedule_matches_hand_trace(B):
+    strip = lambda s: [re.sub(r" L0", "", l) for l in s.strip().splitlines()]
+    H = B.Handle(B.make_cfg(si.LLAMA_CONFIGS["L1"], flags=B.FLAG_RECOMPUTE))
+    assert strip(H.schedule(False)) == _norm(LLAMA_FWD_TRACE)
+    assert strip(H.schedule(True)) == _norm(LLAMA_BWD_TRACE_RECOMPUTE)
+    stored = strip(B.Handle(B.make_cfg(si.LLAMA_CONFIGS["L1"])).schedule(True))
+    assert stored == [l for l in _norm(LLAMA_BWD_TRACE_RECOMPUTE) if ".r " not in l]
+    # the FC1 output kept for backward is twice as wide (gate and up), the rotary table exists
+    off, nb = H.tensor_span("pre", 0)
+    c = si.LLAMA_CONFIGS["L1"]
+    assert nb == c["batch"] * c["seq"] * 2 * (c["ffn_hidden"] // c["tp"]) * 2
+    assert H.tensor_span("rope", 0)[1] == c["seq"] * (c["hidden"] // c["n_heads"] // 2) * 8
+
+
+def test_create_rejects_bad_llama_configurations(B):
+    def rc(**over):
+        cfg = dict(si.LLAMA_CONFIGS["L1"])
+        cfg.update(over)
+        c, h = B.make_cfg(cfg), C.c_void_p()
+        r = B.lib.oases_create(C.byref(c), C.byref(h))
+        if r == 0:
+            B.lib.oases_destroy(h)
+        return r
+    assert rc() == 0
+    assert rc(ffn_hidden=720) == B.EINVAL          # 360 columns per rank: not a multiple of 32
+    assert rc(ffn_hidden=705) == B.EINVAL          # not divisible by the degree
+    assert rc(rope_theta=0.5) == B.EINVAL
+    c, h = B.make_cfg(si.CONFIGS["C1"]), C.c_void_p()
+    c.ffn_hidden = 1024
+    assert B.lib.oases_create(C.byref(c), C.byref(h)) == B.EINVAL   # the GPT layer's FFN width is 4h
+    c = B.make_cfg(si.LLAMA_CONFIGS["L1"])
+    c.arch = 7
+    assert B.lib.oases_create(C.byref(c), C.byref(h)) == B.EINVAL

@@ -158,24 +158,3 @@ def test_recompute_mode_and_one_stream_are_bit_identical(name, n_sub):
         for l in range(cfg["n_layers"]):
             for k in PARAMS:
                 assert torch.equal(run["grads"][l][k], base["grads"][l][k]), (flags, l, k)
-
-
-def test_create_rejects_bad_llama_configurations():
-    import ctypes as C
-    from paper_2305_16121_amd import binding as B
-    def rc(**over):
-        cfg = dict(si.LLAMA_CONFIGS["L1"]); cfg.update(over)
-        c, h = B.make_cfg(cfg), C.c_void_p()
-        r = B.lib.oases_create(C.byref(c), C.byref(h))
-        if r == 0:
-            B.lib.oases_destroy(h)
-        return r
-    assert rc() == 0
-    assert rc(ffn_hidden=720) == B.EINVAL          # 360 columns per rank: not a multiple of 32
-    assert rc(ffn_hidden=705) == B.EINVAL          # not divisible by the degree
-    assert rc(rope_theta=0.5) == B.EINVAL
-    c = B.make_cfg(si.CONFIGS["C1"]); c.ffn_hidden = 1024
-    h = C.c_void_p()
-    assert B.lib.oases_create(C.byref(c), C.byref(h)) == B.EINVAL   # the GPT layer's FFN width is 4h
-    c = B.make_cfg(si.LLAMA_CONFIGS["L1"]); c.arch = 7
-    assert B.lib.oases_create(C.byref(c), C.byref(h)) == B.EINVAL
