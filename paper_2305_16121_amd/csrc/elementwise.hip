@@ -213,17 +213,24 @@ __global__ __launch_bounds__(NT) void layernorm_bwd_kernel(const float* __restri
     const size_t base = (size_t)row * h;
     const float m = RMS ? 0.f : mu[row], rs = rstd[row];
     f32x4 gg[NC], xh[NC], dr[NC];
+    uint32_t kb[NC];  // keep bits of the row's dropout mask: integer work done while the row's loads are in flight
     float s1 = 0.f, s2 = 0.f;
 #pragma unroll
     for (int i = 0; i < NC; i++) {
       const int c = tid + i * NT;
       gg[i] = xh[i] = dr[i] = f32x4{0.f, 0.f, 0.f, 0.f};
+      kb[i] = 0u;
       if (c < nc) {
         f32x4 g = *reinterpret_cast<const f32x4*>(part + base + 4 * c);
         if (peer) g += *reinterpret_cast<const f32x4*>(peer + base + 4 * c);
         f32x4 xv = *reinterpret_cast<const f32x4*>(x + base + 4 * c);
         dr[i] = *reinterpret_cast<const f32x4*>(dres + base + 4 * c);   // needed only after the reduction: fetched now
         f32x4 gm = *reinterpret_cast<const f32x4*>(gamma + 4 * c);
+        if (dz) {
+          bool k[4];
+          dropout_keep4(d, ((uint64_t)(row0 + row) * h >> 2) + c, k);
+          kb[i] = (uint32_t)k[0] | ((uint32_t)k[1] << 1) | ((uint32_t)k[2] << 2) | ((uint32_t)k[3] << 3);
+        }
 #pragma unroll
         for (int j = 0; j < 4; j++) {
           xh[i][j] = (xv[j] - m) * rs;
@@ -246,10 +253,8 @@ __global__ __launch_bounds__(NT) void layernorm_bwd_kernel(const float* __restri
         for (int j = 0; j < 4; j++) o[j] += rs * (gg[i][j] - m1 - xh[i][j] * m2);
         *reinterpret_cast<f32x4*>(dxo + base + 4 * c) = o;
         if (dz) {
-          bool k[4];
-          dropout_keep4(d, ((uint64_t)(row0 + row) * h >> 2) + c, k);
 #pragma unroll
-          for (int j = 0; j < 4; j++) o[j] = k[j] ? o[j] * d.scale : 0.f;
+          for (int j = 0; j < 4; j++) o[j] = ((kb[i] >> j) & 1u) ? o[j] * d.scale : 0.f;
           store_bf16x4(dz + base + 4 * c, o[0], o[1], o[2], o[3]);
           az[i] += o;
         }

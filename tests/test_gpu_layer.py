@@ -81,6 +81,10 @@ def test_rank_shard_matches_oracle(name, ranks, dtype):
     dict(hidden=1024, n_heads=8, seq=200, batch=3, tp=2, n_sub=3, n_layers=3, causal=1, dropout_p=0.2, w_sigma=0.02),   # d=128, ragged seq
     dict(hidden=768, n_heads=12, seq=72, batch=4, tp=3, n_sub=2, n_layers=1, causal=0, dropout_p=0.0, w_sigma=0.02),    # d=64, t=3, non-causal
     dict(hidden=512, n_heads=4, seq=264, batch=1, tp=1, n_sub=3, n_layers=2, causal=1, dropout_p=0.1, w_sigma=0.02),    # t=1, chunks of one sequence
+    # the other hidden sizes of the paper's model table (3072, 6144, 12288), short sequences
+    dict(hidden=3072, n_heads=24, seq=128, batch=2, tp=4, n_sub=2, n_layers=1, causal=1, dropout_p=0.1, w_sigma=0.02),
+    dict(hidden=6144, n_heads=48, seq=64, batch=2, tp=8, n_sub=2, n_layers=1, causal=0, dropout_p=0.1, w_sigma=0.01),
+    dict(hidden=12288, n_heads=96, seq=64, batch=2, tp=8, n_sub=2, n_layers=1, causal=1, dropout_p=0.1, w_sigma=0.01),
 ])
 def test_ragged_configurations(cfg):
     layers, x, dy = LH.make_inputs(cfg, seed=3)
