@@ -63,7 +63,7 @@ typedef struct oases_layer_cfg {
   uint64_t seed;                       /* Philox key of the dropout masks */
   float ln_eps;                        /* LayerNorm epsilon; 0 selects 1e-5 */
   int32_t flags;                       /* OASES_FLAG_* */
-  int32_t arch;                        /* OASES_ARCH_GPT (0) or OASES_ARCH_LLAMA */
+  int32_t arch;                        /* OASES_ARCH_GPT (0), OASES_ARCH_LLAMA or OASES_ARCH_BERT */
   int32_t ffn_hidden;                  /* unsharded inner width F of the FFN; 0 selects 4h (OASES_ARCH_GPT requires 0 or 4h) */
   float rope_theta;                    /* base of the rotary embedding (OASES_ARCH_LLAMA); 0 selects 10000 */
 } oases_layer_cfg;
@@ -76,8 +76,11 @@ typedef struct oases_layer_cfg {
  *   (fp % 32 == 0) the members of oases_weights / oases_grads mean: w1 [h, 2fp] bf16 = this rank's gate and up
  *   columns interleaved in blocks of 32 (columns [64k, 64k+32) = gate columns [32k, 32k+32), the next 32 = the same up
  *   columns), w2 [fp, h]; ln1_b, bqkv, bo, ln2_b, b1, b2 are unused and may be NULL.  The same Megatron partition,
- *   the same four reduction points, schedule, flags and peer sums as OASES_ARCH_GPT. */
-enum { OASES_ARCH_GPT = 0, OASES_ARCH_LLAMA = 1 };
+ *   the same four reduction points, schedule, flags and peer sums as OASES_ARCH_GPT.
+ * OASES_ARCH_BERT: post-LayerNorm block (the original Transformer / BERT arrangement; set causal = 0 for BERT):
+ *   s1 = x + dropout(attention(x) Wo + bo), x1 = LN(s1; ln1_g, ln1_b); s2 = x1 + dropout(gelu(x1 W1 + b1) W2 + b2),
+ *   y = LN(s2; ln2_g, ln2_b).  Parameters, shapes, partition and reduction points as OASES_ARCH_GPT. */
+enum { OASES_ARCH_GPT = 0, OASES_ARCH_LLAMA = 1, OASES_ARCH_BERT = 2 };
 
 enum {
   OASES_FLAG_SERIALISE = 1, /* enqueue everything on stream_compute only (same results) */

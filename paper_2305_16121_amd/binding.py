@@ -17,7 +17,7 @@ GEMM_NN, GEMM_NT, GEMM_TN = 0, 1, 2
 EPI_F32, EPI_BF16, EPI_BIAS_BF16, EPI_BIAS_GELU, EPI_DGELU = 0, 1, 2, 3, 4
 EPI_SWIGLU, EPI_DSWIGLU = 6, 7
 FLAG_SERIALISE, FLAG_PROFILE, FLAG_RECOMPUTE = 1, 2, 4
-ARCH_GPT, ARCH_LLAMA = 0, 1
+ARCH_GPT, ARCH_LLAMA, ARCH_BERT = 0, 1, 2
 
 _P = C.c_void_p
 _PARAMS = ("ln1_g", "ln1_b", "wqkv", "bqkv", "wo", "bo", "ln2_g", "ln2_b", "w1", "b1", "w2", "b2")
@@ -108,7 +108,7 @@ def make_cfg(cfg: dict, rank: int = 0, seed: int = 0, flags: int = 0, n_sub: int
     llama = cfg.get("arch") == "llama"
     return LayerCfg(cfg["hidden"], cfg["n_heads"], cfg["seq"], cfg["batch"], cfg["tp"], rank,
                     cfg["n_sub"] if n_sub is None else n_sub, cfg["n_layers"], cfg["causal"], cfg["dropout_p"], seed,
-                    0.0, flags, ARCH_LLAMA if llama else ARCH_GPT, cfg.get("ffn_hidden", 0) if llama else 0,
+                    0.0, flags, ARCH_LLAMA if llama else ARCH_BERT if cfg.get("arch") == "bert" else ARCH_GPT, cfg.get("ffn_hidden", 0) if llama else 0,
                     cfg.get("rope_theta", 0.0) if llama else 0.0)
 
 

@@ -47,7 +47,20 @@ static const char* kOpName[] = {
     "PROJ.wgrad", "ATTN.b", "QKV.dgrad", "R4+LN1.b", "QKV.wgrad", "bqkv.sum",
     "LN2.r", "FC1+GELU.r", "LN1.r", "QKV.r", "ATTN.r", "join", "ROPE.table", "ROPE", "ROPE.r", "ROPE.b"};
 // names of the same operator slots in the LLaMA-style layer (RMSNorm, SwiGLU)
-static const char* op_name(int kind, bool llama) {
+static const char* op_name(int kind, bool llama, bool bert) {
+  if (bert) {  // post-LN: the normalisation sits behind the residual sum, the layer input enters the GEMM as it is
+    switch (kind) {
+      case F_LN1: return "CAST";
+      case R_LN1: return "CAST.r";
+      case R_LN2: return "CAST2.r";
+      case F_R1: return "R1+BDR1+LN1";
+      case F_R2: return "R2+BDR2+LN2";
+      case B_BDR2: return "LN2.b+BDR2.b";
+      case B_R3: return "R3+LN1.b+BDR1.b";
+      case B_R4: return "R4+LN2.b+BDR2.b";
+      default: break;
+    }
+  }
   if (llama) {
     switch (kind) {
       case F_FC1: return "FC1+SWIGLU";
@@ -89,6 +102,7 @@ struct oases_handle {
   int h, nh, d, s, b, t, r, n, L, M, Ms, hp, fp, heads_l;
   int fw;        // columns of the FC1 output that is stored for backward: fp (GeLU), 2*fp (SwiGLU: gate and up)
   bool llama;    // OASES_ARCH_LLAMA: RMSNorm, rotary embedding, SwiGLU, no biases
+  bool bert;     // OASES_ARCH_BERT: post-LayerNorm
   float eps, theta;
   std::vector<Op> fwd, bwd;
   int n_events;
@@ -112,7 +126,9 @@ static void plan_workspace(oases_handle* H) {
       {"v2", M * h * 2},     {"pre", M * fw * 2},   {"f", M * fp * 2},     {"z2", M * h * 4},       {"y", M * h * 4},
       {"dz2", M * h * 2},    {"dg", M * fw * 2},    {"dv2", M * h * 4},    {"dx1", M * h * 4},      {"dz1", M * h * 2},
       {"da", M * hp * 2},    {"delta", st * 4},     {"dqkv", M * 3 * hp * 2}, {"du", M * h * 4},    {"dy", M * h * 4},
-      {"rope", rope}};
+      {"rope", rope},
+      // post-LN: the sums in front of the two LayerNorms (their backward needs them) and the gradient of the second one
+      {"s1", H->bert ? M * h * 4 : 0}, {"s2", H->bert ? M * h * 4 : 0}, {"ds2", H->bert ? M * h * 4 : 0}};
   // Recompute mode (the paper's fine-grained recomputation, Sec. IV-B): only the input of each computation
   // sequence is kept per layer -- x (= y of the layer below) for [LN1,QKV,ATTN,PROJ] and x1 for [LN2,FC1,FC2] -- the
   // activations in between are rebuilt inside backward and live in one region shared by all layers.
@@ -308,6 +324,56 @@ static int run_op(const Run& R, const Op& op) {
   uint16_t* f = wsp<uint16_t>(R, "f", l);
   const bool rms = H->llama;   // RMSNorm, no biases: the bias / beta / mean arguments below are NULL and unused
   const int fw = H->fw;
+  if (H->bert) {
+    // Post-LN layer: s1 = x + drop(Z1 + bo), x1 = LN1(s1); s2 = x1 + drop(Z2 + b2), y = LN2(s2).  The GEMMs read bf16
+    // copies of x and x1; the reduction-point kernels write the sum (for the LayerNorm backward), the normalised row in
+    // fp32 (residual stream) and in bf16 (next GEMM operand).  Backward: the whole gradient of a LayerNorm's output
+    // (residual branch included) passes through it.
+    switch (op.kind) {
+      case F_LN1:
+      case R_LN1:
+        return launch_cast_bf16(xin + r0 * h, u + r0 * h, (int64_t)Ms * h, s);
+      case R_LN2:
+        return launch_cast_bf16(wsp<float>(R, "x1", l) + r0 * h, v2 + r0 * h, (int64_t)Ms * h, s);
+      case F_R1:
+        return launch_bdr_ln(wsp<float>(R, "z1", l) + r0 * h, peer(P ? P->fwd_attn : nullptr), (const float*)W.bo, xin + r0 * h,
+                             wsp<float>(R, "s1", l) + r0 * h, (const float*)W.ln1_g, (const float*)W.ln1_b, v2 + r0 * h,
+                             wsp<float>(R, "mu1", l) + r0, wsp<float>(R, "rstd1", l) + r0, Ms, h, H->eps,
+                             make_drop_cfg(seed, l, 0, p), (int64_t)r0, s, false, wsp<float>(R, "x1", l) + r0 * h);
+      case F_R2: {
+        const bool more = l + 1 < L;  // the bf16 copy of y is the next layer's GEMM operand
+        return launch_bdr_ln(wsp<float>(R, "z2", l) + r0 * h, peer(P ? P->fwd_ffn : nullptr), (const float*)W.b2,
+                             wsp<float>(R, "x1", l) + r0 * h, wsp<float>(R, "s2", l) + r0 * h, (const float*)W.ln2_g,
+                             (const float*)W.ln2_b, more ? wsp<uint16_t>(R, "u", l + 1) + r0 * h : nullptr,
+                             wsp<float>(R, "mu2", l) + r0, wsp<float>(R, "rstd2", l) + r0, Ms, h, H->eps,
+                             make_drop_cfg(seed, l, 1, p), (int64_t)r0, s, false, yout + r0 * h);
+      }
+      case B_BDR2:  // top of the stack: dy through LN2, then the dropout backward of the FFN branch
+        return launch_layernorm_bwd(dyin + r0 * h, nullptr, nullptr, wsp<float>(R, "s2", l) + r0 * h, wsp<float>(R, "mu2", l) + r0,
+                                    wsp<float>(R, "rstd2", l) + r0, (const float*)W.ln2_g, wsp<float>(R, "ds2", l) + r0 * h,
+                                    (float*)R.g[l].ln2_g, (float*)R.g[l].ln2_b, wsp<uint16_t>(R, "dz2", l) + r0 * h, (float*)R.g[l].b2, Ms,
+                                    h, make_drop_cfg(seed, l, 1, p), (int64_t)r0, scr_comm, s, false, true);
+      case B_R3:  // gradient of x1 = FFN-input gradient (reduced) + residual branch ds2, through LN1
+        return launch_layernorm_bwd(wsp<float>(R, "dv2", l) + r0 * h, peer(P ? P->bwd_ffn : nullptr), wsp<float>(R, "ds2", l) + r0 * h,
+                                    wsp<float>(R, "s1", l) + r0 * h, wsp<float>(R, "mu1", l) + r0, wsp<float>(R, "rstd1", l) + r0,
+                                    (const float*)W.ln1_g, wsp<float>(R, "dx1", l) + r0 * h, (float*)R.g[l].ln1_g, (float*)R.g[l].ln1_b,
+                                    wsp<uint16_t>(R, "dz1", l) + r0 * h, (float*)R.g[l].bo, Ms, h, make_drop_cfg(seed, l, 0, p),
+                                    (int64_t)r0, scr_comm, s, false, true);
+      case B_R4:  // gradient of the layer input = QKV-input gradient (reduced) + residual branch ds1
+        if (l == 0)
+          return launch_add3(wsp<float>(R, "du", l) + r0 * h, wsp<float>(R, "dx1", l) + r0 * h, peer(P ? P->bwd_attn : nullptr),
+                             dxout + r0 * h, (int64_t)Ms * h, s);
+        // ... which is the output gradient of the layer below: straight through its LN2 and FFN-branch dropout
+        return launch_layernorm_bwd(wsp<float>(R, "du", l) + r0 * h, peer(P ? P->bwd_attn : nullptr), wsp<float>(R, "dx1", l) + r0 * h,
+                                    wsp<float>(R, "s2", l - 1) + r0 * h, wsp<float>(R, "mu2", l - 1) + r0,
+                                    wsp<float>(R, "rstd2", l - 1) + r0, (const float*)R.w[l - 1].ln2_g,
+                                    wsp<float>(R, "ds2", l - 1) + r0 * h, (float*)R.g[l - 1].ln2_g, (float*)R.g[l - 1].ln2_b,
+                                    wsp<uint16_t>(R, "dz2", l - 1) + r0 * h, (float*)R.g[l - 1].b2, Ms, h,
+                                    make_drop_cfg(seed, l - 1, 1, p), (int64_t)r0, scr_comm, s, false, true);
+      default:
+        break;  // GEMMs, attention, bias sums: as in the GPT layer
+    }
+  }
   switch (op.kind) {
     case F_LN1:
       return launch_layernorm_fwd(xin + r0 * h, (const float*)W.ln1_g, (const float*)W.ln1_b, u + r0 * h,
@@ -489,7 +555,7 @@ int oases_create(const oases_layer_cfg* c, oases_handle** out) {
   const int d = c->hidden / c->n_heads;
   if (d != 64 && d != 128) BAD("head dimension %d unsupported (64 or 128)", d);
   if (c->n_heads % c->tp_degree) BAD("n_heads %d not divisible by tp_degree %d", c->n_heads, c->tp_degree);
-  if (c->arch != OASES_ARCH_GPT && c->arch != OASES_ARCH_LLAMA) BAD("unknown arch %d", c->arch);
+  if (c->arch != OASES_ARCH_GPT && c->arch != OASES_ARCH_LLAMA && c->arch != OASES_ARCH_BERT) BAD("unknown arch %d", c->arch);
   const bool llama = c->arch == OASES_ARCH_LLAMA;
   if (!llama && c->ffn_hidden != 0 && c->ffn_hidden != 4 * c->hidden) BAD("the GPT layer has FFN width 4h (ffn_hidden = 0)");
   const int F = c->ffn_hidden > 0 ? c->ffn_hidden : 4 * c->hidden;
@@ -519,6 +585,7 @@ int oases_create(const oases_layer_cfg* c, oases_handle** out) {
   H->n = c->n_sub; H->L = c->n_layers; H->M = (int)M; H->Ms = (int)Ms;
   H->hp = c->hidden / c->tp_degree; H->fp = F / c->tp_degree; H->heads_l = c->n_heads / c->tp_degree;
   H->llama = llama;
+  H->bert = c->arch == OASES_ARCH_BERT;
   H->fw = llama ? 2 * H->fp : H->fp;
   H->eps = c->ln_eps > 0.f ? c->ln_eps : 1e-5f;
   H->theta = c->rope_theta > 0.f ? c->rope_theta : 10000.f;
@@ -573,7 +640,7 @@ int oases_schedule_dump(const oases_handle* H, int backward, char* buf, size_t n
   std::string s;
   char line[96];
   for (const Op& op : backward ? H->bwd : H->fwd) {
-    const char* name = op_name(op.kind, H->llama);
+    const char* name = op_name(op.kind, H->llama, H->bert);
     if (op.sub < 0) snprintf(line, sizeof line, "%s %s L%d sb*\n", op.stream ? "comm" : "compute", name, op.layer);
     else snprintf(line, sizeof line, "%s %s L%d sb%d\n", op.stream ? "comm" : "compute", name, op.layer, op.sub);
     s += line;

@@ -105,7 +105,10 @@ int launch_layernorm_fwd(const float* x, const float* gamma, const float* beta, 
                          float* rstd, int rows, int h, float eps, hipStream_t s, bool rms = false);
 int launch_bdr_ln(const float* part, const float* peer, const float* bias, const float* xin, float* xo,
                   const float* gamma, const float* beta, void* ln_out, float* mu, float* rstd, int rows,
-                  int h, float eps, const DropCfg& d, int64_t row0, hipStream_t s, bool rms = false);
+                  int h, float eps, const DropCfg& d, int64_t row0, hipStream_t s, bool rms = false, float* ln_f32 = nullptr);
+// post-LN layers: out (bf16) = x (fp32), n elements; out = a + b (+ c) fp32
+int launch_cast_bf16(const float* x, void* out, int64_t n, hipStream_t s);
+int launch_add3(const float* a, const float* b, const float* c, float* out, int64_t n, hipStream_t s);
 // rotary embedding: table [seq][head_dim/2] of (cos, sin) fp32; rotation in place on the Q and K parts of qkv
 int launch_rope_table(float* tab, int seq, int head_dim, float theta, hipStream_t s);
 int launch_rope(void* qkv, int ld, int rows, int64_t row0, int seq, int heads, int head_dim, const float* tab, int inverse,
@@ -115,7 +118,7 @@ int launch_dropout_bwd(const float* dyin, void* dz, float* dbias, int rows, int 
 int launch_layernorm_bwd(const float* part, const float* peer, const float* dres, const float* x,
                          const float* mu, const float* rstd, const float* gamma, float* dxo, float* dgamma,
                          float* dbeta, void* dz, float* dbias, int rows, int h, const DropCfg& d,
-                         int64_t row0, float* scratch, hipStream_t s, bool rms = false);
+                         int64_t row0, float* scratch, hipStream_t s, bool rms = false, bool post = false);
 int launch_colsum_bf16(const void* a, int ld, int rows, int cols, float* out, float* scratch, hipStream_t s);
 // splitk_ws: optional fp32 scratch for split-K partial planes (NULL: never split); forced_variant: 0 = choose, else
 // the instantiation to launch, encoded as gemm_variant() returns it

@@ -49,7 +49,7 @@ __global__ __launch_bounds__(NT) void dropout_mask_kernel(uint8_t* mask, DropCfg
 
 // ------------------------------------------------------------------------------------------------
 // xo = xin + keep * (part + peer + bias) * scale   (if part != nullptr; else the row is xin itself; bias may be NULL)
-// ln_out = gamma * (xo - mu) * rstd + beta          (if ln_out != nullptr)
+// ln_out = gamma * (xo - mu) * rstd + beta          (if ln_out != nullptr; bf16), the same in fp32 to ln_f32 if given
 // RMS: ln_out = gamma * xo * rstd with rstd = 1/sqrt(mean(xo^2) + eps) (RMSNorm: no mean, no beta, mu_out unused)
 template <int NC, bool RMS>
 __global__ __launch_bounds__(NT) void bdr_ln_kernel(const float* __restrict__ part, const float* __restrict__ peer,
@@ -57,7 +57,7 @@ __global__ __launch_bounds__(NT) void bdr_ln_kernel(const float* __restrict__ pa
                                                     float* __restrict__ xo, const float* __restrict__ gamma,
                                                     const float* __restrict__ beta, uint16_t* __restrict__ ln_out,
                                                     float* __restrict__ mu_out, float* __restrict__ rstd_out, int h,
-                                                    float eps, DropCfg d, int64_t row0) {
+                                                    float eps, DropCfg d, int64_t row0, float* __restrict__ ln_f32) {
   __shared__ float red[8];
   const int row = blockIdx.x, tid = threadIdx.x;
   const int nc = h >> 2;
@@ -97,7 +97,7 @@ __global__ __launch_bounds__(NT) void bdr_ln_kernel(const float* __restrict__ pa
       for (int j = 0; j < 4; j++) { float t = x[j] - shift; s += t; q += t * t; }
     }
   }
-  if (!ln_out) return;
+  if (!ln_out && !ln_f32) return;
   block_sum2(s, q, red);
   const float ms = RMS ? 0.f : s / h;
   const float mu = shift + ms;
@@ -116,7 +116,8 @@ __global__ __launch_bounds__(NT) void bdr_ln_kernel(const float* __restrict__ pa
       f32x4 o;
 #pragma unroll
       for (int j = 0; j < 4; j++) o[j] = gm[j] * ((v[i][j] - mu) * rstd) + bt[j];
-      store_bf16x4(ln_out + base + 4 * c, o[0], o[1], o[2], o[3]);
+      if (ln_out) store_bf16x4(ln_out + base + 4 * c, o[0], o[1], o[2], o[3]);
+      if (ln_f32) *reinterpret_cast<f32x4*>(ln_f32 + base + 4 * c) = o;   // post-LN layers: the normalised row is the residual stream
     }
   }
 }
@@ -196,7 +197,9 @@ __global__ __launch_bounds__(NT) void colsum_finalize_kernel(const float* __rest
 // g = part + peer;  dxo = dres + rstd * (g*gamma - mean(g*gamma) - xhat * mean(g*gamma*xhat))
 // partials: scratch[0] dgamma = sum g*xhat, scratch[1] dbeta = sum g, scratch[2] dbias = sum dz
 // RMS: xhat = x * rstd, dxo = dres + rstd * (g*gamma - xhat * mean(g*gamma*xhat)), no dbeta
-template <int NC, int NT, bool RMS>
+// POST (post-LN layers): the residual gradient passes through the LayerNorm too: g = part + peer + dres (dres may be
+// NULL), dxo = rstd * (g*gamma - mean(g*gamma) - xhat * mean(g*gamma*xhat))
+template <int NC, int NT, bool RMS, bool POST>
 __global__ __launch_bounds__(NT) void layernorm_bwd_kernel(const float* __restrict__ part, const float* __restrict__ peer,
                                                            const float* __restrict__ dres, const float* __restrict__ x,
                                                            const float* __restrict__ mu, const float* __restrict__ rstd,
@@ -224,7 +227,8 @@ __global__ __launch_bounds__(NT) void layernorm_bwd_kernel(const float* __restri
         f32x4 g = *reinterpret_cast<const f32x4*>(part + base + 4 * c);
         if (peer) g += *reinterpret_cast<const f32x4*>(peer + base + 4 * c);
         f32x4 xv = *reinterpret_cast<const f32x4*>(x + base + 4 * c);
-        dr[i] = *reinterpret_cast<const f32x4*>(dres + base + 4 * c);   // needed only after the reduction: fetched now
+        if (!POST || dres) dr[i] = *reinterpret_cast<const f32x4*>(dres + base + 4 * c);   // pre-LN: needed only after the reduction, fetched now
+        if (POST) g += dr[i];
         f32x4 gm = *reinterpret_cast<const f32x4*>(gamma + 4 * c);
         if (dz) {
           bool k[4];
@@ -248,7 +252,7 @@ __global__ __launch_bounds__(NT) void layernorm_bwd_kernel(const float* __restri
     for (int i = 0; i < NC; i++) {
       const int c = tid + i * NT;
       if (c < nc) {
-        f32x4 o = dr[i];
+        f32x4 o = POST ? f32x4{0.f, 0.f, 0.f, 0.f} : dr[i];
 #pragma unroll
         for (int j = 0; j < 4; j++) o[j] += rs * (gg[i][j] - m1 - xh[i][j] * m2);
         *reinterpret_cast<f32x4*>(dxo + base + 4 * c) = o;
@@ -331,6 +335,24 @@ __global__ __launch_bounds__(NT) void rope_kernel(uint16_t* __restrict__ qkv, in
   *reinterpret_cast<u32x4*>(p + half) = u32x4{pack_bf16x2(o2[0], o2[1]), pack_bf16x2(o2[2], o2[3]), pack_bf16x2(o2[4], o2[5]), pack_bf16x2(o2[6], o2[7])};
 }
 
+// ------------------------------------------------------------------------------------------------
+// out (bf16) = x (fp32); n4 groups of 4 elements
+__global__ __launch_bounds__(NT) void cast_bf16_kernel(const float* __restrict__ x, uint16_t* __restrict__ out, int64_t n4) {
+  const int64_t i = (int64_t)blockIdx.x * NT + threadIdx.x;
+  if (i >= n4) return;
+  const f32x4 v = *reinterpret_cast<const f32x4*>(x + 4 * i);
+  store_bf16x4(out + 4 * i, v[0], v[1], v[2], v[3]);
+}
+// out = a + b (+ c), fp32
+__global__ __launch_bounds__(NT) void add3_kernel(const float* __restrict__ a, const float* __restrict__ b, const float* __restrict__ c,
+                                                  float* __restrict__ out, int64_t n4) {
+  const int64_t i = (int64_t)blockIdx.x * NT + threadIdx.x;
+  if (i >= n4) return;
+  f32x4 v = *reinterpret_cast<const f32x4*>(a + 4 * i) + *reinterpret_cast<const f32x4*>(b + 4 * i);
+  if (c) v += *reinterpret_cast<const f32x4*>(c + 4 * i);
+  *reinterpret_cast<f32x4*>(out + 4 * i) = v;
+}
+
 // row groups of a two-stage column reduction: about eight rows per group (few partial rows to add up), but at
 // least one group per CU when the rows allow it, at most kColPartials groups
 int col_groups(int rows) {
@@ -407,18 +429,18 @@ int launch_dropout_mask(uint8_t* mask, const DropCfg& d, int64_t row0, int rows,
 
 int launch_bdr_ln(const float* part, const float* peer, const float* bias, const float* xin, float* xo,
                   const float* gamma, const float* beta, void* ln_out, float* mu, float* rstd, int rows, int h,
-                  float eps, const DropCfg& d, int64_t row0, hipStream_t s, bool rms) {
+                  float eps, const DropCfg& d, int64_t row0, hipStream_t s, bool rms, float* ln_f32) {
   if (!check_h(rows, h, "bias_dropout_residual_ln")) return OASES_EINVAL;
-  if (!xin || (part && !xo) || (part && !rms && !bias) || (ln_out && (!gamma || !rstd || (!rms && (!beta || !mu))))) {
+  if (!xin || (part && !xo) || (part && !rms && !bias) || ((ln_out || ln_f32) && (!gamma || !rstd || (!rms && (!beta || !mu))))) {
     set_error("bias_dropout_residual_ln: NULL argument");
     return OASES_ENULL;
   }
   if (rms) {
     OASES_NC_DISPATCH(pick_nc(h), hipLaunchKernelGGL((bdr_ln_kernel<NC, true>), dim3(rows), dim3(NT), 0, s, part, peer, bias, xin, xo,
-                                                     gamma, beta, (uint16_t*)ln_out, mu, rstd, h, eps, d, row0));
+                                                     gamma, beta, (uint16_t*)ln_out, mu, rstd, h, eps, d, row0, ln_f32));
   } else {
     OASES_NC_DISPATCH(pick_nc(h), hipLaunchKernelGGL((bdr_ln_kernel<NC, false>), dim3(rows), dim3(NT), 0, s, part, peer, bias, xin, xo,
-                                                     gamma, beta, (uint16_t*)ln_out, mu, rstd, h, eps, d, row0));
+                                                     gamma, beta, (uint16_t*)ln_out, mu, rstd, h, eps, d, row0, ln_f32));
   }
   OASES_LAUNCH_CHECK("bdr_ln_kernel");
   return 0;
@@ -428,7 +450,7 @@ int launch_layernorm_fwd(const float* x, const float* gamma, const float* beta, 
                          int rows, int h, float eps, hipStream_t s, bool rms) {
   DropCfg d = make_drop_cfg(0, 0, 0, 0.f);
   if (!out) { set_error("layernorm_fwd: NULL output"); return OASES_ENULL; }
-  return launch_bdr_ln(nullptr, nullptr, nullptr, x, nullptr, gamma, beta, out, mu, rstd, rows, h, eps, d, 0, s, rms);
+  return launch_bdr_ln(nullptr, nullptr, nullptr, x, nullptr, gamma, beta, out, mu, rstd, rows, h, eps, d, 0, s, rms, nullptr);
 }
 
 static int finalize(float* scratch, float* o0, float* o1, float* o2, int nk, int groups, int cols, hipStream_t s) {
@@ -452,23 +474,44 @@ int launch_dropout_bwd(const float* dyin, void* dz, float* dbias, int rows, int 
 
 int launch_layernorm_bwd(const float* part, const float* peer, const float* dres, const float* x, const float* mu,
                          const float* rstd, const float* gamma, float* dxo, float* dgamma, float* dbeta, void* dz,
-                         float* dbias, int rows, int h, const DropCfg& d, int64_t row0, float* scratch, hipStream_t s, bool rms) {
+                         float* dbias, int rows, int h, const DropCfg& d, int64_t row0, float* scratch, hipStream_t s, bool rms,
+                         bool post) {
   if (!check_h(rows, h, "layernorm_bwd")) return OASES_EINVAL;
-  if (!part || !dres || !x || !rstd || !gamma || !dxo || !dgamma || !scratch || (!rms && (!mu || !dbeta || (dz && !dbias)))) {
+  if (rms && post) { set_error("layernorm_bwd: no post-norm RMS variant"); return OASES_EINVAL; }
+  if (!part || (!dres && !post) || !x || !rstd || !gamma || !dxo || !dgamma || !scratch || (!rms && (!mu || !dbeta || (dz && !dbias)))) {
     set_error("layernorm_bwd: NULL argument");
     return OASES_ENULL;
   }
   const int groups = col_groups(rows);
   const int want_dbias = dz && dbias;
   if (rms) {
-    OASES_BWD_DISPATCH(h, hipLaunchKernelGGL((layernorm_bwd_kernel<NC, NTHR, true>), dim3(groups), dim3(NTHR), 0, s, part, peer, dres, x,
+    OASES_BWD_DISPATCH(h, hipLaunchKernelGGL((layernorm_bwd_kernel<NC, NTHR, true, false>), dim3(groups), dim3(NTHR), 0, s, part, peer, dres, x,
+                                             mu, rstd, gamma, dxo, (uint16_t*)dz, scratch, rows, h, d, row0, want_dbias));
+  } else if (post) {
+    OASES_BWD_DISPATCH(h, hipLaunchKernelGGL((layernorm_bwd_kernel<NC, NTHR, false, true>), dim3(groups), dim3(NTHR), 0, s, part, peer, dres, x,
                                              mu, rstd, gamma, dxo, (uint16_t*)dz, scratch, rows, h, d, row0, want_dbias));
   } else {
-    OASES_BWD_DISPATCH(h, hipLaunchKernelGGL((layernorm_bwd_kernel<NC, NTHR, false>), dim3(groups), dim3(NTHR), 0, s, part, peer, dres, x,
+    OASES_BWD_DISPATCH(h, hipLaunchKernelGGL((layernorm_bwd_kernel<NC, NTHR, false, false>), dim3(groups), dim3(NTHR), 0, s, part, peer, dres, x,
                                              mu, rstd, gamma, dxo, (uint16_t*)dz, scratch, rows, h, d, row0, want_dbias));
   }
   OASES_LAUNCH_CHECK("layernorm_bwd_kernel");
   return finalize(scratch, dgamma, rms ? nullptr : dbeta, want_dbias ? dbias : nullptr, want_dbias ? 3 : 2, groups, h, s);
+}
+
+int launch_cast_bf16(const float* x, void* out, int64_t n, hipStream_t s) {
+  if (!x || !out) { set_error("cast_bf16: NULL argument"); return OASES_ENULL; }
+  if (n <= 0 || n % 4 || !aligned16(x) || (reinterpret_cast<uintptr_t>(out) & 7u)) { set_error("cast_bf16: n must be a positive multiple of 4, pointers aligned"); return OASES_EINVAL; }
+  hipLaunchKernelGGL(cast_bf16_kernel, dim3((unsigned)((n / 4 + NT - 1) / NT)), dim3(NT), 0, s, x, (uint16_t*)out, n / 4);
+  OASES_LAUNCH_CHECK("cast_bf16_kernel");
+  return 0;
+}
+
+int launch_add3(const float* a, const float* b, const float* c, float* out, int64_t n, hipStream_t s) {
+  if (!a || !b || !out) { set_error("add3: NULL argument"); return OASES_ENULL; }
+  if (n <= 0 || n % 4 || !aligned16(a) || !aligned16(b) || !aligned16(c) || !aligned16(out)) { set_error("add3: n must be a positive multiple of 4, pointers 16-byte aligned"); return OASES_EINVAL; }
+  hipLaunchKernelGGL(add3_kernel, dim3((unsigned)((n / 4 + NT - 1) / NT)), dim3(NT), 0, s, a, b, c, out, n / 4);
+  OASES_LAUNCH_CHECK("add3_kernel");
+  return 0;
 }
 
 int launch_rope_table(float* tab, int seq, int head_dim, float theta, hipStream_t s) {

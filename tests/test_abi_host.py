@@ -225,3 +225,19 @@ def test_create_rejects_bad_llama_configurations(B):
     c = B.make_cfg(si.LLAMA_CONFIGS["L1"])
     c.arch = 7
     assert B.lib.oases_create(C.byref(c), C.byref(h)) == B.EINVAL
+
+
+def test_bert_schedule_and_workspace(B):
+    """Post-LN layer: the layer input enters QKV as a cast (no LayerNorm in front), the top of the backward pass is the
+    backward of LN2 fused with the FFN branch's dropout, the sums in front of both LayerNorms are kept."""
+    cfg = dict(si.CONFIGS["C2"], arch="bert", causal=0)
+    H = B.Handle(B.make_cfg(cfg))
+    fwd, bwd = H.schedule(False).splitlines(), H.schedule(True).splitlines()
+    assert fwd[0] == "compute CAST L0 sb0" and "comm R1+BDR1+LN1 L0 sb0" in fwd and "comm R2+BDR2+LN2 L1 sb1" in fwd
+    assert sum(1 for l in fwd if " CAST " in l) == cfg["n_sub"]            # only layer 0 casts: deeper layers get the bf16 copy from R2
+    assert bwd[0] == "comm LN2.b+BDR2.b L1 sb1" and "comm R4+LN2.b+BDR2.b L0 sb0" in bwd
+    M, h = cfg["batch"] * cfg["seq"], cfg["hidden"]
+    for name in ("s1", "s2", "ds2", "x1"):
+        assert H.tensor_span(name, 1)[1] == M * h * 4
+    G = B.Handle(B.make_cfg(si.CONFIGS["C2"]))
+    assert G.tensor_span("s1", 0)[1] == 0 and H.workspace_bytes > G.workspace_bytes
