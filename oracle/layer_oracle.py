@@ -21,6 +21,10 @@ forward).  There is no blocking, fusion, sub-batching or reordering here: every 
 is one plain tensor expression; `torch.matmul` on CPU is the only library primitive.
 Backward is the chain rule written out by hand (no autograd).
 
+Optional dropout on the attention probabilities (`attn_dropout_p`, off in the benchmark
+configurations): a byte-granular Philox mask on (sequence, global head, query, key), see
+attention_dropout_factor.
+
 Readings where the paper is silent (it names no per-operator formula): pre-LN layer,
 LayerNorm with biased variance and eps = 1e-5, tanh-form GeLU, biases on all four
 linear maps with the row-parallel biases added once after the reduction, two hidden
@@ -147,6 +151,34 @@ class _Rounder:
 BF16_OPERAND_SITES = ("u", "qkv", "P", "A", "v2", "pre", "f", "dZ2", "dG", "dZ1", "dA", "dS", "dqkv")
 
 
+def attention_dropout_threshold(p: float) -> int:
+    """Drop threshold on one byte of a Philox word: keep iff byte >= T.  The rate is thereby quantised to T/256."""
+    return int(round(p * 256))
+
+
+def attention_dropout_factor(seed: int, layer: int, batch: int, seq: int, n_heads_total: int, head0: int, nh_local: int,
+                             p: float):
+    """Dropout on the attention probabilities: the factor keep / (1 - T/256), as a [batch, nh_local, seq, seq] fp64
+    tensor (query index third, key index last), or None if the quantised rate is 0.
+
+    The mask is a function of (sequence b, global head, query position q, key position k): the 4 x 4 block
+    (q div 4, k div 4) draws one Philox4x32-10 output with key (seed lo32, seed hi32) and counter
+    (k div 4, q div 4, b * n_heads_total + head, layer | 2^31); element (q, k) takes byte (k mod 4) of word (q mod 4),
+    low byte first.  Global head index: the mask does not depend on the TP degree, the rank or the sub-batch split."""
+    T = attention_dropout_threshold(p)
+    if T <= 0:
+        return None
+    nb = (seq + 3) // 4
+    b_i, h_i, q4, k4 = np.meshgrid(np.arange(batch, dtype=np.uint64), np.arange(nh_local, dtype=np.uint64) + np.uint64(head0),
+                                   np.arange(nb, dtype=np.uint64), np.arange(nb, dtype=np.uint64), indexing="ij")
+    w = philox4x32_10(k4.ravel(), q4.ravel(), (b_i * np.uint64(n_heads_total) + h_i).ravel(),
+                      np.full(k4.size, (layer & 0x7FFFFFFF) | 0x80000000, dtype=np.uint64), seed & 0xFFFFFFFF, (seed >> 32) & 0xFFFFFFFF)
+    words = np.stack(w, axis=1).reshape(batch, nh_local, nb, nb, 4)                       # [.., q4, k4, q mod 4]
+    bytes_ = np.stack([(words >> np.uint64(8 * j)) & np.uint64(0xFF) for j in range(4)], axis=-1)   # [.., q4, k4, q mod 4, k mod 4]
+    keep = (bytes_ >= np.uint64(T)).transpose(0, 1, 2, 4, 3, 5).reshape(batch, nh_local, 4 * nb, 4 * nb)[:, :, :seq, :seq]
+    return torch.from_numpy(keep.astype(np.float64) * (256.0 / (256.0 - T)))
+
+
 def _heads(t, b, s, nh, d):
     """[b*s, nh*d] -> [b, nh, s, d]"""
     return t.reshape(b, s, nh, d).permute(0, 2, 1, 3)
@@ -156,8 +188,9 @@ def _unheads(t, b, s, nh, d):
     return t.permute(0, 2, 1, 3).reshape(b * s, nh * d)
 
 
-def attention_fwd(q, k, v, batch, seq, nh, d, causal, rb=None):
-    """Softmax attention per (batch item, head) on [batch*seq, nh*d] matrices.  Returns (A, P)."""
+def attention_fwd(q, k, v, batch, seq, nh, d, causal, rb=None, drop=None):
+    """Softmax attention per (batch item, head) on [batch*seq, nh*d] matrices.  Returns (A, P).  `drop`: optional
+    [batch, nh, seq, seq] dropout factor on the probabilities (P itself is returned undropped)."""
     rb = rb or _Rounder(())
     qh, kh, vh = (_heads(t, batch, seq, nh, d) for t in (q, k, v))
     S = (qh @ kh.transpose(2, 3)) / math.sqrt(d)                      # [b, nh, s, s]
@@ -167,16 +200,21 @@ def attention_fwd(q, k, v, batch, seq, nh, d, causal, rb=None):
     S = S - S.max(dim=3, keepdim=True).values
     P = torch.exp(S)
     P = P / P.sum(dim=3, keepdim=True)
-    A = rb("A", _unheads(rb("P", P) @ vh, batch, seq, nh, d))         # [M, nh*d]
+    Pd = P if drop is None else P * drop.to(P.dtype)
+    A = rb("A", _unheads(rb("P", Pd) @ vh, batch, seq, nh, d))        # [M, nh*d]
     return A, P
 
 
-def attention_bwd(dA, q, k, v, P, batch, seq, nh, d, rb=None):
+def attention_bwd(dA, q, k, v, P, batch, seq, nh, d, rb=None, drop=None):
     """Gradients of attention_fwd's inputs for the output gradient dA (softmax' written out)."""
     rb = rb or _Rounder(())
     qh, kh, vh, dAh = (_heads(t, batch, seq, nh, d) for t in (q, k, v, dA))
     dP = dAh @ vh.transpose(2, 3)
-    dvh = rb("P", P).transpose(2, 3) @ dAh
+    Pd = P
+    if drop is not None:               # A = (P * drop) V: the factor multiplies both the path to V and the path to P
+        dP = dP * drop.to(P.dtype)
+        Pd = P * drop.to(P.dtype)
+    dvh = rb("P", Pd).transpose(2, 3) @ dAh
     dS = rb("dS", P * (dP - (dP * P).sum(dim=3, keepdim=True)))
     dqh = (dS @ kh) / math.sqrt(d)
     dkh = (dS.transpose(2, 3) @ qh) / math.sqrt(d)
@@ -185,7 +223,8 @@ def attention_bwd(dA, q, k, v, P, batch, seq, nh, d, rb=None):
 
 def rank_layer_forward(p: dict, x, *, batch: int, seq: int, head_dim: int, causal: bool,
                        dropout_p: float = 0.0, seed: int = 0, layer: int = 0, eps: float = 1e-5,
-                       gelu_tanh: bool = True, peers: dict | None = None, bf16_sites=()):
+                       gelu_tanh: bool = True, peers: dict | None = None, bf16_sites=(), attn_dropout_p: float = 0.0,
+                       head0: int = 0, n_heads_total: int | None = None):
     """Forward of one rank's share.  `p` holds torch tensors wq,wk,wv [h,hp], bq,bk,bv [hp], wo [hp,h],
     bo [h], w1 [h,fp], b1 [fp], w2 [fp,h], b2 [h], ln1_g, ln1_b, ln2_g, ln2_b [h]; x is [batch*seq, h].
     `peers` may hold 'fwd_attn' / 'fwd_ffn': the sum of the other ranks' partial results at the two
@@ -206,7 +245,8 @@ def rank_layer_forward(p: dict, x, *, batch: int, seq: int, head_dim: int, causa
     q = rb("qkv", u @ p["wq"] + p["bq"])
     k = rb("qkv", u @ p["wk"] + p["bk"])
     v = rb("qkv", u @ p["wv"] + p["bv"])
-    A, P = attention_fwd(q, k, v, batch, seq, nh, head_dim, causal, rb)
+    drop = attention_dropout_factor(seed, layer, batch, seq, n_heads_total or nh, head0, nh, attn_dropout_p)
+    A, P = attention_fwd(q, k, v, batch, seq, nh, head_dim, causal, rb, drop)
     Z1r = A @ p["wo"]                                                  # this rank's partial sum
     Z1 = Z1r + peers["fwd_attn"] if peers.get("fwd_attn") is not None else Z1r
     x1 = x + D1 * (Z1 + p["bo"]) * c
@@ -220,7 +260,7 @@ def rank_layer_forward(p: dict, x, *, batch: int, seq: int, head_dim: int, causa
     y = x1 + D2 * (Z2 + p["b2"]) * c
     saved = dict(x=x, u=u, mu1=mu1, rstd1=rstd1, q=q, k=k, v=v, P=P, A=A, Z1r=Z1r, Z1=Z1, x1=x1,
                  mu2=mu2, rstd2=rstd2, v2=v2, pre=pre, f=f, Z2r=Z2r, Z2=Z2, y=y, D1=D1, D2=D2, c=c,
-                 batch=batch, seq=seq, head_dim=head_dim, gelu_tanh=gelu_tanh)
+                 batch=batch, seq=seq, head_dim=head_dim, gelu_tanh=gelu_tanh, drop=drop)
     return y, saved
 
 
@@ -253,7 +293,7 @@ def rank_layer_backward(p: dict, saved: dict, dy, *, peers: dict | None = None, 
     g["bo"] = dZ1.sum(dim=0)
     dA = rb("dA", dZ1 @ p["wo"].t())
     g["wo"] = s["A"].t() @ dZ1
-    dq, dk, dv = attention_bwd(dA, s["q"], s["k"], s["v"], s["P"], b, seq, nh, d, rb)
+    dq, dk, dv = attention_bwd(dA, s["q"], s["k"], s["v"], s["P"], b, seq, nh, d, rb, s.get("drop"))
     for n, dd in (("q", dq), ("k", dk), ("v", dv)):
         g["w" + n] = s["u"].t() @ dd
         g["b" + n] = dd.sum(dim=0)
@@ -274,7 +314,7 @@ def to_torch(params: dict, dtype=torch.float64) -> dict:
 
 
 def model_forward_backward(layers: list, x, dy, cfg: dict, *, seed: int = 0, dtype=torch.float64,
-                           bf16_sites=(), want_backward: bool = True):
+                           bf16_sites=(), want_backward: bool = True, head0: int = 0):
     """Stack of layers (independent weights, layer l+1 reads y_l).  `layers` = list of numpy parameter
     dicts (unsharded, or one rank's slices for the rank-only computation).  Returns a dict with y, dx,
     per-layer grads and per-layer saved / intermediate tensors."""
@@ -286,7 +326,8 @@ def model_forward_backward(layers: list, x, dy, cfg: dict, *, seed: int = 0, dty
     for li, p in enumerate(tp):
         cur, sv = rank_layer_forward(p, cur, batch=cfg["batch"], seq=cfg["seq"], head_dim=d,
                                      causal=bool(cfg["causal"]), dropout_p=cfg["dropout_p"], seed=seed,
-                                     layer=li, bf16_sites=bf16_sites)
+                                     layer=li, bf16_sites=bf16_sites, attn_dropout_p=cfg.get("attn_dropout_p", 0.0),
+                                     head0=head0, n_heads_total=cfg["n_heads"])
         saved.append(sv)
     out = dict(y=cur, saved=saved)
     if want_backward:
