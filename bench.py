@@ -122,6 +122,7 @@ def main():
     ap.add_argument("--serialise", action="store_true", help="single stream")
     ap.add_argument("--recompute", action="store_true",
                     help="fine-grained recomputation: activations are rebuilt inside backward (model flops unchanged, more work)")
+    ap.add_argument("--attn-dropout", type=float, default=None, help="dropout rate on the attention probabilities (off in the workloads)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-profile", action="store_true")
     ap.add_argument("--calib-copy", action="store_true",
@@ -139,6 +140,8 @@ def main():
     cfg = dict({**si.CONFIGS, **si.LLAMA_CONFIGS}[a.config])
     if a.n_sub:
         cfg["n_sub"] = a.n_sub
+    if a.attn_dropout is not None:
+        cfg["attn_dropout_p"] = a.attn_dropout
     M, h = cfg["batch"] * cfg["seq"], cfg["hidden"]
     x, dy = si.make_activations(cfg, 0)
     if cfg.get("arch") == "llama":
@@ -179,7 +182,7 @@ def main():
            "data": "synthetic",
            "config": {"workload": f"{a.config}: {'LLaMA-style' if cfg.get('arch') == 'llama' else 'GPT'} layer h={h} heads={cfg['n_heads']} seq={cfg['seq']} batch={cfg['batch']} "
                                   f"t={cfg['tp']} rank 0 layers={cfg['n_layers']} causal={cfg['causal']} p={cfg['dropout_p']}" + (f" ffn={cfg['ffn_hidden']}" if cfg.get("arch") == "llama" else ""),
-                      "n_sub": cfg["n_sub"], "streams": 1 if a.serialise else 2, "recompute": bool(a.recompute),
+                      "n_sub": cfg["n_sub"], "attn_dropout_p": cfg.get("attn_dropout_p", 0.0), "streams": 1 if a.serialise else 2, "recompute": bool(a.recompute),
                       "workspace_mib": round(H.workspace_bytes / 2 ** 20, 1), "model_gflop_per_step": round(flops / 1e9, 1),
                       "frac_of_bf16_peak": round(tflops / PEAK_BF16_TFLOPS, 4)}}
 

@@ -66,6 +66,7 @@ typedef struct oases_layer_cfg {
   int32_t arch;                        /* OASES_ARCH_GPT (0), OASES_ARCH_LLAMA or OASES_ARCH_BERT */
   int32_t ffn_hidden;                  /* unsharded inner width F of the FFN; 0 selects 4h (OASES_ARCH_GPT requires 0 or 4h) */
   float rope_theta;                    /* base of the rotary embedding (OASES_ARCH_LLAMA); 0 selects 10000 */
+  float attn_dropout_p;                /* dropout on the attention probabilities, [0,1), quantised to round(256 p)/256; any arch */
 } oases_layer_cfg;
 
 /* Layer families (the model rows of the paper's Table III).
@@ -287,6 +288,20 @@ int oases_op_attention_fwd(const void *qkv, void *out, void *lse, int batch, int
 int oases_op_attention_bwd(const void *qkv, const void *out, const void *dout, const void *lse,
                            void *delta, void *dqkv, int batch, int seq, int heads, int head_dim,
                            int causal, int row0, int rows, void *stream);
+
+/* The same two operators with dropout on the attention probabilities (the layer's attn_dropout_p): A = (D o P) V / (1-p'),
+ * p' = T/256, T = round(256 p).  The mask D is a function of (sequence b, global head = head0 + local head, query
+ * position q, key position k), independent of partition and sub-batch split: the 4 x 4 block (q div 4, k div 4) draws
+ * one Philox4x32-10 output with key (seed lo, seed hi) and counter (k div 4, q div 4, b*heads_total + head,
+ * layer | 2^31); element (q, k) is kept iff byte (k mod 4), low byte first, of word (q mod 4) is >= T.  The backward
+ * regenerates the mask.  T == 0 runs the kernels without dropout.  EINVAL if head0 + heads > heads_total. */
+int oases_op_attention_dropout_fwd(const void *qkv, void *out, void *lse, int batch, int seq, int heads,
+                                   int head_dim, int causal, int row0, int rows, uint64_t seed, int layer,
+                                   float p, int head0, int heads_total, void *stream);
+int oases_op_attention_dropout_bwd(const void *qkv, const void *out, const void *dout, const void *lse,
+                                   void *delta, void *dqkv, int batch, int seq, int heads, int head_dim,
+                                   int causal, int row0, int rows, uint64_t seed, int layer, float p,
+                                   int head0, int heads_total, void *stream);
 
 #ifdef __cplusplus
 }

@@ -17,14 +17,15 @@ from __future__ import annotations
 import numpy as np
 import torch
 
-from .layer_oracle import (_Rounder, attention_bwd, attention_fwd, dropout_keep_mask, gelu_fwd, gelu_grad, layer_norm_bwd,
-                           layer_norm_fwd)
+from .layer_oracle import (_Rounder, attention_bwd, attention_dropout_factor, attention_fwd, dropout_keep_mask, gelu_fwd, gelu_grad,
+                           layer_norm_bwd, layer_norm_fwd)
 
 BERT_BF16_OPERAND_SITES = ("u", "qkv", "P", "A", "v2", "pre", "f", "dZ2", "dG", "dZ1", "dA", "dS", "dqkv")
 
 
 def rank_layer_forward(p: dict, x, *, batch: int, seq: int, head_dim: int, causal: bool = False, dropout_p: float = 0.0,
-                       seed: int = 0, layer: int = 0, eps: float = 1e-5, peers: dict | None = None, bf16_sites=()):
+                       seed: int = 0, layer: int = 0, eps: float = 1e-5, peers: dict | None = None, bf16_sites=(), attn_dropout_p: float = 0.0, head0: int = 0,
+                       n_heads_total: int | None = None):
     """`p` as in layer_oracle.rank_layer_forward; ln1_* normalise the attention block's output, ln2_* the FFN block's."""
     rb = _Rounder(bf16_sites)
     peers = peers or {}
@@ -41,7 +42,8 @@ def rank_layer_forward(p: dict, x, *, batch: int, seq: int, head_dim: int, causa
     q = rb("qkv", u @ p["wq"] + p["bq"])
     k = rb("qkv", u @ p["wk"] + p["bk"])
     v = rb("qkv", u @ p["wv"] + p["bv"])
-    A, P = attention_fwd(q, k, v, batch, seq, nh, head_dim, causal, rb)
+    drop = attention_dropout_factor(seed, layer, batch, seq, n_heads_total or nh, head0, nh, attn_dropout_p)
+    A, P = attention_fwd(q, k, v, batch, seq, nh, head_dim, causal, rb, drop)
     Z1r = A @ p["wo"]
     Z1 = Z1r + peers["fwd_attn"] if peers.get("fwd_attn") is not None else Z1r
     s1 = x + D1 * (Z1 + p["bo"]) * c
@@ -55,7 +57,7 @@ def rank_layer_forward(p: dict, x, *, batch: int, seq: int, head_dim: int, causa
     s2 = x1 + D2 * (Z2 + p["b2"]) * c
     y, mu2, rstd2 = layer_norm_fwd(s2, p["ln2_g"], p["ln2_b"], eps)
     saved = dict(x=x, u=u, q=q, k=k, v=v, P=P, A=A, Z1r=Z1r, Z1=Z1, s1=s1, mu1=mu1, rstd1=rstd1, x1=x1, v2=v2, pre=pre, f=f, Z2r=Z2r,
-                 Z2=Z2, s2=s2, mu2=mu2, rstd2=rstd2, y=y, D1=D1, D2=D2, c=c, batch=batch, seq=seq, head_dim=head_dim)
+                 Z2=Z2, s2=s2, mu2=mu2, rstd2=rstd2, y=y, D1=D1, D2=D2, c=c, batch=batch, seq=seq, head_dim=head_dim, drop=drop)
     return y, saved
 
 
@@ -83,7 +85,7 @@ def rank_layer_backward(p: dict, saved: dict, dy, *, peers: dict | None = None, 
     g["bo"] = dZ1.sum(dim=0)
     dA = rb("dA", dZ1 @ p["wo"].t())
     g["wo"] = s["A"].t() @ dZ1
-    dq, dk, dv = attention_bwd(dA, s["q"], s["k"], s["v"], s["P"], b, seq, nh, d, rb)
+    dq, dk, dv = attention_bwd(dA, s["q"], s["k"], s["v"], s["P"], b, seq, nh, d, rb, s.get("drop"))
     for n, dd in (("q", dq), ("k", dk), ("v", dv)):
         g["w" + n] = s["u"].t() @ dd
         g["b" + n] = dd.sum(dim=0)
@@ -95,14 +97,15 @@ def rank_layer_backward(p: dict, saved: dict, dy, *, peers: dict | None = None, 
 
 
 def model_forward_backward(layers: list, x, dy, cfg: dict, *, seed: int = 0, dtype=torch.float64, bf16_sites=(),
-                           want_backward: bool = True):
+                           want_backward: bool = True, head0: int = 0):
     d = cfg["hidden"] // cfg["n_heads"]
     tp = [{k: torch.from_numpy(np.ascontiguousarray(v)).to(dtype) for k, v in l.items()} for l in layers]
     cur = torch.from_numpy(np.ascontiguousarray(x)).to(dtype)
     saved = []
     for li, p in enumerate(tp):
         cur, sv = rank_layer_forward(p, cur, batch=cfg["batch"], seq=cfg["seq"], head_dim=d, causal=bool(cfg["causal"]),
-                                     dropout_p=cfg["dropout_p"], seed=seed, layer=li, bf16_sites=bf16_sites)
+                                     dropout_p=cfg["dropout_p"], seed=seed, layer=li, bf16_sites=bf16_sites,
+                                     attn_dropout_p=cfg.get("attn_dropout_p", 0.0), head0=head0, n_heads_total=cfg["n_heads"])
         saved.append(sv)
     out = dict(y=cur, saved=saved)
     if want_backward:

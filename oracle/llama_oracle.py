@@ -19,7 +19,7 @@ from __future__ import annotations
 
 import torch
 
-from .layer_oracle import _Rounder, attention_bwd, attention_fwd, dropout_keep_mask
+from .layer_oracle import _Rounder, attention_bwd, attention_dropout_factor, attention_fwd, dropout_keep_mask
 
 LLAMA_BF16_OPERAND_SITES = ("u", "qkv", "P", "A", "v2", "gu", "f", "dZ2", "dGU", "dZ1", "dA", "dS", "dqkv")
 
@@ -69,7 +69,7 @@ def silu_grad(z):
 
 def rank_layer_forward(p: dict, x, *, batch: int, seq: int, head_dim: int, causal: bool = True, dropout_p: float = 0.0,
                        seed: int = 0, layer: int = 0, eps: float = 1e-5, theta: float = 10000.0, peers: dict | None = None,
-                       bf16_sites=()):
+                       bf16_sites=(), attn_dropout_p: float = 0.0, head0: int = 0, n_heads_total: int | None = None):
     """`p`: wq, wk, wv [h,hp], wo [hp,h], wg, wu [h,fp], w2 [fp,h], ln1_g, ln2_g [h].  Returns (y, saved)."""
     rb = _Rounder(bf16_sites)
     peers = peers or {}
@@ -87,7 +87,8 @@ def rank_layer_forward(p: dict, x, *, batch: int, seq: int, head_dim: int, causa
     q = rb("qkv", rope_apply(rb("qkv", u @ p["wq"]), batch, seq, head_dim, theta))
     k = rb("qkv", rope_apply(rb("qkv", u @ p["wk"]), batch, seq, head_dim, theta))
     v = rb("qkv", u @ p["wv"])
-    A, P = attention_fwd(q, k, v, batch, seq, nh, head_dim, causal, rb)
+    drop = attention_dropout_factor(seed, layer, batch, seq, n_heads_total or nh, head0, nh, attn_dropout_p)
+    A, P = attention_fwd(q, k, v, batch, seq, nh, head_dim, causal, rb, drop)
     Z1r = A @ p["wo"]
     Z1 = Z1r + peers["fwd_attn"] if peers.get("fwd_attn") is not None else Z1r
     x1 = x + D1 * Z1 * c
@@ -100,7 +101,7 @@ def rank_layer_forward(p: dict, x, *, batch: int, seq: int, head_dim: int, causa
     Z2 = Z2r + peers["fwd_ffn"] if peers.get("fwd_ffn") is not None else Z2r
     y = x1 + D2 * Z2 * c
     saved = dict(x=x, u=u, rstd1=rstd1, q=q, k=k, v=v, P=P, A=A, Z1r=Z1r, Z1=Z1, x1=x1, rstd2=rstd2, v2=v2, gate=gate, up=up,
-                 f=f, Z2r=Z2r, Z2=Z2, y=y, D1=D1, D2=D2, c=c, batch=batch, seq=seq, head_dim=head_dim, theta=theta)
+                 f=f, Z2r=Z2r, Z2=Z2, y=y, D1=D1, D2=D2, c=c, batch=batch, seq=seq, head_dim=head_dim, theta=theta, drop=drop)
     return y, saved
 
 
@@ -128,7 +129,7 @@ def rank_layer_backward(p: dict, saved: dict, dy, *, peers: dict | None = None, 
     dZ1 = rb("dZ1", s["D1"] * dx1 * c)
     dA = rb("dA", dZ1 @ p["wo"].t())
     g["wo"] = s["A"].t() @ dZ1
-    dq, dk, dv = attention_bwd(dA, s["q"], s["k"], s["v"], s["P"], b, seq, nh, d, rb)
+    dq, dk, dv = attention_bwd(dA, s["q"], s["k"], s["v"], s["P"], b, seq, nh, d, rb, s.get("drop"))
     dq = rb("dqkv", rope_apply(dq, b, seq, d, theta, inverse=True))     # back through the rotation
     dk = rb("dqkv", rope_apply(dk, b, seq, d, theta, inverse=True))
     for n, dd in (("q", dq), ("k", dk), ("v", dv)):
@@ -142,7 +143,7 @@ def rank_layer_backward(p: dict, saved: dict, dy, *, peers: dict | None = None, 
 
 
 def model_forward_backward(layers: list, x, dy, cfg: dict, *, seed: int = 0, dtype=torch.float64, bf16_sites=(),
-                           want_backward: bool = True):
+                           want_backward: bool = True, head0: int = 0):
     """Stack of layers, as layer_oracle.model_forward_backward."""
     import numpy as np
     d = cfg["hidden"] // cfg["n_heads"]
@@ -152,7 +153,8 @@ def model_forward_backward(layers: list, x, dy, cfg: dict, *, seed: int = 0, dty
     for li, p in enumerate(tp):
         cur, sv = rank_layer_forward(p, cur, batch=cfg["batch"], seq=cfg["seq"], head_dim=d, causal=bool(cfg["causal"]),
                                      dropout_p=cfg["dropout_p"], seed=seed, layer=li, theta=cfg.get("rope_theta", 10000.0),
-                                     bf16_sites=bf16_sites)
+                                     bf16_sites=bf16_sites, attn_dropout_p=cfg.get("attn_dropout_p", 0.0), head0=head0,
+                                     n_heads_total=cfg["n_heads"])
         saved.append(sv)
     out = dict(y=cur, saved=saved)
     if want_backward:

@@ -28,7 +28,7 @@ class LayerCfg(C.Structure):
     _fields_ = [("hidden", C.c_int32), ("n_heads", C.c_int32), ("seq", C.c_int32), ("batch", C.c_int32),
                 ("tp_degree", C.c_int32), ("tp_rank", C.c_int32), ("n_sub", C.c_int32), ("n_layers", C.c_int32),
                 ("causal", C.c_int32), ("dropout_p", C.c_float), ("seed", C.c_uint64), ("ln_eps", C.c_float),
-                ("flags", C.c_int32), ("arch", C.c_int32), ("ffn_hidden", C.c_int32), ("rope_theta", C.c_float)]
+                ("flags", C.c_int32), ("arch", C.c_int32), ("ffn_hidden", C.c_int32), ("rope_theta", C.c_float), ("attn_dropout_p", C.c_float)]
 
 
 class Weights(C.Structure):
@@ -76,6 +76,8 @@ _sig("oases_gemm_workspace_bytes", _sz, _P)
 _sig("oases_op_colsum_bf16", _i, _P, _i, _i, _i, _P, _P, _P)
 _sig("oases_op_attention_fwd", _i, _P, _P, _P, _i, _i, _i, _i, _i, _i, _i, _P)
 _sig("oases_op_attention_bwd", _i, _P, _P, _P, _P, _P, _P, _i, _i, _i, _i, _i, _i, _i, _P)
+_sig("oases_op_attention_dropout_fwd", _i, _P, _P, _P, _i, _i, _i, _i, _i, _i, _i, _u64, _i, _f, _i, _i, _P)
+_sig("oases_op_attention_dropout_bwd", _i, _P, _P, _P, _P, _P, _P, _i, _i, _i, _i, _i, _i, _i, _u64, _i, _f, _i, _i, _P)
 
 
 class OasesError(RuntimeError):
@@ -109,7 +111,7 @@ def make_cfg(cfg: dict, rank: int = 0, seed: int = 0, flags: int = 0, n_sub: int
     return LayerCfg(cfg["hidden"], cfg["n_heads"], cfg["seq"], cfg["batch"], cfg["tp"], rank,
                     cfg["n_sub"] if n_sub is None else n_sub, cfg["n_layers"], cfg["causal"], cfg["dropout_p"], seed,
                     0.0, flags, ARCH_LLAMA if llama else ARCH_BERT if cfg.get("arch") == "bert" else ARCH_GPT, cfg.get("ffn_hidden", 0) if llama else 0,
-                    cfg.get("rope_theta", 0.0) if llama else 0.0)
+                    cfg.get("rope_theta", 0.0) if llama else 0.0, cfg.get("attn_dropout_p", 0.0))
 
 
 class Handle:

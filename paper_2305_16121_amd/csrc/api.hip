@@ -390,7 +390,8 @@ static int run_op(const Run& R, const Op& op) {
       return launch_rope(wsp<uint16_t>(R, "dqkv", l) + r0 * 3 * hp, 3 * hp, Ms, (int64_t)r0, H->s, H->heads_l, H->d,
                          wsp<float>(R, "rope", 0), 1, s);
     case F_ATTN:
-      return launch_attention_fwd(qkv, attn, wsp<float>(R, "lse", l), H->b, H->s, H->heads_l, H->d, H->cfg.causal, (int)r0, Ms, s);
+      return launch_attention_fwd(qkv, attn, wsp<float>(R, "lse", l), H->b, H->s, H->heads_l, H->d, H->cfg.causal, (int)r0, Ms, s,
+                                  seed, l, H->cfg.attn_dropout_p, H->r * H->heads_l, H->nh);
     case F_PROJ:
       return launch_gemm(OASES_GEMM_NN, OASES_EPI_F32, Ms, h, hp, attn + r0 * hp, hp, W.wo, h, wsp<float>(R, "z1", l) + r0 * h, h,
                          nullptr, nullptr, 0, gws, H->gemm_ws_bytes, 0, s);
@@ -451,7 +452,8 @@ static int run_op(const Run& R, const Op& op) {
                          nullptr, nullptr, 0, gws, H->gemm_ws_bytes, 0, s);
     case B_ATTN:
       return launch_attention_bwd(qkv, attn, wsp<uint16_t>(R, "da", l), wsp<float>(R, "lse", l), wsp<float>(R, "delta", l),
-                                  wsp<uint16_t>(R, "dqkv", l), H->b, H->s, H->heads_l, H->d, H->cfg.causal, (int)r0, Ms, s);
+                                  wsp<uint16_t>(R, "dqkv", l), H->b, H->s, H->heads_l, H->d, H->cfg.causal, (int)r0, Ms, s, seed, l,
+                                  H->cfg.attn_dropout_p, H->r * H->heads_l, H->nh);
     case B_QKV_DGRAD:
       return launch_gemm(OASES_GEMM_NT, OASES_EPI_F32, Ms, h, 3 * hp, wsp<uint16_t>(R, "dqkv", l) + r0 * 3 * hp, 3 * hp, W.wqkv,
                          3 * hp, wsp<float>(R, "du", l) + r0 * h, h, nullptr, nullptr, 0, gws, H->gemm_ws_bytes, 0, s);
@@ -566,6 +568,7 @@ int oases_create(const oases_layer_cfg* c, oases_handle** out) {
   if (c->hidden > 16384) BAD("hidden %d too large (max 16384)", c->hidden);
   if (!(c->dropout_p >= 0.f && c->dropout_p < 1.f)) BAD("dropout_p %g outside [0,1)", (double)c->dropout_p);
   if (c->ln_eps < 0.f) BAD("ln_eps negative");
+  if (!(c->attn_dropout_p >= 0.f && c->attn_dropout_p < 1.f)) BAD("attn_dropout_p %g outside [0,1)", (double)c->attn_dropout_p);
   const long M = (long)c->batch * c->seq;
   if (M > (1l << 30)) BAD("too many tokens");
   if (M % c->n_sub) BAD("tokens %ld not divisible by n_sub %d", M, c->n_sub);
@@ -772,6 +775,17 @@ int oases_op_colsum_bf16(const void* a, int ld, int rows, int cols, void* out, v
 int oases_op_attention_fwd(const void* qkv, void* out, void* lse, int batch, int seq, int heads, int head_dim, int causal, int row0,
                            int rows, void* stream) {
   return launch_attention_fwd(qkv, out, (float*)lse, batch, seq, heads, head_dim, causal, row0, rows, (hipStream_t)stream);
+}
+int oases_op_attention_dropout_fwd(const void* qkv, void* out, void* lse, int batch, int seq, int heads, int head_dim, int causal,
+                                   int row0, int rows, uint64_t seed, int layer, float p, int head0, int heads_total, void* stream) {
+  return launch_attention_fwd(qkv, out, (float*)lse, batch, seq, heads, head_dim, causal, row0, rows, (hipStream_t)stream, seed, layer, p,
+                              head0, heads_total);
+}
+int oases_op_attention_dropout_bwd(const void* qkv, const void* out, const void* dout, const void* lse, void* delta, void* dqkv,
+                                   int batch, int seq, int heads, int head_dim, int causal, int row0, int rows, uint64_t seed, int layer,
+                                   float p, int head0, int heads_total, void* stream) {
+  return launch_attention_bwd(qkv, out, dout, (const float*)lse, (float*)delta, dqkv, batch, seq, heads, head_dim, causal, row0, rows,
+                              (hipStream_t)stream, seed, layer, p, head0, heads_total);
 }
 int oases_op_attention_bwd(const void* qkv, const void* out, const void* dout, const void* lse, void* delta, void* dqkv, int batch,
                            int seq, int heads, int head_dim, int causal, int row0, int rows, void* stream) {

@@ -39,7 +39,22 @@ struct AttnArgs {
   int blocks;  // 32-row blocks per sequence
   int nseq;    // sequences in the row range
   float scale, scale_log2;
+  // dropout on the probabilities (DROP kernels): Philox key, counter word 3 (layer | 2^31), byte threshold, 1/(1 - T/256),
+  // global index of local head 0 and heads of the unsharded layer
+  uint32_t dk0, dk1, dc3, dthresh;
+  float dscale;
+  int head0, heads_total;
 };
+
+// Dropout mask of the probabilities: the 4 x 4 block (q div 4, k div 4) of (sequence b, global head) draws one
+// Philox4x32-10 output with counter (k div 4, q div 4, b * heads_total + head, layer | 2^31); element (q, k) keeps its
+// value iff byte (k mod 4) of word (q mod 4) is >= the threshold.
+__device__ __forceinline__ Philox4 attn_drop_block(const AttnArgs& a, uint32_t k4, uint32_t q4, uint32_t bh) {
+  return philox4x32_10(k4, q4, bh, a.dc3, a.dk0, a.dk1);
+}
+__device__ __forceinline__ uint32_t pick_word(const Philox4& w, int j) {
+  return j == 0 ? w.v[0] : j == 1 ? w.v[1] : j == 2 ? w.v[2] : w.v[3];
+}
 
 // A 32-row tile of a [*, D] bf16 slice in LDS, rows padded so that BOTH access patterns are conflict-free on 64
 // banks: ds_read_b128 of 16 consecutive rows at one column (row stride = 4 resp. 12 banks mod 64) and the
@@ -162,7 +177,7 @@ __device__ __forceinline__ void combine4(const f32x16* acc, float* lds_part, int
 // =================================================================================================
 // forward
 // =================================================================================================
-template <int D, bool CAUSAL>
+template <int D, bool CAUSAL, bool DROP>
 __global__ __launch_bounds__(NT, 2) void attn_fwd_kernel(AttnArgs a) {
   constexpr int KS = D / 16, DT = D / 32, E = DT * 16;
   constexpr int kStageBytes = 4 * 2 * AT<D>::bytes;
@@ -238,6 +253,15 @@ __global__ __launch_bounds__(NT, 2) void attn_fwd_kernel(AttnArgs a) {
     }
     l = l * alpha + psum;
     m = mnew;
+    if (DROP) {  // the row sum keeps every probability; what goes on to V is dropped and rescaled
+      const uint32_t bh = (uint32_t)(seq_idx * a.heads_total + a.head0 + head);
+#pragma unroll
+      for (int grp = 0; grp < 4; grp++) {
+        const uint32_t ww = pick_word(attn_drop_block(a, (uint32_t)(kv0 + 8 * grp + 4 * g) >> 2, (uint32_t)qpos >> 2, bh), qpos & 3);
+#pragma unroll
+        for (int e = 0; e < 4; e++) s[4 * grp + e] = ((ww >> (8 * e)) & 0xffu) >= a.dthresh ? s[4 * grp + e] * a.dscale : 0.f;
+      }
+    }
     if (__any(alpha != 1.0f)) {  // the running maximum rarely moves after the first tiles
 #pragma unroll
       for (int dt = 0; dt < DT; dt++)
@@ -315,7 +339,7 @@ __global__ __launch_bounds__(NT) void attn_delta_kernel(AttnArgs a, int first_ro
 // =================================================================================================
 // backward: dQ for a 32-query block; the four waves split the key tiles
 // =================================================================================================
-template <int D, bool CAUSAL>
+template <int D, bool CAUSAL, bool DROP>
 __global__ __launch_bounds__(NT, 1) void attn_dq_kernel(AttnArgs a) {
   constexpr int KS = D / 16, DT = D / 32, E = DT * 16;
   constexpr int kStageBytes = 4 * 2 * AT<D>::bytes;
@@ -373,6 +397,15 @@ __global__ __launch_bounds__(NT, 1) void attn_dq_kernel(AttnArgs a) {
       dp = MFMA(kc_frag<D>(lv, ks, lane), dof[ks], dp);
     }
     const bool need_mask = (kv0 + 32 > a.seq) || (CAUSAL && kv0 + 31 > q_begin);
+    if (DROP) {  // dP = dropout factor * (dO V^T)
+      const uint32_t bh = (uint32_t)(seq_idx * a.heads_total + a.head0 + head);
+#pragma unroll
+      for (int grp = 0; grp < 4; grp++) {
+        const uint32_t ww = pick_word(attn_drop_block(a, (uint32_t)(kv0 + 8 * grp + 4 * g) >> 2, (uint32_t)qpos >> 2, bh), qpos & 3);
+#pragma unroll
+        for (int e = 0; e < 4; e++) dp[4 * grp + e] = ((ww >> (8 * e)) & 0xffu) >= a.dthresh ? dp[4 * grp + e] * a.dscale : 0.f;
+      }
+    }
 #pragma unroll
     for (int i = 0; i < 16; i++) {
       float ds = __builtin_amdgcn_exp2f(s[i] * a.scale_log2 - lse2) * (dp[i] - dl);
@@ -407,7 +440,7 @@ __global__ __launch_bounds__(NT, 1) void attn_dq_kernel(AttnArgs a) {
 // =================================================================================================
 // backward: dK, dV for a 32-key block; the four waves split the 32-query tiles that see it
 // =================================================================================================
-template <int D, bool CAUSAL>
+template <int D, bool CAUSAL, bool DROP>
 __global__ __launch_bounds__(NT, 1) void attn_dkv_kernel(AttnArgs a) {
   constexpr int KS = D / 16, DT = D / 32, E = DT * 16;
   constexpr int kStageBytes = 4 * (2 * AT<D>::bytes + 256);
@@ -470,16 +503,24 @@ __global__ __launch_bounds__(NT, 1) void attn_dkv_kernel(AttnArgs a) {
       const int ql = 8 * i4 + 4 * g;  // 4 consecutive queries
       f32x4 l4 = *reinterpret_cast<const f32x4*>(lstat + ql);
       f32x4 d4 = *reinterpret_cast<const f32x4*>(lstat + 32 + ql);
+      Philox4 dw;
+      if (DROP) dw = attn_drop_block(a, (uint32_t)kpos >> 2, (uint32_t)(q0 + ql) >> 2, (uint32_t)(seq_idx * a.heads_total + a.head0 + head));
 #pragma unroll
       for (int e = 0; e < 4; e++) {
         const int i = 4 * i4 + e;
-        float p = __builtin_amdgcn_exp2f(s[i] * a.scale_log2 - l4[e]);
-        float ds = p * (dp[i] - d4[e]);
+        const float p = __builtin_amdgcn_exp2f(s[i] * a.scale_log2 - l4[e]);
+        float dpe = dp[i], pv = p;  // pv: what multiplied V in forward
+        if (DROP) {  // this lane's key is byte (kpos mod 4) of the word of query e of the group
+          const bool keep = ((dw.v[e] >> (8 * (kpos & 3))) & 0xffu) >= a.dthresh;
+          dpe = keep ? dpe * a.dscale : 0.f;
+          pv = keep ? p * a.dscale : 0.f;
+        }
+        float ds = p * (dpe - d4[e]);
         if (need_mask) {
           int qp = q0 + ql + e;
-          if (qp >= a.seq || (CAUSAL && kpos > qp)) { p = 0.f; ds = 0.f; }   // select, never multiply: the rest may be NaN
+          if (qp >= a.seq || (CAUSAL && kpos > qp)) { pv = 0.f; ds = 0.f; }   // select, never multiply: the rest may be NaN
         }
-        s[i] = p;
+        s[i] = pv;
         dp[i] = ds;
       }
     }
@@ -546,8 +587,25 @@ int fill_args(AttnArgs& a, int batch, int seq, int heads, int head_dim, int caus
 
 }  // namespace
 
+// fills the dropout fields; false (after set_error) on a bad rate or head range
+static bool fill_dropout(AttnArgs& a, uint64_t seed, int layer, float p_attn, int head0, int heads_total, int heads, const char* who) {
+  if (!(p_attn >= 0.f && p_attn < 1.f)) { set_error("%s: attention dropout rate %g outside [0,1)", who, (double)p_attn); return false; }
+  int T = (int)__builtin_rint((double)p_attn * 256.0);
+  if (T > 255) T = 255;
+  a.dthresh = (uint32_t)T;
+  if (T == 0) return true;
+  if (heads_total <= 0 || head0 < 0 || head0 + heads > heads_total) { set_error("%s: heads [%d,%d) outside the %d heads of the layer", who, head0, head0 + heads, heads_total); return false; }
+  a.dk0 = (uint32_t)seed;
+  a.dk1 = (uint32_t)(seed >> 32);
+  a.dc3 = ((uint32_t)layer & 0x7fffffffu) | 0x80000000u;
+  a.dscale = (float)(256.0 / (256.0 - T));
+  a.head0 = head0;
+  a.heads_total = heads_total;
+  return true;
+}
+
 int launch_attention_fwd(const void* qkv, void* out, float* lse, int batch, int seq, int heads, int head_dim, int causal,
-                         int row0, int rows, hipStream_t s) {
+                         int row0, int rows, hipStream_t s, uint64_t seed, int layer, float p_attn, int head0, int heads_total) {
   if (!qkv || !out || !lse) { set_error("attention_fwd: NULL argument"); return OASES_ENULL; }
   if (!aligned16(qkv) || !aligned16(out)) { set_error("attention_fwd: pointer not 16-byte aligned"); return OASES_EALIGN; }
   AttnArgs a{};
@@ -559,20 +617,23 @@ int launch_attention_fwd(const void* qkv, void* out, float* lse, int batch, int 
   a.scale = 1.0f / sqrtf((float)head_dim);
   a.scale_log2 = a.scale * kLog2e;
   a.nseq = nseq;
+  if (!fill_dropout(a, seed, layer, p_attn, head0, heads_total, heads, "attention_fwd")) return OASES_EINVAL;
   dim3 grid(nseq * a.blocks * heads), block(NT);
-  if (head_dim == 64) {
-    if (causal) hipLaunchKernelGGL((attn_fwd_kernel<64, true>), grid, block, 0, s, a);
-    else hipLaunchKernelGGL((attn_fwd_kernel<64, false>), grid, block, 0, s, a);
-  } else {
-    if (causal) hipLaunchKernelGGL((attn_fwd_kernel<128, true>), grid, block, 0, s, a);
-    else hipLaunchKernelGGL((attn_fwd_kernel<128, false>), grid, block, 0, s, a);
-  }
+#define OASES_ATTN_FWD(DD, CC)                                                                              \
+  do {                                                                                                      \
+    if (a.dthresh) hipLaunchKernelGGL((attn_fwd_kernel<DD, CC, true>), grid, block, 0, s, a);               \
+    else hipLaunchKernelGGL((attn_fwd_kernel<DD, CC, false>), grid, block, 0, s, a);                        \
+  } while (0)
+  if (head_dim == 64) { if (causal) OASES_ATTN_FWD(64, true); else OASES_ATTN_FWD(64, false); }
+  else { if (causal) OASES_ATTN_FWD(128, true); else OASES_ATTN_FWD(128, false); }
+#undef OASES_ATTN_FWD
   OASES_LAUNCH_CHECK("attn_fwd_kernel");
   return 0;
 }
 
 int launch_attention_bwd(const void* qkv, const void* out, const void* dout, const float* lse, float* delta, void* dqkv,
-                         int batch, int seq, int heads, int head_dim, int causal, int row0, int rows, hipStream_t s) {
+                         int batch, int seq, int heads, int head_dim, int causal, int row0, int rows, hipStream_t s, uint64_t seed,
+                         int layer, float p_attn, int head0, int heads_total) {
   if (!qkv || !out || !dout || !lse || !delta || !dqkv) { set_error("attention_bwd: NULL argument"); return OASES_ENULL; }
   if (!aligned16(qkv) || !aligned16(out) || !aligned16(dout) || !aligned16(dqkv)) {
     set_error("attention_bwd: pointer not 16-byte aligned");
@@ -594,14 +655,20 @@ int launch_attention_bwd(const void* qkv, const void* out, const void* dout, con
   const int n_rows = (a.seq0 + nseq) * seq - row0;
   const long pairs = (long)n_rows * heads * (head_dim / 8);
   a.nseq = nseq;
+  if (!fill_dropout(a, seed, layer, p_attn, head0, heads_total, heads, "attention_bwd")) return OASES_EINVAL;
   dim3 dgrid((unsigned)((pairs + NT - 1) / NT)), block(NT), grid(nseq * a.blocks * heads);
   if (head_dim == 64) hipLaunchKernelGGL((attn_delta_kernel<64>), dgrid, block, 0, s, a, first_row, n_rows);
   else hipLaunchKernelGGL((attn_delta_kernel<128>), dgrid, block, 0, s, a, first_row, n_rows);
   OASES_LAUNCH_CHECK("attn_delta_kernel");
-#define OASES_ATTN_BWD(DD, CC)                                                    \
-  do {                                                                            \
-    hipLaunchKernelGGL((attn_dkv_kernel<DD, CC>), grid, block, 0, s, a);          \
-    hipLaunchKernelGGL((attn_dq_kernel<DD, CC>), grid, block, 0, s, a);           \
+#define OASES_ATTN_BWD(DD, CC)                                                              \
+  do {                                                                                      \
+    if (a.dthresh) {                                                                        \
+      hipLaunchKernelGGL((attn_dkv_kernel<DD, CC, true>), grid, block, 0, s, a);            \
+      hipLaunchKernelGGL((attn_dq_kernel<DD, CC, true>), grid, block, 0, s, a);             \
+    } else {                                                                                \
+      hipLaunchKernelGGL((attn_dkv_kernel<DD, CC, false>), grid, block, 0, s, a);           \
+      hipLaunchKernelGGL((attn_dq_kernel<DD, CC, false>), grid, block, 0, s, a);            \
+    }                                                                                       \
   } while (0)
   if (head_dim == 64) { if (causal) OASES_ATTN_BWD(64, true); else OASES_ATTN_BWD(64, false); }
   else { if (causal) OASES_ATTN_BWD(128, true); else OASES_ATTN_BWD(128, false); }

@@ -127,11 +127,14 @@ int launch_gemm(int op, int epi, int M, int N, int K, const void* A, int lda, co
                 hipStream_t s);
 int gemm_variant(int op, int epi, int M, int N, int K, size_t ws_bytes);  // 1e8*[waves split k] + 1e6*slices + 1e3*BM + BN
 constexpr size_t kSplitKWorkspaceBytes = 256u << 20;
+// p_attn > 0: dropout on the probabilities (mask keyed by seed, layer, sequence, global head = head0 + local head, q, k)
 int launch_attention_fwd(const void* qkv, void* out, float* lse, int batch, int seq, int heads, int head_dim,
-                         int causal, int row0, int rows, hipStream_t s);
+                         int causal, int row0, int rows, hipStream_t s, uint64_t seed = 0, int layer = 0, float p_attn = 0.f,
+                         int head0 = 0, int heads_total = 0);
 int launch_attention_bwd(const void* qkv, const void* out, const void* dout, const float* lse, float* delta,
                          void* dqkv, int batch, int seq, int heads, int head_dim, int causal, int row0,
-                         int rows, hipStream_t s);
+                         int rows, hipStream_t s, uint64_t seed = 0, int layer = 0, float p_attn = 0.f, int head0 = 0,
+                         int heads_total = 0);
 
 constexpr int kColPartials = 1024;  // row-groups of the two-stage column reductions
 
