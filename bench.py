@@ -123,6 +123,7 @@ def main():
     ap.add_argument("--recompute", action="store_true",
                     help="fine-grained recomputation: activations are rebuilt inside backward (model flops unchanged, more work)")
     ap.add_argument("--attn-dropout", type=float, default=None, help="dropout rate on the attention probabilities (off in the workloads)")
+    ap.add_argument("--graph", action="store_true", help="capture one step into a HIP graph and time its replays (launch-bound small layers)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-profile", action="store_true")
     ap.add_argument("--calib-copy", action="store_true",
@@ -168,9 +169,18 @@ def main():
     for _ in range(a.warmup):
         step(H)
     torch.cuda.synchronize()
+    run = lambda: step(H)
+    if a.graph:
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=s1):
+            step(H)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        run = graph.replay
     t0 = time.perf_counter()
     for _ in range(a.steps):
-        step(H)
+        run()
     torch.cuda.synchronize()
     dt = (time.perf_counter() - t0) / a.steps
     flops = model_flops(cfg)
@@ -182,7 +192,7 @@ def main():
            "data": "synthetic",
            "config": {"workload": f"{a.config}: {'LLaMA-style' if cfg.get('arch') == 'llama' else 'GPT'} layer h={h} heads={cfg['n_heads']} seq={cfg['seq']} batch={cfg['batch']} "
                                   f"t={cfg['tp']} rank 0 layers={cfg['n_layers']} causal={cfg['causal']} p={cfg['dropout_p']}" + (f" ffn={cfg['ffn_hidden']}" if cfg.get("arch") == "llama" else ""),
-                      "n_sub": cfg["n_sub"], "attn_dropout_p": cfg.get("attn_dropout_p", 0.0), "streams": 1 if a.serialise else 2, "recompute": bool(a.recompute),
+                      "n_sub": cfg["n_sub"], "attn_dropout_p": cfg.get("attn_dropout_p", 0.0), "streams": 1 if a.serialise else 2, "hip_graph": bool(a.graph), "recompute": bool(a.recompute),
                       "workspace_mib": round(H.workspace_bytes / 2 ** 20, 1), "model_gflop_per_step": round(flops / 1e9, 1),
                       "frac_of_bf16_peak": round(tflops / PEAK_BF16_TFLOPS, 4)}}
 
