@@ -6,7 +6,7 @@ the HIP path.
 
 What it computes.  The method (Oases' schedule over Megatron's partition) reaches
 exactly the result of the unsharded layer: the schedule only reorders independent
-sub-batch operators (Sec. IV-A, "results are not affected") and the partition only
+sub-batch operators (Sec. IV-A: the order may change, the results may not) and the partition only
 splits weight matrices by column or by row, with an AllReduce y = sum_i x_i whose
 input gradient equals its output gradient (Sec. IV-B, Eq. (1)).  So the oracle is the
 plain definition of the layer, written for *one rank* in the general form

@@ -1,4 +1,4 @@
-"""Offline profiling + planning for a stack of identical layers (paper Sec. V-C, "offline profiling"): run ONE layer
+"""Offline profiling + planning for a stack of identical layers (the offline profiling step of paper Sec. V-C): run ONE layer
 of the model on this GPU under every power-of-two TMP degree with the library's per-operator timers, turn the
 timings into the cost vectors of Eq. (3), model communication, AllGather and memory analytically, and let the
 library's planner (include/oases_planner.h) choose a degree per layer.
@@ -9,7 +9,7 @@ What is measured: d^0, d^1 (forward and backward, the backward under fine-graine
 it) of the two blocks of a layer -- [LN1, QKV, ATTN, PROJ | reduction] and [BDR1+LN2, FC1, FC2 | reduction]; the
 kernel that consumes a reduction belongs to the block that follows it in the pass.  A weight-gradient GEMM that is
 merged over the sub-batches is charged half to each.
-What is modelled (one node of `--gpus` GPUs, all-to-all links of `--link-gbs` GB/s each way, Sec. V "2K(N-1)/N"):
+What is modelled (one node of `--gpus` GPUs, all-to-all links of `--link-gbs` GB/s each way, AllReduce volume 2K(N-1)/N as in Sec. V):
   AllReduce of a sub-batch partial, K = Ms*h*4 bytes, N = degree:  ring  2K(N-1)/N / link,  mesh  2K/N / link
   AllGather on a change of degree (the activation [Ms, h] fp32):   ring  K(N-1)/N / link,   mesh  K/N / link, N = larger degree
   m_s = 16 bytes per parameter of the block / degree; m_t = the block's saved input, M_local*h*4 bytes;

@@ -152,7 +152,7 @@ def test_sub_batch_count_does_not_change_results(name, subs):
         assert rel_err(run["y"], base["y"]) < 5e-3 and rel_err(run["dx"], base["dx"]) < 1e-2, n
         for l in range(cfg["n_layers"]):
             for k in LH.GPU_PARAMS:   # sums over rows of bf16-stored operands: a flipped bf16 rounding upstream moves a weight
-                # gradient by up to its storage-format floor; the contract's gradient tolerance bounds it
+                # gradient by up to its storage-format floor (bf16 operand storage); the contract's gradient tolerance bounds it
                 assert rel_err(run["grads"][l][k], base["grads"][l][k]) < LH.GRAD_TOL, (n, l, k)
 
 
