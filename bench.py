@@ -89,7 +89,7 @@ def gemm_kernel_label(line, cfg, B, ws_bytes):
     tile = B.lib.oases_op_gemm_variant({"NN": 0, "NT": 1, "TN": 2}[form], epi_id, m, n, k, ws_bytes)
     slices = tile // 1000000 % 100
     split = f"_splitk{slices}" if slices >= 2 else ""
-    wk = "_wavek2" if tile >= 100000000 else ""
+    wk = "_dtl" if tile >= 200000000 else "_wavek2" if tile >= 100000000 else ""
     return f"gemm_{form}_{epi}_{tile // 1000 % 1000}x{tile % 1000}{wk}{split}"
 
 

@@ -485,6 +485,279 @@ __global__ __launch_bounds__(64 * WGM * WGN * WGK) void gemm_kernel(GemmArgs g) 
   else gemm_tile<BM, BN, WGM, WGN, WGK, A_KC, B_KC, EPI, false>(g, lds, m0, n0);
 }
 
+// =================================================================================================
+// 256 x 256 tiles fed by direct-to-LDS loads (global_load_lds_dwordx4): no staging registers, four LDS stages of 32 k,
+// three tiles (96 KB per CU) in flight.  The compiler would put s_waitcnt vmcnt(0) in front of every LDS read that
+// might alias a pending LDS DMA, so the fragment reads are inline assembly and every wait is placed by hand:
+//   vmcnt  -- DMA instructions complete in order, 8 per wave and tile: "tile t has landed" = at most 8 x (younger tiles
+//             in flight) outstanding, then the workgroup barrier makes all four waves' parts visible;
+//   lgkmcnt -- LDS reads return in order: fragments of the older k step are waited for with the younger step's reads
+//             still outstanding.
+// Only whole tiles (M, N multiples of 256, K of 32) and no k slices; everything else runs on the kernels above.
+// =================================================================================================
+#ifndef OASES_DTL_STAGES
+#define OASES_DTL_STAGES 4
+#endif
+constexpr int BKD = 32, NSD = OASES_DTL_STAGES;
+constexpr int kDtlOperand = 256 * BKD * 2;  // bytes of one operand tile
+constexpr int kDtlStage = 2 * kDtlOperand;
+
+template <int OFF>
+__device__ __forceinline__ u32x4 lds_read_b128(uint32_t addr) {
+  u32x4 v;
+  asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(OFF));
+  return v;
+}
+template <int OFF>
+__device__ __forceinline__ u32x2 lds_read_tr16_b64(uint32_t addr) {
+  u32x2 v;
+  asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(OFF));
+  return v;
+}
+// the eight fragments of one k step become valid: at most N younger LDS reads may still be outstanding
+template <int N>
+__device__ __forceinline__ void lds_wait(u32x4 (&a)[4], u32x4 (&b)[4]) {
+  asm volatile("s_waitcnt lgkmcnt(%8)"
+               : "+v"(a[0]), "+v"(a[1]), "+v"(a[2]), "+v"(a[3]), "+v"(b[0]), "+v"(b[1]), "+v"(b[2]), "+v"(b[3])
+               : "n"(N));
+}
+
+// Operand tile in LDS.  KC (k contiguous in memory): [256 rows][32 k] = 64-byte rows, 16-byte chunk c of row r at slot
+// c ^ ((r/4)%4) (16 consecutive rows at one chunk then cover all 64 banks).  MC (row index contiguous in memory):
+// [32 k][256 rows] = 512-byte k rows, chunk c of k row kr at slot c ^ 4*(kr%4) (the 4 k rows x 64 bytes that 32 lanes of
+// a transpose read touch in one LDS cycle then fall on 16 different chunk positions mod 16).  One DMA instruction of a wave writes 1 KB
+// of the tile, lane i the 16 bytes at i*16: the swizzle is applied to the global address the lane fetches.
+template <bool KC>
+__device__ __forceinline__ const char* dtl_src(const uint16_t* base, int ld, int r0, int q, int lane) {
+  if (KC) {
+    const int row = 16 * q + (lane >> 2), chunk = (lane & 3) ^ ((row >> 2) & 3);
+    return reinterpret_cast<const char*>(base + (size_t)(r0 + row) * ld + chunk * 8);
+  }
+  const int kr = 2 * q + (lane >> 5), cc = (lane & 31) ^ (4 * (kr & 3));
+  return reinterpret_cast<const char*>(base + (size_t)kr * ld + r0 + cc * 8);
+}
+// per-lane LDS offsets of the fragment reads of a wave's 128-row part starting at tile row R0
+template <bool KC>
+__device__ __forceinline__ void dtl_frag_offsets(uint32_t* off, int R0, int lane) {
+  if (KC) {  // off[kk]: fragment i adds 32 rows = 2048 bytes
+#pragma unroll
+    for (int kk = 0; kk < 2; kk++) {
+      const int row = R0 + (lane & 31), chunk = kk * 2 + (lane >> 5);
+      off[kk] = (uint32_t)(row * 64 + 16 * (chunk ^ ((row >> 2) & 3)));
+    }
+  } else {  // off[i]: k step kk adds 16 k rows = 8192 bytes, the second half of the fragment 4 k rows = 2048 bytes
+    const int krow = 8 * (lane >> 5) + ((lane & 15) >> 2);
+#pragma unroll
+    for (int i = 0; i < 4; i++) {
+      const int col = R0 + 32 * i + 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
+      off[i] = (uint32_t)(krow * 512 + (((col >> 3) ^ (4 * (krow & 3))) << 4) + (col & 7) * 2);
+    }
+  }
+}
+template <bool KC, int KK>
+__device__ __forceinline__ void dtl_read_frags(u32x4 (&f)[4], uint32_t base, const uint32_t* off) {
+  if constexpr (KC) {
+    const uint32_t a = base + off[KK];
+    f[0] = lds_read_b128<0>(a);
+    f[1] = lds_read_b128<2048>(a);
+    f[2] = lds_read_b128<4096>(a);
+    f[3] = lds_read_b128<6144>(a);
+  } else {
+#define OASES_TR(i)                                                         \
+  {                                                                         \
+    const u32x2 lo = lds_read_tr16_b64<KK * 8192>(base + off[i]);           \
+    const u32x2 hi = lds_read_tr16_b64<KK * 8192 + 2048>(base + off[i]);    \
+    f[i] = u32x4{lo[0], lo[1], hi[0], hi[1]};                               \
+  }
+    OASES_TR(0) OASES_TR(1) OASES_TR(2) OASES_TR(3)
+#undef OASES_TR
+  }
+}
+
+template <bool A_KC, bool B_KC, int EPI>
+__global__ __launch_bounds__(256) void gemm_dtl_kernel(GemmArgs g) {
+  __shared__ __attribute__((aligned(1024))) char lds[NSD * kDtlStage];
+  int tile_m, tile_n;
+  {
+    const int T = g.tiles_m * g.tiles_n, pid = blockIdx.x;
+    const int per = (T + 7) / 8, tall = (T % 8 == 0) ? 8 : T % 8;
+    int xcd = pid & 7, local = pid >> 3;
+    int logical = xcd < tall ? xcd * per + local : tall * per + (xcd - tall) * (per - 1) + local;
+    constexpr int GM = 8;
+    int width = GM * g.tiles_n;
+    int group = logical / width, first_m = group * GM;
+    int gsz = min(g.tiles_m - first_m, GM);
+    tile_m = first_m + (logical % width) % gsz;
+    tile_n = (logical % width) / gsz;
+  }
+  const int m0 = tile_m * 256, n0 = tile_n * 256;
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6), wm = wave >> 1, wn = wave & 1;
+  constexpr int WGM = 2, WGN = 2, WTM = 128, WTN = 128, TM = 4, TN = 4;
+  constexpr bool FULL = true;
+  const int nk = g.K / BKD;
+
+  f32x16 acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; i++)
+#pragma unroll
+    for (int j = 0; j < TN; j++)
+#pragma unroll
+      for (int e = 0; e < 16; e++) acc[i][j][e] = 0.f;
+
+  // DMA sources of this lane: instruction j of this wave is instruction q = 4*wave + j of the operand tile
+  // (the swizzle of an MC tile depends on the parity of q: one source pointer for even, one for odd instructions)
+  const char* srcA[2] = {dtl_src<A_KC>(g.A, g.lda, m0, 4 * wave, lane), dtl_src<A_KC>(g.A, g.lda, m0, 4 * wave + 1, lane)};
+  const char* srcB[2] = {dtl_src<B_KC>(g.B, g.ldb, n0, 4 * wave, lane), dtl_src<B_KC>(g.B, g.ldb, n0, 4 * wave + 1, lane)};
+  const size_t stepA_q = A_KC ? (size_t)32 * g.lda * 2 : (size_t)4 * g.lda * 2;   // two instructions on: 32 rows resp. 4 k rows
+  const size_t stepB_q = B_KC ? (size_t)32 * g.ldb * 2 : (size_t)4 * g.ldb * 2;
+  const size_t stepA_k = A_KC ? (size_t)BKD * 2 : (size_t)BKD * g.lda * 2;          // next k tile
+  const size_t stepB_k = B_KC ? (size_t)BKD * 2 : (size_t)BKD * g.ldb * 2;
+  typedef const void __attribute__((address_space(1))) * gptr_t;
+  typedef void OASES_LDS* lptr_t;
+  auto issue = [&](int t) {
+    char* st = lds + (t % NSD) * kDtlStage + wave * 4096;
+#pragma unroll
+    for (int j = 0; j < 4; j++) {
+      const char* a = srcA[j & 1] + (size_t)t * stepA_k + (j >> 1) * stepA_q;
+      const char* b = srcB[j & 1] + (size_t)t * stepB_k + (j >> 1) * stepB_q;
+      __builtin_amdgcn_global_load_lds((gptr_t)a, (lptr_t)(st + j * 1024), 16, 0, 0);
+      __builtin_amdgcn_global_load_lds((gptr_t)b, (lptr_t)(st + kDtlOperand + j * 1024), 16, 0, 0);
+    }
+  };
+
+  uint32_t offA[4], offB[4];
+  dtl_frag_offsets<A_KC>(offA, wm * WTM, lane);
+  dtl_frag_offsets<B_KC>(offB, wn * WTN, lane);
+  const uint32_t lds0 = (uint32_t)(uintptr_t)(OASES_LDS char*)lds;
+  u32x4 fa[2][4], fb[2][4];
+  constexpr int NRA = A_KC ? 4 : 8, NRB = B_KC ? 4 : 8, NR = NRA + NRB > 15 ? 15 : NRA + NRB;  // reads of one k step (lgkmcnt saturates at 15)
+  auto mma = [&](int buf) {
+#pragma unroll
+    for (int i = 0; i < TM; i++)
+#pragma unroll
+      for (int j = 0; j < TN; j++) {
+        const bf16x8 a = __builtin_bit_cast(bf16x8, fa[buf][i]), b = __builtin_bit_cast(bf16x8, fb[buf][j]);
+        if constexpr (EPI == EPI_F32) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[i][j], 0, 0, 0);
+        else acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b, a, acc[i][j], 0, 0, 0);
+      }
+  };
+  // s_waitcnt vmcnt(n) only.  Steady state: NSD-2 younger tiles of 8 DMA instructions each may still be in flight
+  constexpr int kYoung = 8 * (NSD - 2);
+  constexpr int kVm16 = ((kYoung >> 4) << 14) | (kYoung & 15) | (7 << 4) | (15 << 8), kVm0 = (7 << 4) | (15 << 8);
+
+#pragma unroll
+  for (int t = 0; t < NSD - 1; t++)
+    if (t < nk) issue(t);
+  if (nk > NSD - 2) __builtin_amdgcn_s_waitcnt(kVm16); else __builtin_amdgcn_s_waitcnt(kVm0);
+  __builtin_amdgcn_s_barrier();
+  dtl_read_frags<A_KC, 0>(fa[0], lds0, offA);
+  dtl_read_frags<B_KC, 0>(fb[0], lds0 + kDtlOperand, offB);
+
+  // one 32-wide k tile.  STEADY: tile kt+NSD-1 exists and is requested now (its stage held tile kt-1, which every wave
+  // finished reading before the last barrier), so two younger tiles are in flight when tile kt+1 must have landed;
+  // NEXT: tile kt+1 exists.
+  uint32_t cur = lds0;
+  auto iteration = [&](auto steady_c, auto next_c, int kt) {
+    constexpr bool STEADY = decltype(steady_c)::value, NEXT = decltype(next_c)::value;
+    const uint32_t nxt = cur + kDtlStage == lds0 + NSD * kDtlStage ? lds0 : cur + kDtlStage;
+    dtl_read_frags<A_KC, 1>(fa[1], cur, offA);
+    dtl_read_frags<B_KC, 1>(fb[1], cur + kDtlOperand, offB);
+    lds_wait<NR>(fa[0], fb[0]);
+    if (STEADY) issue(kt + NSD - 1);
+    mma(0);
+    if (NEXT) {
+      if (STEADY) __builtin_amdgcn_s_waitcnt(kVm16); else __builtin_amdgcn_s_waitcnt(kVm0);  // own part of tile kt+1 has landed
+      __builtin_amdgcn_s_barrier();
+      dtl_read_frags<A_KC, 0>(fa[0], nxt, offA);
+      dtl_read_frags<B_KC, 0>(fb[0], nxt + kDtlOperand, offB);
+      lds_wait<NR>(fa[1], fb[1]);
+    } else {
+      lds_wait<0>(fa[1], fb[1]);
+    }
+    mma(1);
+    cur = nxt;
+  };
+  {
+    using T_ = std::true_type;
+    using F_ = std::false_type;
+    int kt = 0;
+    for (; kt + NSD - 1 < nk; kt++) iteration(T_{}, T_{}, kt);
+    for (; kt + 1 < nk; kt++) iteration(F_{}, T_{}, kt);
+    iteration(F_{}, F_{}, kt);
+  }
+  constexpr bool ROWMAJ = EPI == EPI_F32;
+  // epilogue of one 32 x 32 accumulator tile (i,j) of this wave: element e is C[row][col + (e&3)] with
+  //   row = m0 + wm*WTM + 32 i + (lane & 31),  col = n0 + wn*WTN + 32 j + 8 (e>>2) + 4 (lane>>5)
+  auto emit = [&](int i, int j, const f32x16& a) {
+    if constexpr (ROWMAJ) {
+      // element e is C[row0 + 8 (e>>2) + 4 (lane>>5) + (e&3)][col], col = lane & 31 of the tile
+      const int col = n0 + wn * WTN + j * 32 + (lane & 31);
+      if (!FULL && col >= g.N) return;
+      float* cbase = reinterpret_cast<float*>(g.C) + col;
+#pragma unroll
+      for (int e = 0; e < 16; e++) {
+        const int row = m0 + wm * WTM + i * 32 + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
+        if (!FULL && row >= g.M) continue;
+        float* p = cbase + (size_t)row * g.ldc;
+        *p = a[e];
+      }
+      return;
+    }
+    const int row = m0 + wm * WTM + i * 32 + (lane & 31);
+    if (!FULL && row >= g.M) return;
+#pragma unroll
+    for (int q = 0; q < 4; q++) {
+      const int col = n0 + wn * WTN + j * 32 + 8 * q + 4 * (lane >> 5);
+      if (!FULL && col >= g.N) continue;
+      f32x4 v = {a[4 * q], a[4 * q + 1], a[4 * q + 2], a[4 * q + 3]};
+      const size_t o = (size_t)row * g.ldc + col;
+      if (EPI == EPI_DSWIGLU) {
+        // the accumulator holds dF for 4 columns of f; gate and up pre-activations of those columns sit in 32-column
+        // blocks side by side in aux ([gate 32 | up 32] per block), and so do their gradients in C
+        const size_t cg = (size_t)col + (col & ~31);
+        const u32x2 gt = *reinterpret_cast<const u32x2*>(g.aux + (size_t)row * g.ldaux + cg);
+        const u32x2 up = *reinterpret_cast<const u32x2*>(g.aux + (size_t)row * g.ldaux + cg + 32);
+        float dg[4], du[4];
+#pragma unroll
+        for (int e = 0; e < 4; e++) {
+          const float ge = bf16_bits_to_f32((e & 1) ? gt[e >> 1] >> 16 : gt[e >> 1] & 0xffffu);
+          const float ue = bf16_bits_to_f32((e & 1) ? up[e >> 1] >> 16 : up[e >> 1] & 0xffffu);
+          dg[e] = v[e] * ue * silu_grad_f(ge);
+          du[e] = v[e] * silu_f(ge);
+        }
+        uint16_t* cp = reinterpret_cast<uint16_t*>(g.C) + (size_t)row * g.ldc + cg;
+        *reinterpret_cast<u32x2*>(cp) = u32x2{pack_bf16x2(dg[0], dg[1]), pack_bf16x2(dg[2], dg[3])};
+        *reinterpret_cast<u32x2*>(cp + 32) = u32x2{pack_bf16x2(du[0], du[1]), pack_bf16x2(du[2], du[3])};
+      } else if (EPI == EPI_F32) {
+        *reinterpret_cast<f32x4*>(reinterpret_cast<float*>(g.C) + o) = v;
+      } else if (EPI == EPI_ACC_F32) {
+        f32x4* p = reinterpret_cast<f32x4*>(reinterpret_cast<float*>(g.C) + o);
+        *p = *p + v;
+      } else {
+        uint16_t* cp = reinterpret_cast<uint16_t*>(g.C) + o;
+        if (EPI == EPI_BIAS_BF16 || EPI == EPI_BIAS_GELU) v += *reinterpret_cast<const f32x4*>(g.bias + col);
+        if (EPI == EPI_BIAS_GELU) {
+          *reinterpret_cast<u32x2*>(g.aux + (size_t)row * g.ldaux + col) = u32x2{pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3])};
+#pragma unroll
+          for (int e = 0; e < 4; e++) v[e] = gelu_tanh(v[e]);
+        } else if (EPI == EPI_DGELU) {
+          u32x2 x = *reinterpret_cast<const u32x2*>(g.aux + (size_t)row * g.ldaux + col);
+          v[0] *= gelu_tanh_grad(bf16_bits_to_f32(x[0] & 0xffffu));
+          v[1] *= gelu_tanh_grad(bf16_bits_to_f32(x[0] >> 16));
+          v[2] *= gelu_tanh_grad(bf16_bits_to_f32(x[1] & 0xffffu));
+          v[3] *= gelu_tanh_grad(bf16_bits_to_f32(x[1] >> 16));
+        }
+        *reinterpret_cast<u32x2*>(cp) = u32x2{pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3])};
+      }
+    }
+  };
+
+#pragma unroll
+  for (int i = 0; i < TM; i++)
+#pragma unroll
+    for (int j = 0; j < TN; j++) emit(i, j, acc[i][j]);
+}
+
 // split-K second pass: C = epilogue(sum over slices of the fp32 partial planes), slices added in index order
 template <int EPI>
 __global__ __launch_bounds__(256) void splitk_fixup_kernel(const float* __restrict__ part, int S, GemmArgs g) {
@@ -551,9 +824,10 @@ int launch_one(const GemmArgs& g0, int ksplit, float* ws, hipStream_t s) {
 // Tile and split-K choice by a small time model.  Bigger tiles run closer to the MFMA rate (fewer LDS bytes per flop)
 // but a launch only uses the chip well if its workgroup count is near a multiple of the 256 CUs; splitting K multiplies
 // the workgroup count at the price of a second pass over fp32 partial planes.  Rates measured on this part.
-struct TileChoice { int bm, bn, ksplit; bool wave_ksplit; };
+struct TileChoice { int bm, bn, ksplit; bool wave_ksplit; bool dtl = false; };
 // per kind of contraction (0: NN, 1: NT, 2: TN, 3: NN with the bias+GeLU epilogue): whether the rectangular tiles
 // split k between waves, and the sustained rates of the four block tiles
+bool dtl_fits(int M, int N, int K) { return M % 256 == 0 && N % 256 == 0 && K % BKD == 0 && K >= BKD; }
 struct KindTable { bool wave_ksplit; float r256x256, r128x256, r256x128, r128x128; };
 const KindTable g_kinds[4] = {{true, 1150.f, 1000.f, 960.f, 740.f}, {true, 1150.f, 1000.f, 960.f, 740.f},
                         {true, 1150.f, 1000.f, 960.f, 740.f}, {false, 1150.f, 880.f, 900.f, 740.f}};
@@ -573,18 +847,26 @@ TileChoice pick_tile(int kind, int M, int N, int K, size_t ws_bytes) {
       if (t < best_t) { best_t = t; best = TileChoice{c.bm, c.bn, S, kt.wave_ksplit}; }
     }
   }
+  // TN with whole 256 x 256 tiles: the direct-to-LDS kernel is the faster one (both operands go through the
+  // transposing LDS reads, which the staged kernel pays for with bank conflicts on its stores)
+  if (kind == 2 && best.bm == 256 && best.bn == 256 && best.ksplit == 1 && dtl_fits(M, N, K)) best.dtl = true;
   return best;
 }
 
 int encode_variant(const TileChoice& t) {
   const bool rect = t.bm != t.bn;
-  return (rect && t.wave_ksplit ? 100000000 : 0) + t.ksplit * 1000000 + t.bm * 1000 + t.bn;
+  return (t.dtl ? 200000000 : rect && t.wave_ksplit ? 100000000 : 0) + t.ksplit * 1000000 + t.bm * 1000 + t.bn;
 }
 // variant -> TileChoice; false if no such instantiation exists or the k slices do not fit the problem / workspace
 bool decode_variant(int variant, int M, int N, int K, size_t ws_bytes, TileChoice* t) {
   if (variant <= 0) return false;
   const int wk = variant / 100000000, S = variant / 1000000 % 100, bm = variant / 1000 % 1000, bn = variant % 1000;
   const bool square = (bm == 256 && bn == 256) || (bm == 128 && bn == 128), rect = (bm == 256 && bn == 128) || (bm == 128 && bn == 256);
+  if (wk == 2) {  // direct-to-LDS kernel: whole 256 x 256 tiles, no k slices
+    if (bm != 256 || bn != 256 || S != 1 || !dtl_fits(M, N, K)) return false;
+    *t = TileChoice{256, 256, 1, false, true};
+    return true;
+  }
   if (wk > 1 || !(square || rect) || (wk == 1 && !rect) || S < 1 || S > 8) return false;
   if (S > 1) {
     const int k_per = ((K + S - 1) / S + BK - 1) / BK * BK;
@@ -604,6 +886,19 @@ int launch_shape(const GemmArgs& g, float* ws, size_t ws_bytes, int forced_varia
   } else if (!decode_variant(forced_variant, g.M, g.N, g.K, ws ? ws_bytes : 0, &t)) {
     set_error("gemm: variant %d does not exist or does not fit M=%d N=%d K=%d with %zu workspace bytes", forced_variant, g.M, g.N, g.K, ws ? ws_bytes : (size_t)0);
     return OASES_EINVAL;
+  }
+  if (t.dtl) {
+    if constexpr (EPI == EPI_SWIGLU) {
+      set_error("gemm: the direct-to-LDS kernel has no SwiGLU epilogue");
+      return OASES_EINVAL;
+    } else {
+      GemmArgs d = g;
+      d.tiles_m = g.M / 256;
+      d.tiles_n = g.N / 256;
+      hipLaunchKernelGGL((gemm_dtl_kernel<A_KC, B_KC, EPI>), dim3(d.tiles_m * d.tiles_n), dim3(256), 0, s, d);
+      OASES_LAUNCH_CHECK("gemm_dtl_kernel");
+      return 0;
+    }
   }
   if (t.bm == 256 && t.bn == 256) return launch_one<256, 256, 2, 2, 1, A_KC, B_KC, EPI>(g, t.ksplit, ws, s);
   if (!t.wave_ksplit) {

@@ -230,6 +230,45 @@ def test_gemm_every_variant(B, lo, op, variant):
         assert_bf16_close(cb.float(), ref * lo.gelu_grad(pre.float().cpu().double()), 1e-4, 1e-5)
 
 
+@pytest.mark.parametrize("M,N,K", [(256, 256, 32), (512, 768, 96), (768, 256, 4096), (1024, 1024, 1056)])
+@pytest.mark.parametrize("op", ["NN", "NT", "TN"])
+def test_gemm_direct_to_lds_variant(B, lo, op, M, N, K):
+    """The kernel whose tiles arrive by direct-to-LDS loads (variant 2xxxxxxxx: whole 256 x 256 tiles, K % 32 == 0): one to
+    33 k tiles (prologue-only, tail and steady-state paths of its four-stage pipeline), every contraction form, and the
+    epilogues it supports."""
+    variant = 201256256
+    g = gen(M + N + K)
+    a, b = bf16_round(randn(g, M, K)), bf16_round(randn(g, K, N, scale=0.05))
+    ref = a @ b
+    opc = {"NN": B.GEMM_NN, "NT": B.GEMM_NT, "TN": B.GEMM_TN}[op]
+    ad = dev(a if op != "TN" else a.t().contiguous(), torch.bfloat16)
+    bd = dev(b if op != "NT" else b.t().contiguous(), torch.bfloat16)
+    lda, ldb = (K if op != "TN" else M), (N if op != "NT" else K)
+    c = torch.full((M, N), 0.5, dtype=torch.float32, device="cuda")
+    B.check(B.lib.oases_op_gemm_forced(variant, opc, B.EPI_F32, M, N, K, ad.data_ptr(), lda, bd.data_ptr(), ldb, c.data_ptr(), N, None, None, 0,
+                                       None, 0, None))
+    assert rel_err(c, ref + (0.5 if op == "TN" else 0.0)) < 1e-5, (op, M, N, K)
+    if op == "TN":
+        return
+    bias = dev(0.1 * randn(g, N), torch.float32)
+    pre = dev(bf16_round(randn(g, M, N)), torch.bfloat16)
+    cb = torch.empty(M, N, dtype=torch.bfloat16, device="cuda")
+    if op == "NN":
+        aux = torch.empty(M, N, dtype=torch.bfloat16, device="cuda")
+        B.check(B.lib.oases_op_gemm_forced(variant, opc, B.EPI_BIAS_GELU, M, N, K, ad.data_ptr(), lda, bd.data_ptr(), ldb, cb.data_ptr(), N,
+                                           bias.data_ptr(), aux.data_ptr(), N, None, 0, None))
+        z = ref + bias.cpu().double()
+        assert_bf16_close(aux.float(), z, 1e-5, 2e-6 * float(z.abs().max()))
+        assert_bf16_close(cb.float(), lo.gelu_fwd(z), 1e-4, 1e-5)
+    else:
+        B.check(B.lib.oases_op_gemm_forced(variant, opc, B.EPI_DGELU, M, N, K, ad.data_ptr(), lda, bd.data_ptr(), ldb, cb.data_ptr(), N,
+                                           None, pre.data_ptr(), N, None, 0, None))
+        assert_bf16_close(cb.float(), ref * lo.gelu_grad(pre.float().cpu().double()), 1e-4, 1e-5)
+    # shapes it does not cover are refused on the host
+    assert B.lib.oases_op_gemm_forced(variant, opc, B.EPI_F32, M - 8, N, K, ad.data_ptr(), lda, bd.data_ptr(), ldb, c.data_ptr(), N, None, None, 0,
+                                      None, 0, None) == B.EINVAL
+
+
 def test_gemm_forced_variant_errors(B):
     """Variants that do not exist, k slices that do not fit K or the workspace: EINVAL before any launch."""
     M = N = K = 256
