@@ -758,6 +758,191 @@ __global__ __launch_bounds__(256) void gemm_dtl_kernel(GemmArgs g) {
     for (int j = 0; j < TN; j++) emit(i, j, acc[i][j]);
 }
 
+// =================================================================================================
+// 128 x 256 tiles of the TN form (weight gradients: both operands stored [k][rows], fp32 accumulate into C), fed by
+// direct-to-LDS loads.  Three LDS stages of 64 k rows (48 KB each); the two wave pairs split the four 16-wide k steps
+// of a stage between them, so a wave keeps the 128 x 128 accumulator of the square kernel (same LDS bytes read per
+// MFMA) while the launch has twice as many workgroups; the two partial sums of a part meet once, through LDS, after
+// the k loop.  Waits as in the kernel above; a wave issues 12 DMA instructions per tile (4 of A, 8 of B).
+// Whole tiles only: M % 128 == 0, N % 256 == 0, K % 64 == 0.
+// =================================================================================================
+constexpr int BKR = 64, NSR = 3;
+constexpr int kRectA = BKR * 128 * 2, kRectB = BKR * 256 * 2, kRectStage = kRectA + kRectB;
+
+// [k][R rows] tile, k row = 2R bytes, chunk c of k row kr at slot c ^ 4*(kr%4); one DMA instruction covers 512/R k rows
+template <int R>
+__device__ __forceinline__ const char* dtl_src_rows(const uint16_t* base, int ld, int r0, int q, int lane) {
+  constexpr int CPR = R / 8, KPI = 64 / CPR;
+  const int kr = KPI * q + lane / CPR, cc = (lane % CPR) ^ (4 * (kr & 3));
+  return reinterpret_cast<const char*>(base + (size_t)kr * ld + r0 + cc * 8);
+}
+// per-lane offsets of the four fragments of a wave's 128-row part starting at tile row R0, first k step of the tile
+template <int R>
+__device__ __forceinline__ void dtl_frag_offsets_rows(uint32_t* off, int R0, int lane) {
+  const int krow = 8 * (lane >> 5) + ((lane & 15) >> 2);
+#pragma unroll
+  for (int i = 0; i < 4; i++) {
+    const int col = R0 + 32 * i + 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
+    off[i] = (uint32_t)(krow * (2 * R) + (((col >> 3) ^ (4 * (krow & 3))) << 4) + (col & 7) * 2);
+  }
+}
+// fragments of 16-wide k step KK (counted from the k row the offsets start at)
+template <int R, int KK>
+__device__ __forceinline__ void dtl_read_frags_rows(u32x4 (&f)[4], uint32_t base, const uint32_t* off) {
+#pragma unroll
+  for (int i = 0; i < 4; i++) {
+    const u32x2 lo = lds_read_tr16_b64<KK * 16 * 2 * R>(base + off[i]);
+    const u32x2 hi = lds_read_tr16_b64<KK * 16 * 2 * R + 4 * 2 * R>(base + off[i]);
+    f[i] = u32x4{lo[0], lo[1], hi[0], hi[1]};
+  }
+}
+
+__global__ __launch_bounds__(256) void gemm_dtl_wgrad_kernel(GemmArgs g) {
+  constexpr int kExchange = 128 * 256 * 4;
+  __shared__ __attribute__((aligned(1024))) char lds[NSR * kRectStage > kExchange ? NSR * kRectStage : kExchange];
+  int tile_m, tile_n;
+  {
+    const int T = g.tiles_m * g.tiles_n, pid = blockIdx.x;
+    const int per = (T + 7) / 8, tall = (T % 8 == 0) ? 8 : T % 8;
+    int xcd = pid & 7, local = pid >> 3;
+    int logical = xcd < tall ? xcd * per + local : tall * per + (xcd - tall) * (per - 1) + local;
+    constexpr int GM = 8;
+    int width = GM * g.tiles_n;
+    int group = logical / width, first_m = group * GM;
+    int gsz = min(g.tiles_m - first_m, GM);
+    tile_m = first_m + (logical % width) % gsz;
+    tile_n = (logical % width) / gsz;
+  }
+  const int m0 = tile_m * 128, n0 = tile_n * 256;
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6), wn = wave & 1, wk = wave >> 1;
+  constexpr int TM = 4, TN = 4;
+  const int nk = g.K / BKR;
+
+  f32x16 acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; i++)
+#pragma unroll
+    for (int j = 0; j < TN; j++)
+#pragma unroll
+      for (int e = 0; e < 16; e++) acc[i][j][e] = 0.f;
+
+  // this wave's DMA instructions of a tile: A instructions 4*wave..4*wave+3 (4 k rows each), B instructions
+  // 8*wave..8*wave+7 (2 k rows each; the swizzle depends on the parity of the instruction: two source pointers)
+  const char* srcA = dtl_src_rows<128>(g.A, g.lda, m0, 4 * wave, lane);
+  const char* srcB[2] = {dtl_src_rows<256>(g.B, g.ldb, n0, 8 * wave, lane), dtl_src_rows<256>(g.B, g.ldb, n0, 8 * wave + 1, lane)};
+  const size_t stepA_q = (size_t)4 * g.lda * 2, stepB_q = (size_t)4 * g.ldb * 2;  // next instruction (A) / next but one (B)
+  const size_t stepA_k = (size_t)BKR * g.lda * 2, stepB_k = (size_t)BKR * g.ldb * 2;
+  typedef const void __attribute__((address_space(1))) * gptr_t;
+  typedef void OASES_LDS* lptr_t;
+  auto issue = [&](int t) {
+    char* st = lds + (t % NSR) * kRectStage;
+#pragma unroll
+    for (int j = 0; j < 4; j++) {
+      __builtin_amdgcn_global_load_lds((gptr_t)(srcA + (size_t)t * stepA_k + j * stepA_q), (lptr_t)(st + (4 * wave + j) * 1024), 16, 0, 0);
+      __builtin_amdgcn_global_load_lds((gptr_t)(srcB[0] + (size_t)t * stepB_k + j * stepB_q), (lptr_t)(st + kRectA + (8 * wave + 2 * j) * 1024), 16, 0, 0);
+      __builtin_amdgcn_global_load_lds((gptr_t)(srcB[1] + (size_t)t * stepB_k + j * stepB_q), (lptr_t)(st + kRectA + (8 * wave + 2 * j + 1) * 1024), 16, 0, 0);
+    }
+  };
+
+  uint32_t offA[4], offB[4];
+  dtl_frag_offsets_rows<128>(offA, 0, lane);
+  dtl_frag_offsets_rows<256>(offB, wn * 128, lane);
+  // k rows 32*wk .. 32*wk+31 of every tile are this wave's
+  const uint32_t lds0 = (uint32_t)(uintptr_t)(OASES_LDS char*)lds;
+  const uint32_t halfA = wk * 32 * 256, halfB = kRectA + wk * 32 * 512;
+  u32x4 fa[2][4], fb[2][4];
+  auto mma = [&](int buf) {
+#pragma unroll
+    for (int i = 0; i < TM; i++)
+#pragma unroll
+      for (int j = 0; j < TN; j++) {
+        const bf16x8 a = __builtin_bit_cast(bf16x8, fa[buf][i]), b = __builtin_bit_cast(bf16x8, fb[buf][j]);
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b, a, acc[i][j], 0, 0, 0);
+      }
+  };
+  constexpr int kYoung = 12 * (NSR - 2);  // DMA instructions of the younger tiles that may still be in flight
+  constexpr int kVmSteady = ((kYoung >> 4) << 14) | (kYoung & 15) | (7 << 4) | (15 << 8), kVm0 = (7 << 4) | (15 << 8);
+  constexpr int NR = 15;  // 16 reads per k step; the counter saturates at 15
+
+#pragma unroll
+  for (int t = 0; t < NSR - 1; t++)
+    if (t < nk) issue(t);
+  if (nk > NSR - 2) __builtin_amdgcn_s_waitcnt(kVmSteady); else __builtin_amdgcn_s_waitcnt(kVm0);
+  __builtin_amdgcn_s_barrier();
+  dtl_read_frags_rows<128, 0>(fa[0], lds0 + halfA, offA);
+  dtl_read_frags_rows<256, 0>(fb[0], lds0 + halfB, offB);
+
+  uint32_t cur = lds0;
+  auto iteration = [&](auto steady_c, auto next_c, int kt) {
+    constexpr bool STEADY = decltype(steady_c)::value, NEXT = decltype(next_c)::value;
+    const uint32_t nxt = cur + kRectStage == lds0 + NSR * kRectStage ? lds0 : cur + kRectStage;
+    dtl_read_frags_rows<128, 1>(fa[1], cur + halfA, offA);
+    dtl_read_frags_rows<256, 1>(fb[1], cur + halfB, offB);
+    lds_wait<NR>(fa[0], fb[0]);
+    if (STEADY) issue(kt + NSR - 1);  // into the stage of tile kt-1, which every wave left before the last barrier
+    mma(0);
+    if (NEXT) {
+      if (STEADY) __builtin_amdgcn_s_waitcnt(kVmSteady); else __builtin_amdgcn_s_waitcnt(kVm0);  // own part of tile kt+1 has landed
+      __builtin_amdgcn_s_barrier();
+      dtl_read_frags_rows<128, 0>(fa[0], nxt + halfA, offA);
+      dtl_read_frags_rows<256, 0>(fb[0], nxt + halfB, offB);
+      lds_wait<NR>(fa[1], fb[1]);
+    } else {
+      lds_wait<0>(fa[1], fb[1]);
+    }
+    mma(1);
+    cur = nxt;
+  };
+  {
+    using T_ = std::true_type;
+    using F_ = std::false_type;
+    int kt = 0;
+    for (; kt + NSR - 1 < nk; kt++) iteration(T_{}, T_{}, kt);
+    for (; kt + 1 < nk; kt++) iteration(F_{}, T_{}, kt);
+    iteration(F_{}, F_{}, kt);
+  }
+
+  // The two waves that hold the k halves of one 128 x 128 part each finish 64 of its rows: a wave hands the accumulator
+  // tiles of the other 64 rows over through LDS (lane for lane) and adds what it receives to its own.
+  constexpr int HM = TM / 2;
+  f32x4* xch = reinterpret_cast<f32x4*>(lds);
+  const int mine = wave * (HM * TN * 4), theirs = (wave ^ 2) * (HM * TN * 4);
+  __syncthreads();  // every wave is done with the operand stages (all DMA has landed: the last tile was waited for)
+  auto hand_over = [&](auto half_c) {
+    constexpr int H = decltype(half_c)::value;
+#pragma unroll
+    for (int i = 0; i < HM; i++)
+#pragma unroll
+      for (int j = 0; j < TN; j++)
+#pragma unroll
+        for (int q = 0; q < 4; q++) {
+          const f32x16& a = acc[H * HM + i][j];
+          xch[(mine + (i * TN + j) * 4 + q) * 64 + lane] = f32x4{a[4 * q], a[4 * q + 1], a[4 * q + 2], a[4 * q + 3]};
+        }
+  };
+  auto finish = [&](auto half_c) {
+    constexpr int H = decltype(half_c)::value;
+#pragma unroll
+    for (int i = 0; i < HM; i++)
+#pragma unroll
+      for (int j = 0; j < TN; j++) {
+        // element e of tile (i,j): C[m0 + 32 i + (lane & 31)][n0 + 128 wn + 32 j + 8 (e>>2) + 4 (lane>>5) + (e&3)]
+        const f32x16& a = acc[H * HM + i][j];
+        const int row = m0 + (H * HM + i) * 32 + (lane & 31);
+#pragma unroll
+        for (int q = 0; q < 4; q++) {
+          const f32x4 o = xch[(theirs + (i * TN + j) * 4 + q) * 64 + lane];
+          const int col = n0 + wn * 128 + j * 32 + 8 * q + 4 * (lane >> 5);
+          f32x4* p = reinterpret_cast<f32x4*>(reinterpret_cast<float*>(g.C) + (size_t)row * g.ldc + col);
+          *p = *p + (f32x4{a[4 * q], a[4 * q + 1], a[4 * q + 2], a[4 * q + 3]} + o);
+        }
+      }
+  };
+  if (wk == 0) hand_over(std::integral_constant<int, 1>{}); else hand_over(std::integral_constant<int, 0>{});
+  __syncthreads();
+  if (wk == 0) finish(std::integral_constant<int, 0>{}); else finish(std::integral_constant<int, 1>{});
+}
+
 // split-K second pass: C = epilogue(sum over slices of the fp32 partial planes), slices added in index order
 template <int EPI>
 __global__ __launch_bounds__(256) void splitk_fixup_kernel(const float* __restrict__ part, int S, GemmArgs g) {
@@ -828,6 +1013,7 @@ struct TileChoice { int bm, bn, ksplit; bool wave_ksplit; bool dtl = false; };
 // per kind of contraction (0: NN, 1: NT, 2: TN, 3: NN with the bias+GeLU epilogue): whether the rectangular tiles
 // split k between waves, and the sustained rates of the four block tiles
 bool dtl_fits(int M, int N, int K) { return M % 256 == 0 && N % 256 == 0 && K % BKD == 0 && K >= BKD; }
+bool dtl_wgrad_fits(int M, int N, int K) { return M % 128 == 0 && N % 256 == 0 && K % BKR == 0 && K >= BKR; }
 struct KindTable { bool wave_ksplit; float r256x256, r128x256, r256x128, r128x128; };
 const KindTable g_kinds[4] = {{true, 1150.f, 1000.f, 960.f, 740.f}, {true, 1150.f, 1000.f, 960.f, 740.f},
                         {true, 1150.f, 1000.f, 960.f, 740.f}, {false, 1150.f, 880.f, 900.f, 740.f}};
@@ -849,7 +1035,8 @@ TileChoice pick_tile(int kind, int M, int N, int K, size_t ws_bytes) {
   }
   // TN with whole 256 x 256 tiles: the direct-to-LDS kernel is the faster one (both operands go through the
   // transposing LDS reads, which the staged kernel pays for with bank conflicts on its stores)
-  if (kind == 2 && best.bm == 256 && best.bn == 256 && best.ksplit == 1 && dtl_fits(M, N, K)) best.dtl = true;
+  if ((kind == 2 || kind == 0) && best.bm == 256 && best.bn == 256 && best.ksplit == 1 && dtl_fits(M, N, K)) best.dtl = true;
+  if (kind == 2 && best.bm == 128 && best.bn == 256 && best.ksplit == 1 && dtl_wgrad_fits(M, N, K)) { best.dtl = true; best.wave_ksplit = true; }
   return best;
 }
 
@@ -862,10 +1049,11 @@ bool decode_variant(int variant, int M, int N, int K, size_t ws_bytes, TileChoic
   if (variant <= 0) return false;
   const int wk = variant / 100000000, S = variant / 1000000 % 100, bm = variant / 1000 % 1000, bn = variant % 1000;
   const bool square = (bm == 256 && bn == 256) || (bm == 128 && bn == 128), rect = (bm == 256 && bn == 128) || (bm == 128 && bn == 256);
-  if (wk == 2) {  // direct-to-LDS kernel: whole 256 x 256 tiles, no k slices
-    if (bm != 256 || bn != 256 || S != 1 || !dtl_fits(M, N, K)) return false;
-    *t = TileChoice{256, 256, 1, false, true};
-    return true;
+  if (wk == 2) {  // direct-to-LDS kernels: whole 256 x 256 tiles, or 128 x 256 tiles of the TN form; no k slices
+    if (S != 1) return false;
+    if (bm == 256 && bn == 256 && dtl_fits(M, N, K)) { *t = TileChoice{256, 256, 1, false, true}; return true; }
+    if (bm == 128 && bn == 256 && dtl_wgrad_fits(M, N, K)) { *t = TileChoice{128, 256, 1, true, true}; return true; }
+    return false;
   }
   if (wk > 1 || !(square || rect) || (wk == 1 && !rect) || S < 1 || S > 8) return false;
   if (S > 1) {
@@ -886,6 +1074,19 @@ int launch_shape(const GemmArgs& g, float* ws, size_t ws_bytes, int forced_varia
   } else if (!decode_variant(forced_variant, g.M, g.N, g.K, ws ? ws_bytes : 0, &t)) {
     set_error("gemm: variant %d does not exist or does not fit M=%d N=%d K=%d with %zu workspace bytes", forced_variant, g.M, g.N, g.K, ws ? ws_bytes : (size_t)0);
     return OASES_EINVAL;
+  }
+  if (t.dtl && t.bm == 128) {
+    if constexpr (!A_KC && !B_KC && EPI == EPI_ACC_F32) {
+      GemmArgs d = g;
+      d.tiles_m = g.M / 128;
+      d.tiles_n = g.N / 256;
+      hipLaunchKernelGGL(gemm_dtl_wgrad_kernel, dim3(d.tiles_m * d.tiles_n), dim3(256), 0, s, d);
+      OASES_LAUNCH_CHECK("gemm_dtl_wgrad_kernel");
+      return 0;
+    } else {
+      set_error("gemm: the 128x256 direct-to-LDS kernel exists for the TN form only");
+      return OASES_EINVAL;
+    }
   }
   if (t.dtl) {
     if constexpr (EPI == EPI_SWIGLU) {

@@ -269,6 +269,31 @@ def test_gemm_direct_to_lds_variant(B, lo, op, M, N, K):
                                       None, 0, None) == B.EINVAL
 
 
+@pytest.mark.parametrize("M,N,K", [(128, 256, 64), (384, 512, 128), (256, 768, 192), (640, 256, 4096), (1152, 1024, 1088)])
+def test_gemm_direct_to_lds_wgrad_variant(B, M, N, K):
+    """The weight-gradient kernel with 128 x 256 tiles fed by direct-to-LDS loads (variant 201128256; TN form, whole tiles,
+    K % 64 == 0): one to 64 k tiles (prologue-only, drain and steady-state paths of its three-stage pipeline), odd and
+    even tile counts, accumulation into a non-zero C with a padded leading dimension."""
+    variant = 201128256
+    g = gen(M + N + K)
+    a, b = bf16_round(randn(g, M, K)), bf16_round(randn(g, K, N, scale=0.05))
+    ref = a @ b
+    ad, bd = dev(a.t().contiguous(), torch.bfloat16), dev(b, torch.bfloat16)
+    ldc = N + 64
+    c0 = randn(g, M, ldc).float()
+    c = dev(c0, torch.float32)
+    B.check(B.lib.oases_op_gemm_forced(variant, B.GEMM_TN, B.EPI_F32, M, N, K, ad.data_ptr(), M, bd.data_ptr(), N, c.data_ptr(), ldc, None, None, 0,
+                                       None, 0, None))
+    out = c.cpu().double()
+    assert rel_err(out[:, :N], ref + c0[:, :N].double()) < 1e-5, (M, N, K)
+    assert torch.equal(out[:, N:], c0[:, N:].double())  # the padding columns of C are not touched
+    # other forms and shapes it does not cover are refused on the host
+    assert B.lib.oases_op_gemm_forced(variant, B.GEMM_NN, B.EPI_F32, M, N, K, ad.data_ptr(), K, bd.data_ptr(), N, c.data_ptr(), ldc, None, None, 0,
+                                      None, 0, None) == B.EINVAL
+    assert B.lib.oases_op_gemm_forced(variant, B.GEMM_TN, B.EPI_F32, M, N, K - 32, ad.data_ptr(), M, bd.data_ptr(), N, c.data_ptr(), ldc, None, None, 0,
+                                      None, 0, None) == B.EINVAL
+
+
 def test_gemm_forced_variant_errors(B):
     """Variants that do not exist, k slices that do not fit K or the workspace: EINVAL before any launch."""
     M = N = K = 256
