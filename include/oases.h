@@ -254,14 +254,15 @@ int oases_op_gemm(int op, int epi, int M, int N, int K, const void *A, int lda, 
 /* Which kernel instantiation oases_op_gemm launches for a problem given workspace_bytes of split-K scratch:
  * returns 100000000*W + 1000000*slices + 1000*BM + BN, or EINVAL.  BM x BN: block tile; slices: k slices with fp32
  * partial planes in the workspace; W = 1 if the waves of a workgroup split the k steps of a stage between them
- * (rectangular tiles only), e.g. 101128256 = 128x256 tiles, waves split k, one slice; W = 2 names the kernel that
- * loads its operand tiles from global memory straight into LDS (256x256 tiles, four LDS stages of 32 k columns; one
- * slice; needs M % 256 == 0, N % 256 == 0, K % 32 == 0; no SwiGLU epilogue), i.e. 201256256.
+ * (rectangular tiles only), e.g. 101128256 = 128x256 tiles, waves split k, one slice; W = 2 names the kernels that
+ * load their operand tiles from global memory straight into LDS: 201256256 (256x256 tiles, four LDS stages of 32 k
+ * columns; needs M % 256 == 0, N % 256 == 0, K % 32 == 0) and 201128256 (128x256 tiles, three LDS stages of 64 k columns,
+ * waves split k; needs M % 128 == 0, N % 256 == 0, K % 64 == 0); one slice; no SwiGLU epilogue.
  * Host only; used to group per-operator timings by kernel. */
 int oases_op_gemm_variant(int op, int epi, int M, int N, int K, size_t workspace_bytes);
 /* oases_op_gemm on the instantiation `variant` names (encoding above) instead of the one the library would choose:
  * for tests and tuning sweeps.  EINVAL if no such instantiation exists (block tiles 256x256, 128x256, 256x128,
- * 128x128; W = 1 only with the rectangular ones; W = 2 only as 201256256 on shapes it fits; 1..8 slices), if the slices do not fit K (every slice needs at least
+ * 128x128; W = 1 only with the rectangular ones; W = 2 only as 201256256 or 201128256 on shapes they fit; 1..8 slices), if the slices do not fit K (every slice needs at least
  * one k column) or if the workspace is smaller than slices*M*N*4 bytes.  Results of different variants differ only
  * by the fp32 summation order. */
 int oases_op_gemm_forced(int variant, int op, int epi, int M, int N, int K, const void *A, int lda,

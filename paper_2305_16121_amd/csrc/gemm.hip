@@ -116,6 +116,95 @@ __device__ __forceinline__ float silu_grad_f(float z) { const float sg = fast_si
 // instruction-group hints for the machine scheduler (kinds: 0x8 MFMA, 0x20 VMEM read, 0x100 LDS read, 0x200 LDS write)
 #define SGB(mask, n) __builtin_amdgcn_sched_group_barrier(mask, n, 0)
 
+// Epilogue of one 32 x 32 accumulator tile whose first element is C[row0][col0].  Transposed accumulator (every epilogue
+// but the plain fp32 store): element e is C[row][col + (e&3)] with row = row0 + (lane & 31), col = col0 + 8 (e>>2) +
+// 4 (lane>>5), so a lane owns 4 consecutive columns.
+template <int EPI, bool FULL>
+__device__ __forceinline__ void epilogue_tile(const GemmArgs& g, int row0, int col0, int lane, const f32x16& a) {
+  if constexpr (EPI == EPI_F32) {
+    // element e is C[row0 + 8 (e>>2) + 4 (lane>>5) + (e&3)][col], col = lane & 31 of the tile
+    const int col = col0 + (lane & 31);
+    if (!FULL && col >= g.N) return;
+    float* cbase = reinterpret_cast<float*>(g.C) + col;
+#pragma unroll
+    for (int e = 0; e < 16; e++) {
+      const int row = row0 + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
+      if (!FULL && row >= g.M) continue;
+      float* p = cbase + (size_t)row * g.ldc;
+      *p = a[e];
+    }
+    return;
+  }
+  const int row = row0 + (lane & 31);
+  if (!FULL && row >= g.M) return;
+#pragma unroll
+  for (int q = 0; q < 4; q++) {
+    const int col = col0 + 8 * q + 4 * (lane >> 5);
+    if (!FULL && col >= g.N) continue;
+    f32x4 v = {a[4 * q], a[4 * q + 1], a[4 * q + 2], a[4 * q + 3]};
+    const size_t o = (size_t)row * g.ldc + col;
+    if (EPI == EPI_DSWIGLU) {
+      // the accumulator holds dF for 4 columns of f; gate and up pre-activations of those columns sit in 32-column
+      // blocks side by side in aux ([gate 32 | up 32] per block), and so do their gradients in C
+      const size_t cg = (size_t)col + (col & ~31);
+      const u32x2 gt = *reinterpret_cast<const u32x2*>(g.aux + (size_t)row * g.ldaux + cg);
+      const u32x2 up = *reinterpret_cast<const u32x2*>(g.aux + (size_t)row * g.ldaux + cg + 32);
+      float dg[4], du[4];
+#pragma unroll
+      for (int e = 0; e < 4; e++) {
+        const float ge = bf16_bits_to_f32((e & 1) ? gt[e >> 1] >> 16 : gt[e >> 1] & 0xffffu);
+        const float ue = bf16_bits_to_f32((e & 1) ? up[e >> 1] >> 16 : up[e >> 1] & 0xffffu);
+        dg[e] = v[e] * ue * silu_grad_f(ge);
+        du[e] = v[e] * silu_f(ge);
+      }
+      uint16_t* cp = reinterpret_cast<uint16_t*>(g.C) + (size_t)row * g.ldc + cg;
+      *reinterpret_cast<u32x2*>(cp) = u32x2{pack_bf16x2(dg[0], dg[1]), pack_bf16x2(dg[2], dg[3])};
+      *reinterpret_cast<u32x2*>(cp + 32) = u32x2{pack_bf16x2(du[0], du[1]), pack_bf16x2(du[2], du[3])};
+    } else if (EPI == EPI_F32) {
+      *reinterpret_cast<f32x4*>(reinterpret_cast<float*>(g.C) + o) = v;
+    } else if (EPI == EPI_ACC_F32) {
+      f32x4* p = reinterpret_cast<f32x4*>(reinterpret_cast<float*>(g.C) + o);
+      *p = *p + v;
+    } else {
+      uint16_t* cp = reinterpret_cast<uint16_t*>(g.C) + o;
+      if (EPI == EPI_BIAS_BF16 || EPI == EPI_BIAS_GELU) v += *reinterpret_cast<const f32x4*>(g.bias + col);
+      if (EPI == EPI_BIAS_GELU) {
+        *reinterpret_cast<u32x2*>(g.aux + (size_t)row * g.ldaux + col) = u32x2{pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3])};
+#pragma unroll
+        for (int e = 0; e < 4; e++) v[e] = gelu_tanh(v[e]);
+      } else if (EPI == EPI_DGELU) {
+        u32x2 x = *reinterpret_cast<const u32x2*>(g.aux + (size_t)row * g.ldaux + col);
+        v[0] *= gelu_tanh_grad(bf16_bits_to_f32(x[0] & 0xffffu));
+        v[1] *= gelu_tanh_grad(bf16_bits_to_f32(x[0] >> 16));
+        v[2] *= gelu_tanh_grad(bf16_bits_to_f32(x[1] & 0xffffu));
+        v[3] *= gelu_tanh_grad(bf16_bits_to_f32(x[1] >> 16));
+      }
+      *reinterpret_cast<u32x2*>(cp) = u32x2{pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3])};
+    }
+  }
+}
+
+// SwiGLU: two neighbouring accumulator tiles, gate (first column col0 of the interleaved [gate 32 | up 32] layout) and up,
+// hold the same 32 columns of f, element for element
+template <bool FULL>
+__device__ __forceinline__ void epilogue_tile_swiglu(const GemmArgs& g, int row0, int col0, int lane, const f32x16& ag, const f32x16& au) {
+  const int row = row0 + (lane & 31);
+  if (!FULL && row >= g.M) return;
+#pragma unroll
+  for (int q = 0; q < 4; q++) {
+    const int cg = col0 + 8 * q + 4 * (lane >> 5);  // gate column in the interleaved [gate 32 | up 32] layout
+    if (!FULL && cg >= g.N) continue;
+    const int cf = col0 / 2 + 8 * q + 4 * (lane >> 5);
+    uint16_t* ap = g.aux + (size_t)row * g.ldaux + cg;
+    *reinterpret_cast<u32x2*>(ap) = u32x2{pack_bf16x2(ag[4 * q], ag[4 * q + 1]), pack_bf16x2(ag[4 * q + 2], ag[4 * q + 3])};
+    *reinterpret_cast<u32x2*>(ap + 32) = u32x2{pack_bf16x2(au[4 * q], au[4 * q + 1]), pack_bf16x2(au[4 * q + 2], au[4 * q + 3])};
+    float f[4];
+#pragma unroll
+    for (int e = 0; e < 4; e++) f[e] = silu_f(ag[4 * q + e]) * au[4 * q + e];
+    *reinterpret_cast<u32x2*>(reinterpret_cast<uint16_t*>(g.C) + (size_t)row * g.ldc + cf) = u32x2{pack_bf16x2(f[0], f[1]), pack_bf16x2(f[2], f[3])};
+  }
+}
+
 // Waves of a workgroup form a WGM x WGN x WGK grid: a wave owns a (BM/WGM) x (BN/WGN) part of the block tile and,
 // when WGK > 1, every WGK-th pair of the 16-wide k steps of each stage; the WGK partial accumulators of a part are
 // added through LDS after the k loop, in a fixed order.  Splitting k inside the workgroup instead of the tile keeps
@@ -299,89 +388,9 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, char* lds, int m0, 
     iteration(F_{}, F_{}, kt);
   }
 
-  // epilogue of one 32 x 32 accumulator tile (i,j) of this wave: element e is C[row][col + (e&3)] with
-  //   row = m0 + wm*WTM + 32 i + (lane & 31),  col = n0 + wn*WTN + 32 j + 8 (e>>2) + 4 (lane>>5)
-  auto emit = [&](int i, int j, const f32x16& a) {
-    if constexpr (ROWMAJ) {
-      // element e is C[row0 + 8 (e>>2) + 4 (lane>>5) + (e&3)][col], col = lane & 31 of the tile
-      const int col = n0 + wn * WTN + j * 32 + (lane & 31);
-      if (!FULL && col >= g.N) return;
-      float* cbase = reinterpret_cast<float*>(g.C) + col;
-#pragma unroll
-      for (int e = 0; e < 16; e++) {
-        const int row = m0 + wm * WTM + i * 32 + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
-        if (!FULL && row >= g.M) continue;
-        float* p = cbase + (size_t)row * g.ldc;
-        *p = a[e];
-      }
-      return;
-    }
-    const int row = m0 + wm * WTM + i * 32 + (lane & 31);
-    if (!FULL && row >= g.M) return;
-#pragma unroll
-    for (int q = 0; q < 4; q++) {
-      const int col = n0 + wn * WTN + j * 32 + 8 * q + 4 * (lane >> 5);
-      if (!FULL && col >= g.N) continue;
-      f32x4 v = {a[4 * q], a[4 * q + 1], a[4 * q + 2], a[4 * q + 3]};
-      const size_t o = (size_t)row * g.ldc + col;
-      if (EPI == EPI_DSWIGLU) {
-        // the accumulator holds dF for 4 columns of f; gate and up pre-activations of those columns sit in 32-column
-        // blocks side by side in aux ([gate 32 | up 32] per block), and so do their gradients in C
-        const size_t cg = (size_t)col + (col & ~31);
-        const u32x2 gt = *reinterpret_cast<const u32x2*>(g.aux + (size_t)row * g.ldaux + cg);
-        const u32x2 up = *reinterpret_cast<const u32x2*>(g.aux + (size_t)row * g.ldaux + cg + 32);
-        float dg[4], du[4];
-#pragma unroll
-        for (int e = 0; e < 4; e++) {
-          const float ge = bf16_bits_to_f32((e & 1) ? gt[e >> 1] >> 16 : gt[e >> 1] & 0xffffu);
-          const float ue = bf16_bits_to_f32((e & 1) ? up[e >> 1] >> 16 : up[e >> 1] & 0xffffu);
-          dg[e] = v[e] * ue * silu_grad_f(ge);
-          du[e] = v[e] * silu_f(ge);
-        }
-        uint16_t* cp = reinterpret_cast<uint16_t*>(g.C) + (size_t)row * g.ldc + cg;
-        *reinterpret_cast<u32x2*>(cp) = u32x2{pack_bf16x2(dg[0], dg[1]), pack_bf16x2(dg[2], dg[3])};
-        *reinterpret_cast<u32x2*>(cp + 32) = u32x2{pack_bf16x2(du[0], du[1]), pack_bf16x2(du[2], du[3])};
-      } else if (EPI == EPI_F32) {
-        *reinterpret_cast<f32x4*>(reinterpret_cast<float*>(g.C) + o) = v;
-      } else if (EPI == EPI_ACC_F32) {
-        f32x4* p = reinterpret_cast<f32x4*>(reinterpret_cast<float*>(g.C) + o);
-        *p = *p + v;
-      } else {
-        uint16_t* cp = reinterpret_cast<uint16_t*>(g.C) + o;
-        if (EPI == EPI_BIAS_BF16 || EPI == EPI_BIAS_GELU) v += *reinterpret_cast<const f32x4*>(g.bias + col);
-        if (EPI == EPI_BIAS_GELU) {
-          *reinterpret_cast<u32x2*>(g.aux + (size_t)row * g.ldaux + col) = u32x2{pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3])};
-#pragma unroll
-          for (int e = 0; e < 4; e++) v[e] = gelu_tanh(v[e]);
-        } else if (EPI == EPI_DGELU) {
-          u32x2 x = *reinterpret_cast<const u32x2*>(g.aux + (size_t)row * g.ldaux + col);
-          v[0] *= gelu_tanh_grad(bf16_bits_to_f32(x[0] & 0xffffu));
-          v[1] *= gelu_tanh_grad(bf16_bits_to_f32(x[0] >> 16));
-          v[2] *= gelu_tanh_grad(bf16_bits_to_f32(x[1] & 0xffffu));
-          v[3] *= gelu_tanh_grad(bf16_bits_to_f32(x[1] >> 16));
-        }
-        *reinterpret_cast<u32x2*>(cp) = u32x2{pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3])};
-      }
-    }
-  };
-
-  // SwiGLU: accumulator tiles 2jj (gate) and 2jj+1 (up) of a wave hold the same 32 columns of f, element for element
+  auto emit = [&](int i, int j, const f32x16& a) { epilogue_tile<EPI, FULL>(g, m0 + wm * WTM + i * 32, n0 + wn * WTN + j * 32, lane, a); };
   auto emit_pair = [&](int i, int jj, const f32x16& ag, const f32x16& au) {
-    const int row = m0 + wm * WTM + i * 32 + (lane & 31);
-    if (!FULL && row >= g.M) return;
-#pragma unroll
-    for (int q = 0; q < 4; q++) {
-      const int cg = n0 + wn * WTN + jj * 64 + 8 * q + 4 * (lane >> 5);  // gate column in the interleaved [gate 32 | up 32] layout
-      if (!FULL && cg >= g.N) continue;
-      const int cf = (n0 + wn * WTN) / 2 + jj * 32 + 8 * q + 4 * (lane >> 5);
-      uint16_t* ap = g.aux + (size_t)row * g.ldaux + cg;
-      *reinterpret_cast<u32x2*>(ap) = u32x2{pack_bf16x2(ag[4 * q], ag[4 * q + 1]), pack_bf16x2(ag[4 * q + 2], ag[4 * q + 3])};
-      *reinterpret_cast<u32x2*>(ap + 32) = u32x2{pack_bf16x2(au[4 * q], au[4 * q + 1]), pack_bf16x2(au[4 * q + 2], au[4 * q + 3])};
-      float f[4];
-#pragma unroll
-      for (int e = 0; e < 4; e++) f[e] = silu_f(ag[4 * q + e]) * au[4 * q + e];
-      *reinterpret_cast<u32x2*>(reinterpret_cast<uint16_t*>(g.C) + (size_t)row * g.ldc + cf) = u32x2{pack_bf16x2(f[0], f[1]), pack_bf16x2(f[2], f[3])};
-    }
+    epilogue_tile_swiglu<FULL>(g, m0 + wm * WTM + i * 32, n0 + wn * WTN + jj * 64, lane, ag, au);
   };
 
   static_assert(TN % 2 == 0, "tiles of a wave are finished in pairs");
@@ -685,73 +694,7 @@ __global__ __launch_bounds__(256) void gemm_dtl_kernel(GemmArgs g) {
     for (; kt + 1 < nk; kt++) iteration(F_{}, T_{}, kt);
     iteration(F_{}, F_{}, kt);
   }
-  constexpr bool ROWMAJ = EPI == EPI_F32;
-  // epilogue of one 32 x 32 accumulator tile (i,j) of this wave: element e is C[row][col + (e&3)] with
-  //   row = m0 + wm*WTM + 32 i + (lane & 31),  col = n0 + wn*WTN + 32 j + 8 (e>>2) + 4 (lane>>5)
-  auto emit = [&](int i, int j, const f32x16& a) {
-    if constexpr (ROWMAJ) {
-      // element e is C[row0 + 8 (e>>2) + 4 (lane>>5) + (e&3)][col], col = lane & 31 of the tile
-      const int col = n0 + wn * WTN + j * 32 + (lane & 31);
-      if (!FULL && col >= g.N) return;
-      float* cbase = reinterpret_cast<float*>(g.C) + col;
-#pragma unroll
-      for (int e = 0; e < 16; e++) {
-        const int row = m0 + wm * WTM + i * 32 + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
-        if (!FULL && row >= g.M) continue;
-        float* p = cbase + (size_t)row * g.ldc;
-        *p = a[e];
-      }
-      return;
-    }
-    const int row = m0 + wm * WTM + i * 32 + (lane & 31);
-    if (!FULL && row >= g.M) return;
-#pragma unroll
-    for (int q = 0; q < 4; q++) {
-      const int col = n0 + wn * WTN + j * 32 + 8 * q + 4 * (lane >> 5);
-      if (!FULL && col >= g.N) continue;
-      f32x4 v = {a[4 * q], a[4 * q + 1], a[4 * q + 2], a[4 * q + 3]};
-      const size_t o = (size_t)row * g.ldc + col;
-      if (EPI == EPI_DSWIGLU) {
-        // the accumulator holds dF for 4 columns of f; gate and up pre-activations of those columns sit in 32-column
-        // blocks side by side in aux ([gate 32 | up 32] per block), and so do their gradients in C
-        const size_t cg = (size_t)col + (col & ~31);
-        const u32x2 gt = *reinterpret_cast<const u32x2*>(g.aux + (size_t)row * g.ldaux + cg);
-        const u32x2 up = *reinterpret_cast<const u32x2*>(g.aux + (size_t)row * g.ldaux + cg + 32);
-        float dg[4], du[4];
-#pragma unroll
-        for (int e = 0; e < 4; e++) {
-          const float ge = bf16_bits_to_f32((e & 1) ? gt[e >> 1] >> 16 : gt[e >> 1] & 0xffffu);
-          const float ue = bf16_bits_to_f32((e & 1) ? up[e >> 1] >> 16 : up[e >> 1] & 0xffffu);
-          dg[e] = v[e] * ue * silu_grad_f(ge);
-          du[e] = v[e] * silu_f(ge);
-        }
-        uint16_t* cp = reinterpret_cast<uint16_t*>(g.C) + (size_t)row * g.ldc + cg;
-        *reinterpret_cast<u32x2*>(cp) = u32x2{pack_bf16x2(dg[0], dg[1]), pack_bf16x2(dg[2], dg[3])};
-        *reinterpret_cast<u32x2*>(cp + 32) = u32x2{pack_bf16x2(du[0], du[1]), pack_bf16x2(du[2], du[3])};
-      } else if (EPI == EPI_F32) {
-        *reinterpret_cast<f32x4*>(reinterpret_cast<float*>(g.C) + o) = v;
-      } else if (EPI == EPI_ACC_F32) {
-        f32x4* p = reinterpret_cast<f32x4*>(reinterpret_cast<float*>(g.C) + o);
-        *p = *p + v;
-      } else {
-        uint16_t* cp = reinterpret_cast<uint16_t*>(g.C) + o;
-        if (EPI == EPI_BIAS_BF16 || EPI == EPI_BIAS_GELU) v += *reinterpret_cast<const f32x4*>(g.bias + col);
-        if (EPI == EPI_BIAS_GELU) {
-          *reinterpret_cast<u32x2*>(g.aux + (size_t)row * g.ldaux + col) = u32x2{pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3])};
-#pragma unroll
-          for (int e = 0; e < 4; e++) v[e] = gelu_tanh(v[e]);
-        } else if (EPI == EPI_DGELU) {
-          u32x2 x = *reinterpret_cast<const u32x2*>(g.aux + (size_t)row * g.ldaux + col);
-          v[0] *= gelu_tanh_grad(bf16_bits_to_f32(x[0] & 0xffffu));
-          v[1] *= gelu_tanh_grad(bf16_bits_to_f32(x[0] >> 16));
-          v[2] *= gelu_tanh_grad(bf16_bits_to_f32(x[1] & 0xffffu));
-          v[3] *= gelu_tanh_grad(bf16_bits_to_f32(x[1] >> 16));
-        }
-        *reinterpret_cast<u32x2*>(cp) = u32x2{pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3])};
-      }
-    }
-  };
-
+  auto emit = [&](int i, int j, const f32x16& a) { epilogue_tile<EPI, FULL>(g, m0 + wm * WTM + i * 32, n0 + wn * WTN + j * 32, lane, a); };
 #pragma unroll
   for (int i = 0; i < TM; i++)
 #pragma unroll
@@ -759,45 +702,69 @@ __global__ __launch_bounds__(256) void gemm_dtl_kernel(GemmArgs g) {
 }
 
 // =================================================================================================
-// 128 x 256 tiles of the TN form (weight gradients: both operands stored [k][rows], fp32 accumulate into C), fed by
-// direct-to-LDS loads.  Three LDS stages of 64 k rows (48 KB each); the two wave pairs split the four 16-wide k steps
-// of a stage between them, so a wave keeps the 128 x 128 accumulator of the square kernel (same LDS bytes read per
-// MFMA) while the launch has twice as many workgroups; the two partial sums of a part meet once, through LDS, after
-// the k loop.  Waits as in the kernel above; a wave issues 12 DMA instructions per tile (4 of A, 8 of B).
-// Whole tiles only: M % 128 == 0, N % 256 == 0, K % 64 == 0.
+// 128 x 256 tiles fed by direct-to-LDS loads.  Three LDS stages of 64 k (48 KB each); the two wave pairs split the four
+// 16-wide k steps of a stage between them, so a wave keeps the 128 x 128 accumulator of the square kernel (same LDS
+// bytes read per MFMA) while the launch has twice as many workgroups; the two partial sums of a part meet once,
+// through LDS, after the k loop.  Waits as in the kernel above; a wave issues 12 DMA instructions per tile (4 of A,
+// 8 of B).  Whole tiles only: M % 128 == 0, N % 256 == 0, K % 64 == 0.
+// Operand tile in LDS.  KC: [R rows][64 k] = 128-byte rows, chunk c of row r at slot c ^ ((r/2)%8) (16 consecutive
+// rows at one chunk cover all 64 banks); one DMA instruction covers 8 rows.  MC: [64 k][R rows], k row = 2R bytes,
+// chunk c of k row kr at slot c ^ 4*(kr%4); one DMA instruction covers 512/R k rows.  In both the swizzle of
+// instruction q depends on the parity of q only.
 // =================================================================================================
 constexpr int BKR = 64, NSR = 3;
 constexpr int kRectA = BKR * 128 * 2, kRectB = BKR * 256 * 2, kRectStage = kRectA + kRectB;
 
-// [k][R rows] tile, k row = 2R bytes, chunk c of k row kr at slot c ^ 4*(kr%4); one DMA instruction covers 512/R k rows
-template <int R>
-__device__ __forceinline__ const char* dtl_src_rows(const uint16_t* base, int ld, int r0, int q, int lane) {
+template <bool KC, int R>
+__device__ __forceinline__ const char* rect_src(const uint16_t* base, int ld, int r0, int q, int lane) {
+  if (KC) {
+    const int row = 8 * q + (lane >> 3), chunk = (lane & 7) ^ ((row >> 1) & 7);
+    return reinterpret_cast<const char*>(base + (size_t)(r0 + row) * ld + chunk * 8);
+  }
   constexpr int CPR = R / 8, KPI = 64 / CPR;
   const int kr = KPI * q + lane / CPR, cc = (lane % CPR) ^ (4 * (kr & 3));
   return reinterpret_cast<const char*>(base + (size_t)kr * ld + r0 + cc * 8);
 }
-// per-lane offsets of the four fragments of a wave's 128-row part starting at tile row R0, first k step of the tile
-template <int R>
-__device__ __forceinline__ void dtl_frag_offsets_rows(uint32_t* off, int R0, int lane) {
-  const int krow = 8 * (lane >> 5) + ((lane & 15) >> 2);
+// per-lane LDS offsets of the fragment reads of a wave's 128-row part starting at tile row R0, for the k half wk of a
+// tile.  KC: off[kk], k step kk of the half (fragment i adds 32 rows = 4096 bytes); MC: off[i], fragment i (k step kk
+// adds 16 k rows, the second half of a fragment 4 k rows).
+template <bool KC, int R>
+__device__ __forceinline__ void rect_frag_offsets(uint32_t* off, int R0, int wk, int lane) {
+  if (KC) {
 #pragma unroll
-  for (int i = 0; i < 4; i++) {
-    const int col = R0 + 32 * i + 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
-    off[i] = (uint32_t)(krow * (2 * R) + (((col >> 3) ^ (4 * (krow & 3))) << 4) + (col & 7) * 2);
+    for (int kk = 0; kk < 2; kk++) {
+      const int row = R0 + (lane & 31), chunk = 4 * wk + 2 * kk + (lane >> 5);
+      off[kk] = (uint32_t)(row * 128 + 16 * (chunk ^ ((row >> 1) & 7)));
+    }
+  } else {
+    const int krow = 32 * wk + 8 * (lane >> 5) + ((lane & 15) >> 2);
+#pragma unroll
+    for (int i = 0; i < 4; i++) {
+      const int col = R0 + 32 * i + 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
+      off[i] = (uint32_t)(krow * (2 * R) + (((col >> 3) ^ (4 * (krow & 3))) << 4) + (col & 7) * 2);
+    }
   }
 }
-// fragments of 16-wide k step KK (counted from the k row the offsets start at)
-template <int R, int KK>
-__device__ __forceinline__ void dtl_read_frags_rows(u32x4 (&f)[4], uint32_t base, const uint32_t* off) {
+template <bool KC, int R, int KK>
+__device__ __forceinline__ void rect_read_frags(u32x4 (&f)[4], uint32_t base, const uint32_t* off) {
+  if constexpr (KC) {
+    const uint32_t a = base + off[KK];
+    f[0] = lds_read_b128<0>(a);
+    f[1] = lds_read_b128<4096>(a);
+    f[2] = lds_read_b128<8192>(a);
+    f[3] = lds_read_b128<12288>(a);
+  } else {
 #pragma unroll
-  for (int i = 0; i < 4; i++) {
-    const u32x2 lo = lds_read_tr16_b64<KK * 16 * 2 * R>(base + off[i]);
-    const u32x2 hi = lds_read_tr16_b64<KK * 16 * 2 * R + 4 * 2 * R>(base + off[i]);
-    f[i] = u32x4{lo[0], lo[1], hi[0], hi[1]};
+    for (int i = 0; i < 4; i++) {
+      const u32x2 lo = lds_read_tr16_b64<KK * 16 * 2 * R>(base + off[i]);
+      const u32x2 hi = lds_read_tr16_b64<KK * 16 * 2 * R + 4 * 2 * R>(base + off[i]);
+      f[i] = u32x4{lo[0], lo[1], hi[0], hi[1]};
+    }
   }
 }
 
-__global__ __launch_bounds__(256) void gemm_dtl_wgrad_kernel(GemmArgs g) {
+template <bool A_KC, bool B_KC, int EPI>
+__global__ __launch_bounds__(256) void gemm_dtl_rect_kernel(GemmArgs g) {
   constexpr int kExchange = 128 * 256 * 4;
   __shared__ __attribute__((aligned(1024))) char lds[NSR * kRectStage > kExchange ? NSR * kRectStage : kExchange];
   int tile_m, tile_n;
@@ -826,30 +793,29 @@ __global__ __launch_bounds__(256) void gemm_dtl_wgrad_kernel(GemmArgs g) {
 #pragma unroll
       for (int e = 0; e < 16; e++) acc[i][j][e] = 0.f;
 
-  // this wave's DMA instructions of a tile: A instructions 4*wave..4*wave+3 (4 k rows each), B instructions
-  // 8*wave..8*wave+7 (2 k rows each; the swizzle depends on the parity of the instruction: two source pointers)
-  const char* srcA = dtl_src_rows<128>(g.A, g.lda, m0, 4 * wave, lane);
-  const char* srcB[2] = {dtl_src_rows<256>(g.B, g.ldb, n0, 8 * wave, lane), dtl_src_rows<256>(g.B, g.ldb, n0, 8 * wave + 1, lane)};
-  const size_t stepA_q = (size_t)4 * g.lda * 2, stepB_q = (size_t)4 * g.ldb * 2;  // next instruction (A) / next but one (B)
-  const size_t stepA_k = (size_t)BKR * g.lda * 2, stepB_k = (size_t)BKR * g.ldb * 2;
+  // this wave's DMA instructions of a tile: A instructions 4*wave .. 4*wave+3, B instructions 8*wave .. 8*wave+7; one
+  // source pointer for the even and one for the odd instructions of an operand
+  const char* srcA[2] = {rect_src<A_KC, 128>(g.A, g.lda, m0, 4 * wave, lane), rect_src<A_KC, 128>(g.A, g.lda, m0, 4 * wave + 1, lane)};
+  const char* srcB[2] = {rect_src<B_KC, 256>(g.B, g.ldb, n0, 8 * wave, lane), rect_src<B_KC, 256>(g.B, g.ldb, n0, 8 * wave + 1, lane)};
+  // two instructions on: 16 rows (KC), 8 k rows (MC, 128 rows wide), 4 k rows (MC, 256 rows wide); next k tile
+  const size_t stepA_2 = (size_t)(A_KC ? 16 : 8) * g.lda * 2, stepB_2 = (size_t)(B_KC ? 16 : 4) * g.ldb * 2;
+  const size_t stepA_k = A_KC ? (size_t)BKR * 2 : (size_t)BKR * g.lda * 2, stepB_k = B_KC ? (size_t)BKR * 2 : (size_t)BKR * g.ldb * 2;
   typedef const void __attribute__((address_space(1))) * gptr_t;
   typedef void OASES_LDS* lptr_t;
   auto issue = [&](int t) {
     char* st = lds + (t % NSR) * kRectStage;
 #pragma unroll
     for (int j = 0; j < 4; j++) {
-      __builtin_amdgcn_global_load_lds((gptr_t)(srcA + (size_t)t * stepA_k + j * stepA_q), (lptr_t)(st + (4 * wave + j) * 1024), 16, 0, 0);
-      __builtin_amdgcn_global_load_lds((gptr_t)(srcB[0] + (size_t)t * stepB_k + j * stepB_q), (lptr_t)(st + kRectA + (8 * wave + 2 * j) * 1024), 16, 0, 0);
-      __builtin_amdgcn_global_load_lds((gptr_t)(srcB[1] + (size_t)t * stepB_k + j * stepB_q), (lptr_t)(st + kRectA + (8 * wave + 2 * j + 1) * 1024), 16, 0, 0);
+      __builtin_amdgcn_global_load_lds((gptr_t)(srcA[j & 1] + (size_t)t * stepA_k + (j >> 1) * stepA_2), (lptr_t)(st + (4 * wave + j) * 1024), 16, 0, 0);
+      __builtin_amdgcn_global_load_lds((gptr_t)(srcB[0] + (size_t)t * stepB_k + j * stepB_2), (lptr_t)(st + kRectA + (8 * wave + 2 * j) * 1024), 16, 0, 0);
+      __builtin_amdgcn_global_load_lds((gptr_t)(srcB[1] + (size_t)t * stepB_k + j * stepB_2), (lptr_t)(st + kRectA + (8 * wave + 2 * j + 1) * 1024), 16, 0, 0);
     }
   };
 
   uint32_t offA[4], offB[4];
-  dtl_frag_offsets_rows<128>(offA, 0, lane);
-  dtl_frag_offsets_rows<256>(offB, wn * 128, lane);
-  // k rows 32*wk .. 32*wk+31 of every tile are this wave's
+  rect_frag_offsets<A_KC, 128>(offA, 0, wk, lane);
+  rect_frag_offsets<B_KC, 256>(offB, wn * 128, wk, lane);
   const uint32_t lds0 = (uint32_t)(uintptr_t)(OASES_LDS char*)lds;
-  const uint32_t halfA = wk * 32 * 256, halfB = kRectA + wk * 32 * 512;
   u32x4 fa[2][4], fb[2][4];
   auto mma = [&](int buf) {
 #pragma unroll
@@ -857,35 +823,36 @@ __global__ __launch_bounds__(256) void gemm_dtl_wgrad_kernel(GemmArgs g) {
 #pragma unroll
       for (int j = 0; j < TN; j++) {
         const bf16x8 a = __builtin_bit_cast(bf16x8, fa[buf][i]), b = __builtin_bit_cast(bf16x8, fb[buf][j]);
-        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b, a, acc[i][j], 0, 0, 0);
+        if constexpr (EPI == EPI_F32) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[i][j], 0, 0, 0);
+        else acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b, a, acc[i][j], 0, 0, 0);
       }
   };
   constexpr int kYoung = 12 * (NSR - 2);  // DMA instructions of the younger tiles that may still be in flight
   constexpr int kVmSteady = ((kYoung >> 4) << 14) | (kYoung & 15) | (7 << 4) | (15 << 8), kVm0 = (7 << 4) | (15 << 8);
-  constexpr int NR = 15;  // 16 reads per k step; the counter saturates at 15
+  constexpr int NRA = A_KC ? 4 : 8, NRB = B_KC ? 4 : 8, NR = NRA + NRB > 15 ? 15 : NRA + NRB;  // reads of one k step (the counter saturates at 15)
 
 #pragma unroll
   for (int t = 0; t < NSR - 1; t++)
     if (t < nk) issue(t);
   if (nk > NSR - 2) __builtin_amdgcn_s_waitcnt(kVmSteady); else __builtin_amdgcn_s_waitcnt(kVm0);
   __builtin_amdgcn_s_barrier();
-  dtl_read_frags_rows<128, 0>(fa[0], lds0 + halfA, offA);
-  dtl_read_frags_rows<256, 0>(fb[0], lds0 + halfB, offB);
+  rect_read_frags<A_KC, 128, 0>(fa[0], lds0, offA);
+  rect_read_frags<B_KC, 256, 0>(fb[0], lds0 + kRectA, offB);
 
   uint32_t cur = lds0;
   auto iteration = [&](auto steady_c, auto next_c, int kt) {
     constexpr bool STEADY = decltype(steady_c)::value, NEXT = decltype(next_c)::value;
     const uint32_t nxt = cur + kRectStage == lds0 + NSR * kRectStage ? lds0 : cur + kRectStage;
-    dtl_read_frags_rows<128, 1>(fa[1], cur + halfA, offA);
-    dtl_read_frags_rows<256, 1>(fb[1], cur + halfB, offB);
+    rect_read_frags<A_KC, 128, 1>(fa[1], cur, offA);
+    rect_read_frags<B_KC, 256, 1>(fb[1], cur + kRectA, offB);
     lds_wait<NR>(fa[0], fb[0]);
     if (STEADY) issue(kt + NSR - 1);  // into the stage of tile kt-1, which every wave left before the last barrier
     mma(0);
     if (NEXT) {
       if (STEADY) __builtin_amdgcn_s_waitcnt(kVmSteady); else __builtin_amdgcn_s_waitcnt(kVm0);  // own part of tile kt+1 has landed
       __builtin_amdgcn_s_barrier();
-      dtl_read_frags_rows<128, 0>(fa[0], nxt + halfA, offA);
-      dtl_read_frags_rows<256, 0>(fb[0], nxt + halfB, offB);
+      rect_read_frags<A_KC, 128, 0>(fa[0], nxt, offA);
+      rect_read_frags<B_KC, 256, 0>(fb[0], nxt + kRectA, offB);
       lds_wait<NR>(fa[1], fb[1]);
     } else {
       lds_wait<0>(fa[1], fb[1]);
@@ -926,16 +893,14 @@ __global__ __launch_bounds__(256) void gemm_dtl_wgrad_kernel(GemmArgs g) {
     for (int i = 0; i < HM; i++)
 #pragma unroll
       for (int j = 0; j < TN; j++) {
-        // element e of tile (i,j): C[m0 + 32 i + (lane & 31)][n0 + 128 wn + 32 j + 8 (e>>2) + 4 (lane>>5) + (e&3)]
-        const f32x16& a = acc[H * HM + i][j];
-        const int row = m0 + (H * HM + i) * 32 + (lane & 31);
+        f32x16 a = acc[H * HM + i][j];
 #pragma unroll
         for (int q = 0; q < 4; q++) {
           const f32x4 o = xch[(theirs + (i * TN + j) * 4 + q) * 64 + lane];
-          const int col = n0 + wn * 128 + j * 32 + 8 * q + 4 * (lane >> 5);
-          f32x4* p = reinterpret_cast<f32x4*>(reinterpret_cast<float*>(g.C) + (size_t)row * g.ldc + col);
-          *p = *p + (f32x4{a[4 * q], a[4 * q + 1], a[4 * q + 2], a[4 * q + 3]} + o);
+#pragma unroll
+          for (int e = 0; e < 4; e++) a[4 * q + e] += o[e];
         }
+        epilogue_tile<EPI, true>(g, m0 + (H * HM + i) * 32, n0 + wn * 128 + j * 32, lane, a);
       }
   };
   if (wk == 0) hand_over(std::integral_constant<int, 1>{}); else hand_over(std::integral_constant<int, 0>{});
@@ -1013,11 +978,11 @@ struct TileChoice { int bm, bn, ksplit; bool wave_ksplit; bool dtl = false; };
 // per kind of contraction (0: NN, 1: NT, 2: TN, 3: NN with the bias+GeLU epilogue): whether the rectangular tiles
 // split k between waves, and the sustained rates of the four block tiles
 bool dtl_fits(int M, int N, int K) { return M % 256 == 0 && N % 256 == 0 && K % BKD == 0 && K >= BKD; }
-bool dtl_wgrad_fits(int M, int N, int K) { return M % 128 == 0 && N % 256 == 0 && K % BKR == 0 && K >= BKR; }
+bool dtl_rect_fits(int M, int N, int K) { return M % 128 == 0 && N % 256 == 0 && K % BKR == 0 && K >= BKR; }
 struct KindTable { bool wave_ksplit; float r256x256, r128x256, r256x128, r128x128; };
 const KindTable g_kinds[4] = {{true, 1150.f, 1000.f, 960.f, 740.f}, {true, 1150.f, 1000.f, 960.f, 740.f},
                         {true, 1150.f, 1000.f, 960.f, 740.f}, {false, 1150.f, 880.f, 900.f, 740.f}};
-TileChoice pick_tile(int kind, int M, int N, int K, size_t ws_bytes) {
+TileChoice pick_tile(int kind, int epi, int M, int N, int K, size_t ws_bytes) {
   const KindTable& kt = g_kinds[kind];
   const struct { int bm, bn; float tflops; } cand[] = {{256, 256, kt.r256x256}, {128, 256, kt.r128x256}, {256, 128, kt.r256x128}, {128, 128, kt.r128x128}};
   TileChoice best{128, 128, 1, kt.wave_ksplit};
@@ -1033,10 +998,15 @@ TileChoice pick_tile(int kind, int M, int N, int K, size_t ws_bytes) {
       if (t < best_t) { best_t = t; best = TileChoice{c.bm, c.bn, S, kt.wave_ksplit}; }
     }
   }
-  // TN with whole 256 x 256 tiles: the direct-to-LDS kernel is the faster one (both operands go through the
-  // transposing LDS reads, which the staged kernel pays for with bank conflicts on its stores)
-  if ((kind == 2 || kind == 0) && best.bm == 256 && best.bn == 256 && best.ksplit == 1 && dtl_fits(M, N, K)) best.dtl = true;
-  if (kind == 2 && best.bm == 128 && best.bn == 256 && best.ksplit == 1 && dtl_wgrad_fits(M, N, K)) { best.dtl = true; best.wave_ksplit = true; }
+  // Whole tiles without k slices: the direct-to-LDS kernels where they measure faster on operands that come from HBM --
+  // 256 x 256 for TN and plain NN (an operand that goes through the transposing LDS read costs the staged kernel
+  // conflicting LDS stores); 128 x 256 for TN, NN and, except with the plain fp32 store, NT.  (The bias+GeLU forward stays
+  // on its staged 256 x 128 tiles: faster inside a step, although slower on cold operands in isolation.)
+  if (best.ksplit == 1 && epi != EPI_SWIGLU) {
+    const bool rect = best.bm == 128 && best.bn == 256 && kind != 3;
+    if (best.bm == 256 && best.bn == 256 && (kind == 2 || kind == 0) && dtl_fits(M, N, K)) best.dtl = true;
+    if (rect && (kind != 1 || epi != EPI_F32) && dtl_rect_fits(M, N, K)) best = TileChoice{128, 256, 1, true, true};
+  }
   return best;
 }
 
@@ -1049,10 +1019,10 @@ bool decode_variant(int variant, int M, int N, int K, size_t ws_bytes, TileChoic
   if (variant <= 0) return false;
   const int wk = variant / 100000000, S = variant / 1000000 % 100, bm = variant / 1000 % 1000, bn = variant % 1000;
   const bool square = (bm == 256 && bn == 256) || (bm == 128 && bn == 128), rect = (bm == 256 && bn == 128) || (bm == 128 && bn == 256);
-  if (wk == 2) {  // direct-to-LDS kernels: whole 256 x 256 tiles, or 128 x 256 tiles of the TN form; no k slices
+  if (wk == 2) {  // direct-to-LDS kernels: whole 256 x 256 tiles, or 128 x 256 tiles; no k slices
     if (S != 1) return false;
     if (bm == 256 && bn == 256 && dtl_fits(M, N, K)) { *t = TileChoice{256, 256, 1, false, true}; return true; }
-    if (bm == 128 && bn == 256 && dtl_wgrad_fits(M, N, K)) { *t = TileChoice{128, 256, 1, true, true}; return true; }
+    if (bm == 128 && bn == 256 && dtl_rect_fits(M, N, K)) { *t = TileChoice{128, 256, 1, true, true}; return true; }
     return false;
   }
   if (wk > 1 || !(square || rect) || (wk == 1 && !rect) || S < 1 || S > 8) return false;
@@ -1070,28 +1040,22 @@ int launch_shape(const GemmArgs& g, float* ws, size_t ws_bytes, int forced_varia
   if (EPI == EPI_SWIGLU || EPI == EPI_DSWIGLU) ws_bytes = 0;  // their epilogues pair columns: no second pass over partial planes
   TileChoice t;
   if (forced_variant == 0) {
-    t = pick_tile(kind, g.M, g.N, g.K, ws ? ws_bytes : 0);
+    t = pick_tile(kind, EPI, g.M, g.N, g.K, ws ? ws_bytes : 0);
   } else if (!decode_variant(forced_variant, g.M, g.N, g.K, ws ? ws_bytes : 0, &t)) {
     set_error("gemm: variant %d does not exist or does not fit M=%d N=%d K=%d with %zu workspace bytes", forced_variant, g.M, g.N, g.K, ws ? ws_bytes : (size_t)0);
     return OASES_EINVAL;
   }
-  if (t.dtl && t.bm == 128) {
-    if constexpr (!A_KC && !B_KC && EPI == EPI_ACC_F32) {
+  if (t.dtl) {
+    if constexpr (EPI == EPI_SWIGLU) {
+      set_error("gemm: the direct-to-LDS kernels have no SwiGLU epilogue");
+      return OASES_EINVAL;
+    } else if (t.bm == 128) {
       GemmArgs d = g;
       d.tiles_m = g.M / 128;
       d.tiles_n = g.N / 256;
-      hipLaunchKernelGGL(gemm_dtl_wgrad_kernel, dim3(d.tiles_m * d.tiles_n), dim3(256), 0, s, d);
-      OASES_LAUNCH_CHECK("gemm_dtl_wgrad_kernel");
+      hipLaunchKernelGGL((gemm_dtl_rect_kernel<A_KC, B_KC, EPI>), dim3(d.tiles_m * d.tiles_n), dim3(256), 0, s, d);
+      OASES_LAUNCH_CHECK("gemm_dtl_rect_kernel");
       return 0;
-    } else {
-      set_error("gemm: the 128x256 direct-to-LDS kernel exists for the TN form only");
-      return OASES_EINVAL;
-    }
-  }
-  if (t.dtl) {
-    if constexpr (EPI == EPI_SWIGLU) {
-      set_error("gemm: the direct-to-LDS kernel has no SwiGLU epilogue");
-      return OASES_EINVAL;
     } else {
       GemmArgs d = g;
       d.tiles_m = g.M / 256;
@@ -1116,7 +1080,7 @@ int launch_shape(const GemmArgs& g, float* ws, size_t ws_bytes, int forced_varia
 int gemm_variant(int op, int epi, int M, int N, int K, size_t ws_bytes) {
   const int kind = op == OASES_GEMM_TN ? 2 : op == OASES_GEMM_NT ? 1 : (epi == EPI_BIAS_GELU || epi == EPI_SWIGLU) ? 3 : 0;
   if (epi == EPI_SWIGLU || epi == EPI_DSWIGLU) ws_bytes = 0;
-  return encode_variant(pick_tile(kind, M, N, K, ws_bytes));
+  return encode_variant(pick_tile(kind, op == OASES_GEMM_TN ? EPI_ACC_F32 : epi, M, N, K, ws_bytes));
 }
 
 int launch_gemm(int op, int epi, int M, int N, int K, const void* A, int lda, const void* B, int ldb, void* C,

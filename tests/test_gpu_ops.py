@@ -270,28 +270,54 @@ def test_gemm_direct_to_lds_variant(B, lo, op, M, N, K):
 
 
 @pytest.mark.parametrize("M,N,K", [(128, 256, 64), (384, 512, 128), (256, 768, 192), (640, 256, 4096), (1152, 1024, 1088)])
-def test_gemm_direct_to_lds_wgrad_variant(B, M, N, K):
-    """The weight-gradient kernel with 128 x 256 tiles fed by direct-to-LDS loads (variant 201128256; TN form, whole tiles,
-    K % 64 == 0): one to 64 k tiles (prologue-only, drain and steady-state paths of its three-stage pipeline), odd and
-    even tile counts, accumulation into a non-zero C with a padded leading dimension."""
+@pytest.mark.parametrize("op", ["NN", "NT", "TN"])
+def test_gemm_direct_to_lds_rect_variant(B, lo, op, M, N, K):
+    """The kernel with 128 x 256 tiles fed by direct-to-LDS loads (variant 201128256; whole tiles, K % 64 == 0): one to 64
+    k tiles (prologue-only, drain and steady-state paths of its three-stage pipeline), odd and even tile counts, every
+    contraction form, a padded leading dimension of C, and the epilogues it supports."""
     variant = 201128256
     g = gen(M + N + K)
     a, b = bf16_round(randn(g, M, K)), bf16_round(randn(g, K, N, scale=0.05))
     ref = a @ b
-    ad, bd = dev(a.t().contiguous(), torch.bfloat16), dev(b, torch.bfloat16)
+    opc = {"NN": B.GEMM_NN, "NT": B.GEMM_NT, "TN": B.GEMM_TN}[op]
+    ad = dev(a if op != "TN" else a.t().contiguous(), torch.bfloat16)
+    bd = dev(b if op != "NT" else b.t().contiguous(), torch.bfloat16)
+    lda, ldb = (K if op != "TN" else M), (N if op != "NT" else K)
     ldc = N + 64
     c0 = randn(g, M, ldc).float()
     c = dev(c0, torch.float32)
-    B.check(B.lib.oases_op_gemm_forced(variant, B.GEMM_TN, B.EPI_F32, M, N, K, ad.data_ptr(), M, bd.data_ptr(), N, c.data_ptr(), ldc, None, None, 0,
+    B.check(B.lib.oases_op_gemm_forced(variant, opc, B.EPI_F32, M, N, K, ad.data_ptr(), lda, bd.data_ptr(), ldb, c.data_ptr(), ldc, None, None, 0,
                                        None, 0, None))
     out = c.cpu().double()
-    assert rel_err(out[:, :N], ref + c0[:, :N].double()) < 1e-5, (M, N, K)
+    assert rel_err(out[:, :N], ref + (c0[:, :N].double() if op == "TN" else 0.0)) < 1e-5, (op, M, N, K)   # TN accumulates into C
     assert torch.equal(out[:, N:], c0[:, N:].double())  # the padding columns of C are not touched
-    # other forms and shapes it does not cover are refused on the host
-    assert B.lib.oases_op_gemm_forced(variant, B.GEMM_NN, B.EPI_F32, M, N, K, ad.data_ptr(), K, bd.data_ptr(), N, c.data_ptr(), ldc, None, None, 0,
+    # shapes it does not cover are refused on the host
+    assert B.lib.oases_op_gemm_forced(variant, opc, B.EPI_F32, M, N, K - 32, ad.data_ptr(), lda, bd.data_ptr(), ldb, c.data_ptr(), ldc, None, None, 0,
                                       None, 0, None) == B.EINVAL
-    assert B.lib.oases_op_gemm_forced(variant, B.GEMM_TN, B.EPI_F32, M, N, K - 32, ad.data_ptr(), M, bd.data_ptr(), N, c.data_ptr(), ldc, None, None, 0,
+    assert B.lib.oases_op_gemm_forced(variant, opc, B.EPI_F32, M, N - 128, K, ad.data_ptr(), lda, bd.data_ptr(), ldb, c.data_ptr(), ldc, None, None, 0,
                                       None, 0, None) == B.EINVAL
+    if op == "TN":
+        return
+    bias = dev(0.1 * randn(g, N), torch.float32)
+    pre = dev(bf16_round(randn(g, M, N)), torch.bfloat16)
+    cb = torch.empty(M, N, dtype=torch.bfloat16, device="cuda")
+    B.check(B.lib.oases_op_gemm_forced(variant, opc, B.EPI_BF16, M, N, K, ad.data_ptr(), lda, bd.data_ptr(), ldb, cb.data_ptr(), N, None, None, 0,
+                                       None, 0, None))
+    assert_bf16_close(cb.float(), ref, 1e-5, 2e-6 * float(ref.abs().max()))
+    if op == "NN":
+        aux = torch.empty(M, N, dtype=torch.bfloat16, device="cuda")
+        B.check(B.lib.oases_op_gemm_forced(variant, opc, B.EPI_BIAS_BF16, M, N, K, ad.data_ptr(), lda, bd.data_ptr(), ldb, cb.data_ptr(), N,
+                                           bias.data_ptr(), None, 0, None, 0, None))
+        z = ref + bias.cpu().double()
+        assert_bf16_close(cb.float(), z, 1e-5, 2e-6 * float(z.abs().max()))
+        B.check(B.lib.oases_op_gemm_forced(variant, opc, B.EPI_BIAS_GELU, M, N, K, ad.data_ptr(), lda, bd.data_ptr(), ldb, cb.data_ptr(), N,
+                                           bias.data_ptr(), aux.data_ptr(), N, None, 0, None))
+        assert_bf16_close(aux.float(), z, 1e-5, 2e-6 * float(z.abs().max()))
+        assert_bf16_close(cb.float(), lo.gelu_fwd(z), 1e-4, 1e-5)
+    else:
+        B.check(B.lib.oases_op_gemm_forced(variant, opc, B.EPI_DGELU, M, N, K, ad.data_ptr(), lda, bd.data_ptr(), ldb, cb.data_ptr(), N,
+                                           None, pre.data_ptr(), N, None, 0, None))
+        assert_bf16_close(cb.float(), ref * lo.gelu_grad(pre.float().cpu().double()), 1e-4, 1e-5)
 
 
 def test_gemm_forced_variant_errors(B):
@@ -303,7 +329,7 @@ def test_gemm_forced_variant_errors(B):
     call = lambda v, wsb: B.lib.oases_op_gemm_forced(v, B.GEMM_NN, B.EPI_F32, M, N, K, a.data_ptr(), K, a.data_ptr(), N, c.data_ptr(), N, None, None, 0,
                                                      ws.data_ptr(), wsb, None)
     assert call(1128128, ws.numel()) == 0
-    for bad in (0, -5, 1192192, 1064064, 101256256, 101128128, 201128256, 9128128, 128128):
+    for bad in (0, -5, 1192192, 1064064, 101256256, 101128128, 201256128, 201128128, 301128256, 9128128, 128128):
         assert call(bad, ws.numel()) == B.EINVAL, bad
     assert call(2128128, 1024) == B.EINVAL           # workspace too small for two planes
     assert call(8128128, ws.numel()) == B.EINVAL     # 8 slices of 64 do not all start inside K = 256
