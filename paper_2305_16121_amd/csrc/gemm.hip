@@ -456,6 +456,21 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, char* lds, int m0, 
   }
 }
 
+// workgroup id within a launch of tiles_m x tiles_n tiles -> tile: undo the round-robin of workgroup ids over the 8 XCDs so
+// that each XCD's L2 sees a contiguous range of tiles, then walk that range in groups of 8 tile rows
+__device__ __forceinline__ void tile_of_workgroup(int pid, int tiles_m, int tiles_n, int& tile_m, int& tile_n) {
+  const int T = tiles_m * tiles_n;
+  const int per = (T + 7) / 8, tall = (T % 8 == 0) ? 8 : T % 8;
+  const int xcd = pid & 7, local = pid >> 3;
+  const int logical = xcd < tall ? xcd * per + local : tall * per + (xcd - tall) * (per - 1) + local;
+  constexpr int GM = 8;
+  const int width = GM * tiles_n;
+  const int group = logical / width, first_m = group * GM;
+  const int gsz = min(tiles_m - first_m, GM);
+  tile_m = first_m + (logical % width) % gsz;
+  tile_n = (logical % width) / gsz;
+}
+
 template <int BM, int BN, int WGM, int WGN, int WGK, bool A_KC, bool B_KC, int EPI>
 __global__ __launch_bounds__(64 * WGM * WGN * WGK) void gemm_kernel(GemmArgs g) {  // g: by value, adjusted per k slice
   using LA = TileLayout<BM, A_KC>;
@@ -464,23 +479,11 @@ __global__ __launch_bounds__(64 * WGM * WGN * WGK) void gemm_kernel(GemmArgs g) 
   constexpr int kExchange = WGK > 1 ? BM * BN * 4 : 0;  // half of every wave's accumulator
   __shared__ __attribute__((aligned(16))) char lds[kStages > kExchange ? kStages : kExchange];
 
-  // workgroup -> (k slice, tile): undo the round-robin of workgroup ids over the 8 XCDs so that each XCD's L2 sees a
-  // contiguous range of tiles, then walk that range in groups of 8 tile rows.
+  // workgroup -> (k slice, tile)
   int tile_m, tile_n;
   const int T = g.tiles_m * g.tiles_n;
   const int slice = blockIdx.x / T;
-  {
-    int pid = blockIdx.x - slice * T;
-    const int per = (T + 7) / 8, tall = (T % 8 == 0) ? 8 : T % 8;
-    int xcd = pid & 7, local = pid >> 3;
-    int logical = xcd < tall ? xcd * per + local : tall * per + (xcd - tall) * (per - 1) + local;
-    constexpr int GM = 8;
-    int width = GM * g.tiles_n;
-    int group = logical / width, first_m = group * GM;
-    int gsz = min(g.tiles_m - first_m, GM);
-    tile_m = first_m + (logical % width) % gsz;
-    tile_n = (logical % width) / gsz;
-  }
+  tile_of_workgroup(blockIdx.x - slice * T, g.tiles_m, g.tiles_n, tile_m, tile_n);
   if (g.ksplit > 1) {  // this workgroup's k range and partial-result plane
     const int k0 = slice * g.k_per;
     g.A += A_KC ? (size_t)k0 : (size_t)k0 * g.lda;
@@ -587,18 +590,7 @@ template <bool A_KC, bool B_KC, int EPI>
 __global__ __launch_bounds__(256) void gemm_dtl_kernel(GemmArgs g) {
   __shared__ __attribute__((aligned(1024))) char lds[NSD * kDtlStage];
   int tile_m, tile_n;
-  {
-    const int T = g.tiles_m * g.tiles_n, pid = blockIdx.x;
-    const int per = (T + 7) / 8, tall = (T % 8 == 0) ? 8 : T % 8;
-    int xcd = pid & 7, local = pid >> 3;
-    int logical = xcd < tall ? xcd * per + local : tall * per + (xcd - tall) * (per - 1) + local;
-    constexpr int GM = 8;
-    int width = GM * g.tiles_n;
-    int group = logical / width, first_m = group * GM;
-    int gsz = min(g.tiles_m - first_m, GM);
-    tile_m = first_m + (logical % width) % gsz;
-    tile_n = (logical % width) / gsz;
-  }
+  tile_of_workgroup(blockIdx.x, g.tiles_m, g.tiles_n, tile_m, tile_n);
   const int m0 = tile_m * 256, n0 = tile_n * 256;
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6), wm = wave >> 1, wn = wave & 1;
   constexpr int WGM = 2, WGN = 2, WTM = 128, WTN = 128, TM = 4, TN = 4;
@@ -768,18 +760,7 @@ __global__ __launch_bounds__(256) void gemm_dtl_rect_kernel(GemmArgs g) {
   constexpr int kExchange = 128 * 256 * 4;
   __shared__ __attribute__((aligned(1024))) char lds[NSR * kRectStage > kExchange ? NSR * kRectStage : kExchange];
   int tile_m, tile_n;
-  {
-    const int T = g.tiles_m * g.tiles_n, pid = blockIdx.x;
-    const int per = (T + 7) / 8, tall = (T % 8 == 0) ? 8 : T % 8;
-    int xcd = pid & 7, local = pid >> 3;
-    int logical = xcd < tall ? xcd * per + local : tall * per + (xcd - tall) * (per - 1) + local;
-    constexpr int GM = 8;
-    int width = GM * g.tiles_n;
-    int group = logical / width, first_m = group * GM;
-    int gsz = min(g.tiles_m - first_m, GM);
-    tile_m = first_m + (logical % width) % gsz;
-    tile_n = (logical % width) / gsz;
-  }
+  tile_of_workgroup(blockIdx.x, g.tiles_m, g.tiles_n, tile_m, tile_n);
   const int m0 = tile_m * 128, n0 = tile_n * 256;
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6), wn = wave & 1, wk = wave >> 1;
   constexpr int TM = 4, TN = 4;

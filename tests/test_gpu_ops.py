@@ -269,13 +269,13 @@ def test_gemm_direct_to_lds_variant(B, lo, op, M, N, K):
                                       None, 0, None) == B.EINVAL
 
 
-@pytest.mark.parametrize("M,N,K", [(128, 256, 64), (384, 512, 128), (256, 768, 192), (640, 256, 4096), (1152, 1024, 1088)])
+@pytest.mark.parametrize("variant,M,N,K", [(201128256, 128, 256, 64), (201128256, 384, 512, 128), (201128256, 256, 768, 192),
+                                           (201128256, 640, 256, 4096), (201128256, 1152, 1024, 1088), (201128256, 128, 512, 320)])
 @pytest.mark.parametrize("op", ["NN", "NT", "TN"])
-def test_gemm_direct_to_lds_rect_variant(B, lo, op, M, N, K):
+def test_gemm_direct_to_lds_rect_variant(B, lo, op, variant, M, N, K):
     """The kernel with 128 x 256 tiles fed by direct-to-LDS loads (variant 201128256; whole tiles, K % 64 == 0): one to 64
     k tiles (prologue-only, drain and steady-state paths of its three-stage pipeline), odd and even tile counts, every
     contraction form, a padded leading dimension of C, and the epilogues it supports."""
-    variant = 201128256
     g = gen(M + N + K)
     a, b = bf16_round(randn(g, M, K)), bf16_round(randn(g, K, N, scale=0.05))
     ref = a @ b
@@ -294,8 +294,8 @@ def test_gemm_direct_to_lds_rect_variant(B, lo, op, M, N, K):
     # shapes it does not cover are refused on the host
     assert B.lib.oases_op_gemm_forced(variant, opc, B.EPI_F32, M, N, K - 32, ad.data_ptr(), lda, bd.data_ptr(), ldb, c.data_ptr(), ldc, None, None, 0,
                                       None, 0, None) == B.EINVAL
-    assert B.lib.oases_op_gemm_forced(variant, opc, B.EPI_F32, M, N - 128, K, ad.data_ptr(), lda, bd.data_ptr(), ldb, c.data_ptr(), ldc, None, None, 0,
-                                      None, 0, None) == B.EINVAL
+    assert B.lib.oases_op_gemm_forced(variant, opc, B.EPI_F32, M, N - variant % 1000 // 2, K, ad.data_ptr(), lda, bd.data_ptr(), ldb, c.data_ptr(), ldc,
+                                      None, None, 0, None, 0, None) == B.EINVAL
     if op == "TN":
         return
     bias = dev(0.1 * randn(g, N), torch.float32)
