@@ -164,32 +164,31 @@ struct FinalizeArgs {
 };
 __global__ __launch_bounds__(NT) void colsum_finalize_kernel(const float* __restrict__ scratch, FinalizeArgs a, int groups,
                                                              int cols) {
-  // 16 columns x 16 group slices per workgroup; fixed summation tree, so the result does not depend on timing
+  // one output array (blockIdx.y) and 16 columns per workgroup, the groups dealt to 16 slices; fixed summation tree, so
+  // the result does not depend on timing
   __shared__ float red[16][17];
+  const int k = blockIdx.y;
+  if (!a.out[k]) return;
   const int cx = threadIdx.x & 15, gy = threadIdx.x >> 4;
   const int c = blockIdx.x * 16 + cx;
-  for (int k = 0; k < a.nk; k++) {
-    if (!a.out[k]) continue;
-    float s = 0.f;
-    if (c < cols) {
-      const float* p = scratch + (size_t)k * groups * cols + c;
-      int g = gy;
-      for (; g + 48 < groups; g += 64) {
-        float v0 = p[(size_t)g * cols], v1 = p[(size_t)(g + 16) * cols], v2 = p[(size_t)(g + 32) * cols],
-              v3 = p[(size_t)(g + 48) * cols];
-        s += (v0 + v1) + (v2 + v3);
-      }
-      for (; g < groups; g += 16) s += p[(size_t)g * cols];
+  float s = 0.f;
+  if (c < cols) {
+    const float* p = scratch + (size_t)k * groups * cols + c;
+    int g = gy;
+    for (; g + 48 < groups; g += 64) {
+      float v0 = p[(size_t)g * cols], v1 = p[(size_t)(g + 16) * cols], v2 = p[(size_t)(g + 32) * cols],
+            v3 = p[(size_t)(g + 48) * cols];
+      s += (v0 + v1) + (v2 + v3);
     }
-    __syncthreads();
-    red[gy][cx] = s;
-    __syncthreads();
-    if (gy == 0 && c < cols) {
-      float t = 0.f;
+    for (; g < groups; g += 16) s += p[(size_t)g * cols];
+  }
+  red[gy][cx] = s;
+  __syncthreads();
+  if (gy == 0 && c < cols) {
+    float t = 0.f;
 #pragma unroll
-      for (int i = 0; i < 16; i++) t += red[i][cx];
-      a.out[k][c] += t;
-    }
+    for (int i = 0; i < 16; i++) t += red[i][cx];
+    a.out[k][c] += t;
   }
 }
 
@@ -455,7 +454,7 @@ int launch_layernorm_fwd(const float* x, const float* gamma, const float* beta, 
 
 static int finalize(float* scratch, float* o0, float* o1, float* o2, int nk, int groups, int cols, hipStream_t s) {
   FinalizeArgs a{{o0, o1, o2}, nk};
-  hipLaunchKernelGGL(colsum_finalize_kernel, dim3((cols + 15) / 16), dim3(NT), 0, s, scratch, a, groups, cols);
+  hipLaunchKernelGGL(colsum_finalize_kernel, dim3((cols + 15) / 16, nk), dim3(NT), 0, s, scratch, a, groups, cols);
   OASES_LAUNCH_CHECK("colsum_finalize_kernel");
   return 0;
 }
