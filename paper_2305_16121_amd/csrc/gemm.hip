@@ -503,8 +503,9 @@ __global__ __launch_bounds__(64 * WGM * WGN * WGK) void gemm_kernel(GemmArgs g) 
 // might alias a pending LDS DMA, so the fragment reads are inline assembly and every wait is placed by hand:
 //   vmcnt  -- DMA instructions complete in order, 8 per wave and tile: "tile t has landed" = at most 8 x (younger tiles
 //             in flight) outstanding, then the workgroup barrier makes all four waves' parts visible;
-//   lgkmcnt -- LDS reads return in order: fragments of the older k step are waited for with the younger step's reads
-//             still outstanding.
+//   lgkmcnt -- LDS reads return in order: fragments of the first k step are waited for with the second step's reads
+//             still outstanding; the second step's are waited for before the barrier, so that a stage is never
+//             refilled while a wave still reads it.
 // Only whole tiles (M, N multiples of 256, K of 32) and no k slices; everything else runs on the kernels above.
 // =================================================================================================
 #ifndef OASES_DTL_STAGES
@@ -654,9 +655,9 @@ __global__ __launch_bounds__(256) void gemm_dtl_kernel(GemmArgs g) {
   dtl_read_frags<A_KC, 0>(fa[0], lds0, offA);
   dtl_read_frags<B_KC, 0>(fb[0], lds0 + kDtlOperand, offB);
 
-  // one 32-wide k tile.  STEADY: tile kt+NSD-1 exists and is requested now (its stage held tile kt-1, which every wave
-  // finished reading before the last barrier), so two younger tiles are in flight when tile kt+1 must have landed;
-  // NEXT: tile kt+1 exists.
+  // one 32-wide k tile.  STEADY: tile kt+NSD-1 exists and is requested now (its stage held tile kt-1; a wave passes the
+  // barrier of an iteration only after all its reads of that iteration's tile have returned), so NSD-2 younger tiles
+  // are in flight when tile kt+1 must have landed; NEXT: tile kt+1 exists.
   uint32_t cur = lds0;
   auto iteration = [&](auto steady_c, auto next_c, int kt) {
     constexpr bool STEADY = decltype(steady_c)::value, NEXT = decltype(next_c)::value;
@@ -666,14 +667,12 @@ __global__ __launch_bounds__(256) void gemm_dtl_kernel(GemmArgs g) {
     lds_wait<NR>(fa[0], fb[0]);
     if (STEADY) issue(kt + NSD - 1);
     mma(0);
+    lds_wait<0>(fa[1], fb[1]);  // requested before the MFMAs above; with it every read this wave makes of tile kt is complete
     if (NEXT) {
       if (STEADY) __builtin_amdgcn_s_waitcnt(kVm16); else __builtin_amdgcn_s_waitcnt(kVm0);  // own part of tile kt+1 has landed
-      __builtin_amdgcn_s_barrier();
+      __builtin_amdgcn_s_barrier();  // tile kt+1 is visible to every wave, and no wave reads tile kt any more
       dtl_read_frags<A_KC, 0>(fa[0], nxt, offA);
       dtl_read_frags<B_KC, 0>(fb[0], nxt + kDtlOperand, offB);
-      lds_wait<NR>(fa[1], fb[1]);
-    } else {
-      lds_wait<0>(fa[1], fb[1]);
     }
     mma(1);
     cur = nxt;
@@ -827,16 +826,14 @@ __global__ __launch_bounds__(256) void gemm_dtl_rect_kernel(GemmArgs g) {
     rect_read_frags<A_KC, 128, 1>(fa[1], cur, offA);
     rect_read_frags<B_KC, 256, 1>(fb[1], cur + kRectA, offB);
     lds_wait<NR>(fa[0], fb[0]);
-    if (STEADY) issue(kt + NSR - 1);  // into the stage of tile kt-1, which every wave left before the last barrier
+    if (STEADY) issue(kt + NSR - 1);  // into the stage of tile kt-1: its reads had returned before any wave passed the last barrier
     mma(0);
+    lds_wait<0>(fa[1], fb[1]);  // requested before the MFMAs above; with it every read this wave makes of tile kt is complete
     if (NEXT) {
       if (STEADY) __builtin_amdgcn_s_waitcnt(kVmSteady); else __builtin_amdgcn_s_waitcnt(kVm0);  // own part of tile kt+1 has landed
-      __builtin_amdgcn_s_barrier();
+      __builtin_amdgcn_s_barrier();  // tile kt+1 is visible to every wave, and no wave reads tile kt any more
       rect_read_frags<A_KC, 128, 0>(fa[0], nxt, offA);
       rect_read_frags<B_KC, 256, 0>(fb[0], nxt + kRectA, offB);
-      lds_wait<NR>(fa[1], fb[1]);
-    } else {
-      lds_wait<0>(fa[1], fb[1]);
     }
     mma(1);
     cur = nxt;
