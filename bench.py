@@ -43,6 +43,8 @@ def op_flops(line, cfg):
     Ms = M if line.endswith("sb*") else M // cfg["n_sub"]
     hp, fp, fw = widths(cfg)
     op = line.split()[1]
+    if op == "PROJ+QKV.wgrad":
+        return 2.0 * Ms * h * (hp + 3 * hp)
     base = op.split(".")[0].split("+")[0]
     table = {"QKV": 2.0 * Ms * h * 3 * hp, "PROJ": 2.0 * Ms * hp * h, "FC1": 2.0 * Ms * h * fw, "FC2": 2.0 * Ms * fp * h}
     if base in table:
@@ -82,6 +84,8 @@ def gemm_kernel_label(line, cfg, B, ws_bytes):
               "FC1.dgrad": ("NT", "f32", Ms, h, fw),
               "PROJ.dgrad": ("NT", "bf16", Ms, hp, h), "QKV.dgrad": ("NT", "f32", Ms, h, 3 * hp), "FC2.wgrad": ("TN", "acc_f32", fp, h, Ms),
               "FC1.wgrad": ("TN", "acc_f32", h, fw, Ms), "PROJ.wgrad": ("TN", "acc_f32", hp, h, Ms), "QKV.wgrad": ("TN", "acc_f32", h, 3 * hp, Ms)}
+    if op == "PROJ+QKV.wgrad":   # the two weight gradients of the attention block in one launch
+        return "gemm_TN_acc_f32_128x256_dtl_pair"
     if op not in shapes:
         return None
     form, epi, m, n, k = shapes[op]

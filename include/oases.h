@@ -268,6 +268,20 @@ int oases_op_gemm_variant(int op, int epi, int M, int N, int K, size_t workspace
 int oases_op_gemm_forced(int variant, int op, int epi, int M, int N, int K, const void *A, int lda,
                          const void *B, int ldb, void *C, int ldc, const void *bias, void *aux,
                          int ldaux, void *workspace, size_t workspace_bytes, void *stream);
+/* Two weight-gradient contractions over the same K token rows in ONE launch of the 128x256 direct-to-LDS kernel:
+ *   C0 [M0,N0] += A0^T B0   and   C1 [M1,N1] += A1^T B1,   A_i bf16 [K, lda_i >= M_i], B_i bf16 [K, ldb_i >= N_i],
+ *   C_i fp32 [M_i, ldc_i >= N_i] (accumulated into, as the TN form of oases_op_gemm does); all device pointers,
+ * 16-byte aligned; lda, ldb multiples of 8, ldc of 4.  The tiles of the second problem follow those of the first in the
+ * grid, so that two launches that would each leave CUs idle (or need k slices to fill them) share one round of
+ * workgroups: the backward pass issues the attention block's two weight gradients (Sec. II: projection and QKV) this way
+ * when oases_op_gemm_tn_pair_wins says so.  Needs M_i % 128 == 0, N_i % 256 == 0, K % 64 == 0: EINVAL otherwise, before
+ * any launch.  Each C_i gets exactly what oases_op_gemm_forced(201128256, TN, ...) gives it. */
+int oases_op_gemm_tn_pair(int K, int M0, int N0, const void *A0, int lda0, const void *B0, int ldb0, void *C0,
+                          int ldc0, int M1, int N1, const void *A1, int lda1, const void *B1, int ldb1, void *C1,
+                          int ldc1, void *stream);
+/* Host only: 1 if the library issues two such weight gradients as one launch (both fit whole 128x256 tiles, more than 128
+ * tiles together, and fewer rounds of 256 workgroups together than apart), else 0. */
+int oases_op_gemm_tn_pair_wins(int K, int M0, int N0, int M1, int N1);
 /* Bytes of split-K scratch that oases_forward / oases_backward set aside inside the workspace. */
 size_t oases_gemm_workspace_bytes(const oases_handle *h);
 

@@ -71,6 +71,8 @@ _sig("oases_op_rope_table", _i, _P, _i, _i, _f, _P)
 _sig("oases_op_rope", _i, _P, _i, _i, _i64, _i, _i, _i, _P, _i, _P)
 _sig("oases_op_gemm", _i, _i, _i, _i, _i, _i, _P, _i, _P, _i, _P, _i, _P, _P, _i, _P, _sz, _P)
 _sig("oases_op_gemm_variant", _i, _i, _i, _i, _i, _i, _sz)
+_sig("oases_op_gemm_tn_pair", _i, _i, _i, _i, _P, _i, _P, _i, _P, _i, _i, _i, _P, _i, _P, _i, _P, _i, _P)
+_sig("oases_op_gemm_tn_pair_wins", _i, _i, _i, _i, _i, _i)
 _sig("oases_op_gemm_forced", _i, _i, _i, _i, _i, _i, _i, _P, _i, _P, _i, _P, _i, _P, _P, _i, _P, _sz, _P)
 _sig("oases_gemm_workspace_bytes", _sz, _P)
 _sig("oases_op_colsum_bf16", _i, _P, _i, _i, _i, _P, _P, _P)

@@ -39,13 +39,15 @@ enum OpKind {
   JOIN,
   // rotary embedding of the LLaMA-style layer: table once per forward pass, rotation of Q and K behind QKV (forward,
   // recomputation), rotation back of dQ and dK behind the attention backward
-  F_ROPE_TABLE, F_ROPE, R_ROPE, B_ROPE
+  F_ROPE_TABLE, F_ROPE, R_ROPE, B_ROPE,
+  // PROJ.wgrad and QKV.wgrad as one launch, where the shapes make that the faster way
+  B_PQ_WGRAD
 };
 static const char* kOpName[] = {
     "LN1", "QKV", "ATTN", "PROJ", "R1+BDR1+LN2", "FC1+GELU", "FC2", "R2+BDR2",
     "BDR2.b", "FC2.dgrad+dGELU", "FC1.dgrad", "R3+LN2.b+BDR1.b", "FC2.wgrad", "FC1.wgrad", "b1.sum", "PROJ.dgrad",
     "PROJ.wgrad", "ATTN.b", "QKV.dgrad", "R4+LN1.b", "QKV.wgrad", "bqkv.sum",
-    "LN2.r", "FC1+GELU.r", "LN1.r", "QKV.r", "ATTN.r", "join", "ROPE.table", "ROPE", "ROPE.r", "ROPE.b"};
+    "LN2.r", "FC1+GELU.r", "LN1.r", "QKV.r", "ATTN.r", "join", "ROPE.table", "ROPE", "ROPE.r", "ROPE.b", "PROJ+QKV.wgrad"};
 // names of the same operator slots in the LLaMA-style layer (RMSNorm, SwiGLU)
 static const char* op_name(int kind, bool llama, bool bert) {
   if (bert) {  // post-LN: the normalisation sits behind the residual sum, the layer input enters the GEMM as it is
@@ -252,8 +254,12 @@ static void build_backward(oases_handle* H) {
       ops.push_back(Op{B_QKV_DGRAD, l, j, 0, -1, ev_id(H, l, 3, j, 0)});
       ops.push_back(Op{B_R4, l, j, 1, ev_id(H, l, 3, j, 0), ev_id(H, l, 3, j, 1)});
     }
-    ops.push_back(Op{B_PROJ_WGRAD, l, -1, 0, -1, -1});
-    ops.push_back(Op{B_QKV_WGRAD, l, -1, 0, -1, -1});
+    if (gemm_tn_pair_wins(H->M, H->hp, H->h, H->h, 3 * H->hp)) {
+      ops.push_back(Op{B_PQ_WGRAD, l, -1, 0, -1, -1});
+    } else {
+      ops.push_back(Op{B_PROJ_WGRAD, l, -1, 0, -1, -1});
+      ops.push_back(Op{B_QKV_WGRAD, l, -1, 0, -1, -1});
+    }
     if (!H->llama) ops.push_back(Op{B_BQKV_SUM, l, -1, 0, -1, -1});
   }
   for (int j = n - 1; j >= 0; j--) ops.push_back(Op{JOIN, 0, j, 0, ev_id(H, 0, 3, j, 1), -1});
@@ -469,6 +475,9 @@ static int run_op(const Run& R, const Op& op) {
     case B_QKV_WGRAD:
       return launch_gemm(OASES_GEMM_TN, 0, h, 3 * hp, Ms, u + r0 * h, h, wsp<uint16_t>(R, "dqkv", l) + r0 * 3 * hp, 3 * hp,
                          R.g[l].wqkv, 3 * hp, nullptr, nullptr, 0, gws, H->gemm_ws_bytes, 0, s);
+    case B_PQ_WGRAD:
+      return launch_gemm_tn_pair(Ms, hp, h, attn + r0 * hp, hp, wsp<uint16_t>(R, "dz1", l) + r0 * h, h, R.g[l].wo, h, h, 3 * hp, u + r0 * h, h,
+                                 wsp<uint16_t>(R, "dqkv", l) + r0 * 3 * hp, 3 * hp, R.g[l].wqkv, 3 * hp, s);
     case B_BQKV_SUM:
       return launch_colsum_bf16(wsp<uint16_t>(R, "dqkv", l) + r0 * 3 * hp, 3 * hp, Ms, 3 * hp, (float*)R.g[l].bqkv, scr_comp, s);
     // ---------------------------------------------------------------- recompute: the forward kernels again
@@ -768,6 +777,11 @@ int oases_op_gemm_variant(int op, int epi, int M, int N, int K, size_t workspace
   if (op < 0 || op > 2 || M <= 0 || N <= 0 || K <= 0) { set_error("oases_op_gemm_variant: bad argument"); return OASES_EINVAL; }
   return gemm_variant(op, epi, M, N, K, workspace_bytes);
 }
+int oases_op_gemm_tn_pair(int K, int M0, int N0, const void* A0, int lda0, const void* B0, int ldb0, void* C0, int ldc0, int M1, int N1,
+                          const void* A1, int lda1, const void* B1, int ldb1, void* C1, int ldc1, void* stream) {
+  return launch_gemm_tn_pair(K, M0, N0, A0, lda0, B0, ldb0, C0, ldc0, M1, N1, A1, lda1, B1, ldb1, C1, ldc1, (hipStream_t)stream);
+}
+int oases_op_gemm_tn_pair_wins(int K, int M0, int N0, int M1, int N1) { return gemm_tn_pair_wins(K, M0, N0, M1, N1) ? 1 : 0; }
 size_t oases_gemm_workspace_bytes(const oases_handle* H) { return H ? H->gemm_ws_bytes : 0; }
 int oases_op_colsum_bf16(const void* a, int ld, int rows, int cols, void* out, void* scratch, void* stream) {
   return launch_colsum_bf16(a, ld, rows, cols, (float*)out, (float*)scratch, (hipStream_t)stream);

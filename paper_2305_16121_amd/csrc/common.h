@@ -126,6 +126,11 @@ int launch_gemm(int op, int epi, int M, int N, int K, const void* A, int lda, co
                 int ldc, const float* bias, void* aux, int ldaux, void* splitk_ws, size_t splitk_ws_bytes, int forced_variant,
                 hipStream_t s);
 int gemm_variant(int op, int epi, int M, int N, int K, size_t ws_bytes);  // 1e8*[waves split k] + 1e6*slices + 1e3*BM + BN
+// two TN contractions C_i += A_i^T B_i over the same K rows in one launch of the 128x256 direct-to-LDS kernel, and the
+// host rule that says when that beats two launches (both fit whole tiles, fewer rounds of workgroups together)
+int launch_gemm_tn_pair(int K, int M0, int N0, const void* A0, int lda0, const void* B0, int ldb0, void* C0, int ldc0, int M1, int N1,
+                        const void* A1, int lda1, const void* B1, int ldb1, void* C1, int ldc1, hipStream_t s);
+bool gemm_tn_pair_wins(int K, int M0, int N0, int M1, int N1);
 constexpr size_t kSplitKWorkspaceBytes = 256u << 20;
 // p_attn > 0: dropout on the probabilities (mask keyed by seed, layer, sequence, global head = head0 + local head, q, k)
 int launch_attention_fwd(const void* qkv, void* out, float* lse, int batch, int seq, int heads, int head_dim,

@@ -754,12 +754,14 @@ __device__ __forceinline__ void rect_read_frags(u32x4 (&f)[4], uint32_t base, co
   }
 }
 
+constexpr int kRectExchange = 128 * 256 * 4;
+constexpr int kRectLds = NSR * kRectStage > kRectExchange ? NSR * kRectStage : kRectExchange;
+
+// one 128 x 256 tile: workgroup `pid` of the tiles_m x tiles_n tiles of problem g; lds: kRectLds bytes, 1024-byte aligned
 template <bool A_KC, bool B_KC, int EPI>
-__global__ __launch_bounds__(256) void gemm_dtl_rect_kernel(GemmArgs g) {
-  constexpr int kExchange = 128 * 256 * 4;
-  __shared__ __attribute__((aligned(1024))) char lds[NSR * kRectStage > kExchange ? NSR * kRectStage : kExchange];
+__device__ __forceinline__ void dtl_rect_tile(const GemmArgs& g, int pid, char* lds) {
   int tile_m, tile_n;
-  tile_of_workgroup(blockIdx.x, g.tiles_m, g.tiles_n, tile_m, tile_n);
+  tile_of_workgroup(pid, g.tiles_m, g.tiles_n, tile_m, tile_n);
   const int m0 = tile_m * 128, n0 = tile_n * 256;
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6), wn = wave & 1, wk = wave >> 1;
   constexpr int TM = 4, TN = 4;
@@ -884,6 +886,21 @@ __global__ __launch_bounds__(256) void gemm_dtl_rect_kernel(GemmArgs g) {
   if (wk == 0) hand_over(std::integral_constant<int, 1>{}); else hand_over(std::integral_constant<int, 0>{});
   __syncthreads();
   if (wk == 0) finish(std::integral_constant<int, 0>{}); else finish(std::integral_constant<int, 1>{});
+}
+
+template <bool A_KC, bool B_KC, int EPI>
+__global__ __launch_bounds__(256) void gemm_dtl_rect_kernel(GemmArgs g) {
+  __shared__ __attribute__((aligned(1024))) char lds[kRectLds];
+  dtl_rect_tile<A_KC, B_KC, EPI>(g, blockIdx.x, lds);
+}
+
+// Two weight-gradient contractions over the same K rows in one launch: the tiles of the second problem follow those of
+// the first, so that two launches that would each leave CUs idle (or need k slices to fill them) share one round.
+__global__ __launch_bounds__(256) void gemm_dtl_rect_pair_kernel(GemmArgs g0, GemmArgs g1) {
+  __shared__ __attribute__((aligned(1024))) char lds[kRectLds];
+  const int first = g0.tiles_m * g0.tiles_n;
+  if ((int)blockIdx.x < first) dtl_rect_tile<false, false, EPI_ACC_F32>(g0, blockIdx.x, lds);
+  else dtl_rect_tile<false, false, EPI_ACC_F32>(g1, blockIdx.x - first, lds);
 }
 
 // split-K second pass: C = epilogue(sum over slices of the fp32 partial planes), slices added in index order
@@ -1054,6 +1071,36 @@ int launch_shape(const GemmArgs& g, float* ws, size_t ws_bytes, int forced_varia
 }
 
 }  // namespace
+
+bool gemm_tn_pair_wins(int K, int M0, int N0, int M1, int N1) {
+  if (M0 <= 0 || N0 <= 0 || M1 <= 0 || N1 <= 0 || !dtl_rect_fits(M0, N0, K) || !dtl_rect_fits(M1, N1, K)) return false;
+  const long t0 = (long)(M0 / 128) * (N0 / 256), t1 = (long)(M1 / 128) * (N1 / 256);
+  // enough tiles to be worth whole 128 x 256 tiles at all, and fewer rounds of 256 workgroups together than apart
+  return t0 + t1 > 128 && (t0 + t1 + 255) / 256 < (t0 + 255) / 256 + (t1 + 255) / 256;
+}
+
+int launch_gemm_tn_pair(int K, int M0, int N0, const void* A0, int lda0, const void* B0, int ldb0, void* C0, int ldc0, int M1, int N1,
+                        const void* A1, int lda1, const void* B1, int ldb1, void* C1, int ldc1, hipStream_t s) {
+  if (K <= 0 || M0 <= 0 || N0 <= 0 || M1 <= 0 || N1 <= 0 || !dtl_rect_fits(M0, N0, K) || !dtl_rect_fits(M1, N1, K)) {
+    set_error("gemm_tn_pair: needs M %% 128 == 0, N %% 256 == 0, K %% 64 == 0 for both problems (got K=%d, %dx%d and %dx%d)", K, M0, N0, M1, N1);
+    return OASES_EINVAL;
+  }
+  if ((lda0 % 8) || (ldb0 % 8) || (ldc0 % 4) || (lda1 % 8) || (ldb1 % 8) || (ldc1 % 4) || lda0 < M0 || ldb0 < N0 || ldc0 < N0 || lda1 < M1 ||
+      ldb1 < N1 || ldc1 < N1) {
+    set_error("gemm_tn_pair: leading dimension too small or not a multiple of 8 (A, B) / 4 (C)");
+    return OASES_EINVAL;
+  }
+  if (!A0 || !B0 || !C0 || !A1 || !B1 || !C1) { set_error("gemm_tn_pair: NULL operand"); return OASES_ENULL; }
+  if (!aligned16(A0) || !aligned16(B0) || !aligned16(C0) || !aligned16(A1) || !aligned16(B1) || !aligned16(C1)) {
+    set_error("gemm_tn_pair: operand not 16-byte aligned");
+    return OASES_EALIGN;
+  }
+  GemmArgs g0{(const uint16_t*)A0, (const uint16_t*)B0, C0, nullptr, nullptr, M0, N0, K, lda0, ldb0, ldc0, 0, M0 / 128, N0 / 256, 1, K};
+  GemmArgs g1{(const uint16_t*)A1, (const uint16_t*)B1, C1, nullptr, nullptr, M1, N1, K, lda1, ldb1, ldc1, 0, M1 / 128, N1 / 256, 1, K};
+  hipLaunchKernelGGL(gemm_dtl_rect_pair_kernel, dim3(g0.tiles_m * g0.tiles_n + g1.tiles_m * g1.tiles_n), dim3(256), 0, s, g0, g1);
+  OASES_LAUNCH_CHECK("gemm_dtl_rect_pair_kernel");
+  return 0;
+}
 
 int gemm_variant(int op, int epi, int M, int N, int K, size_t ws_bytes) {
   const int kind = op == OASES_GEMM_TN ? 2 : op == OASES_GEMM_NT ? 1 : (epi == EPI_BIAS_GELU || epi == EPI_SWIGLU) ? 3 : 0;

@@ -171,6 +171,29 @@ def test_schedule_structure(B, name):
     assert sum(" LN1 " in l for l in fwd) == n
 
 
+def test_attention_weight_gradients_share_a_launch_where_it_pays(B):
+    """PROJ.wgrad and QKV.wgrad go out as one launch when both fit whole 128 x 256 tiles, have more than 128 tiles together
+    and need fewer rounds of 256 workgroups together than apart (host rule); the schedule then holds one operator for
+    the two."""
+    wins = B.lib.oases_op_gemm_tn_pair_wins
+    assert wins(8192, 512, 4096, 4096, 1536) == 1          # C4: 64 + 192 tiles = one round instead of two
+    assert wins(8192, 1024, 8192, 8192, 3072) == 0         # C5: 256 + 768 tiles, four rounds either way
+    assert wins(4096, 256, 1024, 1024, 768) == 0           # C2: 32 tiles, too few for whole 128 x 256 tiles
+    assert wins(8192, 512, 4096, 4096, 1408) == 0          # N not a multiple of 256
+    assert wins(8200, 512, 4096, 4096, 1536) == 0          # K not a multiple of 64
+    assert wins(0, 512, 4096, 4096, 1536) == 0 and wins(8192, -128, 4096, 4096, 1536) == 0
+    for name, paired in (("C4", True), ("C5", False), ("C2", False)):
+        cfg = si.CONFIGS[name]
+        for flags in (0, B.FLAG_RECOMPUTE):
+            bwd = B.Handle(B.make_cfg(cfg, flags=flags)).schedule(True).splitlines()
+            count = lambda op: sum(f" {op} " in l for l in bwd)
+            assert count("PROJ+QKV.wgrad") == (cfg["n_layers"] if paired else 0), name
+            assert count("PROJ.wgrad") == count("QKV.wgrad") == (0 if paired else cfg["n_layers"]), name
+            assert count("bqkv.sum") == cfg["n_layers"]
+    bwd = B.Handle(B.make_cfg(si.LLAMA_CONFIGS["L4"])).schedule(True).splitlines()
+    assert sum(" PROJ+QKV.wgrad " in l for l in bwd) == 1
+
+
 # ------------------------------------------------------------------ LLaMA-style layer: schedule and configuration checks
 LLAMA_FWD_TRACE = """\
 compute ROPE.table sb*

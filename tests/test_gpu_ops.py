@@ -320,6 +320,42 @@ def test_gemm_direct_to_lds_rect_variant(B, lo, op, variant, M, N, K):
         assert_bf16_close(cb.float(), ref * lo.gelu_grad(pre.float().cpu().double()), 1e-4, 1e-5)
 
 
+@pytest.mark.parametrize("K,M0,N0,M1,N1", [(64, 128, 256, 128, 256), (192, 256, 512, 384, 256), (4096, 128, 768, 640, 256), (1088, 512, 1024, 1152, 768)])
+def test_gemm_tn_pair(B, K, M0, N0, M1, N1):
+    """Two weight gradients in one launch: each result is the product (accumulated into C, padded leading dimensions
+    untouched) and is bit-identical to the same kernel launched for that problem alone."""
+    g = gen(K + M0 + N1)
+    prob = []
+    for (M, N) in ((M0, N0), (M1, N1)):
+        a, b = bf16_round(randn(g, M, K)), bf16_round(randn(g, K, N, scale=0.05))
+        lda, ldb, ldc = M + 8, N + 16, N + 64
+        ap, bp = torch.zeros(K, lda, dtype=torch.float64), torch.zeros(K, ldb, dtype=torch.float64)
+        ap[:, :M], bp[:, :N] = a.t(), b
+        c0 = randn(g, M, ldc).float()
+        prob.append(dict(M=M, N=N, ref=a @ b, ad=dev(ap, torch.bfloat16), bd=dev(bp, torch.bfloat16), lda=lda, ldb=ldb, ldc=ldc, c0=c0,
+                         c=dev(c0, torch.float32), c_alone=dev(c0, torch.float32)))
+    p0, p1 = prob
+    B.check(B.lib.oases_op_gemm_tn_pair(K, M0, N0, p0["ad"].data_ptr(), p0["lda"], p0["bd"].data_ptr(), p0["ldb"], p0["c"].data_ptr(), p0["ldc"],
+                                        M1, N1, p1["ad"].data_ptr(), p1["lda"], p1["bd"].data_ptr(), p1["ldb"], p1["c"].data_ptr(), p1["ldc"], None))
+    for q in prob:
+        B.check(B.lib.oases_op_gemm_forced(201128256, B.GEMM_TN, B.EPI_F32, q["M"], q["N"], K, q["ad"].data_ptr(), q["lda"], q["bd"].data_ptr(), q["ldb"],
+                                           q["c_alone"].data_ptr(), q["ldc"], None, None, 0, None, 0, None))
+        out = q["c"].cpu().double()
+        assert rel_err(out[:, :q["N"]], q["ref"] + q["c0"][:, :q["N"]].double()) < 1e-5
+        assert torch.equal(out[:, q["N"]:], q["c0"][:, q["N"]:].double())
+        assert torch.equal(q["c"], q["c_alone"])
+    # shapes the kernel does not cover, NULL and misaligned operands: refused on the host
+    args = lambda **o: [o.get("K", K), o.get("M0", M0), N0, o.get("A0", p0["ad"].data_ptr()), p0["lda"], p0["bd"].data_ptr(), p0["ldb"], p0["c"].data_ptr(),
+                        p0["ldc"], M1, o.get("N1", N1), p1["ad"].data_ptr(), p1["lda"], p1["bd"].data_ptr(), p1["ldb"], p1["c"].data_ptr(), o.get("ldc1", p1["ldc"]), None]
+    assert B.lib.oases_op_gemm_tn_pair(*args(K=K + 32)) == B.EINVAL
+    assert B.lib.oases_op_gemm_tn_pair(*args(M0=M0 - 64)) == B.EINVAL
+    assert B.lib.oases_op_gemm_tn_pair(*args(N1=N1 - 128)) == B.EINVAL
+    assert B.lib.oases_op_gemm_tn_pair(*args(ldc1=N1 - 4)) == B.EINVAL
+    assert B.lib.oases_op_gemm_tn_pair(*args(A0=None)) == B.ENULL
+    assert B.lib.oases_op_gemm_tn_pair(*args(A0=p0["ad"].data_ptr() + 2)) == B.EALIGN
+    torch.cuda.synchronize()
+
+
 def test_gemm_forced_variant_errors(B):
     """Variants that do not exist, k slices that do not fit K or the workspace: EINVAL before any launch."""
     M = N = K = 256
