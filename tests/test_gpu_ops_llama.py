@@ -166,6 +166,35 @@ def test_gemm_swiglu_epilogues(B, ll, M, fp, K, variant):
     assert_bf16_close(dgu.float(), ref, 1e-4, 1e-5)
 
 
+@pytest.mark.parametrize("variant,M,fp,K", [(201128256, 256, 512, 192), (201128256, 384, 256, 1088), (201256256, 512, 256, 160), (0, 4096, 1536, 4096)])
+def test_gemm_swiglu_gradient_on_direct_to_lds_kernels(B, ll, variant, M, fp, K):
+    """The SwiGLU-gradient epilogue on the kernels whose tiles arrive by direct-to-LDS loads (forced, and as the library's own
+    choice for a shape with whole 128 x 256 tiles); the forward SwiGLU epilogue does not exist there and is refused."""
+    g = gen(11)
+    dz = bf16_round(randn(g, M, K))
+    w2 = bf16_round(randn(g, fp, K, scale=0.05))
+    gu_ref = bf16_round(randn(g, M, 2 * fp))
+    dzd, w2d, gu = dev(dz, torch.bfloat16), dev(w2, torch.bfloat16), dev(gu_ref, torch.bfloat16)
+    dgu = torch.empty(M, 2 * fp, dtype=torch.bfloat16, device="cuda")
+    args = (B.GEMM_NT, B.EPI_DSWIGLU, M, fp, K, dzd.data_ptr(), K, w2d.data_ptr(), K, dgu.data_ptr(), 2 * fp, None, gu.data_ptr(), 2 * fp, None, 0, None)
+    if variant:
+        B.check(B.lib.oases_op_gemm_forced(variant, *args))
+    else:
+        assert B.lib.oases_op_gemm_variant(B.GEMM_NT, B.EPI_DSWIGLU, M, fp, K, 0) == 201128256
+        B.check(B.lib.oases_op_gemm(*args))
+    dF = dz.double() @ w2.double().t()
+    gs = gu_ref.double().reshape(M, fp // 32, 2, 32)
+    gst, ust = gs[:, :, 0].reshape(M, fp), gs[:, :, 1].reshape(M, fp)
+    assert_bf16_close(dgu.float(), interleave(dF * ust * ll.silu_grad(gst), dF * ll.silu(gst)), 1e-4, 1e-5)
+    if variant:
+        f = torch.empty(M, fp // 2, dtype=torch.bfloat16, device="cuda")
+        a = torch.zeros(M, K, dtype=torch.bfloat16, device="cuda")
+        w = torch.zeros(K, fp, dtype=torch.bfloat16, device="cuda")
+        assert B.lib.oases_op_gemm_forced(variant, B.GEMM_NN, B.EPI_SWIGLU, M, fp, K, a.data_ptr(), K, w.data_ptr(), fp, f.data_ptr(), fp // 2, None,
+                                          gu.data_ptr(), 2 * fp, None, 0, None) == B.EINVAL
+    torch.cuda.synchronize()
+
+
 def test_gemm_swiglu_argument_errors(B):
     a = torch.zeros(64, 64, dtype=torch.bfloat16, device="cuda")
     c = torch.zeros(64, 128, dtype=torch.bfloat16, device="cuda")
