@@ -14,6 +14,8 @@
 // and +8 of each 16-key step; the V^T operand comes from the LDS transpose read ds_read_b64_tr_b16).
 // dK/dV keeps S = Q*K^T un-transposed so a lane owns one key and P^T / dS^T are in A-operand position.
 // No atomics: dQ and dK/dV are separate passes, results are deterministic.
+#include <type_traits>
+
 #include "common.h"
 
 namespace oases {
@@ -406,15 +408,19 @@ __global__ __launch_bounds__(NT, 1) void attn_dq_kernel(AttnArgs a) {
         for (int e = 0; e < 4; e++) dp[4 * grp + e] = ((ww >> (8 * e)) & 0xffu) >= a.dthresh ? dp[4 * grp + e] * a.dscale : 0.f;
       }
     }
+    // only tiles on the diagonal or at the end of the sequence pay for the mask (a wave-uniform branch)
+    auto scores = [&](auto mask_c) {
 #pragma unroll
-    for (int i = 0; i < 16; i++) {
-      float ds = __builtin_amdgcn_exp2f(s[i] * a.scale_log2 - lse2) * (dp[i] - dl);
-      if (need_mask) {
-        int kvpos = kv0 + 8 * (i >> 2) + 4 * g + (i & 3);
-        if (kvpos >= a.seq || (CAUSAL && kvpos > qpos)) ds = 0.f;
+      for (int i = 0; i < 16; i++) {
+        float ds = __builtin_amdgcn_exp2f(s[i] * a.scale_log2 - lse2) * (dp[i] - dl);
+        if (decltype(mask_c)::value) {
+          int kvpos = kv0 + 8 * (i >> 2) + 4 * g + (i & 3);
+          if (kvpos >= a.seq || (CAUSAL && kvpos > qpos)) ds = 0.f;
+        }
+        s[i] = ds;
       }
-      s[i] = ds;
-    }
+    };
+    if (need_mask) scores(std::true_type{}); else scores(std::false_type{});
 #pragma unroll
     for (int j = 0; j < 2; j++) {
       bf16x8 db = pack8(s, 8 * j);
@@ -498,32 +504,36 @@ __global__ __launch_bounds__(NT, 1) void attn_dkv_kernel(AttnArgs a) {
       dp = MFMA(kc_frag<D>(ldo, ks, lane), vf[ks], dp);
     }
     const bool need_mask = (q0 + 32 > a.seq) || (CAUSAL && q0 < k_begin + 31);
+    // only tiles on the diagonal or at the end of the sequence pay for the mask (a wave-uniform branch)
+    auto scores = [&](auto mask_c) {
 #pragma unroll
-    for (int i4 = 0; i4 < 4; i4++) {
-      const int ql = 8 * i4 + 4 * g;  // 4 consecutive queries
-      f32x4 l4 = *reinterpret_cast<const f32x4*>(lstat + ql);
-      f32x4 d4 = *reinterpret_cast<const f32x4*>(lstat + 32 + ql);
-      Philox4 dw;
-      if (DROP) dw = attn_drop_block(a, (uint32_t)kpos >> 2, (uint32_t)(q0 + ql) >> 2, (uint32_t)(seq_idx * a.heads_total + a.head0 + head));
+      for (int i4 = 0; i4 < 4; i4++) {
+        const int ql = 8 * i4 + 4 * g;  // 4 consecutive queries
+        f32x4 l4 = *reinterpret_cast<const f32x4*>(lstat + ql);
+        f32x4 d4 = *reinterpret_cast<const f32x4*>(lstat + 32 + ql);
+        Philox4 dw;
+        if (DROP) dw = attn_drop_block(a, (uint32_t)kpos >> 2, (uint32_t)(q0 + ql) >> 2, (uint32_t)(seq_idx * a.heads_total + a.head0 + head));
 #pragma unroll
-      for (int e = 0; e < 4; e++) {
-        const int i = 4 * i4 + e;
-        const float p = __builtin_amdgcn_exp2f(s[i] * a.scale_log2 - l4[e]);
-        float dpe = dp[i], pv = p;  // pv: what multiplied V in forward
-        if (DROP) {  // this lane's key is byte (kpos mod 4) of the word of query e of the group
-          const bool keep = ((dw.v[e] >> (8 * (kpos & 3))) & 0xffu) >= a.dthresh;
-          dpe = keep ? dpe * a.dscale : 0.f;
-          pv = keep ? p * a.dscale : 0.f;
+        for (int e = 0; e < 4; e++) {
+          const int i = 4 * i4 + e;
+          const float p = __builtin_amdgcn_exp2f(s[i] * a.scale_log2 - l4[e]);
+          float dpe = dp[i], pv = p;  // pv: what multiplied V in forward
+          if (DROP) {  // this lane's key is byte (kpos mod 4) of the word of query e of the group
+            const bool keep = ((dw.v[e] >> (8 * (kpos & 3))) & 0xffu) >= a.dthresh;
+            dpe = keep ? dpe * a.dscale : 0.f;
+            pv = keep ? p * a.dscale : 0.f;
+          }
+          float ds = p * (dpe - d4[e]);
+          if (decltype(mask_c)::value) {
+            int qp = q0 + ql + e;
+            if (qp >= a.seq || (CAUSAL && kpos > qp)) { pv = 0.f; ds = 0.f; }   // select, never multiply: the rest may be NaN
+          }
+          s[i] = pv;
+          dp[i] = ds;
         }
-        float ds = p * (dpe - d4[e]);
-        if (need_mask) {
-          int qp = q0 + ql + e;
-          if (qp >= a.seq || (CAUSAL && kpos > qp)) { pv = 0.f; ds = 0.f; }   // select, never multiply: the rest may be NaN
-        }
-        s[i] = pv;
-        dp[i] = ds;
       }
-    }
+    };
+    if (need_mask) scores(std::true_type{}); else scores(std::false_type{});
 #pragma unroll
     for (int j = 0; j < 2; j++) {
       bf16x8 pa = pack8(s, 8 * j);
