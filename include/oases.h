@@ -256,8 +256,9 @@ int oases_op_gemm(int op, int epi, int M, int N, int K, const void *A, int lda, 
  * partial planes in the workspace; W = 1 if the waves of a workgroup split the k steps of a stage between them
  * (rectangular tiles only), e.g. 101128256 = 128x256 tiles, waves split k, one slice; W = 2 names the kernels that
  * load their operand tiles from global memory straight into LDS: 201256256 (256x256 tiles, four LDS stages of 32 k
- * columns; needs M % 256 == 0, N % 256 == 0, K % 32 == 0) and 201128256 (128x256 tiles, three LDS stages of 64 k columns,
- * waves split k; needs M % 128 == 0, N % 256 == 0, K % 64 == 0); one slice; no SwiGLU epilogue.
+ * columns; K % 32 == 0; an operand whose k index is the contiguous one -- A of NN and NT, B of NT -- must fill its tiles:
+ * M resp. N % 256 == 0) and 201128256 (128x256 tiles, three LDS stages of 64 k columns, waves split k; K % 64 == 0;
+ * any M, N the GEMM accepts); one slice; no SwiGLU epilogue.
  * Host only; used to group per-operator timings by kernel. */
 int oases_op_gemm_variant(int op, int epi, int M, int N, int K, size_t workspace_bytes);
 /* oases_op_gemm on the instantiation `variant` names (encoding above) instead of the one the library would choose:
@@ -274,8 +275,8 @@ int oases_op_gemm_forced(int variant, int op, int epi, int M, int N, int K, cons
  * 16-byte aligned; lda, ldb multiples of 8, ldc of 4.  The tiles of the second problem follow those of the first in the
  * grid, so that two launches that would each leave CUs idle (or need k slices to fill them) share one round of
  * workgroups: the backward pass issues the attention block's two weight gradients (Sec. II: projection and QKV) this way
- * when oases_op_gemm_tn_pair_wins says so.  Needs M_i % 128 == 0, N_i % 256 == 0, K % 64 == 0: EINVAL otherwise, before
- * any launch.  Each C_i gets exactly what oases_op_gemm_forced(201128256, TN, ...) gives it. */
+ * when oases_op_gemm_tn_pair_wins says so.  Needs whole tiles, M_i % 128 == 0, N_i % 256 == 0, and K % 64 == 0: EINVAL
+ * otherwise, before any launch.  Each C_i gets exactly what oases_op_gemm_forced(201128256, TN, ...) gives it. */
 int oases_op_gemm_tn_pair(int K, int M0, int N0, const void *A0, int lda0, const void *B0, int ldb0, void *C0,
                           int ldc0, int M1, int N1, const void *A1, int lda1, const void *B1, int ldb1, void *C1,
                           int ldc1, void *stream);

@@ -540,14 +540,19 @@ __device__ __forceinline__ void lds_wait(u32x4 (&a)[4], u32x4 (&b)[4]) {
 // [32 k][256 rows] = 512-byte k rows, chunk c of k row kr at slot c ^ 4*(kr%4) (the 4 k rows x 64 bytes that 32 lanes of
 // a transpose read touch in one LDS cycle then fall on 16 different chunk positions mod 16).  One DMA instruction of a wave writes 1 KB
 // of the tile, lane i the 16 bytes at i*16: the swizzle is applied to the global address the lane fetches.
+// `extent`: rows of the operand's free dimension (M of A, N of B).  A row-indexed operand may end inside the tile
+// (extent a multiple of 8, so whole 16-byte chunks): chunks beyond it are fetched from column 0 instead -- valid memory,
+// and the rows / columns of C they feed are never stored.  A k-major operand must fill its tiles.
 template <bool KC>
-__device__ __forceinline__ const char* dtl_src(const uint16_t* base, int ld, int r0, int q, int lane) {
+__device__ __forceinline__ const char* dtl_src(const uint16_t* base, int ld, int r0, int q, int lane, int extent) {
   if (KC) {
     const int row = 16 * q + (lane >> 2), chunk = (lane & 3) ^ ((row >> 2) & 3);
     return reinterpret_cast<const char*>(base + (size_t)(r0 + row) * ld + chunk * 8);
   }
   const int kr = 2 * q + (lane >> 5), cc = (lane & 31) ^ (4 * (kr & 3));
-  return reinterpret_cast<const char*>(base + (size_t)kr * ld + r0 + cc * 8);
+  int col = r0 + cc * 8;
+  if (col >= extent) col = 0;
+  return reinterpret_cast<const char*>(base + (size_t)kr * ld + col);
 }
 // per-lane LDS offsets of the fragment reads of a wave's 128-row part starting at tile row R0
 template <bool KC>
@@ -587,7 +592,7 @@ __device__ __forceinline__ void dtl_read_frags(u32x4 (&f)[4], uint32_t base, con
   }
 }
 
-template <bool A_KC, bool B_KC, int EPI>
+template <bool A_KC, bool B_KC, int EPI, bool FULL>
 __global__ __launch_bounds__(256) void gemm_dtl_kernel(GemmArgs g) {
   __shared__ __attribute__((aligned(1024))) char lds[NSD * kDtlStage];
   int tile_m, tile_n;
@@ -595,7 +600,6 @@ __global__ __launch_bounds__(256) void gemm_dtl_kernel(GemmArgs g) {
   const int m0 = tile_m * 256, n0 = tile_n * 256;
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6), wm = wave >> 1, wn = wave & 1;
   constexpr int WGM = 2, WGN = 2, WTM = 128, WTN = 128, TM = 4, TN = 4;
-  constexpr bool FULL = true;
   const int nk = g.K / BKD;
 
   f32x16 acc[TM][TN];
@@ -608,8 +612,8 @@ __global__ __launch_bounds__(256) void gemm_dtl_kernel(GemmArgs g) {
 
   // DMA sources of this lane: instruction j of this wave is instruction q = 4*wave + j of the operand tile
   // (the swizzle of an MC tile depends on the parity of q: one source pointer for even, one for odd instructions)
-  const char* srcA[2] = {dtl_src<A_KC>(g.A, g.lda, m0, 4 * wave, lane), dtl_src<A_KC>(g.A, g.lda, m0, 4 * wave + 1, lane)};
-  const char* srcB[2] = {dtl_src<B_KC>(g.B, g.ldb, n0, 4 * wave, lane), dtl_src<B_KC>(g.B, g.ldb, n0, 4 * wave + 1, lane)};
+  const char* srcA[2] = {dtl_src<A_KC>(g.A, g.lda, m0, 4 * wave, lane, g.M), dtl_src<A_KC>(g.A, g.lda, m0, 4 * wave + 1, lane, g.M)};
+  const char* srcB[2] = {dtl_src<B_KC>(g.B, g.ldb, n0, 4 * wave, lane, g.N), dtl_src<B_KC>(g.B, g.ldb, n0, 4 * wave + 1, lane, g.N)};
   const size_t stepA_q = A_KC ? (size_t)32 * g.lda * 2 : (size_t)4 * g.lda * 2;   // two instructions on: 32 rows resp. 4 k rows
   const size_t stepB_q = B_KC ? (size_t)32 * g.ldb * 2 : (size_t)4 * g.ldb * 2;
   const size_t stepA_k = A_KC ? (size_t)BKD * 2 : (size_t)BKD * g.lda * 2;          // next k tile
@@ -707,14 +711,16 @@ constexpr int BKR = 64, NSR = 3;
 constexpr int kRectA = BKR * 128 * 2, kRectB = BKR * 256 * 2, kRectStage = kRectA + kRectB;
 
 template <bool KC, int R>
-__device__ __forceinline__ const char* rect_src(const uint16_t* base, int ld, int r0, int q, int lane) {
-  if (KC) {
+__device__ __forceinline__ const char* rect_src(const uint16_t* base, int ld, int r0, int q, int lane, int extent) {
+  if (KC) {  // rows beyond the operand's extent: the last row again (valid memory; what they feed is never stored)
     const int row = 8 * q + (lane >> 3), chunk = (lane & 7) ^ ((row >> 1) & 7);
-    return reinterpret_cast<const char*>(base + (size_t)(r0 + row) * ld + chunk * 8);
+    return reinterpret_cast<const char*>(base + (size_t)min(r0 + row, extent - 1) * ld + chunk * 8);
   }
   constexpr int CPR = R / 8, KPI = 64 / CPR;
   const int kr = KPI * q + lane / CPR, cc = (lane % CPR) ^ (4 * (kr & 3));
-  return reinterpret_cast<const char*>(base + (size_t)kr * ld + r0 + cc * 8);
+  int col = r0 + cc * 8;
+  if (col >= extent) col = 0;  // beyond a row-indexed operand's extent: see dtl_src
+  return reinterpret_cast<const char*>(base + (size_t)kr * ld + col);
 }
 // per-lane LDS offsets of the fragment reads of a wave's 128-row part starting at tile row R0, for the k half wk of a
 // tile.  KC: off[kk], k step kk of the half (fragment i adds 32 rows = 4096 bytes); MC: off[i], fragment i (k step kk
@@ -758,7 +764,7 @@ constexpr int kRectExchange = 128 * 256 * 4;
 constexpr int kRectLds = NSR * kRectStage > kRectExchange ? NSR * kRectStage : kRectExchange;
 
 // one 128 x 256 tile: workgroup `pid` of the tiles_m x tiles_n tiles of problem g; lds: kRectLds bytes, 1024-byte aligned
-template <bool A_KC, bool B_KC, int EPI>
+template <bool A_KC, bool B_KC, int EPI, bool FULL>
 __device__ __forceinline__ void dtl_rect_tile(const GemmArgs& g, int pid, char* lds) {
   int tile_m, tile_n;
   tile_of_workgroup(pid, g.tiles_m, g.tiles_n, tile_m, tile_n);
@@ -775,22 +781,24 @@ __device__ __forceinline__ void dtl_rect_tile(const GemmArgs& g, int pid, char* 
 #pragma unroll
       for (int e = 0; e < 16; e++) acc[i][j][e] = 0.f;
 
-  // this wave's DMA instructions of a tile: A instructions 4*wave .. 4*wave+3, B instructions 8*wave .. 8*wave+7; one
-  // source pointer for the even and one for the odd instructions of an operand
-  const char* srcA[2] = {rect_src<A_KC, 128>(g.A, g.lda, m0, 4 * wave, lane), rect_src<A_KC, 128>(g.A, g.lda, m0, 4 * wave + 1, lane)};
-  const char* srcB[2] = {rect_src<B_KC, 256>(g.B, g.ldb, n0, 8 * wave, lane), rect_src<B_KC, 256>(g.B, g.ldb, n0, 8 * wave + 1, lane)};
-  // two instructions on: 16 rows (KC), 8 k rows (MC, 128 rows wide), 4 k rows (MC, 256 rows wide); next k tile
-  const size_t stepA_2 = (size_t)(A_KC ? 16 : 8) * g.lda * 2, stepB_2 = (size_t)(B_KC ? 16 : 4) * g.ldb * 2;
-  const size_t stepA_k = A_KC ? (size_t)BKR * 2 : (size_t)BKR * g.lda * 2, stepB_k = B_KC ? (size_t)BKR * 2 : (size_t)BKR * g.ldb * 2;
+  // this wave's DMA instructions of a tile: A instructions 4*wave .. 4*wave+3, B instructions 8*wave .. 8*wave+7, one
+  // source pointer each (rows or chunks beyond an operand's extent are redirected per instruction)
+  const char* srcA[4];
+  const char* srcB[8];
+#pragma unroll
+  for (int j = 0; j < 4; j++) srcA[j] = rect_src<A_KC, 128>(g.A, g.lda, m0, 4 * wave + j, lane, g.M);
+#pragma unroll
+  for (int j = 0; j < 8; j++) srcB[j] = rect_src<B_KC, 256>(g.B, g.ldb, n0, 8 * wave + j, lane, g.N);
+  const size_t stepA_k = A_KC ? (size_t)BKR * 2 : (size_t)BKR * g.lda * 2, stepB_k = B_KC ? (size_t)BKR * 2 : (size_t)BKR * g.ldb * 2;  // next k tile
   typedef const void __attribute__((address_space(1))) * gptr_t;
   typedef void OASES_LDS* lptr_t;
   auto issue = [&](int t) {
     char* st = lds + (t % NSR) * kRectStage;
 #pragma unroll
     for (int j = 0; j < 4; j++) {
-      __builtin_amdgcn_global_load_lds((gptr_t)(srcA[j & 1] + (size_t)t * stepA_k + (j >> 1) * stepA_2), (lptr_t)(st + (4 * wave + j) * 1024), 16, 0, 0);
-      __builtin_amdgcn_global_load_lds((gptr_t)(srcB[0] + (size_t)t * stepB_k + j * stepB_2), (lptr_t)(st + kRectA + (8 * wave + 2 * j) * 1024), 16, 0, 0);
-      __builtin_amdgcn_global_load_lds((gptr_t)(srcB[1] + (size_t)t * stepB_k + j * stepB_2), (lptr_t)(st + kRectA + (8 * wave + 2 * j + 1) * 1024), 16, 0, 0);
+      __builtin_amdgcn_global_load_lds((gptr_t)(srcA[j] + (size_t)t * stepA_k), (lptr_t)(st + (4 * wave + j) * 1024), 16, 0, 0);
+      __builtin_amdgcn_global_load_lds((gptr_t)(srcB[2 * j] + (size_t)t * stepB_k), (lptr_t)(st + kRectA + (8 * wave + 2 * j) * 1024), 16, 0, 0);
+      __builtin_amdgcn_global_load_lds((gptr_t)(srcB[2 * j + 1] + (size_t)t * stepB_k), (lptr_t)(st + kRectA + (8 * wave + 2 * j + 1) * 1024), 16, 0, 0);
     }
   };
 
@@ -880,7 +888,7 @@ __device__ __forceinline__ void dtl_rect_tile(const GemmArgs& g, int pid, char* 
 #pragma unroll
           for (int e = 0; e < 4; e++) a[4 * q + e] += o[e];
         }
-        epilogue_tile<EPI, true>(g, m0 + (H * HM + i) * 32, n0 + wn * 128 + j * 32, lane, a);
+        epilogue_tile<EPI, FULL>(g, m0 + (H * HM + i) * 32, n0 + wn * 128 + j * 32, lane, a);
       }
   };
   if (wk == 0) hand_over(std::integral_constant<int, 1>{}); else hand_over(std::integral_constant<int, 0>{});
@@ -888,10 +896,10 @@ __device__ __forceinline__ void dtl_rect_tile(const GemmArgs& g, int pid, char* 
   if (wk == 0) finish(std::integral_constant<int, 0>{}); else finish(std::integral_constant<int, 1>{});
 }
 
-template <bool A_KC, bool B_KC, int EPI>
+template <bool A_KC, bool B_KC, int EPI, bool FULL>
 __global__ __launch_bounds__(256) void gemm_dtl_rect_kernel(GemmArgs g) {
   __shared__ __attribute__((aligned(1024))) char lds[kRectLds];
-  dtl_rect_tile<A_KC, B_KC, EPI>(g, blockIdx.x, lds);
+  dtl_rect_tile<A_KC, B_KC, EPI, FULL>(g, blockIdx.x, lds);
 }
 
 // Two weight-gradient contractions over the same K rows in one launch: the tiles of the second problem follow those of
@@ -899,8 +907,8 @@ __global__ __launch_bounds__(256) void gemm_dtl_rect_kernel(GemmArgs g) {
 __global__ __launch_bounds__(256) void gemm_dtl_rect_pair_kernel(GemmArgs g0, GemmArgs g1) {
   __shared__ __attribute__((aligned(1024))) char lds[kRectLds];
   const int first = g0.tiles_m * g0.tiles_n;
-  if ((int)blockIdx.x < first) dtl_rect_tile<false, false, EPI_ACC_F32>(g0, blockIdx.x, lds);
-  else dtl_rect_tile<false, false, EPI_ACC_F32>(g1, blockIdx.x - first, lds);
+  if ((int)blockIdx.x < first) dtl_rect_tile<false, false, EPI_ACC_F32, true>(g0, blockIdx.x, lds);
+  else dtl_rect_tile<false, false, EPI_ACC_F32, true>(g1, blockIdx.x - first, lds);
 }
 
 // split-K second pass: C = epilogue(sum over slices of the fp32 partial planes), slices added in index order
@@ -972,8 +980,17 @@ int launch_one(const GemmArgs& g0, int ksplit, float* ws, hipStream_t s) {
 struct TileChoice { int bm, bn, ksplit; bool wave_ksplit; bool dtl = false; };
 // per kind of contraction (0: NN, 1: NT, 2: TN, 3: NN with the bias+GeLU epilogue): whether the rectangular tiles
 // split k between waves, and the sustained rates of the four block tiles
-bool dtl_fits(int M, int N, int K) { return M % 256 == 0 && N % 256 == 0 && K % BKD == 0 && K >= BKD; }
-bool dtl_rect_fits(int M, int N, int K) { return M % 128 == 0 && N % 256 == 0 && K % BKR == 0 && K >= BKR; }
+// Shapes the direct-to-LDS kernels cover, per kind of contraction (0, 3: NN, 1: NT, 2: TN): whole k tiles; in the
+// 256 x 256 kernel a k-major operand must fill its tiles and a row-indexed one (A of TN; B of NN and TN) may end inside
+// its last tile; in the 128 x 256 kernel both may.
+bool dtl_fits(int kind, int M, int N, int K) {
+  return (kind == 2 || M % 256 == 0) && (kind != 1 || N % 256 == 0) && M % 8 == 0 && N % 8 == 0 && K % BKD == 0 && K >= BKD;
+}
+bool dtl_rect_fits(int kind, int M, int N, int K) {  // the 128 x 256 kernel redirects rows of a k-major operand too
+  (void)kind;
+  return M % 8 == 0 && N % 8 == 0 && K % BKR == 0 && K >= BKR;
+}
+bool dtl_rect_whole(int M, int N, int K) { return M % 128 == 0 && N % 256 == 0 && K % BKR == 0 && K >= BKR; }
 struct KindTable { bool wave_ksplit; float r256x256, r128x256, r256x128, r128x128; };
 const KindTable g_kinds[4] = {{true, 1150.f, 1000.f, 960.f, 740.f}, {true, 1150.f, 1000.f, 960.f, 740.f},
                         {true, 1150.f, 1000.f, 960.f, 740.f}, {false, 1150.f, 880.f, 900.f, 740.f}};
@@ -999,8 +1016,8 @@ TileChoice pick_tile(int kind, int epi, int M, int N, int K, size_t ws_bytes) {
   // on its staged 256 x 128 tiles: faster inside a step, although slower on cold operands in isolation.)
   if (best.ksplit == 1 && epi != EPI_SWIGLU) {
     const bool rect = best.bm == 128 && best.bn == 256 && kind != 3;
-    if (best.bm == 256 && best.bn == 256 && (kind == 2 || kind == 0) && dtl_fits(M, N, K)) best.dtl = true;
-    if (rect && (kind != 1 || epi != EPI_F32) && dtl_rect_fits(M, N, K)) best = TileChoice{128, 256, 1, true, true};
+    if (best.bm == 256 && best.bn == 256 && (kind == 2 || kind == 0) && dtl_fits(kind, M, N, K)) best.dtl = true;
+    if (rect && (kind != 1 || epi != EPI_F32) && dtl_rect_fits(kind, M, N, K)) best = TileChoice{128, 256, 1, true, true};
   }
   return best;
 }
@@ -1010,14 +1027,14 @@ int encode_variant(const TileChoice& t) {
   return (t.dtl ? 200000000 : rect && t.wave_ksplit ? 100000000 : 0) + t.ksplit * 1000000 + t.bm * 1000 + t.bn;
 }
 // variant -> TileChoice; false if no such instantiation exists or the k slices do not fit the problem / workspace
-bool decode_variant(int variant, int M, int N, int K, size_t ws_bytes, TileChoice* t) {
+bool decode_variant(int variant, int kind, int M, int N, int K, size_t ws_bytes, TileChoice* t) {
   if (variant <= 0) return false;
   const int wk = variant / 100000000, S = variant / 1000000 % 100, bm = variant / 1000 % 1000, bn = variant % 1000;
   const bool square = (bm == 256 && bn == 256) || (bm == 128 && bn == 128), rect = (bm == 256 && bn == 128) || (bm == 128 && bn == 256);
   if (wk == 2) {  // direct-to-LDS kernels: whole 256 x 256 tiles, or 128 x 256 tiles; no k slices
     if (S != 1) return false;
-    if (bm == 256 && bn == 256 && dtl_fits(M, N, K)) { *t = TileChoice{256, 256, 1, false, true}; return true; }
-    if (bm == 128 && bn == 256 && dtl_rect_fits(M, N, K)) { *t = TileChoice{128, 256, 1, true, true}; return true; }
+    if (bm == 256 && bn == 256 && dtl_fits(kind, M, N, K)) { *t = TileChoice{256, 256, 1, false, true}; return true; }
+    if (bm == 128 && bn == 256 && dtl_rect_fits(kind, M, N, K)) { *t = TileChoice{128, 256, 1, true, true}; return true; }
     return false;
   }
   if (wk > 1 || !(square || rect) || (wk == 1 && !rect) || S < 1 || S > 8) return false;
@@ -1036,7 +1053,7 @@ int launch_shape(const GemmArgs& g, float* ws, size_t ws_bytes, int forced_varia
   TileChoice t;
   if (forced_variant == 0) {
     t = pick_tile(kind, EPI, g.M, g.N, g.K, ws ? ws_bytes : 0);
-  } else if (!decode_variant(forced_variant, g.M, g.N, g.K, ws ? ws_bytes : 0, &t)) {
+  } else if (!decode_variant(forced_variant, kind, g.M, g.N, g.K, ws ? ws_bytes : 0, &t)) {
     set_error("gemm: variant %d does not exist or does not fit M=%d N=%d K=%d with %zu workspace bytes", forced_variant, g.M, g.N, g.K, ws ? ws_bytes : (size_t)0);
     return OASES_EINVAL;
   }
@@ -1044,19 +1061,24 @@ int launch_shape(const GemmArgs& g, float* ws, size_t ws_bytes, int forced_varia
     if constexpr (EPI == EPI_SWIGLU) {
       set_error("gemm: the direct-to-LDS kernels have no SwiGLU epilogue");
       return OASES_EINVAL;
-    } else if (t.bm == 128) {
-      GemmArgs d = g;
-      d.tiles_m = g.M / 128;
-      d.tiles_n = g.N / 256;
-      hipLaunchKernelGGL((gemm_dtl_rect_kernel<A_KC, B_KC, EPI>), dim3(d.tiles_m * d.tiles_n), dim3(256), 0, s, d);
-      OASES_LAUNCH_CHECK("gemm_dtl_rect_kernel");
-      return 0;
     } else {
+      // the 256 x 256 instantiation with bounds checks in the epilogue exists only where a tile can be ragged
+      constexpr bool kCanBeRagged = !A_KC || !B_KC;
+      const int bm = t.bm;  // 128 or 256; both kernels have 256-column tiles
       GemmArgs d = g;
-      d.tiles_m = g.M / 256;
-      d.tiles_n = g.N / 256;
-      hipLaunchKernelGGL((gemm_dtl_kernel<A_KC, B_KC, EPI>), dim3(d.tiles_m * d.tiles_n), dim3(256), 0, s, d);
-      OASES_LAUNCH_CHECK("gemm_dtl_kernel");
+      d.tiles_m = (g.M + bm - 1) / bm;
+      d.tiles_n = (g.N + 255) / 256;
+      const dim3 grid(d.tiles_m * d.tiles_n);
+      const bool whole = g.M % bm == 0 && g.N % 256 == 0;
+      if (!whole && bm == 256 && !kCanBeRagged) { set_error("gemm: direct-to-LDS kernel on a shape it does not cover"); return OASES_EINVAL; }
+      if (bm == 128) {
+        if (whole) hipLaunchKernelGGL((gemm_dtl_rect_kernel<A_KC, B_KC, EPI, true>), grid, dim3(256), 0, s, d);
+        else hipLaunchKernelGGL((gemm_dtl_rect_kernel<A_KC, B_KC, EPI, false>), grid, dim3(256), 0, s, d);
+      } else {
+        if (whole) hipLaunchKernelGGL((gemm_dtl_kernel<A_KC, B_KC, EPI, true>), grid, dim3(256), 0, s, d);
+        else if constexpr (kCanBeRagged) hipLaunchKernelGGL((gemm_dtl_kernel<A_KC, B_KC, EPI, false>), grid, dim3(256), 0, s, d);
+      }
+      OASES_LAUNCH_CHECK("gemm direct-to-LDS kernel");
       return 0;
     }
   }
@@ -1073,7 +1095,7 @@ int launch_shape(const GemmArgs& g, float* ws, size_t ws_bytes, int forced_varia
 }  // namespace
 
 bool gemm_tn_pair_wins(int K, int M0, int N0, int M1, int N1) {
-  if (M0 <= 0 || N0 <= 0 || M1 <= 0 || N1 <= 0 || !dtl_rect_fits(M0, N0, K) || !dtl_rect_fits(M1, N1, K)) return false;
+  if (M0 <= 0 || N0 <= 0 || M1 <= 0 || N1 <= 0 || !dtl_rect_whole(M0, N0, K) || !dtl_rect_whole(M1, N1, K)) return false;
   const long t0 = (long)(M0 / 128) * (N0 / 256), t1 = (long)(M1 / 128) * (N1 / 256);
   // enough tiles to be worth whole 128 x 256 tiles at all, and fewer rounds of 256 workgroups together than apart
   return t0 + t1 > 128 && (t0 + t1 + 255) / 256 < (t0 + 255) / 256 + (t1 + 255) / 256;
@@ -1081,7 +1103,7 @@ bool gemm_tn_pair_wins(int K, int M0, int N0, int M1, int N1) {
 
 int launch_gemm_tn_pair(int K, int M0, int N0, const void* A0, int lda0, const void* B0, int ldb0, void* C0, int ldc0, int M1, int N1,
                         const void* A1, int lda1, const void* B1, int ldb1, void* C1, int ldc1, hipStream_t s) {
-  if (K <= 0 || M0 <= 0 || N0 <= 0 || M1 <= 0 || N1 <= 0 || !dtl_rect_fits(M0, N0, K) || !dtl_rect_fits(M1, N1, K)) {
+  if (K <= 0 || M0 <= 0 || N0 <= 0 || M1 <= 0 || N1 <= 0 || !dtl_rect_whole(M0, N0, K) || !dtl_rect_whole(M1, N1, K)) {
     set_error("gemm_tn_pair: needs M %% 128 == 0, N %% 256 == 0, K %% 64 == 0 for both problems (got K=%d, %dx%d and %dx%d)", K, M0, N0, M1, N1);
     return OASES_EINVAL;
   }

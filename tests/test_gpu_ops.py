@@ -273,7 +273,7 @@ def test_gemm_direct_to_lds_variant(B, lo, op, M, N, K):
                                            (201128256, 640, 256, 4096), (201128256, 1152, 1024, 1088), (201128256, 128, 512, 320)])
 @pytest.mark.parametrize("op", ["NN", "NT", "TN"])
 def test_gemm_direct_to_lds_rect_variant(B, lo, op, variant, M, N, K):
-    """The kernel with 128 x 256 tiles fed by direct-to-LDS loads (variant 201128256; whole tiles, K % 64 == 0): one to 64
+    """The kernel with 128 x 256 tiles fed by direct-to-LDS loads (variant 201128256; K % 64 == 0), here on whole tiles: one to 64
     k tiles (prologue-only, drain and steady-state paths of its three-stage pipeline), odd and even tile counts, every
     contraction form, a padded leading dimension of C, and the epilogues it supports."""
     g = gen(M + N + K)
@@ -294,8 +294,6 @@ def test_gemm_direct_to_lds_rect_variant(B, lo, op, variant, M, N, K):
     # shapes it does not cover are refused on the host
     assert B.lib.oases_op_gemm_forced(variant, opc, B.EPI_F32, M, N, K - 32, ad.data_ptr(), lda, bd.data_ptr(), ldb, c.data_ptr(), ldc, None, None, 0,
                                       None, 0, None) == B.EINVAL
-    assert B.lib.oases_op_gemm_forced(variant, opc, B.EPI_F32, M, N - variant % 1000 // 2, K, ad.data_ptr(), lda, bd.data_ptr(), ldb, c.data_ptr(), ldc,
-                                      None, None, 0, None, 0, None) == B.EINVAL
     if op == "TN":
         return
     bias = dev(0.1 * randn(g, N), torch.float32)
@@ -318,6 +316,58 @@ def test_gemm_direct_to_lds_rect_variant(B, lo, op, variant, M, N, K):
         B.check(B.lib.oases_op_gemm_forced(variant, opc, B.EPI_DGELU, M, N, K, ad.data_ptr(), lda, bd.data_ptr(), ldb, cb.data_ptr(), N,
                                            None, pre.data_ptr(), N, None, 0, None))
         assert_bf16_close(cb.float(), ref * lo.gelu_grad(pre.float().cpu().double()), 1e-4, 1e-5)
+
+
+@pytest.mark.parametrize("variant,op,M,N,K", [(201128256, "TN", 136, 264, 64), (201128256, "TN", 1376, 1000, 192), (201128256, "TN", 88, 8, 128),
+                                              (201128256, "NN", 256, 264, 128), (201128256, "NN", 392, 1000, 1088), (201128256, "NN", 8, 8, 64),
+                                              (201128256, "NT", 136, 264, 64), (201128256, "NT", 1000, 1376, 320), (201128256, "NT", 72, 40, 128),
+                                              (0, "NT", 4096, 1376, 4096), (201256256, "TN", 264, 520, 96),
+                                              (201256256, "TN", 1000, 1376, 160), (201256256, "TN", 8, 8, 32), (201256256, "NN", 512, 776, 224),
+                                              (0, "TN", 1376, 4096, 2048), (0, "TN", 4096, 2752, 1024)])
+def test_gemm_direct_to_lds_ragged_edges(B, lo, variant, op, M, N, K):
+    """Operands may end inside the last tile of the direct-to-LDS kernels (128 x 256: any operand; 256 x 256: a row-indexed
+    one, i.e. A of the TN form and B of the NN and TN forms): the rows / chunks beyond them are fetched from valid memory
+    and what they feed is never stored.  Forced on both kernels, and as the library's own choice for LLaMA-7B's FFN
+    weight-gradient and input-gradient shapes.  C sits inside a larger buffer whose other bytes must stay as they were."""
+    g = gen(M + N + K)
+    a, b = bf16_round(randn(g, M, K)), bf16_round(randn(g, K, N, scale=0.05))
+    ref = a @ b
+    opc = {"NN": B.GEMM_NN, "NT": B.GEMM_NT, "TN": B.GEMM_TN}[op]
+    ad = dev(a if op != "TN" else a.t().contiguous(), torch.bfloat16)
+    bd = dev(b if op != "NT" else b.t().contiguous(), torch.bfloat16)
+    lda, ldb = (K if op != "TN" else M), (N if op != "NT" else K)
+    ldc = N + 40
+    guard = 3                                               # rows of C's buffer before and after the matrix
+    c0 = randn(g, M + 2 * guard, ldc).float()
+    c = dev(c0, torch.float32)
+    cptr = c.data_ptr() + guard * ldc * 4
+    if variant:
+        B.check(B.lib.oases_op_gemm_forced(variant, opc, B.EPI_F32, M, N, K, ad.data_ptr(), lda, bd.data_ptr(), ldb, cptr, ldc, None, None, 0, None, 0, None))
+    else:
+        assert B.lib.oases_op_gemm_variant(opc, B.EPI_DGELU if op == "NT" else B.EPI_F32, M, N, K, 0) >= 200000000
+        B.check(B.lib.oases_op_gemm(opc, B.EPI_F32, M, N, K, ad.data_ptr(), lda, bd.data_ptr(), ldb, cptr, ldc, None, None, 0, None, 0, None))
+    out = c.cpu()
+    body = out[guard:guard + M].double()
+    assert rel_err(body[:, :N], ref + (c0[guard:guard + M, :N].double() if op == "TN" else 0.0)) < 1e-5, (op, M, N, K)
+    assert torch.equal(body[:, N:], c0[guard:guard + M, N:].double())
+    assert torch.equal(out[:guard], c0[:guard]) and torch.equal(out[guard + M:], c0[guard + M:])
+    if op == "NN":                                          # a fused epilogue on a ragged tile
+        bias = dev(0.1 * randn(g, N), torch.float32)
+        cb = torch.full((M, N + 8), 7.0, dtype=torch.bfloat16, device="cuda")
+        aux = torch.full((M, N + 8), 7.0, dtype=torch.bfloat16, device="cuda")
+        B.check(B.lib.oases_op_gemm_forced(variant, opc, B.EPI_BIAS_GELU, M, N, K, ad.data_ptr(), lda, bd.data_ptr(), N, cb.data_ptr(), N + 8,
+                                           bias.data_ptr(), aux.data_ptr(), N + 8, None, 0, None))
+        z = ref + bias.cpu().double()
+        assert_bf16_close(aux[:, :N].float(), z, 1e-5, 2e-6 * float(z.abs().max()))
+        assert_bf16_close(cb[:, :N].float(), lo.gelu_fwd(z), 1e-4, 1e-5)
+        assert bool((cb[:, N:] == 7.0).all()) and bool((aux[:, N:] == 7.0).all())
+    if op == "NT":                                          # (for variant 0: the launch the library itself picks for this epilogue)
+        pre = dev(bf16_round(randn(g, M, N)), torch.bfloat16)
+        cb = torch.full((M, N + 8), 7.0, dtype=torch.bfloat16, device="cuda")
+        args = (opc, B.EPI_DGELU, M, N, K, ad.data_ptr(), lda, bd.data_ptr(), ldb, cb.data_ptr(), N + 8, None, pre.data_ptr(), N, None, 0, None)
+        B.check(B.lib.oases_op_gemm_forced(variant, *args) if variant else B.lib.oases_op_gemm(*args))
+        assert_bf16_close(cb[:, :N].float(), ref * lo.gelu_grad(pre.float().cpu().double()), 1e-4, 1e-5)
+        assert bool((cb[:, N:] == 7.0).all())
 
 
 @pytest.mark.parametrize("K,M0,N0,M1,N1", [(64, 128, 256, 128, 256), (192, 256, 512, 384, 256), (4096, 128, 768, 640, 256), (1088, 512, 1024, 1152, 768)])
