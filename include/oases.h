@@ -258,7 +258,7 @@ int oases_op_gemm(int op, int epi, int M, int N, int K, const void *A, int lda, 
  * load their operand tiles from global memory straight into LDS: 201256256 (256x256 tiles, four LDS stages of 32 k
  * columns; K % 32 == 0; an operand whose k index is the contiguous one -- A of NN and NT, B of NT -- must fill its tiles:
  * M resp. N % 256 == 0) and 201128256 (128x256 tiles, three LDS stages of 64 k columns, waves split k; K % 64 == 0;
- * any M, N the GEMM accepts); one slice; no SwiGLU epilogue.
+ * any M, N the GEMM accepts; no forward SwiGLU epilogue); one slice.
  * Host only; used to group per-operator timings by kernel. */
 int oases_op_gemm_variant(int op, int epi, int M, int N, int K, size_t workspace_bytes);
 /* oases_op_gemm on the instantiation `variant` names (encoding above) instead of the one the library would choose:

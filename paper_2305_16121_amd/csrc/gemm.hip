@@ -693,7 +693,14 @@ __global__ __launch_bounds__(256) void gemm_dtl_kernel(GemmArgs g) {
 #pragma unroll
   for (int i = 0; i < TM; i++)
 #pragma unroll
-    for (int j = 0; j < TN; j++) emit(i, j, acc[i][j]);
+    for (int j = 0; j < TN; j += 2) {
+      if constexpr (EPI == EPI_SWIGLU) {  // tiles j (gate) and j+1 (up) of the interleaved 64-column blocks
+        epilogue_tile_swiglu<FULL>(g, m0 + wm * WTM + i * 32, n0 + wn * WTN + j * 32, lane, acc[i][j], acc[i][j + 1]);
+      } else {
+        emit(i, j, acc[i][j]);
+        emit(i, j + 1, acc[i][j + 1]);
+      }
+    }
 }
 
 // =================================================================================================
@@ -1014,9 +1021,9 @@ TileChoice pick_tile(int kind, int epi, int M, int N, int K, size_t ws_bytes) {
   // 256 x 256 for TN and plain NN (an operand that goes through the transposing LDS read costs the staged kernel
   // conflicting LDS stores); 128 x 256 for TN, NN and, except with the plain fp32 store, NT.  (The bias+GeLU forward stays
   // on its staged 256 x 128 tiles: faster inside a step, although slower on cold operands in isolation.)
-  if (best.ksplit == 1 && epi != EPI_SWIGLU) {
+  if (best.ksplit == 1) {
     const bool rect = best.bm == 128 && best.bn == 256 && kind != 3;
-    if (best.bm == 256 && best.bn == 256 && (kind == 2 || kind == 0) && dtl_fits(kind, M, N, K)) best.dtl = true;
+    if (best.bm == 256 && best.bn == 256 && (kind == 2 || kind == 0 || epi == EPI_SWIGLU) && dtl_fits(kind, M, N, K)) best.dtl = true;
     if (rect && (kind != 1 || epi != EPI_F32) && dtl_rect_fits(kind, M, N, K)) best = TileChoice{128, 256, 1, true, true};
   }
   return best;
@@ -1058,8 +1065,8 @@ int launch_shape(const GemmArgs& g, float* ws, size_t ws_bytes, int forced_varia
     return OASES_EINVAL;
   }
   if (t.dtl) {
-    if constexpr (EPI == EPI_SWIGLU) {
-      set_error("gemm: the direct-to-LDS kernels have no SwiGLU epilogue");
+    if (EPI == EPI_SWIGLU && t.bm == 128) {
+      set_error("gemm: the 128x256 direct-to-LDS kernel has no SwiGLU epilogue");
       return OASES_EINVAL;
     } else {
       // the 256 x 256 instantiation with bounds checks in the epilogue exists only where a tile can be ragged
@@ -1072,8 +1079,10 @@ int launch_shape(const GemmArgs& g, float* ws, size_t ws_bytes, int forced_varia
       const bool whole = g.M % bm == 0 && g.N % 256 == 0;
       if (!whole && bm == 256 && !kCanBeRagged) { set_error("gemm: direct-to-LDS kernel on a shape it does not cover"); return OASES_EINVAL; }
       if (bm == 128) {
-        if (whole) hipLaunchKernelGGL((gemm_dtl_rect_kernel<A_KC, B_KC, EPI, true>), grid, dim3(256), 0, s, d);
-        else hipLaunchKernelGGL((gemm_dtl_rect_kernel<A_KC, B_KC, EPI, false>), grid, dim3(256), 0, s, d);
+        if constexpr (EPI != EPI_SWIGLU) {
+          if (whole) hipLaunchKernelGGL((gemm_dtl_rect_kernel<A_KC, B_KC, EPI, true>), grid, dim3(256), 0, s, d);
+          else hipLaunchKernelGGL((gemm_dtl_rect_kernel<A_KC, B_KC, EPI, false>), grid, dim3(256), 0, s, d);
+        }
       } else {
         if (whole) hipLaunchKernelGGL((gemm_dtl_kernel<A_KC, B_KC, EPI, true>), grid, dim3(256), 0, s, d);
         else if constexpr (kCanBeRagged) hipLaunchKernelGGL((gemm_dtl_kernel<A_KC, B_KC, EPI, false>), grid, dim3(256), 0, s, d);

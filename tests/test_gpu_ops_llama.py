@@ -186,13 +186,36 @@ def test_gemm_swiglu_gradient_on_direct_to_lds_kernels(B, ll, variant, M, fp, K)
     gs = gu_ref.double().reshape(M, fp // 32, 2, 32)
     gst, ust = gs[:, :, 0].reshape(M, fp), gs[:, :, 1].reshape(M, fp)
     assert_bf16_close(dgu.float(), interleave(dF * ust * ll.silu_grad(gst), dF * ll.silu(gst)), 1e-4, 1e-5)
-    if variant:
+    if variant == 201128256:     # the forward SwiGLU epilogue exists on the 256 x 256 kernel only
         f = torch.empty(M, fp // 2, dtype=torch.bfloat16, device="cuda")
         a = torch.zeros(M, K, dtype=torch.bfloat16, device="cuda")
         w = torch.zeros(K, fp, dtype=torch.bfloat16, device="cuda")
         assert B.lib.oases_op_gemm_forced(variant, B.GEMM_NN, B.EPI_SWIGLU, M, fp, K, a.data_ptr(), K, w.data_ptr(), fp, f.data_ptr(), fp // 2, None,
                                           gu.data_ptr(), 2 * fp, None, 0, None) == B.EINVAL
     torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("variant,M,fp,K", [(201256256, 256, 128, 32), (201256256, 512, 352, 160), (201256256, 256, 1376, 1056), (0, 4096, 1376, 512)])
+def test_gemm_swiglu_forward_on_direct_to_lds_kernel(B, ll, variant, M, fp, K):
+    """The SwiGLU epilogue on the 256 x 256 kernel whose tiles arrive by direct-to-LDS loads: whole and ragged column tiles
+    (the interleaved [gate 32 | up 32] blocks end inside the last tile), forced and as the library's choice for LLaMA-7B's
+    FC1 width per rank."""
+    g = gen(13)
+    a = bf16_round(randn(g, M, K))
+    wg, wu = bf16_round(randn(g, K, fp, scale=0.05)), bf16_round(randn(g, K, fp, scale=0.05))
+    ad, wd = dev(a, torch.bfloat16), dev(interleave(wg, wu), torch.bfloat16)
+    f = torch.full((M, fp + 8), 7.0, dtype=torch.bfloat16, device="cuda")
+    gu = torch.full((M, 2 * fp + 8), 7.0, dtype=torch.bfloat16, device="cuda")
+    args = (B.GEMM_NN, B.EPI_SWIGLU, M, 2 * fp, K, ad.data_ptr(), K, wd.data_ptr(), 2 * fp, f.data_ptr(), fp + 8, None, gu.data_ptr(), 2 * fp + 8, None, 0, None)
+    if variant:
+        B.check(B.lib.oases_op_gemm_forced(variant, *args))
+    else:
+        assert B.lib.oases_op_gemm_variant(B.GEMM_NN, B.EPI_SWIGLU, M, 2 * fp, K, 0) == 201256256
+        B.check(B.lib.oases_op_gemm(*args))
+    gate, up = a.double() @ wg.double(), a.double() @ wu.double()
+    assert_bf16_close(gu[:, :2 * fp].float(), interleave(gate, up), 1e-5, 2e-6 * float(gate.abs().max()))
+    assert_bf16_close(f[:, :fp].float(), ll.silu(gate) * up, 1e-4, 1e-5)
+    assert bool((f[:, fp:] == 7.0).all()) and bool((gu[:, 2 * fp:] == 7.0).all())
 
 
 def test_gemm_swiglu_argument_errors(B):
