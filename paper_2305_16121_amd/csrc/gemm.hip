@@ -506,7 +506,8 @@ __global__ __launch_bounds__(64 * WGM * WGN * WGK) void gemm_kernel(GemmArgs g) 
 //   lgkmcnt -- LDS reads return in order: fragments of the first k step are waited for with the second step's reads
 //             still outstanding; the second step's are waited for before the barrier, so that a stage is never
 //             refilled while a wave still reads it.
-// Only whole tiles (M, N multiples of 256, K of 32) and no k slices; everything else runs on the kernels above.
+// K must be a whole number of 32-wide stages and there are no k slices; M and N may end inside a tile where the operand
+// is row-indexed (see dtl_src); everything else runs on the kernels above.
 // =================================================================================================
 #ifndef OASES_DTL_STAGES
 #define OASES_DTL_STAGES 4
@@ -708,7 +709,7 @@ __global__ __launch_bounds__(256) void gemm_dtl_kernel(GemmArgs g) {
 // 16-wide k steps of a stage between them, so a wave keeps the 128 x 128 accumulator of the square kernel (same LDS
 // bytes read per MFMA) while the launch has twice as many workgroups; the two partial sums of a part meet once,
 // through LDS, after the k loop.  Waits as in the kernel above; a wave issues 12 DMA instructions per tile (4 of A,
-// 8 of B).  Whole tiles only: M % 128 == 0, N % 256 == 0, K % 64 == 0.
+// 8 of B).  K % 64 == 0; M and N may end inside a tile (see rect_src).
 // Operand tile in LDS.  KC: [R rows][64 k] = 128-byte rows, chunk c of row r at slot c ^ ((r/2)%8) (16 consecutive
 // rows at one chunk cover all 64 banks); one DMA instruction covers 8 rows.  MC: [64 k][R rows], k row = 2R bytes,
 // chunk c of k row kr at slot c ^ 4*(kr%4); one DMA instruction covers 512/R k rows.  In both the swizzle of
