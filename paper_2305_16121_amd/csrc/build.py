@@ -9,7 +9,11 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 PKG = os.path.dirname(HERE)
 LIB = os.path.join(PKG, "liboases.so")
-SOURCES = ("gemm.hip", "api.hip", "attention.hip", "elementwise.hip", "planner.cc")  # planner.cc: host code only
+# (source, object stem, extra flags); gemm.hip is compiled once per contraction form so that its kernel instantiations build
+# in parallel; planner.cc is host code only
+SOURCES = (("gemm.hip", "gemm_nn", ["-DOASES_GEMM_PART=0"]), ("gemm.hip", "gemm_nt", ["-DOASES_GEMM_PART=1"]),
+           ("gemm.hip", "gemm_tn", ["-DOASES_GEMM_PART=2"]), ("api.hip", "api", []), ("attention.hip", "attention", []),
+           ("elementwise.hip", "elementwise", []), ("planner.cc", "planner", []))
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wno-unused-command-line-argument", "-fno-gpu-rdc"]
 
@@ -26,9 +30,10 @@ def build(verbose: bool = False, extra: list[str] | None = None) -> str:
     os.makedirs(objdir, exist_ok=True)
     hipcc = _hipcc()
 
-    def one(src):
-        obj = os.path.join(objdir, os.path.splitext(src)[0] + ".o")
-        cmd = [hipcc, *FLAGS, *(extra or []), "-c", os.path.join(HERE, src), "-o", obj]
+    def one(item):
+        src, stem, flags = item
+        obj = os.path.join(objdir, stem + ".o")
+        cmd = [hipcc, *FLAGS, *flags, *(extra or []), "-c", os.path.join(HERE, src), "-o", obj]
         r = subprocess.run(cmd, capture_output=True, text=True)
         err = "\n".join(l for l in r.stderr.splitlines() if "packed-fp32-ops" not in l)
         if r.returncode != 0:
@@ -37,7 +42,7 @@ def build(verbose: bool = False, extra: list[str] | None = None) -> str:
             print(err, file=sys.stderr)
         return obj
 
-    with ThreadPoolExecutor(max_workers=5) as ex:
+    with ThreadPoolExecutor(max_workers=7) as ex:
         objs = list(ex.map(one, SOURCES))
     r = subprocess.run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs], capture_output=True, text=True)
     if r.returncode != 0:

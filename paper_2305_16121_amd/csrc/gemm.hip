@@ -13,12 +13,14 @@
 
 #include "common.h"
 
+// This file is compiled once per contraction form (OASES_GEMM_PART = 0: NN and the host entry points, 1: NT, 2: TN), so
+// that the three sets of kernel instantiations build in parallel; without the macro one object holds everything.
+#ifndef OASES_GEMM_PART
+#define OASES_GEMM_PART -1
+#endif
+#define OASES_GEMM_HAS(part) (OASES_GEMM_PART < 0 || OASES_GEMM_PART == (part))
+
 namespace oases {
-
-namespace {
-
-constexpr int BK = 64;          // k extent of one LDS stage
-constexpr int kMcPadBytes = 64; // row padding of a "contraction-major" tile (keeps transpose reads off the same banks)
 
 struct GemmArgs {
   const uint16_t* A;
@@ -31,6 +33,17 @@ struct GemmArgs {
   int tiles_m, tiles_n;
   int ksplit, k_per;  // split-K: slice s covers k in [s*k_per, min(K, (s+1)*k_per)) and writes partial s
 };
+
+// one launcher per contraction form, each defined in its own part
+int launch_gemm_nn(const GemmArgs& g, int epi, float* ws, size_t ws_bytes, int forced_variant, hipStream_t s);
+int launch_gemm_nt(const GemmArgs& g, int epi, float* ws, size_t ws_bytes, int forced_variant, hipStream_t s);
+int launch_gemm_tn(const GemmArgs& g, float* ws, size_t ws_bytes, int forced_variant, hipStream_t s);
+
+namespace {
+
+constexpr int BK = 64;          // k extent of one LDS stage
+constexpr int kMcPadBytes = 64; // row padding of a "contraction-major" tile (keeps transpose reads off the same banks)
+
 
 template <int R, bool KC>
 struct TileLayout {
@@ -1104,6 +1117,37 @@ int launch_shape(const GemmArgs& g, float* ws, size_t ws_bytes, int forced_varia
 
 }  // namespace
 
+#if OASES_GEMM_HAS(0)
+int launch_gemm_nn(const GemmArgs& g, int epi, float* ws, size_t ws_bytes, int forced_variant, hipStream_t s) {
+  switch (epi) {
+    case EPI_F32: return launch_shape<true, false, EPI_F32>(g, ws, ws_bytes, forced_variant, s);
+    case EPI_BF16: return launch_shape<true, false, EPI_BF16>(g, ws, ws_bytes, forced_variant, s);
+    case EPI_BIAS_BF16: return launch_shape<true, false, EPI_BIAS_BF16>(g, ws, ws_bytes, forced_variant, s);
+    case EPI_BIAS_GELU: return launch_shape<true, false, EPI_BIAS_GELU>(g, ws, ws_bytes, forced_variant, s);
+    case EPI_DGELU: return launch_shape<true, false, EPI_DGELU>(g, ws, ws_bytes, forced_variant, s);
+    case EPI_SWIGLU: return launch_shape<true, false, EPI_SWIGLU>(g, ws, ws_bytes, forced_variant, s);
+    default: set_error("gemm: unknown epilogue %d", epi); return OASES_EINVAL;
+  }
+}
+#endif
+#if OASES_GEMM_HAS(1)
+int launch_gemm_nt(const GemmArgs& g, int epi, float* ws, size_t ws_bytes, int forced_variant, hipStream_t s) {
+  switch (epi) {
+    case EPI_F32: return launch_shape<true, true, EPI_F32>(g, ws, ws_bytes, forced_variant, s);
+    case EPI_BF16: return launch_shape<true, true, EPI_BF16>(g, ws, ws_bytes, forced_variant, s);
+    case EPI_BIAS_BF16: return launch_shape<true, true, EPI_BIAS_BF16>(g, ws, ws_bytes, forced_variant, s);
+    case EPI_BIAS_GELU: return launch_shape<true, true, EPI_BIAS_GELU>(g, ws, ws_bytes, forced_variant, s);
+    case EPI_DGELU: return launch_shape<true, true, EPI_DGELU>(g, ws, ws_bytes, forced_variant, s);
+    case EPI_DSWIGLU: return launch_shape<true, true, EPI_DSWIGLU>(g, ws, ws_bytes, forced_variant, s);
+    default: set_error("gemm: unknown epilogue %d", epi); return OASES_EINVAL;
+  }
+}
+#endif
+#if OASES_GEMM_HAS(2)
+int launch_gemm_tn(const GemmArgs& g, float* ws, size_t ws_bytes, int forced_variant, hipStream_t s) {
+  return launch_shape<false, false, EPI_ACC_F32>(g, ws, ws_bytes, forced_variant, s);
+}
+
 bool gemm_tn_pair_wins(int K, int M0, int N0, int M1, int N1) {
   if (M0 <= 0 || N0 <= 0 || M1 <= 0 || N1 <= 0 || !dtl_rect_whole(M0, N0, K) || !dtl_rect_whole(M1, N1, K)) return false;
   const long t0 = (long)(M0 / 128) * (N0 / 256), t1 = (long)(M1 / 128) * (N1 / 256);
@@ -1134,6 +1178,8 @@ int launch_gemm_tn_pair(int K, int M0, int N0, const void* A0, int lda0, const v
   return 0;
 }
 
+#endif  // TN part
+#if OASES_GEMM_HAS(0)
 int gemm_variant(int op, int epi, int M, int N, int K, size_t ws_bytes) {
   const int kind = op == OASES_GEMM_TN ? 2 : op == OASES_GEMM_NT ? 1 : (epi == EPI_BIAS_GELU || epi == EPI_SWIGLU) ? 3 : 0;
   if (epi == EPI_SWIGLU || epi == EPI_DSWIGLU) ws_bytes = 0;
@@ -1154,7 +1200,7 @@ int launch_gemm(int op, int epi, int M, int N, int K, const void* A, int lda, co
   GemmArgs g{(const uint16_t*)A, (const uint16_t*)B, C, bias, (uint16_t*)aux, M, N, K, lda, ldb, ldc, ldaux, 0, 0, 1, K};
   if (op == OASES_GEMM_TN) {
     if (lda < M || ldb < N || ldc < N) { set_error("gemm TN: leading dimension too small"); return OASES_EINVAL; }
-    return launch_shape<false, false, EPI_ACC_F32>(g, ws, wsb, forced_variant, s);
+    return launch_gemm_tn(g, ws, wsb, forced_variant, s);
   }
   const bool nn = op == OASES_GEMM_NN;
   if (!nn && op != OASES_GEMM_NT) { set_error("gemm: unknown op %d", op); return OASES_EINVAL; }
@@ -1164,24 +1210,12 @@ int launch_gemm(int op, int epi, int M, int N, int K, const void* A, int lda, co
   if (epi == EPI_DSWIGLU && (nn || N % 32 || !aux || ldaux < 2 * N)) { set_error("gemm: SwiGLU-gradient epilogue needs the NT form, N %% 32 == 0 and aux [M,2N]"); return OASES_EINVAL; }
   if ((epi == OASES_EPI_BIAS_BF16 || epi == OASES_EPI_BIAS_GELU) && !bias) { set_error("gemm: bias epilogue without bias"); return OASES_ENULL; }
   if ((epi == OASES_EPI_BIAS_GELU || epi == OASES_EPI_DGELU) && (!aux || ldaux < N)) { set_error("gemm: GeLU epilogue without aux"); return OASES_ENULL; }
-#define OASES_GEMM_CASE(E)                                                   \
-  case E:                                                                    \
-    return nn ? launch_shape<true, false, E>(g, ws, wsb, forced_variant, s) : launch_shape<true, true, E>(g, ws, wsb, forced_variant, s);
-  switch (epi) {
-    OASES_GEMM_CASE(EPI_F32)
-    OASES_GEMM_CASE(EPI_BF16)
-    OASES_GEMM_CASE(EPI_BIAS_BF16)
-    OASES_GEMM_CASE(EPI_BIAS_GELU)
-    OASES_GEMM_CASE(EPI_DGELU)
-    case EPI_SWIGLU:
-      return launch_shape<true, false, EPI_SWIGLU>(g, ws, wsb, forced_variant, s);
-    case EPI_DSWIGLU:
-      return launch_shape<true, true, EPI_DSWIGLU>(g, ws, wsb, forced_variant, s);
-    default:
-      set_error("gemm: unknown epilogue %d", epi);
-      return OASES_EINVAL;
+  if ((nn && epi == EPI_DSWIGLU) || (!nn && epi == EPI_SWIGLU) || epi < 0 || epi > EPI_DSWIGLU || epi == EPI_ACC_F32) {
+    set_error("gemm: unknown epilogue %d", epi);
+    return OASES_EINVAL;
   }
-#undef OASES_GEMM_CASE
+  return nn ? launch_gemm_nn(g, epi, ws, wsb, forced_variant, s) : launch_gemm_nt(g, epi, ws, wsb, forced_variant, s);
 }
+#endif  // NN part and host entry points
 
 }  // namespace oases
