@@ -124,3 +124,20 @@ def test_argument_errors():
         P.plan_solve(bad)
     q["m"] = 1e-9
     assert P.plan_solve(q) == (None, float("inf"), None)
+
+
+def test_profiling_driver_knows_every_scheduled_operator():
+    """The offline profiling step charges every operator of the (recompute-mode) schedule to a block: its tables must name
+    every operator the library schedules for the GPT workloads, at every TMP degree it profiles."""
+    import synth_inputs as si
+    from paper_2305_16121_amd import plan_model as pm
+    for name, cfg in si.CONFIGS.items():
+        for t in (1, 2, 4, 8):
+            if cfg["n_heads"] % t:
+                continue
+            c = dict(cfg, tp=t, batch=max(cfg["batch"], 2))
+            H = B.Handle(B.make_cfg(c, flags=B.FLAG_SERIALISE | B.FLAG_PROFILE | B.FLAG_RECOMPUTE))
+            for bwd, table in ((False, pm.FWD_BLOCK), (True, pm.BWD_BLOCK)):
+                ops = {l.split()[1] for l in H.schedule(bwd).splitlines() if l.strip()} - {"join"}
+                assert ops <= set(table), (name, t, sorted(ops - set(table)))
+            H.close()
