@@ -258,12 +258,13 @@ int oases_op_gemm(int op, int epi, int M, int N, int K, const void *A, int lda, 
  * load their operand tiles from global memory straight into LDS: 201256256 (256x256 tiles, four LDS stages of 32 k
  * columns; K % 32 == 0; an operand whose k index is the contiguous one -- A of NN and NT, B of NT -- must fill its tiles:
  * M resp. N % 256 == 0) and 201128256 (128x256 tiles, three LDS stages of 64 k columns, waves split k; K % 64 == 0;
- * any M, N the GEMM accepts; no forward SwiGLU epilogue); one slice.
+ * any M, N the GEMM accepts; no forward SwiGLU epilogue; also over 2 or 4 k slices of whole stages, 202128256 and
+ * 204128256, K % (64 * slices) == 0); the 256x256 kernel takes one slice only.
  * Host only; used to group per-operator timings by kernel. */
 int oases_op_gemm_variant(int op, int epi, int M, int N, int K, size_t workspace_bytes);
 /* oases_op_gemm on the instantiation `variant` names (encoding above) instead of the one the library would choose:
  * for tests and tuning sweeps.  EINVAL if no such instantiation exists (block tiles 256x256, 128x256, 256x128,
- * 128x128; W = 1 only with the rectangular ones; W = 2 only as 201256256 or 201128256 on shapes they fit; 1..8 slices), if the slices do not fit K (every slice needs at least
+ * 128x128; W = 1 only with the rectangular ones; W = 2 only as 201256256, 201128256, 202128256 or 204128256 on shapes they fit; 1..8 slices), if the slices do not fit K (every slice needs at least
  * one k column) or if the workspace is smaller than slices*M*N*4 bytes.  Results of different variants differ only
  * by the fp32 summation order. */
 int oases_op_gemm_forced(int variant, int op, int epi, int M, int N, int K, const void *A, int lda,

@@ -406,6 +406,50 @@ def test_gemm_tn_pair(B, K, M0, N0, M1, N1):
     torch.cuda.synchronize()
 
 
+@pytest.mark.parametrize("variant,op,M,N,K", [(202128256, "NN", 256, 512, 256), (202128256, "NT", 136, 264, 384), (204128256, "NN", 128, 256, 1024),
+                                              (202128256, "TN", 392, 1000, 640), (204128256, "NT", 1024, 512, 4096)])
+def test_gemm_direct_to_lds_k_slices(B, lo, variant, op, M, N, K):
+    """The 128 x 256 direct-to-LDS kernel over two or four k slices of whole stages (variants 202128256, 204128256): fp32
+    partial planes in the workspace, summed in slice order by the second pass, which applies the epilogue."""
+    g = gen(M + N + K)
+    a, b = bf16_round(randn(g, M, K)), bf16_round(randn(g, K, N, scale=0.05))
+    ref = a @ b
+    opc = {"NN": B.GEMM_NN, "NT": B.GEMM_NT, "TN": B.GEMM_TN}[op]
+    ad = dev(a if op != "TN" else a.t().contiguous(), torch.bfloat16)
+    bd = dev(b if op != "NT" else b.t().contiguous(), torch.bfloat16)
+    lda, ldb = (K if op != "TN" else M), (N if op != "NT" else K)
+    S = variant // 1000000 % 100
+    ws = torch.empty(S * M * N * 4, dtype=torch.uint8, device="cuda")
+    c0 = randn(g, M, N + 8).float()
+    c = dev(c0, torch.float32)
+    B.check(B.lib.oases_op_gemm_forced(variant, opc, B.EPI_F32, M, N, K, ad.data_ptr(), lda, bd.data_ptr(), ldb, c.data_ptr(), N + 8, None, None, 0,
+                                       ws.data_ptr(), ws.numel(), None))
+    out = c.cpu().double()
+    assert rel_err(out[:, :N], ref + (c0[:, :N].double() if op == "TN" else 0.0)) < 1e-5
+    assert torch.equal(out[:, N:], c0[:, N:].double())
+    if op != "TN":
+        bias = dev(0.1 * randn(g, N), torch.float32)
+        pre = dev(bf16_round(randn(g, M, N)), torch.bfloat16)
+        cb = torch.empty(M, N, dtype=torch.bfloat16, device="cuda")
+        if op == "NN":
+            aux = torch.empty(M, N, dtype=torch.bfloat16, device="cuda")
+            B.check(B.lib.oases_op_gemm_forced(variant, opc, B.EPI_BIAS_GELU, M, N, K, ad.data_ptr(), lda, bd.data_ptr(), ldb, cb.data_ptr(), N,
+                                               bias.data_ptr(), aux.data_ptr(), N, ws.data_ptr(), ws.numel(), None))
+            z = ref + bias.cpu().double()
+            assert_bf16_close(aux.float(), z, 1e-5, 2e-6 * float(z.abs().max()))
+            assert_bf16_close(cb.float(), lo.gelu_fwd(z), 1e-4, 1e-5)
+        else:
+            B.check(B.lib.oases_op_gemm_forced(variant, opc, B.EPI_DGELU, M, N, K, ad.data_ptr(), lda, bd.data_ptr(), ldb, cb.data_ptr(), N,
+                                               None, pre.data_ptr(), N, ws.data_ptr(), ws.numel(), None))
+            assert_bf16_close(cb.float(), ref * lo.gelu_grad(pre.float().cpu().double()), 1e-4, 1e-5)
+    # slices that are not whole stages, or a workspace that is too small: refused on the host
+    assert B.lib.oases_op_gemm_forced(variant, opc, B.EPI_F32, M, N, K - 64, ad.data_ptr(), lda, bd.data_ptr(), ldb, c.data_ptr(), N + 8, None, None, 0,
+                                      ws.data_ptr(), ws.numel(), None) == B.EINVAL
+    assert B.lib.oases_op_gemm_forced(variant, opc, B.EPI_F32, M, N, K, ad.data_ptr(), lda, bd.data_ptr(), ldb, c.data_ptr(), N + 8, None, None, 0,
+                                      ws.data_ptr(), ws.numel() - 4, None) == B.EINVAL
+    torch.cuda.synchronize()
+
+
 def test_gemm_forced_variant_errors(B):
     """Variants that do not exist, k slices that do not fit K or the workspace: EINVAL before any launch."""
     M = N = K = 256
