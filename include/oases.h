@@ -45,7 +45,7 @@ enum {
   OASES_EINVAL = -1,     /* bad configuration or argument value */
   OASES_ENULL = -2,      /* required pointer is NULL */
   OASES_EALIGN = -3,     /* device pointer not 16-byte aligned */
-  OASES_EWORKSPACE = -4, /* reserved */
+  OASES_EWORKSPACE = -4, /* the problem needs more scratch memory than the call has */
   OASES_EHIP = -5,       /* a HIP runtime call failed; text in oases_last_error() */
   OASES_EINFEASIBLE = -6 /* planner: no strategy satisfies the constraints */
 };
@@ -291,6 +291,14 @@ size_t oases_gemm_workspace_bytes(const oases_handle *h);
  * scratch: fp32 [1024*cols]. */
 int oases_op_colsum_bf16(const void *a, int ld, int rows, int cols, void *out, void *scratch,
                          void *stream);
+
+/* oases_op_colsum_bf16 for callers that cannot allocate device memory or carry a scratch buffer (code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc): the partial-sum rows between the two kernels live in
+ * a 16 MiB device array inside the library (one per GPU, held until the process ends) instead of `scratch`; the call
+ * allocates nothing.  Same kernels, same result bit for bit.  cols <= 4096, else OASES_EWORKSPACE before any launch.
+ * All calls on one GPU share that array: calls that may overlap on one GPU (different streams, different host
+ * threads) race; calls on one stream are ordered and safe. */
+int oases_op_colsum_bf16_static(const void *a, int ld, int rows, int cols, void *out, void *stream);
 
 /* Flash-style attention over the local heads.  qkv [batch*seq, 3*hp] bf16 with hp = heads*d and
  * columns [Q | K | V]; queries are the rows row0..row0+rows-1 (a whole number of sequences, or a chunk
