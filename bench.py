@@ -85,7 +85,7 @@ def gemm_kernel_label(line, cfg, B, ws_bytes):
               "PROJ.dgrad": ("NT", "bf16", Ms, hp, h), "QKV.dgrad": ("NT", "f32", Ms, h, 3 * hp), "FC2.wgrad": ("TN", "acc_f32", fp, h, Ms),
               "FC1.wgrad": ("TN", "acc_f32", h, fw, Ms), "PROJ.wgrad": ("TN", "acc_f32", hp, h, Ms), "QKV.wgrad": ("TN", "acc_f32", h, 3 * hp, Ms)}
     if op == "PROJ+QKV.wgrad":   # the two weight gradients of the attention block in one launch
-        return "gemm_TN_acc_f32_128x256_dtl_pair"
+        return "gemm_TN_acc_f32_128x256_pp_pair"
     if op not in shapes:
         return None
     form, epi, m, n, k = shapes[op]
@@ -93,7 +93,7 @@ def gemm_kernel_label(line, cfg, B, ws_bytes):
     tile = B.lib.oases_op_gemm_variant({"NN": 0, "NT": 1, "TN": 2}[form], epi_id, m, n, k, ws_bytes)
     slices = tile // 1000000 % 100
     split = f"_splitk{slices}" if slices >= 2 else ""
-    wk = "_dtl" if tile >= 200000000 else "_wavek2" if tile >= 100000000 else ""
+    wk = "_pp" if tile >= 300000000 else "_dtl" if tile >= 200000000 else "_wavek2" if tile >= 100000000 else ""
     return f"gemm_{form}_{epi}_{tile // 1000 % 1000}x{tile % 1000}{wk}{split}"
 
 

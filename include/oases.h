@@ -86,11 +86,19 @@ enum { OASES_ARCH_GPT = 0, OASES_ARCH_LLAMA = 1, OASES_ARCH_BERT = 2 };
 enum {
   OASES_FLAG_SERIALISE = 1, /* enqueue everything on stream_compute only (same results) */
   OASES_FLAG_PROFILE = 2,   /* bracket every operator with timing events, see oases_profile_read */
-  OASES_FLAG_RECOMPUTE = 4  /* fine-grained recomputation (paper Sec. IV-B): keep only the input of each computation
+  OASES_FLAG_RECOMPUTE = 4, /* fine-grained recomputation (paper Sec. IV-B): keep only the input of each computation
                                sequence (x, x1) per layer, rebuild u, qkv, attention output, LSE, v2, pre, f inside
                                oases_backward with the forward kernels -- never a reduction point -- interleaved with
                                the backward operators of the same sub-batch (Alg. 1 "At Backward"); the rebuilt
                                activations share one region of the workspace across layers; same results, bit for bit */
+  OASES_FLAG_PIN_GEMM = 8   /* choose the kernel of every forward / input-gradient GEMM as for a launch over all M token rows
+                               instead of the sub-batch's Ms rows: the order in which the fp32 terms of an element are added
+                               (k slices, k split between waves) then does not depend on n_sub, and y, dx and the weight
+                               gradients are the same bit for bit for every sub-batch count (the invariant of Sec. IV-A:
+                               splitting the batch leaves the results unchanged); bias and LayerNorm-parameter gradients,
+                               which are summed over row groups of a sub-batch, still differ in the last bits.  Default
+                               (flag clear): each launch takes the kernel that is fastest for its own shape, and results
+                               for different n_sub agree to fp32 summation order only */
 };
 
 typedef struct oases_handle oases_handle; /* opaque; holds host metadata and HIP events only */
@@ -259,25 +267,27 @@ int oases_op_gemm(int op, int epi, int M, int N, int K, const void *A, int lda, 
  * columns; K % 32 == 0; an operand whose k index is the contiguous one -- A of NN and NT, B of NT -- must fill its tiles:
  * M resp. N % 256 == 0) and 201128256 (128x256 tiles, three LDS stages of 64 k columns, waves split k; K % 64 == 0;
  * any M, N the GEMM accepts; no forward SwiGLU epilogue; also over 2 or 4 k slices of whole stages, 202128256 and
- * 204128256, K % (64 * slices) == 0); the 256x256 kernel takes one slice only.
+ * 204128256, K % (64 * slices) == 0); the 256x256 kernel takes one slice only.  W = 3 names the eight-wave forms of
+ * the same tiles (two waves per SIMD that alternate between loading and multiplying): 301256256, 301128256, 302128256,
+ * 304128256, on the shapes of their W = 2 counterparts; 301128256 gives bit for bit what 201128256 gives.
  * Host only; used to group per-operator timings by kernel. */
 int oases_op_gemm_variant(int op, int epi, int M, int N, int K, size_t workspace_bytes);
 /* oases_op_gemm on the instantiation `variant` names (encoding above) instead of the one the library would choose:
  * for tests and tuning sweeps.  EINVAL if no such instantiation exists (block tiles 256x256, 128x256, 256x128,
- * 128x128; W = 1 only with the rectangular ones; W = 2 only as 201256256, 201128256, 202128256 or 204128256 on shapes they fit; 1..8 slices), if the slices do not fit K (every slice needs at least
+ * 128x128; W = 1 only with the rectangular ones; W = 2, 3 only as x01256256, x01128256, x02128256 or x04128256 on shapes they fit; 1..8 slices), if the slices do not fit K (every slice needs at least
  * one k column) or if the workspace is smaller than slices*M*N*4 bytes.  Results of different variants differ only
  * by the fp32 summation order. */
 int oases_op_gemm_forced(int variant, int op, int epi, int M, int N, int K, const void *A, int lda,
                          const void *B, int ldb, void *C, int ldc, const void *bias, void *aux,
                          int ldaux, void *workspace, size_t workspace_bytes, void *stream);
-/* Two weight-gradient contractions over the same K token rows in ONE launch of the 128x256 direct-to-LDS kernel:
+/* Two weight-gradient contractions over the same K token rows in ONE launch of the eight-wave 128x256 direct-to-LDS kernel:
  *   C0 [M0,N0] += A0^T B0   and   C1 [M1,N1] += A1^T B1,   A_i bf16 [K, lda_i >= M_i], B_i bf16 [K, ldb_i >= N_i],
  *   C_i fp32 [M_i, ldc_i >= N_i] (accumulated into, as the TN form of oases_op_gemm does); all device pointers,
  * 16-byte aligned; lda, ldb multiples of 8, ldc of 4.  The tiles of the second problem follow those of the first in the
  * grid, so that two launches that would each leave CUs idle (or need k slices to fill them) share one round of
  * workgroups: the backward pass issues the attention block's two weight gradients (Sec. II: projection and QKV) this way
  * when oases_op_gemm_tn_pair_wins says so.  Needs whole tiles, M_i % 128 == 0, N_i % 256 == 0, and K % 64 == 0: EINVAL
- * otherwise, before any launch.  Each C_i gets exactly what oases_op_gemm_forced(201128256, TN, ...) gives it. */
+ * otherwise, before any launch.  Each C_i gets exactly what oases_op_gemm_forced(301128256, TN, ...) gives it. */
 int oases_op_gemm_tn_pair(int K, int M0, int N0, const void *A0, int lda0, const void *B0, int ldb0, void *C0,
                           int ldc0, int M1, int N1, const void *A1, int lda1, const void *B1, int ldb1, void *C1,
                           int ldc1, void *stream);

@@ -16,7 +16,7 @@ OK, EINVAL, ENULL, EALIGN, EWORKSPACE, EHIP = 0, -1, -2, -3, -4, -5
 GEMM_NN, GEMM_NT, GEMM_TN = 0, 1, 2
 EPI_F32, EPI_BF16, EPI_BIAS_BF16, EPI_BIAS_GELU, EPI_DGELU = 0, 1, 2, 3, 4
 EPI_SWIGLU, EPI_DSWIGLU = 6, 7
-FLAG_SERIALISE, FLAG_PROFILE, FLAG_RECOMPUTE = 1, 2, 4
+FLAG_SERIALISE, FLAG_PROFILE, FLAG_RECOMPUTE, FLAG_PIN_GEMM = 1, 2, 4, 8
 ARCH_GPT, ARCH_LLAMA, ARCH_BERT = 0, 1, 2
 
 _P = C.c_void_p

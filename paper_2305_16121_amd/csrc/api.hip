@@ -322,6 +322,7 @@ static int run_op(const Run& R, const Op& op) {
   float* scr_comm = reinterpret_cast<float*>(R.ws + H->scratch_comm_off);
   float* scr_comp = reinterpret_cast<float*>(R.ws + H->scratch_compute_off);
   void* gws = R.ws + H->gemm_ws_off;  // split-K partial planes (compute stream only)
+  const int pin = (H->cfg.flags & OASES_FLAG_PIN_GEMM) ? H->M : 0;  // kernels chosen as for all M rows, whatever the sub-batch
   uint16_t* u = wsp<uint16_t>(R, "u", l);
   uint16_t* qkv = wsp<uint16_t>(R, "qkv", l);
   uint16_t* attn = wsp<uint16_t>(R, "attn", l);
@@ -386,7 +387,7 @@ static int run_op(const Run& R, const Op& op) {
                                   wsp<float>(R, "mu1", l) + r0, wsp<float>(R, "rstd1", l) + r0, Ms, h, H->eps, s, rms);
     case F_QKV:
       return launch_gemm(OASES_GEMM_NN, rms ? OASES_EPI_BF16 : OASES_EPI_BIAS_BF16, Ms, 3 * hp, h, u + r0 * h, h, W.wqkv, 3 * hp,
-                         qkv + r0 * 3 * hp, 3 * hp, (const float*)W.bqkv, nullptr, 0, gws, H->gemm_ws_bytes, 0, s);
+                         qkv + r0 * 3 * hp, 3 * hp, (const float*)W.bqkv, nullptr, 0, gws, H->gemm_ws_bytes, 0, s, pin);
     case F_ROPE_TABLE:
       return launch_rope_table(wsp<float>(R, "rope", 0), H->s, H->d, H->theta, s);
     case F_ROPE:
@@ -400,7 +401,7 @@ static int run_op(const Run& R, const Op& op) {
                                   seed, l, H->cfg.attn_dropout_p, H->r * H->heads_l, H->nh);
     case F_PROJ:
       return launch_gemm(OASES_GEMM_NN, OASES_EPI_F32, Ms, h, hp, attn + r0 * hp, hp, W.wo, h, wsp<float>(R, "z1", l) + r0 * h, h,
-                         nullptr, nullptr, 0, gws, H->gemm_ws_bytes, 0, s);
+                         nullptr, nullptr, 0, gws, H->gemm_ws_bytes, 0, s, pin);
     case F_R1:
       return launch_bdr_ln(wsp<float>(R, "z1", l) + r0 * h, peer(P ? P->fwd_attn : nullptr), (const float*)W.bo, xin + r0 * h,
                            wsp<float>(R, "x1", l) + r0 * h, (const float*)W.ln2_g, (const float*)W.ln2_b, v2 + r0 * h,
@@ -409,12 +410,12 @@ static int run_op(const Run& R, const Op& op) {
     case F_FC1:
       if (H->llama)  // w1 = [gate | up] columns interleaved in blocks of 32; pre = both pre-activations, f = silu(gate)*up
         return launch_gemm(OASES_GEMM_NN, OASES_EPI_SWIGLU, Ms, fw, h, v2 + r0 * h, h, W.w1, fw, f + r0 * fp, fp, nullptr,
-                           pre + r0 * fw, fw, gws, H->gemm_ws_bytes, 0, s);
+                           pre + r0 * fw, fw, gws, H->gemm_ws_bytes, 0, s, pin);
       return launch_gemm(OASES_GEMM_NN, OASES_EPI_BIAS_GELU, Ms, fp, h, v2 + r0 * h, h, W.w1, fp, f + r0 * fp, fp,
-                         (const float*)W.b1, pre + r0 * fp, fp, gws, H->gemm_ws_bytes, 0, s);
+                         (const float*)W.b1, pre + r0 * fp, fp, gws, H->gemm_ws_bytes, 0, s, pin);
     case F_FC2:
       return launch_gemm(OASES_GEMM_NN, OASES_EPI_F32, Ms, h, fp, f + r0 * fp, fp, W.w2, h, wsp<float>(R, "z2", l) + r0 * h, h,
-                         nullptr, nullptr, 0, gws, H->gemm_ws_bytes, 0, s);
+                         nullptr, nullptr, 0, gws, H->gemm_ws_bytes, 0, s, pin);
     case F_R2: {
       const bool more = l + 1 < L;  // fuse the next layer's LN1 behind this layer's output
       return launch_bdr_ln(wsp<float>(R, "z2", l) + r0 * h, peer(P ? P->fwd_ffn : nullptr), (const float*)W.b2,
@@ -430,12 +431,12 @@ static int run_op(const Run& R, const Op& op) {
     case B_FC2_DGRAD:
       if (H->llama)
         return launch_gemm(OASES_GEMM_NT, OASES_EPI_DSWIGLU, Ms, fp, h, wsp<uint16_t>(R, "dz2", l) + r0 * h, h, W.w2, h,
-                           wsp<uint16_t>(R, "dg", l) + r0 * fw, fw, nullptr, pre + r0 * fw, fw, gws, H->gemm_ws_bytes, 0, s);
+                           wsp<uint16_t>(R, "dg", l) + r0 * fw, fw, nullptr, pre + r0 * fw, fw, gws, H->gemm_ws_bytes, 0, s, pin);
       return launch_gemm(OASES_GEMM_NT, OASES_EPI_DGELU, Ms, fp, h, wsp<uint16_t>(R, "dz2", l) + r0 * h, h, W.w2, h,
-                         wsp<uint16_t>(R, "dg", l) + r0 * fp, fp, nullptr, pre + r0 * fp, fp, gws, H->gemm_ws_bytes, 0, s);
+                         wsp<uint16_t>(R, "dg", l) + r0 * fp, fp, nullptr, pre + r0 * fp, fp, gws, H->gemm_ws_bytes, 0, s, pin);
     case B_FC1_DGRAD:
       return launch_gemm(OASES_GEMM_NT, OASES_EPI_F32, Ms, h, fw, wsp<uint16_t>(R, "dg", l) + r0 * fw, fw, W.w1, fw,
-                         wsp<float>(R, "dv2", l) + r0 * h, h, nullptr, nullptr, 0, gws, H->gemm_ws_bytes, 0, s);
+                         wsp<float>(R, "dv2", l) + r0 * h, h, nullptr, nullptr, 0, gws, H->gemm_ws_bytes, 0, s, pin);
     case B_R3:
       return launch_layernorm_bwd(wsp<float>(R, "dv2", l) + r0 * h, peer(P ? P->bwd_ffn : nullptr), dyin + r0 * h,
                                   wsp<float>(R, "x1", l) + r0 * h, wsp<float>(R, "mu2", l) + r0, wsp<float>(R, "rstd2", l) + r0,
@@ -452,7 +453,7 @@ static int run_op(const Run& R, const Op& op) {
       return launch_colsum_bf16(wsp<uint16_t>(R, "dg", l) + r0 * fp, fp, Ms, fp, (float*)R.g[l].b1, scr_comp, s);
     case B_PROJ_DGRAD:
       return launch_gemm(OASES_GEMM_NT, OASES_EPI_BF16, Ms, hp, h, wsp<uint16_t>(R, "dz1", l) + r0 * h, h, W.wo, h,
-                         wsp<uint16_t>(R, "da", l) + r0 * hp, hp, nullptr, nullptr, 0, gws, H->gemm_ws_bytes, 0, s);
+                         wsp<uint16_t>(R, "da", l) + r0 * hp, hp, nullptr, nullptr, 0, gws, H->gemm_ws_bytes, 0, s, pin);
     case B_PROJ_WGRAD:
       return launch_gemm(OASES_GEMM_TN, 0, hp, h, Ms, attn + r0 * hp, hp, wsp<uint16_t>(R, "dz1", l) + r0 * h, h, R.g[l].wo, h,
                          nullptr, nullptr, 0, gws, H->gemm_ws_bytes, 0, s);
@@ -462,7 +463,7 @@ static int run_op(const Run& R, const Op& op) {
                                   H->cfg.attn_dropout_p, H->r * H->heads_l, H->nh);
     case B_QKV_DGRAD:
       return launch_gemm(OASES_GEMM_NT, OASES_EPI_F32, Ms, h, 3 * hp, wsp<uint16_t>(R, "dqkv", l) + r0 * 3 * hp, 3 * hp, W.wqkv,
-                         3 * hp, wsp<float>(R, "du", l) + r0 * h, h, nullptr, nullptr, 0, gws, H->gemm_ws_bytes, 0, s);
+                         3 * hp, wsp<float>(R, "du", l) + r0 * h, h, nullptr, nullptr, 0, gws, H->gemm_ws_bytes, 0, s, pin);
     case B_R4: {
       const bool more = l > 0;  // fuse the dropout backward of the layer below (its BDR2) behind dx
       return launch_layernorm_bwd(wsp<float>(R, "du", l) + r0 * h, peer(P ? P->bwd_attn : nullptr),

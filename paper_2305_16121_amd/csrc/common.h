@@ -122,9 +122,11 @@ int launch_layernorm_bwd(const float* part, const float* peer, const float* dres
 int launch_colsum_bf16(const void* a, int ld, int rows, int cols, float* out, float* scratch, hipStream_t s);
 // splitk_ws: optional fp32 scratch for split-K partial planes (NULL: never split); forced_variant: 0 = choose, else
 // the instantiation to launch, encoded as gemm_variant() returns it
+// choice_rows > M (NN / NT): the kernel is chosen as for a launch of that many rows, so that launches over parts of those rows
+// (sub-batches) add the fp32 terms of an element in one order whatever the part
 int launch_gemm(int op, int epi, int M, int N, int K, const void* A, int lda, const void* B, int ldb, void* C,
                 int ldc, const float* bias, void* aux, int ldaux, void* splitk_ws, size_t splitk_ws_bytes, int forced_variant,
-                hipStream_t s);
+                hipStream_t s, int choice_rows = 0);
 int gemm_variant(int op, int epi, int M, int N, int K, size_t ws_bytes);  // 1e8*[waves split k] + 1e6*slices + 1e3*BM + BN
 // two TN contractions C_i += A_i^T B_i over the same K rows in one launch of the 128x256 direct-to-LDS kernel, and the
 // host rule that says when that beats two launches (both fit whole tiles, fewer rounds of workgroups together)

@@ -35,8 +35,9 @@ struct GemmArgs {
 };
 
 // one launcher per contraction form, each defined in its own part
-int launch_gemm_nn(const GemmArgs& g, int epi, float* ws, size_t ws_bytes, int forced_variant, hipStream_t s);
-int launch_gemm_nt(const GemmArgs& g, int epi, float* ws, size_t ws_bytes, int forced_variant, hipStream_t s);
+// choice_rows > 0: the kernel is chosen as if the launch had that many rows (see launch_gemm)
+int launch_gemm_nn(const GemmArgs& g, int epi, float* ws, size_t ws_bytes, int forced_variant, int choice_rows, hipStream_t s);
+int launch_gemm_nt(const GemmArgs& g, int epi, float* ws, size_t ws_bytes, int forced_variant, int choice_rows, hipStream_t s);
 int launch_gemm_tn(const GemmArgs& g, float* ws, size_t ws_bytes, int forced_variant, hipStream_t s);
 
 namespace {
@@ -932,13 +933,251 @@ __global__ __launch_bounds__(256) void gemm_dtl_rect_kernel(GemmArgs g) {  // g:
   dtl_rect_tile<A_KC, B_KC, EPI, FULL>(g, pid, lds);
 }
 
+// =================================================================================================
+// Eight-wave kernels: two waves on every SIMD, alternating between a memory phase and an MFMA phase.
+// A wave's part of the block tile is 128 x 64 (128 accumulator registers), so two waves fit the register file of a SIMD.
+// Waves 0-3 (one per SIMD) and waves 4-7 run the same loop one phase apart: group 1 passes one extra barrier before the
+// loop and group 0 one behind it, so that every workgroup barrier ends a memory phase of one group and an MFMA phase of
+// the other.  Memory phase of k tile kt: the 12 operand fragments of the tile are read from LDS into registers, the
+// direct-to-LDS loads of tile kt+NS-1 are issued into the stage that held tile kt-1, and the wave waits until its own
+// loads of tile kt+1 have landed.  MFMA phase: 16 MFMAs, nothing else.  While one wave of a SIMD multiplies, the other
+// one's LDS reads, address arithmetic and waits cost the MFMA pipe nothing.
+//   Why this is safe.  Number the barriers B0 (before the loop, all waves), B(2k+1) = {group 0 ends its memory phase k, group
+//   1 ends its MFMA phase k-1 (k = 0: the extra barrier)}, B(2k+2) = {group 0 ends MFMA phase k, group 1 ends memory phase
+//   k}.  Group 0 reads tile k between B(2k) and B(2k+1), group 1 between B(2k+1) and B(2k+2); every wave's reads have
+//   returned (lgkmcnt(0)) before it reaches the barrier that ends the phase.  (a) Tile k is complete before it is read:
+//   each wave waits for its own loads of tile k in its memory phase k-1, i.e. before B(2k-1) (group 0) or B(2k) (group
+//   1); tile 0 before B0.  (b) A stage is refilled only after its last reader is done: tile k+NS-1 replaces tile k-1;
+//   group 0 issues it behind B(2k), group 1 behind B(2k+1); the last reads of tile k-1 are group 1's, complete before
+//   B(2k).
+// 256 x 256 tiles (variant 301256256): waves 2 x 4, LDS stages and layouts of the four-wave direct-to-LDS kernel (four
+// stages of 32 k).  128 x 256 tiles (301128256, over k slices 302128256 / 304128256): waves 1 x 4 x 2 -- the two groups
+// split the four k steps of a 64-wide stage and add their accumulators through LDS after the loop -- three stages,
+// layouts of the four-wave 128 x 256 kernel.  Shapes: as those kernels.
+// =================================================================================================
+// fragment I (of NF) of k step KK.  KC: off[KK] + I * FRAG bytes; MC: off[I] + KK * KSTEP bytes, second half HALF bytes on
+template <bool KC, int KK, int I, int FRAG, int KSTEP, int HALF>
+__device__ __forceinline__ u32x4 pp_read_frag(uint32_t base, const uint32_t* off) {
+  if constexpr (KC) {
+    return lds_read_b128<I * FRAG>(base + off[KK]);
+  } else {
+    const u32x2 lo = lds_read_tr16_b64<KK * KSTEP>(base + off[I]);
+    const u32x2 hi = lds_read_tr16_b64<KK * KSTEP + HALF>(base + off[I]);
+    return u32x4{lo[0], lo[1], hi[0], hi[1]};
+  }
+}
+__device__ __forceinline__ void pp_wait_frags(u32x4 (&a)[2][4], u32x4 (&b)[2][2]) {
+  asm volatile("s_waitcnt lgkmcnt(0)"
+               : "+v"(a[0][0]), "+v"(a[0][1]), "+v"(a[0][2]), "+v"(a[0][3]), "+v"(a[1][0]), "+v"(a[1][1]), "+v"(a[1][2]), "+v"(a[1][3]),
+                 "+v"(b[0][0]), "+v"(b[0][1]), "+v"(b[1][0]), "+v"(b[1][1]));
+}
+
+constexpr int kPpLds256 = NSD * kDtlStage;                                  // 128 KB
+constexpr int kPpExchange = 8 * 2 * 2 * 4 * 64 * 16;                        // 128 x 256 tiles: half of every wave's accumulator
+constexpr int kPpLds128 = NSR * kRectStage > kPpExchange ? NSR * kRectStage : kPpExchange;  // 144 KB
+
+template <int BM, bool A_KC, bool B_KC, int EPI, bool FULL>
+__device__ __forceinline__ void pp_tile(const GemmArgs& g, int pid, char* lds) {
+  static_assert(BM == 256 || BM == 128, "block tiles 256 x 256 and 128 x 256");
+  constexpr bool SQ = BM == 256;
+  constexpr int NS = SQ ? NSD : NSR;                 // LDS stages
+  constexpr int KT = SQ ? BKD : BKR;                 // k extent of a stage
+  constexpr int kOpA = SQ ? kDtlOperand : kRectA;    // bytes of the A tile of a stage (B behind it)
+  constexpr int kStage = SQ ? kDtlStage : kRectStage;
+  constexpr int PER_A = 2, PER_B = SQ ? 2 : 4, PER = PER_A + PER_B;  // direct-to-LDS instructions of a wave per stage
+  int tile_m, tile_n;
+  tile_of_workgroup(pid, g.tiles_m, g.tiles_n, tile_m, tile_n);
+  const int m0 = tile_m * BM, n0 = tile_n * 256;
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int grp = wave >> 2, wn = wave & 3;          // grp: phase group; 256 x 256: also the row half, 128 x 256: the k half
+  const int nk = g.K / KT;
+
+  f32x16 acc[4][2];
+#pragma unroll
+  for (int i = 0; i < 4; i++)
+#pragma unroll
+    for (int j = 0; j < 2; j++)
+#pragma unroll
+      for (int e = 0; e < 16; e++) acc[i][j][e] = 0.f;
+
+  const char* srcA[PER_A];
+  const char* srcB[PER_B];
+#pragma unroll
+  for (int j = 0; j < PER_A; j++)
+    srcA[j] = SQ ? dtl_src<A_KC>(g.A, g.lda, m0, PER_A * wave + j, lane, g.M) : rect_src<A_KC, 128>(g.A, g.lda, m0, PER_A * wave + j, lane, g.M);
+#pragma unroll
+  for (int j = 0; j < PER_B; j++)
+    srcB[j] = SQ ? dtl_src<B_KC>(g.B, g.ldb, n0, PER_B * wave + j, lane, g.N) : rect_src<B_KC, 256>(g.B, g.ldb, n0, PER_B * wave + j, lane, g.N);
+  const size_t stepA_k = A_KC ? (size_t)KT * 2 : (size_t)KT * g.lda * 2, stepB_k = B_KC ? (size_t)KT * 2 : (size_t)KT * g.ldb * 2;  // next k tile
+  typedef const void __attribute__((address_space(1))) * gptr_t;
+  typedef void OASES_LDS* lptr_t;
+  auto issue = [&](int t) {
+    char* st = lds + (t % NS) * kStage;
+#pragma unroll
+    for (int j = 0; j < PER_A; j++)
+      __builtin_amdgcn_global_load_lds((gptr_t)(srcA[j] + (size_t)t * stepA_k), (lptr_t)(st + (PER_A * wave + j) * 1024), 16, 0, 0);
+#pragma unroll
+    for (int j = 0; j < PER_B; j++)
+      __builtin_amdgcn_global_load_lds((gptr_t)(srcB[j] + (size_t)t * stepB_k), (lptr_t)(st + kOpA + (PER_B * wave + j) * 1024), 16, 0, 0);
+  };
+
+  uint32_t offA[4], offB[4];
+  if constexpr (SQ) {
+    dtl_frag_offsets<A_KC>(offA, grp * 128, lane);
+    dtl_frag_offsets<B_KC>(offB, wn * 64, lane);
+  } else {
+    rect_frag_offsets<A_KC, 128>(offA, 0, grp, lane);
+    rect_frag_offsets<B_KC, 256>(offB, wn * 64, grp, lane);
+  }
+  // strides of the LDS layouts: fragment to fragment (k-major operand), k step to k step and first to second half of a
+  // fragment (row-indexed operand)
+  constexpr int FRAG = SQ ? 2048 : 4096;
+  constexpr int KSTEP_A = SQ ? 8192 : 16 * 2 * 128, HALF_A = SQ ? 2048 : 4 * 2 * 128;
+  constexpr int KSTEP_B = SQ ? 8192 : 16 * 2 * 256, HALF_B = SQ ? 2048 : 4 * 2 * 256;
+  const uint32_t lds0 = (uint32_t)(uintptr_t)(OASES_LDS char*)lds;
+  u32x4 fa[2][4], fb[2][2];
+  auto read_stage = [&](uint32_t st) {
+#define OASES_PP_A(KK, I) fa[KK][I] = pp_read_frag<A_KC, KK, I, FRAG, KSTEP_A, HALF_A>(st, offA);
+#define OASES_PP_B(KK, I) fb[KK][I] = pp_read_frag<B_KC, KK, I, FRAG, KSTEP_B, HALF_B>(st + kOpA, offB);
+    OASES_PP_A(0, 0) OASES_PP_A(0, 1) OASES_PP_A(0, 2) OASES_PP_A(0, 3) OASES_PP_B(0, 0) OASES_PP_B(0, 1)
+    OASES_PP_A(1, 0) OASES_PP_A(1, 1) OASES_PP_A(1, 2) OASES_PP_A(1, 3) OASES_PP_B(1, 0) OASES_PP_B(1, 1)
+#undef OASES_PP_A
+#undef OASES_PP_B
+  };
+  auto mma = [&]() {
+#pragma unroll
+    for (int kk = 0; kk < 2; kk++)
+#pragma unroll
+      for (int i = 0; i < 4; i++)
+#pragma unroll
+        for (int j = 0; j < 2; j++) {
+          const bf16x8 a = __builtin_bit_cast(bf16x8, fa[kk][i]), b = __builtin_bit_cast(bf16x8, fb[kk][j]);
+          if constexpr (EPI == EPI_F32) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[i][j], 0, 0, 0);
+          else acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b, a, acc[i][j], 0, 0, 0);
+        }
+  };
+  constexpr int kYoung = PER * (NS - 2);  // direct-to-LDS instructions of the younger tiles that may still be in flight
+  constexpr int kVmSteady = ((kYoung >> 4) << 14) | (kYoung & 15) | (7 << 4) | (15 << 8), kVm0 = (7 << 4) | (15 << 8);
+
+#pragma unroll
+  for (int t = 0; t < NS - 1; t++)
+    if (t < nk) issue(t);
+  if (nk > NS - 2) __builtin_amdgcn_s_waitcnt(kVmSteady); else __builtin_amdgcn_s_waitcnt(kVm0);  // own part of tile 0
+  __builtin_amdgcn_s_barrier();                 // B0
+  if (grp == 1) __builtin_amdgcn_s_barrier();   // group 1 runs one phase behind
+  __builtin_amdgcn_sched_barrier(0);
+
+  uint32_t cur = lds0;
+  auto iteration = [&](auto steady_c, int kt) {
+    constexpr bool STEADY = decltype(steady_c)::value;  // tile kt+NS-1 exists and is requested now
+#ifndef OASES_PP_SKIP
+#define OASES_PP_SKIP 0
+#endif
+    if (!(OASES_PP_SKIP & 2) || kt == 0) read_stage(cur);
+    if (STEADY) {
+      if (!(OASES_PP_SKIP & 1)) issue(kt + NS - 1);
+      __builtin_amdgcn_s_waitcnt(kVmSteady);
+    } else {
+      __builtin_amdgcn_s_waitcnt(kVm0);
+    }
+    pp_wait_frags(fa, fb);
+    __builtin_amdgcn_sched_barrier(0);
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_sched_barrier(0);
+    if (!(OASES_PP_SKIP & 4)) __builtin_amdgcn_s_setprio(1);
+    mma();
+    if (!(OASES_PP_SKIP & 4)) __builtin_amdgcn_s_setprio(0);
+    __builtin_amdgcn_sched_barrier(0);
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_sched_barrier(0);
+    cur = cur + kStage == lds0 + NS * kStage ? lds0 : cur + kStage;
+  };
+  {
+    int kt = 0;
+    for (; kt + NS - 1 < nk; kt++) iteration(std::true_type{}, kt);
+    for (; kt < nk; kt++) iteration(std::false_type{}, kt);
+  }
+  if (grp == 0) __builtin_amdgcn_s_barrier();   // group 0 catches up: both groups have passed the same number of barriers
+  __builtin_amdgcn_sched_barrier(0);
+
+  if constexpr (SQ) {
+#pragma unroll
+    for (int i = 0; i < 4; i++) {
+      if constexpr (EPI == EPI_SWIGLU) {  // the wave's 64 columns are one [gate 32 | up 32] block
+        epilogue_tile_swiglu<FULL>(g, m0 + grp * 128 + i * 32, n0 + wn * 64, lane, acc[i][0], acc[i][1]);
+      } else {
+        epilogue_tile<EPI, FULL>(g, m0 + grp * 128 + i * 32, n0 + wn * 64, lane, acc[i][0]);
+        epilogue_tile<EPI, FULL>(g, m0 + grp * 128 + i * 32, n0 + wn * 64 + 32, lane, acc[i][1]);
+      }
+    }
+  } else {
+    // The two waves that hold the k halves of one 128 x 64 part each finish 64 of its rows: a wave hands the accumulator
+    // tiles of the other 64 rows over through LDS (lane for lane) and adds what it receives to its own (two terms: the
+    // order of the addition does not matter).
+    f32x4* xch = reinterpret_cast<f32x4*>(lds);
+    const int mine = wave * 16, theirs = (wave ^ 4) * 16;  // 2 x 2 tiles x 4 quarters per wave
+    __syncthreads();  // every wave has its last fragments in registers, and all direct-to-LDS loads have landed
+    auto hand_over = [&](auto half_c) {
+      constexpr int H = decltype(half_c)::value;
+#pragma unroll
+      for (int i = 0; i < 2; i++)
+#pragma unroll
+        for (int j = 0; j < 2; j++)
+#pragma unroll
+          for (int q = 0; q < 4; q++) {
+            const f32x16& a = acc[H * 2 + i][j];
+            xch[(mine + (i * 2 + j) * 4 + q) * 64 + lane] = f32x4{a[4 * q], a[4 * q + 1], a[4 * q + 2], a[4 * q + 3]};
+          }
+    };
+    auto finish = [&](auto half_c) {
+      constexpr int H = decltype(half_c)::value;
+#pragma unroll
+      for (int i = 0; i < 2; i++) {
+        f32x16 a[2] = {acc[H * 2 + i][0], acc[H * 2 + i][1]};
+#pragma unroll
+        for (int j = 0; j < 2; j++)
+#pragma unroll
+          for (int q = 0; q < 4; q++) {
+            const f32x4 o = xch[(theirs + (i * 2 + j) * 4 + q) * 64 + lane];
+#pragma unroll
+            for (int e = 0; e < 4; e++) a[j][4 * q + e] += o[e];
+          }
+        if constexpr (EPI == EPI_SWIGLU) {
+          epilogue_tile_swiglu<FULL>(g, m0 + (H * 2 + i) * 32, n0 + wn * 64, lane, a[0], a[1]);
+        } else {
+          epilogue_tile<EPI, FULL>(g, m0 + (H * 2 + i) * 32, n0 + wn * 64, lane, a[0]);
+          epilogue_tile<EPI, FULL>(g, m0 + (H * 2 + i) * 32, n0 + wn * 64 + 32, lane, a[1]);
+        }
+      }
+    };
+    if (grp == 0) hand_over(std::integral_constant<int, 1>{}); else hand_over(std::integral_constant<int, 0>{});
+    __syncthreads();
+    if (grp == 0) finish(std::integral_constant<int, 0>{}); else finish(std::integral_constant<int, 1>{});
+  }
+}
+
+template <int BM, bool A_KC, bool B_KC, int EPI, bool FULL>
+__global__ __launch_bounds__(512) void gemm_pp_kernel(GemmArgs g) {  // g: by value, adjusted per k slice
+  __shared__ __attribute__((aligned(1024))) char lds[BM == 256 ? kPpLds256 : kPpLds128];
+  int pid = blockIdx.x;
+  if (BM == 128 && g.ksplit > 1) {  // this workgroup's k range (k_per: a whole number of stages) and fp32 partial-result plane
+    const int T = g.tiles_m * g.tiles_n, slice = pid / T, k0 = slice * g.k_per;
+    pid -= slice * T;
+    g.A += A_KC ? (size_t)k0 : (size_t)k0 * g.lda;
+    g.B += B_KC ? (size_t)k0 : (size_t)k0 * g.ldb;
+    g.K = g.k_per;
+    g.C = reinterpret_cast<float*>(g.C) + (size_t)slice * g.M * g.ldc;
+  }
+  pp_tile<BM, A_KC, B_KC, EPI, FULL>(g, pid, lds);
+}
+
 // Two weight-gradient contractions over the same K rows in one launch: the tiles of the second problem follow those of
 // the first, so that two launches that would each leave CUs idle (or need k slices to fill them) share one round.
-__global__ __launch_bounds__(256) void gemm_dtl_rect_pair_kernel(GemmArgs g0, GemmArgs g1) {
-  __shared__ __attribute__((aligned(1024))) char lds[kRectLds];
+__global__ __launch_bounds__(512) void gemm_pp_pair_kernel(GemmArgs g0, GemmArgs g1) {
+  __shared__ __attribute__((aligned(1024))) char lds[kPpLds128];
   const int first = g0.tiles_m * g0.tiles_n;
-  if ((int)blockIdx.x < first) dtl_rect_tile<false, false, EPI_ACC_F32, true>(g0, blockIdx.x, lds);
-  else dtl_rect_tile<false, false, EPI_ACC_F32, true>(g1, blockIdx.x - first, lds);
+  if ((int)blockIdx.x < first) pp_tile<128, false, false, EPI_ACC_F32, true>(g0, blockIdx.x, lds);
+  else pp_tile<128, false, false, EPI_ACC_F32, true>(g1, blockIdx.x - first, lds);
 }
 
 // split-K second pass: C = epilogue(sum over slices of the fp32 partial planes), slices added in index order
@@ -1007,7 +1246,7 @@ int launch_one(const GemmArgs& g0, int ksplit, float* ws, hipStream_t s) {
 // Tile and split-K choice by a small time model.  Bigger tiles run closer to the MFMA rate (fewer LDS bytes per flop)
 // but a launch only uses the chip well if its workgroup count is near a multiple of the 256 CUs; splitting K multiplies
 // the workgroup count at the price of a second pass over fp32 partial planes.  Rates measured on this part.
-struct TileChoice { int bm, bn, ksplit; bool wave_ksplit; bool dtl = false; };
+struct TileChoice { int bm, bn, ksplit; bool wave_ksplit; bool dtl = false; bool pp = false; };  // pp: the eight-wave kernel of a direct-to-LDS tile shape
 // per kind of contraction (0: NN, 1: NT, 2: TN, 3: NN with the bias+GeLU epilogue): whether the rectangular tiles
 // split k between waves, and the sustained rates of the four block tiles
 // Shapes the direct-to-LDS kernels cover, per kind of contraction (0, 3: NN, 1: NT, 2: TN): whole k tiles; in the
@@ -1047,7 +1286,7 @@ TileChoice pick_tile(int kind, int epi, int M, int N, int K, size_t ws_bytes) {
   if (best.ksplit == 1) {
     const bool rect = best.bm == 128 && best.bn == 256 && kind != 3;
     if (best.bm == 256 && best.bn == 256 && (kind == 2 || kind == 0 || epi == EPI_SWIGLU) && dtl_fits(kind, M, N, K)) best.dtl = true;
-    if (rect && (kind != 1 || epi != EPI_F32) && dtl_rect_fits(kind, M, N, K)) best = TileChoice{128, 256, 1, true, true};
+    if (rect && (kind != 1 || epi != EPI_F32) && dtl_rect_fits(kind, M, N, K)) best = TileChoice{128, 256, 1, true, true, kind == 2};  // weight gradients: eight waves (measured 6-9 % faster)
     // Few rows, long k (a sub-batch of 1024 rows against K = 8192): 128 x 128 tiles fill the chip but run at the small
     // tile's rate; the 128 x 256 direct-to-LDS kernel over two k slices fills it too, and is faster even with its second
     // pass (measured on cold operands: 87-93 us against 108-116 us).
@@ -1061,21 +1300,21 @@ TileChoice pick_tile(int kind, int epi, int M, int N, int K, size_t ws_bytes) {
 
 int encode_variant(const TileChoice& t) {
   const bool rect = t.bm != t.bn;
-  return (t.dtl ? 200000000 : rect && t.wave_ksplit ? 100000000 : 0) + t.ksplit * 1000000 + t.bm * 1000 + t.bn;
+  return (t.dtl ? (t.pp ? 300000000 : 200000000) : rect && t.wave_ksplit ? 100000000 : 0) + t.ksplit * 1000000 + t.bm * 1000 + t.bn;
 }
 // variant -> TileChoice; false if no such instantiation exists or the k slices do not fit the problem / workspace
 bool decode_variant(int variant, int kind, int M, int N, int K, size_t ws_bytes, TileChoice* t) {
   if (variant <= 0) return false;
   const int wk = variant / 100000000, S = variant / 1000000 % 100, bm = variant / 1000 % 1000, bn = variant % 1000;
   const bool square = (bm == 256 && bn == 256) || (bm == 128 && bn == 128), rect = (bm == 256 && bn == 128) || (bm == 128 && bn == 256);
-  if (wk == 2 && S == 1) {  // direct-to-LDS kernels, one k slice
-    if (bm == 256 && bn == 256 && dtl_fits(kind, M, N, K)) { *t = TileChoice{256, 256, 1, false, true}; return true; }
-    if (bm == 128 && bn == 256 && dtl_rect_fits(kind, M, N, K)) { *t = TileChoice{128, 256, 1, true, true}; return true; }
+  if ((wk == 2 || wk == 3) && S == 1) {  // direct-to-LDS kernels (3: eight waves), one k slice
+    if (bm == 256 && bn == 256 && dtl_fits(kind, M, N, K)) { *t = TileChoice{256, 256, 1, false, true, wk == 3}; return true; }
+    if (bm == 128 && bn == 256 && dtl_rect_fits(kind, M, N, K)) { *t = TileChoice{128, 256, 1, true, true, wk == 3}; return true; }
     return false;
   }
-  if (wk == 2 && bm == 128 && bn == 256 && (S == 2 || S == 4)) {  // the 128 x 256 kernel over k slices of whole stages
+  if ((wk == 2 || wk == 3) && bm == 128 && bn == 256 && (S == 2 || S == 4)) {  // the 128 x 256 kernels over k slices of whole stages
     if (K % (S * BKR) || !dtl_rect_fits(kind, M, N, K / S) || (size_t)S * M * N * 4 > ws_bytes) return false;
-    *t = TileChoice{128, 256, S, true, true};
+    *t = TileChoice{128, 256, S, true, true, wk == 3};
     return true;
   }
   if (wk > 1 || !(square || rect) || (wk == 1 && !rect) || S < 1 || S > 8) return false;
@@ -1088,15 +1327,61 @@ bool decode_variant(int variant, int kind, int M, int N, int K, size_t ws_bytes,
 }
 
 template <bool A_KC, bool B_KC, int EPI>
-int launch_shape(const GemmArgs& g, float* ws, size_t ws_bytes, int forced_variant, hipStream_t s) {
+int launch_shape(const GemmArgs& g, float* ws, size_t ws_bytes, int forced_variant, int choice_rows, hipStream_t s) {
   constexpr int kind = !A_KC ? 2 : B_KC ? 1 : (EPI == EPI_BIAS_GELU || EPI == EPI_SWIGLU) ? 3 : 0;
   if (EPI == EPI_SWIGLU || EPI == EPI_DSWIGLU) ws_bytes = 0;  // their epilogues pair columns: no second pass over partial planes
   TileChoice t;
   if (forced_variant == 0) {
-    t = pick_tile(kind, EPI, g.M, g.N, g.K, ws ? ws_bytes : 0);
+    // Pinned choice: the number of k slices and whether waves split k -- the two things that set the order in which the
+    // fp32 terms of an output element are added -- come from (choice_rows, N, K, epilogue), so every launch over a part of
+    // those rows adds in the same order.  The 256 x 256 direct-to-LDS kernels need whole row tiles; a part that has none
+    // runs the staged kernel of the same tile, which adds in the same order.
+    const bool pinned = kind != 2 && choice_rows > g.M;
+    t = pick_tile(kind, EPI, pinned ? choice_rows : g.M, g.N, g.K, ws ? ws_bytes : 0);
+    if (pinned && t.dtl && t.bm == 256 && !dtl_fits(kind, g.M, g.N, g.K)) t.dtl = t.pp = false;
   } else if (!decode_variant(forced_variant, kind, g.M, g.N, g.K, ws ? ws_bytes : 0, &t)) {
     set_error("gemm: variant %d does not exist or does not fit M=%d N=%d K=%d with %zu workspace bytes", forced_variant, g.M, g.N, g.K, ws ? ws_bytes : (size_t)0);
     return OASES_EINVAL;
+  }
+  if (t.dtl && t.pp) {
+    constexpr bool kCanBeRagged = !A_KC || !B_KC;
+    const int bm = t.bm;
+    GemmArgs d = g;
+    d.tiles_m = (g.M + bm - 1) / bm;
+    d.tiles_n = (g.N + 255) / 256;
+    const bool whole = g.M % bm == 0 && g.N % 256 == 0;
+    if (!whole && bm == 256 && !kCanBeRagged) { set_error("gemm: direct-to-LDS kernel on a shape it does not cover"); return OASES_EINVAL; }
+    if (bm == 128 && t.ksplit > 1) {
+      if constexpr (EPI == EPI_SWIGLU || EPI == EPI_DSWIGLU) {
+        set_error("gemm: the SwiGLU epilogues do not run over k slices");
+        return OASES_EINVAL;
+      } else {
+        if (!ws) { set_error("gemm: split-K chosen without a workspace"); return OASES_ENULL; }
+        GemmArgs p = d;
+        p.ksplit = t.ksplit;
+        p.k_per = g.K / t.ksplit;
+        p.C = ws;
+        p.ldc = g.N;
+        const dim3 sgrid(d.tiles_m * d.tiles_n * t.ksplit);
+        if (whole) hipLaunchKernelGGL((gemm_pp_kernel<128, A_KC, B_KC, EPI_F32, true>), sgrid, dim3(512), 0, s, p);
+        else hipLaunchKernelGGL((gemm_pp_kernel<128, A_KC, B_KC, EPI_F32, false>), sgrid, dim3(512), 0, s, p);
+        OASES_LAUNCH_CHECK("gemm_pp_kernel (split-K)");
+        const long n4 = (long)g.M * (g.N / 4);
+        hipLaunchKernelGGL((splitk_fixup_kernel<EPI>), dim3((unsigned)((n4 + 255) / 256)), dim3(256), 0, s, ws, t.ksplit, d);
+        OASES_LAUNCH_CHECK("splitk_fixup_kernel");
+        return 0;
+      }
+    }
+    const dim3 grid(d.tiles_m * d.tiles_n);
+    if (bm == 128) {
+      if (whole) hipLaunchKernelGGL((gemm_pp_kernel<128, A_KC, B_KC, EPI, true>), grid, dim3(512), 0, s, d);
+      else hipLaunchKernelGGL((gemm_pp_kernel<128, A_KC, B_KC, EPI, false>), grid, dim3(512), 0, s, d);
+    } else {
+      if (whole) hipLaunchKernelGGL((gemm_pp_kernel<256, A_KC, B_KC, EPI, true>), grid, dim3(512), 0, s, d);
+      else if constexpr (kCanBeRagged) hipLaunchKernelGGL((gemm_pp_kernel<256, A_KC, B_KC, EPI, false>), grid, dim3(512), 0, s, d);
+    }
+    OASES_LAUNCH_CHECK("gemm_pp_kernel");
+    return 0;
   }
   if (t.dtl) {
     if (EPI == EPI_SWIGLU && t.bm == 128) {
@@ -1159,34 +1444,34 @@ int launch_shape(const GemmArgs& g, float* ws, size_t ws_bytes, int forced_varia
 }  // namespace
 
 #if OASES_GEMM_HAS(0)
-int launch_gemm_nn(const GemmArgs& g, int epi, float* ws, size_t ws_bytes, int forced_variant, hipStream_t s) {
+int launch_gemm_nn(const GemmArgs& g, int epi, float* ws, size_t ws_bytes, int forced_variant, int choice_rows, hipStream_t s) {
   switch (epi) {
-    case EPI_F32: return launch_shape<true, false, EPI_F32>(g, ws, ws_bytes, forced_variant, s);
-    case EPI_BF16: return launch_shape<true, false, EPI_BF16>(g, ws, ws_bytes, forced_variant, s);
-    case EPI_BIAS_BF16: return launch_shape<true, false, EPI_BIAS_BF16>(g, ws, ws_bytes, forced_variant, s);
-    case EPI_BIAS_GELU: return launch_shape<true, false, EPI_BIAS_GELU>(g, ws, ws_bytes, forced_variant, s);
-    case EPI_DGELU: return launch_shape<true, false, EPI_DGELU>(g, ws, ws_bytes, forced_variant, s);
-    case EPI_SWIGLU: return launch_shape<true, false, EPI_SWIGLU>(g, ws, ws_bytes, forced_variant, s);
+    case EPI_F32: return launch_shape<true, false, EPI_F32>(g, ws, ws_bytes, forced_variant, choice_rows, s);
+    case EPI_BF16: return launch_shape<true, false, EPI_BF16>(g, ws, ws_bytes, forced_variant, choice_rows, s);
+    case EPI_BIAS_BF16: return launch_shape<true, false, EPI_BIAS_BF16>(g, ws, ws_bytes, forced_variant, choice_rows, s);
+    case EPI_BIAS_GELU: return launch_shape<true, false, EPI_BIAS_GELU>(g, ws, ws_bytes, forced_variant, choice_rows, s);
+    case EPI_DGELU: return launch_shape<true, false, EPI_DGELU>(g, ws, ws_bytes, forced_variant, choice_rows, s);
+    case EPI_SWIGLU: return launch_shape<true, false, EPI_SWIGLU>(g, ws, ws_bytes, forced_variant, choice_rows, s);
     default: set_error("gemm: unknown epilogue %d", epi); return OASES_EINVAL;
   }
 }
 #endif
 #if OASES_GEMM_HAS(1)
-int launch_gemm_nt(const GemmArgs& g, int epi, float* ws, size_t ws_bytes, int forced_variant, hipStream_t s) {
+int launch_gemm_nt(const GemmArgs& g, int epi, float* ws, size_t ws_bytes, int forced_variant, int choice_rows, hipStream_t s) {
   switch (epi) {
-    case EPI_F32: return launch_shape<true, true, EPI_F32>(g, ws, ws_bytes, forced_variant, s);
-    case EPI_BF16: return launch_shape<true, true, EPI_BF16>(g, ws, ws_bytes, forced_variant, s);
-    case EPI_BIAS_BF16: return launch_shape<true, true, EPI_BIAS_BF16>(g, ws, ws_bytes, forced_variant, s);
-    case EPI_BIAS_GELU: return launch_shape<true, true, EPI_BIAS_GELU>(g, ws, ws_bytes, forced_variant, s);
-    case EPI_DGELU: return launch_shape<true, true, EPI_DGELU>(g, ws, ws_bytes, forced_variant, s);
-    case EPI_DSWIGLU: return launch_shape<true, true, EPI_DSWIGLU>(g, ws, ws_bytes, forced_variant, s);
+    case EPI_F32: return launch_shape<true, true, EPI_F32>(g, ws, ws_bytes, forced_variant, choice_rows, s);
+    case EPI_BF16: return launch_shape<true, true, EPI_BF16>(g, ws, ws_bytes, forced_variant, choice_rows, s);
+    case EPI_BIAS_BF16: return launch_shape<true, true, EPI_BIAS_BF16>(g, ws, ws_bytes, forced_variant, choice_rows, s);
+    case EPI_BIAS_GELU: return launch_shape<true, true, EPI_BIAS_GELU>(g, ws, ws_bytes, forced_variant, choice_rows, s);
+    case EPI_DGELU: return launch_shape<true, true, EPI_DGELU>(g, ws, ws_bytes, forced_variant, choice_rows, s);
+    case EPI_DSWIGLU: return launch_shape<true, true, EPI_DSWIGLU>(g, ws, ws_bytes, forced_variant, choice_rows, s);
     default: set_error("gemm: unknown epilogue %d", epi); return OASES_EINVAL;
   }
 }
 #endif
 #if OASES_GEMM_HAS(2)
 int launch_gemm_tn(const GemmArgs& g, float* ws, size_t ws_bytes, int forced_variant, hipStream_t s) {
-  return launch_shape<false, false, EPI_ACC_F32>(g, ws, ws_bytes, forced_variant, s);
+  return launch_shape<false, false, EPI_ACC_F32>(g, ws, ws_bytes, forced_variant, 0, s);
 }
 
 bool gemm_tn_pair_wins(int K, int M0, int N0, int M1, int N1) {
@@ -1214,8 +1499,8 @@ int launch_gemm_tn_pair(int K, int M0, int N0, const void* A0, int lda0, const v
   }
   GemmArgs g0{(const uint16_t*)A0, (const uint16_t*)B0, C0, nullptr, nullptr, M0, N0, K, lda0, ldb0, ldc0, 0, M0 / 128, N0 / 256, 1, K};
   GemmArgs g1{(const uint16_t*)A1, (const uint16_t*)B1, C1, nullptr, nullptr, M1, N1, K, lda1, ldb1, ldc1, 0, M1 / 128, N1 / 256, 1, K};
-  hipLaunchKernelGGL(gemm_dtl_rect_pair_kernel, dim3(g0.tiles_m * g0.tiles_n + g1.tiles_m * g1.tiles_n), dim3(256), 0, s, g0, g1);
-  OASES_LAUNCH_CHECK("gemm_dtl_rect_pair_kernel");
+  hipLaunchKernelGGL(gemm_pp_pair_kernel, dim3(g0.tiles_m * g0.tiles_n + g1.tiles_m * g1.tiles_n), dim3(512), 0, s, g0, g1);
+  OASES_LAUNCH_CHECK("gemm_pp_pair_kernel");
   return 0;
 }
 
@@ -1229,7 +1514,7 @@ int gemm_variant(int op, int epi, int M, int N, int K, size_t ws_bytes) {
 
 int launch_gemm(int op, int epi, int M, int N, int K, const void* A, int lda, const void* B, int ldb, void* C,
                 int ldc, const float* bias, void* aux, int ldaux, void* splitk_ws, size_t splitk_ws_bytes, int forced_variant,
-                hipStream_t s) {
+                hipStream_t s, int choice_rows) {
   float* ws = reinterpret_cast<float*>(splitk_ws);
   const size_t wsb = splitk_ws_bytes;
   if (M <= 0 || N <= 0 || K <= 0 || (M % 8) || (N % 8) || (K % 8) || (lda % 8) || (ldb % 8) || (ldc % 4) || (aux && ldaux % 4)) {
@@ -1255,7 +1540,7 @@ int launch_gemm(int op, int epi, int M, int N, int K, const void* A, int lda, co
     set_error("gemm: unknown epilogue %d", epi);
     return OASES_EINVAL;
   }
-  return nn ? launch_gemm_nn(g, epi, ws, wsb, forced_variant, s) : launch_gemm_nt(g, epi, ws, wsb, forced_variant, s);
+  return nn ? launch_gemm_nn(g, epi, ws, wsb, forced_variant, choice_rows, s) : launch_gemm_nt(g, epi, ws, wsb, forced_variant, choice_rows, s);
 }
 #endif  // NN part and host entry points
 

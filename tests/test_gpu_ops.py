@@ -232,11 +232,11 @@ def test_gemm_every_variant(B, lo, op, variant):
 
 @pytest.mark.parametrize("M,N,K", [(256, 256, 32), (512, 768, 96), (768, 256, 4096), (1024, 1024, 1056)])
 @pytest.mark.parametrize("op", ["NN", "NT", "TN"])
-def test_gemm_direct_to_lds_variant(B, lo, op, M, N, K):
+@pytest.mark.parametrize("variant", [201256256, 301256256])
+def test_gemm_direct_to_lds_variant(B, lo, op, M, N, K, variant):
     """The kernel whose tiles arrive by direct-to-LDS loads (variant 2xxxxxxxx: whole 256 x 256 tiles, K % 32 == 0): one to
     33 k tiles (prologue-only, tail and steady-state paths of its four-stage pipeline), every contraction form, and the
-    epilogues it supports."""
-    variant = 201256256
+    epilogues it supports.  301256256: the eight-wave kernel on the same tiles."""
     g = gen(M + N + K)
     a, b = bf16_round(randn(g, M, K)), bf16_round(randn(g, K, N, scale=0.05))
     ref = a @ b
@@ -269,8 +269,8 @@ def test_gemm_direct_to_lds_variant(B, lo, op, M, N, K):
                                       None, 0, None) == B.EINVAL
 
 
-@pytest.mark.parametrize("variant,M,N,K", [(201128256, 128, 256, 64), (201128256, 384, 512, 128), (201128256, 256, 768, 192),
-                                           (201128256, 640, 256, 4096), (201128256, 1152, 1024, 1088), (201128256, 128, 512, 320)])
+@pytest.mark.parametrize("variant,M,N,K", [(v, *mnk) for v in (201128256, 301128256) for mnk in
+                                           [(128, 256, 64), (384, 512, 128), (256, 768, 192), (640, 256, 4096), (1152, 1024, 1088), (128, 512, 320)]])
 @pytest.mark.parametrize("op", ["NN", "NT", "TN"])
 def test_gemm_direct_to_lds_rect_variant(B, lo, op, variant, M, N, K):
     """The kernel with 128 x 256 tiles fed by direct-to-LDS loads (variant 201128256; K % 64 == 0), here on whole tiles: one to 64
@@ -323,7 +323,12 @@ def test_gemm_direct_to_lds_rect_variant(B, lo, op, variant, M, N, K):
                                               (201128256, "NT", 136, 264, 64), (201128256, "NT", 1000, 1376, 320), (201128256, "NT", 72, 40, 128),
                                               (0, "NT", 4096, 1376, 4096), (201256256, "TN", 264, 520, 96),
                                               (201256256, "TN", 1000, 1376, 160), (201256256, "TN", 8, 8, 32), (201256256, "NN", 512, 776, 224),
-                                              (0, "TN", 1376, 4096, 2048), (0, "TN", 4096, 2752, 1024)])
+                                              (0, "TN", 1376, 4096, 2048), (0, "TN", 4096, 2752, 1024),
+                                              (301128256, "TN", 136, 264, 64), (301128256, "TN", 1376, 1000, 192), (301128256, "TN", 88, 8, 128),
+                                              (301128256, "NN", 256, 264, 128), (301128256, "NN", 392, 1000, 1088), (301128256, "NN", 8, 8, 64),
+                                              (301128256, "NT", 136, 264, 64), (301128256, "NT", 1000, 1376, 320), (301128256, "NT", 72, 40, 128),
+                                              (301256256, "TN", 264, 520, 96), (301256256, "TN", 1000, 1376, 160), (301256256, "TN", 8, 8, 32),
+                                              (301256256, "NN", 512, 776, 224)])
 def test_gemm_direct_to_lds_ragged_edges(B, lo, variant, op, M, N, K):
     """Operands may end inside the last tile of the direct-to-LDS kernels (128 x 256: any operand; 256 x 256: a row-indexed
     one, i.e. A of the TN form and B of the NN and TN forms): the rows / chunks beyond them are fetched from valid memory
@@ -407,7 +412,9 @@ def test_gemm_tn_pair(B, K, M0, N0, M1, N1):
 
 
 @pytest.mark.parametrize("variant,op,M,N,K", [(202128256, "NN", 256, 512, 256), (202128256, "NT", 136, 264, 384), (204128256, "NN", 128, 256, 1024),
-                                              (202128256, "TN", 392, 1000, 640), (204128256, "NT", 1024, 512, 4096)])
+                                              (202128256, "TN", 392, 1000, 640), (204128256, "NT", 1024, 512, 4096),
+                                              (302128256, "NN", 256, 512, 256), (302128256, "NT", 136, 264, 384), (304128256, "NN", 128, 256, 1024),
+                                              (302128256, "TN", 392, 1000, 640), (304128256, "NT", 1024, 512, 4096)])
 def test_gemm_direct_to_lds_k_slices(B, lo, variant, op, M, N, K):
     """The 128 x 256 direct-to-LDS kernel over two or four k slices of whole stages (variants 202128256, 204128256): fp32
     partial planes in the workspace, summed in slice order by the second pass, which applies the epilogue."""
@@ -459,7 +466,7 @@ def test_gemm_forced_variant_errors(B):
     call = lambda v, wsb: B.lib.oases_op_gemm_forced(v, B.GEMM_NN, B.EPI_F32, M, N, K, a.data_ptr(), K, a.data_ptr(), N, c.data_ptr(), N, None, None, 0,
                                                      ws.data_ptr(), wsb, None)
     assert call(1128128, ws.numel()) == 0
-    for bad in (0, -5, 1192192, 1064064, 101256256, 101128128, 201256128, 201128128, 301128256, 9128128, 128128):
+    for bad in (0, -5, 1192192, 1064064, 101256256, 101128128, 201256128, 201128128, 301128128, 401128256, 308128256, 9128128, 128128):
         assert call(bad, ws.numel()) == B.EINVAL, bad
     assert call(2128128, 1024) == B.EINVAL           # workspace too small for two planes
     assert call(8128128, ws.numel()) == B.EINVAL     # 8 slices of 64 do not all start inside K = 256
