@@ -119,6 +119,85 @@ def cpu_baseline(cfg, name):
             "sample": f"the whole step: rank-0 shard of {name}, forward+backward, fp32 torch-CPU oracle, {reps} repetition(s)"}
 
 
+class Workload:
+    """Device-resident inputs, parameters, gradients and workspace of one rank-0 shard."""
+
+    def __init__(self, name, n_sub=None, attn_dropout=None):
+        import torch
+        import synth_inputs as si
+        from paper_2305_16121_amd import binding as B
+        self.name = name
+        cfg = dict({**si.CONFIGS, **si.LLAMA_CONFIGS}[name])
+        if n_sub:
+            cfg["n_sub"] = n_sub
+        if attn_dropout is not None:
+            cfg["attn_dropout_p"] = attn_dropout
+        self.cfg = cfg
+        x, dy = si.make_activations(cfg, 0)
+        if cfg.get("arch") == "llama":
+            self.W = [B.pack_llama_rank_params(si.shard_llama_layer_params(si.make_llama_layer_params(cfg, l, 0), cfg, 0)) for l in range(cfg["n_layers"])]
+        else:
+            self.W = [B.pack_rank_params(si.shard_layer_params(si.make_layer_params(cfg, l, 0), cfg, 0)) for l in range(cfg["n_layers"])]
+        self.G = [B.zero_grads_like(w) for w in self.W]
+        self.xd, self.dyd = torch.from_numpy(x).cuda(), torch.from_numpy(dy).cuda()
+        self.yd, self.dxd = torch.empty_like(self.xd), torch.empty_like(self.xd)
+        self.s1, self.s2 = torch.cuda.Stream(), torch.cuda.Stream()
+        self.ws = None
+        self.peers = None
+
+    def handle(self, flags=0, n_sub=None):
+        import torch
+        from paper_2305_16121_amd import binding as B
+        H = B.Handle(B.make_cfg(self.cfg, rank=0, seed=0, flags=flags, n_sub=n_sub))
+        if self.ws is None or self.ws.numel() < H.workspace_bytes:
+            self.ws = torch.empty(H.workspace_bytes, dtype=torch.uint8, device="cuda")
+        return H
+
+    def make_peers(self):
+        """Peer sums at the four reduction points of every layer (any values: what is timed is the read beside the partial)."""
+        import torch
+        if self.peers is None:
+            self.peers = [{k: 0.01 * torch.randn_like(self.xd) for k in ("fwd_attn", "fwd_ffn", "bwd_ffn", "bwd_attn")} for _ in self.W]
+        return self.peers
+
+    def step(self, H, peers=None):
+        H.forward(self.W, self.xd, self.yd, self.ws, peers=peers, s_compute=self.s1, s_comm=self.s2)
+        H.backward(self.W, self.xd, self.dyd, self.dxd, self.G, self.ws, peers=peers, s_compute=self.s1, s_comm=self.s2)
+
+    def time_ms(self, H, steps, warmup, peers=None):
+        import torch
+        for _ in range(warmup):
+            self.step(H, peers)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            self.step(H, peers)
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / steps * 1e3
+
+
+def mfma_rate(B):
+    """Sustained rate of a register-resident MFMA loop (no memory traffic) with zero and with pseudo-random operands."""
+    import torch
+    wgs, iters = 1024, 4000
+    out = torch.empty(wgs * 256, dtype=torch.float32, device="cuda")
+    res = {}
+    for label, rnd in (("zero_operands", 0), ("random_operands", 1)):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        st = torch.cuda.current_stream()
+        for _ in range(2):
+            B.check(B.lib.oases_probe_mfma_rate(rnd, iters, wgs, out.data_ptr(), st.cuda_stream))
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(5):
+            B.check(B.lib.oases_probe_mfma_rate(rnd, iters, wgs, out.data_ptr(), st.cuda_stream))
+        e1.record()
+        torch.cuda.synchronize()
+        res[label] = round(5 * wgs * 4 * iters * 8 * 32768.0 / (e0.elapsed_time(e1) * 1e-3) / 1e12, 1)
+    res["unit"] = "TFLOP/s"
+    return res
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -133,6 +212,7 @@ def main():
     ap.add_argument("--graph", action="store_true", help="capture one step into a HIP graph and time its replays (launch-bound small layers)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-profile", action="store_true")
+    ap.add_argument("--no-extra", action="store_true", help="skip the further timings (one stream, n_sub = 1, peer sums, pinned kernels, C5, MFMA rate)")
     ap.add_argument("--calib-copy", action="store_true",
                     help="run one plain elementwise kernel of known size (reads and writes 256 MiB) first: the unit check for rocprofv3 byte counters")
     a = ap.parse_args()
@@ -145,28 +225,13 @@ def main():
     if not torch.cuda.is_available():
         sys.exit("bench.py: no GPU visible")
 
-    cfg = dict({**si.CONFIGS, **si.LLAMA_CONFIGS}[a.config])
-    if a.n_sub:
-        cfg["n_sub"] = a.n_sub
-    if a.attn_dropout is not None:
-        cfg["attn_dropout_p"] = a.attn_dropout
+    wl = Workload(a.config, a.n_sub, a.attn_dropout)
+    cfg = wl.cfg
     M, h = cfg["batch"] * cfg["seq"], cfg["hidden"]
-    x, dy = si.make_activations(cfg, 0)
-    if cfg.get("arch") == "llama":
-        W = [B.pack_llama_rank_params(si.shard_llama_layer_params(si.make_llama_layer_params(cfg, l, 0), cfg, 0)) for l in range(cfg["n_layers"])]
-    else:
-        W = [B.pack_rank_params(si.shard_layer_params(si.make_layer_params(cfg, l, 0), cfg, 0)) for l in range(cfg["n_layers"])]
-    G = [B.zero_grads_like(w) for w in W]
-    xd, dyd = torch.from_numpy(x).cuda(), torch.from_numpy(dy).cuda()
-    yd, dxd = torch.empty_like(xd), torch.empty_like(xd)
+    W, G, xd, dyd, yd, dxd, s1, s2 = wl.W, wl.G, wl.xd, wl.dyd, wl.yd, wl.dxd, wl.s1, wl.s2
     flags = (B.FLAG_SERIALISE if a.serialise else 0) | (B.FLAG_RECOMPUTE if a.recompute else 0)
-    H = B.Handle(B.make_cfg(cfg, rank=0, seed=0, flags=flags))
-    ws = torch.empty(H.workspace_bytes, dtype=torch.uint8, device="cuda")
-    s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
-
-    def step(handle):
-        handle.forward(W, xd, yd, ws, s_compute=s1, s_comm=s2)
-        handle.backward(W, xd, dyd, dxd, G, ws, s_compute=s1, s_comm=s2)
+    H = wl.handle(flags)
+    step = wl.step
 
     if a.calib_copy:
         src = torch.ones(64 << 20, dtype=torch.float32, device="cuda")
@@ -205,7 +270,7 @@ def main():
 
     # per-operator HIP-event timers over the same schedule (serialised so that every bracket holds one operator)
     if not a.no_profile:
-        HP = B.Handle(B.make_cfg(cfg, rank=0, seed=0, flags=B.FLAG_SERIALISE | B.FLAG_PROFILE | (B.FLAG_RECOMPUTE if a.recompute else 0)))
+        HP = wl.handle(B.FLAG_SERIALISE | B.FLAG_PROFILE | (B.FLAG_RECOMPUTE if a.recompute else 0))
         acc = {}
         reps = max(3, min(a.steps, 10))
         step(HP)
@@ -245,6 +310,27 @@ def main():
                            "unit": "TFLOP/s", "frac": round(dom["tflops"] / PEAK_BF16_TFLOPS, 4), "traffic": traffic,
                            "avg_launch_ms": dom["avg_ms"], "flops_per_launch": d["flops"] / d["launches"]}
         HP.close()
+
+    # further measurements of the same build, each its own short timing (not part of `value`)
+    if not a.no_extra:
+        k, w = max(5, a.steps // 2), 3
+        rflag = B.FLAG_RECOMPUTE if a.recompute else 0
+        ex = {}
+        ex["two_streams_ms"] = round(wl.time_ms(wl.handle(rflag), k, w), 4)
+        ex["one_stream_ms"] = round(wl.time_ms(wl.handle(rflag | B.FLAG_SERIALISE), k, w), 4)
+        ex["n_sub_1_ms"] = round(wl.time_ms(wl.handle(rflag, n_sub=1), k, w), 4)          # arithmetic-density loss of sub-batching (Fig. 5)
+        ex["with_peer_sums_ms"] = round(wl.time_ms(wl.handle(rflag), k, w, peers=wl.make_peers()), 4)   # reduction points read a peer sum
+        ex["pinned_kernel_choice_ms"] = round(wl.time_ms(wl.handle(rflag | B.FLAG_PIN_GEMM), k, w), 4)
+        ex["mfma_rate_from_registers"] = mfma_rate(B)
+        if a.config == "C4":          # the other configuration the target is quoted on
+            w5 = Workload("C5")
+            ms5 = w5.time_ms(w5.handle(0), k, w)
+            f5 = model_flops(w5.cfg)
+            ex["C5"] = {"workload": "C5: GPT layer h=8192 heads=64 seq=2048 batch=2 t=8 rank 0 causal p=0.1, n_sub=4, two streams",
+                        "ms_per_step": round(ms5, 4), "tflops": round(f5 / ms5 / 1e9, 1), "frac_of_bf16_peak": round(f5 / ms5 / 1e9 / PEAK_BF16_TFLOPS, 4),
+                        "one_stream_ms": round(w5.time_ms(w5.handle(B.FLAG_SERIALISE), k, w), 4),
+                        "n_sub_1_ms": round(w5.time_ms(w5.handle(0, n_sub=1), k, w), 4)}
+        out["extra"] = ex
 
     if not a.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, a.config)

@@ -150,6 +150,34 @@ int oases_backward(oases_handle *h, const oases_weights *w, const void *x, const
                    void *dx, const oases_grads *g, const oases_peer_sums *peers, void *workspace,
                    void *stream_compute, void *stream_comm);
 
+/* Segment-level calls: lock-step emulation of the t ranks of a partition on one GPU.  What rank r feeds into its FFN block
+ * depends on the other ranks' attention partials, so t ranks can only be run side by side one computation sequence at a
+ * time: each rank (its own handle, weights and workspace) runs a segment up to its reduction point, the caller forms
+ * y = sum_i x_i over the ranks' partials (the AllReduce of Sec. IV-B, whose input gradient is its output gradient, Eq. (1))
+ * and hands the sum to every rank's next segment.  A segment runs the operators of ONE layer for ALL sub-batches, in the
+ * order of oases_schedule_dump, on one stream.
+ *   forward  segment 0: [LN1 (first layer), QKV, attention, projection]              ends in   Z1_r  (fwd_attn point)
+ *            segment 1: [bias+dropout+residual+LN2 on Z1, FC1+GeLU, FC2]             Z1 in,    ends in Z2_r (fwd_ffn point)
+ *            segment 2: [bias+dropout+residual on Z2 (+ LN1 of the next layer)]      Z2 in,    writes the layer output
+ *   backward segment 2: [dropout backward of dy]  (top layer only; below it this work belongs to segment 3 of the layer above)
+ *            segment 1: [FC2 and FC1 input gradients, their weight gradients]        ends in   dV2_r (bwd_ffn point)
+ *            segment 0: [LN2 backward + residual + dropout backward on dV2, projection / attention / QKV gradients]
+ *                                                                                     dV2 in,   ends in dU_r (bwd_attn point)
+ *            segment 3: [LN1 backward + residual on dU]                               dU in,    writes dx (or the layer below's dy)
+ * Forward: layers bottom-up, segments 0, 1, 2; backward: layers top-down, segments 2 (top layer), 1, 0, 3.
+ * partial_out: device [M,h] fp32 that receives the partial the segment ends in, or NULL (it then stays in the workspace
+ *   tensor "z1" / "z2" / "dv2" / "du", see oases_workspace_tensor); EINVAL if given for a segment that ends in none.
+ * reduced_in: device [M,h] fp32, the REDUCED tensor (sum over all ranks, this rank's partial included) the segment starts
+ *   from, or NULL to read this rank's own partial from the workspace (t = 1); EINVAL if given for a segment that starts
+ *   from none.  x, y, dy, dx, w, g, workspace as in oases_forward / oases_backward (the same workspace through all
+ *   segments of a step); peer sums do not exist at this level.  Run back to back with NULL partial_out / reduced_in the
+ *   segments give what oases_forward / oases_backward give without peer sums, bit for bit. */
+int oases_forward_segment(oases_handle *h, int layer, int segment, const oases_weights *w, const void *x, void *y,
+                          void *workspace, void *partial_out, const void *reduced_in, void *stream);
+int oases_backward_segment(oases_handle *h, int layer, int segment, const oases_weights *w, const void *x,
+                           const void *dy, void *dx, const oases_grads *g, void *workspace, void *partial_out,
+                           const void *reduced_in, void *stream);
+
 /* The operator order of the schedule as text, one operator per line
  * ("<stream> <op> L<layer> sb<sub-batch>", "sb*" = all sub-batches at once), NUL-terminated into buf (at most n bytes).
  * Returns the number of bytes the full text needs (like snprintf).  Host only. */
@@ -339,6 +367,14 @@ int oases_op_attention_dropout_bwd(const void *qkv, const void *out, const void 
                                    void *delta, void *dqkv, int batch, int seq, int heads, int head_dim,
                                    int causal, int row0, int rows, uint64_t seed, int layer, float p,
                                    int head0, int heads_total, void *stream);
+
+/* Measurement helper for the roofline the GEMMs are priced against (no step of the path): every wave of `workgroups`
+ * 256-thread workgroups issues iters x 8 register-resident v_mfma_f32_32x32x16_bf16 (2 * 32*32*16 flop each) on 8
+ * independent accumulators, with no memory traffic; random_operands = 0: all-zero operands, 1: pseudo-random, roughly
+ * normal bf16 operands (on a power-capped part the sustained clock, and so the rate, depends on the operand values).
+ * out: device fp32 [workgroups * 256], written once per thread.  The caller times the launch:
+ * flop = workgroups * 4 waves * iters * 8 * 32768. */
+int oases_probe_mfma_rate(int random_operands, int iters, int workgroups, void *out, void *stream);
 
 #ifdef __cplusplus
 }

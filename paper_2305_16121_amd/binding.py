@@ -56,6 +56,8 @@ _sig("oases_destroy", None, _P)
 _sig("oases_workspace_bytes", _sz, _P)
 _sig("oases_forward", _i, _P, C.POINTER(Weights), _P, _P, C.POINTER(PeerSums), _P, _P, _P)
 _sig("oases_backward", _i, _P, C.POINTER(Weights), _P, _P, _P, C.POINTER(Grads), C.POINTER(PeerSums), _P, _P, _P)
+_sig("oases_forward_segment", _i, _P, _i, _i, C.POINTER(Weights), _P, _P, _P, _P, _P, _P)
+_sig("oases_backward_segment", _i, _P, _i, _i, C.POINTER(Weights), _P, _P, _P, C.POINTER(Grads), _P, _P, _P, _P)
 _sig("oases_schedule_dump", _i, _P, _i, C.c_char_p, _sz)
 _sig("oases_profile_read", _i, _P, _i, C.POINTER(C.c_float), _i)
 _sig("oases_workspace_tensor", _i, _P, C.c_char_p, _i, C.POINTER(_sz), C.POINTER(_sz))
@@ -77,6 +79,7 @@ _sig("oases_op_gemm_forced", _i, _i, _i, _i, _i, _i, _i, _P, _i, _P, _i, _P, _i,
 _sig("oases_gemm_workspace_bytes", _sz, _P)
 _sig("oases_op_colsum_bf16", _i, _P, _i, _i, _i, _P, _P, _P)
 _sig("oases_op_colsum_bf16_static", _i, _P, _i, _i, _i, _P, _P)
+_sig("oases_probe_mfma_rate", _i, _i, _i, _i, _P, _P)
 _sig("oases_op_attention_fwd", _i, _P, _P, _P, _i, _i, _i, _i, _i, _i, _i, _P)
 _sig("oases_op_attention_bwd", _i, _P, _P, _P, _P, _P, _P, _i, _i, _i, _i, _i, _i, _i, _P)
 _sig("oases_op_attention_dropout_fwd", _i, _P, _P, _P, _i, _i, _i, _i, _i, _i, _i, _u64, _i, _f, _i, _i, _P)
@@ -180,6 +183,18 @@ class Handle:
         p = self._structs(PeerSums, _PEERS, peers) if peers is not None else None
         check(lib.oases_backward(self._h, w, ptr(x), ptr(dy), ptr(dx), g, p, ptr(workspace), stream_ptr(s_compute),
                                  stream_ptr(s_comm)))
+
+
+    def forward_segment(self, layer, segment, weights, x, y, workspace, partial_out=None, reduced_in=None, stream=None):
+        w = self._structs(Weights, _PARAMS, weights)
+        check(lib.oases_forward_segment(self._h, layer, segment, w, ptr(x), ptr(y), ptr(workspace), ptr(partial_out), ptr(reduced_in),
+                                        stream_ptr(stream)))
+
+    def backward_segment(self, layer, segment, weights, x, dy, dx, grads, workspace, partial_out=None, reduced_in=None, stream=None):
+        w = self._structs(Weights, _PARAMS, weights)
+        g = self._structs(Grads, _PARAMS, grads)
+        check(lib.oases_backward_segment(self._h, layer, segment, w, ptr(x), ptr(dy), ptr(dx), g, ptr(workspace), ptr(partial_out),
+                                         ptr(reduced_in), stream_ptr(stream)))
 
 
 # ------------------------------------------------------------------------------------------------

@@ -89,6 +89,9 @@ struct Op {
   int record;  // event recorded after the op (-1 none)
 };
 
+// workspace tensors of a layer, in the order plan_workspace lays them out (index into oases_handle::tensors)
+enum TensorId { T_u, T_mu1, T_rstd1, T_qkv, T_attn, T_lse, T_z1, T_x1, T_mu2, T_rstd2, T_v2, T_pre, T_f, T_z2, T_y, T_dz2, T_dg, T_dv2, T_dx1, T_dz1, T_da, T_delta, T_dqkv, T_du, T_dy, T_rope, T_s1, T_s2, T_ds2, T_COUNT };
+
 struct Tensor {
   const char* name;
   size_t offset, bytes;
@@ -119,7 +122,7 @@ namespace oases {
 
 static size_t align_up(size_t x) { return (x + 255) & ~(size_t)255; }
 
-static void plan_workspace(oases_handle* H) {
+static bool plan_workspace(oases_handle* H) {
   const size_t M = H->M, h = H->h, hp = H->hp, fp = H->fp, fw = H->fw, st = (size_t)H->b * H->heads_l * H->s;
   const size_t rope = H->llama ? (size_t)H->s * (H->d / 2) * 8 : 0;  // (cos, sin) table; layer 0's copy is the one in use
   struct { const char* n; size_t bytes; } list[] = {
@@ -149,6 +152,9 @@ static void plan_workspace(oases_handle* H) {
     }
   }
   H->layer_bytes = off;
+  static const char* kIdNames[T_COUNT] = {"u", "mu1", "rstd1", "qkv", "attn", "lse", "z1", "x1", "mu2", "rstd2", "v2", "pre", "f", "z2", "y", "dz2", "dg", "dv2", "dx1", "dz1", "da", "delta", "dqkv", "du", "dy", "rope", "s1", "s2", "ds2"};
+  for (int i = 0; i < T_COUNT; i++)
+    if ((int)H->tensors.size() != T_COUNT || strcmp(H->tensors[i].name, kIdNames[i])) return false;  // TensorId out of step with the list above
   size_t tot = off * H->L;
   H->shared_off = tot;
   tot += soff;
@@ -165,6 +171,7 @@ static void plan_workspace(oases_handle* H) {
   H->gemm_ws_bytes = 8 * mn * 4 < kSplitKWorkspaceBytes ? 8 * mn * 4 : kSplitKWorkspaceBytes;
   tot += align_up(H->gemm_ws_bytes);
   H->total_bytes = tot;
+  return true;
 }
 
 static size_t tensor_off(const oases_handle* H, const char* name, int layer) {
@@ -297,11 +304,16 @@ struct Run {
   const float* dy;  // backward input
   float* dx;        // backward output
   hipStream_t st[2];
+  // segment-level calls: the tensor at reduction point k (0..3 = R1..R4) that the producing GEMM writes (instead of the
+  // workspace partial) and that the consuming kernel reads as the already reduced sum (instead of partial + peer sum)
+  float* partial_out[4] = {nullptr, nullptr, nullptr, nullptr};
+  const float* reduced_in[4] = {nullptr, nullptr, nullptr, nullptr};
 };
 
 template <typename T>
-static T* wsp(const Run& R, const char* name, int layer) {
-  return reinterpret_cast<T*>(R.ws + tensor_off(R.H, name, layer));
+static T* wsp(const Run& R, TensorId id, int layer) {  // offsets were resolved when the handle was created
+  const Tensor& t = R.H->tensors[id];
+  return reinterpret_cast<T*>(R.ws + (t.shared ? R.H->shared_off + t.offset : (size_t)layer * R.H->layer_bytes + t.offset));
 }
 
 static int run_op(const Run& R, const Op& op) {
@@ -313,22 +325,30 @@ static int run_op(const Run& R, const Op& op) {
   const oases_weights& W = R.w[l];
   const oases_peer_sums* P = R.peers ? &R.peers[l] : nullptr;
   auto peer = [&](const void* base) -> const float* { return base ? (const float*)base + r0 * h : nullptr; };
+  static const TensorId kPartId[4] = {T_z1, T_z2, T_dv2, T_du};
+  // reduction point k: where its producer writes this sub-batch's rows, what its consumer reads, and the peer sum beside it
+  auto part_w = [&](int k) -> float* { return (R.partial_out[k] ? R.partial_out[k] : wsp<float>(R, kPartId[k], l)) + r0 * h; };
+  auto part_r = [&](int k) -> const float* { return (R.reduced_in[k] ? R.reduced_in[k] : wsp<float>(R, kPartId[k], l)) + r0 * h; };
+  auto peer_k = [&](int k) -> const float* {
+    if (R.reduced_in[k] || !P) return nullptr;   // an already reduced tensor has the peers in it
+    return peer(k == 0 ? P->fwd_attn : k == 1 ? P->fwd_ffn : k == 2 ? P->bwd_ffn : P->bwd_attn);
+  };
   const float p = H->cfg.dropout_p;
   const uint64_t seed = H->cfg.seed;
-  const float* xin = l == 0 ? R.x : wsp<float>(R, "y", l - 1);                 // layer input
-  float* yout = l == L - 1 ? R.y : wsp<float>(R, "y", l);                      // layer output
-  const float* dyin = R.dy && l == L - 1 ? R.dy : wsp<float>(R, "dy", l);      // gradient of the layer output
-  float* dxout = l == 0 ? R.dx : wsp<float>(R, "dy", l - 1);                   // gradient of the layer input
+  const float* xin = l == 0 ? R.x : wsp<float>(R, T_y, l - 1);                 // layer input
+  float* yout = l == L - 1 ? R.y : wsp<float>(R, T_y, l);                      // layer output
+  const float* dyin = R.dy && l == L - 1 ? R.dy : wsp<float>(R, T_dy, l);      // gradient of the layer output
+  float* dxout = l == 0 ? R.dx : wsp<float>(R, T_dy, l - 1);                   // gradient of the layer input
   float* scr_comm = reinterpret_cast<float*>(R.ws + H->scratch_comm_off);
   float* scr_comp = reinterpret_cast<float*>(R.ws + H->scratch_compute_off);
   void* gws = R.ws + H->gemm_ws_off;  // split-K partial planes (compute stream only)
   const int pin = (H->cfg.flags & OASES_FLAG_PIN_GEMM) ? H->M : 0;  // kernels chosen as for all M rows, whatever the sub-batch
-  uint16_t* u = wsp<uint16_t>(R, "u", l);
-  uint16_t* qkv = wsp<uint16_t>(R, "qkv", l);
-  uint16_t* attn = wsp<uint16_t>(R, "attn", l);
-  uint16_t* v2 = wsp<uint16_t>(R, "v2", l);
-  uint16_t* pre = wsp<uint16_t>(R, "pre", l);
-  uint16_t* f = wsp<uint16_t>(R, "f", l);
+  uint16_t* u = wsp<uint16_t>(R, T_u, l);
+  uint16_t* qkv = wsp<uint16_t>(R, T_qkv, l);
+  uint16_t* attn = wsp<uint16_t>(R, T_attn, l);
+  uint16_t* v2 = wsp<uint16_t>(R, T_v2, l);
+  uint16_t* pre = wsp<uint16_t>(R, T_pre, l);
+  uint16_t* f = wsp<uint16_t>(R, T_f, l);
   const bool rms = H->llama;   // RMSNorm, no biases: the bias / beta / mean arguments below are NULL and unused
   const int fw = H->fw;
   if (H->bert) {
@@ -341,41 +361,41 @@ static int run_op(const Run& R, const Op& op) {
       case R_LN1:
         return launch_cast_bf16(xin + r0 * h, u + r0 * h, (int64_t)Ms * h, s);
       case R_LN2:
-        return launch_cast_bf16(wsp<float>(R, "x1", l) + r0 * h, v2 + r0 * h, (int64_t)Ms * h, s);
+        return launch_cast_bf16(wsp<float>(R, T_x1, l) + r0 * h, v2 + r0 * h, (int64_t)Ms * h, s);
       case F_R1:
-        return launch_bdr_ln(wsp<float>(R, "z1", l) + r0 * h, peer(P ? P->fwd_attn : nullptr), (const float*)W.bo, xin + r0 * h,
-                             wsp<float>(R, "s1", l) + r0 * h, (const float*)W.ln1_g, (const float*)W.ln1_b, v2 + r0 * h,
-                             wsp<float>(R, "mu1", l) + r0, wsp<float>(R, "rstd1", l) + r0, Ms, h, H->eps,
-                             make_drop_cfg(seed, l, 0, p), (int64_t)r0, s, false, wsp<float>(R, "x1", l) + r0 * h);
+        return launch_bdr_ln(part_r(0), peer_k(0), (const float*)W.bo, xin + r0 * h,
+                             wsp<float>(R, T_s1, l) + r0 * h, (const float*)W.ln1_g, (const float*)W.ln1_b, v2 + r0 * h,
+                             wsp<float>(R, T_mu1, l) + r0, wsp<float>(R, T_rstd1, l) + r0, Ms, h, H->eps,
+                             make_drop_cfg(seed, l, 0, p), (int64_t)r0, s, false, wsp<float>(R, T_x1, l) + r0 * h);
       case F_R2: {
         const bool more = l + 1 < L;  // the bf16 copy of y is the next layer's GEMM operand
-        return launch_bdr_ln(wsp<float>(R, "z2", l) + r0 * h, peer(P ? P->fwd_ffn : nullptr), (const float*)W.b2,
-                             wsp<float>(R, "x1", l) + r0 * h, wsp<float>(R, "s2", l) + r0 * h, (const float*)W.ln2_g,
-                             (const float*)W.ln2_b, more ? wsp<uint16_t>(R, "u", l + 1) + r0 * h : nullptr,
-                             wsp<float>(R, "mu2", l) + r0, wsp<float>(R, "rstd2", l) + r0, Ms, h, H->eps,
+        return launch_bdr_ln(part_r(1), peer_k(1), (const float*)W.b2,
+                             wsp<float>(R, T_x1, l) + r0 * h, wsp<float>(R, T_s2, l) + r0 * h, (const float*)W.ln2_g,
+                             (const float*)W.ln2_b, more ? wsp<uint16_t>(R, T_u, l + 1) + r0 * h : nullptr,
+                             wsp<float>(R, T_mu2, l) + r0, wsp<float>(R, T_rstd2, l) + r0, Ms, h, H->eps,
                              make_drop_cfg(seed, l, 1, p), (int64_t)r0, s, false, yout + r0 * h);
       }
       case B_BDR2:  // top of the stack: dy through LN2, then the dropout backward of the FFN branch
-        return launch_layernorm_bwd(dyin + r0 * h, nullptr, nullptr, wsp<float>(R, "s2", l) + r0 * h, wsp<float>(R, "mu2", l) + r0,
-                                    wsp<float>(R, "rstd2", l) + r0, (const float*)W.ln2_g, wsp<float>(R, "ds2", l) + r0 * h,
-                                    (float*)R.g[l].ln2_g, (float*)R.g[l].ln2_b, wsp<uint16_t>(R, "dz2", l) + r0 * h, (float*)R.g[l].b2, Ms,
+        return launch_layernorm_bwd(dyin + r0 * h, nullptr, nullptr, wsp<float>(R, T_s2, l) + r0 * h, wsp<float>(R, T_mu2, l) + r0,
+                                    wsp<float>(R, T_rstd2, l) + r0, (const float*)W.ln2_g, wsp<float>(R, T_ds2, l) + r0 * h,
+                                    (float*)R.g[l].ln2_g, (float*)R.g[l].ln2_b, wsp<uint16_t>(R, T_dz2, l) + r0 * h, (float*)R.g[l].b2, Ms,
                                     h, make_drop_cfg(seed, l, 1, p), (int64_t)r0, scr_comm, s, false, true);
       case B_R3:  // gradient of x1 = FFN-input gradient (reduced) + residual branch ds2, through LN1
-        return launch_layernorm_bwd(wsp<float>(R, "dv2", l) + r0 * h, peer(P ? P->bwd_ffn : nullptr), wsp<float>(R, "ds2", l) + r0 * h,
-                                    wsp<float>(R, "s1", l) + r0 * h, wsp<float>(R, "mu1", l) + r0, wsp<float>(R, "rstd1", l) + r0,
-                                    (const float*)W.ln1_g, wsp<float>(R, "dx1", l) + r0 * h, (float*)R.g[l].ln1_g, (float*)R.g[l].ln1_b,
-                                    wsp<uint16_t>(R, "dz1", l) + r0 * h, (float*)R.g[l].bo, Ms, h, make_drop_cfg(seed, l, 0, p),
+        return launch_layernorm_bwd(part_r(2), peer_k(2), wsp<float>(R, T_ds2, l) + r0 * h,
+                                    wsp<float>(R, T_s1, l) + r0 * h, wsp<float>(R, T_mu1, l) + r0, wsp<float>(R, T_rstd1, l) + r0,
+                                    (const float*)W.ln1_g, wsp<float>(R, T_dx1, l) + r0 * h, (float*)R.g[l].ln1_g, (float*)R.g[l].ln1_b,
+                                    wsp<uint16_t>(R, T_dz1, l) + r0 * h, (float*)R.g[l].bo, Ms, h, make_drop_cfg(seed, l, 0, p),
                                     (int64_t)r0, scr_comm, s, false, true);
       case B_R4:  // gradient of the layer input = QKV-input gradient (reduced) + residual branch ds1
         if (l == 0)
-          return launch_add3(wsp<float>(R, "du", l) + r0 * h, wsp<float>(R, "dx1", l) + r0 * h, peer(P ? P->bwd_attn : nullptr),
+          return launch_add3(part_r(3), wsp<float>(R, T_dx1, l) + r0 * h, peer_k(3),
                              dxout + r0 * h, (int64_t)Ms * h, s);
         // ... which is the output gradient of the layer below: straight through its LN2 and FFN-branch dropout
-        return launch_layernorm_bwd(wsp<float>(R, "du", l) + r0 * h, peer(P ? P->bwd_attn : nullptr), wsp<float>(R, "dx1", l) + r0 * h,
-                                    wsp<float>(R, "s2", l - 1) + r0 * h, wsp<float>(R, "mu2", l - 1) + r0,
-                                    wsp<float>(R, "rstd2", l - 1) + r0, (const float*)R.w[l - 1].ln2_g,
-                                    wsp<float>(R, "ds2", l - 1) + r0 * h, (float*)R.g[l - 1].ln2_g, (float*)R.g[l - 1].ln2_b,
-                                    wsp<uint16_t>(R, "dz2", l - 1) + r0 * h, (float*)R.g[l - 1].b2, Ms, h,
+        return launch_layernorm_bwd(part_r(3), peer_k(3), wsp<float>(R, T_dx1, l) + r0 * h,
+                                    wsp<float>(R, T_s2, l - 1) + r0 * h, wsp<float>(R, T_mu2, l - 1) + r0,
+                                    wsp<float>(R, T_rstd2, l - 1) + r0, (const float*)R.w[l - 1].ln2_g,
+                                    wsp<float>(R, T_ds2, l - 1) + r0 * h, (float*)R.g[l - 1].ln2_g, (float*)R.g[l - 1].ln2_b,
+                                    wsp<uint16_t>(R, T_dz2, l - 1) + r0 * h, (float*)R.g[l - 1].b2, Ms, h,
                                     make_drop_cfg(seed, l - 1, 1, p), (int64_t)r0, scr_comm, s, false, true);
       default:
         break;  // GEMMs, attention, bias sums: as in the GPT layer
@@ -384,28 +404,28 @@ static int run_op(const Run& R, const Op& op) {
   switch (op.kind) {
     case F_LN1:
       return launch_layernorm_fwd(xin + r0 * h, (const float*)W.ln1_g, (const float*)W.ln1_b, u + r0 * h,
-                                  wsp<float>(R, "mu1", l) + r0, wsp<float>(R, "rstd1", l) + r0, Ms, h, H->eps, s, rms);
+                                  wsp<float>(R, T_mu1, l) + r0, wsp<float>(R, T_rstd1, l) + r0, Ms, h, H->eps, s, rms);
     case F_QKV:
       return launch_gemm(OASES_GEMM_NN, rms ? OASES_EPI_BF16 : OASES_EPI_BIAS_BF16, Ms, 3 * hp, h, u + r0 * h, h, W.wqkv, 3 * hp,
                          qkv + r0 * 3 * hp, 3 * hp, (const float*)W.bqkv, nullptr, 0, gws, H->gemm_ws_bytes, 0, s, pin);
     case F_ROPE_TABLE:
-      return launch_rope_table(wsp<float>(R, "rope", 0), H->s, H->d, H->theta, s);
+      return launch_rope_table(wsp<float>(R, T_rope, 0), H->s, H->d, H->theta, s);
     case F_ROPE:
     case R_ROPE:
-      return launch_rope(qkv + r0 * 3 * hp, 3 * hp, Ms, (int64_t)r0, H->s, H->heads_l, H->d, wsp<float>(R, "rope", 0), 0, s);
+      return launch_rope(qkv + r0 * 3 * hp, 3 * hp, Ms, (int64_t)r0, H->s, H->heads_l, H->d, wsp<float>(R, T_rope, 0), 0, s);
     case B_ROPE:
-      return launch_rope(wsp<uint16_t>(R, "dqkv", l) + r0 * 3 * hp, 3 * hp, Ms, (int64_t)r0, H->s, H->heads_l, H->d,
-                         wsp<float>(R, "rope", 0), 1, s);
+      return launch_rope(wsp<uint16_t>(R, T_dqkv, l) + r0 * 3 * hp, 3 * hp, Ms, (int64_t)r0, H->s, H->heads_l, H->d,
+                         wsp<float>(R, T_rope, 0), 1, s);
     case F_ATTN:
-      return launch_attention_fwd(qkv, attn, wsp<float>(R, "lse", l), H->b, H->s, H->heads_l, H->d, H->cfg.causal, (int)r0, Ms, s,
+      return launch_attention_fwd(qkv, attn, wsp<float>(R, T_lse, l), H->b, H->s, H->heads_l, H->d, H->cfg.causal, (int)r0, Ms, s,
                                   seed, l, H->cfg.attn_dropout_p, H->r * H->heads_l, H->nh);
     case F_PROJ:
-      return launch_gemm(OASES_GEMM_NN, OASES_EPI_F32, Ms, h, hp, attn + r0 * hp, hp, W.wo, h, wsp<float>(R, "z1", l) + r0 * h, h,
+      return launch_gemm(OASES_GEMM_NN, OASES_EPI_F32, Ms, h, hp, attn + r0 * hp, hp, W.wo, h, part_w(0), h,
                          nullptr, nullptr, 0, gws, H->gemm_ws_bytes, 0, s, pin);
     case F_R1:
-      return launch_bdr_ln(wsp<float>(R, "z1", l) + r0 * h, peer(P ? P->fwd_attn : nullptr), (const float*)W.bo, xin + r0 * h,
-                           wsp<float>(R, "x1", l) + r0 * h, (const float*)W.ln2_g, (const float*)W.ln2_b, v2 + r0 * h,
-                           wsp<float>(R, "mu2", l) + r0, wsp<float>(R, "rstd2", l) + r0, Ms, h, H->eps,
+      return launch_bdr_ln(part_r(0), peer_k(0), (const float*)W.bo, xin + r0 * h,
+                           wsp<float>(R, T_x1, l) + r0 * h, (const float*)W.ln2_g, (const float*)W.ln2_b, v2 + r0 * h,
+                           wsp<float>(R, T_mu2, l) + r0, wsp<float>(R, T_rstd2, l) + r0, Ms, h, H->eps,
                            make_drop_cfg(seed, l, 0, p), (int64_t)r0, s, rms);
     case F_FC1:
       if (H->llama)  // w1 = [gate | up] columns interleaved in blocks of 32; pre = both pre-activations, f = silu(gate)*up
@@ -414,77 +434,77 @@ static int run_op(const Run& R, const Op& op) {
       return launch_gemm(OASES_GEMM_NN, OASES_EPI_BIAS_GELU, Ms, fp, h, v2 + r0 * h, h, W.w1, fp, f + r0 * fp, fp,
                          (const float*)W.b1, pre + r0 * fp, fp, gws, H->gemm_ws_bytes, 0, s, pin);
     case F_FC2:
-      return launch_gemm(OASES_GEMM_NN, OASES_EPI_F32, Ms, h, fp, f + r0 * fp, fp, W.w2, h, wsp<float>(R, "z2", l) + r0 * h, h,
+      return launch_gemm(OASES_GEMM_NN, OASES_EPI_F32, Ms, h, fp, f + r0 * fp, fp, W.w2, h, part_w(1), h,
                          nullptr, nullptr, 0, gws, H->gemm_ws_bytes, 0, s, pin);
     case F_R2: {
       const bool more = l + 1 < L;  // fuse the next layer's LN1 behind this layer's output
-      return launch_bdr_ln(wsp<float>(R, "z2", l) + r0 * h, peer(P ? P->fwd_ffn : nullptr), (const float*)W.b2,
-                           wsp<float>(R, "x1", l) + r0 * h, yout + r0 * h, more ? (const float*)R.w[l + 1].ln1_g : nullptr,
-                           more ? (const float*)R.w[l + 1].ln1_b : nullptr, more ? wsp<uint16_t>(R, "u", l + 1) + r0 * h : nullptr,
-                           more ? wsp<float>(R, "mu1", l + 1) + r0 : nullptr, more ? wsp<float>(R, "rstd1", l + 1) + r0 : nullptr,
+      return launch_bdr_ln(part_r(1), peer_k(1), (const float*)W.b2,
+                           wsp<float>(R, T_x1, l) + r0 * h, yout + r0 * h, more ? (const float*)R.w[l + 1].ln1_g : nullptr,
+                           more ? (const float*)R.w[l + 1].ln1_b : nullptr, more ? wsp<uint16_t>(R, T_u, l + 1) + r0 * h : nullptr,
+                           more ? wsp<float>(R, T_mu1, l + 1) + r0 : nullptr, more ? wsp<float>(R, T_rstd1, l + 1) + r0 : nullptr,
                            Ms, h, H->eps, make_drop_cfg(seed, l, 1, p), (int64_t)r0, s, rms);
     }
     // ---------------------------------------------------------------- backward
     case B_BDR2:
-      return launch_dropout_bwd(dyin + r0 * h, wsp<uint16_t>(R, "dz2", l) + r0 * h, (float*)R.g[l].b2, Ms, h,
+      return launch_dropout_bwd(dyin + r0 * h, wsp<uint16_t>(R, T_dz2, l) + r0 * h, (float*)R.g[l].b2, Ms, h,
                                 make_drop_cfg(seed, l, 1, p), (int64_t)r0, scr_comm, s);
     case B_FC2_DGRAD:
       if (H->llama)
-        return launch_gemm(OASES_GEMM_NT, OASES_EPI_DSWIGLU, Ms, fp, h, wsp<uint16_t>(R, "dz2", l) + r0 * h, h, W.w2, h,
-                           wsp<uint16_t>(R, "dg", l) + r0 * fw, fw, nullptr, pre + r0 * fw, fw, gws, H->gemm_ws_bytes, 0, s, pin);
-      return launch_gemm(OASES_GEMM_NT, OASES_EPI_DGELU, Ms, fp, h, wsp<uint16_t>(R, "dz2", l) + r0 * h, h, W.w2, h,
-                         wsp<uint16_t>(R, "dg", l) + r0 * fp, fp, nullptr, pre + r0 * fp, fp, gws, H->gemm_ws_bytes, 0, s, pin);
+        return launch_gemm(OASES_GEMM_NT, OASES_EPI_DSWIGLU, Ms, fp, h, wsp<uint16_t>(R, T_dz2, l) + r0 * h, h, W.w2, h,
+                           wsp<uint16_t>(R, T_dg, l) + r0 * fw, fw, nullptr, pre + r0 * fw, fw, gws, H->gemm_ws_bytes, 0, s, pin);
+      return launch_gemm(OASES_GEMM_NT, OASES_EPI_DGELU, Ms, fp, h, wsp<uint16_t>(R, T_dz2, l) + r0 * h, h, W.w2, h,
+                         wsp<uint16_t>(R, T_dg, l) + r0 * fp, fp, nullptr, pre + r0 * fp, fp, gws, H->gemm_ws_bytes, 0, s, pin);
     case B_FC1_DGRAD:
-      return launch_gemm(OASES_GEMM_NT, OASES_EPI_F32, Ms, h, fw, wsp<uint16_t>(R, "dg", l) + r0 * fw, fw, W.w1, fw,
-                         wsp<float>(R, "dv2", l) + r0 * h, h, nullptr, nullptr, 0, gws, H->gemm_ws_bytes, 0, s, pin);
+      return launch_gemm(OASES_GEMM_NT, OASES_EPI_F32, Ms, h, fw, wsp<uint16_t>(R, T_dg, l) + r0 * fw, fw, W.w1, fw,
+                         part_w(2), h, nullptr, nullptr, 0, gws, H->gemm_ws_bytes, 0, s, pin);
     case B_R3:
-      return launch_layernorm_bwd(wsp<float>(R, "dv2", l) + r0 * h, peer(P ? P->bwd_ffn : nullptr), dyin + r0 * h,
-                                  wsp<float>(R, "x1", l) + r0 * h, wsp<float>(R, "mu2", l) + r0, wsp<float>(R, "rstd2", l) + r0,
-                                  (const float*)W.ln2_g, wsp<float>(R, "dx1", l) + r0 * h, (float*)R.g[l].ln2_g,
-                                  (float*)R.g[l].ln2_b, wsp<uint16_t>(R, "dz1", l) + r0 * h, (float*)R.g[l].bo, Ms, h,
+      return launch_layernorm_bwd(part_r(2), peer_k(2), dyin + r0 * h,
+                                  wsp<float>(R, T_x1, l) + r0 * h, wsp<float>(R, T_mu2, l) + r0, wsp<float>(R, T_rstd2, l) + r0,
+                                  (const float*)W.ln2_g, wsp<float>(R, T_dx1, l) + r0 * h, (float*)R.g[l].ln2_g,
+                                  (float*)R.g[l].ln2_b, wsp<uint16_t>(R, T_dz1, l) + r0 * h, (float*)R.g[l].bo, Ms, h,
                                   make_drop_cfg(seed, l, 0, p), (int64_t)r0, scr_comm, s, rms);
     case B_FC2_WGRAD:
-      return launch_gemm(OASES_GEMM_TN, 0, fp, h, Ms, f + r0 * fp, fp, wsp<uint16_t>(R, "dz2", l) + r0 * h, h, R.g[l].w2, h,
+      return launch_gemm(OASES_GEMM_TN, 0, fp, h, Ms, f + r0 * fp, fp, wsp<uint16_t>(R, T_dz2, l) + r0 * h, h, R.g[l].w2, h,
                          nullptr, nullptr, 0, gws, H->gemm_ws_bytes, 0, s);
     case B_FC1_WGRAD:
-      return launch_gemm(OASES_GEMM_TN, 0, h, fw, Ms, v2 + r0 * h, h, wsp<uint16_t>(R, "dg", l) + r0 * fw, fw, R.g[l].w1, fw,
+      return launch_gemm(OASES_GEMM_TN, 0, h, fw, Ms, v2 + r0 * h, h, wsp<uint16_t>(R, T_dg, l) + r0 * fw, fw, R.g[l].w1, fw,
                          nullptr, nullptr, 0, gws, H->gemm_ws_bytes, 0, s);
     case B_B1_SUM:
-      return launch_colsum_bf16(wsp<uint16_t>(R, "dg", l) + r0 * fp, fp, Ms, fp, (float*)R.g[l].b1, scr_comp, s);
+      return launch_colsum_bf16(wsp<uint16_t>(R, T_dg, l) + r0 * fp, fp, Ms, fp, (float*)R.g[l].b1, scr_comp, s);
     case B_PROJ_DGRAD:
-      return launch_gemm(OASES_GEMM_NT, OASES_EPI_BF16, Ms, hp, h, wsp<uint16_t>(R, "dz1", l) + r0 * h, h, W.wo, h,
-                         wsp<uint16_t>(R, "da", l) + r0 * hp, hp, nullptr, nullptr, 0, gws, H->gemm_ws_bytes, 0, s, pin);
+      return launch_gemm(OASES_GEMM_NT, OASES_EPI_BF16, Ms, hp, h, wsp<uint16_t>(R, T_dz1, l) + r0 * h, h, W.wo, h,
+                         wsp<uint16_t>(R, T_da, l) + r0 * hp, hp, nullptr, nullptr, 0, gws, H->gemm_ws_bytes, 0, s, pin);
     case B_PROJ_WGRAD:
-      return launch_gemm(OASES_GEMM_TN, 0, hp, h, Ms, attn + r0 * hp, hp, wsp<uint16_t>(R, "dz1", l) + r0 * h, h, R.g[l].wo, h,
+      return launch_gemm(OASES_GEMM_TN, 0, hp, h, Ms, attn + r0 * hp, hp, wsp<uint16_t>(R, T_dz1, l) + r0 * h, h, R.g[l].wo, h,
                          nullptr, nullptr, 0, gws, H->gemm_ws_bytes, 0, s);
     case B_ATTN:
-      return launch_attention_bwd(qkv, attn, wsp<uint16_t>(R, "da", l), wsp<float>(R, "lse", l), wsp<float>(R, "delta", l),
-                                  wsp<uint16_t>(R, "dqkv", l), H->b, H->s, H->heads_l, H->d, H->cfg.causal, (int)r0, Ms, s, seed, l,
+      return launch_attention_bwd(qkv, attn, wsp<uint16_t>(R, T_da, l), wsp<float>(R, T_lse, l), wsp<float>(R, T_delta, l),
+                                  wsp<uint16_t>(R, T_dqkv, l), H->b, H->s, H->heads_l, H->d, H->cfg.causal, (int)r0, Ms, s, seed, l,
                                   H->cfg.attn_dropout_p, H->r * H->heads_l, H->nh);
     case B_QKV_DGRAD:
-      return launch_gemm(OASES_GEMM_NT, OASES_EPI_F32, Ms, h, 3 * hp, wsp<uint16_t>(R, "dqkv", l) + r0 * 3 * hp, 3 * hp, W.wqkv,
-                         3 * hp, wsp<float>(R, "du", l) + r0 * h, h, nullptr, nullptr, 0, gws, H->gemm_ws_bytes, 0, s, pin);
+      return launch_gemm(OASES_GEMM_NT, OASES_EPI_F32, Ms, h, 3 * hp, wsp<uint16_t>(R, T_dqkv, l) + r0 * 3 * hp, 3 * hp, W.wqkv,
+                         3 * hp, part_w(3), h, nullptr, nullptr, 0, gws, H->gemm_ws_bytes, 0, s, pin);
     case B_R4: {
       const bool more = l > 0;  // fuse the dropout backward of the layer below (its BDR2) behind dx
-      return launch_layernorm_bwd(wsp<float>(R, "du", l) + r0 * h, peer(P ? P->bwd_attn : nullptr),
-                                  wsp<float>(R, "dx1", l) + r0 * h, xin + r0 * h, wsp<float>(R, "mu1", l) + r0,
-                                  wsp<float>(R, "rstd1", l) + r0, (const float*)W.ln1_g, dxout + r0 * h, (float*)R.g[l].ln1_g,
-                                  (float*)R.g[l].ln1_b, more ? wsp<uint16_t>(R, "dz2", l - 1) + r0 * h : nullptr,
+      return launch_layernorm_bwd(part_r(3), peer_k(3),
+                                  wsp<float>(R, T_dx1, l) + r0 * h, xin + r0 * h, wsp<float>(R, T_mu1, l) + r0,
+                                  wsp<float>(R, T_rstd1, l) + r0, (const float*)W.ln1_g, dxout + r0 * h, (float*)R.g[l].ln1_g,
+                                  (float*)R.g[l].ln1_b, more ? wsp<uint16_t>(R, T_dz2, l - 1) + r0 * h : nullptr,
                                   more ? (float*)R.g[l - 1].b2 : nullptr, Ms, h, make_drop_cfg(seed, l - 1, 1, p), (int64_t)r0,
                                   scr_comm, s, rms);
     }
     case B_QKV_WGRAD:
-      return launch_gemm(OASES_GEMM_TN, 0, h, 3 * hp, Ms, u + r0 * h, h, wsp<uint16_t>(R, "dqkv", l) + r0 * 3 * hp, 3 * hp,
+      return launch_gemm(OASES_GEMM_TN, 0, h, 3 * hp, Ms, u + r0 * h, h, wsp<uint16_t>(R, T_dqkv, l) + r0 * 3 * hp, 3 * hp,
                          R.g[l].wqkv, 3 * hp, nullptr, nullptr, 0, gws, H->gemm_ws_bytes, 0, s);
     case B_PQ_WGRAD:
-      return launch_gemm_tn_pair(Ms, hp, h, attn + r0 * hp, hp, wsp<uint16_t>(R, "dz1", l) + r0 * h, h, R.g[l].wo, h, h, 3 * hp, u + r0 * h, h,
-                                 wsp<uint16_t>(R, "dqkv", l) + r0 * 3 * hp, 3 * hp, R.g[l].wqkv, 3 * hp, s);
+      return launch_gemm_tn_pair(Ms, hp, h, attn + r0 * hp, hp, wsp<uint16_t>(R, T_dz1, l) + r0 * h, h, R.g[l].wo, h, h, 3 * hp, u + r0 * h, h,
+                                 wsp<uint16_t>(R, T_dqkv, l) + r0 * 3 * hp, 3 * hp, R.g[l].wqkv, 3 * hp, s);
     case B_BQKV_SUM:
-      return launch_colsum_bf16(wsp<uint16_t>(R, "dqkv", l) + r0 * 3 * hp, 3 * hp, Ms, 3 * hp, (float*)R.g[l].bqkv, scr_comp, s);
+      return launch_colsum_bf16(wsp<uint16_t>(R, T_dqkv, l) + r0 * 3 * hp, 3 * hp, Ms, 3 * hp, (float*)R.g[l].bqkv, scr_comp, s);
     // ---------------------------------------------------------------- recompute: the forward kernels again
     case R_LN1:
       return launch_layernorm_fwd(xin + r0 * h, (const float*)W.ln1_g, (const float*)W.ln1_b, u + r0 * h,
-                                  wsp<float>(R, "mu1", l) + r0, wsp<float>(R, "rstd1", l) + r0, Ms, h, H->eps, s, rms);
+                                  wsp<float>(R, T_mu1, l) + r0, wsp<float>(R, T_rstd1, l) + r0, Ms, h, H->eps, s, rms);
     case R_QKV: {
       Op f = op;
       f.kind = F_QKV;
@@ -496,8 +516,8 @@ static int run_op(const Run& R, const Op& op) {
       return run_op(R, f);
     }
     case R_LN2:
-      return launch_layernorm_fwd(wsp<float>(R, "x1", l) + r0 * h, (const float*)W.ln2_g, (const float*)W.ln2_b, v2 + r0 * h,
-                                  wsp<float>(R, "mu2", l) + r0, wsp<float>(R, "rstd2", l) + r0, Ms, h, H->eps, s, rms);
+      return launch_layernorm_fwd(wsp<float>(R, T_x1, l) + r0 * h, (const float*)W.ln2_g, (const float*)W.ln2_b, v2 + r0 * h,
+                                  wsp<float>(R, T_mu2, l) + r0, wsp<float>(R, T_rstd2, l) + r0, Ms, h, H->eps, s, rms);
     case R_FC1: {
       Op f = op;
       f.kind = F_FC1;
@@ -603,7 +623,7 @@ int oases_create(const oases_layer_cfg* c, oases_handle** out) {
   H->eps = c->ln_eps > 0.f ? c->ln_eps : 1e-5f;
   H->theta = c->rope_theta > 0.f ? c->rope_theta : 10000.f;
   H->n_events = H->L * 4 * H->n * 2 + 1;  // + the fork event that orders stream_comm behind stream_compute
-  plan_workspace(H);
+  if (!plan_workspace(H)) { delete H; set_error("oases_create: internal error (workspace plan)"); return OASES_EINVAL; }
   build_forward(H);
   build_backward(H);
   *out = H;
@@ -702,6 +722,91 @@ int oases_backward(oases_handle* H, const oases_weights* w, const void* x, const
   Run R{H, w, g, peers, (char*)workspace, (const float*)x, nullptr, (const float*)dy, (float*)dx,
         {(hipStream_t)stream_compute, (hipStream_t)stream_comm}};
   return run_ops(R, H->bwd);
+}
+
+// ---------------------------------------------------------------------------------------------
+// segment-level calls: one computation sequence of one layer, all sub-batches, up to its reduction point
+// ---------------------------------------------------------------------------------------------
+namespace oases {
+// which segment of its layer an operator of the schedule belongs to (forward: 0 attention block up to R1, 1 FFN block
+// from R1 up to R2, 2 from R2 on; backward: 2 the top layer's dropout backward, 1 FFN block up to R3, 0 attention block
+// from R3 up to R4, 3 from R4 on), or -1
+static int segment_of(int kind, bool backward) {
+  if (!backward) {
+    switch (kind) {
+      case F_ROPE_TABLE: case F_LN1: case F_QKV: case F_ROPE: case F_ATTN: case F_PROJ: return 0;
+      case F_R1: case F_FC1: case F_FC2: return 1;
+      case F_R2: return 2;
+      default: return -1;
+    }
+  }
+  switch (kind) {
+    case B_BDR2: return 2;
+    case R_LN2: case R_FC1: case B_FC2_DGRAD: case B_FC1_DGRAD: case B_FC2_WGRAD: case B_FC1_WGRAD: case B_B1_SUM: return 1;
+    case B_R3: case R_LN1: case R_QKV: case R_ROPE: case R_ATTN: case B_PROJ_DGRAD: case B_ATTN: case B_ROPE: case B_QKV_DGRAD:
+    case B_PROJ_WGRAD: case B_QKV_WGRAD: case B_PQ_WGRAD: case B_BQKV_SUM: return 0;
+    case B_R4: return 3;
+    default: return -1;
+  }
+}
+
+// the operators of (layer, segment) in schedule order on one stream: that order is a valid serial order of the pass
+// (it is what OASES_FLAG_SERIALISE runs), and every operator of a segment depends only on operators of the same segment
+// before it and on earlier segments
+static int run_segment(Run& R, bool backward, int layer, int segment, void* partial_out, const void* reduced_in) {
+  oases_handle* H = R.H;
+  if (layer < 0 || layer >= H->L) { set_error("segment call: layer %d out of range", layer); return OASES_EINVAL; }
+  if (segment < 0 || segment > (backward ? 3 : 2)) { set_error("segment call: segment %d out of range", segment); return OASES_EINVAL; }
+  if (backward && segment == 2 && layer != H->L - 1) {
+    set_error("backward segment 2 exists in the top layer only (below it the dropout backward belongs to segment 3 of the layer above)");
+    return OASES_EINVAL;
+  }
+  // reduction point that the segment ends in (its partial) and the one it starts from (the reduced tensor)
+  const int produces = backward ? (segment == 1 ? 2 : segment == 0 ? 3 : -1) : (segment == 0 ? 0 : segment == 1 ? 1 : -1);
+  const int consumes = backward ? (segment == 0 ? 2 : segment == 3 ? 3 : -1) : (segment == 1 ? 0 : segment == 2 ? 1 : -1);
+  if (partial_out && produces < 0) { set_error("segment call: this segment ends in no reduction point (partial_out must be NULL)"); return OASES_EINVAL; }
+  if (reduced_in && consumes < 0) { set_error("segment call: this segment starts from no reduction point (reduced_in must be NULL)"); return OASES_EINVAL; }
+  if ((partial_out && !aligned16(partial_out)) || (reduced_in && !aligned16(reduced_in))) { set_error("segment call: pointer not 16-byte aligned"); return OASES_EALIGN; }
+  if (produces >= 0) R.partial_out[produces] = (float*)partial_out;
+  if (consumes >= 0) R.reduced_in[consumes] = (const float*)reduced_in;
+  R.st[1] = R.st[0];
+  for (const Op& op0 : backward ? H->bwd : H->fwd) {
+    if (op0.layer != layer || segment_of(op0.kind, backward) != segment) continue;
+    if (op0.kind == F_ROPE_TABLE && layer != 0) continue;
+    Op op = op0;
+    op.stream = 0;
+    const int rc = run_op(R, op);
+    if (rc) return rc;
+  }
+  return 0;
+}
+}  // namespace oases
+
+int oases_forward_segment(oases_handle* H, int layer, int segment, const oases_weights* w, const void* x, void* y, void* workspace,
+                          void* partial_out, const void* reduced_in, void* stream) {
+  if (!H || !w) { set_error("oases_forward_segment: NULL handle or weights"); return OASES_ENULL; }
+  const void* p[] = {x, y, workspace};
+  int rc = check_ptrs(p, 3, "oases_forward_segment");
+  if (rc) return rc;
+  if (x == y) { set_error("oases_forward_segment: y may not alias x"); return OASES_EINVAL; }
+  if ((rc = check_weights(H, w))) return rc;
+  Run R{H, w, nullptr, nullptr, (char*)workspace, (const float*)x, (float*)y, nullptr, nullptr, {(hipStream_t)stream, (hipStream_t)stream}};
+  return run_segment(R, false, layer, segment, partial_out, reduced_in);
+}
+
+int oases_backward_segment(oases_handle* H, int layer, int segment, const oases_weights* w, const void* x, const void* dy, void* dx,
+                           const oases_grads* g, void* workspace, void* partial_out, const void* reduced_in, void* stream) {
+  if (!H || !w || !g) { set_error("oases_backward_segment: NULL handle, weights or grads"); return OASES_ENULL; }
+  const void* p[] = {x, dy, dx, workspace};
+  int rc = check_ptrs(p, 4, "oases_backward_segment");
+  if (rc) return rc;
+  if ((rc = check_weights(H, w))) return rc;
+  for (int l = 0; l < H->L; l++) {
+    const void* q[] = {g[l].ln1_g, g[l].wqkv, g[l].wo, g[l].ln2_g, g[l].w1, g[l].w2, g[l].ln1_b, g[l].bqkv, g[l].bo, g[l].ln2_b, g[l].b1, g[l].b2};
+    if ((rc = check_ptrs(q, H->llama ? 6 : 12, "grads"))) return rc;
+  }
+  Run R{H, w, g, nullptr, (char*)workspace, (const float*)x, nullptr, (const float*)dy, (float*)dx, {(hipStream_t)stream, (hipStream_t)stream}};
+  return run_segment(R, true, layer, segment, partial_out, reduced_in);
 }
 
 // ---------------------------------------------------------------------------------------------

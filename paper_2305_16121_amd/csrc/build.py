@@ -13,7 +13,7 @@ LIB = os.path.join(PKG, "liboases.so")
 # in parallel; planner.cc is host code only
 SOURCES = (("gemm.hip", "gemm_nn", ["-DOASES_GEMM_PART=0"]), ("gemm.hip", "gemm_nt", ["-DOASES_GEMM_PART=1"]),
            ("gemm.hip", "gemm_tn", ["-DOASES_GEMM_PART=2"]), ("api.hip", "api", []), ("attention.hip", "attention", []),
-           ("elementwise.hip", "elementwise", []), ("noalloc.hip", "noalloc", []), ("planner.cc", "planner", []))
+           ("elementwise.hip", "elementwise", []), ("noalloc.hip", "noalloc", []), ("probe.hip", "probe", []), ("planner.cc", "planner", []))
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wno-unused-command-line-argument", "-fno-gpu-rdc"]
 
@@ -42,7 +42,7 @@ def build(verbose: bool = False, extra: list[str] | None = None) -> str:
             print(err, file=sys.stderr)
         return obj
 
-    with ThreadPoolExecutor(max_workers=8) as ex:
+    with ThreadPoolExecutor(max_workers=9) as ex:
         objs = list(ex.map(one, SOURCES))
     r = subprocess.run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs], capture_output=True, text=True)
     if r.returncode != 0:

@@ -9,7 +9,7 @@ import torch
 
 import synth_inputs as si
 from tests import layer_harness as LH
-from tests.test_gpu_layer import check_tensor, compare_run
+from tests.layer_harness import check_tensor, compare_run
 from tests.util import rms_err, bf16_round, assert_bf16_close, dev, randn
 
 pytestmark = pytest.mark.gpu
@@ -138,8 +138,8 @@ def test_layer_with_attention_dropout(arch):
     shards = [si.shard_layer_params(p, cfg, r) for p in layers]
     gpu = LH.gpu_rank_run(cfg, r, layers, x, dy, seed=13)
     ora = mod.model_forward_backward(shards, x, dy, cfg, seed=13, head0=r * heads_l)
-    fl = mod.model_forward_backward(shards, x, dy, cfg, seed=13, head0=r * heads_l, bf16_sites=sites)
-    assert compare_run(gpu, ora, fl, cfg["n_layers"])
+    fl = [mod.model_forward_backward(shards, x, dy, cfg, seed=13, head0=r * heads_l, dtype=dt, bf16_sites=sites) for dt in (torch.float64, torch.float32)]
+    assert compare_run(f"{arch} C2-like with attention dropout, rank {r}, rank-only", gpu, ora, fl, cfg["n_layers"])
     # the run is not the one without attention dropout
     cfg0 = dict(cfg, attn_dropout_p=0.0)
     gpu0 = LH.gpu_rank_run(cfg0, r, layers, x, dy, seed=13)

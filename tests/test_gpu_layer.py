@@ -4,17 +4,18 @@ invariants of the method: shard-sum (Megatron partition), sub-batch invariance, 
 
 Tolerances are the contract's: max|err|/rms(ref) <= 1e-2 for forward activations and <= 3e-2 for input and
 weight gradients.  bf16 storage of the MFMA operands alone can exceed that bound on single outlier elements
-(first tokens of causal attention); a tensor that misses the bound must then (a) stay within 1.5x of the
-oracle's own estimate of that storage floor (the oracle re-run with the operand tensors rounded to bf16; the
-estimate models operand storage only, not what follows from it at second order -- the row sums of dO*O taken from the
-stored bf16 attention output, the fp32 summation order -- and is one draw of an extreme-value statistic) and
-(b) be under 1e-2 in rms-relative error.  Every measured error is printed."""
+(first tokens of causal attention); a tensor that misses the bound must then match the storage-format floor -- two runs
+of the oracle itself with the operand tensors rounded to bf16, one in fp64 and one in fp32 arithmetic -- as
+tests/layer_harness.py states: rms-relative error within 1.25x of the floor's, largest error within 1.5x of the floor's
+largest, rms-relative error under 1e-2.  Every measured error goes into the session's
+parity table (tests/conftest.py)."""
 import numpy as np
 import pytest
 import torch
 
 import synth_inputs as si
 from tests import layer_harness as LH
+from tests.layer_harness import check_tensor, compare_run
 from tests.util import rel_err, rms_err
 
 pytestmark = pytest.mark.gpu
@@ -26,45 +27,17 @@ def _need_gpu():
         pytest.skip("no GPU")
 
 
-def check_tensor(name, got, ref, tol, floor_ref=None, report=None):
-    e, r = rel_err(got, ref), rms_err(got, ref)
-    line = f"{name:14s} max/rms {e:.4f} (tol {tol})  rms-rel {r:.5f}"
-    ok = e <= tol
-    if not ok and floor_ref is not None:
-        fl = rel_err(floor_ref, ref)
-        line += f"  format floor {fl:.4f}"
-        ok = e <= 1.5 * fl and r <= 1e-2
-        line += "  FORMAT-LIMITED" if ok else "  FAIL"
-    elif not ok:
-        line += "  FAIL"
-    print(line)
-    if report is not None:
-        report.append((name, e, r, ok))
-    return ok
-
-
-def compare_run(gpu, ora, floor=None, layers=1):
-    """gpu: result of gpu_rank_run; ora / floor: oracle results (model_forward_backward dicts) in rank layout."""
-    oks = [check_tensor("y", gpu["y"], ora["y"], LH.FWD_TOL, floor["y"] if floor else None),
-           check_tensor("dx", gpu["dx"], ora["dx"], LH.GRAD_TOL, floor["dx"] if floor else None)]
-    for l in range(layers):
-        og = LH.oracle_rank_grads_to_gpu_layout(ora["grads"][l])
-        fg = LH.oracle_rank_grads_to_gpu_layout(floor["grads"][l]) if floor else None
-        for k in LH.GPU_PARAMS:
-            oks.append(check_tensor(f"L{l}.d{k}", gpu["grads"][l][k], og[k], LH.GRAD_TOL, fg[k] if fg else None))
-    return all(oks)
-
-
-def _floor(cfg, rank, layers, x, dy, dtype):
+def _floors(cfg, rank, layers, x, dy, seed=0):
     from oracle import layer_oracle as lo
-    return LH.oracle_rank_only(cfg, rank, layers, x, dy, dtype=dtype, bf16_sites=lo.BF16_OPERAND_SITES)
+    return [LH.oracle_rank_only(cfg, rank, layers, x, dy, seed=seed, dtype=dt, bf16_sites=lo.BF16_OPERAND_SITES)
+            for dt in (torch.float64, torch.float32)]
 
 
 # ------------------------------------------------------------------ the five configurations, rank alone (no peers)
-@pytest.mark.timeout(900)
+@pytest.mark.timeout(1500)
 @pytest.mark.parametrize("name,ranks,dtype", [("C1", (0, 1), torch.float64), ("C2", (0, 3), torch.float64),
-                                              ("C3", (0, 3), torch.float32), ("C4", (0,), torch.float32),
-                                              ("C5", (0,), torch.float32)])
+                                              ("C3", (0, 3), torch.float32), ("C4", (0, 7), torch.float32),
+                                              ("C5", (0, 7), torch.float32)])
 def test_rank_shard_matches_oracle(name, ranks, dtype):
     cfg = si.CONFIGS[name]
     layers, x, dy = LH.make_inputs(cfg)
@@ -72,8 +45,8 @@ def test_rank_shard_matches_oracle(name, ranks, dtype):
         print(f"\n== {name} rank {r}: rank-only layer (oracle on the rank's weight slices)", flush=True)
         gpu = LH.gpu_rank_run(cfg, r, layers, x, dy)
         ora = LH.oracle_rank_only(cfg, r, layers, x, dy, dtype=dtype)
-        fl = _floor(cfg, r, layers, x, dy, dtype)
-        assert compare_run(gpu, ora, fl, cfg["n_layers"]), f"{name} rank {r}"
+        fl = _floors(cfg, r, layers, x, dy)
+        assert compare_run(f"{name} rank {r}, rank-only", gpu, ora, fl, cfg["n_layers"]), f"{name} rank {r}"
         del gpu, ora, fl
         torch.cuda.empty_cache()
 
@@ -94,26 +67,31 @@ def test_ragged_configurations(cfg):
         print(f"\n== ragged config h={cfg['hidden']} seq={cfg['seq']} rank {r}", flush=True)
         gpu = LH.gpu_rank_run(cfg, r, layers, x, dy, seed=11)
         ora = LH.oracle_rank_only(cfg, r, layers, x, dy, seed=11)
-        from oracle import layer_oracle as lo
-        fl = LH.oracle_rank_only(cfg, r, layers, x, dy, seed=11, bf16_sites=lo.BF16_OPERAND_SITES)
-        assert compare_run(gpu, ora, fl, cfg["n_layers"])
+        fl = _floors(cfg, r, layers, x, dy, seed=11)
+        assert compare_run(f"h={cfg['hidden']} seq={cfg['seq']} t={cfg['tp']} rank {r}, rank-only", gpu, ora, fl, cfg["n_layers"])
 
 
 # ------------------------------------------------------------------ with peer sums: every rank reproduces the unsharded layer
-@pytest.mark.timeout(900)
-@pytest.mark.parametrize("name,ranks", [("C1", (0, 1)), ("C2", (0, 1, 2, 3))])
-def test_with_peer_sums_every_rank_gives_the_unsharded_result(name, ranks):
+@pytest.mark.timeout(1500)
+@pytest.mark.parametrize("name,ranks,dtype", [("C1", (0, 1), torch.float64), ("C2", (0, 1, 2, 3), torch.float64), ("C4", (7,), torch.float32)])
+def test_with_peer_sums_every_rank_gives_the_unsharded_result(name, ranks, dtype):
+    """A rank that is handed the other ranks' partial sums at its four reduction points reproduces the UNSHARDED layer:
+    y, dx and its slices of the parameter gradients (Sec. II partition, Sec. IV-B Eq. (1))."""
     cfg = si.CONFIGS[name]
     layers, x, dy = LH.make_inputs(cfg)
     from oracle import layer_oracle as lo
-    fl_full = lo.model_forward_backward(layers, x, dy, cfg, bf16_sites=lo.BF16_OPERAND_SITES)
+    floors = [lo.model_forward_backward(layers, x, dy, cfg, dtype=dt, bf16_sites=lo.BF16_OPERAND_SITES)
+              for dt in ((torch.float64, torch.float32) if dtype == torch.float64 else (torch.float32,))]
+    for f in floors:
+        f.pop("saved"), f.pop("inter")
     for r in ranks:
         print(f"\n== {name} rank {r} with peer sums vs unsharded oracle", flush=True)
-        ora, peers = LH.oracle_unsharded_with_peer_sums(cfg, r, layers, x, dy)
-        gpu = LH.gpu_rank_run(cfg, r, layers, x, dy, peers=peers)
+        ora, peers = LH.oracle_unsharded_with_peer_sums(cfg, r, layers, x, dy, dtype=dtype)
         ora_r = dict(y=ora["y"], dx=ora["dx"], grads=[LH.slice_unsharded_grads(g, cfg, r) for g in ora["grads"]])
-        fl_r = dict(y=fl_full["y"], dx=fl_full["dx"], grads=[LH.slice_unsharded_grads(g, cfg, r) for g in fl_full["grads"]])
-        assert compare_run(gpu, ora_r, fl_r, cfg["n_layers"]), f"{name} rank {r}"
+        del ora
+        gpu = LH.gpu_rank_run(cfg, r, layers, x, dy, peers=peers)
+        fl_r = [dict(y=f["y"], dx=f["dx"], grads=[LH.slice_unsharded_grads(g, cfg, r) for g in f["grads"]]) for f in floors]
+        assert compare_run(f"{name} rank {r}, peer sums vs unsharded", gpu, ora_r, fl_r, cfg["n_layers"]), f"{name} rank {r}"
 
 
 def test_shard_sum_of_gpu_partials():
@@ -131,7 +109,7 @@ def test_shard_sum_of_gpu_partials():
     from oracle import layer_oracle as lo
     fl = lo.model_forward_backward(layers, x, dy, cfg, bf16_sites=lo.BF16_OPERAND_SITES)
     sv, it, fsv, fit = ora["saved"][0], ora["inter"][0], fl["saved"][0], fl["inter"][0]
-    oks = [check_tensor("sum_r " + k, sums[k], ref, tol, fref)
+    oks = [check_tensor("C1 sum over ranks of GPU partials", "sum_r " + k, sums[k], ref, tol, [fref])
            for k, ref, fref, tol in (("z1", sv["Z1"], fsv["Z1"], LH.FWD_TOL), ("z2", sv["Z2"], fsv["Z2"], LH.FWD_TOL),
                                      ("dv2", it["dV2"], fit["dV2"], LH.GRAD_TOL), ("du", it["dU"], fit["dU"], LH.GRAD_TOL))]
     assert all(oks)

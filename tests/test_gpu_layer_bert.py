@@ -6,7 +6,7 @@ import torch
 
 import synth_inputs as si
 from tests import layer_harness as LH
-from tests.test_gpu_layer import compare_run
+from tests.layer_harness import compare_run
 from tests.util import rel_err
 
 pytestmark = pytest.mark.gpu
@@ -50,8 +50,8 @@ def test_rank_shard_matches_oracle(name, ranks, dtype):
         print(f"\n== {name} rank {r}: rank-only post-LN layer", flush=True)
         gpu = LH.gpu_rank_run(cfg, r, layers, x, dy, seed=9)
         ora = oracle_rank_only(cfg, r, layers, x, dy, seed=9, dtype=dtype)
-        fl = oracle_rank_only(cfg, r, layers, x, dy, seed=9, dtype=dtype, bf16_sites=bo.BERT_BF16_OPERAND_SITES)
-        assert compare_run(gpu, ora, fl, cfg["n_layers"]), f"{name} rank {r}"
+        fl = [oracle_rank_only(cfg, r, layers, x, dy, seed=9, dtype=dt, bf16_sites=bo.BERT_BF16_OPERAND_SITES) for dt in (torch.float64, torch.float32)]
+        assert compare_run(f"post-LN {name} rank {r}, rank-only", gpu, ora, fl, cfg["n_layers"]), f"{name} rank {r}"
         del gpu, ora, fl
         torch.cuda.empty_cache()
 
@@ -62,7 +62,7 @@ def test_with_peer_sums_every_rank_gives_the_unsharded_result(name):
     cfg = CONFIGS[name]
     layers, x, dy = LH.make_inputs(cfg)
     full = bo.model_forward_backward(layers, x, dy, cfg)
-    fl_full = bo.model_forward_backward(layers, x, dy, cfg, bf16_sites=bo.BERT_BF16_OPERAND_SITES)
+    fl_fulls = [bo.model_forward_backward(layers, x, dy, cfg, dtype=dt, bf16_sites=bo.BERT_BF16_OPERAND_SITES) for dt in (torch.float64, torch.float32)]
     h, t = cfg["hidden"], cfg["tp"]
     hp, fp = h // t, 4 * h // t
     for r in range(t):
@@ -77,8 +77,8 @@ def test_with_peer_sums_every_rank_gives_the_unsharded_result(name):
         print(f"\n== {name} rank {r} with peer sums vs the unsharded oracle", flush=True)
         gpu = LH.gpu_rank_run(cfg, r, layers, x, dy, peers=peers)
         ora_r = dict(y=full["y"], dx=full["dx"], grads=[LH.slice_unsharded_grads(g, cfg, r) for g in full["grads"]])
-        fl_r = dict(y=fl_full["y"], dx=fl_full["dx"], grads=[LH.slice_unsharded_grads(g, cfg, r) for g in fl_full["grads"]])
-        assert compare_run(gpu, ora_r, fl_r, cfg["n_layers"]), f"{name} rank {r}"
+        fl_r = [dict(y=f["y"], dx=f["dx"], grads=[LH.slice_unsharded_grads(g, cfg, r) for g in f["grads"]]) for f in fl_fulls]
+        assert compare_run(f"post-LN {name} rank {r}, peer sums vs unsharded", gpu, ora_r, fl_r, cfg["n_layers"]), f"{name} rank {r}"
 
 
 @pytest.mark.parametrize("name,subs", [("B1", (1, 2, 4)), ("B2", (1, 2, 4))])

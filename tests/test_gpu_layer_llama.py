@@ -8,7 +8,7 @@ import torch
 
 import synth_inputs as si
 from tests import layer_harness as LH
-from tests.test_gpu_layer import check_tensor
+from tests.layer_harness import compare_run
 from tests.util import rel_err
 
 pytestmark = pytest.mark.gpu
@@ -65,14 +65,8 @@ def oracle_rank_only(cfg, rank, layers, x, dy, seed=0, dtype=torch.float64, bf16
     return ll.model_forward_backward(shards, x, dy, cfg, seed=seed, dtype=dtype, bf16_sites=bf16_sites)
 
 
-def compare(gpu, ora, floor, layers):
-    oks = [check_tensor("y", gpu["y"], ora["y"], LH.FWD_TOL, floor["y"] if floor else None),
-           check_tensor("dx", gpu["dx"], ora["dx"], LH.GRAD_TOL, floor["dx"] if floor else None)]
-    for l in range(layers):
-        og, fg = to_gpu_layout(ora["grads"][l]), to_gpu_layout(floor["grads"][l]) if floor else None
-        for k in PARAMS:
-            oks.append(check_tensor(f"L{l}.d{k}", gpu["grads"][l][k], og[k], LH.GRAD_TOL, fg[k] if fg else None))
-    return all(oks)
+def compare(case, gpu, ora, floors, layers):
+    return compare_run(case, gpu, ora, floors, layers, to_layout=to_gpu_layout)
 
 
 RAGGED = dict(arch="llama", hidden=768, n_heads=6, seq=200, batch=3, tp=3, n_sub=3, n_layers=2, causal=1, dropout_p=0.2, ffn_hidden=2016,
@@ -92,8 +86,8 @@ def test_rank_shard_matches_oracle(name, ranks, dtype):
         print(f"\n== {name} rank {r}: rank-only LLaMA-style layer", flush=True)
         gpu = gpu_run(cfg, r, layers, x, dy, seed=7)
         ora = oracle_rank_only(cfg, r, layers, x, dy, seed=7, dtype=dtype)
-        fl = oracle_rank_only(cfg, r, layers, x, dy, seed=7, dtype=dtype, bf16_sites=ll.LLAMA_BF16_OPERAND_SITES)
-        assert compare(gpu, ora, fl, cfg["n_layers"]), f"{name} rank {r}"
+        fl = [oracle_rank_only(cfg, r, layers, x, dy, seed=7, dtype=dt, bf16_sites=ll.LLAMA_BF16_OPERAND_SITES) for dt in (torch.float64, torch.float32)]
+        assert compare(f"LLaMA-style {name} rank {r}, rank-only", gpu, ora, fl, cfg["n_layers"]), f"{name} rank {r}"
         del gpu, ora, fl
         torch.cuda.empty_cache()
 
@@ -104,7 +98,7 @@ def test_with_peer_sums_every_rank_gives_the_unsharded_result(name):
     cfg = si.LLAMA_CONFIGS[name]
     layers, x, dy = make_inputs(cfg)
     full = ll.model_forward_backward(layers, x, dy, cfg)
-    fl_full = ll.model_forward_backward(layers, x, dy, cfg, bf16_sites=ll.LLAMA_BF16_OPERAND_SITES)
+    fl_fulls = [ll.model_forward_backward(layers, x, dy, cfg, dtype=dt, bf16_sites=ll.LLAMA_BF16_OPERAND_SITES) for dt in (torch.float64, torch.float32)]
     h, t, F = cfg["hidden"], cfg["tp"], cfg["ffn_hidden"]
     hp, fp = h // t, F // t
     for r in range(t):
@@ -127,8 +121,8 @@ def test_with_peer_sums_every_rank_gives_the_unsharded_result(name):
             s["wo"], s["w2"], s["wg"], s["wu"] = g["wo"][a, :], g["w2"][f, :], g["wg"][:, f], g["wu"][:, f]
             return s
         ora_r = dict(y=full["y"], dx=full["dx"], grads=[sl(g) for g in full["grads"]])
-        fl_r = dict(y=fl_full["y"], dx=fl_full["dx"], grads=[sl(g) for g in fl_full["grads"]])
-        assert compare(gpu, ora_r, fl_r, cfg["n_layers"]), f"{name} rank {r}"
+        fl_r = [dict(y=f["y"], dx=f["dx"], grads=[sl(g) for g in f["grads"]]) for f in fl_fulls]
+        assert compare(f"LLaMA-style {name} rank {r}, peer sums vs unsharded", gpu, ora_r, fl_r, cfg["n_layers"]), f"{name} rank {r}"
 
 
 @pytest.mark.parametrize("name,subs", [("L1", (1, 2, 4, 8)), ("L2", (1, 2, 8))])
