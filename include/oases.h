@@ -128,7 +128,8 @@ int oases_create(const oases_layer_cfg *cfg, oases_handle **out);
 void oases_destroy(oases_handle *h);
 
 /* Bytes of caller-allocated device workspace (activation stash of all layers + backward scratch).
- * The same workspace must be passed to oases_forward and to the oases_backward that follows it. */
+ * The same workspace must be passed to oases_forward and to the oases_backward that follows it; every call that takes
+ * a workspace also takes its size in bytes and returns OASES_EWORKSPACE, before any launch, if that is less than this. */
 size_t oases_workspace_bytes(const oases_handle *h);
 
 /* Forward of all layers under Alg. 1 "At Forward": for each computation sequence, sub-batch after
@@ -137,8 +138,8 @@ size_t oases_workspace_bytes(const oases_handle *h);
  * while stream_compute goes on with the next sub-batch.  w: [n_layers]; peers: [n_layers] or NULL.
  * x [M,h] fp32 in, y [M,h] fp32 out (y may not alias x). */
 int oases_forward(oases_handle *h, const oases_weights *w, const void *x, void *y,
-                  const oases_peer_sums *peers, void *workspace, void *stream_compute,
-                  void *stream_comm);
+                  const oases_peer_sums *peers, void *workspace, size_t workspace_bytes,
+                  void *stream_compute, void *stream_comm);
 
 /* Backward of all layers under Alg. 1 "At Backward" with stored activations: sub-batches in
  * reverse order; each column-parallel input-gradient partial starts its reduction point on
@@ -148,7 +149,7 @@ int oases_forward(oases_handle *h, const oases_weights *w, const void *x, void *
  * dy [M,h] fp32 in, dx [M,h] fp32 out; g: [n_layers], accumulated into. */
 int oases_backward(oases_handle *h, const oases_weights *w, const void *x, const void *dy,
                    void *dx, const oases_grads *g, const oases_peer_sums *peers, void *workspace,
-                   void *stream_compute, void *stream_comm);
+                   size_t workspace_bytes, void *stream_compute, void *stream_comm);
 
 /* Segment-level calls: lock-step emulation of the t ranks of a partition on one GPU.  What rank r feeds into its FFN block
  * depends on the other ranks' attention partials, so t ranks can only be run side by side one computation sequence at a
@@ -171,12 +172,15 @@ int oases_backward(oases_handle *h, const oases_weights *w, const void *x, const
  *   from, or NULL to read this rank's own partial from the workspace (t = 1); EINVAL if given for a segment that starts
  *   from none.  x, y, dy, dx, w, g, workspace as in oases_forward / oases_backward (the same workspace through all
  *   segments of a step); peer sums do not exist at this level.  Run back to back with NULL partial_out / reduced_in the
- *   segments give what oases_forward / oases_backward give without peer sums, bit for bit. */
+ *   segments give what oases_forward / oases_backward give without peer sums: y, dx and the weight-matrix gradients bit for
+ *   bit; the bias and LayerNorm-parameter gradients (column sums, which a segment finishes at once and the whole pass
+ *   finishes in one launch at its end) up to the order of the fp32 additions. */
 int oases_forward_segment(oases_handle *h, int layer, int segment, const oases_weights *w, const void *x, void *y,
-                          void *workspace, void *partial_out, const void *reduced_in, void *stream);
+                          void *workspace, size_t workspace_bytes, void *partial_out, const void *reduced_in,
+                          void *stream);
 int oases_backward_segment(oases_handle *h, int layer, int segment, const oases_weights *w, const void *x,
-                           const void *dy, void *dx, const oases_grads *g, void *workspace, void *partial_out,
-                           const void *reduced_in, void *stream);
+                           const void *dy, void *dx, const oases_grads *g, void *workspace, size_t workspace_bytes,
+                           void *partial_out, const void *reduced_in, void *stream);
 
 /* The operator order of the schedule as text, one operator per line
  * ("<stream> <op> L<layer> sb<sub-batch>", "sb*" = all sub-batches at once), NUL-terminated into buf (at most n bytes).

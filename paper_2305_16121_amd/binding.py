@@ -54,10 +54,10 @@ _sig("oases_last_error", C.c_char_p)
 _sig("oases_create", _i, C.POINTER(LayerCfg), C.POINTER(_P))
 _sig("oases_destroy", None, _P)
 _sig("oases_workspace_bytes", _sz, _P)
-_sig("oases_forward", _i, _P, C.POINTER(Weights), _P, _P, C.POINTER(PeerSums), _P, _P, _P)
-_sig("oases_backward", _i, _P, C.POINTER(Weights), _P, _P, _P, C.POINTER(Grads), C.POINTER(PeerSums), _P, _P, _P)
-_sig("oases_forward_segment", _i, _P, _i, _i, C.POINTER(Weights), _P, _P, _P, _P, _P, _P)
-_sig("oases_backward_segment", _i, _P, _i, _i, C.POINTER(Weights), _P, _P, _P, C.POINTER(Grads), _P, _P, _P, _P)
+_sig("oases_forward", _i, _P, C.POINTER(Weights), _P, _P, C.POINTER(PeerSums), _P, _sz, _P, _P)
+_sig("oases_backward", _i, _P, C.POINTER(Weights), _P, _P, _P, C.POINTER(Grads), C.POINTER(PeerSums), _P, _sz, _P, _P)
+_sig("oases_forward_segment", _i, _P, _i, _i, C.POINTER(Weights), _P, _P, _P, _sz, _P, _P, _P)
+_sig("oases_backward_segment", _i, _P, _i, _i, C.POINTER(Weights), _P, _P, _P, C.POINTER(Grads), _P, _sz, _P, _P, _P)
 _sig("oases_schedule_dump", _i, _P, _i, C.c_char_p, _sz)
 _sig("oases_profile_read", _i, _P, _i, C.POINTER(C.c_float), _i)
 _sig("oases_workspace_tensor", _i, _P, C.c_char_p, _i, C.POINTER(_sz), C.POINTER(_sz))
@@ -104,6 +104,11 @@ def ptr(t):
     if isinstance(t, int):
         return t
     return t.data_ptr()
+
+
+def nbytes(t):
+    """Size in bytes of a torch tensor handed over as a buffer (0 for None)."""
+    return 0 if t is None else t.numel() * t.element_size()
 
 
 def stream_ptr(s):
@@ -175,25 +180,25 @@ class Handle:
     def forward(self, weights, x, y, workspace, peers=None, s_compute=None, s_comm=None):
         w = self._structs(Weights, _PARAMS, weights)
         p = self._structs(PeerSums, _PEERS, peers) if peers is not None else None
-        check(lib.oases_forward(self._h, w, ptr(x), ptr(y), p, ptr(workspace), stream_ptr(s_compute), stream_ptr(s_comm)))
+        check(lib.oases_forward(self._h, w, ptr(x), ptr(y), p, ptr(workspace), nbytes(workspace), stream_ptr(s_compute), stream_ptr(s_comm)))
 
     def backward(self, weights, x, dy, dx, grads, workspace, peers=None, s_compute=None, s_comm=None):
         w = self._structs(Weights, _PARAMS, weights)
         g = self._structs(Grads, _PARAMS, grads)
         p = self._structs(PeerSums, _PEERS, peers) if peers is not None else None
-        check(lib.oases_backward(self._h, w, ptr(x), ptr(dy), ptr(dx), g, p, ptr(workspace), stream_ptr(s_compute),
+        check(lib.oases_backward(self._h, w, ptr(x), ptr(dy), ptr(dx), g, p, ptr(workspace), nbytes(workspace), stream_ptr(s_compute),
                                  stream_ptr(s_comm)))
 
 
     def forward_segment(self, layer, segment, weights, x, y, workspace, partial_out=None, reduced_in=None, stream=None):
         w = self._structs(Weights, _PARAMS, weights)
-        check(lib.oases_forward_segment(self._h, layer, segment, w, ptr(x), ptr(y), ptr(workspace), ptr(partial_out), ptr(reduced_in),
+        check(lib.oases_forward_segment(self._h, layer, segment, w, ptr(x), ptr(y), ptr(workspace), nbytes(workspace), ptr(partial_out), ptr(reduced_in),
                                         stream_ptr(stream)))
 
     def backward_segment(self, layer, segment, weights, x, dy, dx, grads, workspace, partial_out=None, reduced_in=None, stream=None):
         w = self._structs(Weights, _PARAMS, weights)
         g = self._structs(Grads, _PARAMS, grads)
-        check(lib.oases_backward_segment(self._h, layer, segment, w, ptr(x), ptr(dy), ptr(dx), g, ptr(workspace), ptr(partial_out),
+        check(lib.oases_backward_segment(self._h, layer, segment, w, ptr(x), ptr(dy), ptr(dx), g, ptr(workspace), nbytes(workspace), ptr(partial_out),
                                          ptr(reduced_in), stream_ptr(stream)))
 
 

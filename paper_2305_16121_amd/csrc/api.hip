@@ -41,13 +41,15 @@ enum OpKind {
   // recomputation), rotation back of dQ and dK behind the attention backward
   F_ROPE_TABLE, F_ROPE, R_ROPE, B_ROPE,
   // PROJ.wgrad and QKV.wgrad as one launch, where the shapes make that the faster way
-  B_PQ_WGRAD
+  B_PQ_WGRAD,
+  // second stage of every column reduction of the backward pass (bias and LayerNorm-parameter gradients), one launch
+  B_COLSUMS
 };
 static const char* kOpName[] = {
     "LN1", "QKV", "ATTN", "PROJ", "R1+BDR1+LN2", "FC1+GELU", "FC2", "R2+BDR2",
     "BDR2.b", "FC2.dgrad+dGELU", "FC1.dgrad", "R3+LN2.b+BDR1.b", "FC2.wgrad", "FC1.wgrad", "b1.sum", "PROJ.dgrad",
     "PROJ.wgrad", "ATTN.b", "QKV.dgrad", "R4+LN1.b", "QKV.wgrad", "bqkv.sum",
-    "LN2.r", "FC1+GELU.r", "LN1.r", "QKV.r", "ATTN.r", "join", "ROPE.table", "ROPE", "ROPE.r", "ROPE.b", "PROJ+QKV.wgrad"};
+    "LN2.r", "FC1+GELU.r", "LN1.r", "QKV.r", "ATTN.r", "join", "ROPE.table", "ROPE", "ROPE.r", "ROPE.b", "PROJ+QKV.wgrad", "colsums"};
 // names of the same operator slots in the LLaMA-style layer (RMSNorm, SwiGLU)
 static const char* op_name(int kind, bool llama, bool bert) {
   if (bert) {  // post-LN: the normalisation sits behind the residual sum, the layer input enters the GEMM as it is
@@ -116,6 +118,9 @@ struct oases_handle {
   bool prof_ran[2] = {false, false};
   std::vector<Tensor> tensors;     // per-layer tensors, offsets relative to the layer base
   size_t layer_bytes, shared_off, scratch_comm_off, scratch_compute_off, gemm_ws_off, gemm_ws_bytes, total_bytes;
+  // arena of partial rows of the backward pass's column reductions, per layer: five slots (see ColsumSlot)
+  size_t colsum_off, colsum_layer_bytes, colsum_slot_off[5];
+  int colsum_groups_sub, colsum_groups_all;  // row groups of a reduction over a sub-batch's rows / over all M rows
 };
 
 namespace oases {
@@ -163,6 +168,21 @@ static bool plan_workspace(oases_handle* H) {
   H->scratch_compute_off = tot;
   size_t wide = 3 * hp > fw ? 3 * hp : fw;
   tot += align_up((size_t)kColPartials * wide * 4);
+  // Partial rows of the column reductions of a backward pass, kept until its single second-stage launch.  Slots of a
+  // layer: three reduction-point kernels with up to three output arrays each, laid out [array][sub-batch][group][h], and
+  // the two bias sums over all rows [group][columns].
+  {
+    H->colsum_groups_sub = colsum_groups(H->Ms);
+    H->colsum_groups_all = colsum_groups(H->M);
+    const size_t tri = align_up((size_t)3 * H->n * H->colsum_groups_sub * h * 4);
+    size_t o = 0;
+    for (int k = 0; k < 3; k++) { H->colsum_slot_off[k] = o; o += tri; }
+    H->colsum_slot_off[3] = o; o += align_up((size_t)H->colsum_groups_all * fw * 4);
+    H->colsum_slot_off[4] = o; o += align_up((size_t)H->colsum_groups_all * 3 * hp * 4);
+    H->colsum_layer_bytes = o;
+    H->colsum_off = tot;
+    tot += o * H->L;
+  }
   // split-K partial planes: up to 8 fp32 copies of the widest GEMM output of the layer
   const size_t Ms = H->Ms;
   size_t mn = Ms * h;
@@ -270,6 +290,8 @@ static void build_backward(oases_handle* H) {
     if (!H->llama) ops.push_back(Op{B_BQKV_SUM, l, -1, 0, -1, -1});
   }
   for (int j = n - 1; j >= 0; j--) ops.push_back(Op{JOIN, 0, j, 0, ev_id(H, 0, 3, j, 1), -1});
+  // every first stage of a column reduction has run (both streams are joined): one launch adds up all partial rows
+  ops.push_back(Op{B_COLSUMS, 0, -1, 0, -1, -1});
 }
 
 static int check_ptrs(const void* const* p, int n, const char* who) {
@@ -308,6 +330,11 @@ struct Run {
   // workspace partial) and that the consuming kernel reads as the already reduced sum (instead of partial + peer sum)
   float* partial_out[4] = {nullptr, nullptr, nullptr, nullptr};
   const float* reduced_in[4] = {nullptr, nullptr, nullptr, nullptr};
+  // whole backward pass: the second stage of the column reductions is collected here and launched once (B_COLSUMS);
+  // segment calls finish every reduction at once (defer_colsums = false)
+  bool defer_colsums = false;
+  std::vector<ColsumJob>* jobs = nullptr;  // capacity fixed before the pass
+  int* n_jobs = nullptr;
 };
 
 template <typename T>
@@ -341,6 +368,38 @@ static int run_op(const Run& R, const Op& op) {
   float* dxout = l == 0 ? R.dx : wsp<float>(R, T_dy, l - 1);                   // gradient of the layer input
   float* scr_comm = reinterpret_cast<float*>(R.ws + H->scratch_comm_off);
   float* scr_comp = reinterpret_cast<float*>(R.ws + H->scratch_compute_off);
+  // Column reductions.  slot: 0 the top layer's dropout backward, 1 / 2 the reduction-point kernels behind R3 / R4, 3 / 4 the
+  // bias sums of FC1 / QKV.  Whole pass: the partial rows go to this operator's slot of the arena and the second stage
+  // joins the list; otherwise they go to the stream's scratch and the second stage follows at once.
+  ColsumSink sink;
+  float* cs_scratch = nullptr;
+  auto colsum = [&](int slot) -> ColsumSink* {
+    if (!R.defer_colsums) { cs_scratch = slot < 3 ? scr_comm : scr_comp; return nullptr; }
+    float* base = reinterpret_cast<float*>(R.ws + H->colsum_off + (size_t)l * H->colsum_layer_bytes + H->colsum_slot_off[slot]);
+    if (slot < 3) {
+      const int g = H->colsum_groups_sub;
+      sink.first_row = j * g;
+      sink.rows_total = H->n * g;
+      sink.kstride = (size_t)H->n * g * h;
+      cs_scratch = base + (size_t)sink.first_row * h;
+    } else {
+      sink.first_row = 0;
+      sink.rows_total = H->colsum_groups_all;
+      sink.kstride = 0;
+      cs_scratch = base;
+    }
+    sink.jobs = R.jobs->data();
+    sink.n = *R.n_jobs;
+    sink.cap = (int)R.jobs->size();
+    return &sink;
+  };
+  auto colsum_done = [&](int rc) -> int {  // behind a launch that was given colsum(...): keep what it put on the list
+    if (rc == 0 && R.defer_colsums) {
+      if (sink.overflow) { set_error("internal error: column-reduction job list too short"); return OASES_EINVAL; }
+      *R.n_jobs = sink.n;
+    }
+    return rc;
+  };
   void* gws = R.ws + H->gemm_ws_off;  // split-K partial planes (compute stream only)
   const int pin = (H->cfg.flags & OASES_FLAG_PIN_GEMM) ? H->M : 0;  // kernels chosen as for all M rows, whatever the sub-batch
   uint16_t* u = wsp<uint16_t>(R, T_u, l);
@@ -376,27 +435,27 @@ static int run_op(const Run& R, const Op& op) {
                              make_drop_cfg(seed, l, 1, p), (int64_t)r0, s, false, yout + r0 * h);
       }
       case B_BDR2:  // top of the stack: dy through LN2, then the dropout backward of the FFN branch
-        return launch_layernorm_bwd(dyin + r0 * h, nullptr, nullptr, wsp<float>(R, T_s2, l) + r0 * h, wsp<float>(R, T_mu2, l) + r0,
+        { ColsumSink* cs = colsum(0); return colsum_done(launch_layernorm_bwd(dyin + r0 * h, nullptr, nullptr, wsp<float>(R, T_s2, l) + r0 * h, wsp<float>(R, T_mu2, l) + r0,
                                     wsp<float>(R, T_rstd2, l) + r0, (const float*)W.ln2_g, wsp<float>(R, T_ds2, l) + r0 * h,
                                     (float*)R.g[l].ln2_g, (float*)R.g[l].ln2_b, wsp<uint16_t>(R, T_dz2, l) + r0 * h, (float*)R.g[l].b2, Ms,
-                                    h, make_drop_cfg(seed, l, 1, p), (int64_t)r0, scr_comm, s, false, true);
+                                    h, make_drop_cfg(seed, l, 1, p), (int64_t)r0, cs_scratch, s, false, true, cs)); }
       case B_R3:  // gradient of x1 = FFN-input gradient (reduced) + residual branch ds2, through LN1
-        return launch_layernorm_bwd(part_r(2), peer_k(2), wsp<float>(R, T_ds2, l) + r0 * h,
+        { ColsumSink* cs = colsum(1); return colsum_done(launch_layernorm_bwd(part_r(2), peer_k(2), wsp<float>(R, T_ds2, l) + r0 * h,
                                     wsp<float>(R, T_s1, l) + r0 * h, wsp<float>(R, T_mu1, l) + r0, wsp<float>(R, T_rstd1, l) + r0,
                                     (const float*)W.ln1_g, wsp<float>(R, T_dx1, l) + r0 * h, (float*)R.g[l].ln1_g, (float*)R.g[l].ln1_b,
                                     wsp<uint16_t>(R, T_dz1, l) + r0 * h, (float*)R.g[l].bo, Ms, h, make_drop_cfg(seed, l, 0, p),
-                                    (int64_t)r0, scr_comm, s, false, true);
+                                    (int64_t)r0, cs_scratch, s, false, true, cs)); }
       case B_R4:  // gradient of the layer input = QKV-input gradient (reduced) + residual branch ds1
         if (l == 0)
           return launch_add3(part_r(3), wsp<float>(R, T_dx1, l) + r0 * h, peer_k(3),
                              dxout + r0 * h, (int64_t)Ms * h, s);
         // ... which is the output gradient of the layer below: straight through its LN2 and FFN-branch dropout
-        return launch_layernorm_bwd(part_r(3), peer_k(3), wsp<float>(R, T_dx1, l) + r0 * h,
+        { ColsumSink* cs = colsum(2); return colsum_done(launch_layernorm_bwd(part_r(3), peer_k(3), wsp<float>(R, T_dx1, l) + r0 * h,
                                     wsp<float>(R, T_s2, l - 1) + r0 * h, wsp<float>(R, T_mu2, l - 1) + r0,
                                     wsp<float>(R, T_rstd2, l - 1) + r0, (const float*)R.w[l - 1].ln2_g,
                                     wsp<float>(R, T_ds2, l - 1) + r0 * h, (float*)R.g[l - 1].ln2_g, (float*)R.g[l - 1].ln2_b,
                                     wsp<uint16_t>(R, T_dz2, l - 1) + r0 * h, (float*)R.g[l - 1].b2, Ms, h,
-                                    make_drop_cfg(seed, l - 1, 1, p), (int64_t)r0, scr_comm, s, false, true);
+                                    make_drop_cfg(seed, l - 1, 1, p), (int64_t)r0, cs_scratch, s, false, true, cs)); }
       default:
         break;  // GEMMs, attention, bias sums: as in the GPT layer
     }
@@ -446,8 +505,8 @@ static int run_op(const Run& R, const Op& op) {
     }
     // ---------------------------------------------------------------- backward
     case B_BDR2:
-      return launch_dropout_bwd(dyin + r0 * h, wsp<uint16_t>(R, T_dz2, l) + r0 * h, (float*)R.g[l].b2, Ms, h,
-                                make_drop_cfg(seed, l, 1, p), (int64_t)r0, scr_comm, s);
+      { ColsumSink* cs = colsum(0); return colsum_done(launch_dropout_bwd(dyin + r0 * h, wsp<uint16_t>(R, T_dz2, l) + r0 * h, (float*)R.g[l].b2, Ms, h,
+                                make_drop_cfg(seed, l, 1, p), (int64_t)r0, cs_scratch, s, cs)); }
     case B_FC2_DGRAD:
       if (H->llama)
         return launch_gemm(OASES_GEMM_NT, OASES_EPI_DSWIGLU, Ms, fp, h, wsp<uint16_t>(R, T_dz2, l) + r0 * h, h, W.w2, h,
@@ -458,11 +517,11 @@ static int run_op(const Run& R, const Op& op) {
       return launch_gemm(OASES_GEMM_NT, OASES_EPI_F32, Ms, h, fw, wsp<uint16_t>(R, T_dg, l) + r0 * fw, fw, W.w1, fw,
                          part_w(2), h, nullptr, nullptr, 0, gws, H->gemm_ws_bytes, 0, s, pin);
     case B_R3:
-      return launch_layernorm_bwd(part_r(2), peer_k(2), dyin + r0 * h,
+      { ColsumSink* cs = colsum(1); return colsum_done(launch_layernorm_bwd(part_r(2), peer_k(2), dyin + r0 * h,
                                   wsp<float>(R, T_x1, l) + r0 * h, wsp<float>(R, T_mu2, l) + r0, wsp<float>(R, T_rstd2, l) + r0,
                                   (const float*)W.ln2_g, wsp<float>(R, T_dx1, l) + r0 * h, (float*)R.g[l].ln2_g,
                                   (float*)R.g[l].ln2_b, wsp<uint16_t>(R, T_dz1, l) + r0 * h, (float*)R.g[l].bo, Ms, h,
-                                  make_drop_cfg(seed, l, 0, p), (int64_t)r0, scr_comm, s, rms);
+                                  make_drop_cfg(seed, l, 0, p), (int64_t)r0, cs_scratch, s, rms, false, cs)); }
     case B_FC2_WGRAD:
       return launch_gemm(OASES_GEMM_TN, 0, fp, h, Ms, f + r0 * fp, fp, wsp<uint16_t>(R, T_dz2, l) + r0 * h, h, R.g[l].w2, h,
                          nullptr, nullptr, 0, gws, H->gemm_ws_bytes, 0, s);
@@ -470,7 +529,7 @@ static int run_op(const Run& R, const Op& op) {
       return launch_gemm(OASES_GEMM_TN, 0, h, fw, Ms, v2 + r0 * h, h, wsp<uint16_t>(R, T_dg, l) + r0 * fw, fw, R.g[l].w1, fw,
                          nullptr, nullptr, 0, gws, H->gemm_ws_bytes, 0, s);
     case B_B1_SUM:
-      return launch_colsum_bf16(wsp<uint16_t>(R, T_dg, l) + r0 * fp, fp, Ms, fp, (float*)R.g[l].b1, scr_comp, s);
+      { ColsumSink* cs = colsum(3); return colsum_done(launch_colsum_bf16(wsp<uint16_t>(R, T_dg, l) + r0 * fp, fp, Ms, fp, (float*)R.g[l].b1, cs_scratch, s, cs)); }
     case B_PROJ_DGRAD:
       return launch_gemm(OASES_GEMM_NT, OASES_EPI_BF16, Ms, hp, h, wsp<uint16_t>(R, T_dz1, l) + r0 * h, h, W.wo, h,
                          wsp<uint16_t>(R, T_da, l) + r0 * hp, hp, nullptr, nullptr, 0, gws, H->gemm_ws_bytes, 0, s, pin);
@@ -486,12 +545,12 @@ static int run_op(const Run& R, const Op& op) {
                          3 * hp, part_w(3), h, nullptr, nullptr, 0, gws, H->gemm_ws_bytes, 0, s, pin);
     case B_R4: {
       const bool more = l > 0;  // fuse the dropout backward of the layer below (its BDR2) behind dx
-      return launch_layernorm_bwd(part_r(3), peer_k(3),
+      { ColsumSink* cs = colsum(2); return colsum_done(launch_layernorm_bwd(part_r(3), peer_k(3),
                                   wsp<float>(R, T_dx1, l) + r0 * h, xin + r0 * h, wsp<float>(R, T_mu1, l) + r0,
                                   wsp<float>(R, T_rstd1, l) + r0, (const float*)W.ln1_g, dxout + r0 * h, (float*)R.g[l].ln1_g,
                                   (float*)R.g[l].ln1_b, more ? wsp<uint16_t>(R, T_dz2, l - 1) + r0 * h : nullptr,
                                   more ? (float*)R.g[l - 1].b2 : nullptr, Ms, h, make_drop_cfg(seed, l - 1, 1, p), (int64_t)r0,
-                                  scr_comm, s, rms);
+                                  cs_scratch, s, rms, false, cs)); }
     }
     case B_QKV_WGRAD:
       return launch_gemm(OASES_GEMM_TN, 0, h, 3 * hp, Ms, u + r0 * h, h, wsp<uint16_t>(R, T_dqkv, l) + r0 * 3 * hp, 3 * hp,
@@ -500,7 +559,7 @@ static int run_op(const Run& R, const Op& op) {
       return launch_gemm_tn_pair(Ms, hp, h, attn + r0 * hp, hp, wsp<uint16_t>(R, T_dz1, l) + r0 * h, h, R.g[l].wo, h, h, 3 * hp, u + r0 * h, h,
                                  wsp<uint16_t>(R, T_dqkv, l) + r0 * 3 * hp, 3 * hp, R.g[l].wqkv, 3 * hp, s);
     case B_BQKV_SUM:
-      return launch_colsum_bf16(wsp<uint16_t>(R, T_dqkv, l) + r0 * 3 * hp, 3 * hp, Ms, 3 * hp, (float*)R.g[l].bqkv, scr_comp, s);
+      { ColsumSink* cs = colsum(4); return colsum_done(launch_colsum_bf16(wsp<uint16_t>(R, T_dqkv, l) + r0 * 3 * hp, 3 * hp, Ms, 3 * hp, (float*)R.g[l].bqkv, cs_scratch, s, cs)); }
     // ---------------------------------------------------------------- recompute: the forward kernels again
     case R_LN1:
       return launch_layernorm_fwd(xin + r0 * h, (const float*)W.ln1_g, (const float*)W.ln1_b, u + r0 * h,
@@ -525,6 +584,12 @@ static int run_op(const Run& R, const Op& op) {
     }
     case JOIN:
       return 0;
+    case B_COLSUMS: {
+      if (!R.defer_colsums) return 0;
+      const int rc = launch_colsum_finalize(R.jobs->data(), *R.n_jobs, s);
+      *R.n_jobs = 0;
+      return rc;
+    }
   }
   set_error("unknown operator %d", op.kind);
   return OASES_EINVAL;
@@ -695,13 +760,20 @@ static int check_weights(const oases_handle* H, const oases_weights* w) {
   return 0;
 }
 
+static int check_workspace(const oases_handle* H, size_t bytes, const char* who) {
+  if (bytes >= H->total_bytes) return 0;
+  set_error("%s: workspace of %zu bytes is smaller than the %zu bytes oases_workspace_bytes() asks for", who, bytes, H->total_bytes);
+  return OASES_EWORKSPACE;
+}
+
 int oases_forward(oases_handle* H, const oases_weights* w, const void* x, void* y, const oases_peer_sums* peers,
-                  void* workspace, void* stream_compute, void* stream_comm) {
+                  void* workspace, size_t workspace_bytes, void* stream_compute, void* stream_comm) {
   if (!H || !w) { set_error("oases_forward: NULL handle or weights"); return OASES_ENULL; }
   const void* p[] = {x, y, workspace};
   int rc = check_ptrs(p, 3, "oases_forward");
   if (rc) return rc;
   if (x == y) { set_error("oases_forward: y may not alias x"); return OASES_EINVAL; }
+  if ((rc = check_workspace(H, workspace_bytes, "oases_forward"))) return rc;
   if ((rc = check_weights(H, w))) return rc;
   Run R{H, w, nullptr, peers, (char*)workspace, (const float*)x, (float*)y, nullptr, nullptr,
         {(hipStream_t)stream_compute, (hipStream_t)stream_comm}};
@@ -709,11 +781,12 @@ int oases_forward(oases_handle* H, const oases_weights* w, const void* x, void* 
 }
 
 int oases_backward(oases_handle* H, const oases_weights* w, const void* x, const void* dy, void* dx, const oases_grads* g,
-                   const oases_peer_sums* peers, void* workspace, void* stream_compute, void* stream_comm) {
+                   const oases_peer_sums* peers, void* workspace, size_t workspace_bytes, void* stream_compute, void* stream_comm) {
   if (!H || !w || !g) { set_error("oases_backward: NULL handle, weights or grads"); return OASES_ENULL; }
   const void* p[] = {x, dy, dx, workspace};
   int rc = check_ptrs(p, 4, "oases_backward");
   if (rc) return rc;
+  if ((rc = check_workspace(H, workspace_bytes, "oases_backward"))) return rc;
   if ((rc = check_weights(H, w))) return rc;
   for (int l = 0; l < H->L; l++) {
     const void* q[] = {g[l].ln1_g, g[l].wqkv, g[l].wo, g[l].ln2_g, g[l].w1, g[l].w2, g[l].ln1_b, g[l].bqkv, g[l].bo, g[l].ln2_b, g[l].b1, g[l].b2};
@@ -721,6 +794,11 @@ int oases_backward(oases_handle* H, const oases_weights* w, const void* x, const
   }
   Run R{H, w, g, peers, (char*)workspace, (const float*)x, nullptr, (const float*)dy, (float*)dx,
         {(hipStream_t)stream_compute, (hipStream_t)stream_comm}};
+  std::vector<ColsumJob> jobs((size_t)H->L * 12);  // at most 11 output arrays of column reductions per layer
+  int n_jobs = 0;
+  R.defer_colsums = true;
+  R.jobs = &jobs;
+  R.n_jobs = &n_jobs;
   return run_ops(R, H->bwd);
 }
 
@@ -783,23 +861,26 @@ static int run_segment(Run& R, bool backward, int layer, int segment, void* part
 }  // namespace oases
 
 int oases_forward_segment(oases_handle* H, int layer, int segment, const oases_weights* w, const void* x, void* y, void* workspace,
-                          void* partial_out, const void* reduced_in, void* stream) {
+                          size_t workspace_bytes, void* partial_out, const void* reduced_in, void* stream) {
   if (!H || !w) { set_error("oases_forward_segment: NULL handle or weights"); return OASES_ENULL; }
   const void* p[] = {x, y, workspace};
   int rc = check_ptrs(p, 3, "oases_forward_segment");
   if (rc) return rc;
   if (x == y) { set_error("oases_forward_segment: y may not alias x"); return OASES_EINVAL; }
+  if ((rc = check_workspace(H, workspace_bytes, "oases_forward_segment"))) return rc;
   if ((rc = check_weights(H, w))) return rc;
   Run R{H, w, nullptr, nullptr, (char*)workspace, (const float*)x, (float*)y, nullptr, nullptr, {(hipStream_t)stream, (hipStream_t)stream}};
   return run_segment(R, false, layer, segment, partial_out, reduced_in);
 }
 
 int oases_backward_segment(oases_handle* H, int layer, int segment, const oases_weights* w, const void* x, const void* dy, void* dx,
-                           const oases_grads* g, void* workspace, void* partial_out, const void* reduced_in, void* stream) {
+                           const oases_grads* g, void* workspace, size_t workspace_bytes, void* partial_out, const void* reduced_in,
+                           void* stream) {
   if (!H || !w || !g) { set_error("oases_backward_segment: NULL handle, weights or grads"); return OASES_ENULL; }
   const void* p[] = {x, dy, dx, workspace};
   int rc = check_ptrs(p, 4, "oases_backward_segment");
   if (rc) return rc;
+  if ((rc = check_workspace(H, workspace_bytes, "oases_backward_segment"))) return rc;
   if ((rc = check_weights(H, w))) return rc;
   for (int l = 0; l < H->L; l++) {
     const void* q[] = {g[l].ln1_g, g[l].wqkv, g[l].wo, g[l].ln2_g, g[l].w1, g[l].w2, g[l].ln1_b, g[l].bqkv, g[l].bo, g[l].ln2_b, g[l].b1, g[l].b2};

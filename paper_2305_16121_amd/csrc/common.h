@@ -98,6 +98,35 @@ __device__ __forceinline__ float gelu_tanh_grad(float x) {
   return 0.5f * (1.0f + t) + 0.5f * x * (1.0f - t * t) * c0 * (1.0f + 3.0f * c1 * x * x);
 }
 
+// ---- two-stage column reductions (bias and LayerNorm-parameter gradients) ------------------------------------
+// First stage: the kernel that walks the rows leaves one partial row per row group in a scratch array [groups][cols].
+// Second stage: out[c] += sum over the partial rows, in a fixed order.  The second stage either follows at once, or --
+// with a ColsumSink -- is put on a list, so that all column reductions of a pass share one launch at its end and the
+// partial rows of one output from all sub-batches are added up together.
+struct ColsumJob {
+  const float* src;  // [groups][cols] partial rows
+  float* out;        // [cols], accumulated into; NULL: no job
+  int groups, cols;
+};
+constexpr int kMaxColsumJobs = 48;  // jobs of one second-stage launch
+struct ColsumSink {
+  // layout of the caller's arena for one first-stage call: its partial rows start at row `first_row` of `rows_total` rows
+  // per output array, the arrays of a call with several outputs lie `kstride` floats apart
+  int first_row = 0, rows_total = 0;
+  size_t kstride = 0;
+  ColsumJob* jobs = nullptr;  // list being built (capacity cap)
+  int n = 0, cap = 0;
+  bool overflow = false;
+  void add(float* out, const float* base, int groups, int cols) {  // one job per output array: the same array is added only once
+    for (int i = 0; i < n; i++)
+      if (jobs[i].out == out && jobs[i].src == base) return;
+    if (n >= cap) { overflow = true; return; }
+    jobs[n++] = ColsumJob{base, out, groups, cols};
+  }
+};
+int colsum_groups(int rows);  // row groups (partial rows) the first stage makes for `rows` rows
+int launch_colsum_finalize(const ColsumJob* jobs, int n, hipStream_t s);
+
 // ---- kernel launchers (one per .hip file), all enqueue-only, return 0 or OASES_E* ---------------
 int launch_dropout_mask(uint8_t* mask, const DropCfg& d, int64_t row0, int rows, int h, hipStream_t s);
 // rms = true: RMSNorm (no mean, no beta; mu / beta unused and may be NULL); bias may be NULL with rms
@@ -113,13 +142,14 @@ int launch_add3(const float* a, const float* b, const float* c, float* out, int6
 int launch_rope_table(float* tab, int seq, int head_dim, float theta, hipStream_t s);
 int launch_rope(void* qkv, int ld, int rows, int64_t row0, int seq, int heads, int head_dim, const float* tab, int inverse,
                 hipStream_t s);
+// sink (dropout_bwd, layernorm_bwd, colsum_bf16): nullptr = the second stage of the column sums follows at once
 int launch_dropout_bwd(const float* dyin, void* dz, float* dbias, int rows, int h, const DropCfg& d,
-                       int64_t row0, float* scratch, hipStream_t s);
+                       int64_t row0, float* scratch, hipStream_t s, ColsumSink* sink = nullptr);
 int launch_layernorm_bwd(const float* part, const float* peer, const float* dres, const float* x,
                          const float* mu, const float* rstd, const float* gamma, float* dxo, float* dgamma,
                          float* dbeta, void* dz, float* dbias, int rows, int h, const DropCfg& d,
-                         int64_t row0, float* scratch, hipStream_t s, bool rms = false, bool post = false);
-int launch_colsum_bf16(const void* a, int ld, int rows, int cols, float* out, float* scratch, hipStream_t s);
+                         int64_t row0, float* scratch, hipStream_t s, bool rms = false, bool post = false, ColsumSink* sink = nullptr);
+int launch_colsum_bf16(const void* a, int ld, int rows, int cols, float* out, float* scratch, hipStream_t s, ColsumSink* sink = nullptr);
 // splitk_ws: optional fp32 scratch for split-K partial planes (NULL: never split); forced_variant: 0 = choose, else
 // the instantiation to launch, encoded as gemm_variant() returns it
 // choice_rows > M (NN / NT): the kernel is chosen as for a launch of that many rows, so that launches over parts of those rows

@@ -157,38 +157,39 @@ __global__ __launch_bounds__(NT) void dropout_bwd_kernel(const float* __restrict
   }
 }
 
-// out[c] += sum_g scratch[k][g][c], for k < nk outputs
+// out[c] += sum over the partial rows src[g][c], g < groups, for every job of the list
 struct FinalizeArgs {
-  float* out[3];
-  int nk;
+  ColsumJob job[kMaxColsumJobs];
+  int n;
 };
-__global__ __launch_bounds__(NT) void colsum_finalize_kernel(const float* __restrict__ scratch, FinalizeArgs a, int groups,
-                                                             int cols) {
-  // one output array (blockIdx.y) and 16 columns per workgroup, the groups dealt to 16 slices; fixed summation tree, so
-  // the result does not depend on timing
-  __shared__ float red[16][17];
-  const int k = blockIdx.y;
-  if (!a.out[k]) return;
+__global__ __launch_bounds__(NT) void colsum_finalize_kernel(FinalizeArgs a) {
+  // one job (blockIdx.y) and 64 columns per workgroup: 16 lanes x 16 bytes cover the 64 columns of a partial row, the 16
+  // groups of lanes take the partial rows 16 apart; fixed summation order and tree, so the result does not depend on timing
+  __shared__ f32x4 red[16][17];
+  const ColsumJob& jb = a.job[blockIdx.y];
+  const int cols = jb.cols, groups = jb.groups;
+  if (!jb.out || (int)blockIdx.x * 64 >= cols) return;
   const int cx = threadIdx.x & 15, gy = threadIdx.x >> 4;
-  const int c = blockIdx.x * 16 + cx;
-  float s = 0.f;
+  const int c = blockIdx.x * 64 + 4 * cx;   // cols is a multiple of 8: a group of four columns is inside or outside
+  f32x4 s = {0.f, 0.f, 0.f, 0.f};
   if (c < cols) {
-    const float* p = scratch + (size_t)k * groups * cols + c;
+    const float* p = jb.src + c;
     int g = gy;
     for (; g + 48 < groups; g += 64) {
-      float v0 = p[(size_t)g * cols], v1 = p[(size_t)(g + 16) * cols], v2 = p[(size_t)(g + 32) * cols],
-            v3 = p[(size_t)(g + 48) * cols];
+      const f32x4 v0 = *reinterpret_cast<const f32x4*>(p + (size_t)g * cols), v1 = *reinterpret_cast<const f32x4*>(p + (size_t)(g + 16) * cols),
+                  v2 = *reinterpret_cast<const f32x4*>(p + (size_t)(g + 32) * cols), v3 = *reinterpret_cast<const f32x4*>(p + (size_t)(g + 48) * cols);
       s += (v0 + v1) + (v2 + v3);
     }
-    for (; g < groups; g += 16) s += p[(size_t)g * cols];
+    for (; g < groups; g += 16) s += *reinterpret_cast<const f32x4*>(p + (size_t)g * cols);
   }
   red[gy][cx] = s;
   __syncthreads();
   if (gy == 0 && c < cols) {
-    float t = 0.f;
+    f32x4 t = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int i = 0; i < 16; i++) t += red[i][cx];
-    a.out[k][c] += t;
+    f32x4* o = reinterpret_cast<f32x4*>(jb.out + c);
+    *o = *o + t;
   }
 }
 
@@ -204,10 +205,9 @@ __global__ __launch_bounds__(NT) void layernorm_bwd_kernel(const float* __restri
                                                            const float* __restrict__ mu, const float* __restrict__ rstd,
                                                            const float* __restrict__ gamma, float* __restrict__ dxo,
                                                            uint16_t* __restrict__ dz, float* __restrict__ scratch, int rows,
-                                                           int h, DropCfg d, int64_t row0, int want_dbias) {
+                                                           int h, DropCfg d, int64_t row0, int want_dbias, size_t gstride) {
   __shared__ float red[2 * (NT / 64)];
   const int tid = threadIdx.x, nc = h >> 2;
-  const size_t gstride = (size_t)gridDim.x * h;
   f32x4 ag[NC], ab[NC], az[NC];
 #pragma unroll
   for (int i = 0; i < NC; i++) ag[i] = ab[i] = az[i] = f32x4{0.f, 0.f, 0.f, 0.f};
@@ -352,10 +352,10 @@ __global__ __launch_bounds__(NT) void add3_kernel(const float* __restrict__ a, c
   *reinterpret_cast<f32x4*>(out + 4 * i) = v;
 }
 
-// row groups of a two-stage column reduction: about eight rows per group (few partial rows to add up), but at
-// least one group per CU when the rows allow it, at most kColPartials groups
+// row groups of a two-stage column reduction: about sixteen rows per group (few partial rows to write and to add up:
+// measured faster than eight), but at least one group per CU when the rows allow it, at most kColPartials groups
 int col_groups(int rows) {
-  int g = rows / 8;
+  int g = rows / 16;
   if (g < 256) g = rows / 2 < 256 ? rows / 2 : 256;
   return g < 1 ? 1 : (g > kColPartials ? kColPartials : g);
 }
@@ -452,29 +452,49 @@ int launch_layernorm_fwd(const float* x, const float* gamma, const float* beta, 
   return launch_bdr_ln(nullptr, nullptr, nullptr, x, nullptr, gamma, beta, out, mu, rstd, rows, h, eps, d, 0, s, rms, nullptr);
 }
 
-static int finalize(float* scratch, float* o0, float* o1, float* o2, int nk, int groups, int cols, hipStream_t s) {
-  FinalizeArgs a{{o0, o1, o2}, nk};
-  hipLaunchKernelGGL(colsum_finalize_kernel, dim3((cols + 15) / 16, nk), dim3(NT), 0, s, scratch, a, groups, cols);
-  OASES_LAUNCH_CHECK("colsum_finalize_kernel");
+int colsum_groups(int rows) { return col_groups(rows); }
+
+int launch_colsum_finalize(const ColsumJob* jobs, int n, hipStream_t s) {
+  for (int first = 0; first < n; first += kMaxColsumJobs) {
+    FinalizeArgs a;
+    a.n = n - first < kMaxColsumJobs ? n - first : kMaxColsumJobs;
+    int cols = 0;
+    for (int i = 0; i < a.n; i++) {
+      a.job[i] = jobs[first + i];
+      if (a.job[i].out && a.job[i].cols > cols) cols = a.job[i].cols;
+    }
+    if (cols == 0) continue;
+    hipLaunchKernelGGL(colsum_finalize_kernel, dim3((cols + 63) / 64, a.n), dim3(NT), 0, s, a);
+    OASES_LAUNCH_CHECK("colsum_finalize_kernel");
+  }
+  return 0;
+}
+
+// the second pass of a column reduction: now (sink == nullptr), or later with the jobs of other reductions in one launch
+static int finish_colsums(ColsumSink* sink, float* scratch, size_t kstride, float* o0, float* o1, float* o2, int groups, int cols, hipStream_t s) {
+  ColsumJob jobs[3] = {{scratch, o0, groups, cols}, {scratch + kstride, o1, groups, cols}, {scratch + 2 * kstride, o2, groups, cols}};
+  if (!sink) return launch_colsum_finalize(jobs, 3, s);
+  for (const ColsumJob& j : jobs)
+    if (j.out) sink->add(j.out, j.src - (size_t)sink->first_row * cols, sink->rows_total, cols);
   return 0;
 }
 
 int launch_dropout_bwd(const float* dyin, void* dz, float* dbias, int rows, int h, const DropCfg& d, int64_t row0,
-                       float* scratch, hipStream_t s) {
+                       float* scratch, hipStream_t s, ColsumSink* sink) {
   if (!check_h(rows, h, "dropout_bwd")) return OASES_EINVAL;
   if (!dyin || !dz || (dbias && !scratch)) { set_error("dropout_bwd: NULL argument"); return OASES_ENULL; }
   const int groups = col_groups(rows);
   OASES_BWD_DISPATCH(h, hipLaunchKernelGGL((dropout_bwd_kernel<NC, NTHR>), dim3(groups), dim3(NTHR), 0, s, dyin, (uint16_t*)dz,
                                            dbias ? scratch : nullptr, rows, h, d, row0));
   OASES_LAUNCH_CHECK("dropout_bwd_kernel");
-  if (dbias) return finalize(scratch, dbias, nullptr, nullptr, 1, groups, h, s);
+  if (dbias) return finish_colsums(sink, scratch, 0, dbias, nullptr, nullptr, groups, h, s);
   return 0;
 }
 
 int launch_layernorm_bwd(const float* part, const float* peer, const float* dres, const float* x, const float* mu,
                          const float* rstd, const float* gamma, float* dxo, float* dgamma, float* dbeta, void* dz,
                          float* dbias, int rows, int h, const DropCfg& d, int64_t row0, float* scratch, hipStream_t s, bool rms,
-                         bool post) {
+                         bool post, ColsumSink* sink) {
   if (!check_h(rows, h, "layernorm_bwd")) return OASES_EINVAL;
   if (rms && post) { set_error("layernorm_bwd: no post-norm RMS variant"); return OASES_EINVAL; }
   if (!part || (!dres && !post) || !x || !rstd || !gamma || !dxo || !dgamma || !scratch || (!rms && (!mu || !dbeta || (dz && !dbias)))) {
@@ -483,18 +503,20 @@ int launch_layernorm_bwd(const float* part, const float* peer, const float* dres
   }
   const int groups = col_groups(rows);
   const int want_dbias = dz && dbias;
+  // distance between the three arrays of partial rows: behind one another for this call alone, or as the sink lays them out
+  const size_t kstride = sink ? sink->kstride : (size_t)groups * h;
   if (rms) {
     OASES_BWD_DISPATCH(h, hipLaunchKernelGGL((layernorm_bwd_kernel<NC, NTHR, true, false>), dim3(groups), dim3(NTHR), 0, s, part, peer, dres, x,
-                                             mu, rstd, gamma, dxo, (uint16_t*)dz, scratch, rows, h, d, row0, want_dbias));
+                                             mu, rstd, gamma, dxo, (uint16_t*)dz, scratch, rows, h, d, row0, want_dbias, kstride));
   } else if (post) {
     OASES_BWD_DISPATCH(h, hipLaunchKernelGGL((layernorm_bwd_kernel<NC, NTHR, false, true>), dim3(groups), dim3(NTHR), 0, s, part, peer, dres, x,
-                                             mu, rstd, gamma, dxo, (uint16_t*)dz, scratch, rows, h, d, row0, want_dbias));
+                                             mu, rstd, gamma, dxo, (uint16_t*)dz, scratch, rows, h, d, row0, want_dbias, kstride));
   } else {
     OASES_BWD_DISPATCH(h, hipLaunchKernelGGL((layernorm_bwd_kernel<NC, NTHR, false, false>), dim3(groups), dim3(NTHR), 0, s, part, peer, dres, x,
-                                             mu, rstd, gamma, dxo, (uint16_t*)dz, scratch, rows, h, d, row0, want_dbias));
+                                             mu, rstd, gamma, dxo, (uint16_t*)dz, scratch, rows, h, d, row0, want_dbias, kstride));
   }
   OASES_LAUNCH_CHECK("layernorm_bwd_kernel");
-  return finalize(scratch, dgamma, rms ? nullptr : dbeta, want_dbias ? dbias : nullptr, want_dbias ? 3 : 2, groups, h, s);
+  return finish_colsums(sink, scratch, kstride, dgamma, rms ? nullptr : dbeta, want_dbias ? dbias : nullptr, groups, h, s);
 }
 
 int launch_cast_bf16(const float* x, void* out, int64_t n, hipStream_t s) {
@@ -537,14 +559,14 @@ int launch_rope(void* qkv, int ld, int rows, int64_t row0, int seq, int heads, i
   return 0;
 }
 
-int launch_colsum_bf16(const void* a, int ld, int rows, int cols, float* out, float* scratch, hipStream_t s) {
+int launch_colsum_bf16(const void* a, int ld, int rows, int cols, float* out, float* scratch, hipStream_t s, ColsumSink* sink) {
   if (!a || !out || !scratch) { set_error("colsum_bf16: NULL argument"); return OASES_ENULL; }
   if (rows <= 0 || cols <= 0 || cols % 8 || ld % 8 || ld < cols) { set_error("colsum_bf16: bad shape"); return OASES_EINVAL; }
   const int groups = col_groups(rows);
   hipLaunchKernelGGL(colsum_bf16_kernel, dim3(groups, (cols / 8 + NT - 1) / NT), dim3(NT), 0, s, (const uint16_t*)a, ld, rows,
                      cols, scratch);
   OASES_LAUNCH_CHECK("colsum_bf16_kernel");
-  return finalize(scratch, out, nullptr, nullptr, 1, groups, cols, s);
+  return finish_colsums(sink, scratch, 0, out, nullptr, nullptr, groups, cols, s);
 }
 
 }  // namespace oases

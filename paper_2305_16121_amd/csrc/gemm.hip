@@ -10,6 +10,11 @@
 // v_mfma_f32_32x32x16_bf16: A lane l holds row l%32, k = 8*(l/32)..+7; B the same with columns;
 // accumulator element i of lane l is C[8*(i/4) + 4*(l/32) + i%4][l%32].
 #include <type_traits>
+#ifdef OASES_GEMM_TUNE_HOOK
+#include <stdio.h>
+#include <stdlib.h>
+#include <string.h>
+#endif
 
 #include "common.h"
 
@@ -1339,6 +1344,18 @@ int launch_shape(const GemmArgs& g, float* ws, size_t ws_bytes, int forced_varia
     const bool pinned = kind != 2 && choice_rows > g.M;
     t = pick_tile(kind, EPI, pinned ? choice_rows : g.M, g.N, g.K, ws ? ws_bytes : 0);
     if (pinned && t.dtl && t.bm == 256 && !dtl_fits(kind, g.M, g.N, g.K)) t.dtl = t.pp = false;
+#ifdef OASES_GEMM_TUNE_HOOK
+    {  // tuning aid (not compiled into the library): OASES_GEMM_TUNE="kind:epi:M:N:K=variant;..." overrides the choice
+      static const char* tune = getenv("OASES_GEMM_TUNE");
+      if (tune) {
+        char key[96];
+        snprintf(key, sizeof key, "%d:%d:%d:%d:%d=", kind, (int)EPI, g.M, g.N, g.K);
+        const char* hit = strstr(tune, key);
+        TileChoice tt;
+        if (hit && decode_variant(atoi(hit + strlen(key)), kind, g.M, g.N, g.K, ws ? ws_bytes : 0, &tt)) t = tt;
+      }
+    }
+#endif
   } else if (!decode_variant(forced_variant, kind, g.M, g.N, g.K, ws ? ws_bytes : 0, &t)) {
     set_error("gemm: variant %d does not exist or does not fit M=%d N=%d K=%d with %zu workspace bytes", forced_variant, g.M, g.N, g.K, ws ? ws_bytes : (size_t)0);
     return OASES_EINVAL;

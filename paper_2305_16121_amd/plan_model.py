@@ -26,7 +26,8 @@ import time
 FWD_BLOCK = {"LN1": 0, "QKV": 0, "ATTN": 0, "PROJ": 0, "R1+BDR1+LN2": 1, "FC1+GELU": 1, "FC2": 1, "R2+BDR2": 0}
 BWD_BLOCK = {"BDR2.b": 1, "LN2.r": 1, "FC1+GELU.r": 1, "FC2.dgrad+dGELU": 1, "FC1.dgrad": 1, "FC2.wgrad": 1, "FC1.wgrad": 1, "b1.sum": 1,
              "R3+LN2.b+BDR1.b": 0, "LN1.r": 0, "QKV.r": 0, "ATTN.r": 0, "PROJ.dgrad": 0, "ATTN.b": 0, "QKV.dgrad": 0, "PROJ.wgrad": 0,
-             "QKV.wgrad": 0, "PROJ+QKV.wgrad": 0, "bqkv.sum": 0, "R4+LN1.b": 1}
+             "QKV.wgrad": 0, "PROJ+QKV.wgrad": 0, "bqkv.sum": 0, "R4+LN1.b": 1,
+             "colsums": 0}   # second stage of all column reductions of the pass (last operator): charged to the attention block
 
 
 def profile_degree(cfg, reps):

@@ -87,7 +87,8 @@ def test_workspace_plan(B):
 # communication operator runs for sub-batch 0, its communication starts, the sequence is replayed for sub-batch 1;
 # then the next sequence.  Backward: saved sequences are popped last-first, so sub-batch 1 leads; operators behind a
 # communication operator travel with it on the communication stream; the weight-gradient GEMMs of a block run once,
-# over all sub-batches' rows ("sb*"), behind the block's last reduction start.
+# over all sub-batches' rows ("sb*"), behind the block's last reduction start.  The last operator adds up the partial rows
+# of every column reduction of the pass (bias and LayerNorm-parameter gradients) in one launch.
 FWD_TRACE = """\
 compute LN1 sb0|compute QKV sb0|compute ATTN sb0|compute PROJ sb0|comm R1+BDR1+LN2 sb0
 compute LN1 sb1|compute QKV sb1|compute ATTN sb1|compute PROJ sb1|comm R1+BDR1+LN2 sb1
@@ -102,7 +103,7 @@ compute FC2.wgrad sb*|compute FC1.wgrad sb*|compute b1.sum sb*
 compute PROJ.dgrad sb1|compute ATTN.b sb1|compute QKV.dgrad sb1|comm R4+LN1.b sb1
 compute PROJ.dgrad sb0|compute ATTN.b sb0|compute QKV.dgrad sb0|comm R4+LN1.b sb0
 compute PROJ.wgrad sb*|compute QKV.wgrad sb*|compute bqkv.sum sb*
-compute join sb1|compute join sb0"""
+compute join sb1|compute join sb0|compute colsums sb*"""
 
 
 # The same with fine-grained recomputation (Sec. IV-B): each popped sequence is first rebuilt from its stored input by the
@@ -115,7 +116,7 @@ compute FC2.wgrad sb*|compute FC1.wgrad sb*|compute b1.sum sb*
 compute LN1.r sb1|compute QKV.r sb1|compute ATTN.r sb1|compute PROJ.dgrad sb1|compute ATTN.b sb1|compute QKV.dgrad sb1|comm R4+LN1.b sb1
 compute LN1.r sb0|compute QKV.r sb0|compute ATTN.r sb0|compute PROJ.dgrad sb0|compute ATTN.b sb0|compute QKV.dgrad sb0|comm R4+LN1.b sb0
 compute PROJ.wgrad sb*|compute QKV.wgrad sb*|compute bqkv.sum sb*
-compute join sb1|compute join sb0"""
+compute join sb1|compute join sb0|compute colsums sb*"""
 
 
 def _norm(trace):
@@ -229,7 +230,7 @@ compute FC2.wgrad sb*|compute FC1.wgrad sb*
 compute RMS1.r sb1|compute QKV.r sb1|compute ROPE.r sb1|compute ATTN.r sb1|compute PROJ.dgrad sb1|compute ATTN.b sb1|compute ROPE.b sb1|compute QKV.dgrad sb1|comm R4+RMS1.b sb1
 compute RMS1.r sb0|compute QKV.r sb0|compute ROPE.r sb0|compute ATTN.r sb0|compute PROJ.dgrad sb0|compute ATTN.b sb0|compute ROPE.b sb0|compute QKV.dgrad sb0|comm R4+RMS1.b sb0
 compute PROJ.wgrad sb*|compute QKV.wgrad sb*
-compute join sb1|compute join sb0"""
+compute join sb1|compute join sb0|compute colsums sb*"""
 
 
 def test_llama_schedule_matches_hand_trace(B):

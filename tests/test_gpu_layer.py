@@ -228,6 +228,9 @@ def test_forward_argument_errors():
     with pytest.raises(B.OasesError) as e:
         H.forward(W, xd, None, ws)
     assert e.value.code == B.ENULL
+    with pytest.raises(B.OasesError) as e:       # a workspace smaller than the plan is refused before any launch
+        H.forward(W, xd, torch.empty_like(xd), ws[:H.workspace_bytes - 256])
+    assert e.value.code == B.EWORKSPACE
     W[0]["w1"] = None
     with pytest.raises(B.OasesError) as e:
         H.forward(W, xd, torch.empty_like(xd), ws)

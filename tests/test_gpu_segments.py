@@ -85,7 +85,8 @@ def test_lock_step_ranks_reproduce_the_unsharded_layer(name):
 @pytest.mark.parametrize("name,flags", [("C1", 0), ("C2", 0), ("C2", 4)])
 def test_segments_back_to_back_are_the_whole_pass(name, flags):
     """With no partial / reduced tensors handed over, the segments of one rank in order give what oases_forward /
-    oases_backward give without peer sums, bit for bit (also in recomputation mode, flags = 4)."""
+    oases_backward give without peer sums: y, dx and the weight-matrix gradients bit for bit, the bias and LayerNorm-parameter
+    gradients up to the order of their fp32 column sums (also in recomputation mode, flags = 4)."""
     cfg = si.CONFIGS[name]
     layers, x, dy = LH.make_inputs(cfg)
     from paper_2305_16121_amd import binding as B
@@ -106,10 +107,15 @@ def test_segments_back_to_back_are_the_whole_pass(name, flags):
         for seg in (1, 0, 3):
             H.backward_segment(l, seg, W, xd, dyd, dx, G, ws)
     torch.cuda.synchronize()
+    from tests.util import rel_err
     assert torch.equal(y, whole["y"]) and torch.equal(dx, whole["dx"])
     for l in range(L):
-        for k in LH.GPU_PARAMS:
+        for k in ("wqkv", "wo", "w1", "w2"):
             assert torch.equal(G[l][k], whole["grads"][l][k]), (l, k)
+        # column sums: a segment adds up its own partial rows at once, the whole pass adds those of all sub-batches in one
+        # launch at its end -- the same terms in another fp32 order
+        for k in ("ln1_g", "ln1_b", "bqkv", "bo", "ln2_g", "ln2_b", "b1", "b2"):
+            assert rel_err(G[l][k], whole["grads"][l][k]) < 1e-5, (l, k)
 
 
 def test_segment_argument_errors():
