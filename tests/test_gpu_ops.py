@@ -577,7 +577,8 @@ def _attn_ref(lo, qkv, batch, seq, heads, d, causal):
 
 
 ATTN_CASES = [(2, 256, 2, 64, 1), (2, 256, 2, 128, 1), (3, 200, 1, 64, 0), (1, 328, 2, 128, 0), (2, 72, 3, 64, 1), (1, 1, 1, 64, 1),
-              (1, 1024, 1, 128, 1), (1, 2048, 1, 128, 1)]
+              (1, 1024, 1, 128, 1), (1, 2048, 1, 128, 1),
+              (3, 1024, 3, 64, 1)]    # the last one has more than 256 blocks: the backward runs as two launches, not one
 
 
 @pytest.mark.parametrize("batch,seq,heads,d,causal", ATTN_CASES)
