@@ -36,7 +36,9 @@ Parity pins (tests/test_oracle_*.py): Philox known-answer vectors, fp64 central 
 differences, torch autograd over library layer_norm / scaled_dot_product_attention /
 gelu as an independent derivation, closed forms (causal row 0, zero weights, s = 1),
 Megatron shard-sum identities.  The `bf16_sites` option (rounding of named tensors) is
-an estimate of the storage-format error floor, not part of the definition: unpinned.
+an estimate of the storage-format error floor, not part of the definition; it is pinned
+by tests/test_oracle_floor.py (rounding on the bit pattern, where each site rounds, what
+its consumers read).
 """
 from __future__ import annotations
 
