@@ -281,7 +281,7 @@ static void build_backward(oases_handle* H) {
       ops.push_back(Op{B_QKV_DGRAD, l, j, 0, -1, ev_id(H, l, 3, j, 0)});
       ops.push_back(Op{B_R4, l, j, 1, ev_id(H, l, 3, j, 0), ev_id(H, l, 3, j, 1)});
     }
-    if (gemm_tn_pair_wins(H->M, H->hp, H->h, H->h, 3 * H->hp)) {
+    if (gemm_tn_pair_wins(H->M, H->hp, H->h, H->h, 3 * H->hp) && gemm_span_fits(H->M, H->h) && gemm_span_fits(H->M, 3 * H->hp)) {
       ops.push_back(Op{B_PQ_WGRAD, l, -1, 0, -1, -1});
     } else {
       ops.push_back(Op{B_PROJ_WGRAD, l, -1, 0, -1, -1});

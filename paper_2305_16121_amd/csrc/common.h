@@ -157,6 +157,9 @@ int launch_colsum_bf16(const void* a, int ld, int rows, int cols, float* out, fl
 int launch_gemm(int op, int epi, int M, int N, int K, const void* A, int lda, const void* B, int ldb, void* C,
                 int ldc, const float* bias, void* aux, int ldaux, void* splitk_ws, size_t splitk_ws_bytes, int forced_variant,
                 hipStream_t s, int choice_rows = 0);
+// the direct-to-LDS kernels address an operand with 32-bit byte offsets: its rows x ld bf16 elements must span less than
+// 2 GiB, or the launcher takes the register-staged kernel of the same tile
+inline bool gemm_span_fits(long rows, long ld) { return rows * ld * 2 < (1L << 31); }
 int gemm_variant(int op, int epi, int M, int N, int K, size_t ws_bytes);  // 1e8*[waves split k] + 1e6*slices + 1e3*BM + BN
 // two TN contractions C_i += A_i^T B_i over the same K rows in one launch of the 128x256 direct-to-LDS kernel, and the
 // host rule that says when that beats two launches (both fit whole tiles, fewer rounds of workgroups together)

@@ -563,6 +563,29 @@ __device__ __forceinline__ void lds_wait(u32x4 (&a)[4], u32x4 (&b)[4]) {
 // `extent`: rows of the operand's free dimension (M of A, N of B).  A row-indexed operand may end inside the tile
 // (extent a multiple of 8, so whole 16-byte chunks): chunks beyond it are fetched from column 0 instead -- valid memory,
 // and the rows / columns of C they feed are never stored.  A k-major operand must fill its tiles.
+//
+// The eight-wave kernels fetch the tiles with buffer loads (resource in SGPRs + 32-bit lane offset + SGPR tile offset)
+// straight into LDS.  Measured on L2-resident tiles, one workgroup per CU: 57.6 GB/s per CU with four issuing waves and
+// 97.7 with eight, against 35.7 and 84.5 for global_load_lds with 64-bit lane addresses; more loads in flight per wave
+// change neither figure (a wave sustains one 1 KB load per 75-95 ns), so it is the issue rate of these loads that bounds
+// the kernels below.  An operand must span less than 2 GiB (gemm_span_fits, checked by the launcher).
+typedef void OASES_LDS* lds_ptr_t;
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t operand_rsrc(const void* p) {
+  return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p), 0, 0x7fffffff, 0x00020000);
+}
+__device__ __forceinline__ uint32_t lane_offset(const char* p, const void* base) { return (uint32_t)(p - reinterpret_cast<const char*>(base)); }
+// 16 bytes per lane: lane i's go to dst + 16 i (dst is uniform over the wave)
+__device__ __forceinline__ void dma16(__amdgpu_buffer_rsrc_t r, uint32_t lane_off, uint32_t tile_off, char* dst) {
+  __builtin_amdgcn_raw_ptr_buffer_load_lds(r, (lds_ptr_t)dst, 16, (int)lane_off, (int)tile_off, 0, 0);
+}
+
+// the same through global_load_lds (64-bit lane address): what the four-wave kernels use -- they issue a tile's loads between
+// MFMAs of the same wave, where the buffer form measured 5-10 % slower
+__device__ __forceinline__ void dma16_global(const void* base, uint32_t lane_off, uint32_t tile_off, char* dst) {
+  typedef const void __attribute__((address_space(1))) * gptr_t;
+  __builtin_amdgcn_global_load_lds((gptr_t)(reinterpret_cast<const char*>(base) + lane_off + (size_t)tile_off), (lds_ptr_t)dst, 16, 0, 0);
+}
+
 template <bool KC>
 __device__ __forceinline__ const char* dtl_src(const uint16_t* base, int ld, int r0, int q, int lane, int extent) {
   if (KC) {
@@ -632,22 +655,18 @@ __global__ __launch_bounds__(256) void gemm_dtl_kernel(GemmArgs g) {
 
   // DMA sources of this lane: instruction j of this wave is instruction q = 4*wave + j of the operand tile
   // (the swizzle of an MC tile depends on the parity of q: one source pointer for even, one for odd instructions)
-  const char* srcA[2] = {dtl_src<A_KC>(g.A, g.lda, m0, 4 * wave, lane, g.M), dtl_src<A_KC>(g.A, g.lda, m0, 4 * wave + 1, lane, g.M)};
-  const char* srcB[2] = {dtl_src<B_KC>(g.B, g.ldb, n0, 4 * wave, lane, g.N), dtl_src<B_KC>(g.B, g.ldb, n0, 4 * wave + 1, lane, g.N)};
-  const size_t stepA_q = A_KC ? (size_t)32 * g.lda * 2 : (size_t)4 * g.lda * 2;   // two instructions on: 32 rows resp. 4 k rows
-  const size_t stepB_q = B_KC ? (size_t)32 * g.ldb * 2 : (size_t)4 * g.ldb * 2;
-  const size_t stepA_k = A_KC ? (size_t)BKD * 2 : (size_t)BKD * g.lda * 2;          // next k tile
-  const size_t stepB_k = B_KC ? (size_t)BKD * 2 : (size_t)BKD * g.ldb * 2;
-  typedef const void __attribute__((address_space(1))) * gptr_t;
-  typedef void OASES_LDS* lptr_t;
+  const uint32_t srcA[2] = {lane_offset(dtl_src<A_KC>(g.A, g.lda, m0, 4 * wave, lane, g.M), g.A), lane_offset(dtl_src<A_KC>(g.A, g.lda, m0, 4 * wave + 1, lane, g.M), g.A)};
+  const uint32_t srcB[2] = {lane_offset(dtl_src<B_KC>(g.B, g.ldb, n0, 4 * wave, lane, g.N), g.B), lane_offset(dtl_src<B_KC>(g.B, g.ldb, n0, 4 * wave + 1, lane, g.N), g.B)};
+  const uint32_t stepA_q = A_KC ? 32u * g.lda * 2 : 4u * g.lda * 2;   // two instructions on: 32 rows resp. 4 k rows
+  const uint32_t stepB_q = B_KC ? 32u * g.ldb * 2 : 4u * g.ldb * 2;
+  const uint32_t stepA_k = A_KC ? (uint32_t)BKD * 2 : (uint32_t)BKD * g.lda * 2;          // next k tile
+  const uint32_t stepB_k = B_KC ? (uint32_t)BKD * 2 : (uint32_t)BKD * g.ldb * 2;
   auto issue = [&](int t) {
     char* st = lds + (t % NSD) * kDtlStage + wave * 4096;
 #pragma unroll
     for (int j = 0; j < 4; j++) {
-      const char* a = srcA[j & 1] + (size_t)t * stepA_k + (j >> 1) * stepA_q;
-      const char* b = srcB[j & 1] + (size_t)t * stepB_k + (j >> 1) * stepB_q;
-      __builtin_amdgcn_global_load_lds((gptr_t)a, (lptr_t)(st + j * 1024), 16, 0, 0);
-      __builtin_amdgcn_global_load_lds((gptr_t)b, (lptr_t)(st + kDtlOperand + j * 1024), 16, 0, 0);
+      dma16_global(g.A, srcA[j & 1], (uint32_t)t * stepA_k + (j >> 1) * stepA_q, st + j * 1024);
+      dma16_global(g.B, srcB[j & 1], (uint32_t)t * stepB_k + (j >> 1) * stepB_q, st + kDtlOperand + j * 1024);
     }
   };
 
@@ -810,22 +829,19 @@ __device__ __forceinline__ void dtl_rect_tile(const GemmArgs& g, int pid, char* 
 
   // this wave's DMA instructions of a tile: A instructions 4*wave .. 4*wave+3, B instructions 8*wave .. 8*wave+7, one
   // source pointer each (rows or chunks beyond an operand's extent are redirected per instruction)
-  const char* srcA[4];
-  const char* srcB[8];
+  uint32_t srcA[4], srcB[8];
 #pragma unroll
-  for (int j = 0; j < 4; j++) srcA[j] = rect_src<A_KC, 128>(g.A, g.lda, m0, 4 * wave + j, lane, g.M);
+  for (int j = 0; j < 4; j++) srcA[j] = lane_offset(rect_src<A_KC, 128>(g.A, g.lda, m0, 4 * wave + j, lane, g.M), g.A);
 #pragma unroll
-  for (int j = 0; j < 8; j++) srcB[j] = rect_src<B_KC, 256>(g.B, g.ldb, n0, 8 * wave + j, lane, g.N);
-  const size_t stepA_k = A_KC ? (size_t)BKR * 2 : (size_t)BKR * g.lda * 2, stepB_k = B_KC ? (size_t)BKR * 2 : (size_t)BKR * g.ldb * 2;  // next k tile
-  typedef const void __attribute__((address_space(1))) * gptr_t;
-  typedef void OASES_LDS* lptr_t;
+  for (int j = 0; j < 8; j++) srcB[j] = lane_offset(rect_src<B_KC, 256>(g.B, g.ldb, n0, 8 * wave + j, lane, g.N), g.B);
+  const uint32_t stepA_k = A_KC ? (uint32_t)BKR * 2 : (uint32_t)BKR * g.lda * 2, stepB_k = B_KC ? (uint32_t)BKR * 2 : (uint32_t)BKR * g.ldb * 2;  // next k tile
   auto issue = [&](int t) {
     char* st = lds + (t % NSR) * kRectStage;
 #pragma unroll
     for (int j = 0; j < 4; j++) {
-      __builtin_amdgcn_global_load_lds((gptr_t)(srcA[j] + (size_t)t * stepA_k), (lptr_t)(st + (4 * wave + j) * 1024), 16, 0, 0);
-      __builtin_amdgcn_global_load_lds((gptr_t)(srcB[2 * j] + (size_t)t * stepB_k), (lptr_t)(st + kRectA + (8 * wave + 2 * j) * 1024), 16, 0, 0);
-      __builtin_amdgcn_global_load_lds((gptr_t)(srcB[2 * j + 1] + (size_t)t * stepB_k), (lptr_t)(st + kRectA + (8 * wave + 2 * j + 1) * 1024), 16, 0, 0);
+      dma16_global(g.A, srcA[j], (uint32_t)t * stepA_k, st + (4 * wave + j) * 1024);
+      dma16_global(g.B, srcB[2 * j], (uint32_t)t * stepB_k, st + kRectA + (8 * wave + 2 * j) * 1024);
+      dma16_global(g.B, srcB[2 * j + 1], (uint32_t)t * stepB_k, st + kRectA + (8 * wave + 2 * j + 1) * 1024);
     }
   };
 
@@ -1005,25 +1021,21 @@ __device__ __forceinline__ void pp_tile(const GemmArgs& g, int pid, char* lds) {
 #pragma unroll
       for (int e = 0; e < 16; e++) acc[i][j][e] = 0.f;
 
-  const char* srcA[PER_A];
-  const char* srcB[PER_B];
+  const __amdgpu_buffer_rsrc_t rsA = operand_rsrc(g.A), rsB = operand_rsrc(g.B);
+  uint32_t srcA[PER_A], srcB[PER_B];
 #pragma unroll
   for (int j = 0; j < PER_A; j++)
-    srcA[j] = SQ ? dtl_src<A_KC>(g.A, g.lda, m0, PER_A * wave + j, lane, g.M) : rect_src<A_KC, 128>(g.A, g.lda, m0, PER_A * wave + j, lane, g.M);
+    srcA[j] = lane_offset(SQ ? dtl_src<A_KC>(g.A, g.lda, m0, PER_A * wave + j, lane, g.M) : rect_src<A_KC, 128>(g.A, g.lda, m0, PER_A * wave + j, lane, g.M), g.A);
 #pragma unroll
   for (int j = 0; j < PER_B; j++)
-    srcB[j] = SQ ? dtl_src<B_KC>(g.B, g.ldb, n0, PER_B * wave + j, lane, g.N) : rect_src<B_KC, 256>(g.B, g.ldb, n0, PER_B * wave + j, lane, g.N);
-  const size_t stepA_k = A_KC ? (size_t)KT * 2 : (size_t)KT * g.lda * 2, stepB_k = B_KC ? (size_t)KT * 2 : (size_t)KT * g.ldb * 2;  // next k tile
-  typedef const void __attribute__((address_space(1))) * gptr_t;
-  typedef void OASES_LDS* lptr_t;
+    srcB[j] = lane_offset(SQ ? dtl_src<B_KC>(g.B, g.ldb, n0, PER_B * wave + j, lane, g.N) : rect_src<B_KC, 256>(g.B, g.ldb, n0, PER_B * wave + j, lane, g.N), g.B);
+  const uint32_t stepA_k = A_KC ? (uint32_t)KT * 2 : (uint32_t)KT * g.lda * 2, stepB_k = B_KC ? (uint32_t)KT * 2 : (uint32_t)KT * g.ldb * 2;  // next k tile
   auto issue = [&](int t) {
     char* st = lds + (t % NS) * kStage;
 #pragma unroll
-    for (int j = 0; j < PER_A; j++)
-      __builtin_amdgcn_global_load_lds((gptr_t)(srcA[j] + (size_t)t * stepA_k), (lptr_t)(st + (PER_A * wave + j) * 1024), 16, 0, 0);
+    for (int j = 0; j < PER_A; j++) dma16(rsA, srcA[j], (uint32_t)t * stepA_k, st + (PER_A * wave + j) * 1024);
 #pragma unroll
-    for (int j = 0; j < PER_B; j++)
-      __builtin_amdgcn_global_load_lds((gptr_t)(srcB[j] + (size_t)t * stepB_k), (lptr_t)(st + kOpA + (PER_B * wave + j) * 1024), 16, 0, 0);
+    for (int j = 0; j < PER_B; j++) dma16(rsB, srcB[j], (uint32_t)t * stepB_k, st + kOpA + (PER_B * wave + j) * 1024);
   };
 
   uint32_t offA[4], offB[4];
@@ -1087,13 +1099,13 @@ __device__ __forceinline__ void pp_tile(const GemmArgs& g, int pid, char* lds) {
     }
     pp_wait_frags(fa, fb);
     __builtin_amdgcn_sched_barrier(0);
-    __builtin_amdgcn_s_barrier();
+    if (!(OASES_PP_SKIP & 16)) __builtin_amdgcn_s_barrier();
     __builtin_amdgcn_sched_barrier(0);
     if (!(OASES_PP_SKIP & 4)) __builtin_amdgcn_s_setprio(1);
-    mma();
+    if (!(OASES_PP_SKIP & 8)) mma();
     if (!(OASES_PP_SKIP & 4)) __builtin_amdgcn_s_setprio(0);
     __builtin_amdgcn_sched_barrier(0);
-    __builtin_amdgcn_s_barrier();
+    if (!(OASES_PP_SKIP & 16)) __builtin_amdgcn_s_barrier();
     __builtin_amdgcn_sched_barrier(0);
     cur = cur + kStage == lds0 + NS * kStage ? lds0 : cur + kStage;
   };
@@ -1266,8 +1278,8 @@ bool dtl_rect_fits(int kind, int M, int N, int K) {  // the 128 x 256 kernel red
 }
 bool dtl_rect_whole(int M, int N, int K) { return M % 128 == 0 && N % 256 == 0 && K % BKR == 0 && K >= BKR; }
 struct KindTable { bool wave_ksplit; float r256x256, r128x256, r256x128, r128x128; };
-const KindTable g_kinds[4] = {{true, 1150.f, 1000.f, 960.f, 740.f}, {true, 1150.f, 1000.f, 960.f, 740.f},
-                        {true, 1150.f, 1000.f, 960.f, 740.f}, {false, 1150.f, 880.f, 900.f, 740.f}};
+const KindTable g_kinds[4] = {{true, 1200.f, 1080.f, 960.f, 740.f}, {true, 1200.f, 1080.f, 960.f, 740.f},
+                        {true, 1200.f, 1080.f, 960.f, 740.f}, {false, 1200.f, 1080.f, 900.f, 740.f}};
 TileChoice pick_tile(int kind, int epi, int M, int N, int K, size_t ws_bytes) {
   const KindTable& kt = g_kinds[kind];
   const struct { int bm, bn; float tflops; } cand[] = {{256, 256, kt.r256x256}, {128, 256, kt.r128x256}, {256, 128, kt.r256x128}, {128, 128, kt.r128x128}};
@@ -1284,21 +1296,21 @@ TileChoice pick_tile(int kind, int epi, int M, int N, int K, size_t ws_bytes) {
       if (t < best_t) { best_t = t; best = TileChoice{c.bm, c.bn, S, kt.wave_ksplit}; }
     }
   }
-  // Whole tiles without k slices: the direct-to-LDS kernels where they measure faster on operands that come from HBM --
-  // 256 x 256 for TN and plain NN (an operand that goes through the transposing LDS read costs the staged kernel
-  // conflicting LDS stores); 128 x 256 for TN, NN and, except with the plain fp32 store, NT.  (The bias+GeLU forward stays
-  // on its staged 256 x 128 tiles: faster inside a step, although slower on cold operands in isolation.)
+  // Whole tiles without k slices: the eight-wave direct-to-LDS kernels, which measure faster than the four-wave and the
+  // register-staged kernels of the same tile on every shape of the two full-size workloads (cold operands, 3-15 %).
   if (best.ksplit == 1) {
-    const bool rect = best.bm == 128 && best.bn == 256 && kind != 3;
-    if (best.bm == 256 && best.bn == 256 && (kind == 2 || kind == 0 || epi == EPI_SWIGLU) && dtl_fits(kind, M, N, K)) best.dtl = true;
-    if (rect && (kind != 1 || epi != EPI_F32) && dtl_rect_fits(kind, M, N, K)) best = TileChoice{128, 256, 1, true, true, kind == 2};  // weight gradients: eight waves (measured 6-9 % faster)
+    if (best.bm == 256 && best.bn == 256 && dtl_fits(kind, M, N, K)) best.dtl = best.pp = true;
+    if (best.bm == 128 && best.bn == 256 && dtl_rect_fits(kind, M, N, K)) best = TileChoice{128, 256, 1, true, true, true};
     // Few rows, long k (a sub-batch of 1024 rows against K = 8192): 128 x 128 tiles fill the chip but run at the small
     // tile's rate; the 128 x 256 direct-to-LDS kernel over two k slices fills it too, and is faster even with its second
     // pass (measured on cold operands: 87-93 us against 108-116 us).
     const long rtiles = (long)((M + 127) / 128) * ((N + 255) / 256);
     if (best.bm == 128 && best.bn == 128 && epi != EPI_SWIGLU && epi != EPI_DSWIGLU && 2 * rtiles >= 192 && 2 * rtiles <= 256 && K >= 4096 &&
         K % (2 * BKR) == 0 && dtl_rect_fits(kind, M, N, K / 2) && (size_t)2 * M * N * 4 <= ws_bytes)
-      best = TileChoice{128, 256, 2, true, true};
+      best = TileChoice{128, 256, 2, true, true, true};
+  } else if (best.bm == 128 && best.bn == 256 && (best.ksplit == 2 || best.ksplit == 4) && epi != EPI_SWIGLU && epi != EPI_DSWIGLU &&
+             K % (best.ksplit * BKR) == 0 && dtl_rect_fits(kind, M, N, K / best.ksplit)) {
+    best = TileChoice{128, 256, best.ksplit, true, true, true};  // k slices of whole stages: the eight-wave kernel
   }
   return best;
 }
@@ -1344,6 +1356,8 @@ int launch_shape(const GemmArgs& g, float* ws, size_t ws_bytes, int forced_varia
     const bool pinned = kind != 2 && choice_rows > g.M;
     t = pick_tile(kind, EPI, pinned ? choice_rows : g.M, g.N, g.K, ws ? ws_bytes : 0);
     if (pinned && t.dtl && t.bm == 256 && !dtl_fits(kind, g.M, g.N, g.K)) t.dtl = t.pp = false;
+    const int rows = pinned ? choice_rows : g.M;
+    if (t.dtl && !(gemm_span_fits(A_KC ? rows : g.K, g.lda) && gemm_span_fits(B_KC ? g.N : g.K, g.ldb))) t.dtl = t.pp = false;
 #ifdef OASES_GEMM_TUNE_HOOK
     {  // tuning aid (not compiled into the library): OASES_GEMM_TUNE="kind:epi:M:N:K=variant;..." overrides the choice
       static const char* tune = getenv("OASES_GEMM_TUNE");
@@ -1358,6 +1372,9 @@ int launch_shape(const GemmArgs& g, float* ws, size_t ws_bytes, int forced_varia
 #endif
   } else if (!decode_variant(forced_variant, kind, g.M, g.N, g.K, ws ? ws_bytes : 0, &t)) {
     set_error("gemm: variant %d does not exist or does not fit M=%d N=%d K=%d with %zu workspace bytes", forced_variant, g.M, g.N, g.K, ws ? ws_bytes : (size_t)0);
+    return OASES_EINVAL;
+  } else if (t.dtl && !(gemm_span_fits(A_KC ? g.M : g.K, g.lda) && gemm_span_fits(B_KC ? g.N : g.K, g.ldb))) {
+    set_error("gemm: variant %d (direct-to-LDS) needs operands that span less than 2 GiB (lda=%d ldb=%d)", forced_variant, g.lda, g.ldb);
     return OASES_EINVAL;
   }
   if (t.dtl && t.pp) {
@@ -1507,6 +1524,10 @@ int launch_gemm_tn_pair(int K, int M0, int N0, const void* A0, int lda0, const v
   if ((lda0 % 8) || (ldb0 % 8) || (ldc0 % 4) || (lda1 % 8) || (ldb1 % 8) || (ldc1 % 4) || lda0 < M0 || ldb0 < N0 || ldc0 < N0 || lda1 < M1 ||
       ldb1 < N1 || ldc1 < N1) {
     set_error("gemm_tn_pair: leading dimension too small or not a multiple of 8 (A, B) / 4 (C)");
+    return OASES_EINVAL;
+  }
+  if (!gemm_span_fits(K, lda0) || !gemm_span_fits(K, ldb0) || !gemm_span_fits(K, lda1) || !gemm_span_fits(K, ldb1)) {
+    set_error("gemm_tn_pair: an operand spans 2 GiB or more (K=%d rows)", K);
     return OASES_EINVAL;
   }
   if (!A0 || !B0 || !C0 || !A1 || !B1 || !C1) { set_error("gemm_tn_pair: NULL operand"); return OASES_ENULL; }

@@ -196,20 +196,21 @@ def test_attention_weight_gradients_share_a_launch_where_it_pays(B):
 
 
 def test_gemm_choice_for_the_measured_workloads(B):
-    """The kernel instantiation the library picks (host query) for launches of the measured workloads: the direct-to-LDS
-    kernels where they were measured faster, k slices only with a workspace that holds the partial planes."""
+    """The kernel instantiation the library picks (host query) for launches of the measured workloads: the eight-wave
+    direct-to-LDS kernels wherever whole k tiles allow them, k slices only with a workspace that holds the partial planes."""
     v = B.lib.oases_op_gemm_variant
     ws = 256 << 20
-    assert v(B.GEMM_TN, B.EPI_F32, 2048, 4096, 8192, ws) == 301128256          # C4: merged weight gradient of FC2 (eight waves)
-    assert v(B.GEMM_NN, B.EPI_BIAS_BF16, 4096, 1536, 4096, ws) == 201128256    # C4: QKV
-    assert v(B.GEMM_NN, B.EPI_BIAS_GELU, 4096, 2048, 4096, ws) == 1256128      # C4: FC1 stays on the staged 256 x 128 tiles
-    assert v(B.GEMM_NN, B.EPI_BIAS_GELU, 1024, 4096, 8192, ws) == 202128256    # C5: few rows, long k -> two k slices
+    assert v(B.GEMM_TN, B.EPI_F32, 2048, 4096, 8192, ws) == 301128256          # C4: merged weight gradient of FC2
+    assert v(B.GEMM_NN, B.EPI_BIAS_BF16, 4096, 1536, 4096, ws) == 301128256    # C4: QKV
+    assert v(B.GEMM_NN, B.EPI_BIAS_GELU, 4096, 2048, 4096, ws) == 301128256    # C4: FC1
+    assert v(B.GEMM_NT, B.EPI_F32, 4096, 4096, 2048, ws) == 301256256          # C4: FC1 input gradient
+    assert v(B.GEMM_NN, B.EPI_BIAS_GELU, 1024, 4096, 8192, ws) == 302128256    # C5: few rows, long k -> two k slices
     assert v(B.GEMM_NN, B.EPI_BIAS_GELU, 1024, 4096, 8192, 0) == 1128128       # ... not without a workspace
-    assert v(B.GEMM_NT, B.EPI_DGELU, 1024, 4096, 8192, ws) == 202128256
-    assert v(B.GEMM_TN, B.EPI_F32, 8192, 4096, 8192, ws) == 201256256          # C5: merged weight gradient of FC1
-    assert v(B.GEMM_TN, B.EPI_F32, 4096, 2752, 8192, ws) == 201256256          # L4: a ragged last tile column
-    assert v(B.GEMM_NN, B.EPI_SWIGLU, 4096, 2752, 4096, ws) == 201256256       # L4: FC1 + SwiGLU
-    assert v(B.GEMM_NT, B.EPI_DSWIGLU, 4096, 1376, 4096, ws) == 201128256      # L4: FC2 input gradient
+    assert v(B.GEMM_NT, B.EPI_DGELU, 1024, 4096, 8192, ws) == 302128256
+    assert v(B.GEMM_TN, B.EPI_F32, 8192, 4096, 8192, ws) == 301256256          # C5: merged weight gradient of FC1
+    assert v(B.GEMM_TN, B.EPI_F32, 4096, 2752, 8192, ws) == 301256256          # L4: a ragged last tile column
+    assert v(B.GEMM_NN, B.EPI_SWIGLU, 4096, 2752, 4096, ws) == 301256256       # L4: FC1 + SwiGLU
+    assert v(B.GEMM_NT, B.EPI_DSWIGLU, 4096, 1376, 4096, ws) == 301128256      # L4: FC2 input gradient
 
 
 # ------------------------------------------------------------------ LLaMA-style layer: schedule and configuration checks

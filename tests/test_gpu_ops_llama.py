@@ -166,10 +166,11 @@ def test_gemm_swiglu_epilogues(B, ll, M, fp, K, variant):
     assert_bf16_close(dgu.float(), ref, 1e-4, 1e-5)
 
 
-@pytest.mark.parametrize("variant,M,fp,K", [(201128256, 256, 512, 192), (201128256, 384, 256, 1088), (201256256, 512, 256, 160), (0, 4096, 1536, 4096)])
+@pytest.mark.parametrize("variant,M,fp,K", [(201128256, 256, 512, 192), (201128256, 384, 256, 1088), (201256256, 512, 256, 160), (301128256, 256, 512, 192),
+                                              (301128256, 392, 288, 1088), (301256256, 512, 256, 160), (0, 4096, 1536, 4096)])
 def test_gemm_swiglu_gradient_on_direct_to_lds_kernels(B, ll, variant, M, fp, K):
     """The SwiGLU-gradient epilogue on the kernels whose tiles arrive by direct-to-LDS loads (forced, and as the library's own
-    choice for a shape with whole 128 x 256 tiles); the forward SwiGLU epilogue does not exist there and is refused."""
+    choice for a shape with whole 128 x 256 tiles); the four-wave 128 x 256 kernel has no forward SwiGLU epilogue and refuses it."""
     g = gen(11)
     dz = bf16_round(randn(g, M, K))
     w2 = bf16_round(randn(g, fp, K, scale=0.05))
@@ -180,13 +181,13 @@ def test_gemm_swiglu_gradient_on_direct_to_lds_kernels(B, ll, variant, M, fp, K)
     if variant:
         B.check(B.lib.oases_op_gemm_forced(variant, *args))
     else:
-        assert B.lib.oases_op_gemm_variant(B.GEMM_NT, B.EPI_DSWIGLU, M, fp, K, 0) == 201128256
+        assert B.lib.oases_op_gemm_variant(B.GEMM_NT, B.EPI_DSWIGLU, M, fp, K, 0) == 301128256
         B.check(B.lib.oases_op_gemm(*args))
     dF = dz.double() @ w2.double().t()
     gs = gu_ref.double().reshape(M, fp // 32, 2, 32)
     gst, ust = gs[:, :, 0].reshape(M, fp), gs[:, :, 1].reshape(M, fp)
     assert_bf16_close(dgu.float(), interleave(dF * ust * ll.silu_grad(gst), dF * ll.silu(gst)), 1e-4, 1e-5)
-    if variant == 201128256:     # the forward SwiGLU epilogue exists on the 256 x 256 kernel only
+    if variant == 201128256:     # the four-wave 128 x 256 kernel has no forward SwiGLU epilogue
         f = torch.empty(M, fp // 2, dtype=torch.bfloat16, device="cuda")
         a = torch.zeros(M, K, dtype=torch.bfloat16, device="cuda")
         w = torch.zeros(K, fp, dtype=torch.bfloat16, device="cuda")
@@ -195,9 +196,11 @@ def test_gemm_swiglu_gradient_on_direct_to_lds_kernels(B, ll, variant, M, fp, K)
     torch.cuda.synchronize()
 
 
-@pytest.mark.parametrize("variant,M,fp,K", [(201256256, 256, 128, 32), (201256256, 512, 352, 160), (201256256, 256, 1376, 1056), (0, 4096, 1376, 512)])
+@pytest.mark.parametrize("variant,M,fp,K", [(201256256, 256, 128, 32), (201256256, 512, 352, 160), (201256256, 256, 1376, 1056), (301256256, 512, 352, 160),
+                                              (301256256, 256, 1376, 1056), (301128256, 264, 352, 192), (301128256, 128, 1376, 1088), (0, 4096, 1376, 512)])
 def test_gemm_swiglu_forward_on_direct_to_lds_kernel(B, ll, variant, M, fp, K):
-    """The SwiGLU epilogue on the 256 x 256 kernel whose tiles arrive by direct-to-LDS loads: whole and ragged column tiles
+    """The SwiGLU epilogue on the kernels whose tiles arrive by direct-to-LDS loads (256 x 256 with four or eight waves, 128 x 256
+    with eight): whole and ragged column tiles
     (the interleaved [gate 32 | up 32] blocks end inside the last tile), forced and as the library's choice for LLaMA-7B's
     FC1 width per rank."""
     g = gen(13)
@@ -210,7 +213,7 @@ def test_gemm_swiglu_forward_on_direct_to_lds_kernel(B, ll, variant, M, fp, K):
     if variant:
         B.check(B.lib.oases_op_gemm_forced(variant, *args))
     else:
-        assert B.lib.oases_op_gemm_variant(B.GEMM_NN, B.EPI_SWIGLU, M, 2 * fp, K, 0) == 201256256
+        assert B.lib.oases_op_gemm_variant(B.GEMM_NN, B.EPI_SWIGLU, M, 2 * fp, K, 0) == 301256256
         B.check(B.lib.oases_op_gemm(*args))
     gate, up = a.double() @ wg.double(), a.double() @ wu.double()
     assert_bf16_close(gu[:, :2 * fp].float(), interleave(gate, up), 1e-5, 2e-6 * float(gate.abs().max()))
