@@ -565,10 +565,9 @@ __device__ __forceinline__ void lds_wait(u32x4 (&a)[4], u32x4 (&b)[4]) {
 // and the rows / columns of C they feed are never stored.  A k-major operand must fill its tiles.
 //
 // The eight-wave kernels fetch the tiles with buffer loads (resource in SGPRs + 32-bit lane offset + SGPR tile offset)
-// straight into LDS.  Measured on L2-resident tiles, one workgroup per CU: 57.6 GB/s per CU with four issuing waves and
-// 97.7 with eight, against 35.7 and 84.5 for global_load_lds with 64-bit lane addresses; more loads in flight per wave
-// change neither figure (a wave sustains one 1 KB load per 75-95 ns), so it is the issue rate of these loads that bounds
-// the kernels below.  An operand must span less than 2 GiB (gemm_span_fits, checked by the launcher).
+// straight into LDS: no address arithmetic in the vector ALU and half the address registers; measured 5-10 % faster
+// there than global_load_lds with 64-bit lane addresses (TN 2048 x 4096 x 8192: 1029 -> 1120 TFLOP/s, 4096 x 4096 x
+// 8192: 1111 -> 1228).  An operand must span less than 2 GiB (gemm_span_fits, checked by the launcher).
 typedef void OASES_LDS* lds_ptr_t;
 __device__ __forceinline__ __amdgpu_buffer_rsrc_t operand_rsrc(const void* p) {
   return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p), 0, 0x7fffffff, 0x00020000);
@@ -1029,7 +1028,11 @@ __device__ __forceinline__ void pp_tile(const GemmArgs& g, int pid, char* lds) {
 #pragma unroll
   for (int j = 0; j < PER_B; j++)
     srcB[j] = lane_offset(SQ ? dtl_src<B_KC>(g.B, g.ldb, n0, PER_B * wave + j, lane, g.N) : rect_src<B_KC, 256>(g.B, g.ldb, n0, PER_B * wave + j, lane, g.N), g.B);
+#ifdef OASES_PP_SAMEK   // timing experiment: every k tile is tile 0 (all loads hit L2)
+  const uint32_t stepA_k = 0, stepB_k = 0;
+#else
   const uint32_t stepA_k = A_KC ? (uint32_t)KT * 2 : (uint32_t)KT * g.lda * 2, stepB_k = B_KC ? (uint32_t)KT * 2 : (uint32_t)KT * g.ldb * 2;  // next k tile
+#endif
   auto issue = [&](int t) {
     char* st = lds + (t % NS) * kStage;
 #pragma unroll
@@ -1087,6 +1090,9 @@ __device__ __forceinline__ void pp_tile(const GemmArgs& g, int pid, char* lds) {
   uint32_t cur = lds0;
   auto iteration = [&](auto steady_c, int kt) {
     constexpr bool STEADY = decltype(steady_c)::value;  // tile kt+NS-1 exists and is requested now
+    // Timing experiments only (results are wrong with any bit set): -DOASES_PP_SKIP=bits switches parts of the loop off --
+    // 1 the direct-to-LDS loads, 2 the fragment reads (tile 0's stay), 4 the priority changes, 8 the MFMAs, 16 the two
+    // barriers (every wave still passes the same number of barriers); -DOASES_PP_SAMEK makes every k tile tile 0.
 #ifndef OASES_PP_SKIP
 #define OASES_PP_SKIP 0
 #endif

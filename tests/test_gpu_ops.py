@@ -473,6 +473,29 @@ def test_gemm_forced_variant_errors(B):
     torch.cuda.synchronize()
 
 
+def test_gemm_operand_that_spans_2gib_takes_the_staged_kernel(B):
+    """The direct-to-LDS kernels address an operand with 32-bit byte offsets.  An A whose rows lie 2^18 elements apart
+    spans 2 GiB: the library's own choice still gives the product (register-staged kernel of the same tile), a forced
+    direct-to-LDS variant is refused."""
+    M, N, K, lda = 4096, 2048, 256, 1 << 18
+    g = gen(23)
+    a, b = bf16_round(randn(g, M, K)), bf16_round(randn(g, K, N, scale=0.05))
+    big = torch.zeros(M, lda, dtype=torch.bfloat16, device="cuda")
+    big[:, :K] = dev(a, torch.bfloat16)
+    bd = dev(b, torch.bfloat16)
+    c = torch.full((M, N), float("nan"), dtype=torch.float32, device="cuda")
+    args = (B.GEMM_NN, B.EPI_F32, M, N, K, big.data_ptr(), lda, bd.data_ptr(), N, c.data_ptr(), N, None, None, 0, None, 0, None)
+    assert B.lib.oases_op_gemm_variant(B.GEMM_NN, B.EPI_F32, M, N, K, 0) // 100000000 == 3    # a dense A would go to the eight-wave kernel
+    B.check(B.lib.oases_op_gemm(*args))
+    torch.cuda.synchronize()
+    assert rel_err(c, a.double() @ b.double()) < 1e-5
+    for v in (301256256, 201256256, 301128256, 201128256):
+        assert B.lib.oases_op_gemm_forced(v, *args) == B.EINVAL, v
+    assert "2 GiB" in B.lib.oases_last_error().decode()
+    del big
+    torch.cuda.empty_cache()
+
+
 @pytest.mark.parametrize("M,N,K", [(384, 768, 512), (136, 264, 72), (2048, 2048, 256)])
 def test_gemm_epilogues(B, lo, M, N, K):
     g = gen(7)
