@@ -301,7 +301,10 @@ int oases_op_gemm(int op, int epi, int M, int N, int K, const void *A, int lda, 
  * any M, N the GEMM accepts; no forward SwiGLU epilogue; also over 2 or 4 k slices of whole stages, 202128256 and
  * 204128256, K % (64 * slices) == 0); the 256x256 kernel takes one slice only.  W = 3 names the eight-wave forms of
  * the same tiles (two waves per SIMD that alternate between loading and multiplying): 301256256, 301128256, 302128256,
- * 304128256, on the shapes of their W = 2 counterparts; 301128256 gives bit for bit what 201128256 gives.
+ * 304128256, on the shapes of their W = 2 counterparts; 301128256 gives bit for bit what 201128256 gives.  The W = 2 and
+ * W = 3 kernels address an operand with 32-bit byte offsets: oases_op_gemm launches them only if rows x leading
+ * dimension x 2 bytes of A and of B stay under 2 GiB (the staged kernel of the same tile otherwise), and
+ * oases_op_gemm_forced returns EINVAL for them on larger operands.
  * Host only; used to group per-operator timings by kernel. */
 int oases_op_gemm_variant(int op, int epi, int M, int N, int K, size_t workspace_bytes);
 /* oases_op_gemm on the instantiation `variant` names (encoding above) instead of the one the library would choose:
