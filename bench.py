@@ -198,6 +198,29 @@ def mfma_rate(B):
     return res
 
 
+def lds_load_rate(B):
+    """Per-CU rate of L2-resident direct-to-LDS loads, one workgroup of four or eight waves per CU (GB/s per CU)."""
+    import torch
+    wgs, iters = 256, 4000
+    src = torch.zeros(wgs * 65536, dtype=torch.uint8, device="cuda")
+    out = torch.zeros(512, dtype=torch.float32, device="cuda")
+    res = {}
+    st = torch.cuda.current_stream()
+    for waves in (4, 8):
+        call = lambda: B.check(B.lib.oases_probe_lds_load_rate(waves, iters, wgs, src.data_ptr(), src.numel(), out.data_ptr(), st.cuda_stream))
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        call()
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(3):
+            call()
+        e1.record()
+        torch.cuda.synchronize()
+        res[f"{waves}_waves"] = round(3 * waves * iters * 8192.0 / (e0.elapsed_time(e1) * 1e-3) / 1e9, 1)
+    res["unit"] = "GB/s per CU"
+    return res
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -322,6 +345,7 @@ def main():
         ex["with_peer_sums_ms"] = round(wl.time_ms(wl.handle(rflag), k, w, peers=wl.make_peers()), 4)   # reduction points read a peer sum
         ex["pinned_kernel_choice_ms"] = round(wl.time_ms(wl.handle(rflag | B.FLAG_PIN_GEMM), k, w), 4)
         ex["mfma_rate_from_registers"] = mfma_rate(B)
+        ex["direct_to_lds_load_rate"] = lds_load_rate(B)
         if a.config == "C4":          # the other configuration the target is quoted on
             w5 = Workload("C5")
             ms5 = w5.time_ms(w5.handle(0), k, w)

@@ -382,6 +382,13 @@ int oases_op_attention_dropout_bwd(const void *qkv, const void *out, const void 
  * out: device fp32 [workgroups * 256], written once per thread.  The caller times the launch:
  * flop = workgroups * 4 waves * iters * 8 * 32768. */
 int oases_probe_mfma_rate(int random_operands, int iters, int workgroups, void *out, void *stream);
+/* Measurement helper (no step of the path): the rate at which a workgroup of `waves` (4 or 8) waves pulls data that is
+ * resident in its XCD's L2 straight into LDS with 16-byte-per-lane direct-to-LDS loads -- the ceiling over the operand
+ * streams of the GEMM kernels.  Workgroup b sweeps bytes [65536 b, 65536 (b+1)) of src (device, 16-byte aligned,
+ * src_bytes >= 65536 * workgroups) iters times, each wave 8 KiB per iteration; nothing is read back.  out: device fp32
+ * [>= 512], not written in practice.  The caller times the launch: bytes = workgroups * waves * iters * 8192. */
+int oases_probe_lds_load_rate(int waves, int iters, int workgroups, const void *src, size_t src_bytes, void *out,
+                              void *stream);
 
 #ifdef __cplusplus
 }

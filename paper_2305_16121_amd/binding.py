@@ -80,6 +80,7 @@ _sig("oases_gemm_workspace_bytes", _sz, _P)
 _sig("oases_op_colsum_bf16", _i, _P, _i, _i, _i, _P, _P, _P)
 _sig("oases_op_colsum_bf16_static", _i, _P, _i, _i, _i, _P, _P)
 _sig("oases_probe_mfma_rate", _i, _i, _i, _i, _P, _P)
+_sig("oases_probe_lds_load_rate", _i, _i, _i, _i, _P, _sz, _P, _P)
 _sig("oases_op_attention_fwd", _i, _P, _P, _P, _i, _i, _i, _i, _i, _i, _i, _P)
 _sig("oases_op_attention_bwd", _i, _P, _P, _P, _P, _P, _P, _i, _i, _i, _i, _i, _i, _i, _P)
 _sig("oases_op_attention_dropout_fwd", _i, _P, _P, _P, _i, _i, _i, _i, _i, _i, _i, _u64, _i, _f, _i, _i, _P)

@@ -747,3 +747,20 @@ def test_attention_argument_errors(B):
     assert f(t.data_ptr(), o.data_ptr(), l.data_ptr(), 2, 128, 1, 64, 0, 0, 64, None) == B.EINVAL        # chunk, non-causal
     assert f(t.data_ptr(), o.data_ptr(), l.data_ptr(), 2, 128, 1, 64, 1, 0, 512, None) == B.EINVAL       # beyond the batch
     assert f(None, o.data_ptr(), l.data_ptr(), 2, 128, 1, 64, 1, 0, 256, None) == B.ENULL
+
+
+# ------------------------------------------------------------------ measurement helpers
+def test_probe_entry_points(B):
+    """The two measurement helpers run and refuse bad arguments (what they measure is reported by bench.py)."""
+    out = torch.zeros(64 * 256, dtype=torch.float32, device="cuda")
+    B.check(B.lib.oases_probe_mfma_rate(1, 10, 64, out.data_ptr(), None))
+    assert B.lib.oases_probe_mfma_rate(0, 0, 64, out.data_ptr(), None) == B.EINVAL
+    assert B.lib.oases_probe_mfma_rate(0, 10, 64, None, None) == B.ENULL
+    src = torch.zeros(16 * 65536, dtype=torch.uint8, device="cuda")
+    for waves in (4, 8):
+        B.check(B.lib.oases_probe_lds_load_rate(waves, 20, 16, src.data_ptr(), src.numel(), out.data_ptr(), None))
+    assert B.lib.oases_probe_lds_load_rate(6, 20, 16, src.data_ptr(), src.numel(), out.data_ptr(), None) == B.EINVAL
+    assert B.lib.oases_probe_lds_load_rate(8, 20, 17, src.data_ptr(), src.numel(), out.data_ptr(), None) == B.EINVAL   # src too small
+    assert B.lib.oases_probe_lds_load_rate(8, 20, 16, None, src.numel(), out.data_ptr(), None) == B.ENULL
+    torch.cuda.synchronize()
+    assert bool((src == 0).all())
