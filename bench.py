@@ -317,8 +317,10 @@ def main():
                    "ms_per_step": round(d["ms"] / reps, 4)}
             if d["flops"]:
                 row["tflops"] = round(d["flops"] / d["launches"] / (avg_ms * 1e-3) / 1e12, 1)
+                row["frac_of_mfma_peak"] = round(row["tflops"] / PEAK_BF16_TFLOPS, 3)
             if d["bytes"]:
                 row["gbs"] = round(d["bytes"] / d["launches"] / (avg_ms * 1e-3) / 1e9, 1)
+                row["frac_of_hbm_peak"] = round(row["gbs"] / PEAK_HBM_GBS, 3)
             table.append(row)
         table.sort(key=lambda r: -r["ms_per_step"])
         out["kernels"] = table
